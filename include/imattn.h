@@ -1,0 +1,153 @@
+/*
+ * imattn.h -- C ABI of the Interlaced-Mask (IM) attention library for AMD
+ * Instinct MI355X (gfx950).
+ *
+ * The library computes multi-head attention over the concatenation
+ * V_m = [V_t; V_v; V_a] of the modality sequences with ONE set of projection
+ * weights for all modalities, under a block pattern of live (all-zero, "O") and
+ * masked (all-minus-infinity, "J") modality blocks -- the Interlaced Mask of the
+ * GsiT paper (Sec. 5 "All-Modal-In-One Fusion", Eq. "ifm" and the IEM equation;
+ * Eq. "allmodalinone fusion").  Nothing is loaded or multiplied for a masked
+ * block: this is the role the paper gives its "Decomposition" step (Sec. 6
+ * "Inner Decomposition for Efficiency").
+ *
+ * General conventions
+ *   - Pointers named in "device" lists are device (HBM) pointers owned by the
+ *     caller; the im_shape_t, size outputs and im_work_item_t arrays are host
+ *     memory.  The library never allocates or frees device memory and keeps no
+ *     device state between calls.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream).  No call synchronises the device.
+ *   - Arrays are dense row-major.  Activations are [B, T_m, d] with
+ *     T_m = sum(seg_len) and the segments stored one after the other in the
+ *     order given by seg_len (the paper's order is text, vision, audio).
+ *   - Weights are [d_in, d_out] and applied as y = x W (Sec. 3 writes
+ *     W in R^{d x d^f}); biases are [d_out] or NULL.
+ *   - dtype IM_DTYPE_F32: every float array is fp32.
+ *     dtype IM_DTYPE_BF16: activations, weights and biases are bfloat16; all
+ *     accumulation is fp32; weight/bias GRADIENTS are written in fp32.
+ *   - Return value: IM_OK, or a negative error code.  Arguments are validated
+ *     before anything is enqueued, so a failing call has no side effects.
+ *     im_last_error() returns a thread-local description of the last failure.
+ *   - Numerical conventions: a key is padding if key_pad[b, c] != 0 or if its
+ *     position inside its segment is >= valid_len[b, segment]; padded keys get
+ *     weight exactly 0.  Padded QUERY rows are computed like any other row.  A
+ *     query row with no live, valid key has attention output 0 (y = b_o) and
+ *     contributes 0 to every gradient.  A row with several live blocks is
+ *     normalised by ONE softmax over all its live keys (the additive -inf
+ *     definition; Sec. 7.1 "Information Disorder").
+ */
+#ifndef IMATTN_H
+#define IMATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define IM_MAX_SEG 8
+
+#define IM_DTYPE_F32 0
+#define IM_DTYPE_BF16 1
+
+#define IM_OK 0
+#define IM_ERR_INVALID (-1)     /* null required pointer, bad shape, live_mask bits out of range */
+#define IM_ERR_UNSUPPORTED (-2) /* dtype / head dimension / model dimension this build has no kernel for */
+#define IM_ERR_WORKSPACE (-3)   /* workspace_bytes smaller than im_attention_sizes / gsit_layer_sizes reports */
+#define IM_ERR_HIP (-4)         /* a HIP runtime call failed; text in im_last_error() */
+
+/* Named 3x3 patterns for segment order (t, v, a) = (0, 1, 2).
+ * Bit (i * n_seg + j) set <=> block (query segment i, key segment j) is O (live).
+ * IFM forward / backward: Sec. 5 Eq. "ifm"; IEM: the M_intra equation after it. */
+#define IM_IFM_FORWARD 0x062ull  /* live (t,v), (v,a), (a,t) */
+#define IM_IFM_BACKWARD 0x08Cull /* live (t,a), (v,t), (a,v) */
+#define IM_IEM 0x111ull          /* live (t,t), (v,v), (a,a) */
+#define IM_DENSE3 0x1FFull       /* ordinary self-attention over V_m */
+
+/* The problem statement: per-modality lengths, model width, heads, block pattern. */
+typedef struct im_shape {
+  int32_t batch;               /* B >= 1 */
+  int32_t n_seg;               /* number of modality segments, 1..IM_MAX_SEG (3 in the paper) */
+  int32_t seg_len[IM_MAX_SEG]; /* padded length T_s >= 1 of each segment, concatenation order */
+  int32_t d_model;             /* d */
+  int32_t n_heads;             /* H, d % H == 0; head dimension dh = d / H */
+  uint64_t live_mask;          /* the IM: bit (i*n_seg + j) <=> block (query seg i, key seg j) live */
+  float scale;                 /* multiplies Q K^T before the softmax (App. B "apply scaling and softmax"); usually 1/sqrt(dh) */
+  int32_t dtype;               /* IM_DTYPE_F32 or IM_DTYPE_BF16 */
+} im_shape_t;
+
+/* One unit of the live-block schedule (host side; see im_schedule_build). */
+typedef struct im_work_item {
+  int32_t q_seg;     /* query segment i */
+  int32_t q_start;   /* first query row of the tile inside segment i */
+  int32_t q_rows;    /* rows in the tile (<= tile_rows) */
+  int32_t n_key_seg; /* number of live key segments for this query segment */
+  int32_t key_seg[IM_MAX_SEG]; /* their indices j, ascending */
+  int64_t pairs;     /* q_rows * sum_j T_j : (query, key) pairs this item covers (padded lengths) */
+} im_work_item_t;
+
+/* Sec. 6 "Decomposition": enumerate, for ONE (batch element, head), the query
+ * tiles and the live key segments each must visit; nothing is emitted for a
+ * masked block.  Items are ordered by decreasing `pairs` (heaviest first).  Pure
+ * host function, no GPU needed.  items may be NULL to only count.  *n_pairs
+ * receives sum(pairs) = sum over live (i,j) of T_i T_j (App. B, attention cost
+ * "w/ Decomposition").  Returns IM_ERR_INVALID if max_items is too small. */
+int im_schedule_build(const im_shape_t* shape, int32_t tile_rows, im_work_item_t* items, int32_t max_items,
+                      int32_t* n_items, int64_t* n_pairs);
+
+/* Bytes of the `saved` buffer (forward -> backward) and of the largest
+ * workspace any of im_attention_fwd / im_attention_bwd needs for this shape. */
+int im_attention_sizes(const im_shape_t* shape, size_t* saved_bytes, size_t* workspace_bytes);
+
+/* y = IMAttention(x): shared Q/K/V projection (Sec. 3; App. A Eq. "adjmat_all"),
+ * scores and row softmax on the live blocks only (App. A Eq. "sbg_sbg0",
+ * Sec. 5), aggregation P V with heads concatenated (App. A Eq. "sbg_sbg1"), output
+ * projection.
+ * device in : x [B,T_m,d]; wq, wk, wv, wo [d,d]; bq, bk, bv, bo [d] or NULL;
+ *             valid_len int32 [B,n_seg] or NULL; key_pad uint8 [B,T_m] or NULL
+ *             (both given: a key is padding if either says so).
+ * device out: y [B,T_m,d]; saved (saved_bytes; opaque: projected Q, K, V, the
+ *             attention output before W_o and the per-row log-sum-exp) or NULL
+ *             for inference; workspace (scratch, contents undefined afterwards). */
+int im_attention_fwd(const im_shape_t* shape, const void* x, const void* wq, const void* wk, const void* wv,
+                     const void* wo, const void* bq, const void* bk, const void* bv, const void* bo,
+                     const int32_t* valid_len, const uint8_t* key_pad, void* y, void* saved, void* workspace,
+                     size_t workspace_bytes, void* hip_stream);
+
+/* Gradients of im_attention_fwd given dy [B,T_m,d] and the `saved` buffer of the
+ * forward call with the same arguments (the paper states no backward; this is
+ * the chain rule of the definition above, restricted to live blocks).
+ * device out (overwritten, not accumulated): dx [B,T_m,d] (activation dtype);
+ *   dwq, dwk, dwv, dwo fp32 [d,d]; dbq, dbk, dbv, dbo fp32 [d], each may be NULL
+ *   if not wanted.  Results are bitwise reproducible run to run. */
+int im_attention_bwd(const im_shape_t* shape, const void* x, const void* wq, const void* wk, const void* wv,
+                     const void* wo, const int32_t* valid_len, const uint8_t* key_pad, const void* saved,
+                     const void* dy, void* dx, void* dwq, void* dwk, void* dwv, void* dwo, void* dbq, void* dbk,
+                     void* dbv, void* dbo, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* One GsiT encoder layer, a = MLP o MHSA_2 (Sec. 5 Eq. "allmodalinone fusion";
+ * MLP weights W_1 [d, d_ff], W_2 [d_ff, d] as in App. B), in the pre-LayerNorm
+ * residual form:  h = x + IMAttention(LN(x; ln1)),  y = h + GELU(LN(h; ln2) W_1 + b_1) W_2 + b_2
+ * (exact erf GELU; LayerNorm over the feature axis, biased variance, eps = ln_eps).
+ * device in : as im_attention_fwd plus ln1_g, ln1_b, ln2_g, ln2_b [d]; w1 [d,d_ff];
+ *             b1 [d_ff] or NULL; w2 [d_ff,d]; b2 [d] or NULL.
+ * device out: y [B,T_m,d] (may alias x); workspace of gsit_layer_sizes bytes. */
+int gsit_layer_sizes(const im_shape_t* shape, int32_t d_ff, size_t* workspace_bytes);
+int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const void* ln1_g, const void* ln1_b,
+                   const void* wq, const void* wk, const void* wv, const void* wo, const void* bq, const void* bk,
+                   const void* bv, const void* bo, const void* ln2_g, const void* ln2_b, const void* w1,
+                   const void* b1, const void* w2, const void* b2, float ln_eps, const int32_t* valid_len,
+                   const uint8_t* key_pad, void* y, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Description of the last error on the calling thread ("" if none).  Static storage. */
+const char* im_last_error(void);
+
+/* Library version string, e.g. "imattn 0.1 gfx950". */
+const char* im_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IMATTN_H */

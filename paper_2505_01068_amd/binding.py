@@ -1,0 +1,144 @@
+"""ctypes binding over libimattn.so: same names as the C ABI (include/imattn.h).
+
+Argument marshalling only.  Torch supplies device memory and the current HIP
+stream; every step of the computation runs inside the library's kernels.  There
+is no fallback: a missing library or a non-zero return code raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+IM_MAX_SEG = 8
+IM_DTYPE_F32, IM_DTYPE_BF16 = 0, 1
+IM_IFM_FORWARD, IM_IFM_BACKWARD, IM_IEM, IM_DENSE = 0x062, 0x08C, 0x111, 0x1FF
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libimattn.so")
+
+
+class ImShape(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_seg", C.c_int32), ("seg_len", C.c_int32 * IM_MAX_SEG),
+                ("d_model", C.c_int32), ("n_heads", C.c_int32), ("live_mask", C.c_uint64),
+                ("scale", C.c_float), ("dtype", C.c_int32)]
+
+
+class ImWorkItem(C.Structure):
+    _fields_ = [("q_seg", C.c_int32), ("q_start", C.c_int32), ("q_rows", C.c_int32), ("n_key_seg", C.c_int32),
+                ("key_seg", C.c_int32 * IM_MAX_SEG), ("pairs", C.c_int64)]
+
+
+class ImAttnError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"imattn error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Load the shared library (built in-tree by paper_2505_01068_amd/build.py); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} not found: build it with `python -m paper_2505_01068_amd.build` "
+                              "(there is no CPU or PyTorch fallback)")
+        L = C.CDLL(_LIB_PATH)
+        vp, sz = C.c_void_p, C.c_size_t
+        shp = C.POINTER(ImShape)
+        L.im_last_error.restype = C.c_char_p
+        L.im_version.restype = C.c_char_p
+        L.im_schedule_build.argtypes = [shp, C.c_int32, C.POINTER(ImWorkItem), C.c_int32, C.POINTER(C.c_int32),
+                                        C.POINTER(C.c_int64)]
+        L.im_attention_sizes.argtypes = [shp, C.POINTER(sz), C.POINTER(sz)]
+        L.im_attention_fwd.argtypes = [shp] + [vp] * 14 + [sz, vp]
+        L.im_attention_bwd.argtypes = [shp] + [vp] * 19 + [sz, vp]
+        L.gsit_layer_sizes.argtypes = [shp, C.c_int32, C.POINTER(sz)]
+        L.gsit_layer_fwd.argtypes = [shp, C.c_int32] + [vp] * 17 + [C.c_float] + [vp] * 4 + [sz, vp]
+        for f in (L.im_schedule_build, L.im_attention_sizes, L.im_attention_fwd, L.im_attention_bwd,
+                  L.gsit_layer_sizes, L.gsit_layer_fwd):
+            f.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise ImAttnError(rc, lib().im_last_error().decode())
+
+
+def make_shape(batch, seg_len, d_model, n_heads, live_mask, scale, dtype):
+    s = ImShape()
+    s.batch, s.n_seg, s.d_model, s.n_heads = int(batch), len(seg_len), int(d_model), int(n_heads)
+    for i, n in enumerate(seg_len):
+        s.seg_len[i] = int(n)
+    s.live_mask, s.scale = int(live_mask), float(scale)
+    s.dtype = {"fp32": IM_DTYPE_F32, "bf16": IM_DTYPE_BF16, torch.float32: IM_DTYPE_F32,
+               torch.bfloat16: IM_DTYPE_BF16, 0: 0, 1: 1}[dtype]
+    return s
+
+
+def _p(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def im_schedule_build(shape, tile_rows):
+    """Host-side listing of the live-block schedule: (items, n_pairs)."""
+    n, pairs = C.c_int32(0), C.c_int64(0)
+    _check(lib().im_schedule_build(C.byref(shape), tile_rows, None, 0, C.byref(n), C.byref(pairs)))
+    items = (ImWorkItem * max(1, n.value))()
+    _check(lib().im_schedule_build(C.byref(shape), tile_rows, items, n.value, C.byref(n), C.byref(pairs)))
+    return [items[i] for i in range(n.value)], pairs.value
+
+
+def im_attention_sizes(shape):
+    a, b = C.c_size_t(0), C.c_size_t(0)
+    _check(lib().im_attention_sizes(C.byref(shape), C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def gsit_layer_sizes(shape, d_ff):
+    a = C.c_size_t(0)
+    _check(lib().gsit_layer_sizes(C.byref(shape), int(d_ff), C.byref(a)))
+    return a.value
+
+
+def im_attention_fwd(shape, x, wq, wk, wv, wo, bq=None, bk=None, bv=None, bo=None, valid_len=None, key_pad=None,
+                     y=None, saved=None, workspace=None):
+    """y = IMAttention(x).  Tensors are CUDA(HIP) tensors; `saved`/`workspace` are uint8 buffers."""
+    if y is None:
+        y = torch.empty_like(x)
+    wbytes = 0 if workspace is None else workspace.numel()
+    _check(lib().im_attention_fwd(C.byref(shape), _p(x), _p(wq), _p(wk), _p(wv), _p(wo), _p(bq), _p(bk), _p(bv),
+                                  _p(bo), _p(valid_len), _p(key_pad), _p(y), _p(saved), _p(workspace), wbytes,
+                                  _stream()))
+    return y
+
+
+def im_attention_bwd(shape, x, wq, wk, wv, wo, saved, dy, dx, dwq, dwk, dwv, dwo, dbq=None, dbk=None, dbv=None,
+                     dbo=None, valid_len=None, key_pad=None, workspace=None):
+    wbytes = 0 if workspace is None else workspace.numel()
+    _check(lib().im_attention_bwd(C.byref(shape), _p(x), _p(wq), _p(wk), _p(wv), _p(wo), _p(valid_len), _p(key_pad),
+                                  _p(saved), _p(dy), _p(dx), _p(dwq), _p(dwk), _p(dwv), _p(dwo), _p(dbq), _p(dbk),
+                                  _p(dbv), _p(dbo), _p(workspace), wbytes, _stream()))
+    return dx
+
+
+def gsit_layer_fwd(shape, d_ff, x, p, ln_eps=1e-5, valid_len=None, key_pad=None, y=None, workspace=None):
+    """One encoder layer; `p` maps parameter names (ln1_g, ln1_b, wq, ..., w2, b2) to device tensors."""
+    if y is None:
+        y = torch.empty_like(x)
+    wbytes = 0 if workspace is None else workspace.numel()
+    g = p.get
+    _check(lib().gsit_layer_fwd(C.byref(shape), int(d_ff), _p(x), _p(p["ln1_g"]), _p(p["ln1_b"]), _p(p["wq"]),
+                                _p(p["wk"]), _p(p["wv"]), _p(p["wo"]), _p(g("bq")), _p(g("bk")), _p(g("bv")),
+                                _p(g("bo")), _p(p["ln2_g"]), _p(p["ln2_b"]), _p(p["w1"]), _p(g("b1")), _p(p["w2"]),
+                                _p(g("b2")), float(ln_eps), _p(valid_len), _p(key_pad), _p(y), _p(workspace), wbytes,
+                                _stream()))
+    return y

@@ -1,0 +1,440 @@
+// C-ABI entry points: argument validation, the live-block schedule, workspace
+// carving and kernel sequencing.  No device memory is allocated here and no call
+// synchronises; everything is enqueued on the caller's stream.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+
+#include "common.hpp"
+#include "mfma_path.hpp"
+
+namespace imattn {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+static int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+static int check_hip(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(IM_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  return IM_OK;
+}
+
+static int validate_shape(const im_shape_t* s) {
+  if (!s) return fail(IM_ERR_INVALID, "shape is NULL");
+  if (s->batch < 1) return fail(IM_ERR_INVALID, "batch must be >= 1 (got %d)", s->batch);
+  if (s->n_seg < 1 || s->n_seg > IM_MAX_SEG)
+    return fail(IM_ERR_INVALID, "n_seg must be in 1..%d (got %d)", IM_MAX_SEG, s->n_seg);
+  long T = 0;
+  for (int i = 0; i < s->n_seg; ++i) {
+    if (s->seg_len[i] < 1) return fail(IM_ERR_INVALID, "seg_len[%d] must be >= 1 (got %d)", i, s->seg_len[i]);
+    T += s->seg_len[i];
+  }
+  if (T > (1 << 24)) return fail(IM_ERR_INVALID, "T_m = %ld too large", T);
+  if (s->d_model < 1 || s->n_heads < 1 || s->d_model % s->n_heads != 0)
+    return fail(IM_ERR_INVALID, "d_model (%d) must be a positive multiple of n_heads (%d)", s->d_model, s->n_heads);
+  const int nb = s->n_seg * s->n_seg;
+  if (nb < 64 && (s->live_mask >> nb) != 0)
+    return fail(IM_ERR_INVALID, "live_mask has bits set at or above n_seg^2 = %d", nb);
+  if (!(s->scale == s->scale) || isinf(s->scale)) return fail(IM_ERR_INVALID, "scale must be finite");
+  if (s->dtype != IM_DTYPE_F32 && s->dtype != IM_DTYPE_BF16)
+    return fail(IM_ERR_INVALID, "dtype must be IM_DTYPE_F32 or IM_DTYPE_BF16 (got %d)", s->dtype);
+  if ((long)s->batch * T * s->d_model > (1l << 40)) return fail(IM_ERR_INVALID, "problem too large");
+  return IM_OK;
+}
+
+// Which kernel family serves this shape.
+enum Path { PATH_ROWLANE, PATH_MFMA, PATH_NONE };
+static Path pick_path(const im_shape_t* s) {
+  const int dh = s->d_model / s->n_heads;
+  if (s->dtype == IM_DTYPE_BF16 && mfma_supports(s->d_model, dh)) return PATH_MFMA;
+  if (rowlane_supports(dh)) return PATH_ROWLANE;
+  return PATH_NONE;
+}
+static int check_supported(const im_shape_t* s) {
+  if (pick_path(s) == PATH_NONE)
+    return fail(IM_ERR_UNSUPPORTED,
+                "no kernel for dtype %d with head dimension %d (supported: head dim <= 16 for fp32/bf16; bf16 with "
+                "head dim 64 and d_model %% 64 == 0)",
+                s->dtype, s->d_model / s->n_heads);
+  return IM_OK;
+}
+
+// Sec. 6 "Decomposition": per query segment the set of live key segments, per key
+// segment the set of query segments that read it, and the tile order (segments
+// by decreasing live range, i.e. decreasing work per row).
+static void build_geo(const im_shape_t* s, int q_tile, int k_tile, Geo* g) {
+  memset(g, 0, sizeof(*g));
+  g->B = s->batch; g->H = s->n_heads; g->d = s->d_model; g->dh = s->d_model / s->n_heads; g->n_seg = s->n_seg;
+  int off = 0;
+  for (int i = 0; i < s->n_seg; ++i) { g->seg_off[i] = off; g->seg_len[i] = s->seg_len[i]; off += s->seg_len[i]; }
+  g->seg_off[s->n_seg] = off;
+  g->T = off;
+  for (int i = 0; i < s->n_seg; ++i)
+    for (int j = 0; j < s->n_seg; ++j)
+      if ((s->live_mask >> (i * s->n_seg + j)) & 1ull) { g->q_live[i] |= 1u << j; g->k_live[j] |= 1u << i; }
+  auto order = [&](const unsigned* live, int tile_rows, int* ord, int* prefix, int* nord) {
+    long work[IM_MAX_SEG];
+    int n = 0;
+    for (int i = 0; i < s->n_seg; ++i) {
+      if (!live[i]) continue;
+      long w = 0;
+      for (int j = 0; j < s->n_seg; ++j) if ((live[i] >> j) & 1u) w += s->seg_len[j];
+      work[i] = w;
+      ord[n++] = i;
+    }
+    std::stable_sort(ord, ord + n, [&](int a, int b) { return work[a] > work[b]; });
+    prefix[0] = 0;
+    for (int k = 0; k < n; ++k) prefix[k + 1] = prefix[k] + (s->seg_len[ord[k]] + tile_rows - 1) / tile_rows;
+    *nord = n;
+  };
+  order(g->q_live, q_tile, g->q_order, g->q_tile_prefix, &g->q_nord);
+  order(g->k_live, k_tile, g->k_order, g->k_tile_prefix, &g->k_nord);
+  g->scale = s->scale;
+  g->scale_log2e = s->scale * 1.44269504088896340736f;
+}
+
+static inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+struct Bump {
+  char* base; size_t off, cap;
+  void* take(size_t n) { void* p = base ? base + off : nullptr; off += align256(n); return p; }
+};
+
+// Layout of the forward's saved tensors (also used from workspace when saved == NULL).
+struct SavedLayout {
+  size_t qkv, o, lse, extra, total;  // byte offsets; `extra` = transposed copies of the MFMA path
+};
+static SavedLayout saved_layout(const im_shape_t* s) {
+  const size_t es = s->dtype == IM_DTYPE_BF16 ? 2 : 4;
+  long T = 0;
+  for (int i = 0; i < s->n_seg; ++i) T += s->seg_len[i];
+  const size_t R = (size_t)s->batch * T, d = s->d_model;
+  SavedLayout L;
+  size_t off = 0;
+  L.qkv = off; off += align256(R * 3 * d * es);
+  L.o = off; off += align256(R * d * es);
+  L.lse = off; off += align256((size_t)s->batch * s->n_heads * T * sizeof(float));
+  L.extra = off;
+  if (pick_path(s) == PATH_MFMA) off += align256(mfma_saved_extra_bytes(s->batch, (int)T, (int)d));
+  L.total = off;
+  return L;
+}
+
+static size_t bwd_workspace_bytes(const im_shape_t* s) {
+  const size_t es = s->dtype == IM_DTYPE_BF16 ? 2 : 4;
+  long T = 0;
+  for (int i = 0; i < s->n_seg; ++i) T += s->seg_len[i];
+  const size_t R = (size_t)s->batch * T, d = s->d_model;
+  if (pick_path(s) == PATH_MFMA) return mfma_bwd_workspace_bytes(s->batch, (int)T, (int)d, s->n_heads);
+  size_t n = 0;
+  n += align256(R * d * es);                                          // dO
+  n += align256(R * 3 * d * es);                                      // dQ | dK | dV
+  n += align256((size_t)s->batch * s->n_heads * T * sizeof(float));   // delta
+  n += align256(std::max(gemm_alu_partial_bytes((int)d, (int)(3 * d), (int)R, nullptr),
+                         gemm_alu_partial_bytes((int)d, (int)d, (int)R, nullptr)));
+  n += align256(colsum_partial_bytes((int)R, (int)d));
+  n += align256(3 * d * d * sizeof(float));                           // sinks for unwanted weight gradients
+  return n;
+}
+
+static hipStream_t as_stream(void* p) { return (hipStream_t)p; }
+
+// ---------------------------------------------------------------------------------------------
+// forward on the ALU path; `res` (same layout as y) is added to y when not NULL.
+static int fwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const void* wk, const void* wv,
+                       const void* wo, const void* bq, const void* bk, const void* bv, const void* bo,
+                       const int32_t* valid_len, const uint8_t* key_pad, void* y, const void* res, char* sv,
+                       hipStream_t st) {
+  const int bf = s->dtype == IM_DTYPE_BF16;
+  const size_t es = bf ? 2 : 4;
+  Geo g;
+  build_geo(s, 64, 64, &g);
+  const SavedLayout L = saved_layout(s);
+  const long R = (long)g.B * g.T, d = g.d;
+  char* qkv = sv + L.qkv;
+  void* o = sv + L.o;
+  float* lse2 = (float*)(sv + L.lse);
+
+  GemmDesc p;
+  memset(&p, 0, sizeof(p));
+  p.A = x; p.sam = d; p.sak = 1;
+  p.B[0] = wq; p.B[1] = wk; p.B[2] = wv; p.sbk = d; p.sbn = 1; p.b_split = 1; p.n_per = (int)d;
+  p.bias[0] = bq; p.bias[1] = bk; p.bias[2] = bv; p.bias_split = 1;
+  p.C[0] = qkv; p.ldc = 3 * d; p.M = (int)R; p.N = (int)(3 * d); p.K = (int)d;
+  int rc = launch_gemm_alu(p, bf, bf, bf, st);
+  if (rc) return rc;
+
+  rc = launch_rowlane_fwd(g, bf, qkv, qkv + d * es, qkv + 2 * d * es, 3 * d, valid_len, key_pad, o, d, lse2, st);
+  if (rc) return rc;
+
+  memset(&p, 0, sizeof(p));
+  p.A = o; p.sam = d; p.sak = 1;
+  p.B[0] = wo; p.sbk = d; p.sbn = 1;
+  p.bias[0] = bo; p.C[0] = y; p.ldc = d; p.res = res; p.M = (int)R; p.N = (int)d; p.K = (int)d;
+  rc = launch_gemm_alu(p, bf, bf, bf, st);
+  if (rc) return rc;
+  return check_hip("im_attention_fwd launch");
+}
+
+static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const void* wk, const void* wv,
+                       const void* wo, const int32_t* valid_len, const uint8_t* key_pad, const char* sv,
+                       const void* dy, void* dx, void* dwq, void* dwk, void* dwv, void* dwo, void* dbq, void* dbk,
+                       void* dbv, void* dbo, char* ws, hipStream_t st) {
+  const int bf = s->dtype == IM_DTYPE_BF16;
+  const size_t es = bf ? 2 : 4;
+  Geo g;
+  build_geo(s, 64, 64, &g);
+  const SavedLayout L = saved_layout(s);
+  const long R = (long)g.B * g.T, d = g.d;
+  const char* qkv = sv + L.qkv;
+  const void* o = sv + L.o;
+  const float* lse2 = (const float*)(sv + L.lse);
+
+  Bump b{ws, 0, 0};
+  char* d_o = (char*)b.take(R * d * es);
+  char* dqkv = (char*)b.take(R * 3 * d * es);
+  float* delta = (float*)b.take((size_t)g.B * g.H * g.T * sizeof(float));
+  int split = 1;
+  const size_t pbytes = std::max(gemm_alu_partial_bytes((int)d, (int)(3 * d), (int)R, &split),
+                                 gemm_alu_partial_bytes((int)d, (int)d, (int)R, nullptr));
+  float* partial = (float*)b.take(pbytes);
+  float* cpart = (float*)b.take(colsum_partial_bytes((int)R, (int)d));
+  float* sink = (float*)b.take(3 * d * d * sizeof(float));
+
+  GemmDesc p;
+  int rc;
+  // dO = dy Wo^T
+  memset(&p, 0, sizeof(p));
+  p.A = dy; p.sam = d; p.sak = 1;
+  p.B[0] = wo; p.sbk = 1; p.sbn = d;
+  p.C[0] = d_o; p.ldc = d; p.M = (int)R; p.N = (int)d; p.K = (int)d;
+  if ((rc = launch_gemm_alu(p, bf, bf, bf, st))) return rc;
+  // dWo = O^T dy
+  if (dwo) {
+    memset(&p, 0, sizeof(p));
+    p.A = o; p.sam = 1; p.sak = d;
+    p.B[0] = dy; p.sbk = d; p.sbn = 1;
+    p.C[0] = dwo; p.ldc = d; p.M = (int)d; p.N = (int)d; p.K = (int)R;
+    gemm_alu_partial_bytes((int)d, (int)d, (int)R, &p.split_k);
+    p.partial = partial;
+    if ((rc = launch_gemm_alu(p, bf, bf, 0, st))) return rc;
+  }
+  if (dbo && (rc = launch_colsum(dy, d, (int)R, (int)d, bf, (float*)dbo, cpart, st))) return rc;
+
+  rc = launch_rowlane_bwd(g, bf, qkv, qkv + d * es, qkv + 2 * d * es, 3 * d, o, d_o, d, lse2, valid_len, key_pad,
+                          delta, dqkv, dqkv + d * es, dqkv + 2 * d * es, 3 * d, st);
+  if (rc) return rc;
+
+  // dWq | dWk | dWv = x^T [dQ | dK | dV]
+  if (dwq || dwk || dwv) {
+    memset(&p, 0, sizeof(p));
+    p.A = x; p.sam = 1; p.sak = d;
+    p.B[0] = dqkv; p.sbk = 3 * d; p.sbn = 1;
+    p.C[0] = dwq ? dwq : sink; p.C[1] = dwk ? dwk : sink + d * d; p.C[2] = dwv ? dwv : sink + 2 * d * d;
+    p.c_split = 1; p.n_per = (int)d; p.ldc = d; p.M = (int)d; p.N = (int)(3 * d); p.K = (int)R;
+    p.split_k = split; p.partial = partial;
+    if ((rc = launch_gemm_alu(p, bf, bf, 0, st))) return rc;
+  }
+  void* dbs[3] = {dbq, dbk, dbv};
+  for (int i = 0; i < 3; ++i)
+    if (dbs[i] && (rc = launch_colsum(dqkv + i * d * es, 3 * d, (int)R, (int)d, bf, (float*)dbs[i], cpart, st)))
+      return rc;
+  // dx = dQ Wq^T + dK Wk^T + dV Wv^T
+  if (dx) {
+    memset(&p, 0, sizeof(p));
+    p.A = dqkv; p.sam = 3 * d; p.sak = 1;
+    p.B[0] = wq; p.B[1] = wk; p.B[2] = wv; p.sbk = 1; p.sbn = d; p.b_split = 2; p.k_per = (int)d;
+    p.C[0] = dx; p.ldc = d; p.M = (int)R; p.N = (int)d; p.K = (int)(3 * d);
+    if ((rc = launch_gemm_alu(p, bf, bf, bf, st))) return rc;
+  }
+  return check_hip("im_attention_bwd launch");
+}
+
+}  // namespace imattn
+
+using namespace imattn;
+
+extern "C" {
+
+const char* im_last_error(void) { return g_err; }
+const char* im_version(void) { return "imattn 0.1 gfx950"; }
+
+int im_schedule_build(const im_shape_t* shape, int32_t tile_rows, im_work_item_t* items, int32_t max_items,
+                      int32_t* n_items, int64_t* n_pairs) {
+  int rc = validate_shape(shape);
+  if (rc) return rc;
+  if (tile_rows < 1) return fail(IM_ERR_INVALID, "tile_rows must be >= 1");
+  Geo g;
+  build_geo(shape, tile_rows, tile_rows, &g);
+  const int n = g.q_tile_prefix[g.q_nord];
+  int64_t pairs = 0;
+  if (items && max_items < n) return fail(IM_ERR_INVALID, "max_items (%d) < number of work items (%d)", max_items, n);
+  for (int t = 0; t < n; ++t) {
+    int seg, start;
+    decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, tile_rows, t, seg, start);
+    im_work_item_t it;
+    memset(&it, 0, sizeof(it));
+    it.q_seg = seg; it.q_start = start; it.q_rows = std::min(tile_rows, g.seg_len[seg] - start);
+    long klen = 0;
+    for (int j = 0; j < g.n_seg; ++j)
+      if ((g.q_live[seg] >> j) & 1u) { it.key_seg[it.n_key_seg++] = j; klen += g.seg_len[j]; }
+    it.pairs = (int64_t)it.q_rows * klen;
+    pairs += it.pairs;
+    if (items) items[t] = it;
+  }
+  if (n_items) *n_items = n;
+  if (n_pairs) *n_pairs = pairs;
+  return IM_OK;
+}
+
+int im_attention_sizes(const im_shape_t* shape, size_t* saved_bytes, size_t* workspace_bytes) {
+  int rc = validate_shape(shape);
+  if (rc) return rc;
+  if ((rc = check_supported(shape))) return rc;
+  const SavedLayout L = saved_layout(shape);
+  if (saved_bytes) *saved_bytes = L.total;
+  if (workspace_bytes) {
+    size_t fwd = L.total;  // inference keeps Q, K, V, O, LSE in the workspace
+    if (pick_path(shape) == PATH_MFMA) fwd += mfma_fwd_workspace_bytes(shape->d_model);
+    *workspace_bytes = std::max(fwd, bwd_workspace_bytes(shape));
+  }
+  return IM_OK;
+}
+
+int im_attention_fwd(const im_shape_t* shape, const void* x, const void* wq, const void* wk, const void* wv,
+                     const void* wo, const void* bq, const void* bk, const void* bv, const void* bo,
+                     const int32_t* valid_len, const uint8_t* key_pad, void* y, void* saved, void* workspace,
+                     size_t workspace_bytes, void* hip_stream) {
+  int rc = validate_shape(shape);
+  if (rc) return rc;
+  if ((rc = check_supported(shape))) return rc;
+  if (!x || !wq || !wk || !wv || !wo || !y) return fail(IM_ERR_INVALID, "x, wq, wk, wv, wo and y must not be NULL");
+  const SavedLayout L = saved_layout(shape);
+  const Path path = pick_path(shape);
+  size_t need = saved ? 0 : L.total;
+  if (path == PATH_MFMA) need += mfma_fwd_workspace_bytes(shape->d_model);
+  if (need > 0 && (!workspace || workspace_bytes < need))
+    return fail(IM_ERR_WORKSPACE, "im_attention_fwd needs %zu workspace bytes, got %zu", need, workspace_bytes);
+  char* sv = saved ? (char*)saved : (char*)workspace;
+  char* ws = saved ? (char*)workspace : (char*)workspace + L.total;
+  if (path == PATH_MFMA)
+    return mfma_attention_fwd(shape, x, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, y, nullptr, sv, L.qkv,
+                              L.o, L.lse, L.extra, ws, as_stream(hip_stream));
+  return fwd_rowlane(shape, x, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, y, nullptr, sv,
+                     as_stream(hip_stream));
+}
+
+int im_attention_bwd(const im_shape_t* shape, const void* x, const void* wq, const void* wk, const void* wv,
+                     const void* wo, const int32_t* valid_len, const uint8_t* key_pad, const void* saved,
+                     const void* dy, void* dx, void* dwq, void* dwk, void* dwv, void* dwo, void* dbq, void* dbk,
+                     void* dbv, void* dbo, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = validate_shape(shape);
+  if (rc) return rc;
+  if ((rc = check_supported(shape))) return rc;
+  if (!x || !wq || !wk || !wv || !wo || !saved || !dy)
+    return fail(IM_ERR_INVALID, "x, wq, wk, wv, wo, saved and dy must not be NULL");
+  const size_t need = bwd_workspace_bytes(shape);
+  if (!workspace || workspace_bytes < need)
+    return fail(IM_ERR_WORKSPACE, "im_attention_bwd needs %zu workspace bytes, got %zu", need, workspace_bytes);
+  const SavedLayout L = saved_layout(shape);
+  if (pick_path(shape) == PATH_MFMA)
+    return mfma_attention_bwd(shape, x, wq, wk, wv, wo, valid_len, key_pad, (const char*)saved, L.qkv, L.o, L.lse,
+                              L.extra, dy, dx, dwq, dwk, dwv, dwo, dbq, dbk, dbv, dbo, (char*)workspace,
+                              as_stream(hip_stream));
+  return bwd_rowlane(shape, x, wq, wk, wv, wo, valid_len, key_pad, (const char*)saved, dy, dx, dwq, dwk, dwv, dwo, dbq,
+                     dbk, dbv, dbo, (char*)workspace, as_stream(hip_stream));
+}
+
+static int layer_check(const im_shape_t* shape, int32_t d_ff) {
+  int rc = validate_shape(shape);
+  if (rc) return rc;
+  if ((rc = check_supported(shape))) return rc;
+  if (d_ff < 1) return fail(IM_ERR_INVALID, "d_ff must be >= 1 (got %d)", d_ff);
+  return IM_OK;
+}
+
+static size_t layer_ws(const im_shape_t* s, int32_t d_ff, size_t* attn_ws_bytes) {
+  const size_t es = s->dtype == IM_DTYPE_BF16 ? 2 : 4;
+  long T = 0;
+  for (int i = 0; i < s->n_seg; ++i) T += s->seg_len[i];
+  const size_t R = (size_t)s->batch * T, d = s->d_model;
+  size_t aws = saved_layout(s).total;
+  if (pick_path(s) == PATH_MFMA) aws += mfma_fwd_workspace_bytes(s->d_model);
+  if (attn_ws_bytes) *attn_ws_bytes = aws;
+  return align256(R * d * es) /* LN out */ + align256(R * d * es) /* h */ + align256(R * (size_t)d_ff * es) + align256(aws);
+}
+
+int gsit_layer_sizes(const im_shape_t* shape, int32_t d_ff, size_t* workspace_bytes) {
+  int rc = layer_check(shape, d_ff);
+  if (rc) return rc;
+  if (workspace_bytes) *workspace_bytes = layer_ws(shape, d_ff, nullptr);
+  return IM_OK;
+}
+
+int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const void* ln1_g, const void* ln1_b,
+                   const void* wq, const void* wk, const void* wv, const void* wo, const void* bq, const void* bk,
+                   const void* bv, const void* bo, const void* ln2_g, const void* ln2_b, const void* w1,
+                   const void* b1, const void* w2, const void* b2, float ln_eps, const int32_t* valid_len,
+                   const uint8_t* key_pad, void* y, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = layer_check(shape, d_ff);
+  if (rc) return rc;
+  if (!x || !ln1_g || !ln1_b || !wq || !wk || !wv || !wo || !ln2_g || !ln2_b || !w1 || !w2 || !y)
+    return fail(IM_ERR_INVALID, "x, LayerNorm parameters, wq, wk, wv, wo, w1, w2 and y must not be NULL");
+  if (!(ln_eps >= 0.f)) return fail(IM_ERR_INVALID, "ln_eps must be >= 0");
+  size_t aws = 0;
+  const size_t need = layer_ws(shape, d_ff, &aws);
+  if (!workspace || workspace_bytes < need)
+    return fail(IM_ERR_WORKSPACE, "gsit_layer_fwd needs %zu workspace bytes, got %zu", need, workspace_bytes);
+  hipStream_t st = as_stream(hip_stream);
+  const int bf = shape->dtype == IM_DTYPE_BF16;
+  const size_t es = bf ? 2 : 4;
+  long T = 0;
+  for (int i = 0; i < shape->n_seg; ++i) T += shape->seg_len[i];
+  const long R = (long)shape->batch * T, d = shape->d_model;
+  Bump b{(char*)workspace, 0, 0};
+  void* u = b.take(R * d * es);
+  void* h = b.take(R * d * es);
+  void* z = b.take(R * (size_t)d_ff * es);
+  char* aw = (char*)b.take(aws);
+
+  if ((rc = launch_layernorm(x, ln1_g, ln1_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
+  // h = x + IMAttention(u)
+  const SavedLayout L = saved_layout(shape);
+  if (pick_path(shape) == PATH_MFMA)
+    rc = mfma_attention_fwd(shape, u, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, h, x, aw, L.qkv, L.o, L.lse,
+                            L.extra, aw + L.total, st);
+  else
+    rc = fwd_rowlane(shape, u, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, h, x, aw, st);
+  if (rc) return rc;
+  if ((rc = launch_layernorm(h, ln2_g, ln2_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
+  // z = GELU(u W1 + b1);  y = h + z W2 + b2
+  GemmDesc p;
+  memset(&p, 0, sizeof(p));
+  p.A = u; p.sam = d; p.sak = 1; p.B[0] = w1; p.sbk = d_ff; p.sbn = 1; p.bias[0] = b1;
+  p.C[0] = z; p.ldc = d_ff; p.M = (int)R; p.N = d_ff; p.K = (int)d; p.gelu = 1;
+  if ((rc = launch_gemm_alu(p, bf, bf, bf, st))) return rc;
+  memset(&p, 0, sizeof(p));
+  p.A = z; p.sam = d_ff; p.sak = 1; p.B[0] = w2; p.sbk = d; p.sbn = 1; p.bias[0] = b2;
+  p.C[0] = y; p.ldc = d; p.res = h; p.M = (int)R; p.N = (int)d; p.K = d_ff;
+  if ((rc = launch_gemm_alu(p, bf, bf, bf, st))) return rc;
+  return check_hip("gsit_layer_fwd launch");
+}
+
+}  // extern "C"

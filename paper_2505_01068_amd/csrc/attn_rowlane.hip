@@ -1,0 +1,360 @@
+// Row-per-lane IM attention for small head dimensions (dh <= 16), plain fp32 ALU.
+//
+// The multimodal-sentiment shapes have head dimension 5..8: a contraction that
+// short cannot fill an MFMA tile, so the live-block products are done as FMAs
+// with one query row (forward, dQ) or one key row (dK/dV) per lane and the
+// other operand broadcast from LDS.  Each workgroup is one 64-wide wavefront
+// owning a tile of 64 rows of one modality segment; it visits only the key
+// (query) segments the Interlaced Mask leaves live for its segment (Sec. 6
+// "Decomposition"), trimmed to the valid length, and keeps one running maximum
+// and sum per row across all of them (joint row softmax, Sec. 7.1).
+#include "common.hpp"
+
+namespace imattn {
+
+constexpr int RL_ROWS = 64;    // rows per tile == lanes
+constexpr int RL_CHUNK = 128;  // rows of the other operand staged in LDS at a time
+
+template <typename T, int DHP>
+__global__ __launch_bounds__(RL_ROWS) void rowlane_fwd_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K,
+                                                              const T* __restrict__ V, long ld,
+                                                              const int32_t* __restrict__ valid_len,
+                                                              const uint8_t* __restrict__ key_pad, T* __restrict__ O,
+                                                              long ldo, float* __restrict__ lse2) {
+  __shared__ float sK[RL_CHUNK][DHP];
+  __shared__ float sV[RL_CHUNK][DHP];
+  __shared__ float sBias[RL_CHUNK];
+  const int lane = threadIdx.x, h = blockIdx.y, b = blockIdx.z;
+  int qs, q0;
+  decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, RL_ROWS, blockIdx.x, qs, q0);
+  const int row = q0 + lane;
+  const bool active = row < g.seg_len[qs];
+  const long t = (long)b * g.T + g.seg_off[qs] + (active ? row : 0);
+  const int dh = g.dh, hc = h * dh;
+
+  float q[DHP], acc[DHP];
+#pragma unroll
+  for (int e = 0; e < DHP; ++e) {
+    q[e] = (e < dh) ? ldf(Q + t * ld + hc + e) * g.scale_log2e : 0.f;
+    acc[e] = 0.f;
+  }
+  float m = IM_NEG_INF, l = 0.f;
+
+  const unsigned live = g.q_live[qs];
+  for (int j = 0; j < g.n_seg; ++j) {
+    if (!((live >> j) & 1u)) continue;
+    int klen = g.seg_len[j];
+    if (valid_len) klen = min(klen, max(0, valid_len[b * g.n_seg + j]));
+    const long kbase = (long)b * g.T + g.seg_off[j];
+    for (int c0 = 0; c0 < klen; c0 += RL_CHUNK) {
+      const int n = min(RL_CHUNK, klen - c0);
+      const int n4 = (n + 3) & ~3;
+      __syncthreads();
+      for (int i = lane; i < n4 * DHP; i += RL_ROWS) {
+        const int c = i / DHP, e = i % DHP;
+        const bool ok = (c < n) && (e < dh);
+        const long a = (kbase + c0 + c) * ld + hc + e;
+        sK[c][e] = ok ? ldf(K + a) : 0.f;
+        sV[c][e] = ok ? ldf(V + a) : 0.f;
+      }
+      for (int c = lane; c < n4; c += RL_ROWS) {
+        bool ok = c < n;
+        if (ok && key_pad) ok = key_pad[(long)b * g.T + g.seg_off[j] + c0 + c] == 0;
+        sBias[c] = ok ? 0.f : IM_NEG_INF;
+      }
+      __syncthreads();
+      for (int c = 0; c < n4; c += 4) {
+        float s[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          float a = sBias[c + u];
+#pragma unroll
+          for (int e = 0; e < DHP; ++e) a = fmaf(q[e], sK[c + u][e], a);
+          s[u] = a;
+        }
+        const float mn = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), m);
+        const float ms = (mn == IM_NEG_INF) ? 0.f : mn;
+        const float alpha = exp2f(m - ms);
+        l *= alpha;
+#pragma unroll
+        for (int e = 0; e < DHP; ++e) acc[e] *= alpha;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const float p = exp2f(s[u] - ms);
+          l += p;
+#pragma unroll
+          for (int e = 0; e < DHP; ++e) acc[e] = fmaf(p, sV[c + u][e], acc[e]);
+        }
+        m = mn;
+      }
+    }
+  }
+  if (active) {
+    const float inv = (l > 0.f) ? 1.f / l : 0.f;
+#pragma unroll
+    for (int e = 0; e < DHP; ++e)
+      if (e < dh) stf(O + t * ldo + hc + e, acc[e] * inv);
+    if (lse2) lse2[((long)b * g.H + h) * g.T + g.seg_off[qs] + row] = (l > 0.f) ? m + log2f(l) : IM_NEG_INF;
+  }
+}
+
+// dQ (and delta = rowsum(dO * O)) : one query row per lane, keys broadcast from LDS.
+template <typename T, int DHP>
+__global__ __launch_bounds__(RL_ROWS) void rowlane_dq_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K,
+                                                             const T* __restrict__ V, long ld, const T* __restrict__ O,
+                                                             const T* __restrict__ dO, long ldo,
+                                                             const float* __restrict__ lse2,
+                                                             const int32_t* __restrict__ valid_len,
+                                                             const uint8_t* __restrict__ key_pad,
+                                                             float* __restrict__ delta, T* __restrict__ dQ, long ldg) {
+  __shared__ float sK[RL_CHUNK][DHP];
+  __shared__ float sV[RL_CHUNK][DHP];
+  __shared__ float sBias[RL_CHUNK];
+  const int lane = threadIdx.x, h = blockIdx.y, b = blockIdx.z;
+  int qs, q0;
+  decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, RL_ROWS, blockIdx.x, qs, q0);
+  const int row = q0 + lane;
+  const bool active = row < g.seg_len[qs];
+  const long t = (long)b * g.T + g.seg_off[qs] + (active ? row : 0);
+  const int dh = g.dh, hc = h * dh;
+  const long li = ((long)b * g.H + h) * g.T + g.seg_off[qs] + (active ? row : 0);
+
+  float q[DHP], go[DHP], acc[DHP];
+  float dl = 0.f;
+#pragma unroll
+  for (int e = 0; e < DHP; ++e) {
+    q[e] = (e < dh) ? ldf(Q + t * ld + hc + e) * g.scale_log2e : 0.f;
+    go[e] = (e < dh) ? ldf(dO + t * ldo + hc + e) : 0.f;
+    const float oo = (e < dh) ? ldf(O + t * ldo + hc + e) : 0.f;
+    dl = fmaf(go[e], oo, dl);
+    acc[e] = 0.f;
+  }
+  float ls = lse2[li];
+  if (ls == IM_NEG_INF) ls = __builtin_inff();  // row with no live valid key: every p becomes 0
+  if (active) delta[li] = dl;
+
+  const unsigned live = g.q_live[qs];
+  for (int j = 0; j < g.n_seg; ++j) {
+    if (!((live >> j) & 1u)) continue;
+    int klen = g.seg_len[j];
+    if (valid_len) klen = min(klen, max(0, valid_len[b * g.n_seg + j]));
+    const long kbase = (long)b * g.T + g.seg_off[j];
+    for (int c0 = 0; c0 < klen; c0 += RL_CHUNK) {
+      const int n = min(RL_CHUNK, klen - c0);
+      __syncthreads();
+      for (int i = lane; i < n * DHP; i += RL_ROWS) {
+        const int c = i / DHP, e = i % DHP;
+        const long a = (kbase + c0 + c) * ld + hc + e;
+        sK[c][e] = (e < dh) ? ldf(K + a) : 0.f;
+        sV[c][e] = (e < dh) ? ldf(V + a) : 0.f;
+      }
+      for (int c = lane; c < n; c += RL_ROWS) {
+        bool ok = true;
+        if (key_pad) ok = key_pad[(long)b * g.T + g.seg_off[j] + c0 + c] == 0;
+        sBias[c] = ok ? 0.f : IM_NEG_INF;
+      }
+      __syncthreads();
+      for (int c = 0; c < n; ++c) {
+        float s = sBias[c], dp = 0.f;
+#pragma unroll
+        for (int e = 0; e < DHP; ++e) {
+          s = fmaf(q[e], sK[c][e], s);
+          dp = fmaf(go[e], sV[c][e], dp);
+        }
+        const float p = exp2f(s - ls);
+        const float ds = p * (dp - dl);
+#pragma unroll
+        for (int e = 0; e < DHP; ++e) acc[e] = fmaf(ds, sK[c][e], acc[e]);
+      }
+    }
+  }
+  if (active) {
+#pragma unroll
+    for (int e = 0; e < DHP; ++e)
+      if (e < dh) stf(dQ + t * ldg + hc + e, acc[e] * g.scale);
+  }
+}
+
+// dK, dV : one key row per lane, query rows (Q, dO, lse, delta) broadcast from LDS.
+// Each key segment has a single producer workgroup per tile, so no atomics.
+template <typename T, int DHP>
+__global__ __launch_bounds__(RL_ROWS) void rowlane_dkv_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K,
+                                                              const T* __restrict__ V, long ld,
+                                                              const T* __restrict__ dO, long ldo,
+                                                              const float* __restrict__ lse2,
+                                                              const float* __restrict__ delta,
+                                                              const int32_t* __restrict__ valid_len,
+                                                              const uint8_t* __restrict__ key_pad, T* __restrict__ dK,
+                                                              T* __restrict__ dV, long ldg) {
+  __shared__ float sQ[RL_CHUNK][DHP];
+  __shared__ float sG[RL_CHUNK][DHP];
+  __shared__ float sL[RL_CHUNK];
+  __shared__ float sD[RL_CHUNK];
+  const int lane = threadIdx.x, h = blockIdx.y, b = blockIdx.z;
+  int ks, k0;
+  decode_tile(g.k_order, g.k_tile_prefix, g.k_nord, RL_ROWS, blockIdx.x, ks, k0);
+  const int row = k0 + lane;
+  const bool in_seg = row < g.seg_len[ks];
+  bool valid = in_seg;
+  if (valid && valid_len) valid = row < valid_len[b * g.n_seg + ks];
+  const long t = (long)b * g.T + g.seg_off[ks] + (in_seg ? row : 0);
+  if (valid && key_pad) valid = key_pad[t] == 0;
+  const int dh = g.dh, hc = h * dh;
+
+  float k[DHP], v[DHP], ak[DHP], av[DHP];
+#pragma unroll
+  for (int e = 0; e < DHP; ++e) {
+    k[e] = (e < dh) ? ldf(K + t * ld + hc + e) : 0.f;
+    v[e] = (e < dh) ? ldf(V + t * ld + hc + e) : 0.f;
+    ak[e] = 0.f;
+    av[e] = 0.f;
+  }
+  const unsigned live = g.k_live[ks];
+  for (int i = 0; i < g.n_seg; ++i) {
+    if (!((live >> i) & 1u)) continue;
+    const int qlen = g.seg_len[i];
+    const long qbase = (long)b * g.T + g.seg_off[i];
+    const long lbase = ((long)b * g.H + h) * g.T + g.seg_off[i];
+    for (int r0 = 0; r0 < qlen; r0 += RL_CHUNK) {
+      const int n = min(RL_CHUNK, qlen - r0);
+      __syncthreads();
+      for (int x = lane; x < n * DHP; x += RL_ROWS) {
+        const int r = x / DHP, e = x % DHP;
+        sQ[r][e] = (e < dh) ? ldf(Q + (qbase + r0 + r) * ld + hc + e) * g.scale_log2e : 0.f;
+        sG[r][e] = (e < dh) ? ldf(dO + (qbase + r0 + r) * ldo + hc + e) : 0.f;
+      }
+      for (int r = lane; r < n; r += RL_ROWS) {
+        const float ls = lse2[lbase + r0 + r];
+        sL[r] = (ls == IM_NEG_INF) ? __builtin_inff() : ls;
+        sD[r] = delta[lbase + r0 + r];
+      }
+      __syncthreads();
+      for (int r = 0; r < n; ++r) {
+        float s = 0.f, dp = 0.f;
+#pragma unroll
+        for (int e = 0; e < DHP; ++e) {
+          s = fmaf(sQ[r][e], k[e], s);
+          dp = fmaf(sG[r][e], v[e], dp);
+        }
+        const float p = exp2f(s - sL[r]);
+        const float ds = p * (dp - sD[r]);
+#pragma unroll
+        for (int e = 0; e < DHP; ++e) {
+          av[e] = fmaf(p, sG[r][e], av[e]);
+          ak[e] = fmaf(ds, sQ[r][e], ak[e]);
+        }
+      }
+    }
+  }
+  if (in_seg) {
+    // sQ holds q * scale * log2(e); dK = scale * dS^T q  ==  ln(2) * dS^T (q * scale * log2 e)
+    const float ln2 = 0.69314718055994530942f;
+#pragma unroll
+    for (int e = 0; e < DHP; ++e)
+      if (e < dh) {
+        stf(dK + t * ldg + hc + e, valid ? ak[e] * ln2 : 0.f);
+        stf(dV + t * ldg + hc + e, valid ? av[e] : 0.f);
+      }
+  }
+}
+
+// Zero the gradient rows of segments that no live block reads as keys / as queries.
+template <typename T>
+__global__ void zero_rows_kernel(T* p, long ld, int B, int T_m, int row0, int nrows, int d) {
+  const long n = (long)B * nrows * d;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
+    const int e = i % d;
+    const long r = i / d;
+    const int b = r / nrows, rr = r % nrows;
+    stf(p + ((long)b * T_m + row0 + rr) * ld + e, 0.f);
+  }
+}
+
+bool rowlane_supports(int dh) { return dh >= 1 && dh <= 16; }
+
+template <typename T>
+static int fwd_dispatch(const Geo& g, const T* q, const T* k, const T* v, long ld, const int32_t* vl, const uint8_t* kp,
+                        T* o, long ldo, float* lse2, hipStream_t st) {
+  const int ntiles = g.q_tile_prefix[g.q_nord];
+  if (ntiles == 0) return IM_OK;
+  dim3 grid(ntiles, g.H, g.B), block(RL_ROWS);
+  if (g.dh <= 8)
+    hipLaunchKernelGGL((rowlane_fwd_kernel<T, 8>), grid, block, 0, st, g, q, k, v, ld, vl, kp, o, ldo, lse2);
+  else
+    hipLaunchKernelGGL((rowlane_fwd_kernel<T, 16>), grid, block, 0, st, g, q, k, v, ld, vl, kp, o, ldo, lse2);
+  return IM_OK;
+}
+
+// Rows of query segments with no live block never get written by the kernels: the
+// host zero-fills them (output 0, lse -inf) before launching.
+template <typename T>
+static void zero_dead_rows(const Geo& g, bool query_side, T* p, long ld, hipStream_t st) {
+  for (int s = 0; s < g.n_seg; ++s) {
+    const unsigned live = query_side ? g.q_live[s] : g.k_live[s];
+    if (live) continue;
+    hipLaunchKernelGGL((zero_rows_kernel<T>), dim3(64), dim3(256), 0, st, p, ld, g.B, g.T, g.seg_off[s], g.seg_len[s],
+                       g.d);
+  }
+}
+
+__global__ void fill_lse_kernel(float* lse2, int BH, int T_m, int row0, int nrows) {
+  const long n = (long)BH * nrows;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x)
+    lse2[(i / nrows) * T_m + row0 + (i % nrows)] = IM_NEG_INF;
+}
+
+int launch_rowlane_fwd(const Geo& g, int bf16, const void* q, const void* k, const void* v, long ld,
+                       const int32_t* valid_len, const uint8_t* key_pad, void* o, long ldo, float* lse2,
+                       hipStream_t st) {
+  if (!rowlane_supports(g.dh)) return IM_ERR_UNSUPPORTED;
+  for (int s = 0; s < g.n_seg; ++s)
+    if (!g.q_live[s] && lse2)
+      hipLaunchKernelGGL(fill_lse_kernel, dim3(16), dim3(256), 0, st, lse2, g.B * g.H, g.T, g.seg_off[s], g.seg_len[s]);
+  if (bf16) {
+    zero_dead_rows<bf16_t>(g, true, (bf16_t*)o, ldo, st);
+    return fwd_dispatch<bf16_t>(g, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, ld, valid_len, key_pad,
+                                (bf16_t*)o, ldo, lse2, st);
+  }
+  zero_dead_rows<float>(g, true, (float*)o, ldo, st);
+  return fwd_dispatch<float>(g, (const float*)q, (const float*)k, (const float*)v, ld, valid_len, key_pad, (float*)o,
+                             ldo, lse2, st);
+}
+
+template <typename T>
+static int bwd_dispatch(const Geo& g, const T* q, const T* k, const T* v, long ld, const T* o, const T* d_o, long ldo,
+                        const float* lse2, const int32_t* vl, const uint8_t* kp, float* delta, T* dq, T* dk, T* dv,
+                        long ldg, hipStream_t st) {
+  zero_dead_rows<T>(g, true, dq, ldg, st);
+  zero_dead_rows<T>(g, false, dk, ldg, st);
+  zero_dead_rows<T>(g, false, dv, ldg, st);
+  const int nq = g.q_tile_prefix[g.q_nord], nk = g.k_tile_prefix[g.k_nord];
+  if (nq == 0) return IM_OK;
+  dim3 block(RL_ROWS);
+  if (g.dh <= 8) {
+    hipLaunchKernelGGL((rowlane_dq_kernel<T, 8>), dim3(nq, g.H, g.B), block, 0, st, g, q, k, v, ld, o, d_o, ldo, lse2,
+                       vl, kp, delta, dq, ldg);
+    hipLaunchKernelGGL((rowlane_dkv_kernel<T, 8>), dim3(nk, g.H, g.B), block, 0, st, g, q, k, v, ld, d_o, ldo, lse2,
+                       delta, vl, kp, dk, dv, ldg);
+  } else {
+    hipLaunchKernelGGL((rowlane_dq_kernel<T, 16>), dim3(nq, g.H, g.B), block, 0, st, g, q, k, v, ld, o, d_o, ldo, lse2,
+                       vl, kp, delta, dq, ldg);
+    hipLaunchKernelGGL((rowlane_dkv_kernel<T, 16>), dim3(nk, g.H, g.B), block, 0, st, g, q, k, v, ld, d_o, ldo, lse2,
+                       delta, vl, kp, dk, dv, ldg);
+  }
+  return IM_OK;
+}
+
+int launch_rowlane_bwd(const Geo& g, int bf16, const void* q, const void* k, const void* v, long ld, const void* o,
+                       const void* d_o, long ldo, const float* lse2, const int32_t* valid_len, const uint8_t* key_pad,
+                       float* delta, void* dq, void* dk, void* dv, long ldg, hipStream_t st) {
+  if (!rowlane_supports(g.dh)) return IM_ERR_UNSUPPORTED;
+  if (bf16)
+    return bwd_dispatch<bf16_t>(g, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, ld, (const bf16_t*)o,
+                                (const bf16_t*)d_o, ldo, lse2, valid_len, key_pad, delta, (bf16_t*)dq, (bf16_t*)dk,
+                                (bf16_t*)dv, ldg, st);
+  return bwd_dispatch<float>(g, (const float*)q, (const float*)k, (const float*)v, ld, (const float*)o,
+                             (const float*)d_o, ldo, lse2, valid_len, key_pad, delta, (float*)dq, (float*)dk,
+                             (float*)dv, ldg, st);
+}
+
+}  // namespace imattn

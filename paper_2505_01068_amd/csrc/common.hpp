@@ -1,0 +1,99 @@
+// Shared host/device definitions for the IM attention kernels (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "imattn.h"
+
+namespace imattn {
+
+typedef uint16_t bf16_t;  // raw bfloat16 storage
+
+// Geometry of one IM attention problem, passed to kernels by value.
+// Activations are [B, T, ld] rows with the head h occupying columns
+// [h*dh, (h+1)*dh) of each tensor's row slice.
+struct Geo {
+  int B, H, d, dh, T, n_seg;
+  int seg_off[IM_MAX_SEG + 1];
+  int seg_len[IM_MAX_SEG];
+  unsigned q_live[IM_MAX_SEG];  // query segment i -> bit set of live key segments j
+  unsigned k_live[IM_MAX_SEG];  // key segment j   -> bit set of query segments i that read it
+  // Tile schedule (Sec. 6 "Decomposition"): segments in order of decreasing
+  // work per row; tiles of one segment are consecutive.  Segments with no live
+  // partner are absent.
+  int q_order[IM_MAX_SEG], q_tile_prefix[IM_MAX_SEG + 1], q_nord;
+  int k_order[IM_MAX_SEG], k_tile_prefix[IM_MAX_SEG + 1], k_nord;
+  float scale, scale_log2e;
+};
+
+// tile index -> (segment, first row).  Same code on host (schedule listing)
+// and device (kernels), so the listing is what the kernels execute.
+__host__ __device__ inline void decode_tile(const int* order, const int* prefix, int nord, int tile_rows, int tile,
+                                            int& seg, int& start) {
+  int k = 0;
+  while (k + 1 < nord && tile >= prefix[k + 1]) ++k;
+  seg = order[k];
+  start = (tile - prefix[k]) * tile_rows;
+}
+
+__device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+__device__ __forceinline__ bf16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);                                        // round to nearest even
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float ldf(const float* p) { return *p; }
+__device__ __forceinline__ float ldf(const bf16_t* p) { return bf2f(*p); }
+__device__ __forceinline__ void stf(float* p, float v) { *p = v; }
+__device__ __forceinline__ void stf(bf16_t* p, float v) { *p = f2bf(v); }
+
+#define IM_NEG_INF (-__builtin_inff())
+
+// ---- launchers implemented in the .hip files (all enqueue on `st`, none syncs) ----
+
+// fp32-ALU GEMM  C[m,n] = sum_k A(m,k) B(k,n) (+bias[n]) (+res[m,n]), optional GELU,
+// operands addressed by strides; B / bias / C may be split over up to 3 buffers.
+struct GemmDesc {
+  const void* A;
+  long sam, sak;            // element strides of A(m,k)
+  const void* B[3];
+  long sbk, sbn;            // element strides of B(k,n) inside one B buffer
+  int b_split;              // 0: one B buffer; 1: B[s] holds column block s (n_per columns each); 2: row block s (k_per rows each)
+  int n_per, k_per;         // block extents for the splits (n_per also blocks bias / C when those are split)
+  const void* bias[3];      // bias along N; bias_split = 1: bias[s] belongs to column block s
+  void* C[3];               // outputs; c_split = 1: column block s goes to the [M, n_per] matrix C[s]
+  int c_split, bias_split;
+  long ldc;
+  const void* res;          // residual added in the epilogue (same dtype/ld as C[0]) or NULL
+  int M, N, K;
+  int gelu;                 // apply exact GELU after bias
+  int split_k;              // >1: partial sums in `partial` [split_k, M, N] fp32, reduced in fixed order
+  float* partial;
+  // batched-K form (weight gradients): K runs over kb batches of kt rows; A/B advance by sab/sbb per batch
+  int kb, kt;
+  long sab, sbb;
+};
+int launch_gemm_alu(const GemmDesc& g, int a_bf16, int b_bf16, int c_bf16, hipStream_t st);
+size_t gemm_alu_partial_bytes(int M, int N, int K, int* split_k);
+
+// column sums of a [R, n] matrix (bias gradients), deterministic two-stage
+int launch_colsum(const void* a, long lda, int R, int n, int a_bf16, float* out, float* partial, hipStream_t st);
+size_t colsum_partial_bytes(int R, int n);
+
+// row-per-lane attention for small head dims (plain ALU)
+int launch_rowlane_fwd(const Geo& g, int bf16, const void* q, const void* k, const void* v, long ld,
+                       const int32_t* valid_len, const uint8_t* key_pad, void* o, long ldo, float* lse2,
+                       hipStream_t st);
+int launch_rowlane_bwd(const Geo& g, int bf16, const void* q, const void* k, const void* v, long ld, const void* o,
+                       const void* d_o, long ldo, const float* lse2, const int32_t* valid_len, const uint8_t* key_pad,
+                       float* delta, void* dq, void* dk, void* dv, long ldg, hipStream_t st);
+bool rowlane_supports(int dh);
+
+// LayerNorm rows
+int launch_layernorm(const void* x, const void* gamma, const void* beta, void* y, int R, int d, float eps, int bf16,
+                     hipStream_t st);
+
+void set_error(const char* fmt, ...);
+
+}  // namespace imattn

@@ -1,0 +1,243 @@
+// fp32-ALU GEMM with strided operands, used for the projections of the small
+// multimodal-sentiment shapes (d = 32..64: the whole weight fits in a few LDS
+// tiles and the work is bandwidth / launch bound, not MFMA bound) and as the
+// fp32 path of the library.  Also: deterministic column sums and LayerNorm.
+#include "common.hpp"
+
+namespace imattn {
+
+constexpr int GA_BM = 64, GA_BN = 64, GA_BK = 16, GA_THREADS = 256;
+
+struct GemmDev {
+  const void* A;
+  long sam, sak;
+  const void* B[3];
+  long sbk, sbn;
+  int b_split, n_per, k_per;
+  const void* bias[3];
+  void* C[3];
+  int c_split, bias_split;
+  long ldc;
+  const void* res;
+  int M, N, K, gelu, split_k;
+  float* partial;
+  int kb, kt;
+  long sab, sbb;
+};
+
+__device__ __forceinline__ float gelu_exact(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752440f)); }
+
+template <typename TA, typename TB, typename TC>
+__global__ __launch_bounds__(GA_THREADS) void gemm_alu_kernel(GemmDev g) {
+  __shared__ __attribute__((aligned(16))) float As[GA_BK][GA_BM + 4];
+  __shared__ __attribute__((aligned(16))) float Bs[GA_BK][GA_BN + 4];
+  const int tid = threadIdx.x;
+  const int m0 = blockIdx.y * GA_BM, n0 = blockIdx.x * GA_BN;
+  const int tx = tid % 16, ty = tid / 16;
+  const TA* A = (const TA*)g.A;
+
+  // K range of this split
+  const int ktiles = (g.K + GA_BK - 1) / GA_BK;
+  const int per_split = (ktiles + g.split_k - 1) / g.split_k;
+  const int kt_begin = blockIdx.z * per_split;
+  const int kt_end = min(ktiles, kt_begin + per_split);
+
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+
+  const bool a_kfast = (g.sak == 1);
+  const bool b_nfast = (g.sbn == 1);
+  for (int kt = kt_begin; kt < kt_end; ++kt) {
+    const int kbase = kt * GA_BK;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int idx = tid + u * GA_THREADS;
+      int m, k;
+      if (a_kfast) { k = idx % GA_BK; m = idx / GA_BK; } else { m = idx % GA_BM; k = idx / GA_BM; }
+      const int gm = m0 + m, gk = kbase + k;
+      float v = 0.f;
+      if (gm < g.M && gk < g.K) {
+        long off;
+        if (g.kb > 1) { const int bb = gk / g.kt, kk = gk % g.kt; off = bb * g.sab + (long)kk * g.sak; }
+        else off = (long)gk * g.sak;
+        v = ldf(A + (long)gm * g.sam + off);
+      }
+      As[k][m] = v;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int idx = tid + u * GA_THREADS;
+      int n, k;
+      if (b_nfast) { n = idx % GA_BN; k = idx / GA_BN; } else { k = idx % GA_BK; n = idx / GA_BK; }
+      const int gn = n0 + n, gk = kbase + k;
+      float v = 0.f;
+      if (gn < g.N && gk < g.K) {
+        int sel = 0, kk = gk, nn = gn;
+        long boff = 0;
+        if (g.b_split == 1) { sel = gn / g.n_per; nn = gn % g.n_per; }
+        else if (g.b_split == 2) { sel = gk / g.k_per; kk = gk % g.k_per; }
+        if (g.kb > 1) { const int bb = gk / g.kt; kk = gk % g.kt; boff = bb * g.sbb; }
+        v = ldf((const TB*)g.B[sel] + boff + (long)kk * g.sbk + (long)nn * g.sbn);
+      }
+      Bs[k][n] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < GA_BK; ++k) {
+      const float4 a = *(const float4*)&As[k][ty * 4];
+      const float4 b = *(const float4*)&Bs[k][tx * 4];
+      const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int gm = m0 + ty * 4 + i;
+    if (gm >= g.M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int gn = n0 + tx * 4 + j;
+      if (gn >= g.N) continue;
+      float v = acc[i][j];
+      if (g.split_k > 1) {
+        g.partial[((long)blockIdx.z * g.M + gm) * g.N + gn] = v;
+        continue;
+      }
+      int sel = 0, nn = gn;
+      if (g.n_per > 0) { sel = gn / g.n_per; nn = gn % g.n_per; }
+      const int bsel = g.bias_split ? sel : 0;
+      if (g.bias[bsel]) v += ldf((const TC*)g.bias[bsel] + (g.bias_split ? nn : gn));
+      if (g.gelu) v = gelu_exact(v);
+      if (g.c_split) {
+        stf((TC*)g.C[sel] + (long)gm * g.ldc + nn, v);
+      } else {
+        if (g.res) v += ldf((const TC*)g.res + (long)gm * g.ldc + gn);
+        stf((TC*)g.C[0] + (long)gm * g.ldc + gn, v);
+      }
+    }
+  }
+}
+
+// Sum split-K partials in a fixed order and write fp32 outputs (weight gradients).
+__global__ void gemm_splitk_reduce_kernel(GemmDev g) {
+  const long n_out = (long)g.M * g.N;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n_out; i += (long)gridDim.x * blockDim.x) {
+    float s = 0.f;
+    for (int z = 0; z < g.split_k; ++z) s += g.partial[z * n_out + i];
+    const int gm = i / g.N, gn = i % g.N;
+    int sel = 0, nn = gn;
+    if (g.n_per > 0) { sel = gn / g.n_per; nn = gn % g.n_per; }
+    if (g.c_split) ((float*)g.C[sel])[(long)gm * g.ldc + nn] = s;
+    else ((float*)g.C[0])[(long)gm * g.ldc + gn] = s;
+  }
+}
+
+size_t gemm_alu_partial_bytes(int M, int N, int K, int* split_k) {
+  // Split only reductions that are much longer than the output is wide (weight gradients).
+  int s = 1;
+  const long tiles = (long)((M + GA_BM - 1) / GA_BM) * ((N + GA_BN - 1) / GA_BN);
+  if (K >= 2048 && tiles < 256) {
+    s = (int)((512 + tiles - 1) / tiles);
+    const int ktiles = (K + GA_BK - 1) / GA_BK;
+    if (s > ktiles / 8) s = ktiles / 8;
+    if (s < 1) s = 1;
+  }
+  if (split_k) *split_k = s;
+  return s > 1 ? (size_t)s * M * N * sizeof(float) : 0;
+}
+
+int launch_gemm_alu(const GemmDesc& d, int a_bf16, int b_bf16, int c_bf16, hipStream_t st) {
+  GemmDev g;
+  g.A = d.A; g.sam = d.sam; g.sak = d.sak;
+  for (int i = 0; i < 3; ++i) { g.B[i] = d.B[i]; g.bias[i] = d.bias[i]; g.C[i] = d.C[i]; }
+  g.sbk = d.sbk; g.sbn = d.sbn; g.b_split = d.b_split; g.n_per = d.n_per; g.k_per = d.k_per; g.c_split = d.c_split;
+  g.bias_split = d.bias_split; g.ldc = d.ldc;
+  g.res = d.res; g.M = d.M; g.N = d.N; g.K = d.K; g.gelu = d.gelu;
+  g.split_k = d.split_k > 1 ? d.split_k : 1; g.partial = d.partial;
+  g.kb = d.kb > 1 ? d.kb : 1; g.kt = d.kb > 1 ? d.kt : d.K; g.sab = d.sab; g.sbb = d.sbb;
+  if (g.M <= 0 || g.N <= 0) return IM_OK;
+  dim3 grid((g.N + GA_BN - 1) / GA_BN, (g.M + GA_BM - 1) / GA_BM, g.split_k), block(GA_THREADS);
+  const int key = (a_bf16 ? 4 : 0) | (b_bf16 ? 2 : 0) | (c_bf16 ? 1 : 0);
+  switch (key) {
+    case 0: hipLaunchKernelGGL((gemm_alu_kernel<float, float, float>), grid, block, 0, st, g); break;
+    case 7: hipLaunchKernelGGL((gemm_alu_kernel<bf16_t, bf16_t, bf16_t>), grid, block, 0, st, g); break;
+    case 6: hipLaunchKernelGGL((gemm_alu_kernel<bf16_t, bf16_t, float>), grid, block, 0, st, g); break;
+    default: set_error("gemm_alu: unsupported operand type combination %d", key); return IM_ERR_UNSUPPORTED;
+  }
+  if (g.split_k > 1) hipLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3(64), dim3(256), 0, st, g);
+  return IM_OK;
+}
+
+// ---- column sums (bias gradients): stage 1 sums blocks of rows, stage 2 sums the blocks in order ----
+constexpr int CS_ROWS = 512;
+
+template <typename T>
+__global__ void colsum_stage1(const T* a, long lda, int R, int n, float* partial) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= n) return;
+  const int r0 = blockIdx.y * CS_ROWS, r1 = min(R, r0 + CS_ROWS);
+  float s = 0.f;
+  for (int r = r0; r < r1; ++r) s += ldf(a + (long)r * lda + c);
+  partial[(long)blockIdx.y * n + c] = s;
+}
+__global__ void colsum_stage2(const float* partial, int nblk, int n, float* out) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= n) return;
+  float s = 0.f;
+  for (int b = 0; b < nblk; ++b) s += partial[(long)b * n + c];
+  out[c] = s;
+}
+size_t colsum_partial_bytes(int R, int n) { return (size_t)((R + CS_ROWS - 1) / CS_ROWS) * n * sizeof(float); }
+
+int launch_colsum(const void* a, long lda, int R, int n, int a_bf16, float* out, float* partial, hipStream_t st) {
+  const int nblk = (R + CS_ROWS - 1) / CS_ROWS;
+  dim3 grid((n + 63) / 64, nblk), block(64);
+  if (a_bf16) hipLaunchKernelGGL((colsum_stage1<bf16_t>), grid, block, 0, st, (const bf16_t*)a, lda, R, n, partial);
+  else hipLaunchKernelGGL((colsum_stage1<float>), grid, block, 0, st, (const float*)a, lda, R, n, partial);
+  hipLaunchKernelGGL(colsum_stage2, dim3((n + 63) / 64), dim3(64), 0, st, partial, nblk, n, out);
+  return IM_OK;
+}
+
+// ---- LayerNorm over the feature axis: one wavefront per row, two-pass (mean, then variance) in fp32 ----
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+                                                        const T* __restrict__ beta, T* __restrict__ y, int R, int d,
+                                                        float eps) {
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const long r = (long)blockIdx.x * 4 + wave;
+  if (r >= R) return;
+  const T* xr = x + r * d;
+  float s = 0.f;
+  for (int e = lane; e < d; e += 64) s += ldf(xr + e);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+  const float mu = s / d;
+  float v = 0.f;
+  for (int e = lane; e < d; e += 64) { const float t = ldf(xr + e) - mu; v = fmaf(t, t, v); }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  const float rstd = rsqrtf(v / d + eps);
+  for (int e = lane; e < d; e += 64) stf(y + r * d + e, (ldf(xr + e) - mu) * rstd * ldf(gamma + e) + ldf(beta + e));
+}
+
+int launch_layernorm(const void* x, const void* gamma, const void* beta, void* y, int R, int d, float eps, int bf16,
+                     hipStream_t st) {
+  dim3 grid((R + 3) / 4), block(256);
+  if (bf16)
+    hipLaunchKernelGGL((layernorm_kernel<bf16_t>), grid, block, 0, st, (const bf16_t*)x, (const bf16_t*)gamma,
+                       (const bf16_t*)beta, (bf16_t*)y, R, d, eps);
+  else
+    hipLaunchKernelGGL((layernorm_kernel<float>), grid, block, 0, st, (const float*)x, (const float*)gamma,
+                       (const float*)beta, (float*)y, R, d, eps);
+  return IM_OK;
+}
+
+}  // namespace imattn

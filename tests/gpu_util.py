@@ -1,0 +1,99 @@
+"""Helpers for the GPU parity tests: move a synthetic problem to the device, call the
+C-ABI through the binding, and compare with the fp64 oracle under the stated tolerance."""
+import numpy as np
+import torch
+
+import oracle
+from paper_2505_01068_amd import binding as B
+
+# Tolerances of the parity bar: per tensor, max|gpu - oracle| <= tol * max|oracle|.
+TOL = {"fp32": 1e-5, "bf16": 2e-2}
+W_NAMES = ("wq", "wk", "wv", "wo")
+B_NAMES = ("bq", "bk", "bv", "bo")
+
+
+def tdtype(dtype):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+def to_dev(a, dtype):
+    if a is None:
+        return None
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if t.dtype == torch.float32:
+        t = t.to(tdtype(dtype))
+    return t.cuda()
+
+
+def rel_err(gpu, ref):
+    gpu = gpu.detach().float().cpu().numpy().astype(np.float64) if isinstance(gpu, torch.Tensor) else np.asarray(gpu, np.float64)
+    ref = np.asarray(ref, np.float64)
+    assert gpu.shape == ref.shape, (gpu.shape, ref.shape)
+    assert np.all(np.isfinite(gpu)), "non-finite values in GPU result"
+    return float(np.max(np.abs(gpu - ref)) / max(np.max(np.abs(ref)), 1e-30))
+
+
+def assert_close(gpu, ref, tol, what=""):
+    e = rel_err(gpu, ref)
+    assert e <= tol, f"{what}: relative error {e:.3e} > {tol:.1e}"
+    return e
+
+
+class Problem:
+    """One IM-attention problem resident on the GPU."""
+
+    def __init__(self, g, live_mask):
+        self.g, self.lm, self.dtype = g, int(live_mask), g["dtype"]
+        x = g["x"]
+        self.shape = B.make_shape(x.shape[0], g["seg_len"], x.shape[2], g["n_heads"], live_mask, g["scale"], self.dtype)
+        self.t = {n: to_dev(g.get(n), self.dtype) for n in ("x", "dy") + W_NAMES + B_NAMES}
+        self.t["valid_len"] = to_dev(g.get("valid_len"), self.dtype)
+        self.t["key_pad"] = to_dev(g.get("key_pad"), self.dtype)
+        sb, wb = B.im_attention_sizes(self.shape)
+        self.saved = torch.empty(sb, dtype=torch.uint8, device="cuda")
+        self.ws = torch.empty(max(wb, 1), dtype=torch.uint8, device="cuda")
+
+    def fwd(self, save=True):
+        t = self.t
+        y = torch.empty_like(t["x"])
+        B.im_attention_fwd(self.shape, t["x"], t["wq"], t["wk"], t["wv"], t["wo"], t["bq"], t["bk"], t["bv"], t["bo"],
+                           t["valid_len"], t["key_pad"], y=y, saved=self.saved if save else None, workspace=self.ws)
+        return y
+
+    def bwd(self):
+        t = self.t
+        d = t["x"].shape[-1]
+        f32 = dict(dtype=torch.float32, device="cuda")
+        out = {"dx": torch.empty_like(t["x"])}
+        for n in W_NAMES:
+            out["d" + n] = torch.empty(d, d, **f32)
+        for n in B_NAMES:
+            out["d" + n] = torch.empty(d, **f32) if t[n] is not None else None
+        B.im_attention_bwd(self.shape, t["x"], t["wq"], t["wk"], t["wv"], t["wo"], self.saved, t["dy"], out["dx"],
+                           out["dwq"], out["dwk"], out["dwv"], out["dwo"], out["dbq"], out["dbk"], out["dbv"],
+                           out["dbo"], t["valid_len"], t["key_pad"], workspace=self.ws)
+        return out
+
+    def oracle_fwd(self, cache=False):
+        g = self.g
+        return oracle.forward(g["x"], g["wq"], g["wk"], g["wv"], g["wo"], g["seg_len"], self.lm, g["n_heads"],
+                              g["scale"], bq=g.get("bq"), bk=g.get("bk"), bv=g.get("bv"), bo=g.get("bo"),
+                              valid_len=g.get("valid_len"), key_pad=g.get("key_pad"), return_cache=cache)
+
+    def check(self, backward=True, tol=None, what=""):
+        tol = TOL[self.dtype] if tol is None else tol
+        y = self.fwd(save=True)
+        torch.cuda.synchronize()
+        if backward:
+            y_ref, cache = self.oracle_fwd(cache=True)
+        else:
+            y_ref = self.oracle_fwd()
+        errs = {"y": assert_close(y, y_ref, tol, what + " y")}
+        if backward:
+            grads = self.bwd()
+            torch.cuda.synchronize()
+            ref = oracle.backward(cache, self.g["dy"])
+            for n, v in grads.items():
+                if v is not None:
+                    errs[n] = assert_close(v, ref[n], tol, what + " " + n)
+        return errs

@@ -1,0 +1,114 @@
+"""GPU parity, fp32 path: HIP kernels through the C ABI vs the fp64 oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_01068_amd import synth
+from tests.gpu_util import Problem, assert_close, TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+@pytest.mark.parametrize("name", sorted(oracle.NAMED_PATTERNS))
+def test_c1_all_patterns_forward(name):
+    say(f"[case] c1 fwd pattern={name}")
+    g = synth.attention_inputs(**synth.workload("c1"))
+    Problem(g, oracle.NAMED_PATTERNS[name]).check(backward=False, what=f"c1/{name}")
+
+
+@pytest.mark.parametrize("name", ["ifm_forward", "ifm_backward", "iem", "self_only", "dense", "structure1_a"])
+@pytest.mark.parametrize("padding", ["none", "valid_len", "key_pad"])
+def test_ragged_multi_tile_fwd_bwd(name, padding):
+    # several 64-row tiles per segment, ragged tails, LDS chunks of 128 keys with a tail, biases
+    say(f"[case] ragged fwd+bwd pattern={name} padding={padding}")
+    g = synth.attention_inputs(3, (37, 201, 130), 40, 8, "fp32", padding, seed=101, bias=True)
+    Problem(g, oracle.NAMED_PATTERNS[name]).check(what=f"ragged/{name}/{padding}")
+
+
+@pytest.mark.parametrize("cfg", ["c2", "c3"])
+@pytest.mark.parametrize("name", ["ifm_forward", "ifm_backward", "iem"])
+def test_full_size_configs(cfg, name):
+    say(f"[case] {cfg} full size fwd+bwd pattern={name}")
+    g = synth.attention_inputs(**synth.workload(cfg))
+    errs = Problem(g, oracle.NAMED_PATTERNS[name]).check(what=f"{cfg}/{name}")
+    say(f"    errors: " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
+
+
+def test_c2_trailing_padding_through_valid_len():
+    say("[case] c2 trailing-5 valid_len variant")
+    w = synth.workload("c2", padding="none")
+    g = synth.attention_inputs(**w)
+    g["valid_len"] = np.full((w["batch"], 3), 45, dtype=np.int32)
+    Problem(g, oracle.IM_IFM_FORWARD).check(what="c2/valid45")
+
+
+@pytest.mark.parametrize("seg,H,d", [((1, 1, 1), 1, 4), ((1, 65, 64), 2, 32), ((64, 128, 192), 4, 32),
+                                     ((7,), 2, 16), ((33, 90), 2, 24), ((5, 9, 70, 11), 4, 64), ((129, 3, 64), 3, 48)])
+def test_shapes_and_segment_counts(seg, H, d):
+    say(f"[case] shape seg={seg} H={H} d={d}")
+    n = len(seg)
+    g = synth.attention_inputs(2, seg, d, H, "fp32", "valid_len", seed=7, bias=True)
+    masks = [(1 << (n * n)) - 1, sum(1 << (i * n + (i + 1) % n) for i in range(n)), sum(1 << (i * n + i) for i in range(n))]
+    for lm in masks:
+        Problem(g, lm).check(what=f"seg={seg} lm={lm:#x}")
+
+
+def test_dead_segments_and_fully_masked_rows():
+    say("[case] dead segments / fully masked rows")
+    g = synth.attention_inputs(2, (9, 70, 33), 16, 2, "fp32", "none", seed=9, bias=True)
+    # only block (t <- v) live: v, a queries dead; t, a never keys
+    p = Problem(g, 1 << 1)
+    p.check(what="single block")
+    y = p.fwd()
+    torch.cuda.synchronize()
+    bo = g["bo"]
+    np.testing.assert_allclose(y[:, 9:].cpu().numpy(), np.broadcast_to(bo, (2, 103, 16)), rtol=1e-6, atol=1e-7)
+    # a segment with zero valid keys for one sample
+    g["valid_len"] = np.array([[9, 0, 33], [4, 70, 1]], dtype=np.int32)
+    for lm in (oracle.IM_IFM_FORWARD, oracle.IM_IFM_BACKWARD, oracle.NAMED_PATTERNS["self_only"]):
+        Problem(g, lm).check(what=f"zero-valid lm={lm:#x}")
+    # nothing live at all
+    p = Problem(g, 0)
+    p.check(what="empty mask")
+
+
+def test_dead_block_contents_do_not_matter_bitwise():
+    say("[case] dead block poison")
+    g = synth.attention_inputs(2, (20, 100, 70), 40, 8, "fp32", "none", seed=13)
+    y0 = Problem(g, oracle.IM_IFM_FORWARD).fwd()
+    g2 = dict(g)
+    x2 = g["x"].copy()
+    x2[:, 120:] = 1e4                      # audio rows are dead for text queries (t <- v only)
+    g2["x"] = x2
+    y1 = Problem(g2, oracle.IM_IFM_FORWARD).fwd()
+    torch.cuda.synchronize()
+    assert torch.equal(y0[:, :20], y1[:, :20])
+
+
+def test_bitwise_reproducible():
+    say("[case] determinism")
+    g = synth.attention_inputs(**synth.workload("c3", batch=4))
+    p = Problem(g, oracle.IM_IFM_FORWARD)
+    y0 = p.fwd().clone()
+    g0 = {k: v.clone() for k, v in p.bwd().items() if v is not None}
+    y1 = p.fwd()
+    g1 = p.bwd()
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
+    for k in g0:
+        assert torch.equal(g0[k], g1[k]), k
+
+
+def test_inference_without_saved_matches():
+    say("[case] saved=NULL inference")
+    g = synth.attention_inputs(2, (37, 201, 130), 40, 8, "fp32", "valid_len", seed=3)
+    p = Problem(g, oracle.IM_IFM_BACKWARD)
+    y0 = p.fwd(save=True).clone()
+    y1 = p.fwd(save=False)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
