@@ -74,7 +74,7 @@ typedef struct im_shape {
   int32_t d_model;             /* d */
   int32_t n_heads;             /* H, d % H == 0; head dimension dh = d / H */
   uint64_t live_mask;          /* the IM: bit (i*n_seg + j) <=> block (query seg i, key seg j) live */
-  float scale;                 /* multiplies Q K^T before the softmax (App. B "apply scaling and softmax"); usually 1/sqrt(dh) */
+  float scale;                 /* multiplies Q K^T before the softmax (App. B "apply scaling and softmax"); finite, >= 0; usually 1/sqrt(dh) */
   int32_t dtype;               /* IM_DTYPE_F32 or IM_DTYPE_BF16 */
 } im_shape_t;
 

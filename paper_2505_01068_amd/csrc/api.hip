@@ -52,7 +52,7 @@ static int validate_shape(const im_shape_t* s) {
   const int nb = s->n_seg * s->n_seg;
   if (nb < 64 && (s->live_mask >> nb) != 0)
     return fail(IM_ERR_INVALID, "live_mask has bits set at or above n_seg^2 = %d", nb);
-  if (!(s->scale == s->scale) || isinf(s->scale)) return fail(IM_ERR_INVALID, "scale must be finite");
+  if (!(s->scale >= 0.f) || isinf(s->scale)) return fail(IM_ERR_INVALID, "scale must be finite and >= 0");
   if (s->dtype != IM_DTYPE_F32 && s->dtype != IM_DTYPE_BF16)
     return fail(IM_ERR_INVALID, "dtype must be IM_DTYPE_F32 or IM_DTYPE_BF16 (got %d)", s->dtype);
   if ((long)s->batch * T * s->d_model > (1l << 40)) return fail(IM_ERR_INVALID, "problem too large");
@@ -79,7 +79,7 @@ static int check_supported(const im_shape_t* s) {
 // Sec. 6 "Decomposition": per query segment the set of live key segments, per key
 // segment the set of query segments that read it, and the tile order (segments
 // by decreasing live range, i.e. decreasing work per row).
-static void build_geo(const im_shape_t* s, int q_tile, int k_tile, Geo* g) {
+void build_geo(const im_shape_t* s, int q_tile, int k_tile, Geo* g) {
   memset(g, 0, sizeof(*g));
   g->B = s->batch; g->H = s->n_heads; g->d = s->d_model; g->dh = s->d_model / s->n_heads; g->n_seg = s->n_seg;
   int off = 0;
@@ -132,7 +132,7 @@ static SavedLayout saved_layout(const im_shape_t* s) {
   L.o = off; off += align256(R * d * es);
   L.lse = off; off += align256((size_t)s->batch * s->n_heads * T * sizeof(float));
   L.extra = off;
-  if (pick_path(s) == PATH_MFMA) off += align256(mfma_saved_extra_bytes(s->batch, (int)T, (int)d));
+  if (pick_path(s) == PATH_MFMA) off += align256(mfma_saved_extra_bytes(s));
   L.total = off;
   return L;
 }
@@ -142,7 +142,7 @@ static size_t bwd_workspace_bytes(const im_shape_t* s) {
   long T = 0;
   for (int i = 0; i < s->n_seg; ++i) T += s->seg_len[i];
   const size_t R = (size_t)s->batch * T, d = s->d_model;
-  if (pick_path(s) == PATH_MFMA) return mfma_bwd_workspace_bytes(s->batch, (int)T, (int)d, s->n_heads);
+  if (pick_path(s) == PATH_MFMA) return mfma_bwd_workspace_bytes(s);
   size_t n = 0;
   n += align256(R * d * es);                                          // dO
   n += align256(R * 3 * d * es);                                      // dQ | dK | dV

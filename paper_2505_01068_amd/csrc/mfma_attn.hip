@@ -1,0 +1,618 @@
+// Flash-style IM attention on the CDNA4 matrix cores: bf16 operands, fp32
+// accumulation, head dimension 64.
+//
+// All three kernels compute "transposed" products so that every per-row
+// quantity of the softmax lives on the lane that owns the row:
+//   forward / dQ : lane <-> query row.  S^T = K Q^T  (rows = keys, cols = queries);
+//                  O^T = V^T P^T and dQ^T = K^T dS^T take P^T / dS^T straight from
+//                  the accumulator registers (see perm32 in mfma_common.hpp).
+//   dK / dV      : lane <-> key row.    S = Q K^T (rows = queries), dP = dO V^T;
+//                  dV^T = dO^T P and dK^T = Q^T dS take P / dS from registers.
+// K/V (or Q/dO) tiles of 64 rows are staged through LDS; the second operand of
+// each product that needs a transposed matrix reads it from a pre-transposed
+// copy in HBM ([B, d, Tp] with every modality segment padded to a multiple of 8
+// tokens) written by the projection GEMMs / the kernels themselves.
+//
+// Only live (query segment, key segment) blocks of the Interlaced Mask are
+// visited (Sec. 6 "Decomposition"); a row with several live segments carries
+// one running max / sum across all of them (Sec. 7.1).
+#include "mfma_common.hpp"
+#include "mfma_path.hpp"
+
+namespace imattn {
+
+constexpr int KT = 64;  // keys (or query rows) per staged tile
+
+// key-validity bit mask of one 64-key tile (bit k <=> key k0+k is a valid key)
+__device__ __forceinline__ unsigned long long tile_key_mask(const uint8_t* key_pad_row, int k0, int klen, int lane) {
+  const int k = k0 + lane;
+  bool ok = k < klen;
+  if (ok && key_pad_row) ok = key_pad_row[k] == 0;
+  return __ballot(ok);
+}
+
+// ------------------------------------------------------------------------------------------
+// Forward.  Workgroup = 4 waves; each wave owns QB blocks of 32 query rows.
+template <int QB>
+__global__ __launch_bounds__(256) void mfma_fwd_kernel(Geo g, GeoT gt, const bf16_t* __restrict__ QKV, long ld,
+                                                       const bf16_t* __restrict__ QKVt,
+                                                       const int32_t* __restrict__ valid_len,
+                                                       const uint8_t* __restrict__ key_pad, bf16_t* __restrict__ O,
+                                                       long ldo, bf16_t* __restrict__ Ot, float* __restrict__ lse2) {
+  __shared__ __attribute__((aligned(16))) bf16_t sK[KT * LDS_LD];
+  __shared__ __attribute__((aligned(16))) bf16_t sVt[64 * LDS_LD];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
+  const int h = blockIdx.y, b = blockIdx.z;
+  constexpr int WG_ROWS = 128 * QB;
+  int qs, q0;
+  decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, WG_ROWS, blockIdx.x, qs, q0);
+  const int qlen = g.seg_len[qs];
+  const int d = g.d;
+  const float c = g.scale_log2e;
+
+  // Q operand (B of S^T = K Q^T): lane holds query row lo of each block, 8 consecutive dh per k-step
+  bf16x8 qreg[QB][4];
+  int qrow[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    qrow[qb] = q0 + (wave * QB + qb) * 32 + lo;
+    const int rc = min(qrow[qb], qlen - 1);
+    const bf16_t* p = QKV + ((long)b * g.T + g.seg_off[qs] + rc) * ld + h * 64 + hi * 8;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) qreg[qb][s] = as_bf16x8(*(const u32x4*)(p + s * 16));
+  }
+
+  f32x16 oacc[2][QB];
+  float m[QB], l[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    m[qb] = IM_NEG_INF;
+    l[qb] = 0.f;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[db][qb][r] = 0.f;
+  }
+
+  const int prow = perm32(lo);
+  const unsigned live = g.q_live[qs];
+  for (int j = 0; j < g.n_seg; ++j) {
+    if (!((live >> j) & 1u)) continue;
+    int klen = g.seg_len[j];
+    if (valid_len) klen = min(klen, max(0, valid_len[b * g.n_seg + j]));
+    const bf16_t* Kbase = QKV + ((long)b * g.T + g.seg_off[j]) * ld + d + h * 64;
+    const bf16_t* Vtbase = QKVt + ((long)b * 3 * d + 2 * d + h * 64) * gt.Tp + gt.tp_off[j];
+    const uint8_t* kp_row = key_pad ? key_pad + (long)b * g.T + g.seg_off[j] : nullptr;
+    TileRegs tk, tv;
+    if (klen > 0) {
+      load_rows_tile(tk, Kbase, ld, 0, g.seg_len[j] - 1, tid);
+      load_cols_tile(tv, Vtbase, gt.Tp, 0, klen, tid);
+    }
+    for (int k0 = 0; k0 < klen; k0 += KT) {
+      __syncthreads();
+      store_tile(tk, sK, tid);
+      store_tile(tv, sVt, tid);
+      __syncthreads();
+      if (k0 + KT < klen) {
+        load_rows_tile(tk, Kbase, ld, k0 + KT, g.seg_len[j] - 1, tid);
+        load_cols_tile(tv, Vtbase, gt.Tp, k0 + KT, klen, tid);
+      }
+      // ---- S^T = K Q^T ----
+      f32x16 sacc[2][QB];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sacc[kb][qb][r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const bf16x8 a = lds_frag(sK, kb * 32 + prow, s * 16 + hi * 8);
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb) sacc[kb][qb] = mfma32(a, qreg[qb][s], sacc[kb][qb]);
+        }
+      }
+      // ---- mask the tail / padded keys (wave-uniform branch) ----
+      const bool need_mask = (k0 + KT > klen) || (kp_row != nullptr);
+      if (need_mask) {
+        const unsigned long long km = tile_key_mask(kp_row, k0, klen, lane) >> (8 * hi);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            // register r of block kb on this lane half is key kb*32 + 16*(r/8) + 8*hi + r%8
+            const bool ok = (km >> (kb * 32 + 16 * (r >> 3) + (r & 7))) & 1ull;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) sacc[kb][qb][r] = ok ? sacc[kb][qb][r] : IM_NEG_INF;
+          }
+      }
+      // ---- online softmax, one running (max, sum) per query row ----
+      bf16x8 pb[2][QB][2];
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        float mx = sacc[0][qb][0];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][qb][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float mn = fmaxf(m[qb], mx);
+        const float ms = (mn == IM_NEG_INF) ? 0.f : mn;
+        const float alpha = fast_exp2((m[qb] - ms) * c);
+        const float msc = ms * c;
+        float rs = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          float p[16];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            p[r] = fast_exp2(fmaf(sacc[kb][qb][r], c, -msc));
+            rs += p[r];
+          }
+          pb[kb][qb][0] = pack8(p);
+          pb[kb][qb][1] = pack8(p + 8);
+        }
+        l[qb] = fmaf(l[qb], alpha, rs);
+        m[qb] = mn;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
+      }
+      // ---- O^T += V^T P^T ----
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const bf16x8 a = lds_frag(sVt, db * 32 + lo, s * 16 + hi * 8);
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb) oacc[db][qb] = mfma32(a, pb[s >> 1][qb][s & 1], oacc[db][qb]);
+        }
+    }
+  }
+
+  // ---- epilogue: normalise, write O rows, O^T columns and the log-sum-exp ----
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const float lt = l[qb] + __shfl_xor(l[qb], 32, 64);
+    const float inv = lt > 0.f ? 1.f / lt : 0.f;
+    const int row = qrow[qb];
+    if (row >= qlen) continue;
+    const long t = (long)b * g.T + g.seg_off[qs] + row;
+    if (hi == 0 && lse2) lse2[((long)b * g.H + h) * g.T + g.seg_off[qs] + row] = lt > 0.f ? fmaf(m[qb], c, log2f(lt)) : IM_NEG_INF;
+    const int pad_end = (row == qlen - 1) ? ((qlen + 7) & ~7) : 0;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int dh0 = db * 32 + 8 * i + 4 * hi;
+        float v[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) v[jj] = oacc[db][qb][4 * i + jj] * inv;
+        u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+        *(u32x2*)(O + t * ldo + h * 64 + dh0) = pk;
+        if (Ot) {
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) {
+            bf16_t* col = Ot + ((long)b * d + h * 64 + dh0 + jj) * gt.Tp + gt.tp_off[qs];
+            col[row] = (bf16_t)((jj & 1) ? (pk[jj >> 1] >> 16) : (pk[jj >> 1] & 0xffffu));
+            for (int z = qlen; z < pad_end; ++z) col[z] = 0;
+          }
+        }
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// dQ (and delta = rowsum(dO * O)).  Same ownership as the forward: lane <-> query row.
+template <int QB>
+__global__ __launch_bounds__(256) void mfma_dq_kernel(Geo g, GeoT gt, const bf16_t* __restrict__ QKV, long ld,
+                                                      const bf16_t* __restrict__ QKVt, const bf16_t* __restrict__ O,
+                                                      const bf16_t* __restrict__ dO, long ldo,
+                                                      const float* __restrict__ lse2,
+                                                      const int32_t* __restrict__ valid_len,
+                                                      const uint8_t* __restrict__ key_pad, float* __restrict__ delta,
+                                                      bf16_t* __restrict__ dQKV, long ldg,
+                                                      bf16_t* __restrict__ dQKVt) {
+  __shared__ __attribute__((aligned(16))) bf16_t sK[KT * LDS_LD];
+  __shared__ __attribute__((aligned(16))) bf16_t sV[KT * LDS_LD];
+  __shared__ __attribute__((aligned(16))) bf16_t sKt[64 * LDS_LD];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
+  const int h = blockIdx.y, b = blockIdx.z;
+  constexpr int WG_ROWS = 128 * QB;
+  int qs, q0;
+  decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, WG_ROWS, blockIdx.x, qs, q0);
+  const int qlen = g.seg_len[qs];
+  const int d = g.d;
+  const float c = g.scale_log2e;
+
+  bf16x8 qreg[QB][4], greg[QB][4];
+  int qrow[QB];
+  float ls[QB], dl[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    qrow[qb] = q0 + (wave * QB + qb) * 32 + lo;
+    const int rc = min(qrow[qb], qlen - 1);
+    const long t = (long)b * g.T + g.seg_off[qs] + rc;
+    const bf16_t* p = QKV + t * ld + h * 64 + hi * 8;
+    const bf16_t* pg = dO + t * ldo + h * 64 + hi * 8;
+    const bf16_t* po = O + t * ldo + h * 64 + hi * 8;
+    float acc = 0.f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      qreg[qb][s] = as_bf16x8(*(const u32x4*)(p + s * 16));
+      const u32x4 gv = *(const u32x4*)(pg + s * 16), ov = *(const u32x4*)(po + s * 16);
+      greg[qb][s] = as_bf16x8(gv);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc = fmaf(__uint_as_float(gv[e] << 16), __uint_as_float(ov[e] << 16), acc);
+        acc = fmaf(__uint_as_float(gv[e] & 0xffff0000u), __uint_as_float(ov[e] & 0xffff0000u), acc);
+      }
+    }
+    acc += __shfl_xor(acc, 32, 64);
+    dl[qb] = acc;
+    const long li = ((long)b * g.H + h) * g.T + g.seg_off[qs] + rc;
+    const float lv = lse2[li];
+    ls[qb] = (lv == IM_NEG_INF) ? __builtin_inff() : lv;
+    if (hi == 0 && qrow[qb] < qlen) delta[li] = acc;
+  }
+
+  f32x16 dqacc[2][QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dqacc[db][qb][r] = 0.f;
+
+  const int prow = perm32(lo);
+  const unsigned live = g.q_live[qs];
+  for (int j = 0; j < g.n_seg; ++j) {
+    if (!((live >> j) & 1u)) continue;
+    int klen = g.seg_len[j];
+    if (valid_len) klen = min(klen, max(0, valid_len[b * g.n_seg + j]));
+    const bf16_t* Kbase = QKV + ((long)b * g.T + g.seg_off[j]) * ld + d + h * 64;
+    const bf16_t* Vbase = Kbase + d;
+    const bf16_t* Ktbase = QKVt + ((long)b * 3 * d + d + h * 64) * gt.Tp + gt.tp_off[j];
+    const uint8_t* kp_row = key_pad ? key_pad + (long)b * g.T + g.seg_off[j] : nullptr;
+    TileRegs tk, tv, tkt;
+    if (klen > 0) {
+      load_rows_tile(tk, Kbase, ld, 0, g.seg_len[j] - 1, tid);
+      load_rows_tile(tv, Vbase, ld, 0, g.seg_len[j] - 1, tid);
+      load_cols_tile(tkt, Ktbase, gt.Tp, 0, klen, tid);
+    }
+    for (int k0 = 0; k0 < klen; k0 += KT) {
+      __syncthreads();
+      store_tile(tk, sK, tid);
+      store_tile(tv, sV, tid);
+      store_tile(tkt, sKt, tid);
+      __syncthreads();
+      if (k0 + KT < klen) {
+        load_rows_tile(tk, Kbase, ld, k0 + KT, g.seg_len[j] - 1, tid);
+        load_rows_tile(tv, Vbase, ld, k0 + KT, g.seg_len[j] - 1, tid);
+        load_cols_tile(tkt, Ktbase, gt.Tp, k0 + KT, klen, tid);
+      }
+      const bool need_mask = (k0 + KT > klen) || (kp_row != nullptr);
+      unsigned long long km = ~0ull;
+      if (need_mask) km = tile_key_mask(kp_row, k0, klen, lane) >> (8 * hi);
+      bf16x8 dsb[2][QB][2];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        f32x16 sacc[QB], pacc[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) { sacc[qb][r] = 0.f; pacc[qb][r] = 0.f; }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const bf16x8 ak = lds_frag(sK, kb * 32 + prow, s * 16 + hi * 8);
+          const bf16x8 av = lds_frag(sV, kb * 32 + prow, s * 16 + hi * 8);
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb) {
+            sacc[qb] = mfma32(ak, qreg[qb][s], sacc[qb]);   // S^T  = K Q^T
+            pacc[qb] = mfma32(av, greg[qb][s], pacc[qb]);   // dP^T = V dO^T
+          }
+        }
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+          float ds[16];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float p = fast_exp2(fmaf(sacc[qb][r], c, -ls[qb]));
+            if (need_mask) p = ((km >> (kb * 32 + 16 * (r >> 3) + (r & 7))) & 1ull) ? p : 0.f;
+            ds[r] = p * (pacc[qb][r] - dl[qb]);
+          }
+          dsb[kb][qb][0] = pack8(ds);
+          dsb[kb][qb][1] = pack8(ds + 8);
+        }
+      }
+      // dQ^T += K^T dS^T
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const bf16x8 a = lds_frag(sKt, db * 32 + lo, s * 16 + hi * 8);
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb) dqacc[db][qb] = mfma32(a, dsb[s >> 1][qb][s & 1], dqacc[db][qb]);
+        }
+    }
+  }
+
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const int row = qrow[qb];
+    if (row >= qlen) continue;
+    const long t = (long)b * g.T + g.seg_off[qs] + row;
+    const int pad_end = (row == qlen - 1) ? ((qlen + 7) & ~7) : 0;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int dh0 = db * 32 + 8 * i + 4 * hi;
+        float v[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) v[jj] = dqacc[db][qb][4 * i + jj] * g.scale;
+        u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+        *(u32x2*)(dQKV + t * ldg + h * 64 + dh0) = pk;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          bf16_t* col = dQKVt + ((long)b * 3 * d + h * 64 + dh0 + jj) * gt.Tp + gt.tp_off[qs];
+          col[row] = (bf16_t)((jj & 1) ? (pk[jj >> 1] >> 16) : (pk[jj >> 1] & 0xffffu));
+          for (int z = qlen; z < pad_end; ++z) col[z] = 0;
+        }
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// dK, dV.  Each wave owns KB blocks of 32 key rows (lane <-> key row) and streams
+// the query rows of every query segment that reads this key segment.  A key tile
+// has exactly one producer, so the result is deterministic without atomics.
+template <int KB>
+__global__ __launch_bounds__(256) void mfma_dkv_kernel(Geo g, GeoT gt, const bf16_t* __restrict__ QKV, long ld,
+                                                       const bf16_t* __restrict__ QKVt, const bf16_t* __restrict__ dO,
+                                                       long ldo, const bf16_t* __restrict__ dOt,
+                                                       const float* __restrict__ lse2, const float* __restrict__ delta,
+                                                       const int32_t* __restrict__ valid_len,
+                                                       const uint8_t* __restrict__ key_pad, bf16_t* __restrict__ dQKV,
+                                                       long ldg, bf16_t* __restrict__ dQKVt) {
+  __shared__ __attribute__((aligned(16))) bf16_t sQ[KT * LDS_LD];
+  __shared__ __attribute__((aligned(16))) bf16_t sG[KT * LDS_LD];
+  __shared__ __attribute__((aligned(16))) bf16_t sQt[64 * LDS_LD];
+  __shared__ __attribute__((aligned(16))) bf16_t sGt[64 * LDS_LD];
+  __shared__ __attribute__((aligned(16))) float sL[KT];
+  __shared__ __attribute__((aligned(16))) float sD[KT];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
+  const int h = blockIdx.y, b = blockIdx.z;
+  constexpr int WG_ROWS = 128 * KB;
+  int ks, k0;
+  decode_tile(g.k_order, g.k_tile_prefix, g.k_nord, WG_ROWS, blockIdx.x, ks, k0);
+  const int klen_seg = g.seg_len[ks];
+  const int d = g.d;
+  const float c = g.scale_log2e;
+
+  bf16x8 kreg[KB][4], vreg[KB][4];
+  int krow[KB];
+  bool kvalid[KB];
+#pragma unroll
+  for (int kb = 0; kb < KB; ++kb) {
+    krow[kb] = k0 + (wave * KB + kb) * 32 + lo;
+    const int rc = min(krow[kb], klen_seg - 1);
+    const long t = (long)b * g.T + g.seg_off[ks] + rc;
+    const bf16_t* p = QKV + t * ld + d + h * 64 + hi * 8;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      kreg[kb][s] = as_bf16x8(*(const u32x4*)(p + s * 16));
+      vreg[kb][s] = as_bf16x8(*(const u32x4*)(p + d + s * 16));
+    }
+    bool ok = krow[kb] < klen_seg;
+    if (ok && valid_len) ok = krow[kb] < valid_len[b * g.n_seg + ks];
+    if (ok && key_pad) ok = key_pad[t] == 0;
+    kvalid[kb] = ok;
+  }
+
+  f32x16 dkacc[2][KB], dvacc[2][KB];
+#pragma unroll
+  for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { dkacc[db][kb][r] = 0.f; dvacc[db][kb][r] = 0.f; }
+
+  const int prow = perm32(lo);
+  const unsigned live = g.k_live[ks];
+  for (int i = 0; i < g.n_seg; ++i) {
+    if (!((live >> i) & 1u)) continue;
+    const int qlen = g.seg_len[i];
+    const bf16_t* Qbase = QKV + ((long)b * g.T + g.seg_off[i]) * ld + h * 64;
+    const bf16_t* Gbase = dO + ((long)b * g.T + g.seg_off[i]) * ldo + h * 64;
+    const bf16_t* Qtbase = QKVt + ((long)b * 3 * d + h * 64) * gt.Tp + gt.tp_off[i];
+    const bf16_t* Gtbase = dOt + ((long)b * d + h * 64) * gt.Tp + gt.tp_off[i];
+    const long lbase = ((long)b * g.H + h) * g.T + g.seg_off[i];
+    TileRegs tq, tg, tqt, tgt;
+    float rl = 0.f, rd = 0.f;
+    auto prefetch = [&](int r0) {
+      load_rows_tile(tq, Qbase, ld, r0, qlen - 1, tid);
+      load_rows_tile(tg, Gbase, ldo, r0, qlen - 1, tid);
+      load_cols_tile(tqt, Qtbase, gt.Tp, r0, qlen, tid);
+      load_cols_tile(tgt, Gtbase, gt.Tp, r0, qlen, tid);
+      if (tid < KT) {
+        const int r = r0 + tid;
+        const float lv = (r < qlen) ? lse2[lbase + r] : IM_NEG_INF;
+        rl = (lv == IM_NEG_INF) ? __builtin_inff() : lv;  // rows past the segment / without keys: p = 0
+        rd = (r < qlen) ? delta[lbase + r] : 0.f;
+      }
+    };
+    prefetch(0);
+    for (int r0 = 0; r0 < qlen; r0 += KT) {
+      __syncthreads();
+      store_tile(tq, sQ, tid);
+      store_tile(tg, sG, tid);
+      store_tile(tqt, sQt, tid);
+      store_tile(tgt, sGt, tid);
+      if (tid < KT) { sL[tid] = rl; sD[tid] = rd; }
+      __syncthreads();
+      if (r0 + KT < qlen) prefetch(r0 + KT);
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        // per-register lse / delta of the query rows this lane half holds
+        float L[16], D[16];
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const float4 l0 = *(const float4*)&sL[qb * 32 + half * 16 + hi * 8], l1 = *(const float4*)&sL[qb * 32 + half * 16 + hi * 8 + 4];
+          const float4 d0 = *(const float4*)&sD[qb * 32 + half * 16 + hi * 8], d1 = *(const float4*)&sD[qb * 32 + half * 16 + hi * 8 + 4];
+          L[half * 8 + 0] = l0.x; L[half * 8 + 1] = l0.y; L[half * 8 + 2] = l0.z; L[half * 8 + 3] = l0.w;
+          L[half * 8 + 4] = l1.x; L[half * 8 + 5] = l1.y; L[half * 8 + 6] = l1.z; L[half * 8 + 7] = l1.w;
+          D[half * 8 + 0] = d0.x; D[half * 8 + 1] = d0.y; D[half * 8 + 2] = d0.z; D[half * 8 + 3] = d0.w;
+          D[half * 8 + 4] = d1.x; D[half * 8 + 5] = d1.y; D[half * 8 + 6] = d1.z; D[half * 8 + 7] = d1.w;
+        }
+        bf16x8 pb[KB][2], dsb[KB][2];
+        f32x16 sacc[KB], pacc[KB];
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) { sacc[kb][r] = 0.f; pacc[kb][r] = 0.f; }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const bf16x8 aq = lds_frag(sQ, qb * 32 + prow, s * 16 + hi * 8);
+          const bf16x8 ag = lds_frag(sG, qb * 32 + prow, s * 16 + hi * 8);
+#pragma unroll
+          for (int kb = 0; kb < KB; ++kb) {
+            sacc[kb] = mfma32(aq, kreg[kb][s], sacc[kb]);   // S  = Q K^T
+            pacc[kb] = mfma32(ag, vreg[kb][s], pacc[kb]);   // dP = dO V^T
+          }
+        }
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+          float p[16], ds[16];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            p[r] = fast_exp2(fmaf(sacc[kb][r], c, -L[r]));
+            ds[r] = p[r] * (pacc[kb][r] - D[r]);
+          }
+          pb[kb][0] = pack8(p); pb[kb][1] = pack8(p + 8);
+          dsb[kb][0] = pack8(ds); dsb[kb][1] = pack8(ds + 8);
+        }
+        // dV^T += dO^T P ; dK^T += Q^T dS   (contraction over the 32 query rows of this block)
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            const bf16x8 agt = lds_frag(sGt, db * 32 + lo, qb * 32 + half * 16 + hi * 8);
+            const bf16x8 aqt = lds_frag(sQt, db * 32 + lo, qb * 32 + half * 16 + hi * 8);
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+              dvacc[db][kb] = mfma32(agt, pb[kb][half], dvacc[db][kb]);
+              dkacc[db][kb] = mfma32(aqt, dsb[kb][half], dkacc[db][kb]);
+            }
+          }
+      }
+    }
+  }
+
+#pragma unroll
+  for (int kb = 0; kb < KB; ++kb) {
+    const int row = krow[kb];
+    if (row >= klen_seg) continue;
+    const long t = (long)b * g.T + g.seg_off[ks] + row;
+    const int pad_end = (row == klen_seg - 1) ? ((klen_seg + 7) & ~7) : 0;
+    const float zk = kvalid[kb] ? g.scale : 0.f, zv = kvalid[kb] ? 1.f : 0.f;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int dh0 = db * 32 + 8 * i + 4 * hi;
+        u32x2 pk = {pack_bf16(dkacc[db][kb][4 * i] * zk, dkacc[db][kb][4 * i + 1] * zk),
+                    pack_bf16(dkacc[db][kb][4 * i + 2] * zk, dkacc[db][kb][4 * i + 3] * zk)};
+        u32x2 pv = {pack_bf16(dvacc[db][kb][4 * i] * zv, dvacc[db][kb][4 * i + 1] * zv),
+                    pack_bf16(dvacc[db][kb][4 * i + 2] * zv, dvacc[db][kb][4 * i + 3] * zv)};
+        *(u32x2*)(dQKV + t * ldg + d + h * 64 + dh0) = pk;
+        *(u32x2*)(dQKV + t * ldg + 2 * d + h * 64 + dh0) = pv;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          bf16_t* ck = dQKVt + ((long)b * 3 * d + d + h * 64 + dh0 + jj) * gt.Tp + gt.tp_off[ks];
+          bf16_t* cv = ck + (long)d * gt.Tp;
+          ck[row] = (bf16_t)((jj & 1) ? (pk[jj >> 1] >> 16) : (pk[jj >> 1] & 0xffffu));
+          cv[row] = (bf16_t)((jj & 1) ? (pv[jj >> 1] >> 16) : (pv[jj >> 1] & 0xffffu));
+          for (int z = klen_seg; z < pad_end; ++z) { ck[z] = 0; cv[z] = 0; }
+        }
+      }
+  }
+}
+
+// zero columns [c0, c0+n) of nch channel rows of a transposed [B, C, Tp] buffer, and rows of a row-major one
+__global__ void zero_tcols_kernel(bf16_t* buf, long batch_stride, int B, int ch0, int nch, long tp, int c0, int n) {
+  const long total = (long)B * nch * n;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int col = i % n;
+    const long r = i / n;
+    const int ch = r % nch, b = r / nch;
+    buf[b * batch_stride + (long)(ch0 + ch) * tp + c0 + col] = 0;
+  }
+}
+__global__ void zero_rows16_kernel(bf16_t* p, long ld, int B, int T_m, int row0, int nrows, int col0, int ncols) {
+  const long n = (long)B * nrows * ncols;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
+    const int e = i % ncols;
+    const long r = i / ncols;
+    const int b = r / nrows, rr = r % nrows;
+    p[((long)b * T_m + row0 + rr) * ld + col0 + e] = 0;
+  }
+}
+__global__ void fill_lse_seg_kernel(float* lse2, int BH, int T_m, int row0, int nrows) {
+  const long n = (long)BH * nrows;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x)
+    lse2[(i / nrows) * T_m + row0 + (i % nrows)] = IM_NEG_INF;
+}
+
+// ---- host launchers ----
+constexpr int FWD_QB = 2, DQ_QB = 1, DKV_KB = 1;
+int mfma_fwd_tile_rows() { return 128 * FWD_QB; }
+int mfma_dq_tile_rows() { return 128 * DQ_QB; }
+int mfma_dkv_tile_rows() { return 128 * DKV_KB; }
+
+void launch_mfma_fwd(const Geo& g, const GeoT& gt, const bf16_t* qkv, long ld, const bf16_t* qkvt,
+                     const int32_t* valid_len, const uint8_t* key_pad, bf16_t* o, long ldo, bf16_t* ot, float* lse2,
+                     hipStream_t st) {
+  // query segments with no live block: output 0, lse -inf
+  for (int s = 0; s < g.n_seg; ++s) {
+    if (g.q_live[s]) continue;
+    hipLaunchKernelGGL(zero_rows16_kernel, dim3(64), dim3(256), 0, st, o, ldo, g.B, g.T, g.seg_off[s], g.seg_len[s], 0, g.d);
+    if (ot)
+      hipLaunchKernelGGL(zero_tcols_kernel, dim3(64), dim3(256), 0, st, ot, (long)g.d * gt.Tp, g.B, 0, g.d, (long)gt.Tp,
+                         gt.tp_off[s], gt.tp_off[s + 1] - gt.tp_off[s]);
+    if (lse2) hipLaunchKernelGGL(fill_lse_seg_kernel, dim3(16), dim3(256), 0, st, lse2, g.B * g.H, g.T, g.seg_off[s], g.seg_len[s]);
+  }
+  const int nt = g.q_tile_prefix[g.q_nord];
+  if (nt == 0) return;
+  hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB>), dim3(nt, g.H, g.B), dim3(256), 0, st, g, gt, qkv, ld, qkvt, valid_len,
+                     key_pad, o, ldo, ot, lse2);
+}
+
+void launch_mfma_bwd(const Geo& gq, const Geo& gk, const GeoT& gt, const bf16_t* qkv, long ld, const bf16_t* qkvt,
+                     const bf16_t* o, const bf16_t* d_o, long ldo, const bf16_t* d_ot, const float* lse2,
+                     const int32_t* valid_len, const uint8_t* key_pad, float* delta, bf16_t* dqkv, long ldg,
+                     bf16_t* dqkvt, hipStream_t st) {
+  const Geo& g = gq;
+  for (int s = 0; s < g.n_seg; ++s) {
+    const int ncol = gt.tp_off[s + 1] - gt.tp_off[s];
+    if (!g.q_live[s]) {
+      hipLaunchKernelGGL(zero_rows16_kernel, dim3(64), dim3(256), 0, st, dqkv, ldg, g.B, g.T, g.seg_off[s], g.seg_len[s], 0, g.d);
+      hipLaunchKernelGGL(zero_tcols_kernel, dim3(64), dim3(256), 0, st, dqkvt, 3l * g.d * gt.Tp, g.B, 0, g.d, (long)gt.Tp,
+                         gt.tp_off[s], ncol);
+    }
+    if (!g.k_live[s]) {
+      hipLaunchKernelGGL(zero_rows16_kernel, dim3(64), dim3(256), 0, st, dqkv, ldg, g.B, g.T, g.seg_off[s], g.seg_len[s], g.d, 2 * g.d);
+      hipLaunchKernelGGL(zero_tcols_kernel, dim3(64), dim3(256), 0, st, dqkvt, 3l * g.d * gt.Tp, g.B, g.d, 2 * g.d, (long)gt.Tp,
+                         gt.tp_off[s], ncol);
+    }
+  }
+  const int nq = gq.q_tile_prefix[gq.q_nord], nk = gk.k_tile_prefix[gk.k_nord];
+  if (nq == 0) return;
+  hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB>), dim3(nq, g.H, g.B), dim3(256), 0, st, gq, gt, qkv, ld, qkvt, o, d_o, ldo,
+                     lse2, valid_len, key_pad, delta, dqkv, ldg, dqkvt);
+  hipLaunchKernelGGL((mfma_dkv_kernel<DKV_KB>), dim3(nk, g.H, g.B), dim3(256), 0, st, gk, gt, qkv, ld, qkvt, d_o, ldo,
+                     d_ot, lse2, delta, valid_len, key_pad, dqkv, ldg, dqkvt);
+}
+
+}  // namespace imattn

@@ -1,0 +1,128 @@
+"""GPU parity, bf16 paths (MFMA kernels at head dim 64; row-per-lane kernels at small head dims)
+vs the fp64 oracle evaluated on the same bf16-rounded inputs.  Bar: 2e-2 relative, per tensor."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_01068_amd import synth
+from tests.gpu_util import Problem, assert_close, TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+@pytest.mark.parametrize("name", ["ifm_forward", "ifm_backward", "iem", "self_only", "dense", "structure2_b"])
+@pytest.mark.parametrize("padding", ["none", "valid_len", "key_pad"])
+def test_mfma_ragged_fwd_bwd(name, padding):
+    # head dim 64; segments span several 64-key tiles and 128/256-row query tiles with ragged tails,
+    # lengths that are not multiples of 8 (padded transposed layout), biases
+    say(f"[case] mfma ragged pattern={name} padding={padding}")
+    g = synth.attention_inputs(2, (70, 300, 129), 128, 2, "bf16", padding, seed=201, bias=True)
+    errs = Problem(g, oracle.NAMED_PATTERNS[name]).check(what=f"mfma/{name}/{padding}")
+    say("    " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
+
+
+@pytest.mark.parametrize("seg,H", [((1, 1, 1), 1), ((64, 128, 256), 1), ((7,), 2), ((33, 90), 1), ((5, 9, 70, 11), 1),
+                                   ((257, 3, 64), 2), ((8, 520, 8), 1)])
+def test_mfma_shapes_and_segment_counts(seg, H):
+    say(f"[case] mfma shape seg={seg} H={H}")
+    n = len(seg)
+    g = synth.attention_inputs(2, seg, 64 * H, H, "bf16", "valid_len", seed=17, bias=True)
+    masks = [(1 << (n * n)) - 1, sum(1 << (i * n + (i + 1) % n) for i in range(n)), sum(1 << (i * n + i) for i in range(n))]
+    for lm in masks:
+        Problem(g, lm).check(what=f"mfma seg={seg} lm={lm:#x}")
+
+
+def test_mfma_dead_segments_and_fully_masked_rows():
+    say("[case] mfma dead segments / fully masked rows")
+    g = synth.attention_inputs(2, (9, 70, 33), 64, 1, "bf16", "none", seed=9, bias=True)
+    Problem(g, 1 << 1).check(what="mfma single block")
+    g["valid_len"] = np.array([[9, 0, 33], [4, 70, 1]], dtype=np.int32)
+    for lm in (oracle.IM_IFM_FORWARD, oracle.IM_IFM_BACKWARD, oracle.NAMED_PATTERNS["self_only"], 0):
+        Problem(g, lm).check(what=f"mfma zero-valid lm={lm:#x}")
+
+
+def test_mfma_bitwise_reproducible_and_inference_path():
+    say("[case] mfma determinism / saved=NULL")
+    g = synth.attention_inputs(2, (70, 300, 129), 128, 2, "bf16", "valid_len", seed=5)
+    p = Problem(g, oracle.IM_IFM_FORWARD)
+    y0 = p.fwd().clone()
+    g0 = {k: v.clone() for k, v in p.bwd().items() if v is not None}
+    y1 = p.fwd().clone()
+    g1 = p.bwd()
+    y2 = p.fwd(save=False)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1) and torch.equal(y0, y2)
+    for k in g0:
+        assert torch.equal(g0[k], g1[k]), k
+
+
+def test_mfma_dead_block_contents_do_not_matter_bitwise():
+    say("[case] mfma dead block poison")
+    g = synth.attention_inputs(1, (64, 200, 136), 64, 1, "bf16", "none", seed=13)
+    y0 = Problem(g, oracle.IM_IFM_FORWARD).fwd()
+    g2 = dict(g)
+    x2 = g["x"].copy()
+    x2[:, 264:] = 3e4                      # audio rows are dead for text queries (t <- v only)
+    g2["x"] = x2
+    y1 = Problem(g2, oracle.IM_IFM_FORWARD).fwd()
+    torch.cuda.synchronize()
+    assert torch.equal(y0[:, :64], y1[:, :64])
+
+
+@pytest.mark.parametrize("name", ["ifm_forward", "iem"])
+def test_rowlane_bf16_small_heads(name):
+    # the encoder-layer shape: d = 64, 8 heads of dimension 8, bf16 storage
+    say(f"[case] rowlane bf16 pattern={name}")
+    g = synth.attention_inputs(4, (50, 500, 375), 64, 8, "bf16", "valid_len", seed=23, bias=True)
+    errs = Problem(g, oracle.NAMED_PATTERNS[name]).check(what=f"rowlane-bf16/{name}")
+    say("    " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
+
+
+# ---- the scaled-up benchmark shape at full size, in the launch configuration bench.py times ----
+_full = {}
+
+
+def _full_problem():
+    if "p" not in _full:
+        g = synth.attention_inputs(**synth.workload("c5"))
+        p = Problem(g, oracle.IM_IFM_FORWARD)
+        y = p.fwd()
+        grads = p.bwd()
+        torch.cuda.synchronize()
+        _full.update(p=p, g=g, y=y.float().cpu().numpy(), grads={k: v.float().cpu().numpy() for k, v in grads.items() if v is not None},
+                     acc={}, done=set())
+    return _full
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("b", list(range(8)))
+def test_c5_full_size_per_batch_element(b):
+    """Batch elements are independent in y and dx, so the dense oracle checks them one at a time
+    (about 30 s of CPU each); its weight-gradient contributions are summed for the next test."""
+    say(f"[case] c5 full size, batch element {b}")
+    f = _full_problem()
+    g = f["g"]
+    sl = slice(b, b + 1)
+    y_ref, cache = oracle.forward(g["x"][sl], g["wq"], g["wk"], g["wv"], g["wo"], g["seg_len"], oracle.IM_IFM_FORWARD,
+                                  g["n_heads"], g["scale"], return_cache=True)
+    e_y = assert_close(f["y"][sl], y_ref, TOL["bf16"], f"c5[{b}] y")
+    ref = oracle.backward(cache, g["dy"][sl])
+    e_dx = assert_close(f["grads"]["dx"][sl], ref["dx"], TOL["bf16"], f"c5[{b}] dx")
+    for n in ("dwq", "dwk", "dwv", "dwo"):
+        f["acc"][n] = f["acc"].get(n, 0) + ref[n]
+    f["done"].add(b)
+    say(f"    y={e_y:.1e} dx={e_dx:.1e}")
+
+
+def test_c5_full_size_weight_gradients():
+    f = _full_problem()
+    if len(f["done"]) < 8:
+        pytest.skip("needs the eight per-element tests of this module to have run first")
+    for n in ("dwq", "dwk", "dwv", "dwo"):
+        e = assert_close(f["grads"][n], f["acc"][n], TOL["bf16"], f"c5 {n}")
+        say(f"    {n}={e:.1e}")
