@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the IM-attention hot path on one MI355X.
+
+One "step" = one im_attention_fwd + one im_attention_bwd through the C ABI
+(schedule, shared QKV projection, live-block scores / softmax / aggregation,
+output projection and the whole backward) on one batch of synthetic inputs that
+is already resident in HBM.  The headline value is live-block attention
+TFLOP/s: (4 + 10) * P * d flops per step, P = number of (query, valid live key)
+pairs over the batch, divided by the time of the WHOLE step (projections and
+weight gradients included in the time, not in the flops).
+
+Prints ONE JSON line.  The `roofline` object is for the dominant kernel of the
+step, timed with HIP events recorded by the library on the call's stream
+(im_profile_enable); `cpu_baseline` is the fp64 CPU oracle timed on a bounded
+sample (one batch element) of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_BF16_TFLOPS = 2500.0
+PEAK_FP32_VALU_TFLOPS = 157.3
+
+
+def live_pairs(seg_len, live_mask, batch, valid_len, key_pad):
+    """(query row, valid live key) pairs over the batch -- integer bookkeeping of the workload."""
+    import numpy as np
+    n = len(seg_len)
+    off = np.concatenate([[0], np.cumsum(seg_len)])
+    total = 0
+    for b in range(batch):
+        klen = []
+        for j in range(n):
+            k = seg_len[j] if valid_len is None else min(seg_len[j], int(valid_len[b, j]))
+            if key_pad is not None:
+                k = int((key_pad[b, off[j]:off[j] + k] == 0).sum())
+            klen.append(k)
+        for i in range(n):
+            for j in range(n):
+                if (live_mask >> (i * n + j)) & 1:
+                    total += seg_len[i] * klen[j]
+    return total
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="c5", choices=["c2", "c3", "c5"])
+    ap.add_argument("--mask", default="ifm_forward", choices=["ifm_forward", "ifm_backward", "iem"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2505_01068_amd import binding as B, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    masks = {"ifm_forward": B.IM_IFM_FORWARD, "ifm_backward": B.IM_IFM_BACKWARD, "iem": B.IM_IEM}
+    lm = masks[args.mask]
+
+    w = synth.workload(args.config)
+    g = synth.attention_inputs(**w)
+    dtype = g["dtype"]
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    Bsz, T, d = g["x"].shape
+    H = g["n_heads"]
+
+    def dev(a):
+        if a is None:
+            return None
+        t = torch.from_numpy(np.ascontiguousarray(a))
+        return (t.to(tdt) if t.dtype == torch.float32 else t).cuda()
+
+    shape = B.make_shape(Bsz, g["seg_len"], d, H, lm, g["scale"], dtype)
+    x, dy = dev(g["x"]), dev(g["dy"])
+    wq, wk, wv, wo = (dev(g[n]) for n in ("wq", "wk", "wv", "wo"))
+    vl, kp = dev(g["valid_len"]), dev(g["key_pad"])
+    sb, wb = B.im_attention_sizes(shape)
+    saved = torch.empty(sb, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(wb, dtype=torch.uint8, device="cuda")
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    dws = [torch.empty(d, d, dtype=torch.float32, device="cuda") for _ in range(4)]
+
+    def step():
+        B.im_attention_fwd(shape, x, wq, wk, wv, wo, valid_len=vl, key_pad=kp, y=y, saved=saved, workspace=ws)
+        B.im_attention_bwd(shape, x, wq, wk, wv, wo, saved, dy, dx, *dws, valid_len=vl, key_pad=kp, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.im_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    B.im_profile_enable(False)
+    prof = B.im_profile_get()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+
+    P = live_pairs(g["seg_len"], lm, Bsz, g["valid_len"], g["key_pad"])
+    core_flops = 14.0 * P * d                         # 4 P d forward + 10 P d backward (summed over heads)
+    proj_flops = 24.0 * Bsz * T * d * d               # 8 fwd + 16 bwd
+    value = core_flops / (ms_step * 1e-3) / 1e12
+
+    # ---- roofline of the dominant kernel (by accumulated event time) ----
+    # algorithmic flops per launch: forward 4 P d (two products); dK/dV kernel 8 P d (S, dP, dV, dK);
+    # dQ kernel 2 P d (the dQ product; its recomputed S and dP are not algorithmic work)
+    alg = {"attn_fwd": 4.0 * P * d, "attn_dkv": 8.0 * P * d, "attn_dq": 2.0 * P * d,
+           "proj_fwd": 8.0 * Bsz * T * d * d, "proj_bwd": 8.0 * Bsz * T * d * d, "wgrad": 8.0 * Bsz * T * d * d}
+    kern = {k: (v[0] / max(v[1], 1), v[1]) for k, v in prof.items() if v[1] > 0}
+    per_step = {k: prof[k][0] / args.steps for k in prof if prof[k][1] > 0}
+    attn_keys = [k for k in ("attn_fwd", "attn_dq", "attn_dkv") if k in per_step]
+    dom = max(attn_keys, key=lambda k: per_step[k])
+    dom_ms = per_step[dom]
+    mfma_bound = dtype == "bf16" and d // H == 64
+    if mfma_bound:
+        achieved = alg[dom] / (dom_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": PEAK_MFMA_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_BF16_TFLOPS, 4), "traffic": None,
+                "avg_launch_ms": round(dom_ms, 4)}
+    else:
+        # small head dims: plain fp32 ALU work (FMAs of the two/five products; exp and softmax bookkeeping not counted)
+        achieved = alg[dom] / (dom_ms * 1e-3) / 1e12
+        roof = {"bound": "alu", "kernel": dom, "achieved": round(achieved, 3), "peak": PEAK_FP32_VALU_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_VALU_TFLOPS, 4), "traffic": None,
+                "avg_launch_ms": round(dom_ms, 4)}
+
+    out = {
+        "metric": "IM-attention fwd+bwd TFLOP/s on live blocks; % of HBM/MFMA roofline",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.config}: B={Bsz} L_t/L_v/L_a={'/'.join(map(str, g['seg_len']))} d={d} H={H} "
+                               f"{dtype} fwd+bwd, mask={args.mask}, padding={w['padding']}",
+                   "live_pairs": P, "core_gflop_per_step": round(core_flops / 1e9, 2),
+                   "proj_gflop_per_step": round(proj_flops / 1e9, 2)},
+        "with_projection_tflops": round((core_flops + proj_flops) / (ms_step * 1e-3) / 1e12, 3),
+        "kernel_ms_per_step": {k: round(v, 4) for k, v in per_step.items()},
+        "attn_core_tflops": round(core_flops / (sum(per_step[k] for k in attn_keys) * 1e-3) / 1e12, 3),
+        "roofline": roof,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        n_sample = Bsz                                        # ~10-30 s of CPU work on the benchmark host
+        sl = slice(0, n_sample)
+        t0 = time.perf_counter()
+        _, cache = oracle.forward(g["x"][sl], g["wq"], g["wk"], g["wv"], g["wo"], g["seg_len"], lm, H, g["scale"],
+                                  valid_len=None if g["valid_len"] is None else g["valid_len"][sl],
+                                  key_pad=None if g["key_pad"] is None else g["key_pad"][sl], return_cache=True)
+        oracle.backward(cache, g["dy"][sl])
+        dt = time.perf_counter() - t0
+        P1 = live_pairs(g["seg_len"], lm, n_sample, None if g["valid_len"] is None else g["valid_len"][sl],
+                        None if g["key_pad"] is None else g["key_pad"][sl])
+        out["cpu_baseline"] = {"value": round(14.0 * P1 * d / dt / 1e12, 6), "unit": "TFLOP/s", "cores": int(cores),
+                               "kind": "oracle", "seconds": round(dt, 2),
+                               "sample": f"first {n_sample} of {Bsz} batch elements of the same workload, dense fp64 "
+                                         "numpy oracle fwd+bwd (live-block flops counted, dense work done)"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -141,6 +141,16 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
                    const void* b1, const void* w2, const void* b2, float ln_eps, const int32_t* valid_len,
                    const uint8_t* key_pad, void* y, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Kernel timing for benchmarks (off by default).  While enabled, the library
+ * brackets each kernel family it launches with hipEvents recorded on the call's
+ * stream.  im_profile_get synchronises on the recorded events, so call it after
+ * the stream has drained; it returns the number of families, and for family
+ * `idx` its name (static storage), accumulated milliseconds and launch count
+ * since the last im_profile_enable(1).  Not thread-safe; at most 8192 launches
+ * are recorded between resets (later ones are not timed).  Host memory only. */
+int im_profile_enable(int on);
+int im_profile_get(int idx, const char** name, double* total_ms, int64_t* launches);
+
 /* Description of the last error on the calling thread ("" if none).  Static storage. */
 const char* im_last_error(void);
 

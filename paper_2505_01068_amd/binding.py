@@ -57,6 +57,10 @@ def lib():
         L.im_attention_bwd.argtypes = [shp] + [vp] * 19 + [sz, vp]
         L.gsit_layer_sizes.argtypes = [shp, C.c_int32, C.POINTER(sz)]
         L.gsit_layer_fwd.argtypes = [shp, C.c_int32] + [vp] * 17 + [C.c_float] + [vp] * 4 + [sz, vp]
+        L.im_profile_enable.argtypes = [C.c_int]
+        L.im_profile_get.argtypes = [C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        L.im_profile_enable.restype = C.c_int
+        L.im_profile_get.restype = C.c_int
         for f in (L.im_schedule_build, L.im_attention_sizes, L.im_attention_fwd, L.im_attention_bwd,
                   L.gsit_layer_sizes, L.gsit_layer_fwd):
             f.restype = C.c_int
@@ -142,3 +146,18 @@ def gsit_layer_fwd(shape, d_ff, x, p, ln_eps=1e-5, valid_len=None, key_pad=None,
                                 _p(g("b2")), float(ln_eps), _p(valid_len), _p(key_pad), _p(y), _p(workspace), wbytes,
                                 _stream()))
     return y
+
+
+def im_profile_enable(on):
+    lib().im_profile_enable(1 if on else 0)
+
+
+def im_profile_get():
+    """{family: (total_ms, launches)} since the last im_profile_enable(True); call after a synchronize."""
+    out = {}
+    n = lib().im_profile_get(0, None, None, None)
+    for i in range(n):
+        name, ms, cnt = C.c_char_p(), C.c_double(0), C.c_int64(0)
+        lib().im_profile_get(i, C.byref(name), C.byref(ms), C.byref(cnt))
+        out[name.value.decode()] = (ms.value, cnt.value)
+    return out

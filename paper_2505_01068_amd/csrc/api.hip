@@ -30,6 +30,29 @@ static int fail(int code, const char* fmt, ...) {
   return code;
 }
 
+// ---- optional kernel-family timing ----
+static const char* kProfNames[PF_COUNT] = {"proj_fwd", "attn_fwd", "attn_dq", "attn_dkv", "proj_bwd", "wgrad", "misc"};
+constexpr int PROF_MAX = 8192;
+static bool g_prof_on = false;
+static int g_prof_n = 0;
+static hipEvent_t g_prof_ev[PROF_MAX][2];
+static int g_prof_family[PROF_MAX];
+static int g_prof_created = 0;
+
+ProfScope::ProfScope(ProfFamily f, hipStream_t s) : slot(-1), st(s) {
+  if (!g_prof_on || g_prof_n >= PROF_MAX) return;
+  if (g_prof_n >= g_prof_created) {
+    if (hipEventCreate(&g_prof_ev[g_prof_n][0]) != hipSuccess || hipEventCreate(&g_prof_ev[g_prof_n][1]) != hipSuccess) return;
+    g_prof_created = g_prof_n + 1;
+  }
+  slot = g_prof_n++;
+  g_prof_family[slot] = f;
+  (void)hipEventRecord(g_prof_ev[slot][0], st);
+}
+ProfScope::~ProfScope() {
+  if (slot >= 0) (void)hipEventRecord(g_prof_ev[slot][1], st);
+}
+
 static int check_hip(const char* what) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(IM_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
@@ -178,12 +201,15 @@ static int fwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
   p.B[0] = wq; p.B[1] = wk; p.B[2] = wv; p.sbk = d; p.sbn = 1; p.b_split = 1; p.n_per = (int)d;
   p.bias[0] = bq; p.bias[1] = bk; p.bias[2] = bv; p.bias_split = 1;
   p.C[0] = qkv; p.ldc = 3 * d; p.M = (int)R; p.N = (int)(3 * d); p.K = (int)d;
-  int rc = launch_gemm_alu(p, bf, bf, bf, st);
+  int rc;
+  { ProfScope ps(PF_PROJ_FWD, st); rc = launch_gemm_alu(p, bf, bf, bf, st); }
   if (rc) return rc;
 
-  rc = launch_rowlane_fwd(g, bf, qkv, qkv + d * es, qkv + 2 * d * es, 3 * d, valid_len, key_pad, o, d, lse2, st);
+  { ProfScope ps(PF_ATTN_FWD, st);
+  rc = launch_rowlane_fwd(g, bf, qkv, qkv + d * es, qkv + 2 * d * es, 3 * d, valid_len, key_pad, o, d, lse2, st); }
   if (rc) return rc;
 
+  ProfScope ps2(PF_PROJ_FWD, st);
   memset(&p, 0, sizeof(p));
   p.A = o; p.sam = d; p.sak = 1;
   p.B[0] = wo; p.sbk = d; p.sbn = 1;
@@ -225,7 +251,7 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
   p.A = dy; p.sam = d; p.sak = 1;
   p.B[0] = wo; p.sbk = 1; p.sbn = d;
   p.C[0] = d_o; p.ldc = d; p.M = (int)R; p.N = (int)d; p.K = (int)d;
-  if ((rc = launch_gemm_alu(p, bf, bf, bf, st))) return rc;
+  { ProfScope ps(PF_PROJ_BWD, st); if ((rc = launch_gemm_alu(p, bf, bf, bf, st))) return rc; }
   // dWo = O^T dy
   if (dwo) {
     memset(&p, 0, sizeof(p));
@@ -234,9 +260,10 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
     p.C[0] = dwo; p.ldc = d; p.M = (int)d; p.N = (int)d; p.K = (int)R;
     gemm_alu_partial_bytes((int)d, (int)d, (int)R, &p.split_k);
     p.partial = partial;
+    ProfScope ps(PF_WGRAD, st);
     if ((rc = launch_gemm_alu(p, bf, bf, 0, st))) return rc;
   }
-  if (dbo && (rc = launch_colsum(dy, d, (int)R, (int)d, bf, (float*)dbo, cpart, st))) return rc;
+  if (dbo) { ProfScope ps(PF_WGRAD, st); if ((rc = launch_colsum(dy, d, (int)R, (int)d, bf, (float*)dbo, cpart, st))) return rc; }
 
   rc = launch_rowlane_bwd(g, bf, qkv, qkv + d * es, qkv + 2 * d * es, 3 * d, o, d_o, d, lse2, valid_len, key_pad,
                           delta, dqkv, dqkv + d * es, dqkv + 2 * d * es, 3 * d, st);
@@ -250,18 +277,22 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
     p.C[0] = dwq ? dwq : sink; p.C[1] = dwk ? dwk : sink + d * d; p.C[2] = dwv ? dwv : sink + 2 * d * d;
     p.c_split = 1; p.n_per = (int)d; p.ldc = d; p.M = (int)d; p.N = (int)(3 * d); p.K = (int)R;
     p.split_k = split; p.partial = partial;
+    ProfScope ps(PF_WGRAD, st);
     if ((rc = launch_gemm_alu(p, bf, bf, 0, st))) return rc;
   }
   void* dbs[3] = {dbq, dbk, dbv};
   for (int i = 0; i < 3; ++i)
-    if (dbs[i] && (rc = launch_colsum(dqkv + i * d * es, 3 * d, (int)R, (int)d, bf, (float*)dbs[i], cpart, st)))
-      return rc;
+    if (dbs[i]) {
+      ProfScope ps(PF_WGRAD, st);
+      if ((rc = launch_colsum(dqkv + i * d * es, 3 * d, (int)R, (int)d, bf, (float*)dbs[i], cpart, st))) return rc;
+    }
   // dx = dQ Wq^T + dK Wk^T + dV Wv^T
   if (dx) {
     memset(&p, 0, sizeof(p));
     p.A = dqkv; p.sam = 3 * d; p.sak = 1;
     p.B[0] = wq; p.B[1] = wk; p.B[2] = wv; p.sbk = 1; p.sbn = d; p.b_split = 2; p.k_per = (int)d;
     p.C[0] = dx; p.ldc = d; p.M = (int)R; p.N = (int)d; p.K = (int)(3 * d);
+    ProfScope ps(PF_PROJ_BWD, st);
     if ((rc = launch_gemm_alu(p, bf, bf, bf, st))) return rc;
   }
   return check_hip("im_attention_bwd launch");
@@ -274,6 +305,28 @@ using namespace imattn;
 extern "C" {
 
 const char* im_last_error(void) { return g_err; }
+
+int im_profile_enable(int on) {
+  g_prof_on = on != 0;
+  if (on) g_prof_n = 0;
+  return IM_OK;
+}
+
+int im_profile_get(int idx, const char** name, double* total_ms, int64_t* launches) {
+  if (idx < 0 || idx >= PF_COUNT) return PF_COUNT;
+  double ms = 0.0;
+  int64_t n = 0;
+  for (int i = 0; i < g_prof_n; ++i) {
+    if (g_prof_family[i] != idx) continue;
+    float t = 0.f;
+    if (hipEventSynchronize(g_prof_ev[i][1]) == hipSuccess &&
+        hipEventElapsedTime(&t, g_prof_ev[i][0], g_prof_ev[i][1]) == hipSuccess) { ms += t; ++n; }
+  }
+  if (name) *name = kProfNames[idx];
+  if (total_ms) *total_ms = ms;
+  if (launches) *launches = n;
+  return PF_COUNT;
+}
 const char* im_version(void) { return "imattn 0.1 gfx950"; }
 
 int im_schedule_build(const im_shape_t* shape, int32_t tile_rows, im_work_item_t* items, int32_t max_items,

@@ -331,15 +331,19 @@ static int bwd_dispatch(const Geo& g, const T* q, const T* k, const T* v, long l
   if (nq == 0) return IM_OK;
   dim3 block(RL_ROWS);
   if (g.dh <= 8) {
-    hipLaunchKernelGGL((rowlane_dq_kernel<T, 8>), dim3(nq, g.H, g.B), block, 0, st, g, q, k, v, ld, o, d_o, ldo, lse2,
-                       vl, kp, delta, dq, ldg);
-    hipLaunchKernelGGL((rowlane_dkv_kernel<T, 8>), dim3(nk, g.H, g.B), block, 0, st, g, q, k, v, ld, d_o, ldo, lse2,
-                       delta, vl, kp, dk, dv, ldg);
+    { ProfScope ps(PF_ATTN_DQ, st);
+      hipLaunchKernelGGL((rowlane_dq_kernel<T, 8>), dim3(nq, g.H, g.B), block, 0, st, g, q, k, v, ld, o, d_o, ldo, lse2,
+                         vl, kp, delta, dq, ldg); }
+    { ProfScope ps(PF_ATTN_DKV, st);
+      hipLaunchKernelGGL((rowlane_dkv_kernel<T, 8>), dim3(nk, g.H, g.B), block, 0, st, g, q, k, v, ld, d_o, ldo, lse2,
+                         delta, vl, kp, dk, dv, ldg); }
   } else {
-    hipLaunchKernelGGL((rowlane_dq_kernel<T, 16>), dim3(nq, g.H, g.B), block, 0, st, g, q, k, v, ld, o, d_o, ldo, lse2,
-                       vl, kp, delta, dq, ldg);
-    hipLaunchKernelGGL((rowlane_dkv_kernel<T, 16>), dim3(nk, g.H, g.B), block, 0, st, g, q, k, v, ld, d_o, ldo, lse2,
-                       delta, vl, kp, dk, dv, ldg);
+    { ProfScope ps(PF_ATTN_DQ, st);
+      hipLaunchKernelGGL((rowlane_dq_kernel<T, 16>), dim3(nq, g.H, g.B), block, 0, st, g, q, k, v, ld, o, d_o, ldo, lse2,
+                         vl, kp, delta, dq, ldg); }
+    { ProfScope ps(PF_ATTN_DKV, st);
+      hipLaunchKernelGGL((rowlane_dkv_kernel<T, 16>), dim3(nk, g.H, g.B), block, 0, st, g, q, k, v, ld, d_o, ldo, lse2,
+                         delta, vl, kp, dk, dv, ldg); }
   }
   return IM_OK;
 }

@@ -96,4 +96,14 @@ int launch_layernorm(const void* x, const void* gamma, const void* beta, void* y
 
 void set_error(const char* fmt, ...);
 
+// Optional per-kernel-family timing (see im_profile_enable): records an event pair
+// around the launches issued while the scope is alive.
+enum ProfFamily { PF_PROJ_FWD = 0, PF_ATTN_FWD, PF_ATTN_DQ, PF_ATTN_DKV, PF_PROJ_BWD, PF_WGRAD, PF_MISC, PF_COUNT };
+struct ProfScope {
+  int slot;
+  hipStream_t st;
+  ProfScope(ProfFamily f, hipStream_t s);
+  ~ProfScope();
+};
+
 }  // namespace imattn

@@ -585,6 +585,7 @@ void launch_mfma_fwd(const Geo& g, const GeoT& gt, const bf16_t* qkv, long ld, c
   }
   const int nt = g.q_tile_prefix[g.q_nord];
   if (nt == 0) return;
+  ProfScope ps(PF_ATTN_FWD, st);
   hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB>), dim3(nt, g.H, g.B), dim3(256), 0, st, g, gt, qkv, ld, qkvt, valid_len,
                      key_pad, o, ldo, ot, lse2);
 }
@@ -609,10 +610,12 @@ void launch_mfma_bwd(const Geo& gq, const Geo& gk, const GeoT& gt, const bf16_t*
   }
   const int nq = gq.q_tile_prefix[gq.q_nord], nk = gk.k_tile_prefix[gk.k_nord];
   if (nq == 0) return;
-  hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB>), dim3(nq, g.H, g.B), dim3(256), 0, st, gq, gt, qkv, ld, qkvt, o, d_o, ldo,
-                     lse2, valid_len, key_pad, delta, dqkv, ldg, dqkvt);
-  hipLaunchKernelGGL((mfma_dkv_kernel<DKV_KB>), dim3(nk, g.H, g.B), dim3(256), 0, st, gk, gt, qkv, ld, qkvt, d_o, ldo,
-                     d_ot, lse2, delta, valid_len, key_pad, dqkv, ldg, dqkvt);
+  { ProfScope ps(PF_ATTN_DQ, st);
+    hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB>), dim3(nq, g.H, g.B), dim3(256), 0, st, gq, gt, qkv, ld, qkvt, o, d_o, ldo,
+                       lse2, valid_len, key_pad, delta, dqkv, ldg, dqkvt); }
+  { ProfScope ps(PF_ATTN_DKV, st);
+    hipLaunchKernelGGL((mfma_dkv_kernel<DKV_KB>), dim3(nk, g.H, g.B), dim3(256), 0, st, gk, gt, qkv, ld, qkvt, d_o, ldo,
+                       d_ot, lse2, delta, valid_len, key_pad, dqkv, ldg, dqkvt); }
 }
 
 }  // namespace imattn

@@ -90,9 +90,11 @@ int mfma_attention_fwd(const im_shape_t* s, const void* x, const void* wq, const
   bf16_t* wt = (bf16_t*)ws;  // [4][d][d]: Wq^T, Wk^T, Wv^T, Wo^T
 
   const void* wsrc[4] = {wq, wk, wv, wo};
+  MGemm p;
+  {
+  ProfScope ps(PF_PROJ_FWD, st);
   for (int i = 0; i < 4; ++i) launch_transpose_w((const bf16_t*)wsrc[i], d, d, wt + (size_t)i * d * d, st);
 
-  MGemm p;
   init_gemm(&p, g, gt);
   p.A = (const bf16_t*)x; p.lda = d;
   p.B[0] = wt; p.ldb = d;  // rows n of [Wq^T; Wk^T; Wv^T] are contiguous: one [3d][d] matrix
@@ -101,6 +103,7 @@ int mfma_attention_fwd(const im_shape_t* s, const void* x, const void* wq, const
   p.C = qkv; p.ldc = 3 * d;
   p.Ct = qkvt; p.ct_bs = (long)3 * d * gt.Tp;
   launch_mfma_gemm(p, st);
+  }
 
   launch_mfma_fwd(g, gt, qkv, 3 * d, qkvt, valid_len, key_pad, o, d, ot, lse2, st);
 
@@ -111,7 +114,7 @@ int mfma_attention_fwd(const im_shape_t* s, const void* x, const void* wq, const
   p.bias[0] = (const bf16_t*)bo; p.n_per = d;
   p.res = (const bf16_t*)res;
   p.C = (bf16_t*)y; p.ldc = d;
-  launch_mfma_gemm(p, st);
+  { ProfScope ps(PF_PROJ_FWD, st); launch_mfma_gemm(p, st); }
 
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_error("im_attention_fwd (MFMA path) launch: %s", hipGetErrorString(e)); return IM_ERR_HIP; }
@@ -152,9 +155,10 @@ int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const
   p.B[0] = (const bf16_t*)wo; p.ldb = d;
   p.M = (int)dm.R; p.N = d; p.kt = d;
   p.C = d_o; p.ldc = d; p.Ct = d_ot; p.ct_bs = (long)d * gt.Tp;
-  launch_mfma_gemm(p, st);
+  { ProfScope ps(PF_PROJ_BWD, st); launch_mfma_gemm(p, st); }
 
   if (dwo) {
+    ProfScope ps(PF_WGRAD, st);
     launch_transpose_pad((const bf16_t*)dy, d, d, g, gt, dyt, st);
     init_gemm(&p, g, gt);
     p.A = ot; p.lda = gt.Tp; p.a_bs = (long)d * gt.Tp;
@@ -164,11 +168,12 @@ int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const
     launch_mfma_gemm(p, st);
     launch_splitk_reduce(partial, w.split_o, d, d, (float*)dwo, nullptr, nullptr, 0, st);
   }
-  if (dbo) launch_colsum(dy, d, (int)dm.R, d, 1, (float*)dbo, cpart, st);
+  if (dbo) { ProfScope ps(PF_WGRAD, st); launch_colsum(dy, d, (int)dm.R, d, 1, (float*)dbo, cpart, st); }
 
   launch_mfma_bwd(g, g, gt, qkv, 3 * d, qkvt, o, d_o, d, d_ot, lse2, valid_len, key_pad, delta, dqkv, 3 * d, dqkvt, st);
 
   if (dwq || dwk || dwv) {
+    ProfScope ps(PF_WGRAD, st);
     launch_transpose_pad((const bf16_t*)x, d, d, g, gt, xt, st);
     init_gemm(&p, g, gt);
     p.A = xt; p.lda = gt.Tp; p.a_bs = (long)d * gt.Tp;
@@ -180,7 +185,7 @@ int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const
   }
   void* dbs[3] = {dbq, dbk, dbv};
   for (int i = 0; i < 3; ++i)
-    if (dbs[i]) launch_colsum(dqkv + (size_t)i * d, 3 * d, (int)dm.R, d, 1, (float*)dbs[i], cpart, st);
+    if (dbs[i]) { ProfScope ps(PF_WGRAD, st); launch_colsum(dqkv + (size_t)i * d, 3 * d, (int)dm.R, d, 1, (float*)dbs[i], cpart, st); }
 
   if (dx) {
     init_gemm(&p, g, gt);
@@ -188,6 +193,7 @@ int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const
     p.B[0] = (const bf16_t*)wq; p.B[1] = (const bf16_t*)wk; p.B[2] = (const bf16_t*)wv; p.ldb = d; p.b_kper = d;
     p.M = (int)dm.R; p.N = d; p.kt = 3 * d;
     p.C = (bf16_t*)dx; p.ldc = d;
+    ProfScope ps(PF_PROJ_BWD, st);
     launch_mfma_gemm(p, st);
   }
   hipError_t e = hipGetLastError();

@@ -1,0 +1,77 @@
+"""GPU parity of gsit_layer_fwd (one pre-LayerNorm encoder layer) and of the 4-layer encoder stack."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_01068_amd import binding as B, synth
+from tests.gpu_util import assert_close, to_dev, TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def run_layers(g, layers, lm, dtype, d_ff, in_place=False):
+    x = g["x"]
+    shape = B.make_shape(x.shape[0], g["seg_len"], x.shape[2], g["n_heads"], lm, g["scale"], dtype)
+    ws = torch.empty(B.gsit_layer_sizes(shape, d_ff), dtype=torch.uint8, device="cuda")
+    h = to_dev(x, dtype)
+    vl, kp = to_dev(g.get("valid_len"), dtype), to_dev(g.get("key_pad"), dtype)
+    for p in layers:
+        pd = {k: to_dev(v, dtype) for k, v in p.items()}
+        h = B.gsit_layer_fwd(shape, d_ff, h, pd, valid_len=vl, key_pad=kp, y=h if in_place else None, workspace=ws)
+    torch.cuda.synchronize()
+    return h
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("name", ["ifm_forward", "ifm_backward", "iem", "self_only"])
+@pytest.mark.parametrize("bias", [True, False])
+def test_single_layer(dtype, name, bias):
+    say(f"[case] layer dtype={dtype} pattern={name} bias={bias}")
+    d, H, d_ff, seg = 64, 8, 256, (37, 201, 130)
+    g = synth.attention_inputs(3, seg, d, H, dtype, "valid_len", seed=301, with_dy=False)
+    p = synth.layer_params(d, d_ff, 301, 0, dtype=dtype, bias=bias)
+    lm = oracle.NAMED_PATTERNS[name]
+    y = run_layers(g, [p], lm, dtype, d_ff)
+    ref = oracle.gsit_layer_forward(g["x"], p, seg, lm, H, g["scale"], valid_len=g["valid_len"])
+    assert_close(y, ref, TOL[dtype], f"layer/{dtype}/{name}")
+
+
+def test_layer_odd_widths_fp32():
+    say("[case] layer fp32 d=40 d_ff=100")
+    d, H, d_ff, seg = 40, 8, 100, (20, 70, 33)
+    g = synth.attention_inputs(2, seg, d, H, "fp32", "key_pad", seed=302, with_dy=False)
+    p = synth.layer_params(d, d_ff, 302, 0, dtype="fp32")
+    y = run_layers(g, [p], oracle.IM_IFM_FORWARD, "fp32", d_ff)
+    ref = oracle.gsit_layer_forward(g["x"], p, seg, oracle.IM_IFM_FORWARD, H, g["scale"], key_pad=g["key_pad"])
+    assert_close(y, ref, TOL["fp32"], "layer odd widths")
+
+
+def test_layer_identity_when_output_weights_vanish():
+    say("[case] layer identity")
+    d, H, d_ff, seg = 64, 8, 256, (20, 70, 33)
+    g = synth.attention_inputs(2, seg, d, H, "bf16", "none", seed=303, with_dy=False)
+    p = synth.layer_params(d, d_ff, 303, 0, dtype="bf16")
+    for n in ("wo", "bo", "w2", "b2"):
+        p[n] = np.zeros_like(p[n])
+    y = run_layers(g, [p], oracle.IM_IFM_FORWARD, "bf16", d_ff)
+    assert torch.equal(y.float().cpu(), torch.from_numpy(g["x"]))
+
+
+@pytest.mark.parametrize("name", ["ifm_forward", "iem"])
+def test_c4_four_layer_encoder_full_size(name):
+    say(f"[case] c4 full size 4 layers pattern={name}")
+    w = synth.workload("c4")
+    g = synth.attention_inputs(**{**w, "with_dy": False})
+    layers = [synth.layer_params(w["d_model"], w["d_ff"], w["seed"], l, dtype="bf16") for l in range(w["n_layers"])]
+    lm = oracle.NAMED_PATTERNS[name]
+    y = run_layers(g, layers, lm, "bf16", w["d_ff"], in_place=False)
+    ref = oracle.gsit_encoder_forward(g["x"], layers, g["seg_len"], lm, g["n_heads"], g["scale"])
+    e = assert_close(y, ref, TOL["bf16"], f"c4/{name}")
+    say(f"    y={e:.1e}")
+    y2 = run_layers(g, layers, lm, "bf16", w["d_ff"], in_place=True)     # y aliasing x
+    assert torch.equal(y, y2)
