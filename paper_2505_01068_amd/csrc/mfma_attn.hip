@@ -34,7 +34,7 @@ __device__ __forceinline__ unsigned long long tile_key_mask(const uint8_t* key_p
 // ------------------------------------------------------------------------------------------
 // Forward.  Workgroup = 4 waves; each wave owns QB blocks of 32 query rows.
 template <int QB>
-__global__ __launch_bounds__(256) void mfma_fwd_kernel(Geo g, GeoT gt, const bf16_t* __restrict__ QKV, long ld,
+__global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, GeoT gt, const bf16_t* __restrict__ QKV, long ld,
                                                        const bf16_t* __restrict__ QKVt,
                                                        const int32_t* __restrict__ valid_len,
                                                        const uint8_t* __restrict__ key_pad, bf16_t* __restrict__ O,
@@ -206,7 +206,7 @@ __global__ __launch_bounds__(256) void mfma_fwd_kernel(Geo g, GeoT gt, const bf1
 // ------------------------------------------------------------------------------------------
 // dQ (and delta = rowsum(dO * O)).  Same ownership as the forward: lane <-> query row.
 template <int QB>
-__global__ __launch_bounds__(256) void mfma_dq_kernel(Geo g, GeoT gt, const bf16_t* __restrict__ QKV, long ld,
+__global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, GeoT gt, const bf16_t* __restrict__ QKV, long ld,
                                                       const bf16_t* __restrict__ QKVt, const bf16_t* __restrict__ O,
                                                       const bf16_t* __restrict__ dO, long ldo,
                                                       const float* __restrict__ lse2,
@@ -313,13 +313,19 @@ __global__ __launch_bounds__(256) void mfma_dq_kernel(Geo g, GeoT gt, const bf16
             pacc[qb] = mfma32(av, greg[qb][s], pacc[qb]);   // dP^T = V dO^T
           }
         }
+        if (need_mask) {  // wave-uniform: tail tile or key_pad present
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              sacc[qb][r] = ((km >> (kb * 32 + 16 * (r >> 3) + (r & 7))) & 1ull) ? sacc[qb][r] : IM_NEG_INF;
+        }
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
           float ds[16];
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            float p = fast_exp2(fmaf(sacc[qb][r], c, -ls[qb]));
-            if (need_mask) p = ((km >> (kb * 32 + 16 * (r >> 3) + (r & 7))) & 1ull) ? p : 0.f;
+            const float p = fast_exp2(fmaf(sacc[qb][r], c, -ls[qb]));
             ds[r] = p * (pacc[qb][r] - dl[qb]);
           }
           dsb[kb][qb][0] = pack8(ds);
@@ -369,7 +375,7 @@ __global__ __launch_bounds__(256) void mfma_dq_kernel(Geo g, GeoT gt, const bf16
 // the query rows of every query segment that reads this key segment.  A key tile
 // has exactly one producer, so the result is deterministic without atomics.
 template <int KB>
-__global__ __launch_bounds__(256) void mfma_dkv_kernel(Geo g, GeoT gt, const bf16_t* __restrict__ QKV, long ld,
+__global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, GeoT gt, const bf16_t* __restrict__ QKV, long ld,
                                                        const bf16_t* __restrict__ QKVt, const bf16_t* __restrict__ dO,
                                                        long ldo, const bf16_t* __restrict__ dOt,
                                                        const float* __restrict__ lse2, const float* __restrict__ delta,
