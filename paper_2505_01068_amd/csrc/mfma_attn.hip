@@ -8,10 +8,10 @@
 //                  the accumulator registers (see perm32 in mfma_common.hpp).
 //   dK / dV      : lane <-> key row.    S = Q K^T (rows = queries), dP = dO V^T;
 //                  dV^T = dO^T P and dK^T = Q^T dS take P / dS from registers.
-// K/V (or Q/dO) tiles of 64 rows are staged through LDS; the second operand of
-// each product that needs a transposed matrix reads it from a pre-transposed
-// copy in HBM ([B, d, Tp] with every modality segment padded to a multiple of 8
-// tokens) written by the projection GEMMs / the kernels themselves.
+// K/V (or Q/dO) tiles of 64 rows are staged row-major through LDS once; products
+// that need the tile transposed (V^T, K^T, Q^T, dO^T as the MFMA "A" operand)
+// read it with the gfx950 LDS transpose read (ds_read_b64_tr_b16), so no
+// transposed copy of any tensor exists in HBM.
 //
 // Only live (query segment, key segment) blocks of the Interlaced Mask are
 // visited (Sec. 6 "Decomposition"); a row with several live segments carries
@@ -34,13 +34,12 @@ __device__ __forceinline__ unsigned long long tile_key_mask(const uint8_t* key_p
 // ------------------------------------------------------------------------------------------
 // Forward.  Workgroup = 4 waves; each wave owns QB blocks of 32 query rows.
 template <int QB>
-__global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, GeoT gt, const bf16_t* __restrict__ QKV, long ld,
-                                                       const bf16_t* __restrict__ QKVt,
+__global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
                                                        const int32_t* __restrict__ valid_len,
                                                        const uint8_t* __restrict__ key_pad, bf16_t* __restrict__ O,
-                                                       long ldo, bf16_t* __restrict__ Ot, float* __restrict__ lse2) {
+                                                       long ldo, float* __restrict__ lse2) {
   __shared__ __attribute__((aligned(16))) bf16_t sK[KT * LDS_LD];
-  __shared__ __attribute__((aligned(16))) bf16_t sVt[64 * LDS_LD];
+  __shared__ __attribute__((aligned(16))) bf16_t sV[KT * LDS_LD];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int h = blockIdx.y, b = blockIdx.z;
   constexpr int WG_ROWS = 128 * QB;
@@ -81,21 +80,21 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, GeoT gt, const 
     int klen = g.seg_len[j];
     if (valid_len) klen = min(klen, max(0, valid_len[b * g.n_seg + j]));
     const bf16_t* Kbase = QKV + ((long)b * g.T + g.seg_off[j]) * ld + d + h * 64;
-    const bf16_t* Vtbase = QKVt + ((long)b * 3 * d + 2 * d + h * 64) * gt.Tp + gt.tp_off[j];
+    const bf16_t* Vbase = Kbase + d;
     const uint8_t* kp_row = key_pad ? key_pad + (long)b * g.T + g.seg_off[j] : nullptr;
     TileRegs tk, tv;
     if (klen > 0) {
       load_rows_tile(tk, Kbase, ld, 0, g.seg_len[j] - 1, tid);
-      load_cols_tile(tv, Vtbase, gt.Tp, 0, klen, tid);
+      load_rows_tile(tv, Vbase, ld, 0, g.seg_len[j] - 1, tid);
     }
     for (int k0 = 0; k0 < klen; k0 += KT) {
       __syncthreads();
       store_tile(tk, sK, tid);
-      store_tile(tv, sVt, tid);
+      store_tile(tv, sV, tid);
       __syncthreads();
       if (k0 + KT < klen) {
         load_rows_tile(tk, Kbase, ld, k0 + KT, g.seg_len[j] - 1, tid);
-        load_cols_tile(tv, Vtbase, gt.Tp, k0 + KT, klen, tid);
+        load_rows_tile(tv, Vbase, ld, k0 + KT, g.seg_len[j] - 1, tid);
       }
       // ---- S^T = K Q^T ----
       f32x16 sacc[2][QB];
@@ -164,7 +163,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, GeoT gt, const 
       for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const bf16x8 a = lds_frag(sVt, db * 32 + lo, s * 16 + hi * 8);
+          const bf16x8 a = lds_frag_tr(sV, LDS_LD, s * 16, db * 32, lane);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) oacc[db][qb] = mfma32(a, pb[s >> 1][qb][s & 1], oacc[db][qb]);
         }
@@ -180,7 +179,6 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, GeoT gt, const 
     if (row >= qlen) continue;
     const long t = (long)b * g.T + g.seg_off[qs] + row;
     if (hi == 0 && lse2) lse2[((long)b * g.H + h) * g.T + g.seg_off[qs] + row] = lt > 0.f ? fmaf(m[qb], c, log2f(lt)) : IM_NEG_INF;
-    const int pad_end = (row == qlen - 1) ? ((qlen + 7) & ~7) : 0;
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -189,16 +187,8 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, GeoT gt, const 
         float v[4];
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) v[jj] = oacc[db][qb][4 * i + jj] * inv;
-        u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+        const u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
         *(u32x2*)(O + t * ldo + h * 64 + dh0) = pk;
-        if (Ot) {
-#pragma unroll
-          for (int jj = 0; jj < 4; ++jj) {
-            bf16_t* col = Ot + ((long)b * d + h * 64 + dh0 + jj) * gt.Tp + gt.tp_off[qs];
-            col[row] = (bf16_t)((jj & 1) ? (pk[jj >> 1] >> 16) : (pk[jj >> 1] & 0xffffu));
-            for (int z = qlen; z < pad_end; ++z) col[z] = 0;
-          }
-        }
       }
   }
 }
@@ -206,17 +196,15 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, GeoT gt, const 
 // ------------------------------------------------------------------------------------------
 // dQ (and delta = rowsum(dO * O)).  Same ownership as the forward: lane <-> query row.
 template <int QB>
-__global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, GeoT gt, const bf16_t* __restrict__ QKV, long ld,
-                                                      const bf16_t* __restrict__ QKVt, const bf16_t* __restrict__ O,
+__global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
+                                                      const bf16_t* __restrict__ O,
                                                       const bf16_t* __restrict__ dO, long ldo,
                                                       const float* __restrict__ lse2,
                                                       const int32_t* __restrict__ valid_len,
                                                       const uint8_t* __restrict__ key_pad, float* __restrict__ delta,
-                                                      bf16_t* __restrict__ dQKV, long ldg,
-                                                      bf16_t* __restrict__ dQKVt) {
+                                                      bf16_t* __restrict__ dQKV, long ldg) {
   __shared__ __attribute__((aligned(16))) bf16_t sK[KT * LDS_LD];
   __shared__ __attribute__((aligned(16))) bf16_t sV[KT * LDS_LD];
-  __shared__ __attribute__((aligned(16))) bf16_t sKt[64 * LDS_LD];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int h = blockIdx.y, b = blockIdx.z;
   constexpr int WG_ROWS = 128 * QB;
@@ -273,24 +261,20 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, GeoT gt, const b
     if (valid_len) klen = min(klen, max(0, valid_len[b * g.n_seg + j]));
     const bf16_t* Kbase = QKV + ((long)b * g.T + g.seg_off[j]) * ld + d + h * 64;
     const bf16_t* Vbase = Kbase + d;
-    const bf16_t* Ktbase = QKVt + ((long)b * 3 * d + d + h * 64) * gt.Tp + gt.tp_off[j];
     const uint8_t* kp_row = key_pad ? key_pad + (long)b * g.T + g.seg_off[j] : nullptr;
-    TileRegs tk, tv, tkt;
+    TileRegs tk, tv;
     if (klen > 0) {
       load_rows_tile(tk, Kbase, ld, 0, g.seg_len[j] - 1, tid);
       load_rows_tile(tv, Vbase, ld, 0, g.seg_len[j] - 1, tid);
-      load_cols_tile(tkt, Ktbase, gt.Tp, 0, klen, tid);
     }
     for (int k0 = 0; k0 < klen; k0 += KT) {
       __syncthreads();
       store_tile(tk, sK, tid);
       store_tile(tv, sV, tid);
-      store_tile(tkt, sKt, tid);
       __syncthreads();
       if (k0 + KT < klen) {
         load_rows_tile(tk, Kbase, ld, k0 + KT, g.seg_len[j] - 1, tid);
         load_rows_tile(tv, Vbase, ld, k0 + KT, g.seg_len[j] - 1, tid);
-        load_cols_tile(tkt, Ktbase, gt.Tp, k0 + KT, klen, tid);
       }
       const bool need_mask = (k0 + KT > klen) || (kp_row != nullptr);
       unsigned long long km = ~0ull;
@@ -337,7 +321,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, GeoT gt, const b
       for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const bf16x8 a = lds_frag(sKt, db * 32 + lo, s * 16 + hi * 8);
+          const bf16x8 a = lds_frag_tr(sK, LDS_LD, s * 16, db * 32, lane);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) dqacc[db][qb] = mfma32(a, dsb[s >> 1][qb][s & 1], dqacc[db][qb]);
         }
@@ -349,7 +333,6 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, GeoT gt, const b
     const int row = qrow[qb];
     if (row >= qlen) continue;
     const long t = (long)b * g.T + g.seg_off[qs] + row;
-    const int pad_end = (row == qlen - 1) ? ((qlen + 7) & ~7) : 0;
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -358,14 +341,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, GeoT gt, const b
         float v[4];
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) v[jj] = dqacc[db][qb][4 * i + jj] * g.scale;
-        u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+        const u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
         *(u32x2*)(dQKV + t * ldg + h * 64 + dh0) = pk;
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          bf16_t* col = dQKVt + ((long)b * 3 * d + h * 64 + dh0 + jj) * gt.Tp + gt.tp_off[qs];
-          col[row] = (bf16_t)((jj & 1) ? (pk[jj >> 1] >> 16) : (pk[jj >> 1] & 0xffffu));
-          for (int z = qlen; z < pad_end; ++z) col[z] = 0;
-        }
       }
   }
 }
@@ -375,17 +352,14 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, GeoT gt, const b
 // the query rows of every query segment that reads this key segment.  A key tile
 // has exactly one producer, so the result is deterministic without atomics.
 template <int KB>
-__global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, GeoT gt, const bf16_t* __restrict__ QKV, long ld,
-                                                       const bf16_t* __restrict__ QKVt, const bf16_t* __restrict__ dO,
-                                                       long ldo, const bf16_t* __restrict__ dOt,
+__global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
+                                                       const bf16_t* __restrict__ dO, long ldo,
                                                        const float* __restrict__ lse2, const float* __restrict__ delta,
                                                        const int32_t* __restrict__ valid_len,
                                                        const uint8_t* __restrict__ key_pad, bf16_t* __restrict__ dQKV,
-                                                       long ldg, bf16_t* __restrict__ dQKVt) {
+                                                       long ldg) {
   __shared__ __attribute__((aligned(16))) bf16_t sQ[KT * LDS_LD];
   __shared__ __attribute__((aligned(16))) bf16_t sG[KT * LDS_LD];
-  __shared__ __attribute__((aligned(16))) bf16_t sQt[64 * LDS_LD];
-  __shared__ __attribute__((aligned(16))) bf16_t sGt[64 * LDS_LD];
   __shared__ __attribute__((aligned(16))) float sL[KT];
   __shared__ __attribute__((aligned(16))) float sD[KT];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
@@ -432,16 +406,12 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, GeoT gt, const 
     const int qlen = g.seg_len[i];
     const bf16_t* Qbase = QKV + ((long)b * g.T + g.seg_off[i]) * ld + h * 64;
     const bf16_t* Gbase = dO + ((long)b * g.T + g.seg_off[i]) * ldo + h * 64;
-    const bf16_t* Qtbase = QKVt + ((long)b * 3 * d + h * 64) * gt.Tp + gt.tp_off[i];
-    const bf16_t* Gtbase = dOt + ((long)b * d + h * 64) * gt.Tp + gt.tp_off[i];
     const long lbase = ((long)b * g.H + h) * g.T + g.seg_off[i];
-    TileRegs tq, tg, tqt, tgt;
+    TileRegs tq, tg;
     float rl = 0.f, rd = 0.f;
     auto prefetch = [&](int r0) {
       load_rows_tile(tq, Qbase, ld, r0, qlen - 1, tid);
       load_rows_tile(tg, Gbase, ldo, r0, qlen - 1, tid);
-      load_cols_tile(tqt, Qtbase, gt.Tp, r0, qlen, tid);
-      load_cols_tile(tgt, Gtbase, gt.Tp, r0, qlen, tid);
       if (tid < KT) {
         const int r = r0 + tid;
         const float lv = (r < qlen) ? lse2[lbase + r] : IM_NEG_INF;
@@ -454,8 +424,6 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, GeoT gt, const 
       __syncthreads();
       store_tile(tq, sQ, tid);
       store_tile(tg, sG, tid);
-      store_tile(tqt, sQt, tid);
-      store_tile(tgt, sGt, tid);
       if (tid < KT) { sL[tid] = rl; sD[tid] = rd; }
       __syncthreads();
       if (r0 + KT < qlen) prefetch(r0 + KT);
@@ -504,8 +472,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, GeoT gt, const 
         for (int db = 0; db < 2; ++db)
 #pragma unroll
           for (int half = 0; half < 2; ++half) {
-            const bf16x8 agt = lds_frag(sGt, db * 32 + lo, qb * 32 + half * 16 + hi * 8);
-            const bf16x8 aqt = lds_frag(sQt, db * 32 + lo, qb * 32 + half * 16 + hi * 8);
+            const bf16x8 agt = lds_frag_tr(sG, LDS_LD, qb * 32 + half * 16, db * 32, lane);
+            const bf16x8 aqt = lds_frag_tr(sQ, LDS_LD, qb * 32 + half * 16, db * 32, lane);
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) {
               dvacc[db][kb] = mfma32(agt, pb[kb][half], dvacc[db][kb]);
@@ -521,41 +489,23 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, GeoT gt, const 
     const int row = krow[kb];
     if (row >= klen_seg) continue;
     const long t = (long)b * g.T + g.seg_off[ks] + row;
-    const int pad_end = (row == klen_seg - 1) ? ((klen_seg + 7) & ~7) : 0;
     const float zk = kvalid[kb] ? g.scale : 0.f, zv = kvalid[kb] ? 1.f : 0.f;
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int dh0 = db * 32 + 8 * i + 4 * hi;
-        u32x2 pk = {pack_bf16(dkacc[db][kb][4 * i] * zk, dkacc[db][kb][4 * i + 1] * zk),
-                    pack_bf16(dkacc[db][kb][4 * i + 2] * zk, dkacc[db][kb][4 * i + 3] * zk)};
-        u32x2 pv = {pack_bf16(dvacc[db][kb][4 * i] * zv, dvacc[db][kb][4 * i + 1] * zv),
-                    pack_bf16(dvacc[db][kb][4 * i + 2] * zv, dvacc[db][kb][4 * i + 3] * zv)};
+        const u32x2 pk = {pack_bf16(dkacc[db][kb][4 * i] * zk, dkacc[db][kb][4 * i + 1] * zk),
+                          pack_bf16(dkacc[db][kb][4 * i + 2] * zk, dkacc[db][kb][4 * i + 3] * zk)};
+        const u32x2 pv = {pack_bf16(dvacc[db][kb][4 * i] * zv, dvacc[db][kb][4 * i + 1] * zv),
+                          pack_bf16(dvacc[db][kb][4 * i + 2] * zv, dvacc[db][kb][4 * i + 3] * zv)};
         *(u32x2*)(dQKV + t * ldg + d + h * 64 + dh0) = pk;
         *(u32x2*)(dQKV + t * ldg + 2 * d + h * 64 + dh0) = pv;
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          bf16_t* ck = dQKVt + ((long)b * 3 * d + d + h * 64 + dh0 + jj) * gt.Tp + gt.tp_off[ks];
-          bf16_t* cv = ck + (long)d * gt.Tp;
-          ck[row] = (bf16_t)((jj & 1) ? (pk[jj >> 1] >> 16) : (pk[jj >> 1] & 0xffffu));
-          cv[row] = (bf16_t)((jj & 1) ? (pv[jj >> 1] >> 16) : (pv[jj >> 1] & 0xffffu));
-          for (int z = klen_seg; z < pad_end; ++z) { ck[z] = 0; cv[z] = 0; }
-        }
       }
   }
 }
 
-// zero columns [c0, c0+n) of nch channel rows of a transposed [B, C, Tp] buffer, and rows of a row-major one
-__global__ void zero_tcols_kernel(bf16_t* buf, long batch_stride, int B, int ch0, int nch, long tp, int c0, int n) {
-  const long total = (long)B * nch * n;
-  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
-    const int col = i % n;
-    const long r = i / n;
-    const int ch = r % nch, b = r / nch;
-    buf[b * batch_stride + (long)(ch0 + ch) * tp + c0 + col] = 0;
-  }
-}
+// zero a column range of some rows of a row-major activation matrix
 __global__ void zero_rows16_kernel(bf16_t* p, long ld, int B, int T_m, int row0, int nrows, int col0, int ncols) {
   const long n = (long)B * nrows * ncols;
   for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
@@ -577,51 +527,38 @@ int mfma_fwd_tile_rows() { return 128 * FWD_QB; }
 int mfma_dq_tile_rows() { return 128 * DQ_QB; }
 int mfma_dkv_tile_rows() { return 128 * DKV_KB; }
 
-void launch_mfma_fwd(const Geo& g, const GeoT& gt, const bf16_t* qkv, long ld, const bf16_t* qkvt,
-                     const int32_t* valid_len, const uint8_t* key_pad, bf16_t* o, long ldo, bf16_t* ot, float* lse2,
-                     hipStream_t st) {
+void launch_mfma_fwd(const Geo& g, const bf16_t* qkv, long ld, const int32_t* valid_len, const uint8_t* key_pad,
+                     bf16_t* o, long ldo, float* lse2, hipStream_t st) {
   // query segments with no live block: output 0, lse -inf
   for (int s = 0; s < g.n_seg; ++s) {
     if (g.q_live[s]) continue;
     hipLaunchKernelGGL(zero_rows16_kernel, dim3(64), dim3(256), 0, st, o, ldo, g.B, g.T, g.seg_off[s], g.seg_len[s], 0, g.d);
-    if (ot)
-      hipLaunchKernelGGL(zero_tcols_kernel, dim3(64), dim3(256), 0, st, ot, (long)g.d * gt.Tp, g.B, 0, g.d, (long)gt.Tp,
-                         gt.tp_off[s], gt.tp_off[s + 1] - gt.tp_off[s]);
     if (lse2) hipLaunchKernelGGL(fill_lse_seg_kernel, dim3(16), dim3(256), 0, st, lse2, g.B * g.H, g.T, g.seg_off[s], g.seg_len[s]);
   }
   const int nt = g.q_tile_prefix[g.q_nord];
   if (nt == 0) return;
   ProfScope ps(PF_ATTN_FWD, st);
-  hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB>), dim3(nt, g.H, g.B), dim3(256), 0, st, g, gt, qkv, ld, qkvt, valid_len,
-                     key_pad, o, ldo, ot, lse2);
+  hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB>), dim3(nt, g.H, g.B), dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o,
+                     ldo, lse2);
 }
 
-void launch_mfma_bwd(const Geo& gq, const Geo& gk, const GeoT& gt, const bf16_t* qkv, long ld, const bf16_t* qkvt,
-                     const bf16_t* o, const bf16_t* d_o, long ldo, const bf16_t* d_ot, const float* lse2,
-                     const int32_t* valid_len, const uint8_t* key_pad, float* delta, bf16_t* dqkv, long ldg,
-                     bf16_t* dqkvt, hipStream_t st) {
-  const Geo& g = gq;
+void launch_mfma_bwd(const Geo& g, const bf16_t* qkv, long ld, const bf16_t* o, const bf16_t* d_o, long ldo,
+                     const float* lse2, const int32_t* valid_len, const uint8_t* key_pad, float* delta, bf16_t* dqkv,
+                     long ldg, hipStream_t st) {
   for (int s = 0; s < g.n_seg; ++s) {
-    const int ncol = gt.tp_off[s + 1] - gt.tp_off[s];
-    if (!g.q_live[s]) {
+    if (!g.q_live[s])
       hipLaunchKernelGGL(zero_rows16_kernel, dim3(64), dim3(256), 0, st, dqkv, ldg, g.B, g.T, g.seg_off[s], g.seg_len[s], 0, g.d);
-      hipLaunchKernelGGL(zero_tcols_kernel, dim3(64), dim3(256), 0, st, dqkvt, 3l * g.d * gt.Tp, g.B, 0, g.d, (long)gt.Tp,
-                         gt.tp_off[s], ncol);
-    }
-    if (!g.k_live[s]) {
+    if (!g.k_live[s])
       hipLaunchKernelGGL(zero_rows16_kernel, dim3(64), dim3(256), 0, st, dqkv, ldg, g.B, g.T, g.seg_off[s], g.seg_len[s], g.d, 2 * g.d);
-      hipLaunchKernelGGL(zero_tcols_kernel, dim3(64), dim3(256), 0, st, dqkvt, 3l * g.d * gt.Tp, g.B, g.d, 2 * g.d, (long)gt.Tp,
-                         gt.tp_off[s], ncol);
-    }
   }
-  const int nq = gq.q_tile_prefix[gq.q_nord], nk = gk.k_tile_prefix[gk.k_nord];
+  const int nq = g.q_tile_prefix[g.q_nord], nk = g.k_tile_prefix[g.k_nord];
   if (nq == 0) return;
   { ProfScope ps(PF_ATTN_DQ, st);
-    hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB>), dim3(nq, g.H, g.B), dim3(256), 0, st, gq, gt, qkv, ld, qkvt, o, d_o, ldo,
-                       lse2, valid_len, key_pad, delta, dqkv, ldg, dqkvt); }
+    hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB>), dim3(nq, g.H, g.B), dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2,
+                       valid_len, key_pad, delta, dqkv, ldg); }
   { ProfScope ps(PF_ATTN_DKV, st);
-    hipLaunchKernelGGL((mfma_dkv_kernel<DKV_KB>), dim3(nk, g.H, g.B), dim3(256), 0, st, gk, gt, qkv, ld, qkvt, d_o, ldo,
-                       d_ot, lse2, delta, valid_len, key_pad, dqkv, ldg, dqkvt); }
+    hipLaunchKernelGGL((mfma_dkv_kernel<DKV_KB>), dim3(nk, g.H, g.B), dim3(256), 0, st, g, qkv, ld, d_o, ldo, lse2, delta,
+                       valid_len, key_pad, dqkv, ldg); }
 }
 
 }  // namespace imattn

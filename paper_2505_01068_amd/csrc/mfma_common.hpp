@@ -62,13 +62,6 @@ __device__ __forceinline__ bf16x8 pack8(const float* v) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Padded-transposed token axis: segment s starts at tp_off[s] (multiple of 8);
-// Tp = sum of round_up_8(seg_len).  Pad columns of a transposed buffer hold 0.
-struct GeoT {
-  int tp_off[IM_MAX_SEG + 1];
-  int Tp;
-};
-
 // Stage a 64-row x 64-column bf16 tile from global memory into LDS (row stride
 // LDS_LD) with 256 threads: two 16-byte loads per thread.
 //   row r of the tile lives at  base + rowidx(r) * gstride  (rowidx clamps tails)
@@ -86,34 +79,32 @@ __device__ __forceinline__ void load_rows_tile(TileRegs& t, const bf16_t* base, 
   }
 }
 
-// rows = channels, columns = tokens c0 .. c0+63 of a transposed [C, Tp] matrix;
-// columns >= cmax are zero-filled (cmax relative to the same origin as c0).
-__device__ __forceinline__ void load_cols_tile(TileRegs& t, const bf16_t* base, long tp, int c0, int cmax, int tid) {
-#pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int r = (tid >> 3) + u * 32, c = c0 + (tid & 7) * 8;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (c < cmax) {
-      v = *(const u32x4*)(base + (long)r * tp + c);
-      if (c + 8 > cmax) {
-        const int keep = cmax - c;  // 1..7 valid elements
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const unsigned lo_ok = (2 * e < keep) ? 0xffffu : 0u, hi_ok = (2 * e + 1 < keep) ? 0xffff0000u : 0u;
-          v[e] &= (lo_ok | hi_ok);
-        }
-      }
-    }
-    t.v[u] = v;
-  }
-}
-
 __device__ __forceinline__ void store_tile(const TileRegs& t, bf16_t* lds, int tid) {
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     const int r = (tid >> 3) + u * 32, c = (tid & 7) * 8;
     *(u32x4*)(lds + r * LDS_LD + c) = t.v[u];
   }
+}
+
+// Transposed fragment from a K-MAJOR tile (row = contraction index k, columns = m) using the
+// gfx950 LDS transpose read.  ds_read_b64_tr_b16 exchanges data inside each group of 16 lanes:
+// result[lane i][e] = data[lane 4e + i/4][i % 4] (checked on hardware), where data[lane j] are the
+// four 16-bit elements lane j's address points at.  With lane j pointing at (row k0 + j/4,
+// columns m0 + 4*(j%4) ..+3) a group reads a 4 x 16 block and lane i receives column m0 + i, rows
+// k0..k0+3.  Two reads give the 8 consecutive k a 32x32x16 operand needs: lane l gets
+// m = m_base + (l % 32), k = k_base + 8*(l / 32) + 0..7.
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8 lds_frag_tr(const bf16_t* lds, int ld, int k_base, int m_base, int lane) {
+  const int j = lane & 15, g = lane >> 4;
+  const bf16_t* p = lds + (k_base + 8 * (g >> 1) + (j >> 2)) * ld + m_base + 16 * (g & 1) + 4 * (j & 3);
+  typedef v4i16 __attribute__((address_space(3))) * lds_v4_ptr;
+  const v4i16 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_ptr)(p));
+  const v4i16 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_ptr)(p + 4 * ld));
+  union { v4i16 h[2]; bf16x8 v; } x;
+  x.h[0] = a;
+  x.h[1] = b;
+  return x.v;
 }
 
 __device__ __forceinline__ bf16x8 lds_frag(const bf16_t* lds, int row, int col) {

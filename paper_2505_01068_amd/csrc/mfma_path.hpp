@@ -5,40 +5,32 @@
 
 namespace imattn {
 
-struct GeoT;
-
-// Descriptor of one bf16 MFMA GEMM  C[M,N] = A[M,K] B[N,K]^T  (see mfma_gemm.hip).
+// Descriptor of one bf16 MFMA GEMM  C[M,N] = sum_k A(m,k) B(n,k)  (see mfma_gemm.hip).
 struct MGemm {
-  const bf16_t* A; long lda, a_bs;       // A rows (K contiguous); a_bs = element stride between K batches
-  const bf16_t* B[3]; long ldb, b_bs;    // B rows (K contiguous)
-  int b_kper;                            // > 0: B[s] covers K columns [s*b_kper, (s+1)*b_kper)
-  int M, N, kb, kt;                      // K = kb batches of kt columns (kb = 1 for an ordinary GEMM)
+  const bf16_t* A; long lda; int a_kmajor;  // a_kmajor = 0: A is [M][K] rows; 1: A is [K][M] rows
+  const bf16_t* B[3]; long ldb; int b_kmajor;  // b_kmajor = 0: B is [N][K] rows; 1: B is [K][N] rows
+  int b_kper;                            // > 0 (m-major B): B[s] covers K columns [s*b_kper, (s+1)*b_kper)
+  int b_nper;                            // > 0 (k-major B): B[s] covers N columns [s*b_nper, (s+1)*b_nper)
+  int M, N, K;
   int split_k; float* partial;           // partial != NULL: write fp32 partial[z][M][N] instead of the epilogue
   const bf16_t* bias[3]; int n_per;      // bias[n / n_per][n % n_per] (n_per = N for a single bias), or all NULL
   int gelu;
   const bf16_t* res;                     // residual rows, same ld as C
-  bf16_t* C; long ldc;                   // row-major output (may be NULL)
-  bf16_t* Ct; long ct_bs;                // token-transposed output [batch][N][Tp] (may be NULL); ct_bs = N_total * Tp
-  int Tp, T, n_seg;
-  int seg_off[IM_MAX_SEG + 1], tp_off[IM_MAX_SEG + 1];
+  bf16_t* C; long ldc;                   // row-major output
 };
 void launch_mfma_gemm(const MGemm& p, hipStream_t st);
-int mfma_gemm_split(int M, int N, int total_ktiles);
+int mfma_gemm_split(int M, int N, int K);
 void launch_splitk_reduce(const float* partial, int split_k, int M, int N, float* o0, float* o1, float* o2, int n_per,
                           hipStream_t st);
-void launch_transpose_pad(const bf16_t* x, long ld, int C, const Geo& g, const GeoT& gt, bf16_t* xt, hipStream_t st);
-void launch_transpose_w(const bf16_t* w, int K, int N, bf16_t* wt, hipStream_t st);
 
 int mfma_fwd_tile_rows();
 int mfma_dq_tile_rows();
 int mfma_dkv_tile_rows();
-void launch_mfma_fwd(const Geo& g, const GeoT& gt, const bf16_t* qkv, long ld, const bf16_t* qkvt,
-                     const int32_t* valid_len, const uint8_t* key_pad, bf16_t* o, long ldo, bf16_t* ot, float* lse2,
-                     hipStream_t st);
-void launch_mfma_bwd(const Geo& gq, const Geo& gk, const GeoT& gt, const bf16_t* qkv, long ld, const bf16_t* qkvt,
-                     const bf16_t* o, const bf16_t* d_o, long ldo, const bf16_t* d_ot, const float* lse2,
-                     const int32_t* valid_len, const uint8_t* key_pad, float* delta, bf16_t* dqkv, long ldg,
-                     bf16_t* dqkvt, hipStream_t st);
+void launch_mfma_fwd(const Geo& g, const bf16_t* qkv, long ld, const int32_t* valid_len, const uint8_t* key_pad,
+                     bf16_t* o, long ldo, float* lse2, hipStream_t st);
+void launch_mfma_bwd(const Geo& g, const bf16_t* qkv, long ld, const bf16_t* o, const bf16_t* d_o, long ldo,
+                     const float* lse2, const int32_t* valid_len, const uint8_t* key_pad, float* delta, bf16_t* dqkv,
+                     long ldg, hipStream_t st);
 
 // Geometry helper shared with api.hip
 void build_geo(const im_shape_t* s, int q_tile, int k_tile, Geo* g);
