@@ -50,6 +50,24 @@ __device__ __forceinline__ void stf(bf16_t* p, float v) { *p = f2bf(v); }
 
 #define IM_NEG_INF (-__builtin_inff())
 
+// XCD-aware workgroup index.  The dispatcher deals consecutive workgroup ids round-robin to the
+// 8 XCDs (each with its own L2).  Remapping id -> (id % 8) * chunk + id / 8 makes every XCD work
+// through one CONTIGUOUS range of logical tiles, so tiles that share an operand (the K/V of one
+// (batch, head); the activation rows of one GEMM row block) meet in the same L2.
+#ifdef __HIPCC__
+__device__ __forceinline__ void xcd_block_index(int& bx, int& by, int& bz) {
+  const unsigned gx = gridDim.x, gy = gridDim.y, gz = gridDim.z;
+  const unsigned total = gx * gy * gz;
+  const unsigned lin = blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z);
+  const unsigned xcd = lin & 7u, idx = lin >> 3;
+  const unsigned q = total >> 3, r = total & 7u;
+  const unsigned logical = xcd * q + (xcd < r ? xcd : r) + idx;
+  bx = logical % gx;
+  by = (logical / gx) % gy;
+  bz = logical / (gx * gy);
+}
+#endif
+
 // ---- launchers implemented in the .hip files (all enqueue on `st`, none syncs) ----
 
 // fp32-ALU GEMM  C[m,n] = sum_k A(m,k) B(k,n) (+bias[n]) (+res[m,n]), optional GELU,

@@ -41,10 +41,11 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
   __shared__ __attribute__((aligned(16))) bf16_t sK[KT * LDS_LD];
   __shared__ __attribute__((aligned(16))) bf16_t sV[KT * LDS_LD];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
-  const int h = blockIdx.y, b = blockIdx.z;
+  int tile, h, b;
+  xcd_block_index(tile, h, b);
   constexpr int WG_ROWS = 128 * QB;
   int qs, q0;
-  decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, WG_ROWS, blockIdx.x, qs, q0);
+  decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, WG_ROWS, tile, qs, q0);
   const int qlen = g.seg_len[qs];
   const int d = g.d;
   const float c = g.scale_log2e;
@@ -206,10 +207,11 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
   __shared__ __attribute__((aligned(16))) bf16_t sK[KT * LDS_LD];
   __shared__ __attribute__((aligned(16))) bf16_t sV[KT * LDS_LD];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
-  const int h = blockIdx.y, b = blockIdx.z;
+  int tile, h, b;
+  xcd_block_index(tile, h, b);
   constexpr int WG_ROWS = 128 * QB;
   int qs, q0;
-  decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, WG_ROWS, blockIdx.x, qs, q0);
+  decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, WG_ROWS, tile, qs, q0);
   const int qlen = g.seg_len[qs];
   const int d = g.d;
   const float c = g.scale_log2e;
@@ -363,10 +365,11 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
   __shared__ __attribute__((aligned(16))) float sL[KT];
   __shared__ __attribute__((aligned(16))) float sD[KT];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
-  const int h = blockIdx.y, b = blockIdx.z;
+  int tile, h, b;
+  xcd_block_index(tile, h, b);
   constexpr int WG_ROWS = 128 * KB;
   int ks, k0;
-  decode_tile(g.k_order, g.k_tile_prefix, g.k_nord, WG_ROWS, blockIdx.x, ks, k0);
+  decode_tile(g.k_order, g.k_tile_prefix, g.k_nord, WG_ROWS, tile, ks, k0);
   const int klen_seg = g.seg_len[ks];
   const int d = g.d;
   const float c = g.scale_log2e;

@@ -79,11 +79,13 @@ __global__ __launch_bounds__(256) void mfma_gemm_kernel(MGemm p) {
   __shared__ __attribute__((aligned(16))) bf16_t sB[BKM ? GK * KM_LD : GN * LDS_LD];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int wm = wave >> 1, wn = wave & 1;
-  const int m0 = blockIdx.y * GM, n0 = blockIdx.x * GN;
+  int bx, by, bz;
+  xcd_block_index(bx, by, bz);
+  const int m0 = by * GM, n0 = bx * GN;
 
   const int ktiles = (p.K + GK - 1) / GK;
   const int per_split = (ktiles + p.split_k - 1) / p.split_k;
-  const int it_begin = blockIdx.z * per_split, it_end = min(ktiles, it_begin + per_split);
+  const int it_begin = bz * per_split, it_end = min(ktiles, it_begin + per_split);
 
   f32x16 acc[2][2];  // [n block][m block]: rows of the accumulator = n, cols = m
 #pragma unroll
@@ -148,7 +150,7 @@ __global__ __launch_bounds__(256) void mfma_gemm_kernel(MGemm p) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j];
         if (p.partial) {
-          *(float4*)(p.partial + ((long)blockIdx.z * p.M + m) * p.N + n) = make_float4(v[0], v[1], v[2], v[3]);
+          *(float4*)(p.partial + ((long)bz * p.M + m) * p.N + n) = make_float4(v[0], v[1], v[2], v[3]);
           continue;
         }
         if (p.n_per > 0) {
