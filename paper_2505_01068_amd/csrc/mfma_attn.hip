@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
   decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, WG_ROWS, tile, qs, q0);
   const int qlen = g.seg_len[qs];
   const int d = g.d;
-  const float c = g.scale_log2e;
+  const float c = fmaxf(g.scale_log2e, 1e-30f);  // > 0 so that -inf * c stays -inf when scale == 0
 
   // Q operand (B of S^T = K Q^T): lane holds query row lo of each block, 8 consecutive dh per k-step
   bf16x8 qreg[QB][4];
@@ -75,6 +75,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
   }
 
   const int prow = perm32(lo);
+  const float tau = c > 0.f ? 8.f / c : __builtin_inff();
   const unsigned live = g.q_live[qs];
   for (int j = 0; j < g.n_seg; ++j) {
     if (!((live >> j) & 1u)) continue;
@@ -136,10 +137,21 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
 #pragma unroll
           for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][qb][r]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float mn = fmaxf(m[qb], mx);
-        const float ms = (mn == IM_NEG_INF) ? 0.f : mn;
-        const float alpha = fast_exp2((m[qb] - ms) * c);
-        const float msc = ms * c;
+        // Lazy rescale: the running reference m only moves when the tile maximum exceeds it by more
+        // than 2^8 in the exponent domain, so probabilities stay <= 256 (exact in bf16's range) and
+        // the accumulator rescale below is skipped for almost every tile after the first.
+        const bool upd = mx > m[qb] + tau;
+        if (__any(upd)) {
+          const float mn = upd ? mx : m[qb];
+          const float alpha = (m[qb] == IM_NEG_INF) ? 0.f : fast_exp2((m[qb] - mn) * c);
+          l[qb] *= alpha;
+#pragma unroll
+          for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
+          m[qb] = mn;
+        }
+        const float msc = (m[qb] == IM_NEG_INF) ? 0.f : m[qb] * c;
         float rs = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
@@ -152,12 +164,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
           pb[kb][qb][0] = pack8(p);
           pb[kb][qb][1] = pack8(p + 8);
         }
-        l[qb] = fmaf(l[qb], alpha, rs);
-        m[qb] = mn;
-#pragma unroll
-        for (int db = 0; db < 2; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
+        l[qb] += rs;
       }
       // ---- O^T += V^T P^T ----
 #pragma unroll
@@ -214,7 +221,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
   decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, WG_ROWS, tile, qs, q0);
   const int qlen = g.seg_len[qs];
   const int d = g.d;
-  const float c = g.scale_log2e;
+  const float c = fmaxf(g.scale_log2e, 1e-30f);  // > 0 so that -inf * c stays -inf when scale == 0
 
   bf16x8 qreg[QB][4], greg[QB][4];
   int qrow[QB];
@@ -372,7 +379,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
   decode_tile(g.k_order, g.k_tile_prefix, g.k_nord, WG_ROWS, tile, ks, k0);
   const int klen_seg = g.seg_len[ks];
   const int d = g.d;
-  const float c = g.scale_log2e;
+  const float c = fmaxf(g.scale_log2e, 1e-30f);  // > 0 so that -inf * c stays -inf when scale == 0
 
   bf16x8 kreg[KB][4], vreg[KB][4];
   int krow[KB];

@@ -126,3 +126,21 @@ def test_c5_full_size_weight_gradients():
     for n in ("dwq", "dwk", "dwv", "dwo"):
         e = assert_close(f["grads"][n], f["acc"][n], TOL["bf16"], f"c5 {n}")
         say(f"    {n}={e:.1e}")
+
+
+def test_mfma_zero_scale_and_large_scores():
+    """scale = 0 gives uniform attention over valid keys (no NaN from -inf * 0); large, growing scores
+    exercise the lazily updated softmax reference (tile maxima far above the running one)."""
+    say("[case] mfma scale=0 / growing scores")
+    g = synth.attention_inputs(2, (70, 300, 129), 64, 1, "bf16", "valid_len", seed=31, bias=False)
+    g0 = dict(g, scale=0.0)
+    Problem(g0, oracle.IM_IFM_FORWARD).check(what="mfma scale=0")
+    g1 = dict(g)
+    x = g["x"].copy()
+    ramp = np.linspace(0.3, 2.2, x.shape[1], dtype=np.float32)[None, :, None]
+    g1["x"] = synth.to_bf16_grid(x * ramp)       # later keys have larger scores: row maxima keep growing
+    g1["scale"] = 0.35                           # exponent range well beyond the 2^8 rescale threshold
+    # forward only: with softmax this peaked the bf16 rounding of Q and K alone moves the gradients by
+    # more than the bar (conditioning of the problem, not of the kernel)
+    for lm in (oracle.IM_IFM_FORWARD, oracle.IM_DENSE):
+        Problem(g1, lm).check(backward=False, what=f"mfma growing scores lm={lm:#x}")
