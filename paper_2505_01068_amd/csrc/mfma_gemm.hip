@@ -175,24 +175,286 @@ __global__ __launch_bounds__(256) void mfma_gemm_kernel(MGemm p) {
   }
 }
 
-// partial[z][M][N] -> out (fp32), z summed in fixed order; output column blocks may go to 3 matrices
-__global__ void mfma_splitk_reduce_kernel(const float* partial, int split_k, int M, int N, float* o0, float* o1,
-                                          float* o2, int n_per) {
-  const long n_out = (long)M * N;
-  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n_out; i += (long)gridDim.x * blockDim.x) {
-    float s = 0.f;
-    for (int z = 0; z < split_k; ++z) s += partial[z * n_out + i];
-    const int m = i / N, n = i % N;
-    if (n_per > 0) {
-      float* o = (n / n_per == 0) ? o0 : (n / n_per == 1) ? o1 : o2;
-      if (o) o[(long)m * n_per + n % n_per] = s;
+// ------------------------------------------------------------------------------------------
+// Large-tile kernel with asynchronous global->LDS staging.
+//
+// The 128 x 128 kernel above is bound by bytes in flight, not by the matrix cores: one
+// register-staged k-tile per workgroup covers well under the L2/HBM round trip.  Here the
+// tile is 256 x 256 (4 waves, each 128 x 128 = 4 x 4 MFMA blocks, 256 accumulator registers), a
+// quarter of the operand traffic per flop, and operands go straight from global memory into a
+// ring of four 32-deep LDS stages with global_load_lds_dwordx4 (no staging registers), three
+// stages in flight while one is multiplied, one barrier per stage.
+//
+// A direct load writes lane i's 16 bytes at (wave-uniform LDS base) + 16 i, so rows cannot be
+// padded; bank conflicts are avoided by XOR-swizzling the 16-byte chunk index instead:
+//   m-major tile [256 rows][4 chunks]  : chunk kc of row r sits at r*4 + (kc ^ ((r >> 2) & 3))
+//   k-major tile [32 rows][32 chunks]  : chunk c of row k sits at k*32 + (c ^ ((k & 3) << 2))
+// (16 consecutive rows read at one kc, resp. the 4 x 4 chunk footprint of a transpose read, then
+// cover all 64 banks exactly once).  Each lane fetches the global chunk that belongs in its slot.
+constexpr int DM = 256, DN = 256, DK = 32, DSTAGES = 4;
+constexpr int DMA_STAGE_BYTES = (DM + DN) * DK * 2;           // 32 KB
+constexpr int DMA_LDS_BYTES = DSTAGES * DMA_STAGE_BYTES;      // 128 KB
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* glb_void_ptr;
+
+template <bool AKM, bool BKM>
+__global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
+  extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  int bx, by, bz;
+  xcd_block_index(bx, by, bz);
+  const int m0 = by * DM, n0 = bx * DN;
+
+  const int ktiles = p.K / DK;  // K % 32 == 0 is required by the launcher
+  const int per_split = (ktiles + p.split_k - 1) / p.split_k;
+  const int it_begin = bz * per_split, it_end = min(ktiles, it_begin + per_split);
+  const int n_it = max(0, it_end - it_begin);
+
+  // ---- per-thread source pointers of the 4 + 4 chunks it fetches per stage (advanced by DK per stage) ----
+  const bf16_t* ga[4];
+  const bf16_t* gb[4];   // k-major B: source pointer; m-major B: only the offset inside one matrix is used
+  long gboff[4];
+  long a_step, b_step;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int slot = (wave * 4 + j) * 64 + lane;  // chunk slot inside the 1024-chunk tile
+    if (AKM) {
+      const int k = slot >> 5, pos = slot & 31, c = pos ^ ((k & 3) << 2);
+      const int col = min(m0 + c * 8, p.M - 8);
+      ga[j] = p.A + (long)(it_begin * DK + k) * p.lda + col;
     } else {
-      o0[i] = s;
+      const int r = slot >> 2, pos = slot & 3, kc = pos ^ ((r >> 2) & 3);
+      ga[j] = p.A + (long)min(m0 + r, p.M - 1) * p.lda + it_begin * DK + kc * 8;
+    }
+    if (BKM) {
+      const int k = slot >> 5, pos = slot & 31, c = pos ^ ((k & 3) << 2);
+      const int col = min(n0 + c * 8, p.N - 8);
+      const bf16_t* mat = p.B[0];
+      int cc = col;
+      if (p.b_nper > 0) { mat = p.B[col / p.b_nper]; cc = col % p.b_nper; }
+      gb[j] = mat + (long)(it_begin * DK + k) * p.ldb + cc;
+    } else {
+      const int r = slot >> 2, pos = slot & 3, kc = pos ^ ((r >> 2) & 3);
+      gb[j] = p.B[0];
+      gboff[j] = (long)min(n0 + r, p.N - 1) * p.ldb + kc * 8;  // k offset added per stage (K may be split over B[])
+    }
+    if (BKM) gboff[j] = 0;
+  }
+  a_step = AKM ? (long)DK * p.lda : DK;
+  b_step = BKM ? (long)DK * p.ldb : DK;
+
+  auto issue = [&](int it_rel) {  // fetch stage it_rel (relative to it_begin) into ring slot it_rel % DSTAGES
+    char* base = (char*)smem + (it_rel % DSTAGES) * DMA_STAGE_BYTES;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bf16_t* src = ga[j] + (long)it_rel * a_step;
+      __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(base + (wave * 4 + j) * 1024), 16, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bf16_t* src;
+      if (BKM) {
+        src = gb[j] + (long)it_rel * b_step;
+      } else {
+        const int k0 = (it_begin + it_rel) * DK;
+        const bf16_t* mat = p.B[0];
+        int kk = k0;
+        if (p.b_kper > 0) { mat = p.B[k0 / p.b_kper]; kk = k0 % p.b_kper; }
+        src = mat + gboff[j] + kk;
+      }
+      __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(base + DM * DK * 2 + (wave * 4 + j) * 1024), 16,
+                                       0, 0);
+    }
+  };
+
+  f32x16 acc[4][4];  // [n block][m block]
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+  // ---- LDS byte offsets of this lane's fragments inside a stage ----
+  int offA[2][4], offB[2][4];   // [k-step][block]; for k-major operands the second transpose read is +4 rows
+  int offA2[2][4], offB2[2][4];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      if (AKM) {
+        const int j = lane & 15, gq = lane >> 4;
+        const int kr = ks * 16 + 8 * (gq >> 1) + (j >> 2), col = wm * 128 + x * 32 + 16 * (gq & 1) + 4 * (j & 3);
+        offA[ks][x] = (kr * 32 + ((col >> 3) ^ ((kr & 3) << 2))) * 16 + (col & 7) * 2;
+        offA2[ks][x] = ((kr + 4) * 32 + ((col >> 3) ^ (((kr + 4) & 3) << 2))) * 16 + (col & 7) * 2;
+      } else {
+        const int row = wm * 128 + x * 32 + lo, kc = ks * 2 + hi;
+        offA[ks][x] = (row * 4 + (kc ^ ((row >> 2) & 3))) * 16;
+        offA2[ks][x] = 0;
+      }
+      if (BKM) {
+        const int j = lane & 15, gq = lane >> 4;
+        const int kr = ks * 16 + 8 * (gq >> 1) + (j >> 2), col = wn * 128 + x * 32 + 16 * (gq & 1) + 4 * (j & 3);
+        offB[ks][x] = DM * DK * 2 + (kr * 32 + ((col >> 3) ^ ((kr & 3) << 2))) * 16 + (col & 7) * 2;
+        offB2[ks][x] = DM * DK * 2 + ((kr + 4) * 32 + ((col >> 3) ^ (((kr + 4) & 3) << 2))) * 16 + (col & 7) * 2;
+      } else {
+        const int row = wn * 128 + x * 32 + lo, kc = ks * 2 + hi;
+        offB[ks][x] = DM * DK * 2 + (row * 4 + (kc ^ ((row >> 2) & 3))) * 16;
+        offB2[ks][x] = 0;
+      }
+    }
+  auto frag = [&](const char* st, int o1, int o2, bool km) -> bf16x8 {
+    if (!km) return as_bf16x8(*(const u32x4*)(st + o1));
+    typedef v4i16 __attribute__((address_space(3))) * lds_v4_ptr;
+    union { v4i16 h[2]; bf16x8 v; } x;
+    x.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_ptr)(st + o1));
+    x.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_ptr)(st + o2));
+    return x.v;
+  };
+
+  // ---- pipeline: stages it+1 .. it+3 in flight while stage it is multiplied ----
+#pragma unroll
+  for (int s = 0; s < DSTAGES - 1; ++s)
+    if (s < n_it) issue(s);
+  for (int it = 0; it < n_it; ++it) {
+    // this lane's loads of stage `it` have landed when at most the loads of the later stages remain
+    const int later = min(DSTAGES - 2, n_it - 1 - it);
+    // (8 loads per thread and stage).  A bare s_barrier is used: __syncthreads() would also drain vmcnt.
+    if (later >= 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    else if (later == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (it + DSTAGES - 1 < n_it) issue(it + DSTAGES - 1);
+    const char* st = (const char*)smem + (it % DSTAGES) * DMA_STAGE_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      bf16x8 fa[4], fb[4];
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        fa[x] = frag(st, offA[ks][x], offA2[ks][x], AKM);
+        fb[x] = frag(st, offB[ks][x], offB2[ks][x], BKM);
+      }
+#pragma unroll
+      for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) acc[nb][mb] = mfma32(fb[nb], fa[mb], acc[nb][mb]);
+    }
+  }
+
+  // ---- epilogue ----
+  if (p.partial) {  // split-K: fp32 partial sums, 16 bytes per lane
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) {
+      const int m = m0 + wm * 128 + mb * 32 + lo;
+      if (m >= p.M) continue;
+#pragma unroll
+      for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int n = n0 + wn * 128 + nb * 32 + 8 * i + 4 * hi;
+          if (n >= p.N) continue;
+          *(float4*)(p.partial + ((long)bz * p.M + m) * p.N + n) =
+              make_float4(acc[nb][mb][4 * i], acc[nb][mb][4 * i + 1], acc[nb][mb][4 * i + 2], acc[nb][mb][4 * i + 3]);
+        }
+    }
+    return;
+  }
+  // bf16 output: a lane owns a ROW of the accumulator tile (8 bytes per register quad), which would
+  // make every store touch 64 different cache lines.  The wave's 128 x 128 tile therefore goes through
+  // its own quarter of the (now idle) stage ring, 64 rows at a time, and leaves as 16-byte stores in
+  // which 16 consecutive lanes cover one 256-byte row segment.
+  __builtin_amdgcn_s_barrier();  // every wave has finished reading the last stage
+  asm volatile("" ::: "memory");
+  constexpr int EP_LD = 136;     // bf16 per staged row (128 + 8 pad)
+  bf16_t* stg = smem + wave * (DMA_LDS_BYTES / 8);
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+#pragma unroll
+    for (int mq = 0; mq < 2; ++mq) {
+      const int mb = half * 2 + mq;
+      const int m = m0 + wm * 128 + mb * 32 + lo;
+#pragma unroll
+      for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int nl = nb * 32 + 8 * i + 4 * hi;
+          const int n = n0 + wn * 128 + nl;
+          float v[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j];
+          if (p.n_per > 0 && n < p.N) {
+            const int sel = n / p.n_per, nn = n % p.n_per;
+            if (p.bias[sel]) {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) v[j] += bf2f(p.bias[sel][nn + j]);
+            }
+          }
+          if (p.gelu) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = gelu_exact_f(v[j]);
+          }
+          if (p.res && m < p.M && n < p.N) {
+            const u32x2 rv = *(const u32x2*)(p.res + (long)m * p.ldc + n);
+            v[0] += __uint_as_float(rv[0] << 16); v[1] += __uint_as_float(rv[0] & 0xffff0000u);
+            v[2] += __uint_as_float(rv[1] << 16); v[3] += __uint_as_float(rv[1] & 0xffff0000u);
+          }
+          const u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+          *(u32x2*)(stg + (mq * 32 + lo) * EP_LD + nl) = pk;
+        }
+    }
+    // 64 rows x 16 chunks of 16 bytes; lane -> (row = q / 16, chunk = q % 16)
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+      const int q = t * 64 + lane, row = q >> 4, ch = q & 15;
+      const int m = m0 + wm * 128 + half * 64 + row, n = n0 + wn * 128 + ch * 8;
+      const u32x4 val = *(const u32x4*)(stg + row * EP_LD + ch * 8);
+      if (m < p.M && n < p.N) *(u32x4*)(p.C + (long)m * p.ldc + n) = val;  // N is a multiple of 8 on this path
     }
   }
 }
 
+// partial[z][M][N] -> out (fp32), z summed in fixed order; output column blocks may go to 3 matrices.
+// One thread per 4 consecutive outputs (N and n_per are multiples of 4).
+__global__ void mfma_splitk_reduce_kernel(const float* partial, int split_k, int M, int N, float* o0, float* o1,
+                                          float* o2, int n_per) {
+  const long n_out = (long)M * N;
+  const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i >= n_out) return;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int z = 0; z < split_k; ++z) {
+    const float4 v = *(const float4*)(partial + z * n_out + i);
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  const int m = i / N, n = i % N;
+  if (n_per > 0) {
+    float* o = (n / n_per == 0) ? o0 : (n / n_per == 1) ? o1 : o2;
+    if (o) *(float4*)(o + (long)m * n_per + n % n_per) = s;
+  } else {
+    *(float4*)(o0 + i) = s;
+  }
+}
+
+// The asynchronous large-tile kernel is used for the weight gradients (both operands k-major, long
+// contraction over token rows): measured on MI355X it is 1.5x faster there than the 128 x 128 kernel,
+// while for the short-K (K = d) projections, whose row-major operands contribute only 64 bytes per
+// row and stage, the 128 x 128 kernel with three workgroups per CU is the faster one.
+static bool use_dma(int M, int N, int K, bool akm = true, bool bkm = true) {
+  return akm && bkm && M >= DM && N >= DN && K % DK == 0 && K >= 64 * DK && M % 8 == 0 && N % 8 == 0;
+}
+
 int mfma_gemm_split(int M, int N, int K) {
+  if (use_dma(M, N, K)) {
+    const long tiles = (long)((M + DM - 1) / DM) * ((N + DN - 1) / DN);
+    const int ktiles = K / DK;
+    if (tiles >= 128 || ktiles < 32) return 1;
+    int s = (int)(256 / tiles);
+    if (s > ktiles / 8) s = ktiles / 8;
+    return s < 1 ? 1 : s;
+  }
   const long tiles = (long)((M + GM - 1) / GM) * ((N + GN - 1) / GN);
   const int ktiles = (K + GK - 1) / GK;
   if (tiles >= 256 || ktiles < 16) return 1;
@@ -201,7 +463,26 @@ int mfma_gemm_split(int M, int N, int K) {
   return s < 1 ? 1 : s;
 }
 
+template <bool AKM, bool BKM>
+static void launch_dma(const MGemm& p, hipStream_t st) {
+  static bool configured = false;  // raise the dynamic-LDS limit once per instantiation (128 KB > the 64 KB default)
+  if (!configured) {
+    (void)hipFuncSetAttribute((const void*)mfma_gemm_dma_kernel<AKM, BKM>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              DMA_LDS_BYTES);
+    configured = true;
+  }
+  dim3 grid((p.N + DN - 1) / DN, (p.M + DM - 1) / DM, p.split_k);
+  hipLaunchKernelGGL((mfma_gemm_dma_kernel<AKM, BKM>), grid, dim3(256), DMA_LDS_BYTES, st, p);
+}
+
 void launch_mfma_gemm(const MGemm& p, hipStream_t st) {
+  if (use_dma(p.M, p.N, p.K, p.a_kmajor, p.b_kmajor) && (p.b_kper == 0 || p.b_kper % DK == 0)) {
+    if (p.a_kmajor && p.b_kmajor) launch_dma<true, true>(p, st);
+    else if (p.b_kmajor) launch_dma<false, true>(p, st);
+    else if (p.a_kmajor) launch_dma<true, false>(p, st);
+    else launch_dma<false, false>(p, st);
+    return;
+  }
   dim3 grid((p.N + GN - 1) / GN, (p.M + GM - 1) / GM, p.split_k);
   if (p.a_kmajor && p.b_kmajor) hipLaunchKernelGGL((mfma_gemm_kernel<true, true>), grid, dim3(256), 0, st, p);
   else if (p.b_kmajor) hipLaunchKernelGGL((mfma_gemm_kernel<false, true>), grid, dim3(256), 0, st, p);
@@ -210,7 +491,9 @@ void launch_mfma_gemm(const MGemm& p, hipStream_t st) {
 }
 void launch_splitk_reduce(const float* partial, int split_k, int M, int N, float* o0, float* o1, float* o2, int n_per,
                           hipStream_t st) {
-  hipLaunchKernelGGL(mfma_splitk_reduce_kernel, dim3(256), dim3(256), 0, st, partial, split_k, M, N, o0, o1, o2, n_per);
+  const long quads = ((long)M * N + 3) / 4;
+  hipLaunchKernelGGL(mfma_splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, partial, split_k,
+                     M, N, o0, o1, o2, n_per);
 }
 
 }  // namespace imattn

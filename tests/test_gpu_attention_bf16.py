@@ -37,6 +37,15 @@ def test_mfma_shapes_and_segment_counts(seg, H):
         Problem(g, lm).check(what=f"mfma seg={seg} lm={lm:#x}")
 
 
+def test_mfma_wide_model_weight_gradient_kernel():
+    # d = 320 (5 heads), 2048 token rows: the weight gradients take the asynchronous 256 x 256 GEMM
+    # kernel with ragged row / column tiles (320 = 256 + 64, 960 = 3 * 256 + 192) and split-K
+    say("[case] mfma d=320 R=2048 (large-tile weight-gradient GEMM)")
+    g = synth.attention_inputs(2, (300, 420, 304), 320, 5, "bf16", "valid_len", seed=41, bias=True)
+    errs = Problem(g, oracle.IM_IFM_BACKWARD).check(what="mfma d=320")
+    say("    " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
+
+
 def test_mfma_dead_segments_and_fully_masked_rows():
     say("[case] mfma dead segments / fully masked rows")
     g = synth.attention_inputs(2, (9, 70, 33), 64, 1, "bf16", "none", seed=9, bias=True)
