@@ -14,15 +14,20 @@ namespace imattn {
 
 constexpr int RL_ROWS = 64;    // rows per tile == lanes
 constexpr int RL_CHUNK = 128;  // rows of the other operand staged in LDS at a time
+// Kernels are instantiated for the exact head dimension DH (register arrays and FMA loops have DH
+// entries: at dh = 5 a padded-to-8 loop would waste 3 of every 8 FMAs); LDS rows are padded to a
+// power of two for aligned broadcast reads.
+__host__ __device__ constexpr int lds_row(int dh) { return dh <= 4 ? 4 : dh <= 8 ? 8 : 16; }
 
-template <typename T, int DHP>
+template <typename T, int DH>
 __global__ __launch_bounds__(RL_ROWS) void rowlane_fwd_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K,
                                                               const T* __restrict__ V, long ld,
                                                               const int32_t* __restrict__ valid_len,
                                                               const uint8_t* __restrict__ key_pad, T* __restrict__ O,
                                                               long ldo, float* __restrict__ lse2) {
-  __shared__ float sK[RL_CHUNK][DHP];
-  __shared__ float sV[RL_CHUNK][DHP];
+  constexpr int LP = lds_row(DH);
+  __shared__ float sK[RL_CHUNK][LP];
+  __shared__ float sV[RL_CHUNK][LP];
   __shared__ float sBias[RL_CHUNK];
   const int lane = threadIdx.x, h = blockIdx.y, b = blockIdx.z;
   int qs, q0;
@@ -32,9 +37,9 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_fwd_kernel(Geo g, const T* __
   const long t = (long)b * g.T + g.seg_off[qs] + (active ? row : 0);
   const int dh = g.dh, hc = h * dh;
 
-  float q[DHP], acc[DHP];
+  float q[DH], acc[DH];
 #pragma unroll
-  for (int e = 0; e < DHP; ++e) {
+  for (int e = 0; e < DH; ++e) {
     q[e] = (e < dh) ? ldf(Q + t * ld + hc + e) * g.scale_log2e : 0.f;
     acc[e] = 0.f;
   }
@@ -50,8 +55,8 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_fwd_kernel(Geo g, const T* __
       const int n = min(RL_CHUNK, klen - c0);
       const int n4 = (n + 3) & ~3;
       __syncthreads();
-      for (int i = lane; i < n4 * DHP; i += RL_ROWS) {
-        const int c = i / DHP, e = i % DHP;
+      for (int i = lane; i < n4 * LP; i += RL_ROWS) {
+        const int c = i / LP, e = i % LP;
         const bool ok = (c < n) && (e < dh);
         const long a = (kbase + c0 + c) * ld + hc + e;
         sK[c][e] = ok ? ldf(K + a) : 0.f;
@@ -69,21 +74,21 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_fwd_kernel(Geo g, const T* __
         for (int u = 0; u < 4; ++u) {
           float a = sBias[c + u];
 #pragma unroll
-          for (int e = 0; e < DHP; ++e) a = fmaf(q[e], sK[c + u][e], a);
+          for (int e = 0; e < DH; ++e) a = fmaf(q[e], sK[c + u][e], a);
           s[u] = a;
         }
         const float mn = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), m);
         const float ms = (mn == IM_NEG_INF) ? 0.f : mn;
-        const float alpha = exp2f(m - ms);
+        const float alpha = __builtin_amdgcn_exp2f(m - ms);
         l *= alpha;
 #pragma unroll
-        for (int e = 0; e < DHP; ++e) acc[e] *= alpha;
+        for (int e = 0; e < DH; ++e) acc[e] *= alpha;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const float p = exp2f(s[u] - ms);
+          const float p = __builtin_amdgcn_exp2f(s[u] - ms);
           l += p;
 #pragma unroll
-          for (int e = 0; e < DHP; ++e) acc[e] = fmaf(p, sV[c + u][e], acc[e]);
+          for (int e = 0; e < DH; ++e) acc[e] = fmaf(p, sV[c + u][e], acc[e]);
         }
         m = mn;
       }
@@ -92,14 +97,14 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_fwd_kernel(Geo g, const T* __
   if (active) {
     const float inv = (l > 0.f) ? 1.f / l : 0.f;
 #pragma unroll
-    for (int e = 0; e < DHP; ++e)
+    for (int e = 0; e < DH; ++e)
       if (e < dh) stf(O + t * ldo + hc + e, acc[e] * inv);
     if (lse2) lse2[((long)b * g.H + h) * g.T + g.seg_off[qs] + row] = (l > 0.f) ? m + log2f(l) : IM_NEG_INF;
   }
 }
 
 // dQ (and delta = rowsum(dO * O)) : one query row per lane, keys broadcast from LDS.
-template <typename T, int DHP>
+template <typename T, int DH>
 __global__ __launch_bounds__(RL_ROWS) void rowlane_dq_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K,
                                                              const T* __restrict__ V, long ld, const T* __restrict__ O,
                                                              const T* __restrict__ dO, long ldo,
@@ -107,8 +112,9 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dq_kernel(Geo g, const T* __r
                                                              const int32_t* __restrict__ valid_len,
                                                              const uint8_t* __restrict__ key_pad,
                                                              float* __restrict__ delta, T* __restrict__ dQ, long ldg) {
-  __shared__ float sK[RL_CHUNK][DHP];
-  __shared__ float sV[RL_CHUNK][DHP];
+  constexpr int LP = lds_row(DH);
+  __shared__ float sK[RL_CHUNK][LP];
+  __shared__ float sV[RL_CHUNK][LP];
   __shared__ float sBias[RL_CHUNK];
   const int lane = threadIdx.x, h = blockIdx.y, b = blockIdx.z;
   int qs, q0;
@@ -119,10 +125,10 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dq_kernel(Geo g, const T* __r
   const int dh = g.dh, hc = h * dh;
   const long li = ((long)b * g.H + h) * g.T + g.seg_off[qs] + (active ? row : 0);
 
-  float q[DHP], go[DHP], acc[DHP];
+  float q[DH], go[DH], acc[DH];
   float dl = 0.f;
 #pragma unroll
-  for (int e = 0; e < DHP; ++e) {
+  for (int e = 0; e < DH; ++e) {
     q[e] = (e < dh) ? ldf(Q + t * ld + hc + e) * g.scale_log2e : 0.f;
     go[e] = (e < dh) ? ldf(dO + t * ldo + hc + e) : 0.f;
     const float oo = (e < dh) ? ldf(O + t * ldo + hc + e) : 0.f;
@@ -142,8 +148,8 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dq_kernel(Geo g, const T* __r
     for (int c0 = 0; c0 < klen; c0 += RL_CHUNK) {
       const int n = min(RL_CHUNK, klen - c0);
       __syncthreads();
-      for (int i = lane; i < n * DHP; i += RL_ROWS) {
-        const int c = i / DHP, e = i % DHP;
+      for (int i = lane; i < n * LP; i += RL_ROWS) {
+        const int c = i / LP, e = i % LP;
         const long a = (kbase + c0 + c) * ld + hc + e;
         sK[c][e] = (e < dh) ? ldf(K + a) : 0.f;
         sV[c][e] = (e < dh) ? ldf(V + a) : 0.f;
@@ -157,27 +163,27 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dq_kernel(Geo g, const T* __r
       for (int c = 0; c < n; ++c) {
         float s = sBias[c], dp = 0.f;
 #pragma unroll
-        for (int e = 0; e < DHP; ++e) {
+        for (int e = 0; e < DH; ++e) {
           s = fmaf(q[e], sK[c][e], s);
           dp = fmaf(go[e], sV[c][e], dp);
         }
-        const float p = exp2f(s - ls);
+        const float p = __builtin_amdgcn_exp2f(s - ls);
         const float ds = p * (dp - dl);
 #pragma unroll
-        for (int e = 0; e < DHP; ++e) acc[e] = fmaf(ds, sK[c][e], acc[e]);
+        for (int e = 0; e < DH; ++e) acc[e] = fmaf(ds, sK[c][e], acc[e]);
       }
     }
   }
   if (active) {
 #pragma unroll
-    for (int e = 0; e < DHP; ++e)
+    for (int e = 0; e < DH; ++e)
       if (e < dh) stf(dQ + t * ldg + hc + e, acc[e] * g.scale);
   }
 }
 
 // dK, dV : one key row per lane, query rows (Q, dO, lse, delta) broadcast from LDS.
 // Each key segment has a single producer workgroup per tile, so no atomics.
-template <typename T, int DHP>
+template <typename T, int DH>
 __global__ __launch_bounds__(RL_ROWS) void rowlane_dkv_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K,
                                                               const T* __restrict__ V, long ld,
                                                               const T* __restrict__ dO, long ldo,
@@ -186,8 +192,9 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dkv_kernel(Geo g, const T* __
                                                               const int32_t* __restrict__ valid_len,
                                                               const uint8_t* __restrict__ key_pad, T* __restrict__ dK,
                                                               T* __restrict__ dV, long ldg) {
-  __shared__ float sQ[RL_CHUNK][DHP];
-  __shared__ float sG[RL_CHUNK][DHP];
+  constexpr int LP = lds_row(DH);
+  __shared__ float sQ[RL_CHUNK][LP];
+  __shared__ float sG[RL_CHUNK][LP];
   __shared__ float sL[RL_CHUNK];
   __shared__ float sD[RL_CHUNK];
   const int lane = threadIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -201,9 +208,9 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dkv_kernel(Geo g, const T* __
   if (valid && key_pad) valid = key_pad[t] == 0;
   const int dh = g.dh, hc = h * dh;
 
-  float k[DHP], v[DHP], ak[DHP], av[DHP];
+  float k[DH], v[DH], ak[DH], av[DH];
 #pragma unroll
-  for (int e = 0; e < DHP; ++e) {
+  for (int e = 0; e < DH; ++e) {
     k[e] = (e < dh) ? ldf(K + t * ld + hc + e) : 0.f;
     v[e] = (e < dh) ? ldf(V + t * ld + hc + e) : 0.f;
     ak[e] = 0.f;
@@ -218,8 +225,8 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dkv_kernel(Geo g, const T* __
     for (int r0 = 0; r0 < qlen; r0 += RL_CHUNK) {
       const int n = min(RL_CHUNK, qlen - r0);
       __syncthreads();
-      for (int x = lane; x < n * DHP; x += RL_ROWS) {
-        const int r = x / DHP, e = x % DHP;
+      for (int x = lane; x < n * LP; x += RL_ROWS) {
+        const int r = x / LP, e = x % LP;
         sQ[r][e] = (e < dh) ? ldf(Q + (qbase + r0 + r) * ld + hc + e) * g.scale_log2e : 0.f;
         sG[r][e] = (e < dh) ? ldf(dO + (qbase + r0 + r) * ldo + hc + e) : 0.f;
       }
@@ -232,14 +239,14 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dkv_kernel(Geo g, const T* __
       for (int r = 0; r < n; ++r) {
         float s = 0.f, dp = 0.f;
 #pragma unroll
-        for (int e = 0; e < DHP; ++e) {
+        for (int e = 0; e < DH; ++e) {
           s = fmaf(sQ[r][e], k[e], s);
           dp = fmaf(sG[r][e], v[e], dp);
         }
-        const float p = exp2f(s - sL[r]);
+        const float p = __builtin_amdgcn_exp2f(s - sL[r]);
         const float ds = p * (dp - sD[r]);
 #pragma unroll
-        for (int e = 0; e < DHP; ++e) {
+        for (int e = 0; e < DH; ++e) {
           av[e] = fmaf(p, sG[r][e], av[e]);
           ak[e] = fmaf(ds, sQ[r][e], ak[e]);
         }
@@ -250,7 +257,7 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dkv_kernel(Geo g, const T* __
     // sQ holds q * scale * log2(e); dK = scale * dS^T q  ==  ln(2) * dS^T (q * scale * log2 e)
     const float ln2 = 0.69314718055994530942f;
 #pragma unroll
-    for (int e = 0; e < DHP; ++e)
+    for (int e = 0; e < DH; ++e)
       if (e < dh) {
         stf(dK + t * ldg + hc + e, valid ? ak[e] * ln2 : 0.f);
         stf(dV + t * ldg + hc + e, valid ? av[e] : 0.f);
@@ -272,16 +279,26 @@ __global__ void zero_rows_kernel(T* p, long ld, int B, int T_m, int row0, int nr
 
 bool rowlane_supports(int dh) { return dh >= 1 && dh <= 16; }
 
+// smallest instantiated head dimension >= dh
+#define RL_DISPATCH(dh, LAUNCH) \
+  do {                          \
+    if ((dh) <= 4) LAUNCH(4);   \
+    else if ((dh) == 5) LAUNCH(5); \
+    else if ((dh) == 6) LAUNCH(6); \
+    else if ((dh) <= 8) LAUNCH(8); \
+    else if ((dh) <= 12) LAUNCH(12); \
+    else LAUNCH(16);            \
+  } while (0)
+
 template <typename T>
 static int fwd_dispatch(const Geo& g, const T* q, const T* k, const T* v, long ld, const int32_t* vl, const uint8_t* kp,
                         T* o, long ldo, float* lse2, hipStream_t st) {
   const int ntiles = g.q_tile_prefix[g.q_nord];
   if (ntiles == 0) return IM_OK;
   dim3 grid(ntiles, g.H, g.B), block(RL_ROWS);
-  if (g.dh <= 8)
-    hipLaunchKernelGGL((rowlane_fwd_kernel<T, 8>), grid, block, 0, st, g, q, k, v, ld, vl, kp, o, ldo, lse2);
-  else
-    hipLaunchKernelGGL((rowlane_fwd_kernel<T, 16>), grid, block, 0, st, g, q, k, v, ld, vl, kp, o, ldo, lse2);
+#define RL_FWD(DHV) hipLaunchKernelGGL((rowlane_fwd_kernel<T, DHV>), grid, block, 0, st, g, q, k, v, ld, vl, kp, o, ldo, lse2)
+  RL_DISPATCH(g.dh, RL_FWD);
+#undef RL_FWD
   return IM_OK;
 }
 
@@ -330,21 +347,12 @@ static int bwd_dispatch(const Geo& g, const T* q, const T* k, const T* v, long l
   const int nq = g.q_tile_prefix[g.q_nord], nk = g.k_tile_prefix[g.k_nord];
   if (nq == 0) return IM_OK;
   dim3 block(RL_ROWS);
-  if (g.dh <= 8) {
-    { ProfScope ps(PF_ATTN_DQ, st);
-      hipLaunchKernelGGL((rowlane_dq_kernel<T, 8>), dim3(nq, g.H, g.B), block, 0, st, g, q, k, v, ld, o, d_o, ldo, lse2,
-                         vl, kp, delta, dq, ldg); }
-    { ProfScope ps(PF_ATTN_DKV, st);
-      hipLaunchKernelGGL((rowlane_dkv_kernel<T, 8>), dim3(nk, g.H, g.B), block, 0, st, g, q, k, v, ld, d_o, ldo, lse2,
-                         delta, vl, kp, dk, dv, ldg); }
-  } else {
-    { ProfScope ps(PF_ATTN_DQ, st);
-      hipLaunchKernelGGL((rowlane_dq_kernel<T, 16>), dim3(nq, g.H, g.B), block, 0, st, g, q, k, v, ld, o, d_o, ldo, lse2,
-                         vl, kp, delta, dq, ldg); }
-    { ProfScope ps(PF_ATTN_DKV, st);
-      hipLaunchKernelGGL((rowlane_dkv_kernel<T, 16>), dim3(nk, g.H, g.B), block, 0, st, g, q, k, v, ld, d_o, ldo, lse2,
-                         delta, vl, kp, dk, dv, ldg); }
-  }
+#define RL_DQ(DHV) hipLaunchKernelGGL((rowlane_dq_kernel<T, DHV>), dim3(nq, g.H, g.B), block, 0, st, g, q, k, v, ld, o, d_o, ldo, lse2, vl, kp, delta, dq, ldg)
+#define RL_DKV(DHV) hipLaunchKernelGGL((rowlane_dkv_kernel<T, DHV>), dim3(nk, g.H, g.B), block, 0, st, g, q, k, v, ld, d_o, ldo, lse2, delta, vl, kp, dk, dv, ldg)
+  { ProfScope ps(PF_ATTN_DQ, st); RL_DISPATCH(g.dh, RL_DQ); }
+  { ProfScope ps(PF_ATTN_DKV, st); RL_DISPATCH(g.dh, RL_DKV); }
+#undef RL_DQ
+#undef RL_DKV
   return IM_OK;
 }
 

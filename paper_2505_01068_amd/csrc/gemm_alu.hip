@@ -126,12 +126,21 @@ __global__ __launch_bounds__(GA_THREADS) void gemm_alu_kernel(GemmDev g) {
   }
 }
 
-// Sum split-K partials in a fixed order and write fp32 outputs (weight gradients).
-__global__ void gemm_splitk_reduce_kernel(GemmDev g) {
+// Sum split-K partials in a fixed order and write fp32 outputs (weight gradients).  A block of 256
+// threads owns 64 consecutive outputs; thread (zz, o) sums partials z = zz, zz+4, ... and the four
+// sub-sums are added in a fixed order, so the result does not depend on scheduling.
+__global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmDev g) {
+  __shared__ float part[4][64];
   const long n_out = (long)g.M * g.N;
-  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n_out; i += (long)gridDim.x * blockDim.x) {
-    float s = 0.f;
-    for (int z = 0; z < g.split_k; ++z) s += g.partial[z * n_out + i];
+  const int o = threadIdx.x & 63, zz = threadIdx.x >> 6;
+  const long i = (long)blockIdx.x * 64 + o;
+  float s = 0.f;
+  if (i < n_out)
+    for (int z = zz; z < g.split_k; z += 4) s += g.partial[z * n_out + i];
+  part[zz][o] = s;
+  __syncthreads();
+  if (zz == 0 && i < n_out) {
+    s = (part[0][o] + part[1][o]) + (part[2][o] + part[3][o]);
     const int gm = i / g.N, gn = i % g.N;
     int sel = 0, nn = gn;
     if (g.n_per > 0) { sel = gn / g.n_per; nn = gn % g.n_per; }
@@ -148,6 +157,7 @@ size_t gemm_alu_partial_bytes(int M, int N, int K, int* split_k) {
     s = (int)((512 + tiles - 1) / tiles);
     const int ktiles = (K + GA_BK - 1) / GA_BK;
     if (s > ktiles / 8) s = ktiles / 8;
+    if (s > 128) s = 128;
     if (s < 1) s = 1;
   }
   if (split_k) *split_k = s;
@@ -172,7 +182,8 @@ int launch_gemm_alu(const GemmDesc& d, int a_bf16, int b_bf16, int c_bf16, hipSt
     case 6: hipLaunchKernelGGL((gemm_alu_kernel<bf16_t, bf16_t, float>), grid, block, 0, st, g); break;
     default: set_error("gemm_alu: unsupported operand type combination %d", key); return IM_ERR_UNSUPPORTED;
   }
-  if (g.split_k > 1) hipLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3(64), dim3(256), 0, st, g);
+  if (g.split_k > 1)
+    hipLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3((unsigned)(((long)g.M * g.N + 63) / 64)), dim3(256), 0, st, g);
   return IM_OK;
 }
 
