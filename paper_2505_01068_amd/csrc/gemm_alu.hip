@@ -50,7 +50,10 @@ __global__ __launch_bounds__(GA_THREADS) void gemm_alu_kernel(GemmDev g) {
 
   const bool a_kfast = (g.sak == 1);
   const bool b_nfast = (g.sbn == 1);
-  for (int kt = kt_begin; kt < kt_end; ++kt) {
+  // The next k-tile is fetched into registers while the current one is multiplied (the global round
+  // trip would otherwise be exposed once per 16-deep tile).
+  float ra[4], rb[4];
+  auto fetch = [&](int kt) {
     const int kbase = kt * GA_BK;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -65,7 +68,7 @@ __global__ __launch_bounds__(GA_THREADS) void gemm_alu_kernel(GemmDev g) {
         else off = (long)gk * g.sak;
         v = ldf(A + (long)gm * g.sam + off);
       }
-      As[k][m] = v;
+      ra[u] = v;
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -82,9 +85,20 @@ __global__ __launch_bounds__(GA_THREADS) void gemm_alu_kernel(GemmDev g) {
         if (g.kb > 1) { const int bb = gk / g.kt; kk = gk % g.kt; boff = bb * g.sbb; }
         v = ldf((const TB*)g.B[sel] + boff + (long)kk * g.sbk + (long)nn * g.sbn);
       }
-      Bs[k][n] = v;
+      rb[u] = v;
+    }
+  };
+  if (kt_begin < kt_end) fetch(kt_begin);
+  for (int kt = kt_begin; kt < kt_end; ++kt) {
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int idx = tid + u * GA_THREADS;
+      if (a_kfast) As[idx % GA_BK][idx / GA_BK] = ra[u]; else As[idx / GA_BM][idx % GA_BM] = ra[u];
+      if (b_nfast) Bs[idx / GA_BN][idx % GA_BN] = rb[u]; else Bs[idx % GA_BK][idx / GA_BK] = rb[u];
     }
     __syncthreads();
+    if (kt + 1 < kt_end) fetch(kt + 1);
 #pragma unroll
     for (int k = 0; k < GA_BK; ++k) {
       const float4 a = *(const float4*)&As[k][ty * 4];
@@ -95,7 +109,6 @@ __global__ __launch_bounds__(GA_THREADS) void gemm_alu_kernel(GemmDev g) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
     }
-    __syncthreads();
   }
 
 #pragma unroll
