@@ -51,6 +51,22 @@ def live_pairs(seg_len, live_mask, batch, valid_len, key_pad):
     return total
 
 
+def stored_traffic(config, family):
+    """HBM bytes per launch of the dominant kernel from the committed counter summary
+    (profiles/<config>_<family>_traffic.md), or None if there is none or the kernel source changed since."""
+    import hashlib
+    import re
+    path = os.path.join(ROOT, "profiles", f"{config}_{family}_traffic.md")
+    try:
+        m = re.search(r"^TRAFFIC_JSON (.*)$", open(path).read(), flags=re.M)
+        rec = json.loads(m.group(1))
+        src = "mfma_attn.hip" if "mfma" in rec["kernel"] else "attn_rowlane.hip"
+        cur = hashlib.sha256(open(os.path.join(ROOT, "paper_2505_01068_amd", "csrc", src), "rb").read()).hexdigest()
+        return rec["bytes_per_launch"] if cur == rec["source_sha256"] else None
+    except Exception:
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,6 +75,8 @@ def main():
     ap.add_argument("--config", default="c5", choices=["c2", "c3", "c5"])
     ap.add_argument("--mask", default="ifm_forward", choices=["ifm_forward", "ifm_backward", "iem"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run one 1 GiB device copy first (reference reading for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -102,6 +120,12 @@ def main():
         B.im_attention_fwd(shape, x, wq, wk, wv, wo, valid_len=vl, key_pad=kp, y=y, saved=saved, workspace=ws)
         B.im_attention_bwd(shape, x, wq, wk, wv, wo, saved, dy, dx, *dws, valid_len=vl, key_pad=kp, workspace=ws)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -130,17 +154,18 @@ def main():
     attn_keys = [k for k in ("attn_fwd", "attn_dq", "attn_dkv") if k in per_step]
     dom = max(attn_keys, key=lambda k: per_step[k])
     dom_ms = per_step[dom]
+    traffic = stored_traffic(args.config, dom)
     mfma_bound = dtype == "bf16" and d // H == 64
     if mfma_bound:
         achieved = alg[dom] / (dom_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": PEAK_MFMA_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_BF16_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_BF16_TFLOPS, 4), "traffic": traffic,
                 "avg_launch_ms": round(dom_ms, 4)}
     else:
         # small head dims: plain fp32 ALU work (FMAs of the two/five products; exp and softmax bookkeeping not counted)
         achieved = alg[dom] / (dom_ms * 1e-3) / 1e12
         roof = {"bound": "alu", "kernel": dom, "achieved": round(achieved, 3), "peak": PEAK_FP32_VALU_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_VALU_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_VALU_TFLOPS, 4), "traffic": traffic,
                 "avg_launch_ms": round(dom_ms, 4)}
 
     out = {
