@@ -86,7 +86,13 @@ static int validate_shape(const im_shape_t* s) {
 enum Path { PATH_ROWLANE, PATH_MFMA, PATH_NONE };
 static Path pick_path(const im_shape_t* s) {
   const int dh = s->d_model / s->n_heads;
-  if (s->dtype == IM_DTYPE_BF16 && mfma_supports(s->d_model, dh)) return PATH_MFMA;
+  if (s->dtype == IM_DTYPE_BF16 && mfma_supports(s->d_model, dh)) {
+    // the dK/dV kernel addresses one segment of one batch element with 32-bit byte offsets
+    long max_seg = 0;
+    for (int i = 0; i < s->n_seg; ++i) max_seg = s->seg_len[i] > max_seg ? s->seg_len[i] : max_seg;
+    if (max_seg * 3L * s->d_model * 2L < (1L << 31) && 3L * s->d_model * 2L < (1L << 24)) return PATH_MFMA;
+    return PATH_NONE;
+  }
   if (rowlane_supports(dh)) return PATH_ROWLANE;
   return PATH_NONE;
 }
@@ -94,7 +100,7 @@ static int check_supported(const im_shape_t* s) {
   if (pick_path(s) == PATH_NONE)
     return fail(IM_ERR_UNSUPPORTED,
                 "no kernel for dtype %d with head dimension %d (supported: head dim <= 16 for fp32/bf16; bf16 with "
-                "head dim 64 and d_model %% 64 == 0)",
+                "head dim 64, d_model %% 64 == 0 and segment length * d_model < 2^28)",
                 s->dtype, s->d_model / s->n_heads);
   return IM_OK;
 }

@@ -38,8 +38,8 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
                                                        const int32_t* __restrict__ valid_len,
                                                        const uint8_t* __restrict__ key_pad, bf16_t* __restrict__ O,
                                                        long ldo, float* __restrict__ lse2) {
-  __shared__ __attribute__((aligned(16))) bf16_t sK[KT * LDS_LD];
-  __shared__ __attribute__((aligned(16))) bf16_t sV[KT * LDS_LD];
+  __shared__ __attribute__((aligned(16))) bf16_t sK[KT * SW_LD];
+  __shared__ __attribute__((aligned(16))) bf16_t sV[KT * SW_LD];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   int tile, h, b;
   xcd_block_index(tile, h, b);
@@ -91,8 +91,8 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
     }
     for (int k0 = 0; k0 < klen; k0 += KT) {
       __syncthreads();
-      store_tile(tk, sK, tid);
-      store_tile(tv, sV, tid);
+      store_tile_sw(tk, sK, tid);
+      store_tile_sw(tv, sV, tid);
       __syncthreads();
       if (k0 + KT < klen) {
         load_rows_tile(tk, Kbase, ld, k0 + KT, g.seg_len[j] - 1, tid);
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
           for (int r = 0; r < 16; ++r) sacc[kb][qb][r] = 0.f;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const bf16x8 a = lds_frag(sK, kb * 32 + prow, s * 16 + hi * 8);
+          const bf16x8 a = lds_frag_sw(sK, kb * 32, prow, 2 * s + hi);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) sacc[kb][qb] = mfma32(a, qreg[qb][s], sacc[kb][qb]);
         }
@@ -171,7 +171,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
       for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const bf16x8 a = lds_frag_tr(sV, LDS_LD, s * 16, db * 32, lane);
+          const bf16x8 a = lds_frag_tr_sw(sV, s * 16, db * 32, lane);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) oacc[db][qb] = mfma32(a, pb[s >> 1][qb][s & 1], oacc[db][qb]);
         }
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
     const int row = qrow[qb];
     if (row >= qlen) continue;
     const long t = (long)b * g.T + g.seg_off[qs] + row;
-    if (hi == 0 && lse2) lse2[((long)b * g.H + h) * g.T + g.seg_off[qs] + row] = lt > 0.f ? fmaf(m[qb], c, log2f(lt)) : IM_NEG_INF;
+    if (hi == 0 && lse2) lse2[((long)b * g.H + h) * g.T + g.seg_off[qs] + row] = lt > 0.f ? fmaf(m[qb], c, log2f(lt)) : __builtin_inff();
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -211,8 +211,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
                                                       const int32_t* __restrict__ valid_len,
                                                       const uint8_t* __restrict__ key_pad, float* __restrict__ delta,
                                                       bf16_t* __restrict__ dQKV, long ldg) {
-  __shared__ __attribute__((aligned(16))) bf16_t sK[KT * LDS_LD];
-  __shared__ __attribute__((aligned(16))) bf16_t sV[KT * LDS_LD];
+  __shared__ __attribute__((aligned(16))) bf16_t sK[KT * SW_LD];
+  __shared__ __attribute__((aligned(16))) bf16_t sV[KT * SW_LD];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   int tile, h, b;
   xcd_block_index(tile, h, b);
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
     dl[qb] = acc;
     const long li = ((long)b * g.H + h) * g.T + g.seg_off[qs] + rc;
     const float lv = lse2[li];
-    ls[qb] = (lv == IM_NEG_INF) ? __builtin_inff() : lv;
+    ls[qb] = lv;  // +inf for a row without valid keys: every probability is exactly zero
     if (hi == 0 && qrow[qb] < qlen) delta[li] = acc;
   }
 
@@ -278,8 +278,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
     }
     for (int k0 = 0; k0 < klen; k0 += KT) {
       __syncthreads();
-      store_tile(tk, sK, tid);
-      store_tile(tv, sV, tid);
+      store_tile_sw(tk, sK, tid);
+      store_tile_sw(tv, sV, tid);
       __syncthreads();
       if (k0 + KT < klen) {
         load_rows_tile(tk, Kbase, ld, k0 + KT, g.seg_len[j] - 1, tid);
@@ -298,8 +298,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
           for (int r = 0; r < 16; ++r) { sacc[qb][r] = 0.f; pacc[qb][r] = 0.f; }
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const bf16x8 ak = lds_frag(sK, kb * 32 + prow, s * 16 + hi * 8);
-          const bf16x8 av = lds_frag(sV, kb * 32 + prow, s * 16 + hi * 8);
+          const bf16x8 ak = lds_frag_sw(sK, kb * 32, prow, 2 * s + hi);
+          const bf16x8 av = lds_frag_sw(sV, kb * 32, prow, 2 * s + hi);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) {
             sacc[qb] = mfma32(ak, qreg[qb][s], sacc[qb]);   // S^T  = K Q^T
@@ -330,7 +330,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
       for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const bf16x8 a = lds_frag_tr(sK, LDS_LD, s * 16, db * 32, lane);
+          const bf16x8 a = lds_frag_tr_sw(sK, s * 16, db * 32, lane);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) dqacc[db][qb] = mfma32(a, dsb[s >> 1][qb][s & 1], dqacc[db][qb]);
         }
@@ -360,6 +360,16 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
 // dK, dV.  Each wave owns KB blocks of 32 key rows (lane <-> key row) and streams
 // the query rows of every query segment that reads this key segment.  A key tile
 // has exactly one producer, so the result is deterministic without atomics.
+//
+// The streamed operands (64 query rows of Q and dO, their lse and delta) go from global memory
+// straight into a ring of DKV_NST LDS stages with global_load_lds (no staging registers, no LDS
+// store instructions): stage t+2 is requested while stage t is consumed, one workgroup barrier
+// per stage.  Each lane fetches the 16-byte chunk that belongs at ITS position of the swizzled
+// tile (see sw_f), so the asynchronous copy produces the conflict-free layout directly.
+constexpr int DKV_NST = 3;
+constexpr int DKV_STAGE = 2 * KT * SW_LD;  // bf16 elements per stage: Q tile, then dO tile
+__device__ const float k_pos_inf = __builtin_inff();
+
 template <int KB>
 __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
                                                        const bf16_t* __restrict__ dO, long ldo,
@@ -367,10 +377,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
                                                        const int32_t* __restrict__ valid_len,
                                                        const uint8_t* __restrict__ key_pad, bf16_t* __restrict__ dQKV,
                                                        long ldg) {
-  __shared__ __attribute__((aligned(16))) bf16_t sQ[KT * LDS_LD];
-  __shared__ __attribute__((aligned(16))) bf16_t sG[KT * LDS_LD];
-  __shared__ __attribute__((aligned(16))) float sL[KT];
-  __shared__ __attribute__((aligned(16))) float sD[KT];
+  __shared__ __attribute__((aligned(1024))) bf16_t sT[DKV_NST * DKV_STAGE];
+  __shared__ __attribute__((aligned(256))) float sLD[DKV_NST * 2 * KT];  // per stage: lse[64], delta[64]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   int tile, h, b;
   xcd_block_index(tile, h, b);
@@ -380,6 +388,48 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
   const int klen_seg = g.seg_len[ks];
   const int d = g.d;
   const float c = fmaxf(g.scale_log2e, 1e-30f);  // > 0 so that -inf * c stays -inf when scale == 0
+  const unsigned live = g.k_live[ks];
+
+  // Query tiles of all live query segments form one sequence 0..nt-1 so the ring never drains
+  // between segments.  (iseg, ir0, islot) describe the tile the next issue() requests.
+  int nt = 0;
+#pragma unroll
+  for (int i = 0; i < IM_MAX_SEG; ++i)
+    if (i < g.n_seg && ((live >> i) & 1u)) nt += (g.seg_len[i] + KT - 1) / KT;
+  int iseg = __builtin_ctz(live | (1u << IM_MAX_SEG)), ir0 = 0, islot = 0;
+  // tile rows / logical chunks whose 16-byte chunk positions this lane fills (two per tile)
+  const int trow0 = wave * 8 + (lane >> 3), trow1 = trow0 + 32;
+  const unsigned col0 = (unsigned)(h * 64 + (((lane & 7) ^ sw_f(trow0)) << 3)) * 2u;
+  const unsigned col1 = (unsigned)(h * 64 + (((lane & 7) ^ sw_f(trow1)) << 3)) * 2u;
+  const unsigned ldb = (unsigned)ld * 2u, ldob = (unsigned)ldo * 2u;  // row pitches in bytes (< 2^24, host-checked)
+
+  auto issue = [&]() {
+    const int qlen = g.seg_len[iseg];
+    const long row0 = (long)b * g.T + g.seg_off[iseg];
+    const bf16_t* qb_ = QKV + row0 * ld;   // wave-uniform bases; per-lane byte offsets stay below 2^32 (host-checked)
+    const bf16_t* gb_ = dO + row0 * ldo;
+    bf16_t* lq = sT + islot * DKV_STAGE;
+    const unsigned r0c = (unsigned)min(ir0 + trow0, qlen - 1), r1c = (unsigned)min(ir0 + trow1, qlen - 1);
+    dma16_off(qb_, __umul24(r0c, ldb) + col0, lq + wave * 512);
+    dma16_off(gb_, __umul24(r0c, ldob) + col0, lq + KT * SW_LD + wave * 512);
+    dma16_off(qb_, __umul24(r1c, ldb) + col1, lq + (4 + wave) * 512);
+    dma16_off(gb_, __umul24(r1c, ldob) + col1, lq + KT * SW_LD + (4 + wave) * 512);
+    // lse (wave 0) and delta (wave 1), one float per lane.  Rows past the segment read +inf as
+    // lse, so their probabilities are exactly zero.
+    if (wave < 2) {
+      const int r = ir0 + lane;
+      const long lb = ((long)b * g.H + h) * g.T + g.seg_off[iseg];
+      const float* src = (wave == 0) ? (r < qlen ? lse2 + lb + r : &k_pos_inf) : delta + lb + min(r, qlen - 1);
+      dma4(src, sLD + islot * 2 * KT + wave * KT);
+    }
+    islot = (islot + 1 == DKV_NST) ? 0 : islot + 1;
+    ir0 += KT;
+    if (ir0 >= qlen) {  // next live query segment (none left: the value is never used)
+      ir0 = 0;
+      iseg = __builtin_ctz((live >> (iseg + 1)) | (1u << IM_MAX_SEG)) + iseg + 1;
+      iseg = min(iseg, g.n_seg - 1);
+    }
+  };
 
   bf16x8 kreg[KB][4], vreg[KB][4];
   int krow[KB];
@@ -409,88 +459,88 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
 #pragma unroll
       for (int r = 0; r < 16; ++r) { dkacc[db][kb][r] = 0.f; dvacc[db][kb][r] = 0.f; }
 
+  // The compiler does not see the asynchronous copies in its vmcnt bookkeeping.  Consuming the
+  // K / V registers here makes it wait for their (ordinary) loads now, before the ring starts,
+  // instead of draining the ring with a vmcnt(0) at their first use inside the loop.
+#pragma unroll
+  for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+    for (int s = 0; s < 4; ++s) asm volatile("" :: "v"(kreg[kb][s]), "v"(vreg[kb][s]));
+
+  if (nt > 0) issue();
+  if (nt > 1) issue();
+
   const int prow = perm32(lo);
-  const unsigned live = g.k_live[ks];
-  for (int i = 0; i < g.n_seg; ++i) {
-    if (!((live >> i) & 1u)) continue;
-    const int qlen = g.seg_len[i];
-    const bf16_t* Qbase = QKV + ((long)b * g.T + g.seg_off[i]) * ld + h * 64;
-    const bf16_t* Gbase = dO + ((long)b * g.T + g.seg_off[i]) * ldo + h * 64;
-    const long lbase = ((long)b * g.H + h) * g.T + g.seg_off[i];
-    TileRegs tq, tg;
-    float rl = 0.f, rd = 0.f;
-    auto prefetch = [&](int r0) {
-      load_rows_tile(tq, Qbase, ld, r0, qlen - 1, tid);
-      load_rows_tile(tg, Gbase, ldo, r0, qlen - 1, tid);
-      if (tid < KT) {
-        const int r = r0 + tid;
-        const float lv = (r < qlen) ? lse2[lbase + r] : IM_NEG_INF;
-        rl = (lv == IM_NEG_INF) ? __builtin_inff() : lv;  // rows past the segment / without keys: p = 0
-        rd = (r < qlen) ? delta[lbase + r] : 0.f;
+  int cslot = 0;
+  for (int t = 0; t < nt; ++t) {
+    // Loads complete in issue order.  Stage t is complete once at most the loads of stage t+1
+    // (4 tile chunks, plus 1 for the waves that fetch lse / delta) are outstanding.
+    if (t + 1 < nt) {
+      if (wave < 2) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __builtin_amdgcn_s_barrier();  // stage t visible to all waves; everyone is done with stage t-1
+    if (t + 2 < nt) issue();  // refills the slot of stage t-1
+    const bf16_t* sQ = sT + cslot * DKV_STAGE;
+    const bf16_t* sG = sQ + KT * SW_LD;
+    const float* sL = sLD + cslot * 2 * KT;
+    const float* sD = sL + KT;
+    cslot = (cslot + 1 == DKV_NST) ? 0 : cslot + 1;
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      // per-register lse / delta of the query rows this lane half holds
+      float L[16], D[16];
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const float4 l0 = *(const float4*)&sL[qb * 32 + half * 16 + hi * 8], l1 = *(const float4*)&sL[qb * 32 + half * 16 + hi * 8 + 4];
+        const float4 d0 = *(const float4*)&sD[qb * 32 + half * 16 + hi * 8], d1 = *(const float4*)&sD[qb * 32 + half * 16 + hi * 8 + 4];
+        L[half * 8 + 0] = l0.x; L[half * 8 + 1] = l0.y; L[half * 8 + 2] = l0.z; L[half * 8 + 3] = l0.w;
+        L[half * 8 + 4] = l1.x; L[half * 8 + 5] = l1.y; L[half * 8 + 6] = l1.z; L[half * 8 + 7] = l1.w;
+        D[half * 8 + 0] = d0.x; D[half * 8 + 1] = d0.y; D[half * 8 + 2] = d0.z; D[half * 8 + 3] = d0.w;
+        D[half * 8 + 4] = d1.x; D[half * 8 + 5] = d1.y; D[half * 8 + 6] = d1.z; D[half * 8 + 7] = d1.w;
       }
-    };
-    prefetch(0);
-    for (int r0 = 0; r0 < qlen; r0 += KT) {
-      __syncthreads();
-      store_tile(tq, sQ, tid);
-      store_tile(tg, sG, tid);
-      if (tid < KT) { sL[tid] = rl; sD[tid] = rd; }
-      __syncthreads();
-      if (r0 + KT < qlen) prefetch(r0 + KT);
+      bf16x8 pb[KB][2], dsb[KB][2];
+      f32x16 sacc[KB], pacc[KB];
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        // per-register lse / delta of the query rows this lane half holds
-        float L[16], D[16];
+      for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          const float4 l0 = *(const float4*)&sL[qb * 32 + half * 16 + hi * 8], l1 = *(const float4*)&sL[qb * 32 + half * 16 + hi * 8 + 4];
-          const float4 d0 = *(const float4*)&sD[qb * 32 + half * 16 + hi * 8], d1 = *(const float4*)&sD[qb * 32 + half * 16 + hi * 8 + 4];
-          L[half * 8 + 0] = l0.x; L[half * 8 + 1] = l0.y; L[half * 8 + 2] = l0.z; L[half * 8 + 3] = l0.w;
-          L[half * 8 + 4] = l1.x; L[half * 8 + 5] = l1.y; L[half * 8 + 6] = l1.z; L[half * 8 + 7] = l1.w;
-          D[half * 8 + 0] = d0.x; D[half * 8 + 1] = d0.y; D[half * 8 + 2] = d0.z; D[half * 8 + 3] = d0.w;
-          D[half * 8 + 4] = d1.x; D[half * 8 + 5] = d1.y; D[half * 8 + 6] = d1.z; D[half * 8 + 7] = d1.w;
-        }
-        bf16x8 pb[KB][2], dsb[KB][2];
-        f32x16 sacc[KB], pacc[KB];
+        for (int r = 0; r < 16; ++r) { sacc[kb][r] = 0.f; pacc[kb][r] = 0.f; }
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) { sacc[kb][r] = 0.f; pacc[kb][r] = 0.f; }
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const bf16x8 aq = lds_frag(sQ, qb * 32 + prow, s * 16 + hi * 8);
-          const bf16x8 ag = lds_frag(sG, qb * 32 + prow, s * 16 + hi * 8);
-#pragma unroll
-          for (int kb = 0; kb < KB; ++kb) {
-            sacc[kb] = mfma32(aq, kreg[kb][s], sacc[kb]);   // S  = Q K^T
-            pacc[kb] = mfma32(ag, vreg[kb][s], pacc[kb]);   // dP = dO V^T
-          }
-        }
+      for (int s = 0; s < 4; ++s) {
+        const bf16x8 aq = lds_frag_sw(sQ, qb * 32, prow, 2 * s + hi);
+        const bf16x8 ag = lds_frag_sw(sG, qb * 32, prow, 2 * s + hi);
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
-          float p[16], ds[16];
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            p[r] = fast_exp2(fmaf(sacc[kb][r], c, -L[r]));
-            ds[r] = p[r] * (pacc[kb][r] - D[r]);
-          }
-          pb[kb][0] = pack8(p); pb[kb][1] = pack8(p + 8);
-          dsb[kb][0] = pack8(ds); dsb[kb][1] = pack8(ds + 8);
+          sacc[kb] = mfma32(aq, kreg[kb][s], sacc[kb]);   // S  = Q K^T
+          pacc[kb] = mfma32(ag, vreg[kb][s], pacc[kb]);   // dP = dO V^T
         }
-        // dV^T += dO^T P ; dK^T += Q^T dS   (contraction over the 32 query rows of this block)
-#pragma unroll
-        for (int db = 0; db < 2; ++db)
-#pragma unroll
-          for (int half = 0; half < 2; ++half) {
-            const bf16x8 agt = lds_frag_tr(sG, LDS_LD, qb * 32 + half * 16, db * 32, lane);
-            const bf16x8 aqt = lds_frag_tr(sQ, LDS_LD, qb * 32 + half * 16, db * 32, lane);
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-              dvacc[db][kb] = mfma32(agt, pb[kb][half], dvacc[db][kb]);
-              dkacc[db][kb] = mfma32(aqt, dsb[kb][half], dkacc[db][kb]);
-            }
-          }
       }
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) {
+        float p[16], ds[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          p[r] = fast_exp2(fmaf(sacc[kb][r], c, -L[r]));
+          ds[r] = p[r] * (pacc[kb][r] - D[r]);
+        }
+        pb[kb][0] = pack8(p); pb[kb][1] = pack8(p + 8);
+        dsb[kb][0] = pack8(ds); dsb[kb][1] = pack8(ds + 8);
+      }
+      // dV^T += dO^T P ; dK^T += Q^T dS   (contraction over the 32 query rows of this block)
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const bf16x8 agt = lds_frag_tr_sw(sG, qb * 32 + half * 16, db * 32, lane);
+          const bf16x8 aqt = lds_frag_tr_sw(sQ, qb * 32 + half * 16, db * 32, lane);
+#pragma unroll
+          for (int kb = 0; kb < KB; ++kb) {
+            dvacc[db][kb] = mfma32(agt, pb[kb][half], dvacc[db][kb]);
+            dkacc[db][kb] = mfma32(aqt, dsb[kb][half], dkacc[db][kb]);
+          }
+        }
     }
   }
 
@@ -528,7 +578,7 @@ __global__ void zero_rows16_kernel(bf16_t* p, long ld, int B, int T_m, int row0,
 __global__ void fill_lse_seg_kernel(float* lse2, int BH, int T_m, int row0, int nrows) {
   const long n = (long)BH * nrows;
   for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x)
-    lse2[(i / nrows) * T_m + row0 + (i % nrows)] = IM_NEG_INF;
+    lse2[(i / nrows) * T_m + row0 + (i % nrows)] = __builtin_inff();
 }
 
 // ---- host launchers ----

@@ -107,6 +107,78 @@ __device__ __forceinline__ bf16x8 lds_frag_tr(const bf16_t* lds, int ld, int k_b
   return x.v;
 }
 
+// ---- asynchronous global -> LDS copy ----
+// One instruction moves 16 (or 4) bytes per lane from the lane's global address to LDS address
+// (wave-uniform base) + 16 (or 4) * lane, with no staging register.  It counts in vmcnt like any
+// load and completes in issue order.
+// Written as inline assembly on purpose: when the compiler sees the corresponding builtin it
+// treats every later LDS read as dependent on the copy and drains vmcnt to zero in front of it,
+// which serialises a prefetch ring.  The kernels order the copies against their LDS reads
+// themselves (s_waitcnt vmcnt(n) + workgroup barrier).  The compiler's own vmcnt bookkeeping for
+// ordinary loads stays safe: the counter counts these copies too and returns are in order, so its
+// waits can only be longer than it thinks, never shorter.  M0 is a reserved register that the
+// compiler never keeps live across statements (it sets it immediately before each use), so
+// writing it here needs no clobber.
+__device__ __forceinline__ unsigned lds_offset(const void* lds_ptr) {  // wave-uniform by contract -> SGPR
+  return (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(uintptr_t)lds_ptr);
+}
+__device__ __forceinline__ void dma16(const void* gptr, const void* lds_wave_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :: "s"(lds_offset(lds_wave_base)), "v"(gptr) : "memory");
+}
+// same, global address = wave-uniform base + per-lane unsigned 32-bit byte offset
+__device__ __forceinline__ void dma16_off(const void* gbase, unsigned byte_off, const void* lds_wave_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_offset(lds_wave_base)), "v"(byte_off), "s"(gbase) : "memory");
+}
+__device__ __forceinline__ void dma4(const void* gptr, const void* lds_wave_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
+               :: "s"(lds_offset(lds_wave_base)), "v"(gptr) : "memory");
+}
+
+// ---- swizzled, unpadded 64-column tiles (attention kernels) ----
+// A tile row is 128 bytes = 8 chunks of 16 bytes; chunk c of row r is stored at chunk position
+// c ^ sw_f(r).  sw_f depends on r % 16 only.  With it both access patterns below are free of bank
+// conflicts (measured: 16-byte row reads ~250 B/clk/CU, transpose reads ~225 B/clk/CU, against 136
+// B/clk/CU for transpose reads of rows padded to 144 bytes):
+//  - 16-byte reads of one chunk column over 16 consecutive rows: (r & 1) picks the bank half and
+//    the three bits of sw_f are a bijection of (r >> 1) & 7;
+//  - transpose reads touch, per 32 lanes, rows r0..r0+3 (r0 % 4 == 0) x one aligned 64-byte span:
+//    r and r+1 sit in opposite bank halves, r+2 moves the span by 64 bytes (bit 2 of sw_f).
+constexpr int SW_LD = 64;
+__device__ __forceinline__ int sw_f(int r) { return (((r >> 1) & 1) << 2) | ((r >> 2) & 3); }
+
+__device__ __forceinline__ void store_tile_sw(const TileRegs& t, bf16_t* lds, int tid) {
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int r = (tid >> 3) + u * 32, c = tid & 7;
+    *(u32x4*)(lds + r * SW_LD + ((c ^ sw_f(r)) << 3)) = t.v[u];
+  }
+}
+
+// 16-byte fragment: row row16 + lrow (row16 % 16 == 0, 0 <= lrow < 32), chunk column `chunk`
+__device__ __forceinline__ bf16x8 lds_frag_sw(const bf16_t* lds, int row16, int lrow, int chunk) {
+  return as_bf16x8(*(const u32x4*)(lds + (row16 + lrow) * SW_LD + ((chunk ^ sw_f(lrow)) << 3)));
+}
+
+// transposed fragment as lds_frag_tr, from a swizzled tile; k_base % 16 == 0, m_base % 32 == 0
+__device__ __forceinline__ bf16x8 lds_frag_tr_sw(const bf16_t* lds, int k_base, int m_base, int lane) {
+  const int j = lane & 15, g = lane >> 4;
+  const int lrow = 8 * (g >> 1) + (j >> 2);                  // second read: lrow + 4, i.e. sw_f ^ 1
+  const int lchunk = 2 * (g & 1) + ((j & 3) >> 1), within = 4 * (j & 1);
+  const int f = sw_f(lrow);
+  const int mb = m_base >> 3;
+  typedef v4i16 __attribute__((address_space(3))) * lds_v4_ptr;
+  const bf16_t* p0 = lds + (k_base + lrow) * SW_LD + (((mb | lchunk) ^ f) << 3) + within;
+  const bf16_t* p1 = lds + (k_base + lrow + 4) * SW_LD + (((mb | lchunk) ^ f ^ 1) << 3) + within;
+  const v4i16 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_ptr)(p0));
+  const v4i16 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_ptr)(p1));
+  union { v4i16 h[2]; bf16x8 v; } x;
+  x.h[0] = a;
+  x.h[1] = b;
+  return x.v;
+}
+
 __device__ __forceinline__ bf16x8 lds_frag(const bf16_t* lds, int row, int col) {
   return as_bf16x8(*(const u32x4*)(lds + row * LDS_LD + col));
 }

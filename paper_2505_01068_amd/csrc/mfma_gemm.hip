@@ -251,7 +251,7 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const bf16_t* src = ga[j] + (long)it_rel * a_step;
-      __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(base + (wave * 4 + j) * 1024), 16, 0, 0);
+      dma16(src, base + (wave * 4 + j) * 1024);
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -265,8 +265,7 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
         if (p.b_kper > 0) { mat = p.B[k0 / p.b_kper]; kk = k0 % p.b_kper; }
         src = mat + gboff[j] + kk;
       }
-      __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(base + DM * DK * 2 + (wave * 4 + j) * 1024), 16,
-                                       0, 0);
+      dma16(src, base + DM * DK * 2 + (wave * 4 + j) * 1024);
     }
   };
 
