@@ -31,6 +31,72 @@ __device__ __forceinline__ unsigned long long tile_key_mask(const uint8_t* key_p
   return __ballot(ok);
 }
 
+// Streamed operands (K and V tiles in the forward and dQ kernels, Q and dO tiles in the dK/dV
+// kernel) go from global memory straight into a ring of RING_NST LDS stages with asynchronous
+// global->LDS copies (no staging registers, no LDS store instructions): stage t+2 is requested
+// while stage t is consumed, with one workgroup barrier per stage.  Each lane fetches the 16-byte
+// chunk that belongs at ITS position of the swizzled tile (see sw_f), so the copy produces the
+// conflict-free layout directly.  The tiles of all live segments form one sequence, so the ring
+// does not drain between segments.
+constexpr int RING_NST = 3;
+constexpr int RING_STAGE = 2 * KT * SW_LD;  // bf16 elements per stage: two 64 x 64 tiles
+
+// Cursor over the 64-row tiles of the live segments, ascending segment order; segments whose
+// length (as given by len_of) is <= 0 are skipped.  len <= 0 <=> exhausted.  All scalar.
+struct TileCursor {
+  unsigned rest;  // live segments not started yet
+  int seg, r0, len;
+};
+template <class LenFn>
+__device__ __forceinline__ void cursor_next_seg(TileCursor& c, LenFn len_of) {
+  c.r0 = 0;
+  c.len = 0;
+  while (c.rest && c.len <= 0) {
+    c.seg = __builtin_ctz(c.rest);
+    c.rest &= c.rest - 1;
+    c.len = len_of(c.seg);
+  }
+}
+template <class LenFn>
+__device__ __forceinline__ void cursor_step(TileCursor& c, LenFn len_of) {
+  c.r0 += KT;
+  if (c.r0 >= c.len) cursor_next_seg(c, len_of);
+}
+
+// Per-lane constants of the ring copies: the two tile rows whose chunk positions this lane fills
+// and the byte offset of the logical chunk inside a row of head h.
+struct RingLane {
+  int trow0, trow1;
+  unsigned col0, col1;
+};
+__device__ __forceinline__ RingLane ring_lane(int wave, int lane, int h) {
+  RingLane r;
+  r.trow0 = wave * 8 + (lane >> 3);
+  r.trow1 = r.trow0 + 32;
+  r.col0 = (unsigned)(h * 64 + (((lane & 7) ^ sw_f(r.trow0)) << 3)) * 2u;
+  r.col1 = (unsigned)(h * 64 + (((lane & 7) ^ sw_f(r.trow1)) << 3)) * 2u;
+  return r;
+}
+// Request rows r0 .. r0+63 (clamped to row_max) of two [rows, pitch] matrices a and b (wave-uniform
+// bases, row pitches in bytes) into the two tiles of LDS stage `stage`.  4 copies per wave.
+__device__ __forceinline__ void ring_issue_pair(const RingLane& rl, int wave, const bf16_t* a, unsigned pitch_a,
+                                                const bf16_t* b, unsigned pitch_b, int r0, int row_max,
+                                                bf16_t* stage) {
+  const unsigned r0c = (unsigned)min(r0 + rl.trow0, row_max), r1c = (unsigned)min(r0 + rl.trow1, row_max);
+  dma16_off(a, __umul24(r0c, pitch_a) + rl.col0, stage + wave * 512);
+  dma16_off(b, __umul24(r0c, pitch_b) + rl.col0, stage + KT * SW_LD + wave * 512);
+  dma16_off(a, __umul24(r1c, pitch_a) + rl.col1, stage + (4 + wave) * 512);
+  dma16_off(b, __umul24(r1c, pitch_b) + rl.col1, stage + KT * SW_LD + (4 + wave) * 512);
+}
+// wait until at most `later` (0 or 1) stages of 4 copies requested after the wanted one are
+// outstanding, then meet the other waves: the wanted stage is visible to all, and every wave has
+// finished reading the stage consumed before it.
+__device__ __forceinline__ void ring_wait(int later) {
+  if (later > 0) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+}
+
 // ------------------------------------------------------------------------------------------
 // Forward.  Workgroup = 4 waves; each wave owns QB blocks of 32 query rows.
 template <int QB>
@@ -38,8 +104,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
                                                        const int32_t* __restrict__ valid_len,
                                                        const uint8_t* __restrict__ key_pad, bf16_t* __restrict__ O,
                                                        long ldo, float* __restrict__ lse2) {
-  __shared__ __attribute__((aligned(16))) bf16_t sK[KT * SW_LD];
-  __shared__ __attribute__((aligned(16))) bf16_t sV[KT * SW_LD];
+  __shared__ __attribute__((aligned(1024))) bf16_t sT[RING_NST * RING_STAGE];  // per stage: K tile, V tile
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   int tile, h, b;
   xcd_block_index(tile, h, b);
@@ -76,28 +141,44 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
 
   const int prow = perm32(lo);
   const float tau = c > 0.f ? 8.f / c : __builtin_inff();
-  const unsigned live = g.q_live[qs];
-  for (int j = 0; j < g.n_seg; ++j) {
-    if (!((live >> j) & 1u)) continue;
-    int klen = g.seg_len[j];
-    if (valid_len) klen = min(klen, max(0, valid_len[b * g.n_seg + j]));
-    const bf16_t* Kbase = QKV + ((long)b * g.T + g.seg_off[j]) * ld + d + h * 64;
-    const bf16_t* Vbase = Kbase + d;
-    const uint8_t* kp_row = key_pad ? key_pad + (long)b * g.T + g.seg_off[j] : nullptr;
-    TileRegs tk, tv;
-    if (klen > 0) {
-      load_rows_tile(tk, Kbase, ld, 0, g.seg_len[j] - 1, tid);
-      load_rows_tile(tv, Vbase, ld, 0, g.seg_len[j] - 1, tid);
-    }
-    for (int k0 = 0; k0 < klen; k0 += KT) {
-      __syncthreads();
-      store_tile_sw(tk, sK, tid);
-      store_tile_sw(tv, sV, tid);
-      __syncthreads();
-      if (k0 + KT < klen) {
-        load_rows_tile(tk, Kbase, ld, k0 + KT, g.seg_len[j] - 1, tid);
-        load_rows_tile(tv, Vbase, ld, k0 + KT, g.seg_len[j] - 1, tid);
-      }
+  // The compiler does not see the asynchronous copies in its vmcnt bookkeeping: consuming the Q
+  // registers here makes it wait for their (ordinary) loads now, not inside the ring loop.
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+    for (int s = 0; s < 4; ++s) asm volatile("" :: "v"(qreg[qb][s]));
+
+  // key tiles of the live key segments; a segment contributes its first min(length, valid length) keys
+  auto klen_of = [&](int j) {
+    int n = g.seg_len[j];
+    if (valid_len) n = min(n, max(0, valid_len[b * g.n_seg + j]));
+    return n;
+  };
+  const RingLane rl = ring_lane(wave, lane, h);
+  const unsigned ldb = (unsigned)ld * 2u;
+  TileCursor ic = {g.q_live[qs], 0, 0, 0}, cc = ic;
+  cursor_next_seg(ic, klen_of);
+  cursor_next_seg(cc, klen_of);
+  int islot = 0, cslot = 0, inflight = 0;
+  auto issue = [&]() {
+    const bf16_t* Kb = QKV + ((long)b * g.T + g.seg_off[ic.seg]) * ld + d;
+    // rows past the valid length but inside the segment are fetched and masked
+    ring_issue_pair(rl, wave, Kb, ldb, Kb + d, ldb, ic.r0, g.seg_len[ic.seg] - 1, sT + islot * RING_STAGE);
+    islot = (islot + 1 == RING_NST) ? 0 : islot + 1;
+    cursor_step(ic, klen_of);
+  };
+  if (ic.len > 0) { issue(); ++inflight; }
+  if (ic.len > 0) { issue(); ++inflight; }
+  while (cc.len > 0) {
+    ring_wait(inflight - 1);
+    if (ic.len > 0) issue(); else --inflight;
+    const bf16_t* sK = sT + cslot * RING_STAGE;
+    const bf16_t* sV = sK + KT * SW_LD;
+    cslot = (cslot + 1 == RING_NST) ? 0 : cslot + 1;
+    const int k0 = cc.r0, klen = cc.len;
+    const uint8_t* kp_row = key_pad ? key_pad + (long)b * g.T + g.seg_off[cc.seg] : nullptr;
+    cursor_step(cc, klen_of);
+    {
       // ---- S^T = K Q^T ----
       f32x16 sacc[2][QB];
 #pragma unroll
@@ -211,8 +292,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
                                                       const int32_t* __restrict__ valid_len,
                                                       const uint8_t* __restrict__ key_pad, float* __restrict__ delta,
                                                       bf16_t* __restrict__ dQKV, long ldg) {
-  __shared__ __attribute__((aligned(16))) bf16_t sK[KT * SW_LD];
-  __shared__ __attribute__((aligned(16))) bf16_t sV[KT * SW_LD];
+  __shared__ __attribute__((aligned(1024))) bf16_t sT[RING_NST * RING_STAGE];  // per stage: K tile, V tile
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   int tile, h, b;
   xcd_block_index(tile, h, b);
@@ -263,28 +343,44 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
       for (int r = 0; r < 16; ++r) dqacc[db][qb][r] = 0.f;
 
   const int prow = perm32(lo);
-  const unsigned live = g.q_live[qs];
-  for (int j = 0; j < g.n_seg; ++j) {
-    if (!((live >> j) & 1u)) continue;
-    int klen = g.seg_len[j];
-    if (valid_len) klen = min(klen, max(0, valid_len[b * g.n_seg + j]));
-    const bf16_t* Kbase = QKV + ((long)b * g.T + g.seg_off[j]) * ld + d + h * 64;
-    const bf16_t* Vbase = Kbase + d;
-    const uint8_t* kp_row = key_pad ? key_pad + (long)b * g.T + g.seg_off[j] : nullptr;
-    TileRegs tk, tv;
-    if (klen > 0) {
-      load_rows_tile(tk, Kbase, ld, 0, g.seg_len[j] - 1, tid);
-      load_rows_tile(tv, Vbase, ld, 0, g.seg_len[j] - 1, tid);
-    }
-    for (int k0 = 0; k0 < klen; k0 += KT) {
-      __syncthreads();
-      store_tile_sw(tk, sK, tid);
-      store_tile_sw(tv, sV, tid);
-      __syncthreads();
-      if (k0 + KT < klen) {
-        load_rows_tile(tk, Kbase, ld, k0 + KT, g.seg_len[j] - 1, tid);
-        load_rows_tile(tv, Vbase, ld, k0 + KT, g.seg_len[j] - 1, tid);
-      }
+  // The compiler does not see the asynchronous copies in its vmcnt bookkeeping: consuming the
+  // loaded registers here makes it wait for their (ordinary) loads now, not inside the ring loop.
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) asm volatile("" :: "v"(qreg[qb][s]), "v"(greg[qb][s]));
+    asm volatile("" :: "v"(ls[qb]), "v"(dl[qb]));
+  }
+
+  auto klen_of = [&](int j) {
+    int n = g.seg_len[j];
+    if (valid_len) n = min(n, max(0, valid_len[b * g.n_seg + j]));
+    return n;
+  };
+  const RingLane rl = ring_lane(wave, lane, h);
+  const unsigned ldb = (unsigned)ld * 2u;
+  TileCursor ic = {g.q_live[qs], 0, 0, 0}, cc = ic;
+  cursor_next_seg(ic, klen_of);
+  cursor_next_seg(cc, klen_of);
+  int islot = 0, cslot = 0, inflight = 0;
+  auto issue = [&]() {
+    const bf16_t* Kb = QKV + ((long)b * g.T + g.seg_off[ic.seg]) * ld + d;
+    ring_issue_pair(rl, wave, Kb, ldb, Kb + d, ldb, ic.r0, g.seg_len[ic.seg] - 1, sT + islot * RING_STAGE);
+    islot = (islot + 1 == RING_NST) ? 0 : islot + 1;
+    cursor_step(ic, klen_of);
+  };
+  if (ic.len > 0) { issue(); ++inflight; }
+  if (ic.len > 0) { issue(); ++inflight; }
+  while (cc.len > 0) {
+    ring_wait(inflight - 1);
+    if (ic.len > 0) issue(); else --inflight;
+    const bf16_t* sK = sT + cslot * RING_STAGE;
+    const bf16_t* sV = sK + KT * SW_LD;
+    cslot = (cslot + 1 == RING_NST) ? 0 : cslot + 1;
+    const int k0 = cc.r0, klen = cc.len;
+    const uint8_t* kp_row = key_pad ? key_pad + (long)b * g.T + g.seg_off[cc.seg] : nullptr;
+    cursor_step(cc, klen_of);
+    {
       const bool need_mask = (k0 + KT > klen) || (kp_row != nullptr);
       unsigned long long km = ~0ull;
       if (need_mask) km = tile_key_mask(kp_row, k0, klen, lane) >> (8 * hi);
@@ -361,13 +457,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
 // the query rows of every query segment that reads this key segment.  A key tile
 // has exactly one producer, so the result is deterministic without atomics.
 //
-// The streamed operands (64 query rows of Q and dO, their lse and delta) go from global memory
-// straight into a ring of DKV_NST LDS stages with global_load_lds (no staging registers, no LDS
-// store instructions): stage t+2 is requested while stage t is consumed, one workgroup barrier
-// per stage.  Each lane fetches the 16-byte chunk that belongs at ITS position of the swizzled
-// tile (see sw_f), so the asynchronous copy produces the conflict-free layout directly.
-constexpr int DKV_NST = 3;
-constexpr int DKV_STAGE = 2 * KT * SW_LD;  // bf16 elements per stage: Q tile, then dO tile
+// Ring stage = Q tile, dO tile (see RING_STAGE) plus the 64 lse and 64 delta values of the rows.
 __device__ const float k_pos_inf = __builtin_inff();
 
 template <int KB>
@@ -377,8 +467,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
                                                        const int32_t* __restrict__ valid_len,
                                                        const uint8_t* __restrict__ key_pad, bf16_t* __restrict__ dQKV,
                                                        long ldg) {
-  __shared__ __attribute__((aligned(1024))) bf16_t sT[DKV_NST * DKV_STAGE];
-  __shared__ __attribute__((aligned(256))) float sLD[DKV_NST * 2 * KT];  // per stage: lse[64], delta[64]
+  __shared__ __attribute__((aligned(1024))) bf16_t sT[RING_NST * RING_STAGE];
+  __shared__ __attribute__((aligned(256))) float sLD[RING_NST * 2 * KT];  // per stage: lse[64], delta[64]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   int tile, h, b;
   xcd_block_index(tile, h, b);
@@ -388,47 +478,27 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
   const int klen_seg = g.seg_len[ks];
   const int d = g.d;
   const float c = fmaxf(g.scale_log2e, 1e-30f);  // > 0 so that -inf * c stays -inf when scale == 0
-  const unsigned live = g.k_live[ks];
 
-  // Query tiles of all live query segments form one sequence 0..nt-1 so the ring never drains
-  // between segments.  (iseg, ir0, islot) describe the tile the next issue() requests.
-  int nt = 0;
-#pragma unroll
-  for (int i = 0; i < IM_MAX_SEG; ++i)
-    if (i < g.n_seg && ((live >> i) & 1u)) nt += (g.seg_len[i] + KT - 1) / KT;
-  int iseg = __builtin_ctz(live | (1u << IM_MAX_SEG)), ir0 = 0, islot = 0;
-  // tile rows / logical chunks whose 16-byte chunk positions this lane fills (two per tile)
-  const int trow0 = wave * 8 + (lane >> 3), trow1 = trow0 + 32;
-  const unsigned col0 = (unsigned)(h * 64 + (((lane & 7) ^ sw_f(trow0)) << 3)) * 2u;
-  const unsigned col1 = (unsigned)(h * 64 + (((lane & 7) ^ sw_f(trow1)) << 3)) * 2u;
-  const unsigned ldb = (unsigned)ld * 2u, ldob = (unsigned)ldo * 2u;  // row pitches in bytes (< 2^24, host-checked)
-
+  auto qlen_of = [&](int i) { return g.seg_len[i]; };
+  const RingLane rl = ring_lane(wave, lane, h);
+  const unsigned ldb = (unsigned)ld * 2u, ldob = (unsigned)ldo * 2u;  // row pitches in bytes
+  TileCursor ic = {g.k_live[ks], 0, 0, 0}, cc = ic;
+  cursor_next_seg(ic, qlen_of);
+  cursor_next_seg(cc, qlen_of);
+  int islot = 0, cslot = 0, inflight = 0;
   auto issue = [&]() {
-    const int qlen = g.seg_len[iseg];
-    const long row0 = (long)b * g.T + g.seg_off[iseg];
-    const bf16_t* qb_ = QKV + row0 * ld;   // wave-uniform bases; per-lane byte offsets stay below 2^32 (host-checked)
-    const bf16_t* gb_ = dO + row0 * ldo;
-    bf16_t* lq = sT + islot * DKV_STAGE;
-    const unsigned r0c = (unsigned)min(ir0 + trow0, qlen - 1), r1c = (unsigned)min(ir0 + trow1, qlen - 1);
-    dma16_off(qb_, __umul24(r0c, ldb) + col0, lq + wave * 512);
-    dma16_off(gb_, __umul24(r0c, ldob) + col0, lq + KT * SW_LD + wave * 512);
-    dma16_off(qb_, __umul24(r1c, ldb) + col1, lq + (4 + wave) * 512);
-    dma16_off(gb_, __umul24(r1c, ldob) + col1, lq + KT * SW_LD + (4 + wave) * 512);
+    const long row0 = (long)b * g.T + g.seg_off[ic.seg];
+    ring_issue_pair(rl, wave, QKV + row0 * ld, ldb, dO + row0 * ldo, ldob, ic.r0, ic.len - 1, sT + islot * RING_STAGE);
     // lse (wave 0) and delta (wave 1), one float per lane.  Rows past the segment read +inf as
     // lse, so their probabilities are exactly zero.
     if (wave < 2) {
-      const int r = ir0 + lane;
-      const long lb = ((long)b * g.H + h) * g.T + g.seg_off[iseg];
-      const float* src = (wave == 0) ? (r < qlen ? lse2 + lb + r : &k_pos_inf) : delta + lb + min(r, qlen - 1);
+      const int r = ic.r0 + lane;
+      const long lb = ((long)b * g.H + h) * g.T + g.seg_off[ic.seg];
+      const float* src = (wave == 0) ? (r < ic.len ? lse2 + lb + r : &k_pos_inf) : delta + lb + min(r, ic.len - 1);
       dma4(src, sLD + islot * 2 * KT + wave * KT);
     }
-    islot = (islot + 1 == DKV_NST) ? 0 : islot + 1;
-    ir0 += KT;
-    if (ir0 >= qlen) {  // next live query segment (none left: the value is never used)
-      ir0 = 0;
-      iseg = __builtin_ctz((live >> (iseg + 1)) | (1u << IM_MAX_SEG)) + iseg + 1;
-      iseg = min(iseg, g.n_seg - 1);
-    }
+    islot = (islot + 1 == RING_NST) ? 0 : islot + 1;
+    cursor_step(ic, qlen_of);
   };
 
   bf16x8 kreg[KB][4], vreg[KB][4];
@@ -467,27 +537,28 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
 #pragma unroll
     for (int s = 0; s < 4; ++s) asm volatile("" :: "v"(kreg[kb][s]), "v"(vreg[kb][s]));
 
-  if (nt > 0) issue();
-  if (nt > 1) issue();
+  if (ic.len > 0) { issue(); ++inflight; }
+  if (ic.len > 0) { issue(); ++inflight; }
 
   const int prow = perm32(lo);
-  int cslot = 0;
-  for (int t = 0; t < nt; ++t) {
-    // Loads complete in issue order.  Stage t is complete once at most the loads of stage t+1
-    // (4 tile chunks, plus 1 for the waves that fetch lse / delta) are outstanding.
-    if (t + 1 < nt) {
+  while (cc.len > 0) {
+    // Copies complete in issue order.  The wanted stage is complete once at most the copies of the
+    // stage requested after it (4 tile chunks, plus 1 on the waves that fetch lse / delta) are
+    // outstanding.
+    if (inflight > 1) {
       if (wave < 2) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
       else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     } else {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
-    __builtin_amdgcn_s_barrier();  // stage t visible to all waves; everyone is done with stage t-1
-    if (t + 2 < nt) issue();  // refills the slot of stage t-1
-    const bf16_t* sQ = sT + cslot * DKV_STAGE;
+    __builtin_amdgcn_s_barrier();  // stage visible to all waves; everyone is done with the one before
+    if (ic.len > 0) issue(); else --inflight;  // refills the slot of the stage consumed before
+    const bf16_t* sQ = sT + cslot * RING_STAGE;
     const bf16_t* sG = sQ + KT * SW_LD;
     const float* sL = sLD + cslot * 2 * KT;
     const float* sD = sL + KT;
-    cslot = (cslot + 1 == DKV_NST) ? 0 : cslot + 1;
+    cslot = (cslot + 1 == RING_NST) ? 0 : cslot + 1;
+    cursor_step(cc, qlen_of);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       // per-register lse / delta of the query rows this lane half holds
