@@ -73,7 +73,9 @@ __device__ __forceinline__ void store_km(const Tile128& t, bf16_t* lds, int tid)
   }
 }
 
-template <bool AKM, bool BKM>
+// EPI: the epilogue may apply GELU and add a residual (separate instantiation, so that the plain
+// bias epilogue of the attention projections stays a few hundred instructions long).
+template <bool AKM, bool BKM, bool EPI>
 __global__ __launch_bounds__(256) void mfma_gemm_kernel(MGemm p) {
   __shared__ __attribute__((aligned(16))) bf16_t sA[AKM ? GK * KM_LD : GM * LDS_LD];
   __shared__ __attribute__((aligned(16))) bf16_t sB[BKM ? GK * KM_LD : GN * LDS_LD];
@@ -136,6 +138,43 @@ __global__ __launch_bounds__(256) void mfma_gemm_kernel(MGemm p) {
   }
 
   // ---- epilogue: lane owns row m; registers 4i..4i+3 are columns n = 8i + 4hi + 0..3 of the block ----
+  if (p.partial) {  // split-K: fp32 partial sums, 16 bytes per lane
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+      const int m = m0 + wm * 64 + mb * 32 + lo;
+      if (m >= p.M) continue;
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int n = n0 + wn * 64 + nb * 32 + 8 * i + 4 * hi;
+          if (n >= p.N) continue;  // N is a multiple of 4 for every caller
+          *(float4*)(p.partial + ((long)bz * p.M + m) * p.N + n) =
+              make_float4(acc[nb][mb][4 * i], acc[nb][mb][4 * i + 1], acc[nb][mb][4 * i + 2], acc[nb][mb][4 * i + 3]);
+        }
+    }
+    return;
+  }
+  // The bias depends on the column only: fetch this lane's 8 x 4 values once.
+  float bv[2][4][4];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int n = n0 + wn * 64 + nb * 32 + 8 * i + 4 * hi;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) bv[nb][i][j] = 0.f;
+      if (p.n_per > 0 && n < p.N) {
+        const int sel = n / p.n_per, nn = n - sel * p.n_per;
+        if (p.bias[sel]) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) bv[nb][i][j] = bf2f(p.bias[sel][nn + j]);
+        }
+      }
+    }
+  // Direct 8-byte stores (a lane owns a row of the accumulator tile).  Staging the tile through LDS
+  // for 16-byte row-contiguous stores was measured slower here: with three workgroups per CU the
+  // stores of one overlap the loads of the others, and the extra barrier costs more than it saves.
 #pragma unroll
   for (int mb = 0; mb < 2; ++mb) {
     const int m = m0 + wm * 64 + mb * 32 + lo;
@@ -148,26 +187,17 @@ __global__ __launch_bounds__(256) void mfma_gemm_kernel(MGemm p) {
         if (n >= p.N) continue;  // N is a multiple of 4 for every caller
         float v[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j];
-        if (p.partial) {
-          *(float4*)(p.partial + ((long)bz * p.M + m) * p.N + n) = make_float4(v[0], v[1], v[2], v[3]);
-          continue;
-        }
-        if (p.n_per > 0) {
-          const int sel = n / p.n_per, nn = n % p.n_per;
-          if (p.bias[sel]) {
+        for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j] + bv[nb][i][j];
+        if constexpr (EPI) {
+          if (p.gelu) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] += bf2f(p.bias[sel][nn + j]);
+            for (int j = 0; j < 4; ++j) v[j] = gelu_exact_f(v[j]);
           }
-        }
-        if (p.gelu) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = gelu_exact_f(v[j]);
-        }
-        if (p.res) {
-          const u32x2 rv = *(const u32x2*)(p.res + (long)m * p.ldc + n);
-          v[0] += __uint_as_float(rv[0] << 16); v[1] += __uint_as_float(rv[0] & 0xffff0000u);
-          v[2] += __uint_as_float(rv[1] << 16); v[3] += __uint_as_float(rv[1] & 0xffff0000u);
+          if (p.res) {
+            const u32x2 rv = *(const u32x2*)(p.res + (long)m * p.ldc + n);
+            v[0] += __uint_as_float(rv[0] << 16); v[1] += __uint_as_float(rv[0] & 0xffff0000u);
+            v[2] += __uint_as_float(rv[1] << 16); v[3] += __uint_as_float(rv[1] & 0xffff0000u);
+          }
         }
         const u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
         *(u32x2*)(p.C + (long)m * p.ldc + n) = pk;
@@ -198,7 +228,7 @@ constexpr int DMA_LDS_BYTES = DSTAGES * DMA_STAGE_BYTES;      // 128 KB
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef const __attribute__((address_space(1))) void* glb_void_ptr;
 
-template <bool AKM, bool BKM>
+template <bool AKM, bool BKM, bool EPI>
 __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
   extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
@@ -370,6 +400,23 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
   asm volatile("" ::: "memory");
   constexpr int EP_LD = 136;     // bf16 per staged row (128 + 8 pad)
   bf16_t* stg = smem + wave * (DMA_LDS_BYTES / 8);
+  // The bias depends on the column only: fetch this lane's 16 x 4 values once, not once per row block.
+  float bv[4][4][4];
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int n = n0 + wn * 128 + nb * 32 + 8 * i + 4 * hi;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) bv[nb][i][j] = 0.f;
+      if (p.n_per > 0 && n < p.N) {
+        const int sel = n / p.n_per, nn = n - sel * p.n_per;
+        if (p.bias[sel]) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) bv[nb][i][j] = bf2f(p.bias[sel][nn + j]);
+        }
+      }
+    }
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
 #pragma unroll
@@ -384,22 +431,17 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
           const int n = n0 + wn * 128 + nl;
           float v[4];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j];
-          if (p.n_per > 0 && n < p.N) {
-            const int sel = n / p.n_per, nn = n % p.n_per;
-            if (p.bias[sel]) {
+          for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j] + bv[nb][i][j];
+          if constexpr (EPI) {
+            if (p.gelu) {
 #pragma unroll
-              for (int j = 0; j < 4; ++j) v[j] += bf2f(p.bias[sel][nn + j]);
+              for (int j = 0; j < 4; ++j) v[j] = gelu_exact_f(v[j]);
             }
-          }
-          if (p.gelu) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = gelu_exact_f(v[j]);
-          }
-          if (p.res && m < p.M && n < p.N) {
-            const u32x2 rv = *(const u32x2*)(p.res + (long)m * p.ldc + n);
-            v[0] += __uint_as_float(rv[0] << 16); v[1] += __uint_as_float(rv[0] & 0xffff0000u);
-            v[2] += __uint_as_float(rv[1] << 16); v[3] += __uint_as_float(rv[1] & 0xffff0000u);
+            if (p.res && m < p.M && n < p.N) {
+              const u32x2 rv = *(const u32x2*)(p.res + (long)m * p.ldc + n);
+              v[0] += __uint_as_float(rv[0] << 16); v[1] += __uint_as_float(rv[0] & 0xffff0000u);
+              v[2] += __uint_as_float(rv[1] << 16); v[3] += __uint_as_float(rv[1] & 0xffff0000u);
+            }
           }
           const u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
           *(u32x2*)(stg + (mq * 32 + lo) * EP_LD + nl) = pk;
@@ -437,12 +479,15 @@ __global__ void mfma_splitk_reduce_kernel(const float* partial, int split_k, int
   }
 }
 
-// The asynchronous large-tile kernel is used for the weight gradients (both operands k-major, long
-// contraction over token rows): measured on MI355X it is 1.5x faster there than the 128 x 128 kernel,
-// while for the short-K (K = d) projections, whose row-major operands contribute only 64 bytes per
-// row and stage, the 128 x 128 kernel with three workgroups per CU is the faster one.
+// Which kernel (measured on MI355X, C5 shapes):
+//  - weight gradients (both operands k-major, long contraction over token rows): the asynchronous
+//    256 x 256 kernel is 1.5x faster than the 128 x 128 kernel;
+//  - projections with row-major activations and k-major weights (QKV, output projection; K = d):
+//    the 256 x 256 kernel needs half the L1 traffic per flop and wins by 1.2-1.35x;
+//  - both operands row-major (dO, dx): the 128 x 128 kernel with three workgroups per CU wins.
 static bool use_dma(int M, int N, int K, bool akm = true, bool bkm = true) {
-  return akm && bkm && M >= DM && N >= DN && K % DK == 0 && K >= 64 * DK && M % 8 == 0 && N % 8 == 0;
+  if (!(bkm && M >= DM && N >= DN && K % DK == 0 && M % 8 == 0 && N % 8 == 0)) return false;
+  return akm ? K >= 64 * DK : K >= 8 * DK;
 }
 
 int mfma_gemm_split(int M, int N, int K) {
@@ -462,31 +507,36 @@ int mfma_gemm_split(int M, int N, int K) {
   return s < 1 ? 1 : s;
 }
 
-template <bool AKM, bool BKM>
+template <bool AKM, bool BKM, bool EPI>
 static void launch_dma(const MGemm& p, hipStream_t st) {
   static bool configured = false;  // raise the dynamic-LDS limit once per instantiation (128 KB > the 64 KB default)
   if (!configured) {
-    (void)hipFuncSetAttribute((const void*)mfma_gemm_dma_kernel<AKM, BKM>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              DMA_LDS_BYTES);
+    (void)hipFuncSetAttribute((const void*)mfma_gemm_dma_kernel<AKM, BKM, EPI>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, DMA_LDS_BYTES);
     configured = true;
   }
   dim3 grid((p.N + DN - 1) / DN, (p.M + DM - 1) / DM, p.split_k);
-  hipLaunchKernelGGL((mfma_gemm_dma_kernel<AKM, BKM>), grid, dim3(256), DMA_LDS_BYTES, st, p);
+  hipLaunchKernelGGL((mfma_gemm_dma_kernel<AKM, BKM, EPI>), grid, dim3(256), DMA_LDS_BYTES, st, p);
 }
-
-void launch_mfma_gemm(const MGemm& p, hipStream_t st) {
-  if (use_dma(p.M, p.N, p.K, p.a_kmajor, p.b_kmajor) && (p.b_kper == 0 || p.b_kper % DK == 0)) {
-    if (p.a_kmajor && p.b_kmajor) launch_dma<true, true>(p, st);
-    else if (p.b_kmajor) launch_dma<false, true>(p, st);
-    else if (p.a_kmajor) launch_dma<true, false>(p, st);
-    else launch_dma<false, false>(p, st);
+template <bool AKM, bool BKM>
+static void launch_layout(const MGemm& p, bool dma, hipStream_t st) {
+  const bool epi = p.gelu || p.res != nullptr;
+  if (dma) {
+    if (epi) launch_dma<AKM, BKM, true>(p, st);
+    else launch_dma<AKM, BKM, false>(p, st);
     return;
   }
   dim3 grid((p.N + GN - 1) / GN, (p.M + GM - 1) / GM, p.split_k);
-  if (p.a_kmajor && p.b_kmajor) hipLaunchKernelGGL((mfma_gemm_kernel<true, true>), grid, dim3(256), 0, st, p);
-  else if (p.b_kmajor) hipLaunchKernelGGL((mfma_gemm_kernel<false, true>), grid, dim3(256), 0, st, p);
-  else if (p.a_kmajor) hipLaunchKernelGGL((mfma_gemm_kernel<true, false>), grid, dim3(256), 0, st, p);
-  else hipLaunchKernelGGL((mfma_gemm_kernel<false, false>), grid, dim3(256), 0, st, p);
+  if (epi) hipLaunchKernelGGL((mfma_gemm_kernel<AKM, BKM, true>), grid, dim3(256), 0, st, p);
+  else hipLaunchKernelGGL((mfma_gemm_kernel<AKM, BKM, false>), grid, dim3(256), 0, st, p);
+}
+
+void launch_mfma_gemm(const MGemm& p, hipStream_t st) {
+  const bool dma = use_dma(p.M, p.N, p.K, p.a_kmajor, p.b_kmajor) && (p.b_kper == 0 || p.b_kper % DK == 0);
+  if (p.a_kmajor && p.b_kmajor) launch_layout<true, true>(p, dma, st);
+  else if (p.b_kmajor) launch_layout<false, true>(p, dma, st);
+  else if (p.a_kmajor) launch_layout<true, false>(p, dma, st);
+  else launch_layout<false, false>(p, dma, st);
 }
 void launch_splitk_reduce(const float* partial, int split_k, int M, int N, float* o0, float* o1, float* o2, int n_per,
                           hipStream_t st) {
