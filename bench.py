@@ -53,16 +53,14 @@ def live_pairs(seg_len, live_mask, batch, valid_len, key_pad):
 
 def stored_traffic(config, family):
     """HBM bytes per launch of the dominant kernel from the committed counter summary
-    (profiles/<config>_<family>_traffic.md), or None if there is none or the kernel source changed since."""
-    import hashlib
+    (profiles/<config>_<family>_traffic.md), or None if there is none or the kernel sources changed since."""
     import re
+    from paper_2505_01068_amd.traffic import source_hash
     path = os.path.join(ROOT, "profiles", f"{config}_{family}_traffic.md")
     try:
         m = re.search(r"^TRAFFIC_JSON (.*)$", open(path).read(), flags=re.M)
         rec = json.loads(m.group(1))
-        src = "mfma_attn.hip" if "mfma" in rec["kernel"] else "attn_rowlane.hip"
-        cur = hashlib.sha256(open(os.path.join(ROOT, "paper_2505_01068_amd", "csrc", src), "rb").read()).hexdigest()
-        return rec["bytes_per_launch"] if cur == rec["source_sha256"] else None
+        return rec["bytes_per_launch"] if source_hash(rec["kernel"]) == rec["source_sha256"] else None
     except Exception:
         return None
 

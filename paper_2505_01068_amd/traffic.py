@@ -23,13 +23,18 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 COPY_BYTES = 1 << 30
-KERNEL_SOURCES = {"mfma_": "csrc/mfma_attn.hip", "rowlane_": "csrc/attn_rowlane.hip"}
+KERNEL_SOURCES = {"mfma_": ["csrc/mfma_attn.hip", "csrc/mfma_common.hpp", "csrc/common.hpp"],
+                  "rowlane_": ["csrc/attn_rowlane.hip", "csrc/common.hpp"]}
 
 
 def source_hash(kernel_name: str) -> str:
-    for key, rel in KERNEL_SOURCES.items():
+    """sha256 over the sources the named kernel is compiled from ("" if unknown)."""
+    for key, rels in KERNEL_SOURCES.items():
         if key in kernel_name:
-            return hashlib.sha256(open(os.path.join(HERE, rel), "rb").read()).hexdigest()
+            h = hashlib.sha256()
+            for rel in rels:
+                h.update(open(os.path.join(HERE, rel), "rb").read())
+            return h.hexdigest()
     return ""
 
 
