@@ -153,3 +153,12 @@ def test_mfma_zero_scale_and_large_scores():
     # more than the bar (conditioning of the problem, not of the kernel)
     for lm in (oracle.IM_IFM_FORWARD, oracle.IM_DENSE):
         Problem(g1, lm).check(backward=False, what=f"mfma growing scores lm={lm:#x}")
+
+
+@pytest.mark.parametrize("name", [n for n in sorted(oracle.NAMED_PATTERNS) if n.startswith(("structure", "self_only"))])
+def test_mfma_pattern_variants_fwd_bwd(name):
+    # Structures 1-3 and Self-Only (Sec. 5.3, Appendix D) on the
+    # matrix-core path: the tile ring runs through several live key segments per query row
+    say(f"[case] mfma pattern variant {name} fwd+bwd")
+    g = synth.attention_inputs(2, (70, 200, 130), 128, 2, "bf16", "valid_len", seed=20250512, bias=True)
+    Problem(g, oracle.NAMED_PATTERNS[name]).check(what=f"mfma-variant/{name}")

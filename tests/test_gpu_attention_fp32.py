@@ -112,3 +112,26 @@ def test_inference_without_saved_matches():
     y1 = p.fwd(save=False)
     torch.cuda.synchronize()
     assert torch.equal(y0, y1)
+
+
+# Maximum sequence lengths (text, vision, audio) of the other three datasets in the paper's dataset
+# table (Appendix E): CMU-MOSEI, CH-SIMS, MIntRec.  Synthetic N(0,1) features of those shapes with
+# per-sample valid lengths stand in for the datasets.
+DATASET_SHAPES = {"mosei": (50, 500, 500), "sims": (39, 400, 55), "mintrec": (30, 230, 480)}
+
+
+@pytest.mark.parametrize("ds", sorted(DATASET_SHAPES))
+@pytest.mark.parametrize("name", ["ifm_forward", "ifm_backward", "iem"])
+def test_other_dataset_shapes(ds, name):
+    say(f"[case] dataset shape {ds} pattern={name}")
+    g = synth.attention_inputs(4, DATASET_SHAPES[ds], 40, 8, "fp32", "valid_len", seed=20250510, bias=False)
+    Problem(g, oracle.NAMED_PATTERNS[name]).check(what=f"{ds}/{name}")
+
+
+@pytest.mark.parametrize("name", [n for n in sorted(oracle.NAMED_PATTERNS) if n.startswith(("structure", "self_only"))])
+def test_pattern_variants_fwd_bwd(name):
+    # Structures 1-3 and Self-Only (Sec. 5.3, Appendix D; Self-Only is also the multi-live-block case of the information-disorder discussion): rows
+    # with several live blocks share ONE softmax across segments (Sec. 7.1)
+    say(f"[case] pattern variant {name} fwd+bwd")
+    g = synth.attention_inputs(2, (50, 200, 150), 40, 8, "fp32", "valid_len", seed=20250511, bias=True)
+    Problem(g, oracle.NAMED_PATTERNS[name]).check(what=f"variant/{name}")
