@@ -1,4 +1,4 @@
-"""CPU oracle for Interlaced-Mask (IM) attention and the GsiT encoder layer.
+"""CPU oracle for Interlaced-Mask (IM) attention, the GsiT encoder layer and the model around it.
 
 TEST INFRASTRUCTURE ONLY.  This package is the slow, plain, fp64 definition the
 GPU library is checked against.  Nothing in the product path may import it: only
@@ -17,3 +17,4 @@ from .im_attention import (  # noqa: F401
     project_qkv, forward, backward, mult_blocks_forward, live_pair_count,
 )
 from .gsit_layer import layer_norm, gelu, gsit_layer_forward, gsit_encoder_forward  # noqa: F401
+from .gsit_model import gsit_model_forward, last_steps  # noqa: F401

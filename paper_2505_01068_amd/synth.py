@@ -169,6 +169,23 @@ def layer_params(d_model, d_ff, seed, layer, dtype="bf16", bias=True):
     return p
 
 
+def model_params(d_model, d_ff, d_ff_intra, n_layers, n_layers_intra, n_seg, n_out, seed, dtype="bf16", bias=True):
+    """Weights of the whole model: two stacks of `n_layers` layers at width d (the two IFM encoders),
+    one stack of `n_layers_intra` layers at width 2d (the IEM encoder), final linear [n_seg*2d, n_out]."""
+    m = {
+        "fwd_layers": [layer_params(d_model, d_ff, seed, l, dtype, bias) for l in range(n_layers)],
+        "bwd_layers": [layer_params(d_model, d_ff, seed, 20 + l, dtype, bias) for l in range(n_layers)],
+        "intra_layers": [layer_params(2 * d_model, d_ff_intra, seed, 40 + l, dtype, bias) for l in range(n_layers_intra)],
+        "wf": xavier_uniform(seed, 9001, n_seg * 2 * d_model, n_out),
+        "bf": (0.1 * normal(seed, 9002, (n_out,))).astype(np.float32) if bias else None,
+    }
+    if dtype == "bf16":
+        m["wf"] = to_bf16_grid(m["wf"])
+        if m["bf"] is not None:
+            m["bf"] = to_bf16_grid(m["bf"])
+    return m
+
+
 def workload(name, **overrides):
     cfg = dict(WORKLOADS[name])
     cfg.update(overrides)
