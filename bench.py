@@ -65,12 +65,120 @@ def stored_traffic(config, family):
         return None
 
 
+def bench_encoder(args, whole_model):
+    """--config c4: the 4-layer encoder forward (layer = pre-LN IM attention + GELU MLP) at the C4 shapes;
+    --config gsit: the whole GsiT forward (two IFM encoders, feature concat, IEM encoder at width 2d, last
+    steps, final linear) at the same shapes.  Forward only; value = live-block attention TFLOP/s of all layers
+    over the whole call."""
+    import numpy as np
+    import torch
+    from paper_2505_01068_amd import binding as B, synth
+
+    torch.cuda.set_device(0)
+    masks = {"ifm_forward": B.IM_IFM_FORWARD, "ifm_backward": B.IM_IFM_BACKWARD, "iem": B.IM_IEM}
+    w = synth.workload("c4")
+    g = synth.attention_inputs(**{**w, "with_dy": False})
+    dtype, tdt = g["dtype"], torch.bfloat16
+    Bsz, T, d = g["x"].shape
+    H, L, d_ff, seg = g["n_heads"], w["n_layers"], w["d_ff"], g["seg_len"]
+
+    def dev(a):
+        if a is None:
+            return None
+        t = torch.from_numpy(np.ascontiguousarray(a))
+        return (t.to(tdt) if t.dtype == torch.float32 else t).cuda()
+
+    x = dev(g["x"])
+    if whole_model:
+        m = synth.model_params(d, d_ff, 2 * d_ff, L, L, len(seg), 1, w["seed"], dtype=dtype)
+        conv = lambda layers: [{k: dev(v) for k, v in p.items()} for p in layers]
+        md = {"fwd_layers": conv(m["fwd_layers"]), "bwd_layers": conv(m["bwd_layers"]),
+              "intra_layers": conv(m["intra_layers"]), "wf": dev(m["wf"]), "bf": dev(m["bf"])}
+        scale_intra = 1.0 / np.sqrt(2 * d / H)
+        shape = B.make_shape(Bsz, seg, d, H, 0, g["scale"], dtype)
+        model = B.make_model(md, d_ff, 2 * d_ff, H, scale_intra)
+        ws = torch.empty(B.gsit_model_sizes(shape, model), dtype=torch.uint8, device="cuda")
+        out_t = torch.empty(Bsz, 1, dtype=tdt, device="cuda")
+
+        def step():
+            B.gsit_model_fwd(shape, model, x, out=out_t, workspace=ws)
+        lm_list = [(B.IM_IFM_FORWARD, d, L), (B.IM_IFM_BACKWARD, d, L), (B.IM_IEM, 2 * d, L)]
+        label = (f"gsit: whole model forward, B={Bsz} L_t/L_v/L_a={'/'.join(map(str, seg))} d={d} H={H} bf16, "
+                 f"{L}+{L} IFM layers, {L} IEM layers at width {2 * d}")
+    else:
+        lm = masks[args.mask]
+        layers = [{k: dev(v) for k, v in synth.layer_params(d, d_ff, w["seed"], l, dtype=dtype).items()} for l in range(L)]
+        shape = B.make_shape(Bsz, seg, d, H, lm, g["scale"], dtype)
+        ws = torch.empty(B.gsit_layer_sizes(shape, d_ff), dtype=torch.uint8, device="cuda")
+        bufs = [torch.empty_like(x), torch.empty_like(x)]
+
+        def step():
+            h = x
+            for l, p in enumerate(layers):
+                h = B.gsit_layer_fwd(shape, d_ff, h, p, y=bufs[l & 1], workspace=ws)
+        lm_list = [(lm, d, L)]
+        label = (f"c4: B={Bsz} L_t/L_v/L_a={'/'.join(map(str, seg))} d={d} H={H} bf16 {L}-layer encoder forward, "
+                 f"mask={args.mask}, padding=none")
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.im_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    B.im_profile_enable(False)
+    prof = B.im_profile_get()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    core = sum(4.0 * live_pairs(seg, m_, Bsz, None, None) * w_ * n_ for m_, w_, n_ in lm_list)
+    other = sum((8.0 * w_ * w_ + 4.0 * w_ * (d_ff * w_ // d)) * Bsz * T * n_ for m_, w_, n_ in lm_list)  # projections + MLP
+    per_step = {k: prof[k][0] / args.steps for k in prof if prof[k][1] > 0}
+    launches = {k: prof[k][1] / args.steps for k in prof if prof[k][1] > 0}
+    dom = "attn_fwd"
+    dom_ms = per_step[dom] / launches[dom]
+    achieved = core / launches[dom] / (dom_ms * 1e-3) / 1e12
+    out = {
+        "metric": "IM-attention fwd TFLOP/s on live blocks; % of ALU roofline",
+        "value": round(core / (ms_step * 1e-3) / 1e12, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": label, "core_gflop_per_step": round(core / 1e9, 2),
+                   "proj_mlp_gflop_per_step": round(other / 1e9, 2)},
+        "with_projection_mlp_tflops": round((core + other) / (ms_step * 1e-3) / 1e12, 3),
+        "kernel_ms_per_step": {k: round(v, 4) for k, v in per_step.items()},
+        "roofline": {"bound": "alu", "kernel": dom, "achieved": round(achieved, 3), "peak": PEAK_FP32_VALU_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_VALU_TFLOPS, 4), "traffic": None,
+                     "avg_launch_ms": round(dom_ms, 4)},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        n_sample = 4
+        t0 = time.perf_counter()
+        if whole_model:
+            oracle.gsit_model_forward(g["x"][:n_sample], m, seg, H, g["scale"], H, scale_intra)
+        else:
+            lay = [synth.layer_params(d, d_ff, w["seed"], l, dtype=dtype) for l in range(L)]
+            oracle.gsit_encoder_forward(g["x"][:n_sample], lay, seg, masks[args.mask], H, g["scale"])
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(core * n_sample / Bsz / dt / 1e12, 6), "unit": "TFLOP/s", "cores": int(cores),
+                               "kind": "oracle", "seconds": round(dt, 2),
+                               "sample": f"first {n_sample} of {Bsz} batch elements of the same workload, dense fp64 numpy oracle forward"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="c5", choices=["c2", "c3", "c5"])
+    ap.add_argument("--config", default="c5", choices=["c2", "c3", "c4", "c5", "gsit"])
     ap.add_argument("--mask", default="ifm_forward", choices=["ifm_forward", "ifm_backward", "iem"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -87,6 +195,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.config in ("c4", "gsit"):
+        return bench_encoder(args, args.config == "gsit")
     torch.cuda.set_device(0)
     masks = {"ifm_forward": B.IM_IFM_FORWARD, "ifm_backward": B.IM_IFM_BACKWARD, "iem": B.IM_IEM}
     lm = masks[args.mask]

@@ -141,6 +141,46 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
                    const void* b1, const void* w2, const void* b2, float ln_eps, const int32_t* valid_len,
                    const uint8_t* key_pad, void* y, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The GsiT model around the encoder layers (Sec. 5, Eq. "allmodalinone fusion"):
+ *   F = Enc_fwd(x) under mask_fwd and B = Enc_bwd(x) under mask_bwd (two stacks of n_layers_inter
+ *   layers of width d = shape->d_model with independent weights, shape->n_heads heads, shape->scale),
+ *   Vbar = F || B (feature concatenation, width 2d),
+ *   A = Enc_intra(Vbar) under mask_intra (n_layers_intra layers of width 2d, n_heads_intra heads,
+ *   scale_intra),
+ *   out = (|| over segments s of A[b, last step of s, :]) wf + bf          [B, n_out].
+ * The paper's masks are IM_IFM_FORWARD, IM_IFM_BACKWARD, IM_IEM; shape->live_mask is ignored.
+ * "Last step" of a segment is position max(min(valid_len[b,s], T_s), 1) - 1 when valid_len is
+ * given, else T_s - 1.  Layers as in gsit_layer_fwd.
+ * host  : shape, model and the three arrays of gsit_layer_params_t it points to.
+ * device: every pointer inside gsit_layer_params_t; wf [n_seg*2d, n_out] row-major; bf [n_out] or
+ *         NULL; x [B,T_m,d]; valid_len, key_pad as in im_attention_fwd; out [B, n_out] (dtype of
+ *         shape->dtype); workspace of gsit_model_sizes bytes.  Nothing is allocated; all work is
+ *         enqueued on hip_stream.  Errors as for gsit_layer_fwd. */
+typedef struct {
+  const void *ln1_g, *ln1_b, *wq, *wk, *wv, *wo, *bq, *bk, *bv, *bo, *ln2_g, *ln2_b, *w1, *b1, *w2, *b2;
+} gsit_layer_params_t;
+
+typedef struct {
+  int32_t n_layers_inter;  /* layers of each of the two inter-modal (IFM) encoders, >= 1 */
+  int32_t n_layers_intra;  /* layers of the intra-modal (IEM) encoder, >= 1 */
+  int32_t d_ff_inter;      /* hidden width of the MLPs at width d */
+  int32_t d_ff_intra;      /* hidden width of the MLPs at width 2d */
+  int32_t n_heads_intra;   /* heads at width 2d; must divide 2d */
+  int32_t n_out;           /* outputs of the final linear f */
+  float scale_intra;       /* score scale at width 2d, normally 1/sqrt(2d / n_heads_intra) */
+  float ln_eps;
+  uint64_t mask_fwd, mask_bwd, mask_intra;
+  const gsit_layer_params_t* fwd_layers;    /* host array [n_layers_inter] */
+  const gsit_layer_params_t* bwd_layers;    /* host array [n_layers_inter] */
+  const gsit_layer_params_t* intra_layers;  /* host array [n_layers_intra], width 2d */
+  const void* wf;
+  const void* bf;
+} gsit_model_t;
+
+int gsit_model_sizes(const im_shape_t* shape, const gsit_model_t* model, size_t* workspace_bytes);
+int gsit_model_fwd(const im_shape_t* shape, const gsit_model_t* model, const void* x, const int32_t* valid_len,
+                   const uint8_t* key_pad, void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Kernel timing for benchmarks (off by default).  While enabled, the library
  * brackets each kernel family it launches with hipEvents recorded on the call's
  * stream.  im_profile_get synchronises on the recorded events, so call it after

@@ -61,8 +61,11 @@ def lib():
         L.im_profile_get.argtypes = [C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.im_profile_enable.restype = C.c_int
         L.im_profile_get.restype = C.c_int
+        L.gsit_model_sizes.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_size_t)]
+        L.gsit_model_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_size_t, C.c_void_p]
         for f in (L.im_schedule_build, L.im_attention_sizes, L.im_attention_fwd, L.im_attention_bwd,
-                  L.gsit_layer_sizes, L.gsit_layer_fwd):
+                  L.gsit_layer_sizes, L.gsit_layer_fwd, L.gsit_model_sizes, L.gsit_model_fwd):
             f.restype = C.c_int
         _lib = L
     return _lib
@@ -146,6 +149,66 @@ def gsit_layer_fwd(shape, d_ff, x, p, ln_eps=1e-5, valid_len=None, key_pad=None,
                                 _p(g("b2")), float(ln_eps), _p(valid_len), _p(key_pad), _p(y), _p(workspace), wbytes,
                                 _stream()))
     return y
+
+
+LAYER_FIELDS = ("ln1_g", "ln1_b", "wq", "wk", "wv", "wo", "bq", "bk", "bv", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
+
+
+class GsitLayerParams(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in LAYER_FIELDS]
+
+
+class GsitModel(C.Structure):
+    _fields_ = [("n_layers_inter", C.c_int32), ("n_layers_intra", C.c_int32), ("d_ff_inter", C.c_int32),
+                ("d_ff_intra", C.c_int32), ("n_heads_intra", C.c_int32), ("n_out", C.c_int32),
+                ("scale_intra", C.c_float), ("ln_eps", C.c_float),
+                ("mask_fwd", C.c_uint64), ("mask_bwd", C.c_uint64), ("mask_intra", C.c_uint64),
+                ("fwd_layers", C.POINTER(GsitLayerParams)), ("bwd_layers", C.POINTER(GsitLayerParams)),
+                ("intra_layers", C.POINTER(GsitLayerParams)), ("wf", C.c_void_p), ("bf", C.c_void_p)]
+
+
+def _layer_array(layers):
+    arr = (GsitLayerParams * len(layers))()
+    for i, p in enumerate(layers):
+        for n in LAYER_FIELDS:
+            t = p.get(n)
+            setattr(arr[i], n, None if t is None else t.data_ptr())
+    return arr
+
+
+def make_model(model, d_ff_inter, d_ff_intra, n_heads_intra, scale_intra, ln_eps=1e-5,
+               mask_fwd=0x062, mask_bwd=0x08C, mask_intra=0x111):
+    """gsit_model_t from a dict of device tensors: fwd_layers / bwd_layers / intra_layers (lists of
+    layer dicts as for gsit_layer_fwd), wf, bf.  The returned object keeps the arrays alive."""
+    m = GsitModel()
+    m._keep = (_layer_array(model["fwd_layers"]), _layer_array(model["bwd_layers"]), _layer_array(model["intra_layers"]), model)
+    m.n_layers_inter, m.n_layers_intra = len(model["fwd_layers"]), len(model["intra_layers"])
+    if len(model["bwd_layers"]) != m.n_layers_inter:
+        raise ValueError("the two inter-modal encoders must have the same number of layers")
+    m.d_ff_inter, m.d_ff_intra, m.n_heads_intra = int(d_ff_inter), int(d_ff_intra), int(n_heads_intra)
+    m.n_out = int(model["wf"].shape[1])
+    m.scale_intra, m.ln_eps = float(scale_intra), float(ln_eps)
+    m.mask_fwd, m.mask_bwd, m.mask_intra = int(mask_fwd), int(mask_bwd), int(mask_intra)
+    m.fwd_layers, m.bwd_layers, m.intra_layers = m._keep[0], m._keep[1], m._keep[2]
+    m.wf = model["wf"].data_ptr()
+    m.bf = None if model.get("bf") is None else model["bf"].data_ptr()
+    return m
+
+
+def gsit_model_sizes(shape, model):
+    a = C.c_size_t(0)
+    _check(lib().gsit_model_sizes(C.byref(shape), C.byref(model), C.byref(a)))
+    return a.value
+
+
+def gsit_model_fwd(shape, model, x, valid_len=None, key_pad=None, out=None, workspace=None):
+    """out [B, n_out] = GsiT(x): two IFM encoders, feature concat, IEM encoder, last steps, final linear."""
+    if out is None:
+        out = torch.empty(x.shape[0], model.n_out, dtype=x.dtype, device=x.device)
+    wbytes = 0 if workspace is None else workspace.numel()
+    _check(lib().gsit_model_fwd(C.byref(shape), C.byref(model), _p(x), _p(valid_len), _p(key_pad), _p(out),
+                                _p(workspace), wbytes, _stream()))
+    return out
 
 
 def im_profile_enable(on):

@@ -18,7 +18,8 @@ def test_every_declared_symbol_is_exported():
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = re.findall(r"^\s*(?:const\s+char\s*\*|int)\s+(\w+)\s*\(", hdr, flags=re.M)
     assert set(names) >= {"im_attention_fwd", "im_attention_bwd", "gsit_layer_fwd", "im_attention_sizes",
-                          "gsit_layer_sizes", "im_schedule_build", "im_last_error", "im_version"}
+                          "gsit_layer_sizes", "gsit_model_sizes", "gsit_model_fwd", "im_schedule_build", "im_last_error",
+                          "im_version"}
     L = B.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -80,6 +81,30 @@ def test_null_pointers_and_small_workspace_fail_before_any_launch():
     assert rc == -1
     rc = L.gsit_layer_fwd(C.byref(s), 0, *([one] * 17), 1e-5, None, None, one, one, 1 << 30, None)
     assert rc == -1
+
+
+def test_model_entry_rejects_bad_arguments_on_the_host():
+    L = B.lib()
+    s = shape()
+    one = C.c_void_p(256)
+    lay = (B.GsitLayerParams * 1)()
+    m = B.GsitModel()
+    m.n_layers_inter = m.n_layers_intra = 1
+    m.d_ff_inter, m.d_ff_intra, m.n_heads_intra, m.n_out = 64, 128, 4, 3
+    m.scale_intra, m.ln_eps = 0.25, 1e-5
+    m.mask_fwd, m.mask_bwd, m.mask_intra = B.IM_IFM_FORWARD, B.IM_IFM_BACKWARD, B.IM_IEM
+    m.fwd_layers = m.bwd_layers = m.intra_layers = lay
+    m.wf = 256
+    n = C.c_size_t(0)
+    assert L.gsit_model_sizes(C.byref(s), C.byref(m), C.byref(n)) == 0 and n.value > 0
+    assert L.gsit_model_fwd(C.byref(s), C.byref(m), one, None, None, one, one, 16, None) == -3
+    assert L.gsit_model_fwd(C.byref(s), C.byref(m), None, None, None, one, one, n.value, None) == -1
+    m.n_heads_intra = 5                       # does not divide 2d = 64
+    assert L.gsit_model_sizes(C.byref(s), C.byref(m), C.byref(n)) == -1 and b"n_heads_intra" in L.im_last_error()
+    m.n_heads_intra, m.n_layers_intra = 4, 0
+    assert L.gsit_model_sizes(C.byref(s), C.byref(m), C.byref(n)) == -1
+    m.n_layers_intra, m.mask_intra = 1, 1 << 9   # bit outside the 3 x 3 pattern
+    assert L.gsit_model_sizes(C.byref(s), C.byref(m), C.byref(n)) == -1
 
 
 @pytest.mark.parametrize("seg", [(50, 375, 500), (50, 500, 500), (39, 400, 55), (30, 230, 480), (8, 8, 8), (512, 2048, 2048)])
