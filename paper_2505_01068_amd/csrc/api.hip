@@ -207,8 +207,12 @@ static int fwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
   p.B[0] = wq; p.B[1] = wk; p.B[2] = wv; p.sbk = d; p.sbn = 1; p.b_split = 1; p.n_per = (int)d;
   p.bias[0] = bq; p.bias[1] = bk; p.bias[2] = bv; p.bias_split = 1;
   p.C[0] = qkv; p.ldc = 3 * d; p.M = (int)R; p.N = (int)(3 * d); p.K = (int)d;
-  int rc;
-  { ProfScope ps(PF_PROJ_FWD, st); rc = launch_gemm_alu(p, bf, bf, bf, st); }
+  int rc = IM_OK;
+  // bf16 projections go to the matrix cores whenever the widths allow 16-byte chunks
+  const bool mm = mfma_linear_ok(bf, d, d);
+  { ProfScope ps(PF_PROJ_FWD, st);
+    if (mm) mfma_linear(x, d, wq, wk, wv, d, (int)d, bq, bk, bv, 0, nullptr, qkv, 3 * d, (int)R, (int)(3 * d), (int)d, st);
+    else rc = launch_gemm_alu(p, bf, bf, bf, st); }
   if (rc) return rc;
 
   { ProfScope ps(PF_ATTN_FWD, st);
@@ -220,7 +224,8 @@ static int fwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
   p.A = o; p.sam = d; p.sak = 1;
   p.B[0] = wo; p.sbk = d; p.sbn = 1;
   p.bias[0] = bo; p.C[0] = y; p.ldc = d; p.res = res; p.M = (int)R; p.N = (int)d; p.K = (int)d;
-  rc = launch_gemm_alu(p, bf, bf, bf, st);
+  if (mm) mfma_linear(o, d, wo, nullptr, nullptr, d, (int)d, bo, nullptr, nullptr, 0, res, y, d, (int)R, (int)d, (int)d, st);
+  else rc = launch_gemm_alu(p, bf, bf, bf, st);
   if (rc) return rc;
   return check_hip("im_attention_fwd launch");
 }
@@ -484,6 +489,12 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
   if (rc) return rc;
   if ((rc = launch_layernorm(h, ln2_g, ln2_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
   // z = GELU(u W1 + b1);  y = h + z W2 + b2
+  if (mfma_linear_ok(bf, d, d_ff) && mfma_linear_ok(bf, d_ff, d)) {
+    ProfScope ps(PF_MISC, st);
+    mfma_linear(u, d, w1, nullptr, nullptr, d_ff, d_ff, b1, nullptr, nullptr, 1, nullptr, z, d_ff, (int)R, d_ff, (int)d, st);
+    mfma_linear(z, d_ff, w2, nullptr, nullptr, d, (int)d, b2, nullptr, nullptr, 0, h, y, d, (int)R, (int)d, d_ff, st);
+    return check_hip("gsit_layer_fwd launch");
+  }
   GemmDesc p;
   memset(&p, 0, sizeof(p));
   p.A = u; p.sam = d; p.sak = 1; p.B[0] = w1; p.sbk = d_ff; p.sbn = 1; p.bias[0] = b1;

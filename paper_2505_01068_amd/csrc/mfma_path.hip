@@ -50,6 +50,22 @@ static void init_gemm(MGemm* p) {
   p->split_k = 1;
 }
 
+void mfma_linear(const void* A, long lda, const void* w0, const void* w1, const void* w2, long ldb, int n_per,
+                 const void* b0, const void* b1, const void* b2, int gelu, const void* res, void* C, long ldc, int M,
+                 int N, int K, hipStream_t st) {
+  MGemm p;
+  init_gemm(&p);
+  p.A = (const bf16_t*)A; p.lda = lda;
+  p.B[0] = (const bf16_t*)w0; p.B[1] = (const bf16_t*)w1; p.B[2] = (const bf16_t*)w2; p.ldb = ldb;
+  p.b_kmajor = 1; p.b_nper = (w1 || w2) ? n_per : 0;
+  p.M = M; p.N = N; p.K = K;
+  p.bias[0] = (const bf16_t*)b0; p.bias[1] = (const bf16_t*)b1; p.bias[2] = (const bf16_t*)b2; p.n_per = n_per;
+  p.gelu = gelu;
+  p.res = (const bf16_t*)res;
+  p.C = (bf16_t*)C; p.ldc = ldc;
+  launch_mfma_gemm(p, st);
+}
+
 int mfma_attention_fwd(const im_shape_t* s, const void* x, const void* wq, const void* wk, const void* wv,
                        const void* wo, const void* bq, const void* bk, const void* bv, const void* bo,
                        const int32_t* valid_len, const uint8_t* key_pad, void* y, const void* res, char* sv,

@@ -19,6 +19,12 @@ struct MGemm {
   bf16_t* C; long ldc;                   // row-major output
 };
 void launch_mfma_gemm(const MGemm& p, hipStream_t st);
+// bf16 linear layer C[M,N] = A[M,K] W + bias (+ GELU) (+ residual) with weights stored [K][N] (k-major),
+// optionally three weight / bias blocks of n_per columns each.  Usable when K % 8 == 0 and N % 8 == 0.
+inline bool mfma_linear_ok(int is_bf16, long K, long N) { return is_bf16 && K % 8 == 0 && N % 8 == 0 && K >= 8 && N >= 8; }
+void mfma_linear(const void* A, long lda, const void* w0, const void* w1, const void* w2, long ldb, int n_per,
+                 const void* b0, const void* b1, const void* b2, int gelu, const void* res, void* C, long ldc, int M,
+                 int N, int K, hipStream_t st);
 int mfma_gemm_split(int M, int N, int K);
 void launch_splitk_reduce(const float* partial, int split_k, int M, int N, float* o0, float* o1, float* o2, int n_per,
                           hipStream_t st);
