@@ -96,6 +96,16 @@ static Path pick_path(const im_shape_t* s) {
   if (rowlane_supports(dh)) return PATH_ROWLANE;
   return PATH_NONE;
 }
+// Inference (nothing saved for a backward) at bf16 head dims 8 / 16 with d % 64 == 0 can run the
+// matrix-core forward in its sub-head mode instead of the row-per-lane kernel.
+static bool subhead_forward(const im_shape_t* s) {
+  const int dh = s->d_model / s->n_heads;
+  if (s->dtype != IM_DTYPE_BF16 || (dh != 8 && dh != 16) || s->d_model % 64 != 0) return false;
+  long max_seg = 0;
+  for (int i = 0; i < s->n_seg; ++i) max_seg = s->seg_len[i] > max_seg ? s->seg_len[i] : max_seg;
+  return max_seg * 3L * s->d_model * 2L < (1L << 31) && 3L * s->d_model * 2L < (1L << 24);
+}
+
 static int check_supported(const im_shape_t* s) {
   if (pick_path(s) == PATH_NONE)
     return fail(IM_ERR_UNSUPPORTED,
@@ -398,7 +408,7 @@ int im_attention_fwd(const im_shape_t* shape, const void* x, const void* wq, con
     return fail(IM_ERR_WORKSPACE, "im_attention_fwd needs %zu workspace bytes, got %zu", need, workspace_bytes);
   char* sv = saved ? (char*)saved : (char*)workspace;
   char* ws = saved ? (char*)workspace : (char*)workspace + L.total;
-  if (path == PATH_MFMA)
+  if (path == PATH_MFMA || (!saved && subhead_forward(shape)))
     return mfma_attention_fwd(shape, x, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, y, nullptr, sv, L.qkv,
                               L.o, L.lse, L.extra, ws, as_stream(hip_stream));
   return fwd_rowlane(shape, x, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, y, nullptr, sv,
@@ -481,7 +491,7 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
   if ((rc = launch_layernorm(x, ln1_g, ln1_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
   // h = x + IMAttention(u)
   const SavedLayout L = saved_layout(shape);
-  if (pick_path(shape) == PATH_MFMA)
+  if (pick_path(shape) == PATH_MFMA || subhead_forward(shape))
     rc = mfma_attention_fwd(shape, u, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, h, x, aw, L.qkv, L.o, L.lse,
                             L.extra, aw + L.total, st);
   else

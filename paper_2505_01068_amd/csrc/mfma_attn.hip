@@ -99,7 +99,15 @@ __device__ __forceinline__ void ring_wait(int later) {
 
 // ------------------------------------------------------------------------------------------
 // Forward.  Workgroup = 4 waves; each wave owns QB blocks of 32 query rows.
-template <int QB>
+//
+// DH = 64: one head = one 64-column group of the activation rows.
+// DH = 8 or 16 ("sub-head" mode, d % 64 == 0): a head is a slice of a 64-column group.  The K/V
+// tiles of the whole group are streamed as before; S^T needs only the one 16-deep k-step that
+// holds the head's columns (for DH = 8 the Q operand of the other lane half is zero), and
+// O^T only the one 32-row block of V^T that holds them.  Per 64-key tile that is 2 + 4 MFMAs per
+// query block instead of 8 + 8, and the softmax stays on 32 x 32 accumulator tiles -- about a
+// quarter of the VALU instructions of the row-per-lane kernel at these head sizes.
+template <int QB, int DH>
 __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
                                                        const int32_t* __restrict__ valid_len,
                                                        const uint8_t* __restrict__ key_pad, bf16_t* __restrict__ O,
@@ -115,26 +123,37 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
   const int d = g.d;
   const float c = fmaxf(g.scale_log2e, 1e-30f);  // > 0 so that -inf * c stays -inf when scale == 0
 
+  constexpr int NS = DH == 64 ? 4 : 1;    // k-steps of S^T
+  constexpr int NDB = DH == 64 ? 2 : 1;   // 32-row blocks of O^T
+  const int cg = (h * DH) >> 6;           // 64-column group of this head
+  const int wo = (h * DH) & 63;           // first column of the head inside the group
+  const int s0 = DH == 64 ? 0 : wo >> 4;  // k-step and O^T block that hold the head (sub-head mode)
+  const int db0 = DH == 64 ? 0 : wo >> 5;
+
   // Q operand (B of S^T = K Q^T): lane holds query row lo of each block, 8 consecutive dh per k-step
-  bf16x8 qreg[QB][4];
+  bf16x8 qreg[QB][NS];
   int qrow[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     qrow[qb] = q0 + (wave * QB + qb) * 32 + lo;
     const int rc = min(qrow[qb], qlen - 1);
-    const bf16_t* p = QKV + ((long)b * g.T + g.seg_off[qs] + rc) * ld + h * 64 + hi * 8;
+    const bf16_t* p = QKV + ((long)b * g.T + g.seg_off[qs] + rc) * ld + cg * 64 + hi * 8;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) qreg[qb][s] = as_bf16x8(*(const u32x4*)(p + s * 16));
+    for (int s = 0; s < NS; ++s) {
+      u32x4 v = *(const u32x4*)(p + (s0 + s) * 16);
+      if (DH == 8 && hi != ((wo >> 3) & 1)) v = u32x4{0u, 0u, 0u, 0u};  // the other head of this k-step
+      qreg[qb][s] = as_bf16x8(v);
+    }
   }
 
-  f32x16 oacc[2][QB];
+  f32x16 oacc[NDB][QB];
   float m[QB], l[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     m[qb] = IM_NEG_INF;
     l[qb] = 0.f;
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[db][qb][r] = 0.f;
   }
@@ -146,7 +165,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-    for (int s = 0; s < 4; ++s) asm volatile("" :: "v"(qreg[qb][s]));
+    for (int s = 0; s < NS; ++s) asm volatile("" :: "v"(qreg[qb][s]));
 
   // key tiles of the live key segments; a segment contributes its first min(length, valid length) keys
   auto klen_of = [&](int j) {
@@ -154,7 +173,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
     if (valid_len) n = min(n, max(0, valid_len[b * g.n_seg + j]));
     return n;
   };
-  const RingLane rl = ring_lane(wave, lane, h);
+  const RingLane rl = ring_lane(wave, lane, cg);
   const unsigned ldb = (unsigned)ld * 2u;
   TileCursor ic = {g.q_live[qs], 0, 0, 0}, cc = ic;
   cursor_next_seg(ic, klen_of);
@@ -188,8 +207,8 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
 #pragma unroll
           for (int r = 0; r < 16; ++r) sacc[kb][qb][r] = 0.f;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const bf16x8 a = lds_frag_sw(sK, kb * 32, prow, 2 * s + hi);
+        for (int s = 0; s < NS; ++s) {
+          const bf16x8 a = lds_frag_sw(sK, kb * 32, prow, 2 * (s0 + s) + hi);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) sacc[kb][qb] = mfma32(a, qreg[qb][s], sacc[kb][qb]);
         }
@@ -227,7 +246,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
           const float alpha = (m[qb] == IM_NEG_INF) ? 0.f : fast_exp2((m[qb] - mn) * c);
           l[qb] *= alpha;
 #pragma unroll
-          for (int db = 0; db < 2; ++db)
+          for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
           m[qb] = mn;
@@ -249,10 +268,10 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
       }
       // ---- O^T += V^T P^T ----
 #pragma unroll
-      for (int db = 0; db < 2; ++db)
+      for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const bf16x8 a = lds_frag_tr_sw(sV, s * 16, db * 32, lane);
+          const bf16x8 a = lds_frag_tr_sw(sV, s * 16, (db0 + db) * 32, lane);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) oacc[db][qb] = mfma32(a, pb[s >> 1][qb][s & 1], oacc[db][qb]);
         }
@@ -269,15 +288,16 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
     const long t = (long)b * g.T + g.seg_off[qs] + row;
     if (hi == 0 && lse2) lse2[((long)b * g.H + h) * g.T + g.seg_off[qs] + row] = lt > 0.f ? fmaf(m[qb], c, log2f(lt)) : __builtin_inff();
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int dh0 = db * 32 + 8 * i + 4 * hi;
+        const int dh0 = (db0 + db) * 32 + 8 * i + 4 * hi;  // column inside the 64-column group
+        if (DH < 64 && (dh0 < wo || dh0 >= wo + DH)) continue;
         float v[4];
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) v[jj] = oacc[db][qb][4 * i + jj] * inv;
         const u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-        *(u32x2*)(O + t * ldo + h * 64 + dh0) = pk;
+        *(u32x2*)(O + t * ldo + cg * 64 + dh0) = pk;
       }
   }
 }
@@ -669,8 +689,10 @@ void launch_mfma_fwd(const Geo& g, const bf16_t* qkv, long ld, const int32_t* va
   const int nt = g.q_tile_prefix[g.q_nord];
   if (nt == 0) return;
   ProfScope ps(PF_ATTN_FWD, st);
-  hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB>), dim3(nt, g.H, g.B), dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o,
-                     ldo, lse2);
+  const dim3 grid(nt, g.H, g.B);
+  if (g.dh == 64) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB, 64>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  else if (g.dh == 16) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB, 16>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  else hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB, 8>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
 }
 
 void launch_mfma_bwd(const Geo& g, const bf16_t* qkv, long ld, const bf16_t* o, const bf16_t* d_o, long ldo,

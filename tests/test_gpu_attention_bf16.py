@@ -162,3 +162,20 @@ def test_mfma_pattern_variants_fwd_bwd(name):
     say(f"[case] mfma pattern variant {name} fwd+bwd")
     g = synth.attention_inputs(2, (70, 200, 130), 128, 2, "bf16", "valid_len", seed=20250512, bias=True)
     Problem(g, oracle.NAMED_PATTERNS[name]).check(what=f"mfma-variant/{name}")
+
+
+@pytest.mark.parametrize("d,H", [(64, 8), (128, 8), (128, 16), (192, 12)])
+@pytest.mark.parametrize("name", ["ifm_forward", "iem", "self_only", "dense"])
+@pytest.mark.parametrize("padding", ["none", "valid_len", "key_pad"])
+def test_subhead_inference_forward(d, H, name, padding):
+    # inference (nothing saved) at head dims 8 / 16: the matrix-core forward in its sub-head mode,
+    # several heads per 64-column group, ragged segments and tails
+    say(f"[case] sub-head inference d={d} H={H} pattern={name} padding={padding}")
+    g = synth.attention_inputs(2, (37, 201, 130), d, H, "bf16", padding, seed=29, bias=True, with_dy=False)
+    p = Problem(g, oracle.NAMED_PATTERNS[name])
+    y = p.fwd(save=False)
+    torch.cuda.synchronize()
+    assert_close(y, p.oracle_fwd(), TOL["bf16"], f"subhead/{d}/{H}/{name}/{padding}")
+    y_train = p.fwd(save=True)       # the training forward (row-per-lane kernels) must agree closely
+    torch.cuda.synchronize()
+    assert_close(y, y_train.float().cpu().numpy(), TOL["bf16"], "subhead vs training forward")
