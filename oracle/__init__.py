@@ -16,5 +16,7 @@ from .im_attention import (  # noqa: F401
     live_mask_from_edges, segment_of_rows, key_invalid, additive_mask,
     project_qkv, forward, backward, mult_blocks_forward, live_pair_count,
 )
-from .gsit_layer import layer_norm, gelu, gsit_layer_forward, gsit_encoder_forward  # noqa: F401
+from .gsit_layer import (  # noqa: F401
+    layer_norm, gelu, gelu_grad, layer_norm_backward, gsit_layer_forward, gsit_layer_backward, gsit_encoder_forward,
+)
 from .gsit_model import gsit_model_forward, last_steps  # noqa: F401
