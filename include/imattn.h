@@ -177,6 +177,29 @@ typedef struct {
   const void* bf;
 } gsit_model_t;
 
+/* Encoder layer, training.  gsit_layer_fwd_train computes the same y as gsit_layer_fwd and fills
+ * `saved` (the attention's saved tensors, h = x + attention, the MLP's pre-activation and
+ * activation); gsit_layer_bwd is the gradient of that forward (the calculus of the layer of Sec. 5;
+ * the paper analyses no backward pass): given dy [B,T_m,d] it overwrites dx [B,T_m,d] (dtype of
+ * shape->dtype) and, for every non-NULL field of `grads`, the fp32 gradient of the parameter of
+ * the same name (shapes of the parameters; not accumulated).  A bias gradient may only be
+ * requested when that bias was given.  Deterministic (fixed-order reductions).
+ * host  : shape, params, grads (structs of device pointers).
+ * device: x, dy, saved (gsit_layer_train_sizes' saved_bytes, written by the forward and read by the
+ *         backward), y, dx, workspace (workspace_bytes of gsit_layer_train_sizes covers both calls).
+ * Errors as for gsit_layer_fwd. */
+typedef struct {
+  void *ln1_g, *ln1_b, *wq, *wk, *wv, *wo, *bq, *bk, *bv, *bo, *ln2_g, *ln2_b, *w1, *b1, *w2, *b2;
+} gsit_layer_grads_t;
+
+int gsit_layer_train_sizes(const im_shape_t* shape, int32_t d_ff, size_t* saved_bytes, size_t* workspace_bytes);
+int gsit_layer_fwd_train(const im_shape_t* shape, int32_t d_ff, const void* x, const gsit_layer_params_t* params,
+                         float ln_eps, const int32_t* valid_len, const uint8_t* key_pad, void* y, void* saved,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const gsit_layer_params_t* params, float ln_eps,
+                   const int32_t* valid_len, const uint8_t* key_pad, const void* saved, const void* dy, void* dx,
+                   const gsit_layer_grads_t* grads, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 int gsit_model_sizes(const im_shape_t* shape, const gsit_model_t* model, size_t* workspace_bytes);
 int gsit_model_fwd(const im_shape_t* shape, const gsit_model_t* model, const void* x, const int32_t* valid_len,
                    const uint8_t* key_pad, void* out, void* workspace, size_t workspace_bytes, void* hip_stream);

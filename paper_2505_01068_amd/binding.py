@@ -61,11 +61,17 @@ def lib():
         L.im_profile_get.argtypes = [C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.im_profile_enable.restype = C.c_int
         L.im_profile_get.restype = C.c_int
+        L.gsit_layer_train_sizes.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        L.gsit_layer_fwd_train.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.gsit_layer_bwd.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.gsit_model_sizes.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_size_t)]
         L.gsit_model_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_size_t, C.c_void_p]
         for f in (L.im_schedule_build, L.im_attention_sizes, L.im_attention_fwd, L.im_attention_bwd,
-                  L.gsit_layer_sizes, L.gsit_layer_fwd, L.gsit_model_sizes, L.gsit_model_fwd):
+                  L.gsit_layer_sizes, L.gsit_layer_fwd, L.gsit_model_sizes, L.gsit_model_fwd,
+                  L.gsit_layer_train_sizes, L.gsit_layer_fwd_train, L.gsit_layer_bwd):
             f.restype = C.c_int
         _lib = L
     return _lib
@@ -193,6 +199,41 @@ def make_model(model, d_ff_inter, d_ff_intra, n_heads_intra, scale_intra, ln_eps
     m.wf = model["wf"].data_ptr()
     m.bf = None if model.get("bf") is None else model["bf"].data_ptr()
     return m
+
+
+def _layer_struct(p):
+    st = GsitLayerParams()
+    for n in LAYER_FIELDS:
+        t = p.get(n)
+        setattr(st, n, None if t is None else t.data_ptr())
+    return st
+
+
+def gsit_layer_train_sizes(shape, d_ff):
+    a, b = C.c_size_t(0), C.c_size_t(0)
+    _check(lib().gsit_layer_train_sizes(C.byref(shape), int(d_ff), C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def gsit_layer_fwd_train(shape, d_ff, x, p, saved, ln_eps=1e-5, valid_len=None, key_pad=None, y=None, workspace=None):
+    """Training forward of one encoder layer: y as gsit_layer_fwd, `saved` filled for gsit_layer_bwd."""
+    if y is None:
+        y = torch.empty_like(x)
+    st = _layer_struct(p)
+    _check(lib().gsit_layer_fwd_train(C.byref(shape), int(d_ff), _p(x), C.byref(st), float(ln_eps), _p(valid_len),
+                                      _p(key_pad), _p(y), _p(saved), _p(workspace), workspace.numel(), _stream()))
+    return y
+
+
+def gsit_layer_bwd(shape, d_ff, x, p, saved, dy, grads, ln_eps=1e-5, valid_len=None, key_pad=None, dx=None, workspace=None):
+    """Backward of one encoder layer.  `grads` maps parameter names to fp32 device tensors to overwrite
+    (missing / None = not wanted).  Returns dx."""
+    if dx is None:
+        dx = torch.empty_like(x)
+    st, gs = _layer_struct(p), _layer_struct(grads)
+    _check(lib().gsit_layer_bwd(C.byref(shape), int(d_ff), _p(x), C.byref(st), float(ln_eps), _p(valid_len), _p(key_pad),
+                                _p(saved), _p(dy), _p(dx), C.byref(gs), _p(workspace), workspace.numel(), _stream()))
+    return dx
 
 
 def gsit_model_sizes(shape, model):

@@ -517,4 +517,187 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
   return check_hip("gsit_layer_fwd launch");
 }
 
+
+// ---- encoder layer, training: forward that saves what the backward needs, and the backward ----
+
+struct LayerTrain {
+  size_t att, h, zpre, a, saved_total;                                   // saved
+  size_t u, v, dz, dv, dh, t, partial, cpart, attws, ws_total;           // backward workspace
+  size_t fwd_ws_total;                                                   // forward workspace: u
+  int split_w1, split_w2;
+  size_t aws_bytes;
+};
+static LayerTrain layer_train_layout(const im_shape_t* s, int32_t d_ff) {
+  LayerTrain L;
+  const size_t es = s->dtype == IM_DTYPE_BF16 ? 2 : 4;
+  long T = 0;
+  for (int i = 0; i < s->n_seg; ++i) T += s->seg_len[i];
+  const size_t R = (size_t)s->batch * T, d = s->d_model, f = (size_t)d_ff;
+  size_t off = 0;
+  L.att = off; off += align256(saved_layout(s).total);
+  L.h = off; off += align256(R * d * es);
+  L.zpre = off; off += align256(R * f * es);
+  L.a = off; off += align256(R * f * es);
+  L.saved_total = off;
+  off = 0;
+  L.u = off; off += align256(R * d * es);
+  L.fwd_ws_total = off + align256(pick_path(s) == PATH_MFMA ? mfma_fwd_workspace_bytes(s->d_model) : 0);
+  L.v = off; off += align256(R * d * es);
+  L.dz = off; off += align256(R * f * es);
+  L.dv = off; off += align256(R * d * es);
+  L.dh = off; off += align256(R * d * es);
+  L.t = off; off += align256(R * d * es);
+  L.split_w1 = L.split_w2 = 1;
+  const size_t p1 = gemm_alu_partial_bytes((int)d, d_ff, (int)R, &L.split_w1);
+  const size_t p2 = gemm_alu_partial_bytes(d_ff, (int)d, (int)R, &L.split_w2);
+  L.partial = off; off += align256(std::max(p1, p2));
+  L.cpart = off; off += align256(colsum_partial_bytes((int)R, (int)std::max(d, f)));
+  L.aws_bytes = bwd_workspace_bytes(s);
+  L.attws = off; off += align256(L.aws_bytes);
+  L.ws_total = off;
+  return L;
+}
+
+int gsit_layer_train_sizes(const im_shape_t* shape, int32_t d_ff, size_t* saved_bytes, size_t* workspace_bytes) {
+  int rc = layer_check(shape, d_ff);
+  if (rc) return rc;
+  const LayerTrain L = layer_train_layout(shape, d_ff);
+  if (saved_bytes) *saved_bytes = L.saved_total;
+  if (workspace_bytes) *workspace_bytes = std::max(L.ws_total, L.fwd_ws_total);
+  return IM_OK;
+}
+
+int gsit_layer_fwd_train(const im_shape_t* shape, int32_t d_ff, const void* x, const gsit_layer_params_t* p, float ln_eps,
+                         const int32_t* valid_len, const uint8_t* key_pad, void* y, void* saved, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+  int rc = layer_check(shape, d_ff);
+  if (rc) return rc;
+  if (!x || !p || !y || !saved) return fail(IM_ERR_INVALID, "x, params, y and saved must not be NULL");
+  if (!p->ln1_g || !p->ln1_b || !p->wq || !p->wk || !p->wv || !p->wo || !p->ln2_g || !p->ln2_b || !p->w1 || !p->w2)
+    return fail(IM_ERR_INVALID, "LayerNorm parameters, wq, wk, wv, wo, w1 and w2 must not be NULL");
+  if (!(ln_eps >= 0.f)) return fail(IM_ERR_INVALID, "ln_eps must be >= 0");
+  const LayerTrain L = layer_train_layout(shape, d_ff);
+  if (!workspace || workspace_bytes < L.fwd_ws_total)
+    return fail(IM_ERR_WORKSPACE, "gsit_layer_fwd_train needs %zu workspace bytes, got %zu", L.fwd_ws_total, workspace_bytes);
+  hipStream_t st = as_stream(hip_stream);
+  const int bf = shape->dtype == IM_DTYPE_BF16;
+  long T = 0;
+  for (int i = 0; i < shape->n_seg; ++i) T += shape->seg_len[i];
+  const long R = (long)shape->batch * T, d = shape->d_model;
+  char* sv = (char*)saved;
+  char* ws = (char*)workspace;
+  void* u = ws + L.u;
+  void* h = sv + L.h;
+  void* zpre = sv + L.zpre;
+  void* a = sv + L.a;
+
+  if ((rc = launch_layernorm(x, p->ln1_g, p->ln1_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
+  const SavedLayout A = saved_layout(shape);
+  if (pick_path(shape) == PATH_MFMA)
+    rc = mfma_attention_fwd(shape, u, p->wq, p->wk, p->wv, p->wo, p->bq, p->bk, p->bv, p->bo, valid_len, key_pad, h, x,
+                            sv + L.att, A.qkv, A.o, A.lse, A.extra, ws + L.u + align256((size_t)R * d * (bf ? 2 : 4)), st);
+  else
+    rc = fwd_rowlane(shape, u, p->wq, p->wk, p->wv, p->wo, p->bq, p->bk, p->bv, p->bo, valid_len, key_pad, h, x,
+                     sv + L.att, st);
+  if (rc) return rc;
+  if ((rc = launch_layernorm(h, p->ln2_g, p->ln2_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
+  if (mfma_linear_ok(bf, d, d_ff) && mfma_linear_ok(bf, d_ff, d)) {
+    mfma_linear(u, d, p->w1, nullptr, nullptr, d_ff, d_ff, p->b1, nullptr, nullptr, 0, nullptr, zpre, d_ff, (int)R, d_ff, (int)d, st);
+    if ((rc = launch_gelu_fwd(zpre, a, R * (long)d_ff, bf, st))) return rc;
+    mfma_linear(a, d_ff, p->w2, nullptr, nullptr, d, (int)d, p->b2, nullptr, nullptr, 0, h, y, d, (int)R, (int)d, d_ff, st);
+    return check_hip("gsit_layer_fwd_train launch");
+  }
+  GemmDesc g;
+  memset(&g, 0, sizeof(g));
+  g.A = u; g.sam = d; g.sak = 1; g.B[0] = p->w1; g.sbk = d_ff; g.sbn = 1; g.bias[0] = p->b1;
+  g.C[0] = zpre; g.ldc = d_ff; g.M = (int)R; g.N = d_ff; g.K = (int)d;
+  if ((rc = launch_gemm_alu(g, bf, bf, bf, st))) return rc;
+  if ((rc = launch_gelu_fwd(zpre, a, R * (long)d_ff, bf, st))) return rc;
+  memset(&g, 0, sizeof(g));
+  g.A = a; g.sam = d_ff; g.sak = 1; g.B[0] = p->w2; g.sbk = d; g.sbn = 1; g.bias[0] = p->b2;
+  g.C[0] = y; g.ldc = d; g.res = h; g.M = (int)R; g.N = (int)d; g.K = d_ff;
+  if ((rc = launch_gemm_alu(g, bf, bf, bf, st))) return rc;
+  return check_hip("gsit_layer_fwd_train launch");
+}
+
+int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const gsit_layer_params_t* p, float ln_eps,
+                   const int32_t* valid_len, const uint8_t* key_pad, const void* saved, const void* dy, void* dx,
+                   const gsit_layer_grads_t* gr, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = layer_check(shape, d_ff);
+  if (rc) return rc;
+  if (!x || !p || !saved || !dy || !dx || !gr) return fail(IM_ERR_INVALID, "x, params, saved, dy, dx and grads must not be NULL");
+  if (!p->ln1_g || !p->ln1_b || !p->wq || !p->wk || !p->wv || !p->wo || !p->ln2_g || !p->ln2_b || !p->w1 || !p->w2)
+    return fail(IM_ERR_INVALID, "LayerNorm parameters, wq, wk, wv, wo, w1 and w2 must not be NULL");
+  if (!(ln_eps >= 0.f)) return fail(IM_ERR_INVALID, "ln_eps must be >= 0");
+  const LayerTrain L = layer_train_layout(shape, d_ff);
+  if (!workspace || workspace_bytes < L.ws_total)
+    return fail(IM_ERR_WORKSPACE, "gsit_layer_bwd needs %zu workspace bytes, got %zu", L.ws_total, workspace_bytes);
+  hipStream_t st = as_stream(hip_stream);
+  const int bf = shape->dtype == IM_DTYPE_BF16;
+  long T = 0;
+  for (int i = 0; i < shape->n_seg; ++i) T += shape->seg_len[i];
+  const long R = (long)shape->batch * T, d = shape->d_model;
+  const char* sv = (const char*)saved;
+  char* ws = (char*)workspace;
+  const void* h = sv + L.h;
+  const void* zpre = sv + L.zpre;
+  const void* a = sv + L.a;
+  void* u = ws + L.u;
+  void* v = ws + L.v;
+  void* dz = ws + L.dz;
+  void* dv = ws + L.dv;
+  void* dh = ws + L.dh;
+  void* t = ws + L.t;
+  float* partial = (float*)(ws + L.partial);
+  float* cpart = (float*)(ws + L.cpart);
+  GemmDesc g;
+
+  // y = h + a W2 + b2
+  if (gr->w2) {  // dW2 = a^T dy
+    memset(&g, 0, sizeof(g));
+    g.A = a; g.sam = 1; g.sak = d_ff; g.B[0] = dy; g.sbk = d; g.sbn = 1;
+    g.C[0] = gr->w2; g.ldc = d; g.M = d_ff; g.N = (int)d; g.K = (int)R; g.split_k = L.split_w2; g.partial = partial;
+    if ((rc = launch_gemm_alu(g, bf, bf, 0, st))) return rc;
+  }
+  if (gr->b2 && (rc = launch_colsum(dy, d, (int)R, (int)d, bf, (float*)gr->b2, cpart, st))) return rc;
+  // dz = (dy W2^T) * GELU'(z)
+  memset(&g, 0, sizeof(g));
+  g.A = dy; g.sam = d; g.sak = 1; g.B[0] = p->w2; g.sbk = 1; g.sbn = d;
+  g.C[0] = dz; g.ldc = d_ff; g.M = (int)R; g.N = d_ff; g.K = (int)d;
+  if ((rc = launch_gemm_alu(g, bf, bf, bf, st))) return rc;
+  if ((rc = launch_gelu_bwd(zpre, dz, R * (long)d_ff, bf, st))) return rc;
+  // z = v W1 + b1 with v = LN(h; ln2)
+  if ((rc = launch_layernorm(h, p->ln2_g, p->ln2_b, v, (int)R, (int)d, ln_eps, bf, st))) return rc;
+  if (gr->w1) {  // dW1 = v^T dz
+    memset(&g, 0, sizeof(g));
+    g.A = v; g.sam = 1; g.sak = d; g.B[0] = dz; g.sbk = d_ff; g.sbn = 1;
+    g.C[0] = gr->w1; g.ldc = d_ff; g.M = (int)d; g.N = d_ff; g.K = (int)R; g.split_k = L.split_w1; g.partial = partial;
+    if ((rc = launch_gemm_alu(g, bf, bf, 0, st))) return rc;
+  }
+  if (gr->b1 && (rc = launch_colsum(dz, d_ff, (int)R, d_ff, bf, (float*)gr->b1, cpart, st))) return rc;
+  memset(&g, 0, sizeof(g));  // dv = dz W1^T
+  g.A = dz; g.sam = d_ff; g.sak = 1; g.B[0] = p->w1; g.sbk = 1; g.sbn = d_ff;
+  g.C[0] = dv; g.ldc = d; g.M = (int)R; g.N = (int)d; g.K = d_ff;
+  if ((rc = launch_gemm_alu(g, bf, bf, bf, st))) return rc;
+  // dh = dy + LN2 backward(dv)
+  if ((rc = launch_layernorm_bwd(h, p->ln2_g, dv, dy, dh, t, (int)R, (int)d, ln_eps, bf, st))) return rc;
+  if (gr->ln2_g && (rc = launch_colsum(t, d, (int)R, (int)d, bf, (float*)gr->ln2_g, cpart, st))) return rc;
+  if (gr->ln2_b && (rc = launch_colsum(dv, d, (int)R, (int)d, bf, (float*)gr->ln2_b, cpart, st))) return rc;
+  // h = x + IMAttention(u), u = LN(x; ln1): attention backward with upstream gradient dh; its dx is du (into dv)
+  if ((rc = launch_layernorm(x, p->ln1_g, p->ln1_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
+  const SavedLayout A = saved_layout(shape);
+  if (pick_path(shape) == PATH_MFMA)
+    rc = mfma_attention_bwd(shape, u, p->wq, p->wk, p->wv, p->wo, valid_len, key_pad, sv + L.att, A.qkv, A.o, A.lse, A.extra,
+                            dh, dv, gr->wq, gr->wk, gr->wv, gr->wo, gr->bq, gr->bk, gr->bv, gr->bo, ws + L.attws, st);
+  else
+    rc = bwd_rowlane(shape, u, p->wq, p->wk, p->wv, p->wo, valid_len, key_pad, sv + L.att, dh, dv, gr->wq, gr->wk, gr->wv,
+                     gr->wo, gr->bq, gr->bk, gr->bv, gr->bo, ws + L.attws, st);
+  if (rc) return rc;
+  // dx = dh + LN1 backward(du)
+  if ((rc = launch_layernorm_bwd(x, p->ln1_g, dv, dh, dx, t, (int)R, (int)d, ln_eps, bf, st))) return rc;
+  if (gr->ln1_g && (rc = launch_colsum(t, d, (int)R, (int)d, bf, (float*)gr->ln1_g, cpart, st))) return rc;
+  if (gr->ln1_b && (rc = launch_colsum(dv, d, (int)R, (int)d, bf, (float*)gr->ln1_b, cpart, st))) return rc;
+  return check_hip("gsit_layer_bwd launch");
+}
+
 }  // extern "C"

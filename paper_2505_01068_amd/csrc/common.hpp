@@ -112,6 +112,13 @@ bool rowlane_supports(int dh);
 int launch_layernorm(const void* x, const void* gamma, const void* beta, void* y, int R, int d, float eps, int bf16,
                      hipStream_t st);
 
+// encoder-layer backward pieces: a = GELU(z); g <- g * GELU'(z) in place; LayerNorm backward of rows
+// (dx = input gradient + res (res may be NULL), t = dy * xhat for the gamma gradient)
+int launch_gelu_fwd(const void* z, void* a, long n, int bf16, hipStream_t st);
+int launch_gelu_bwd(const void* z, void* g, long n, int bf16, hipStream_t st);
+int launch_layernorm_bwd(const void* x, const void* gamma, const void* dy, const void* res, void* dx, void* t, int R,
+                         int d, float eps, int bf16, hipStream_t st);
+
 void set_error(const char* fmt, ...);
 
 // Optional per-kernel-family timing (see im_profile_enable): records an event pair

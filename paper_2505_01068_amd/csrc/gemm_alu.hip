@@ -252,6 +252,85 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const T* __restrict__ x,
   for (int e = lane; e < d; e += 64) stf(y + r * d + e, (ldf(xr + e) - mu) * rstd * ldf(gamma + e) + ldf(beta + e));
 }
 
+// ---- pieces of the encoder-layer backward ----
+__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.f + erff(z * 0.70710678118654752440f)); }
+// d/dz [z Phi(z)] = Phi(z) + z phi(z)
+__device__ __forceinline__ float gelu_grad_f(float z) {
+  return 0.5f * (1.f + erff(z * 0.70710678118654752440f)) + z * __expf(-0.5f * z * z) * 0.39894228040143267794f;
+}
+template <typename T>
+__global__ void gelu_fwd_kernel(const T* __restrict__ z, T* __restrict__ a, long n) {
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) stf(a + i, gelu_f(ldf(z + i)));
+}
+template <typename T>
+__global__ void gelu_bwd_kernel(const T* __restrict__ z, T* __restrict__ g, long n) {  // g: da in, dz out
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x)
+    stf(g + i, ldf(g + i) * gelu_grad_f(ldf(z + i)));
+}
+int launch_gelu_fwd(const void* z, void* a, long n, int bf16, hipStream_t st) {
+  const int blocks = (int)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
+  if (bf16) hipLaunchKernelGGL((gelu_fwd_kernel<bf16_t>), dim3(blocks), dim3(256), 0, st, (const bf16_t*)z, (bf16_t*)a, n);
+  else hipLaunchKernelGGL((gelu_fwd_kernel<float>), dim3(blocks), dim3(256), 0, st, (const float*)z, (float*)a, n);
+  return IM_OK;
+}
+int launch_gelu_bwd(const void* z, void* g, long n, int bf16, hipStream_t st) {
+  const int blocks = (int)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
+  if (bf16) hipLaunchKernelGGL((gelu_bwd_kernel<bf16_t>), dim3(blocks), dim3(256), 0, st, (const bf16_t*)z, (bf16_t*)g, n);
+  else hipLaunchKernelGGL((gelu_bwd_kernel<float>), dim3(blocks), dim3(256), 0, st, (const float*)z, (float*)g, n);
+  return IM_OK;
+}
+
+// LayerNorm backward of one row per wave: with xhat = (x - mean) * rstd and a = gamma * dy,
+//   dx = rstd * (a - mean(a) - xhat * mean(a * xhat)) + res,      t = dy * xhat
+// (the column sums of t and dy over all rows are the gradients of gamma and beta).
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_bwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+                                                            const T* __restrict__ dy, const T* __restrict__ res,
+                                                            T* __restrict__ dx, T* __restrict__ t, int R, int d,
+                                                            float eps) {
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const long r = (long)blockIdx.x * 4 + wave;
+  if (r >= R) return;
+  const T* xr = x + r * d;
+  const T* gr = dy + r * d;
+  float s = 0.f;
+  for (int e = lane; e < d; e += 64) s += ldf(xr + e);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+  const float mu = s / d;
+  float v = 0.f;
+  for (int e = lane; e < d; e += 64) { const float c = ldf(xr + e) - mu; v = fmaf(c, c, v); }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  const float rstd = rsqrtf(v / d + eps);
+  float m1 = 0.f, m2 = 0.f;
+  for (int e = lane; e < d; e += 64) {
+    const float a = ldf(gamma + e) * ldf(gr + e), xh = (ldf(xr + e) - mu) * rstd;
+    m1 += a;
+    m2 = fmaf(a, xh, m2);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) { m1 += __shfl_xor(m1, o, 64); m2 += __shfl_xor(m2, o, 64); }
+  m1 /= d;
+  m2 /= d;
+  for (int e = lane; e < d; e += 64) {
+    const float g = ldf(gr + e), a = ldf(gamma + e) * g, xh = (ldf(xr + e) - mu) * rstd;
+    stf(dx + r * d + e, rstd * (a - m1 - xh * m2) + (res ? ldf(res + r * d + e) : 0.f));
+    stf(t + r * d + e, g * xh);
+  }
+}
+int launch_layernorm_bwd(const void* x, const void* gamma, const void* dy, const void* res, void* dx, void* t, int R,
+                         int d, float eps, int bf16, hipStream_t st) {
+  dim3 grid((R + 3) / 4), block(256);
+  if (bf16)
+    hipLaunchKernelGGL((layernorm_bwd_kernel<bf16_t>), grid, block, 0, st, (const bf16_t*)x, (const bf16_t*)gamma,
+                       (const bf16_t*)dy, (const bf16_t*)res, (bf16_t*)dx, (bf16_t*)t, R, d, eps);
+  else
+    hipLaunchKernelGGL((layernorm_bwd_kernel<float>), grid, block, 0, st, (const float*)x, (const float*)gamma,
+                       (const float*)dy, (const float*)res, (float*)dx, (float*)t, R, d, eps);
+  return IM_OK;
+}
+
 int launch_layernorm(const void* x, const void* gamma, const void* beta, void* y, int R, int d, float eps, int bf16,
                      hipStream_t st) {
   dim3 grid((R + 3) / 4), block(256);

@@ -1,0 +1,95 @@
+"""GPU parity of gsit_layer_fwd_train / gsit_layer_bwd (one encoder layer, forward that saves and
+backward) vs the fp64 layer oracle: dx and the gradient of every parameter."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_01068_amd import binding as B, synth
+from tests.gpu_util import assert_close, to_dev, TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def run(g, p, lm, dtype, d_ff):
+    x = g["x"]
+    shape = B.make_shape(x.shape[0], g["seg_len"], x.shape[2], g["n_heads"], lm, g["scale"], dtype)
+    sb, wb = B.gsit_layer_train_sizes(shape, d_ff)
+    saved = torch.empty(sb, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(wb, dtype=torch.uint8, device="cuda")
+    xd, dyd = to_dev(x, dtype), to_dev(g["dy"], dtype)
+    pd = {k: to_dev(v, dtype) for k, v in p.items()}
+    vl, kp = to_dev(g.get("valid_len"), dtype), to_dev(g.get("key_pad"), dtype)
+    y = B.gsit_layer_fwd_train(shape, d_ff, xd, pd, saved, valid_len=vl, key_pad=kp, workspace=ws)
+    y_inf = B.gsit_layer_fwd(shape, d_ff, xd, pd, valid_len=vl, key_pad=kp,
+                             workspace=torch.empty(B.gsit_layer_sizes(shape, d_ff), dtype=torch.uint8, device="cuda"))
+    grads = {k: torch.full(v.shape, float("nan"), dtype=torch.float32, device="cuda") for k, v in p.items() if v is not None}
+    dx = B.gsit_layer_bwd(shape, d_ff, xd, pd, saved, dyd, grads, valid_len=vl, key_pad=kp, workspace=ws)
+    torch.cuda.synchronize()
+    return y, y_inf, dx, grads
+
+
+def check(g, p, lm, dtype, d_ff, what):
+    y, y_inf, dx, grads = run(g, p, lm, dtype, d_ff)
+    kw = dict(seg_len=g["seg_len"], live_mask=lm, n_heads=g["n_heads"], scale=g["scale"], valid_len=g.get("valid_len"),
+              key_pad=g.get("key_pad"))
+    tol = TOL[dtype]
+    y_ref = oracle.gsit_layer_forward(g["x"], p, **kw)
+    errs = {"y": assert_close(y, y_ref, tol, what + " y"), "y_inf": assert_close(y_inf, y_ref, tol, what + " y (inference)")}
+    ref = oracle.gsit_layer_backward(g["x"], p, g["dy"], **kw)
+    ulp = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -23
+    floor = ulp * max(float(np.max(np.abs(v))) for v in ref.values())
+    errs["dx"] = assert_close(dx, ref["dx"], tol, what + " dx")
+    for n, v in grads.items():
+        r = ref["d" + n]
+        scale = max(float(np.max(np.abs(r))), floor)
+        if n == "bk":   # identically zero in exact arithmetic: measured against what is summed (see the attention tests)
+            scale = max(scale, float(np.max(np.abs(ref["dwk"]))))
+        errs["d" + n] = assert_close(v, r, tol, what + " d" + n, scale)
+    return errs
+
+
+@pytest.mark.parametrize("name", ["ifm_forward", "ifm_backward", "iem", "self_only"])
+@pytest.mark.parametrize("padding", ["valid_len", "key_pad"])
+def test_layer_backward_fp32(name, padding):
+    say(f"[case] layer bwd fp32 pattern={name} padding={padding}")
+    d, H, d_ff, seg = 40, 8, 100, (37, 130, 75)
+    g = synth.attention_inputs(3, seg, d, H, "fp32", padding, seed=501)
+    p = synth.layer_params(d, d_ff, 501, 0, dtype="fp32")
+    errs = check(g, p, oracle.NAMED_PATTERNS[name], "fp32", d_ff, f"layer-bwd/fp32/{name}/{padding}")
+    say("    " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
+
+
+@pytest.mark.parametrize("bias", [True, False])
+def test_layer_backward_bf16_small_heads(bias):
+    say(f"[case] layer bwd bf16 d=64 (row-per-lane attention) bias={bias}")
+    d, H, d_ff, seg = 64, 8, 256, (50, 200, 130)
+    g = synth.attention_inputs(3, seg, d, H, "bf16", "valid_len", seed=502)
+    p = synth.layer_params(d, d_ff, 502, 0, dtype="bf16", bias=bias)
+    errs = check(g, p, oracle.IM_IFM_FORWARD, "bf16", d_ff, "layer-bwd/bf16/d64")
+    say("    " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
+
+
+def test_layer_backward_bf16_matrix_core_attention():
+    say("[case] layer bwd bf16 d=128, head dim 64 (MFMA attention)")
+    d, H, d_ff, seg = 128, 2, 256, (70, 200, 130)
+    g = synth.attention_inputs(2, seg, d, H, "bf16", "valid_len", seed=503)
+    p = synth.layer_params(d, d_ff, 503, 0, dtype="bf16")
+    errs = check(g, p, oracle.IM_IFM_BACKWARD, "bf16", d_ff, "layer-bwd/bf16/d128")
+    say("    " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
+
+
+def test_layer_backward_bitwise_reproducible():
+    say("[case] layer bwd reproducible")
+    d, H, d_ff, seg = 64, 8, 128, (50, 120, 90)
+    g = synth.attention_inputs(2, seg, d, H, "bf16", "valid_len", seed=504)
+    p = synth.layer_params(d, d_ff, 504, 0, dtype="bf16")
+    a = run(g, p, oracle.IM_IFM_FORWARD, "bf16", d_ff)
+    b = run(g, p, oracle.IM_IFM_FORWARD, "bf16", d_ff)
+    assert torch.equal(a[2], b[2])
+    for n in a[3]:
+        assert torch.equal(a[3][n], b[3][n]), n
