@@ -173,12 +173,92 @@ def bench_encoder(args, whole_model):
     print(json.dumps(out))
 
 
+def bench_layer_train(args):
+    """--config c4train: one encoder layer, training forward + backward, at the C4 shapes (bf16)."""
+    import numpy as np
+    import torch
+    from paper_2505_01068_amd import binding as B, synth
+
+    torch.cuda.set_device(0)
+    masks = {"ifm_forward": B.IM_IFM_FORWARD, "ifm_backward": B.IM_IFM_BACKWARD, "iem": B.IM_IEM}
+    lm = masks[args.mask]
+    w = synth.workload("c4")
+    g = synth.attention_inputs(**w)
+    dtype, tdt = g["dtype"], torch.bfloat16
+    Bsz, T, d = g["x"].shape
+    H, d_ff, seg = g["n_heads"], w["d_ff"], g["seg_len"]
+    dev = lambda a: None if a is None else (lambda t: (t.to(tdt) if t.dtype == torch.float32 else t).cuda())(torch.from_numpy(np.ascontiguousarray(a)))
+    pn = synth.layer_params(d, d_ff, w["seed"], 0, dtype=dtype)
+    p = {k: dev(v) for k, v in pn.items()}
+    x, dy = dev(g["x"]), dev(g["dy"])
+    shape = B.make_shape(Bsz, seg, d, H, lm, g["scale"], dtype)
+    sb, wb = B.gsit_layer_train_sizes(shape, d_ff)
+    saved = torch.empty(sb, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(wb, dtype=torch.uint8, device="cuda")
+    grads = {k: torch.empty(v.shape, dtype=torch.float32, device="cuda") for k, v in p.items()}
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+
+    def step():
+        B.gsit_layer_fwd_train(shape, d_ff, x, p, saved, y=y, workspace=ws)
+        B.gsit_layer_bwd(shape, d_ff, x, p, saved, dy, grads, dx=dx, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.im_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    B.im_profile_enable(False)
+    prof = B.im_profile_get()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    P = live_pairs(seg, lm, Bsz, None, None)
+    core = 14.0 * P * d
+    other = 3.0 * (8.0 * d * d + 4.0 * d * d_ff) * Bsz * T     # projections + MLP, forward and the two backward products
+    per_step = {k: prof[k][0] / args.steps for k in prof if prof[k][1] > 0}
+    attn_keys = [k for k in ("attn_fwd", "attn_dq", "attn_dkv") if k in per_step]
+    dom = max(attn_keys, key=lambda k: per_step[k])
+    alg = {"attn_fwd": 4.0 * P * d, "attn_dkv": 8.0 * P * d, "attn_dq": 2.0 * P * d}
+    achieved = alg[dom] / (per_step[dom] * 1e-3) / 1e12
+    out = {
+        "metric": "IM-attention fwd+bwd TFLOP/s on live blocks; % of ALU roofline",
+        "value": round(core / (ms_step * 1e-3) / 1e12, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"c4train: B={Bsz} L_t/L_v/L_a={'/'.join(map(str, seg))} d={d} H={H} d_ff={d_ff} bf16, one "
+                               f"encoder layer training forward + backward, mask={args.mask}, padding=none",
+                   "core_gflop_per_step": round(core / 1e9, 2), "proj_mlp_gflop_per_step": round(other / 1e9, 2)},
+        "with_projection_mlp_tflops": round((core + other) / (ms_step * 1e-3) / 1e12, 3),
+        "kernel_ms_per_step": {k: round(v, 4) for k, v in per_step.items()},
+        "roofline": {"bound": "alu", "kernel": dom, "achieved": round(achieved, 3), "peak": PEAK_FP32_VALU_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_VALU_TFLOPS, 4), "traffic": None,
+                     "avg_launch_ms": round(per_step[dom], 4)},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([q.get("num_threads", 1) for q in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        n_sample = 4
+        t0 = time.perf_counter()
+        oracle.gsit_layer_backward(g["x"][:n_sample], pn, g["dy"][:n_sample], seg, lm, H, g["scale"])
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(core * n_sample / Bsz / dt / 1e12, 6), "unit": "TFLOP/s", "cores": int(cores),
+                               "kind": "oracle", "seconds": round(dt, 2),
+                               "sample": f"first {n_sample} of {Bsz} batch elements, dense fp64 numpy oracle layer forward + backward"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="c5", choices=["c2", "c3", "c4", "c5", "gsit"])
+    ap.add_argument("--config", default="c5", choices=["c2", "c3", "c4", "c4train", "c5", "gsit"])
     ap.add_argument("--mask", default="ifm_forward", choices=["ifm_forward", "ifm_backward", "iem"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -197,6 +277,8 @@ def main():
         sys.exit(1)
     if args.config in ("c4", "gsit"):
         return bench_encoder(args, args.config == "gsit")
+    if args.config == "c4train":
+        return bench_layer_train(args)
     torch.cuda.set_device(0)
     masks = {"ifm_forward": B.IM_IFM_FORWARD, "ifm_backward": B.IM_IFM_BACKWARD, "iem": B.IM_IEM}
     lm = masks[args.mask]

@@ -186,8 +186,11 @@ static size_t bwd_workspace_bytes(const im_shape_t* s) {
   n += align256(R * d * es);                                          // dO
   n += align256(R * 3 * d * es);                                      // dQ | dK | dV
   n += align256((size_t)s->batch * s->n_heads * T * sizeof(float));   // delta
-  n += align256(std::max(gemm_alu_partial_bytes((int)d, (int)(3 * d), (int)R, nullptr),
-                         gemm_alu_partial_bytes((int)d, (int)d, (int)R, nullptr)));
+  size_t pb = std::max(gemm_alu_partial_bytes((int)d, (int)(3 * d), (int)R, nullptr),
+                       gemm_alu_partial_bytes((int)d, (int)d, (int)R, nullptr));
+  if (mfma_linear_ok(s->dtype == IM_DTYPE_BF16, d, d))
+    pb = std::max(pb, std::max(mfma_wgrad_partial_bytes((int)d, (int)(3 * d), (int)R), mfma_wgrad_partial_bytes((int)d, (int)d, (int)R)));
+  n += align256(pb);
   n += align256(colsum_partial_bytes((int)R, (int)d));
   n += align256(3 * d * d * sizeof(float));                           // sinks for unwanted weight gradients
   return n;
@@ -259,8 +262,11 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
   char* dqkv = (char*)b.take(R * 3 * d * es);
   float* delta = (float*)b.take((size_t)g.B * g.H * g.T * sizeof(float));
   int split = 1;
-  const size_t pbytes = std::max(gemm_alu_partial_bytes((int)d, (int)(3 * d), (int)R, &split),
-                                 gemm_alu_partial_bytes((int)d, (int)d, (int)R, nullptr));
+  size_t pbytes = std::max(gemm_alu_partial_bytes((int)d, (int)(3 * d), (int)R, &split),
+                           gemm_alu_partial_bytes((int)d, (int)d, (int)R, nullptr));
+  // bf16 GEMMs go to the matrix cores whenever the widths allow 16-byte chunks
+  const bool mm = mfma_linear_ok(bf, d, d);
+  if (mm) pbytes = std::max(pbytes, std::max(mfma_wgrad_partial_bytes((int)d, (int)(3 * d), (int)R), mfma_wgrad_partial_bytes((int)d, (int)d, (int)R)));
   float* partial = (float*)b.take(pbytes);
   float* cpart = (float*)b.take(colsum_partial_bytes((int)R, (int)d));
   float* sink = (float*)b.take(3 * d * d * sizeof(float));
@@ -272,9 +278,14 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
   p.A = dy; p.sam = d; p.sak = 1;
   p.B[0] = wo; p.sbk = 1; p.sbn = d;
   p.C[0] = d_o; p.ldc = d; p.M = (int)R; p.N = (int)d; p.K = (int)d;
-  { ProfScope ps(PF_PROJ_BWD, st); if ((rc = launch_gemm_alu(p, bf, bf, bf, st))) return rc; }
+  { ProfScope ps(PF_PROJ_BWD, st);
+    if (mm) mfma_dgrad(dy, d, wo, nullptr, nullptr, d, 0, d_o, d, (int)R, (int)d, (int)d, st);
+    else if ((rc = launch_gemm_alu(p, bf, bf, bf, st))) return rc; }
   // dWo = O^T dy
-  if (dwo) {
+  if (dwo && mm) {
+    ProfScope ps(PF_WGRAD, st);
+    mfma_wgrad(o, d, dy, d, (float*)dwo, nullptr, nullptr, 0, (int)d, (int)d, (int)R, partial, st);
+  } else if (dwo) {
     memset(&p, 0, sizeof(p));
     p.A = o; p.sam = 1; p.sak = d;
     p.B[0] = dy; p.sbk = d; p.sbn = 1;
@@ -291,7 +302,10 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
   if (rc) return rc;
 
   // dWq | dWk | dWv = x^T [dQ | dK | dV]
-  if (dwq || dwk || dwv) {
+  if ((dwq || dwk || dwv) && mm) {
+    ProfScope ps(PF_WGRAD, st);
+    mfma_wgrad(x, d, dqkv, 3 * d, (float*)dwq, (float*)dwk, (float*)dwv, (int)d, (int)d, (int)(3 * d), (int)R, partial, st);
+  } else if (dwq || dwk || dwv) {
     memset(&p, 0, sizeof(p));
     p.A = x; p.sam = 1; p.sak = d;
     p.B[0] = dqkv; p.sbk = 3 * d; p.sbn = 1;
@@ -308,7 +322,10 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
       if ((rc = launch_colsum(dqkv + i * d * es, 3 * d, (int)R, (int)d, bf, (float*)dbs[i], cpart, st))) return rc;
     }
   // dx = dQ Wq^T + dK Wk^T + dV Wv^T
-  if (dx) {
+  if (dx && mm) {
+    ProfScope ps(PF_PROJ_BWD, st);
+    mfma_dgrad(dqkv, 3 * d, wq, wk, wv, d, (int)d, dx, d, (int)R, (int)d, (int)(3 * d), st);
+  } else if (dx) {
     memset(&p, 0, sizeof(p));
     p.A = dqkv; p.sam = 3 * d; p.sak = 1;
     p.B[0] = wq; p.B[1] = wk; p.B[2] = wv; p.sbk = 1; p.sbn = d; p.b_split = 2; p.k_per = (int)d;
@@ -548,8 +565,12 @@ static LayerTrain layer_train_layout(const im_shape_t* s, int32_t d_ff) {
   L.dh = off; off += align256(R * d * es);
   L.t = off; off += align256(R * d * es);
   L.split_w1 = L.split_w2 = 1;
-  const size_t p1 = gemm_alu_partial_bytes((int)d, d_ff, (int)R, &L.split_w1);
-  const size_t p2 = gemm_alu_partial_bytes(d_ff, (int)d, (int)R, &L.split_w2);
+  size_t p1 = gemm_alu_partial_bytes((int)d, d_ff, (int)R, &L.split_w1);
+  size_t p2 = gemm_alu_partial_bytes(d_ff, (int)d, (int)R, &L.split_w2);
+  if (mfma_linear_ok(s->dtype == IM_DTYPE_BF16, d, d_ff) && mfma_linear_ok(1, d_ff, d)) {
+    p1 = std::max(p1, mfma_wgrad_partial_bytes((int)d, d_ff, (int)R));
+    p2 = std::max(p2, mfma_wgrad_partial_bytes(d_ff, (int)d, (int)R));
+  }
   L.partial = off; off += align256(std::max(p1, p2));
   L.cpart = off; off += align256(colsum_partial_bytes((int)R, (int)std::max(d, f)));
   L.aws_bytes = bwd_workspace_bytes(s);
@@ -651,9 +672,12 @@ int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const g
   float* partial = (float*)(ws + L.partial);
   float* cpart = (float*)(ws + L.cpart);
   GemmDesc g;
+  const bool mm = mfma_linear_ok(bf, d, d_ff) && mfma_linear_ok(bf, d_ff, d);  // bf16 GEMMs on the matrix cores
 
   // y = h + a W2 + b2
-  if (gr->w2) {  // dW2 = a^T dy
+  if (gr->w2 && mm) {
+    mfma_wgrad(a, d_ff, dy, d, (float*)gr->w2, nullptr, nullptr, 0, d_ff, (int)d, (int)R, partial, st);
+  } else if (gr->w2) {  // dW2 = a^T dy
     memset(&g, 0, sizeof(g));
     g.A = a; g.sam = 1; g.sak = d_ff; g.B[0] = dy; g.sbk = d; g.sbn = 1;
     g.C[0] = gr->w2; g.ldc = d; g.M = d_ff; g.N = (int)d; g.K = (int)R; g.split_k = L.split_w2; g.partial = partial;
@@ -661,24 +685,34 @@ int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const g
   }
   if (gr->b2 && (rc = launch_colsum(dy, d, (int)R, (int)d, bf, (float*)gr->b2, cpart, st))) return rc;
   // dz = (dy W2^T) * GELU'(z)
-  memset(&g, 0, sizeof(g));
-  g.A = dy; g.sam = d; g.sak = 1; g.B[0] = p->w2; g.sbk = 1; g.sbn = d;
-  g.C[0] = dz; g.ldc = d_ff; g.M = (int)R; g.N = d_ff; g.K = (int)d;
-  if ((rc = launch_gemm_alu(g, bf, bf, bf, st))) return rc;
+  if (mm) {
+    mfma_dgrad(dy, d, p->w2, nullptr, nullptr, d, 0, dz, d_ff, (int)R, d_ff, (int)d, st);
+  } else {
+    memset(&g, 0, sizeof(g));
+    g.A = dy; g.sam = d; g.sak = 1; g.B[0] = p->w2; g.sbk = 1; g.sbn = d;
+    g.C[0] = dz; g.ldc = d_ff; g.M = (int)R; g.N = d_ff; g.K = (int)d;
+    if ((rc = launch_gemm_alu(g, bf, bf, bf, st))) return rc;
+  }
   if ((rc = launch_gelu_bwd(zpre, dz, R * (long)d_ff, bf, st))) return rc;
   // z = v W1 + b1 with v = LN(h; ln2)
   if ((rc = launch_layernorm(h, p->ln2_g, p->ln2_b, v, (int)R, (int)d, ln_eps, bf, st))) return rc;
-  if (gr->w1) {  // dW1 = v^T dz
+  if (gr->w1 && mm) {
+    mfma_wgrad(v, d, dz, d_ff, (float*)gr->w1, nullptr, nullptr, 0, (int)d, d_ff, (int)R, partial, st);
+  } else if (gr->w1) {  // dW1 = v^T dz
     memset(&g, 0, sizeof(g));
     g.A = v; g.sam = 1; g.sak = d; g.B[0] = dz; g.sbk = d_ff; g.sbn = 1;
     g.C[0] = gr->w1; g.ldc = d_ff; g.M = (int)d; g.N = d_ff; g.K = (int)R; g.split_k = L.split_w1; g.partial = partial;
     if ((rc = launch_gemm_alu(g, bf, bf, 0, st))) return rc;
   }
   if (gr->b1 && (rc = launch_colsum(dz, d_ff, (int)R, d_ff, bf, (float*)gr->b1, cpart, st))) return rc;
-  memset(&g, 0, sizeof(g));  // dv = dz W1^T
-  g.A = dz; g.sam = d_ff; g.sak = 1; g.B[0] = p->w1; g.sbk = 1; g.sbn = d_ff;
-  g.C[0] = dv; g.ldc = d; g.M = (int)R; g.N = (int)d; g.K = d_ff;
-  if ((rc = launch_gemm_alu(g, bf, bf, bf, st))) return rc;
+  if (mm) {  // dv = dz W1^T
+    mfma_dgrad(dz, d_ff, p->w1, nullptr, nullptr, d_ff, 0, dv, d, (int)R, (int)d, d_ff, st);
+  } else {
+    memset(&g, 0, sizeof(g));
+    g.A = dz; g.sam = d_ff; g.sak = 1; g.B[0] = p->w1; g.sbk = 1; g.sbn = d_ff;
+    g.C[0] = dv; g.ldc = d; g.M = (int)R; g.N = (int)d; g.K = d_ff;
+    if ((rc = launch_gemm_alu(g, bf, bf, bf, st))) return rc;
+  }
   // dh = dy + LN2 backward(dv)
   if ((rc = launch_layernorm_bwd(h, p->ln2_g, dv, dy, dh, t, (int)R, (int)d, ln_eps, bf, st))) return rc;
   if (gr->ln2_g && (rc = launch_colsum(t, d, (int)R, (int)d, bf, (float*)gr->ln2_g, cpart, st))) return rc;

@@ -201,32 +201,54 @@ int launch_gemm_alu(const GemmDesc& d, int a_bf16, int b_bf16, int c_bf16, hipSt
 }
 
 // ---- column sums (bias gradients): stage 1 sums blocks of rows, stage 2 sums the blocks in order ----
-constexpr int CS_ROWS = 512;
+// Column sums of a [R, n] matrix in two deterministic stages.  Stage 1: a block of 256 threads =
+// 4 row groups x 64 columns sums CS_ROWS rows (thread (g, c): rows r0 + g, r0 + g + 4, ..., with four
+// independent running sums so loads overlap), then the 4 groups are added in a fixed order through
+// LDS.  Stage 2 does the same over the per-block partials.
+constexpr int CS_ROWS = 256;
 
 template <typename T>
-__global__ void colsum_stage1(const T* a, long lda, int R, int n, float* partial) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= n) return;
+__global__ __launch_bounds__(256) void colsum_stage1(const T* __restrict__ a, long lda, int R, int n,
+                                                     float* __restrict__ partial) {
+  __shared__ float red[4][64];
+  const int tx = threadIdx.x & 63, g = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + tx;
   const int r0 = blockIdx.y * CS_ROWS, r1 = min(R, r0 + CS_ROWS);
-  float s = 0.f;
-  for (int r = r0; r < r1; ++r) s += ldf(a + (long)r * lda + c);
-  partial[(long)blockIdx.y * n + c] = s;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (c < n) {
+    int r = r0 + g;
+    for (; r + 12 < r1; r += 16) {
+      s0 += ldf(a + (long)r * lda + c);
+      s1 += ldf(a + (long)(r + 4) * lda + c);
+      s2 += ldf(a + (long)(r + 8) * lda + c);
+      s3 += ldf(a + (long)(r + 12) * lda + c);
+    }
+    for (; r < r1; r += 4) s0 += ldf(a + (long)r * lda + c);
+  }
+  red[g][tx] = (s0 + s1) + (s2 + s3);
+  __syncthreads();
+  if (g == 0 && c < n) partial[(long)blockIdx.y * n + c] = (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]);
 }
-__global__ void colsum_stage2(const float* partial, int nblk, int n, float* out) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= n) return;
+__global__ __launch_bounds__(256) void colsum_stage2(const float* __restrict__ partial, int nblk, int n,
+                                                     float* __restrict__ out) {
+  __shared__ float red[4][64];
+  const int tx = threadIdx.x & 63, g = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + tx;
   float s = 0.f;
-  for (int b = 0; b < nblk; ++b) s += partial[(long)b * n + c];
-  out[c] = s;
+  if (c < n)
+    for (int b = g; b < nblk; b += 4) s += partial[(long)b * n + c];
+  red[g][tx] = s;
+  __syncthreads();
+  if (g == 0 && c < n) out[c] = (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]);
 }
 size_t colsum_partial_bytes(int R, int n) { return (size_t)((R + CS_ROWS - 1) / CS_ROWS) * n * sizeof(float); }
 
 int launch_colsum(const void* a, long lda, int R, int n, int a_bf16, float* out, float* partial, hipStream_t st) {
   const int nblk = (R + CS_ROWS - 1) / CS_ROWS;
-  dim3 grid((n + 63) / 64, nblk), block(64);
+  dim3 grid((n + 63) / 64, nblk), block(256);
   if (a_bf16) hipLaunchKernelGGL((colsum_stage1<bf16_t>), grid, block, 0, st, (const bf16_t*)a, lda, R, n, partial);
   else hipLaunchKernelGGL((colsum_stage1<float>), grid, block, 0, st, (const float*)a, lda, R, n, partial);
-  hipLaunchKernelGGL(colsum_stage2, dim3((n + 63) / 64), dim3(64), 0, st, partial, nblk, n, out);
+  hipLaunchKernelGGL(colsum_stage2, dim3((n + 63) / 64), dim3(256), 0, st, partial, nblk, n, out);
   return IM_OK;
 }
 

@@ -66,6 +66,32 @@ void mfma_linear(const void* A, long lda, const void* w0, const void* w1, const 
   launch_mfma_gemm(p, st);
 }
 
+void mfma_dgrad(const void* G, long ldg, const void* w0, const void* w1, const void* w2, long ldw, int k_per, void* C,
+                long ldc, int M, int N, int K, hipStream_t st) {
+  MGemm p;
+  init_gemm(&p);
+  p.A = (const bf16_t*)G; p.lda = ldg;
+  p.B[0] = (const bf16_t*)w0; p.B[1] = (const bf16_t*)w1; p.B[2] = (const bf16_t*)w2; p.ldb = ldw;
+  p.b_kper = (w1 || w2) ? k_per : 0;
+  p.M = M; p.N = N; p.K = K;
+  p.C = (bf16_t*)C; p.ldc = ldc;
+  launch_mfma_gemm(p, st);
+}
+
+size_t mfma_wgrad_partial_bytes(int M, int N, int R) { return (size_t)mfma_gemm_split(M, N, R) * M * N * sizeof(float); }
+
+void mfma_wgrad(const void* A, long lda, const void* G, long ldg, float* o0, float* o1, float* o2, int n_per, int M,
+                int N, int R, float* partial, hipStream_t st) {
+  MGemm p;
+  init_gemm(&p);
+  p.A = (const bf16_t*)A; p.lda = lda; p.a_kmajor = 1;
+  p.B[0] = (const bf16_t*)G; p.ldb = ldg; p.b_kmajor = 1;
+  p.M = M; p.N = N; p.K = R;
+  p.split_k = mfma_gemm_split(M, N, R); p.partial = partial;
+  launch_mfma_gemm(p, st);
+  launch_splitk_reduce(partial, p.split_k, M, N, o0, o1, o2, n_per, st);
+}
+
 int mfma_attention_fwd(const im_shape_t* s, const void* x, const void* wq, const void* wk, const void* wv,
                        const void* wo, const void* bq, const void* bk, const void* bv, const void* bo,
                        const int32_t* valid_len, const uint8_t* key_pad, void* y, const void* res, char* sv,

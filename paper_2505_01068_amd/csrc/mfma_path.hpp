@@ -22,6 +22,16 @@ void launch_mfma_gemm(const MGemm& p, hipStream_t st);
 // bf16 linear layer C[M,N] = A[M,K] W + bias (+ GELU) (+ residual) with weights stored [K][N] (k-major),
 // optionally three weight / bias blocks of n_per columns each.  Usable when K % 8 == 0 and N % 8 == 0.
 inline bool mfma_linear_ok(int is_bf16, long K, long N) { return is_bf16 && K % 8 == 0 && N % 8 == 0 && K >= 8 && N >= 8; }
+// data gradient  C[M,N] = G[M,K] W^T  with W stored [N][K'] row-major; the contraction may run over up to three
+// weights of k_per columns each (K = 3 k_per), as in dx = dQ Wq^T + dK Wk^T + dV Wv^T
+void mfma_dgrad(const void* G, long ldg, const void* w0, const void* w1, const void* w2, long ldw, int k_per, void* C,
+                long ldc, int M, int N, int K, hipStream_t st);
+// weight gradient  C[M,N] (fp32) = A[R,M]^T G[R,N]  (contraction over rows), split-K with a fixed-order
+// reduction; n_per > 0: column block s of n_per columns goes to the [M, n_per] output o<s> (NULL = dropped);
+// n_per = 0: one [M, N] output o0.  `partial`: mfma_wgrad_partial_bytes.  M % 8 == 0 and N % 8 == 0.
+size_t mfma_wgrad_partial_bytes(int M, int N, int R);
+void mfma_wgrad(const void* A, long lda, const void* G, long ldg, float* o0, float* o1, float* o2, int n_per, int M,
+                int N, int R, float* partial, hipStream_t st);
 void mfma_linear(const void* A, long lda, const void* w0, const void* w1, const void* w2, long ldb, int n_per,
                  const void* b0, const void* b1, const void* b2, int gelu, const void* res, void* C, long ldc, int M,
                  int N, int K, hipStream_t st);
