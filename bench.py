@@ -150,7 +150,10 @@ def bench_encoder(args, whole_model):
         "kernel_ms_per_step": {k: round(v, 4) for k, v in per_step.items()},
         "roofline": {"bound": "alu", "kernel": dom, "achieved": round(achieved, 3), "peak": PEAK_FP32_VALU_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_VALU_TFLOPS, 4), "traffic": None,
-                     "avg_launch_ms": round(dom_ms, 4)},
+                     "avg_launch_ms": round(dom_ms, 4),
+                     "note": "head dims 8 / 16: the two contractions run on the matrix cores in sub-head mode (1/8 to 1/2 "
+                             "of each MFMA is useful work); the softmax's plain-ALU instructions bound the kernel, so the "
+                             "algorithmic flops are set against the fp32 vector peak"},
     }
     if not args.no_cpu_baseline:
         import oracle
