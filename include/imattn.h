@@ -209,8 +209,11 @@ int gsit_model_fwd(const im_shape_t* shape, const gsit_model_t* model, const voi
  * stream.  im_profile_get synchronises on the recorded events, so call it after
  * the stream has drained; it returns the number of families, and for family
  * `idx` its name (static storage), accumulated milliseconds and launch count
- * since the last im_profile_enable(1).  Not thread-safe; at most 8192 launches
- * are recorded between resets (later ones are not timed).  Host memory only. */
+ * since the last non-zero im_profile_enable.  `on`: 0 = off; 1 = every family;
+ * any other value = a selection, bit (idx + 1) set <=> family idx is timed (an
+ * event pair costs a few microseconds of stream time, so a benchmark that times
+ * whole steps brackets only the family it reports).  Not thread-safe; at most 8192
+ * launches are recorded between resets (later ones are not timed).  Host memory only. */
 int im_profile_enable(int on);
 int im_profile_get(int idx, const char** name, double* total_ms, int64_t* launches);
 

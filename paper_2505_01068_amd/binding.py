@@ -252,8 +252,23 @@ def gsit_model_fwd(shape, model, x, valid_len=None, key_pad=None, out=None, work
     return out
 
 
-def im_profile_enable(on):
-    lib().im_profile_enable(1 if on else 0)
+def im_profile_enable(on, only=None):
+    """on: time every kernel family; only=<family name>: time just that one (cheaper)."""
+    if only is not None:
+        names = im_profile_names()
+        lib().im_profile_enable(1 << (names.index(only) + 1))
+    else:
+        lib().im_profile_enable(1 if on else 0)
+
+
+def im_profile_names():
+    n = lib().im_profile_get(-1, None, None, None)
+    out = []
+    for i in range(n):
+        name = C.c_char_p()
+        lib().im_profile_get(i, C.byref(name), None, None)
+        out.append(name.value.decode())
+    return out
 
 
 def im_profile_get():

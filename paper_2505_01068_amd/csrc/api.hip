@@ -33,14 +33,14 @@ static int fail(int code, const char* fmt, ...) {
 // ---- optional kernel-family timing ----
 static const char* kProfNames[PF_COUNT] = {"proj_fwd", "attn_fwd", "attn_dq", "attn_dkv", "proj_bwd", "wgrad", "misc"};
 constexpr int PROF_MAX = 8192;
-static bool g_prof_on = false;
+static unsigned g_prof_mask = 0;  // bit f set: kernel family f is bracketed with events
 static int g_prof_n = 0;
 static hipEvent_t g_prof_ev[PROF_MAX][2];
 static int g_prof_family[PROF_MAX];
 static int g_prof_created = 0;
 
 ProfScope::ProfScope(ProfFamily f, hipStream_t s) : slot(-1), st(s) {
-  if (!g_prof_on || g_prof_n >= PROF_MAX) return;
+  if (!((g_prof_mask >> f) & 1u) || g_prof_n >= PROF_MAX) return;
   if (g_prof_n >= g_prof_created) {
     if (hipEventCreate(&g_prof_ev[g_prof_n][0]) != hipSuccess || hipEventCreate(&g_prof_ev[g_prof_n][1]) != hipSuccess) return;
     g_prof_created = g_prof_n + 1;
@@ -345,7 +345,7 @@ extern "C" {
 const char* im_last_error(void) { return g_err; }
 
 int im_profile_enable(int on) {
-  g_prof_on = on != 0;
+  g_prof_mask = on == 1 ? ~0u : on > 1 ? (unsigned)on >> 1 : 0u;
   if (on) g_prof_n = 0;
   return IM_OK;
 }
