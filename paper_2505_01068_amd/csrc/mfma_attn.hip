@@ -1,5 +1,6 @@
 // Flash-style IM attention on the CDNA4 matrix cores: bf16 operands, fp32
-// accumulation, head dimension 64.
+// accumulation, head dimension 64 (forward also head dimensions 8 / 16 in its
+// sub-head mode).
 //
 // All three kernels compute "transposed" products so that every per-row
 // quantity of the softmax lives on the lane that owns the row:
@@ -8,7 +9,8 @@
 //                  the accumulator registers (see perm32 in mfma_common.hpp).
 //   dK / dV      : lane <-> key row.    S = Q K^T (rows = queries), dP = dO V^T;
 //                  dV^T = dO^T P and dK^T = Q^T dS take P / dS from registers.
-// K/V (or Q/dO) tiles of 64 rows are staged row-major through LDS once; products
+// K/V (or Q/dO) tiles of 64 rows go through a ring of LDS stages, row-major
+// (swizzled, filled by asynchronous global->LDS copies); products
 // that need the tile transposed (V^T, K^T, Q^T, dO^T as the MFMA "A" operand)
 // read it with the gfx950 LDS transpose read (ds_read_b64_tr_b16), so no
 // transposed copy of any tensor exists in HBM.

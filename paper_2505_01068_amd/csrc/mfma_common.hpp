@@ -23,7 +23,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int LDS_LD = 72;  // bf16 elements per LDS tile row: 64 + 8 pad (144 B keeps 16-byte reads conflict-free)
+constexpr int LDS_LD = 72;  // bf16 per row of a padded LDS tile (128 x 128 GEMM): 64 + 8 pad, 144 B keeps 16-byte reads conflict-free
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -61,31 +61,6 @@ __device__ __forceinline__ bf16x8 pack8(const float* v) {
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// Stage a 64-row x 64-column bf16 tile from global memory into LDS (row stride
-// LDS_LD) with 256 threads: two 16-byte loads per thread.
-//   row r of the tile lives at  base + rowidx(r) * gstride  (rowidx clamps tails)
-struct TileRegs {
-  u32x4 v[2];
-};
-
-// rows = tokens: tile row r is token row min(r0 + r, rmax) of a [.., ld] activation matrix
-__device__ __forceinline__ void load_rows_tile(TileRegs& t, const bf16_t* base, long ld, int r0, int rmax, int tid) {
-#pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int r = (tid >> 3) + u * 32, c = (tid & 7) * 8;
-    const int rr = min(r0 + r, rmax);
-    t.v[u] = *(const u32x4*)(base + (long)rr * ld + c);
-  }
-}
-
-__device__ __forceinline__ void store_tile(const TileRegs& t, bf16_t* lds, int tid) {
-#pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int r = (tid >> 3) + u * 32, c = (tid & 7) * 8;
-    *(u32x4*)(lds + r * LDS_LD + c) = t.v[u];
-  }
-}
 
 // Transposed fragment from a K-MAJOR tile (row = contraction index k, columns = m) using the
 // gfx950 LDS transpose read.  ds_read_b64_tr_b16 exchanges data inside each group of 16 lanes:
@@ -147,14 +122,6 @@ __device__ __forceinline__ void dma4(const void* gptr, const void* lds_wave_base
 //    r and r+1 sit in opposite bank halves, r+2 moves the span by 64 bytes (bit 2 of sw_f).
 constexpr int SW_LD = 64;
 __device__ __forceinline__ int sw_f(int r) { return (((r >> 1) & 1) << 2) | ((r >> 2) & 3); }
-
-__device__ __forceinline__ void store_tile_sw(const TileRegs& t, bf16_t* lds, int tid) {
-#pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int r = (tid >> 3) + u * 32, c = tid & 7;
-    *(u32x4*)(lds + r * SW_LD + ((c ^ sw_f(r)) << 3)) = t.v[u];
-  }
-}
 
 // 16-byte fragment: row row16 + lrow (row16 % 16 == 0, 0 <= lrow < 32), chunk column `chunk`
 __device__ __forceinline__ bf16x8 lds_frag_sw(const bf16_t* lds, int row16, int lrow, int chunk) {
