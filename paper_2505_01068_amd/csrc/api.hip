@@ -190,6 +190,7 @@ static size_t bwd_workspace_bytes(const im_shape_t* s) {
                        gemm_alu_partial_bytes((int)d, (int)d, (int)R, nullptr));
   if (mfma_linear_ok(s->dtype == IM_DTYPE_BF16, d, d))
     pb = std::max(pb, std::max(mfma_wgrad_partial_bytes((int)d, (int)(3 * d), (int)R), mfma_wgrad_partial_bytes((int)d, (int)d, (int)R)));
+  if (wgrad_small_ok((int)d, (int)(3 * d), (int)d)) pb = std::max(pb, wgrad_small_partial_bytes((int)d, (int)(3 * d), (int)R));
   n += align256(pb);
   n += align256(colsum_partial_bytes((int)R, (int)d));
   n += align256(3 * d * d * sizeof(float));                           // sinks for unwanted weight gradients
@@ -267,6 +268,9 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
   // bf16 GEMMs go to the matrix cores whenever the widths allow 16-byte chunks
   const bool mm = mfma_linear_ok(bf, d, d);
   if (mm) pbytes = std::max(pbytes, std::max(mfma_wgrad_partial_bytes((int)d, (int)(3 * d), (int)R), mfma_wgrad_partial_bytes((int)d, (int)d, (int)R)));
+  // narrow models (d <= 64) off the matrix cores: the dedicated tall-skinny weight-gradient kernel
+  const bool ws_small = !mm && wgrad_small_ok((int)d, (int)(3 * d), (int)d);
+  if (ws_small) pbytes = std::max(pbytes, wgrad_small_partial_bytes((int)d, (int)(3 * d), (int)R));
   float* partial = (float*)b.take(pbytes);
   float* cpart = (float*)b.take(colsum_partial_bytes((int)R, (int)d));
   float* sink = (float*)b.take(3 * d * d * sizeof(float));
@@ -285,6 +289,10 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
   if (dwo && mm) {
     ProfScope ps(PF_WGRAD, st);
     mfma_wgrad(o, d, dy, d, (float*)dwo, nullptr, nullptr, 0, (int)d, (int)d, (int)R, partial, st);
+  } else if (dwo && ws_small) {
+    ProfScope ps(PF_WGRAD, st);
+    const int nb = launch_wgrad_small(o, d, dy, d, (int)R, (int)d, (int)d, bf, partial, st);
+    launch_wgrad_small_reduce(partial, nb, (int)d, (int)d, (float*)dwo, nullptr, nullptr, 0, st);
   } else if (dwo) {
     memset(&p, 0, sizeof(p));
     p.A = o; p.sam = 1; p.sak = d;
@@ -305,6 +313,10 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
   if ((dwq || dwk || dwv) && mm) {
     ProfScope ps(PF_WGRAD, st);
     mfma_wgrad(x, d, dqkv, 3 * d, (float*)dwq, (float*)dwk, (float*)dwv, (int)d, (int)d, (int)(3 * d), (int)R, partial, st);
+  } else if ((dwq || dwk || dwv) && ws_small) {
+    ProfScope ps(PF_WGRAD, st);
+    const int nb = launch_wgrad_small(x, d, dqkv, 3 * d, (int)R, (int)d, (int)(3 * d), bf, partial, st);
+    launch_wgrad_small_reduce(partial, nb, (int)d, (int)(3 * d), (float*)dwq, (float*)dwk, (float*)dwv, (int)d, st);
   } else if (dwq || dwk || dwv) {
     memset(&p, 0, sizeof(p));
     p.A = x; p.sam = 1; p.sak = d;

@@ -112,6 +112,15 @@ bool rowlane_supports(int dh);
 int launch_layernorm(const void* x, const void* gamma, const void* beta, void* y, int R, int d, float eps, int bf16,
                      hipStream_t st);
 
+// weight gradient of a narrow layer, C[M,N] = A[R,M]^T G[R,N] with M <= 64, N <= 256 (see gemm_alu.hip):
+// writes and returns a number of partial [M,N] matrices that the caller sums in a fixed order
+bool wgrad_small_ok(int M, int N, int n_per);
+size_t wgrad_small_partial_bytes(int M, int N, int R);
+void launch_wgrad_small_reduce(const float* partial, int nz, int M, int N, float* o0, float* o1, float* o2, int n_per,
+                               hipStream_t st);
+int launch_wgrad_small(const void* A, long lda, const void* G, long ldg, int R, int M, int N, int in_bf16, float* partial,
+                       hipStream_t st);
+
 // encoder-layer backward pieces: a = GELU(z); g <- g * GELU'(z) in place; LayerNorm backward of rows
 // (dx = input gradient + res (res may be NULL), t = dy * xhat for the gamma gradient)
 int launch_gelu_fwd(const void* z, void* a, long n, int bf16, hipStream_t st);

@@ -201,6 +201,149 @@ int launch_gemm_alu(const GemmDesc& d, int a_bf16, int b_bf16, int c_bf16, hipSt
 }
 
 // ---- column sums (bias gradients): stage 1 sums blocks of rows, stage 2 sums the blocks in order ----
+// ---- weight gradient of a narrow layer: C[M, N] = A[R, M]^T G[R, N], M <= 64, N <= 256, R long ----
+// The general GEMM above spends its time in a latency-bound loop of R / split 16-deep k-tiles.  Here a
+// block stages WS_RB rows of A and G in LDS with all loads in flight at once and every thread keeps a
+// TM x TN patch of the output in registers (thread (ty, tx): rows ty + 8 i, columns tx + 32 j, so the
+// LDS reads are broadcasts / consecutive words).  Each block writes one partial [M, N]; the caller
+// reduces the partials in a fixed order.
+constexpr int WS_RB = 32;
+constexpr int WS_MAX_BLOCKS = 1024;
+template <typename T, int TM, int TN>
+__global__ __launch_bounds__(256) void wgrad_small_kernel(const T* __restrict__ A, long lda, const T* __restrict__ G,
+                                                          long ldg, int R, int M, int N, float* __restrict__ partial) {
+  __shared__ float sm[WS_RB * (64 + 256)];
+  float* sA = sm;
+  float* sG = sm + WS_RB * M;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  float acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = 0.f;
+  int mi[TM], nj[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) mi[i] = min(ty + 8 * i, M - 1);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) nj[j] = min(tx + 32 * j, N - 1);
+  const int nchunks = (R + WS_RB - 1) / WS_RB;
+  for (int ch = blockIdx.x; ch < nchunks; ch += gridDim.x) {
+    const long row0 = (long)ch * WS_RB;
+    __syncthreads();
+    for (int e = threadIdx.x; e < WS_RB * M; e += 256) {
+      const int r = e / M, m = e - r * M;
+      sA[e] = row0 + r < R ? ldf(A + (row0 + r) * lda + m) : 0.f;
+    }
+    for (int e = threadIdx.x; e < WS_RB * N; e += 256) {
+      const int r = e / N, n = e - r * N;
+      sG[e] = row0 + r < R ? ldf(G + (row0 + r) * ldg + n) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll 4
+    for (int r = 0; r < WS_RB; ++r) {
+      float a[TM], g[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) a[i] = sA[r * M + mi[i]];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) g[j] = sG[r * N + nj[j]];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = fmaf(a[i], g[j], acc[i][j]);
+    }
+  }
+  float* out = partial + (long)blockIdx.x * M * N;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = ty + 8 * i;
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = tx + 32 * j;
+      if (n < N) out[(long)m * N + n] = acc[i][j];
+    }
+  }
+}
+
+// out[m, n] = sum_z partial[z][m][n], z in a fixed order; column block s of n_per columns goes to the [M, n_per]
+// matrix o<s> (NULL = dropped) when n_per > 0, else everything to o0.  A block of 256 threads owns 16
+// consecutive outputs: thread (g, o) sums z = g, g + 16, ... with four running sums (independent loads in
+// flight), then the 16 groups are added in a fixed order.
+__global__ __launch_bounds__(256) void wgrad_small_reduce_kernel(const float* __restrict__ partial, int nz, int M, int N,
+                                                                 float* o0, float* o1, float* o2, int n_per) {
+  __shared__ float red[16][16];
+  const int o = threadIdx.x & 15, g = threadIdx.x >> 4;
+  const long n_out = (long)M * N;
+  const long i = (long)blockIdx.x * 16 + o;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (i < n_out) {
+    int z = g;
+    for (; z + 48 < nz; z += 64) {
+      s0 += partial[(long)z * n_out + i];
+      s1 += partial[(long)(z + 16) * n_out + i];
+      s2 += partial[(long)(z + 32) * n_out + i];
+      s3 += partial[(long)(z + 48) * n_out + i];
+    }
+    for (; z < nz; z += 16) s0 += partial[(long)z * n_out + i];
+  }
+  red[g][o] = (s0 + s1) + (s2 + s3);
+  __syncthreads();
+  if (g == 0 && i < n_out) {
+    float v = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v += red[k][o];
+    const int m = (int)(i / N), n = (int)(i - (long)m * N);
+    if (n_per > 0) {
+      float* dst = (n / n_per == 0) ? o0 : (n / n_per == 1) ? o1 : o2;
+      if (dst) dst[(long)m * n_per + n % n_per] = v;
+    } else {
+      o0[i] = v;
+    }
+  }
+}
+void launch_wgrad_small_reduce(const float* partial, int nz, int M, int N, float* o0, float* o1, float* o2, int n_per,
+                               hipStream_t st) {
+  const long n_out = (long)M * N;
+  hipLaunchKernelGGL(wgrad_small_reduce_kernel, dim3((unsigned)((n_out + 15) / 16)), dim3(256), 0, st, partial, nz, M, N, o0,
+                     o1, o2, n_per);
+}
+
+bool wgrad_small_ok(int M, int N, int n_per) {
+  (void)n_per;
+  return M >= 1 && M <= 64 && N >= 1 && N <= 256;
+}
+int wgrad_small_blocks(int R) {
+  const int nchunks = (R + WS_RB - 1) / WS_RB;
+  return nchunks < WS_MAX_BLOCKS ? nchunks : WS_MAX_BLOCKS;
+}
+size_t wgrad_small_partial_bytes(int M, int N, int R) { return (size_t)wgrad_small_blocks(R) * M * N * sizeof(float); }
+
+template <typename T, int TM>
+static void launch_wgrad_small_tn(const T* A, long lda, const T* G, long ldg, int R, int M, int N, float* partial, int blocks,
+                                  hipStream_t st) {
+  const int tn = (N + 31) / 32;
+  if (tn <= 2) hipLaunchKernelGGL((wgrad_small_kernel<T, TM, 2>), dim3(blocks), dim3(256), 0, st, A, lda, G, ldg, R, M, N, partial);
+  else if (tn <= 4) hipLaunchKernelGGL((wgrad_small_kernel<T, TM, 4>), dim3(blocks), dim3(256), 0, st, A, lda, G, ldg, R, M, N, partial);
+  else if (tn <= 6) hipLaunchKernelGGL((wgrad_small_kernel<T, TM, 6>), dim3(blocks), dim3(256), 0, st, A, lda, G, ldg, R, M, N, partial);
+  else hipLaunchKernelGGL((wgrad_small_kernel<T, TM, 8>), dim3(blocks), dim3(256), 0, st, A, lda, G, ldg, R, M, N, partial);
+}
+template <typename T>
+static void launch_wgrad_small_t(const T* A, long lda, const T* G, long ldg, int R, int M, int N, float* partial, int blocks,
+                                 hipStream_t st) {
+  const int tm = (M + 7) / 8;
+  if (tm <= 4) launch_wgrad_small_tn<T, 4>(A, lda, G, ldg, R, M, N, partial, blocks, st);
+  else if (tm <= 5) launch_wgrad_small_tn<T, 5>(A, lda, G, ldg, R, M, N, partial, blocks, st);
+  else launch_wgrad_small_tn<T, 8>(A, lda, G, ldg, R, M, N, partial, blocks, st);
+}
+// Writes wgrad_small_blocks(R) partial [M, N] matrices; returns that count (the number of partials to reduce).
+int launch_wgrad_small(const void* A, long lda, const void* G, long ldg, int R, int M, int N, int in_bf16, float* partial,
+                       hipStream_t st) {
+  const int blocks = wgrad_small_blocks(R);
+  if (in_bf16) launch_wgrad_small_t<bf16_t>((const bf16_t*)A, lda, (const bf16_t*)G, ldg, R, M, N, partial, blocks, st);
+  else launch_wgrad_small_t<float>((const float*)A, lda, (const float*)G, ldg, R, M, N, partial, blocks, st);
+  return blocks;
+}
+
 // Column sums of a [R, n] matrix in two deterministic stages.  Stage 1: a block of 256 threads =
 // 4 row groups x 64 columns sums CS_ROWS rows (thread (g, c): rows r0 + g, r0 + g + 4, ..., with four
 // independent running sums so loads overlap), then the 4 groups are added in a fixed order through
