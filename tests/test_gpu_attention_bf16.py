@@ -46,6 +46,16 @@ def test_mfma_wide_model_weight_gradient_kernel():
     say("    " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
 
 
+def test_mfma_projection_large_tile_ragged_rows():
+    # d = 256, 2 x 1092 = 2184 token rows (a multiple of 8, not of 256): the QKV and output projections
+    # take the asynchronous 256 x 256 GEMM kernel with a ragged last row tile (2184 = 8 * 256 + 136) and,
+    # for N = 768 / 256, full column tiles; biases go through its staged epilogue
+    say("[case] mfma d=256 R=2184 (large-tile projection GEMM, ragged rows)")
+    g = synth.attention_inputs(2, (300, 488, 304), 256, 4, "bf16", "valid_len", seed=43, bias=True)
+    errs = Problem(g, oracle.IM_IFM_FORWARD).check(what="mfma d=256")
+    say("    " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
+
+
 def test_mfma_dead_segments_and_fully_masked_rows():
     say("[case] mfma dead segments / fully masked rows")
     g = synth.attention_inputs(2, (9, 70, 33), 64, 1, "bf16", "none", seed=9, bias=True)
