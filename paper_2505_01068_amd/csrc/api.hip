@@ -96,21 +96,11 @@ static Path pick_path(const im_shape_t* s) {
   if (rowlane_supports(dh)) return PATH_ROWLANE;
   return PATH_NONE;
 }
-// Inference (nothing saved for a backward) at bf16 head dims 8 / 16 with d % 64 == 0 can run the
-// matrix-core forward in its sub-head mode instead of the row-per-lane kernel.
-static bool subhead_forward(const im_shape_t* s) {
-  const int dh = s->d_model / s->n_heads;
-  if (s->dtype != IM_DTYPE_BF16 || (dh != 8 && dh != 16) || s->d_model % 64 != 0) return false;
-  long max_seg = 0;
-  for (int i = 0; i < s->n_seg; ++i) max_seg = s->seg_len[i] > max_seg ? s->seg_len[i] : max_seg;
-  return max_seg * 3L * s->d_model * 2L < (1L << 31) && 3L * s->d_model * 2L < (1L << 24);
-}
-
 static int check_supported(const im_shape_t* s) {
   if (pick_path(s) == PATH_NONE)
     return fail(IM_ERR_UNSUPPORTED,
                 "no kernel for dtype %d with head dimension %d (supported: head dim <= 16 for fp32/bf16; bf16 with "
-                "head dim 64, d_model %% 64 == 0 and segment length * d_model < 2^28)",
+                "head dim 8, 16 or 64, d_model %% 64 == 0 and segment length * d_model < 2^28)",
                 s->dtype, s->d_model / s->n_heads);
   return IM_OK;
 }
@@ -334,7 +324,7 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
       if ((rc = launch_colsum(dqkv + i * d * es, 3 * d, (int)R, (int)d, bf, (float*)dbs[i], cpart, st))) return rc;
     }
   // dx = dQ Wq^T + dK Wk^T + dV Wv^T
-  if (dx && mm) {
+  if (dx && mm && d % 64 == 0) {  // the contraction is split over three weights: whole 64-deep k-tiles per weight
     ProfScope ps(PF_PROJ_BWD, st);
     mfma_dgrad(dqkv, 3 * d, wq, wk, wv, d, (int)d, dx, d, (int)R, (int)d, (int)(3 * d), st);
   } else if (dx) {
@@ -437,7 +427,7 @@ int im_attention_fwd(const im_shape_t* shape, const void* x, const void* wq, con
     return fail(IM_ERR_WORKSPACE, "im_attention_fwd needs %zu workspace bytes, got %zu", need, workspace_bytes);
   char* sv = saved ? (char*)saved : (char*)workspace;
   char* ws = saved ? (char*)workspace : (char*)workspace + L.total;
-  if (path == PATH_MFMA || (!saved && subhead_forward(shape)))
+  if (path == PATH_MFMA)
     return mfma_attention_fwd(shape, x, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, y, nullptr, sv, L.qkv,
                               L.o, L.lse, L.extra, ws, as_stream(hip_stream));
   return fwd_rowlane(shape, x, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, y, nullptr, sv,
@@ -520,7 +510,7 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
   if ((rc = launch_layernorm(x, ln1_g, ln1_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
   // h = x + IMAttention(u)
   const SavedLayout L = saved_layout(shape);
-  if (pick_path(shape) == PATH_MFMA || subhead_forward(shape))
+  if (pick_path(shape) == PATH_MFMA)
     rc = mfma_attention_fwd(shape, u, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, h, x, aw, L.qkv, L.o, L.lse,
                             L.extra, aw + L.total, st);
   else

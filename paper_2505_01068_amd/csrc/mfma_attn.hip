@@ -306,7 +306,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
 
 // ------------------------------------------------------------------------------------------
 // dQ (and delta = rowsum(dO * O)).  Same ownership as the forward: lane <-> query row.
-template <int QB>
+template <int QB, int DH>
 __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
                                                       const bf16_t* __restrict__ O,
                                                       const bf16_t* __restrict__ dO, long ldo,
@@ -325,7 +325,14 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
   const int d = g.d;
   const float c = fmaxf(g.scale_log2e, 1e-30f);  // > 0 so that -inf * c stays -inf when scale == 0
 
-  bf16x8 qreg[QB][4], greg[QB][4];
+  // sub-head mode (DH = 8 / 16) as in the forward: one k-step for S^T and dP^T, one 32-row block of dQ^T
+  constexpr int NS = DH == 64 ? 4 : 1;
+  constexpr int NDB = DH == 64 ? 2 : 1;
+  const int cg = (h * DH) >> 6, wo = (h * DH) & 63;
+  const int s0 = DH == 64 ? 0 : wo >> 4, db0 = DH == 64 ? 0 : wo >> 5;
+  const bool other_half = DH == 8 && hi != ((wo >> 3) & 1);  // this lane half holds another head's columns
+
+  bf16x8 qreg[QB][NS], greg[QB][NS];
   int qrow[QB];
   float ls[QB], dl[QB];
 #pragma unroll
@@ -333,14 +340,17 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
     qrow[qb] = q0 + (wave * QB + qb) * 32 + lo;
     const int rc = min(qrow[qb], qlen - 1);
     const long t = (long)b * g.T + g.seg_off[qs] + rc;
-    const bf16_t* p = QKV + t * ld + h * 64 + hi * 8;
-    const bf16_t* pg = dO + t * ldo + h * 64 + hi * 8;
-    const bf16_t* po = O + t * ldo + h * 64 + hi * 8;
+    const bf16_t* p = QKV + t * ld + cg * 64 + hi * 8;
+    const bf16_t* pg = dO + t * ldo + cg * 64 + hi * 8;
+    const bf16_t* po = O + t * ldo + cg * 64 + hi * 8;
     float acc = 0.f;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      qreg[qb][s] = as_bf16x8(*(const u32x4*)(p + s * 16));
-      const u32x4 gv = *(const u32x4*)(pg + s * 16), ov = *(const u32x4*)(po + s * 16);
+    for (int s = 0; s < NS; ++s) {
+      u32x4 qv = *(const u32x4*)(p + (s0 + s) * 16);
+      u32x4 gv = *(const u32x4*)(pg + (s0 + s) * 16);
+      const u32x4 ov = *(const u32x4*)(po + (s0 + s) * 16);
+      if (other_half) { qv = u32x4{0u, 0u, 0u, 0u}; gv = qv; }
+      qreg[qb][s] = as_bf16x8(qv);
       greg[qb][s] = as_bf16x8(gv);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -356,11 +366,11 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
     if (hi == 0 && qrow[qb] < qlen) delta[li] = acc;
   }
 
-  f32x16 dqacc[2][QB];
+  f32x16 dqacc[NDB][QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
       for (int r = 0; r < 16; ++r) dqacc[db][qb][r] = 0.f;
 
@@ -370,7 +380,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
 #pragma unroll
-    for (int s = 0; s < 4; ++s) asm volatile("" :: "v"(qreg[qb][s]), "v"(greg[qb][s]));
+    for (int s = 0; s < NS; ++s) asm volatile("" :: "v"(qreg[qb][s]), "v"(greg[qb][s]));
     asm volatile("" :: "v"(ls[qb]), "v"(dl[qb]));
   }
 
@@ -379,7 +389,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
     if (valid_len) n = min(n, max(0, valid_len[b * g.n_seg + j]));
     return n;
   };
-  const RingLane rl = ring_lane(wave, lane, h);
+  const RingLane rl = ring_lane(wave, lane, cg);
   const unsigned ldb = (unsigned)ld * 2u;
   TileCursor ic = {g.q_live[qs], 0, 0, 0}, cc = ic;
   cursor_next_seg(ic, klen_of);
@@ -415,9 +425,9 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
 #pragma unroll
           for (int r = 0; r < 16; ++r) { sacc[qb][r] = 0.f; pacc[qb][r] = 0.f; }
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const bf16x8 ak = lds_frag_sw(sK, kb * 32, prow, 2 * s + hi);
-          const bf16x8 av = lds_frag_sw(sV, kb * 32, prow, 2 * s + hi);
+        for (int s = 0; s < NS; ++s) {
+          const bf16x8 ak = lds_frag_sw(sK, kb * 32, prow, 2 * (s0 + s) + hi);
+          const bf16x8 av = lds_frag_sw(sV, kb * 32, prow, 2 * (s0 + s) + hi);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) {
             sacc[qb] = mfma32(ak, qreg[qb][s], sacc[qb]);   // S^T  = K Q^T
@@ -445,10 +455,10 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
       }
       // dQ^T += K^T dS^T
 #pragma unroll
-      for (int db = 0; db < 2; ++db)
+      for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const bf16x8 a = lds_frag_tr_sw(sK, s * 16, db * 32, lane);
+          const bf16x8 a = lds_frag_tr_sw(sK, s * 16, (db0 + db) * 32, lane);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) dqacc[db][qb] = mfma32(a, dsb[s >> 1][qb][s & 1], dqacc[db][qb]);
         }
@@ -461,15 +471,16 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
     if (row >= qlen) continue;
     const long t = (long)b * g.T + g.seg_off[qs] + row;
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int dh0 = db * 32 + 8 * i + 4 * hi;
+        const int dh0 = (db0 + db) * 32 + 8 * i + 4 * hi;  // column inside the 64-column group
+        if (DH < 64 && (dh0 < wo || dh0 >= wo + DH)) continue;
         float v[4];
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) v[jj] = dqacc[db][qb][4 * i + jj] * g.scale;
         const u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-        *(u32x2*)(dQKV + t * ldg + h * 64 + dh0) = pk;
+        *(u32x2*)(dQKV + t * ldg + cg * 64 + dh0) = pk;
       }
   }
 }
@@ -482,7 +493,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
 // Ring stage = Q tile, dO tile (see RING_STAGE) plus the 64 lse and 64 delta values of the rows.
 __device__ const float k_pos_inf = __builtin_inff();
 
-template <int KB>
+template <int KB, int DH>
 __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
                                                        const bf16_t* __restrict__ dO, long ldo,
                                                        const float* __restrict__ lse2, const float* __restrict__ delta,
@@ -501,8 +512,15 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
   const int d = g.d;
   const float c = fmaxf(g.scale_log2e, 1e-30f);  // > 0 so that -inf * c stays -inf when scale == 0
 
+  // sub-head mode (DH = 8 / 16): one k-step for S and dP, one 32-row block of dV^T and dK^T
+  constexpr int NS = DH == 64 ? 4 : 1;
+  constexpr int NDB = DH == 64 ? 2 : 1;
+  const int cg = (h * DH) >> 6, wo = (h * DH) & 63;
+  const int s0 = DH == 64 ? 0 : wo >> 4, db0 = DH == 64 ? 0 : wo >> 5;
+  const bool other_half = DH == 8 && hi != ((wo >> 3) & 1);  // this lane half holds another head's columns
+
   auto qlen_of = [&](int i) { return g.seg_len[i]; };
-  const RingLane rl = ring_lane(wave, lane, h);
+  const RingLane rl = ring_lane(wave, lane, cg);
   const unsigned ldb = (unsigned)ld * 2u, ldob = (unsigned)ldo * 2u;  // row pitches in bytes
   TileCursor ic = {g.k_live[ks], 0, 0, 0}, cc = ic;
   cursor_next_seg(ic, qlen_of);
@@ -523,7 +541,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
     cursor_step(ic, qlen_of);
   };
 
-  bf16x8 kreg[KB][4], vreg[KB][4];
+  bf16x8 kreg[KB][NS], vreg[KB][NS];
   int krow[KB];
   bool kvalid[KB];
 #pragma unroll
@@ -531,11 +549,13 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
     krow[kb] = k0 + (wave * KB + kb) * 32 + lo;
     const int rc = min(krow[kb], klen_seg - 1);
     const long t = (long)b * g.T + g.seg_off[ks] + rc;
-    const bf16_t* p = QKV + t * ld + d + h * 64 + hi * 8;
+    const bf16_t* p = QKV + t * ld + d + cg * 64 + hi * 8;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      kreg[kb][s] = as_bf16x8(*(const u32x4*)(p + s * 16));
-      vreg[kb][s] = as_bf16x8(*(const u32x4*)(p + d + s * 16));
+    for (int s = 0; s < NS; ++s) {
+      u32x4 kv = *(const u32x4*)(p + (s0 + s) * 16), vv = *(const u32x4*)(p + d + (s0 + s) * 16);
+      if (other_half) { kv = u32x4{0u, 0u, 0u, 0u}; vv = kv; }
+      kreg[kb][s] = as_bf16x8(kv);
+      vreg[kb][s] = as_bf16x8(vv);
     }
     bool ok = krow[kb] < klen_seg;
     if (ok && valid_len) ok = krow[kb] < valid_len[b * g.n_seg + ks];
@@ -543,11 +563,11 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
     kvalid[kb] = ok;
   }
 
-  f32x16 dkacc[2][KB], dvacc[2][KB];
+  f32x16 dkacc[NDB][KB], dvacc[NDB][KB];
 #pragma unroll
   for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
       for (int r = 0; r < 16; ++r) { dkacc[db][kb][r] = 0.f; dvacc[db][kb][r] = 0.f; }
 
@@ -557,7 +577,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
 #pragma unroll
   for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-    for (int s = 0; s < 4; ++s) asm volatile("" :: "v"(kreg[kb][s]), "v"(vreg[kb][s]));
+    for (int s = 0; s < NS; ++s) asm volatile("" :: "v"(kreg[kb][s]), "v"(vreg[kb][s]));
 
   if (ic.len > 0) { issue(); ++inflight; }
   if (ic.len > 0) { issue(); ++inflight; }
@@ -601,9 +621,9 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
 #pragma unroll
         for (int r = 0; r < 16; ++r) { sacc[kb][r] = 0.f; pacc[kb][r] = 0.f; }
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const bf16x8 aq = lds_frag_sw(sQ, qb * 32, prow, 2 * s + hi);
-        const bf16x8 ag = lds_frag_sw(sG, qb * 32, prow, 2 * s + hi);
+      for (int s = 0; s < NS; ++s) {
+        const bf16x8 aq = lds_frag_sw(sQ, qb * 32, prow, 2 * (s0 + s) + hi);
+        const bf16x8 ag = lds_frag_sw(sG, qb * 32, prow, 2 * (s0 + s) + hi);
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
           sacc[kb] = mfma32(aq, kreg[kb][s], sacc[kb]);   // S  = Q K^T
@@ -623,11 +643,11 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
       }
       // dV^T += dO^T P ; dK^T += Q^T dS   (contraction over the 32 query rows of this block)
 #pragma unroll
-      for (int db = 0; db < 2; ++db)
+      for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-          const bf16x8 agt = lds_frag_tr_sw(sG, qb * 32 + half * 16, db * 32, lane);
-          const bf16x8 aqt = lds_frag_tr_sw(sQ, qb * 32 + half * 16, db * 32, lane);
+          const bf16x8 agt = lds_frag_tr_sw(sG, qb * 32 + half * 16, (db0 + db) * 32, lane);
+          const bf16x8 aqt = lds_frag_tr_sw(sQ, qb * 32 + half * 16, (db0 + db) * 32, lane);
 #pragma unroll
           for (int kb = 0; kb < KB; ++kb) {
             dvacc[db][kb] = mfma32(agt, pb[kb][half], dvacc[db][kb]);
@@ -644,16 +664,17 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
     const long t = (long)b * g.T + g.seg_off[ks] + row;
     const float zk = kvalid[kb] ? g.scale : 0.f, zv = kvalid[kb] ? 1.f : 0.f;
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int dh0 = db * 32 + 8 * i + 4 * hi;
+        const int dh0 = (db0 + db) * 32 + 8 * i + 4 * hi;  // column inside the 64-column group
+        if (DH < 64 && (dh0 < wo || dh0 >= wo + DH)) continue;
         const u32x2 pk = {pack_bf16(dkacc[db][kb][4 * i] * zk, dkacc[db][kb][4 * i + 1] * zk),
                           pack_bf16(dkacc[db][kb][4 * i + 2] * zk, dkacc[db][kb][4 * i + 3] * zk)};
         const u32x2 pv = {pack_bf16(dvacc[db][kb][4 * i] * zv, dvacc[db][kb][4 * i + 1] * zv),
                           pack_bf16(dvacc[db][kb][4 * i + 2] * zv, dvacc[db][kb][4 * i + 3] * zv)};
-        *(u32x2*)(dQKV + t * ldg + d + h * 64 + dh0) = pk;
-        *(u32x2*)(dQKV + t * ldg + 2 * d + h * 64 + dh0) = pv;
+        *(u32x2*)(dQKV + t * ldg + d + cg * 64 + dh0) = pk;
+        *(u32x2*)(dQKV + t * ldg + 2 * d + cg * 64 + dh0) = pv;
       }
   }
 }
@@ -709,11 +730,15 @@ void launch_mfma_bwd(const Geo& g, const bf16_t* qkv, long ld, const bf16_t* o, 
   const int nq = g.q_tile_prefix[g.q_nord], nk = g.k_tile_prefix[g.k_nord];
   if (nq == 0) return;
   { ProfScope ps(PF_ATTN_DQ, st);
-    hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB>), dim3(nq, g.H, g.B), dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2,
-                       valid_len, key_pad, delta, dqkv, ldg); }
+    const dim3 grid(nq, g.H, g.B);
+    if (g.dh == 64) hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 64>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg);
+    else if (g.dh == 16) hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 16>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg);
+    else hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 8>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg); }
   { ProfScope ps(PF_ATTN_DKV, st);
-    hipLaunchKernelGGL((mfma_dkv_kernel<DKV_KB>), dim3(nk, g.H, g.B), dim3(256), 0, st, g, qkv, ld, d_o, ldo, lse2, delta,
-                       valid_len, key_pad, dqkv, ldg); }
+    const dim3 grid(nk, g.H, g.B);
+    if (g.dh == 64) hipLaunchKernelGGL((mfma_dkv_kernel<DKV_KB, 64>), grid, dim3(256), 0, st, g, qkv, ld, d_o, ldo, lse2, delta, valid_len, key_pad, dqkv, ldg);
+    else if (g.dh == 16) hipLaunchKernelGGL((mfma_dkv_kernel<DKV_KB, 16>), grid, dim3(256), 0, st, g, qkv, ld, d_o, ldo, lse2, delta, valid_len, key_pad, dqkv, ldg);
+    else hipLaunchKernelGGL((mfma_dkv_kernel<DKV_KB, 8>), grid, dim3(256), 0, st, g, qkv, ld, d_o, ldo, lse2, delta, valid_len, key_pad, dqkv, ldg); }
 }
 
 }  // namespace imattn

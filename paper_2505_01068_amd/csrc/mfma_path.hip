@@ -13,7 +13,8 @@ namespace imattn {
 
 static inline size_t al(size_t n) { return (n + 255) & ~(size_t)255; }
 
-bool mfma_supports(int d_model, int dh) { return dh == 64 && d_model % 64 == 0; }
+// head dimension 64, or 8 / 16 in sub-head mode (a head = a slice of a 64-column group)
+bool mfma_supports(int d_model, int dh) { return (dh == 64 || dh == 16 || dh == 8) && d_model % 64 == 0; }
 
 struct Dims { size_t B, T, d, R; };
 static Dims dims(const im_shape_t* s) {

@@ -23,7 +23,7 @@ void launch_mfma_gemm(const MGemm& p, hipStream_t st);
 // optionally three weight / bias blocks of n_per columns each.  Usable when K % 8 == 0 and N % 8 == 0.
 inline bool mfma_linear_ok(int is_bf16, long K, long N) { return is_bf16 && K % 8 == 0 && N % 8 == 0 && K >= 8 && N >= 8; }
 // data gradient  C[M,N] = G[M,K] W^T  with W stored [N][K'] row-major; the contraction may run over up to three
-// weights of k_per columns each (K = 3 k_per), as in dx = dQ Wq^T + dK Wk^T + dV Wv^T
+// weights of k_per columns each (K = 3 k_per, k_per % 64 == 0), as in dx = dQ Wq^T + dK Wk^T + dV Wv^T
 void mfma_dgrad(const void* G, long ldg, const void* w0, const void* w1, const void* w2, long ldw, int k_per, void* C,
                 long ldc, int M, int N, int K, hipStream_t st);
 // weight gradient  C[M,N] (fp32) = A[R,M]^T G[R,N]  (contraction over rows), split-K with a fixed-order

@@ -66,11 +66,22 @@ def test_layer_backward_fp32(name, padding):
 
 @pytest.mark.parametrize("bias", [True, False])
 def test_layer_backward_bf16_small_heads(bias):
-    say(f"[case] layer bwd bf16 d=64 (row-per-lane attention) bias={bias}")
+    say(f"[case] layer bwd bf16 d=64 (sub-head matrix-core attention) bias={bias}")
     d, H, d_ff, seg = 64, 8, 256, (50, 200, 130)
     g = synth.attention_inputs(3, seg, d, H, "bf16", "valid_len", seed=502)
     p = synth.layer_params(d, d_ff, 502, 0, dtype="bf16", bias=bias)
     errs = check(g, p, oracle.IM_IFM_FORWARD, "bf16", d_ff, "layer-bwd/bf16/d64")
+    say("    " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
+
+
+def test_layer_backward_bf16_narrow_widths():
+    # d = 40 (head dim 5: row-per-lane attention), d_ff = 104: multiples of 8 but not of 64, so the
+    # matrix-core GEMMs run with partial k-tiles and the split data gradient stays on the ALU GEMM
+    say("[case] layer bwd bf16 d=40 d_ff=104")
+    d, H, d_ff, seg = 40, 8, 104, (50, 200, 130)
+    g = synth.attention_inputs(3, seg, d, H, "bf16", "key_pad", seed=505)
+    p = synth.layer_params(d, d_ff, 505, 0, dtype="bf16")
+    errs = check(g, p, oracle.IM_IFM_FORWARD, "bf16", d_ff, "layer-bwd/bf16/d40")
     say("    " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
 
 
