@@ -243,7 +243,10 @@ def bench_layer_train(args):
         "kernel_ms_note": "dominant attention family: HIP events over the timed steps; the other families: a separate pass after them with every family bracketed",
         "roofline": {"bound": "alu", "kernel": dom, "achieved": round(achieved, 3), "peak": PEAK_FP32_VALU_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_VALU_TFLOPS, 4), "traffic": None,
-                     "avg_launch_ms": round(per_step[dom], 4)},
+                     "avg_launch_ms": round(per_step[dom], 4),
+                     "note": "head dim 8: the contractions run on the matrix cores in sub-head mode (1/8 to 1/2 of each MFMA "
+                             "is useful work); the softmax's plain-ALU instructions bound the kernel, so the algorithmic "
+                             "flops are set against the fp32 vector peak"},
     }
     if not args.no_cpu_baseline:
         import oracle
@@ -339,7 +342,7 @@ def main():
            "proj_fwd": 8.0 * Bsz * T * d * d, "proj_bwd": 8.0 * Bsz * T * d * d, "wgrad": 8.0 * Bsz * T * d * d}
     attn_keys = [k for k in ("attn_fwd", "attn_dq", "attn_dkv") if k in per_step]
     dom_ms = per_step[dom]
-    traffic = stored_traffic(args.config, dom)
+    traffic = stored_traffic(args.config, dom) if args.mask == "ifm_forward" else None   # counters were taken with the default mask
     mfma_bound = dtype == "bf16" and d // H == 64
     if mfma_bound:
         achieved = alg[dom] / (dom_ms * 1e-3) / 1e12
