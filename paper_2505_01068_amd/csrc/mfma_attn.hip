@@ -79,16 +79,40 @@ __device__ __forceinline__ RingLane ring_lane(int wave, int lane, int h) {
   r.col1 = (unsigned)(h * 64 + (((lane & 7) ^ sw_f(r.trow1)) << 3)) * 2u;
   return r;
 }
-// Request rows r0 .. r0+63 (clamped to row_max) of two [rows, pitch] matrices a and b (wave-uniform
-// bases, row pitches in bytes) into the two tiles of LDS stage `stage`.  4 copies per wave.
-__device__ __forceinline__ void ring_issue_pair(const RingLane& rl, int wave, const bf16_t* a, unsigned pitch_a,
-                                                const bf16_t* b, unsigned pitch_b, int r0, int row_max,
-                                                bf16_t* stage) {
-  const unsigned r0c = (unsigned)min(r0 + rl.trow0, row_max), r1c = (unsigned)min(r0 + rl.trow1, row_max);
-  dma16_off(a, __umul24(r0c, pitch_a) + rl.col0, stage + wave * 512);
-  dma16_off(b, __umul24(r0c, pitch_b) + rl.col0, stage + KT * SW_LD + wave * 512);
-  dma16_off(a, __umul24(r1c, pitch_a) + rl.col1, stage + (4 + wave) * 512);
-  dma16_off(b, __umul24(r1c, pitch_b) + rl.col1, stage + KT * SW_LD + (4 + wave) * 512);
+// Scalar state of the ring copies inside the current segment: byte pointers to the first row of the
+// next tile of the two streamed matrices, and the rows the segment has from there on (> 0).  Kept in
+// scalar registers and advanced by one tile per request, so a request costs a handful of scalar adds.
+struct RingFeed {
+  const char* a;
+  const char* b;
+  int rows;
+};
+// per-lane byte offsets of this lane's four chunks in a tile that lies wholly inside the segment
+struct RingLaneOff { unsigned a0, b0, a1, b1; };
+__device__ __forceinline__ RingLaneOff ring_lane_off(const RingLane& rl, unsigned pitch_a, unsigned pitch_b) {
+  return {__umul24((unsigned)rl.trow0, pitch_a) + rl.col0, __umul24((unsigned)rl.trow0, pitch_b) + rl.col0,
+          __umul24((unsigned)rl.trow1, pitch_a) + rl.col1, __umul24((unsigned)rl.trow1, pitch_b) + rl.col1};
+}
+// Request the next 64-row tile pair of the segment into LDS stage `stage` (4 copies per wave; row
+// pitches in bytes) and advance the feed.  Only the last tile of a segment can be ragged; its
+// missing rows repeat the segment's last row.
+__device__ __forceinline__ void ring_feed_issue(const RingLane& rl, const RingLaneOff& lo, RingFeed& f, unsigned pitch_a,
+                                                unsigned pitch_b, int wave, bf16_t* stage) {
+  if (f.rows >= KT) {
+    dma16_off(f.a, lo.a0, stage + wave * 512);
+    dma16_off(f.b, lo.b0, stage + KT * SW_LD + wave * 512);
+    dma16_off(f.a, lo.a1, stage + (4 + wave) * 512);
+    dma16_off(f.b, lo.b1, stage + KT * SW_LD + (4 + wave) * 512);
+  } else {
+    const unsigned r0c = (unsigned)min(rl.trow0, f.rows - 1), r1c = (unsigned)min(rl.trow1, f.rows - 1);
+    dma16_off(f.a, __umul24(r0c, pitch_a) + rl.col0, stage + wave * 512);
+    dma16_off(f.b, __umul24(r0c, pitch_b) + rl.col0, stage + KT * SW_LD + wave * 512);
+    dma16_off(f.a, __umul24(r1c, pitch_a) + rl.col1, stage + (4 + wave) * 512);
+    dma16_off(f.b, __umul24(r1c, pitch_b) + rl.col1, stage + KT * SW_LD + (4 + wave) * 512);
+  }
+  f.a += (size_t)KT * pitch_a;
+  f.b += (size_t)KT * pitch_b;
+  f.rows -= KT;
 }
 // wait until at most `later` (0 or 1) stages of 4 copies requested after the wanted one are
 // outstanding, then meet the other waves: the wanted stage is visible to all, and every wave has
@@ -115,7 +139,8 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
                                                        const uint8_t* __restrict__ key_pad, bf16_t* __restrict__ O,
                                                        long ldo, float* __restrict__ lse2) {
   __shared__ __attribute__((aligned(1024))) bf16_t sT[RING_NST * RING_STAGE];  // per stage: K tile, V tile
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: branches on it are wave-uniform
   int tile, h, b;
   xcd_block_index(tile, h, b);
   constexpr int WG_ROWS = 128 * QB;
@@ -181,12 +206,23 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
   cursor_next_seg(ic, klen_of);
   cursor_next_seg(cc, klen_of);
   int islot = 0, cslot = 0, inflight = 0;
+  const RingLaneOff rlo = ring_lane_off(rl, ldb, ldb);
+  RingFeed feed = {nullptr, nullptr, 0};
+  // K and V rows of segment ic.seg; rows past the valid length but inside the segment are fetched and masked
+  auto seg_begin = [&]() {
+    feed.a = (const char*)(QKV + ((long)b * g.T + g.seg_off[ic.seg]) * ld + d);
+    feed.b = feed.a + (size_t)d * 2;
+    feed.rows = g.seg_len[ic.seg];
+  };
+  if (ic.len > 0) seg_begin();
   auto issue = [&]() {
-    const bf16_t* Kb = QKV + ((long)b * g.T + g.seg_off[ic.seg]) * ld + d;
-    // rows past the valid length but inside the segment are fetched and masked
-    ring_issue_pair(rl, wave, Kb, ldb, Kb + d, ldb, ic.r0, g.seg_len[ic.seg] - 1, sT + islot * RING_STAGE);
+    ring_feed_issue(rl, rlo, feed, ldb, ldb, wave, sT + islot * RING_STAGE);
     islot = (islot + 1 == RING_NST) ? 0 : islot + 1;
-    cursor_step(ic, klen_of);
+    ic.r0 += KT;
+    if (ic.r0 >= ic.len) {
+      cursor_next_seg(ic, klen_of);
+      if (ic.len > 0) seg_begin();
+    }
   };
   if (ic.len > 0) { issue(); ++inflight; }
   if (ic.len > 0) { issue(); ++inflight; }
@@ -315,7 +351,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
                                                       const uint8_t* __restrict__ key_pad, float* __restrict__ delta,
                                                       bf16_t* __restrict__ dQKV, long ldg) {
   __shared__ __attribute__((aligned(1024))) bf16_t sT[RING_NST * RING_STAGE];  // per stage: K tile, V tile
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: branches on it are wave-uniform
   int tile, h, b;
   xcd_block_index(tile, h, b);
   constexpr int WG_ROWS = 128 * QB;
@@ -363,7 +400,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
     const long li = ((long)b * g.H + h) * g.T + g.seg_off[qs] + rc;
     const float lv = lse2[li];
     ls[qb] = lv;  // +inf for a row without valid keys: every probability is exactly zero
-    if (hi == 0 && qrow[qb] < qlen) delta[li] = acc;
+    if (hi == 0 && qrow[qb] < qlen) delta[li] = DH == 64 ? -acc : acc;  // see the dK/dV kernel
   }
 
   f32x16 dqacc[NDB][QB];
@@ -395,11 +432,23 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
   cursor_next_seg(ic, klen_of);
   cursor_next_seg(cc, klen_of);
   int islot = 0, cslot = 0, inflight = 0;
+  const RingLaneOff rlo = ring_lane_off(rl, ldb, ldb);
+  RingFeed feed = {nullptr, nullptr, 0};
+  // K and V rows of segment ic.seg; rows past the valid length but inside the segment are fetched and masked
+  auto seg_begin = [&]() {
+    feed.a = (const char*)(QKV + ((long)b * g.T + g.seg_off[ic.seg]) * ld + d);
+    feed.b = feed.a + (size_t)d * 2;
+    feed.rows = g.seg_len[ic.seg];
+  };
+  if (ic.len > 0) seg_begin();
   auto issue = [&]() {
-    const bf16_t* Kb = QKV + ((long)b * g.T + g.seg_off[ic.seg]) * ld + d;
-    ring_issue_pair(rl, wave, Kb, ldb, Kb + d, ldb, ic.r0, g.seg_len[ic.seg] - 1, sT + islot * RING_STAGE);
+    ring_feed_issue(rl, rlo, feed, ldb, ldb, wave, sT + islot * RING_STAGE);
     islot = (islot + 1 == RING_NST) ? 0 : islot + 1;
-    cursor_step(ic, klen_of);
+    ic.r0 += KT;
+    if (ic.r0 >= ic.len) {
+      cursor_next_seg(ic, klen_of);
+      if (ic.len > 0) seg_begin();
+    }
   };
   if (ic.len > 0) { issue(); ++inflight; }
   if (ic.len > 0) { issue(); ++inflight; }
@@ -491,6 +540,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
 // has exactly one producer, so the result is deterministic without atomics.
 //
 // Ring stage = Q tile, dO tile (see RING_STAGE) plus the 64 lse and 64 delta values of the rows.
+// At head dim 64 the delta buffer holds -delta (the dQ kernel writes it so): the dP accumulator
+// starts from it, so the MFMA chain ends as dP - delta and no separate subtraction is needed.
 __device__ const float k_pos_inf = __builtin_inff();
 
 template <int KB, int DH>
@@ -502,7 +553,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
                                                        long ldg) {
   __shared__ __attribute__((aligned(1024))) bf16_t sT[RING_NST * RING_STAGE];
   __shared__ __attribute__((aligned(256))) float sLD[RING_NST * 2 * KT];  // per stage: lse[64], delta[64]
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: branches on it are wave-uniform
   int tile, h, b;
   xcd_block_index(tile, h, b);
   constexpr int WG_ROWS = 128 * KB;
@@ -526,19 +578,41 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
   cursor_next_seg(ic, qlen_of);
   cursor_next_seg(cc, qlen_of);
   int islot = 0, cslot = 0, inflight = 0;
-  auto issue = [&]() {
+  const RingLaneOff rlo = ring_lane_off(rl, ldb, ldob);
+  RingFeed feed = {nullptr, nullptr, 0};
+  const float* feed_l = nullptr;  // lse and delta of the next tile's first row
+  const float* feed_d = nullptr;
+  auto seg_begin = [&]() {  // Q and dO rows, lse and delta of segment ic.seg
     const long row0 = (long)b * g.T + g.seg_off[ic.seg];
-    ring_issue_pair(rl, wave, QKV + row0 * ld, ldb, dO + row0 * ldo, ldob, ic.r0, ic.len - 1, sT + islot * RING_STAGE);
+    const long lb = ((long)b * g.H + h) * g.T + g.seg_off[ic.seg];
+    feed.a = (const char*)(QKV + row0 * ld);
+    feed.b = (const char*)(dO + row0 * ldo);
+    feed.rows = ic.len;
+    feed_l = lse2 + lb;
+    feed_d = delta + lb;
+  };
+  if (ic.len > 0) seg_begin();
+  auto issue = [&]() {
     // lse (wave 0) and delta (wave 1), one float per lane.  Rows past the segment read +inf as
     // lse, so their probabilities are exactly zero.
     if (wave < 2) {
-      const int r = ic.r0 + lane;
-      const long lb = ((long)b * g.H + h) * g.T + g.seg_off[ic.seg];
-      const float* src = (wave == 0) ? (r < ic.len ? lse2 + lb + r : &k_pos_inf) : delta + lb + min(r, ic.len - 1);
-      dma4(src, sLD + islot * 2 * KT + wave * KT);
+      float* dst = sLD + islot * 2 * KT + wave * KT;
+      if (feed.rows >= KT) {
+        dma4_off(wave == 0 ? feed_l : feed_d, (unsigned)lane * 4u, dst);
+      } else {
+        const float* src = (wave == 0) ? (lane < feed.rows ? feed_l + lane : &k_pos_inf) : feed_d + min(lane, feed.rows - 1);
+        dma4(src, dst);
+      }
     }
+    feed_l += KT;
+    feed_d += KT;
+    ring_feed_issue(rl, rlo, feed, ldb, ldob, wave, sT + islot * RING_STAGE);
     islot = (islot + 1 == RING_NST) ? 0 : islot + 1;
-    cursor_step(ic, qlen_of);
+    ic.r0 += KT;
+    if (ic.r0 >= ic.len) {
+      cursor_next_seg(ic, qlen_of);
+      if (ic.len > 0) seg_begin();
+    }
   };
 
   bf16x8 kreg[KB][NS], vreg[KB][NS];
@@ -619,7 +693,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { sacc[kb][r] = 0.f; pacc[kb][r] = 0.f; }
+        for (int r = 0; r < 16; ++r) { sacc[kb][r] = 0.f; pacc[kb][r] = DH == 64 ? D[r] : 0.f; }
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
         const bf16x8 aq = lds_frag_sw(sQ, qb * 32, prow, 2 * (s0 + s) + hi);
@@ -636,7 +710,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           p[r] = fast_exp2(fmaf(sacc[kb][r], c, -L[r]));
-          ds[r] = p[r] * (pacc[kb][r] - D[r]);
+          ds[r] = DH == 64 ? p[r] * pacc[kb][r] : p[r] * (pacc[kb][r] - D[r]);
         }
         pb[kb][0] = pack8(p); pb[kb][1] = pack8(p + 8);
         dsb[kb][0] = pack8(ds); dsb[kb][1] = pack8(ds + 8);

@@ -106,6 +106,10 @@ __device__ __forceinline__ void dma16_off(const void* gbase, unsigned byte_off, 
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :: "s"(lds_offset(lds_wave_base)), "v"(byte_off), "s"(gbase) : "memory");
 }
+__device__ __forceinline__ void dma4_off(const void* gbase, unsigned byte_off, const void* lds_wave_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+               :: "s"(lds_offset(lds_wave_base)), "v"(byte_off), "s"(gbase) : "memory");
+}
 __device__ __forceinline__ void dma4(const void* gptr, const void* lds_wave_base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
                :: "s"(lds_offset(lds_wave_base)), "v"(gptr) : "memory");
