@@ -76,6 +76,16 @@ typedef struct im_shape {
   uint64_t live_mask;          /* the IM: bit (i*n_seg + j) <=> block (query seg i, key seg j) live */
   float scale;                 /* multiplies Q K^T before the softmax (App. B "apply scaling and softmax"); finite, >= 0; usually 1/sqrt(dh) */
   int32_t dtype;               /* IM_DTYPE_F32 or IM_DTYPE_BF16 */
+  /* Packed rows (no padding rows in memory; the datasets' sequences are far shorter than their
+   * maxima, Table "Dataset statistics and data forms", average vs. maximum length).  NULL: every
+   * [rows, .] tensor is [B, T_m, .] as described at the entry points.  Non-NULL: device int32
+   * [B * n_seg + 1], cu_rows[0] = 0, non-decreasing; segment s of batch element b occupies rows
+   * cu_rows[b*n_seg+s] .. cu_rows[b*n_seg+s+1]-1 of [total_rows, .] tensors, its length may be
+   * anything in 0..seg_len[s] (seg_len then only bounds the lengths).  valid_len must be NULL
+   * (the lengths are in cu_rows); key_pad, if given, is [total_rows].  Supported by
+   * im_attention_* and gsit_layer_*; the whole-model call needs padded rows. */
+  const int32_t* cu_rows;
+  int64_t total_rows;          /* = cu_rows[B * n_seg] (host copy), >= 1; ignored when cu_rows is NULL */
 } im_shape_t;
 
 /* One unit of the live-block schedule (host side; see im_schedule_build). */

@@ -13,6 +13,7 @@ import torch
 
 IM_MAX_SEG = 8
 IM_DTYPE_F32, IM_DTYPE_BF16 = 0, 1
+IM_OK, IM_ERR_INVALID, IM_ERR_UNSUPPORTED, IM_ERR_WORKSPACE, IM_ERR_HIP = 0, -1, -2, -3, -4
 IM_IFM_FORWARD, IM_IFM_BACKWARD, IM_IEM, IM_DENSE = 0x062, 0x08C, 0x111, 0x1FF
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libimattn.so")
@@ -21,7 +22,8 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libimattn.
 class ImShape(C.Structure):
     _fields_ = [("batch", C.c_int32), ("n_seg", C.c_int32), ("seg_len", C.c_int32 * IM_MAX_SEG),
                 ("d_model", C.c_int32), ("n_heads", C.c_int32), ("live_mask", C.c_uint64),
-                ("scale", C.c_float), ("dtype", C.c_int32)]
+                ("scale", C.c_float), ("dtype", C.c_int32),
+                ("cu_rows", C.c_void_p), ("total_rows", C.c_int64)]
 
 
 class ImWorkItem(C.Structure):
@@ -82,8 +84,13 @@ def _check(rc):
         raise ImAttnError(rc, lib().im_last_error().decode())
 
 
-def make_shape(batch, seg_len, d_model, n_heads, live_mask, scale, dtype):
+def make_shape(batch, seg_len, d_model, n_heads, live_mask, scale, dtype, cu_rows=None, total_rows=0):
+    """The problem statement.  Packed rows: cu_rows = int32 device tensor [batch * n_seg + 1] of row offsets,
+    total_rows = its last entry (host int); seg_len then bounds the per-sample segment lengths.  The shape
+    keeps a reference to cu_rows, whose device memory it points into."""
     s = ImShape()
+    s.cu_rows, s.total_rows = (None, 0) if cu_rows is None else (cu_rows.data_ptr(), int(total_rows))
+    s._cu_rows_ref = cu_rows
     s.batch, s.n_seg, s.d_model, s.n_heads = int(batch), len(seg_len), int(d_model), int(n_heads)
     for i, n in enumerate(seg_len):
         s.seg_len[i] = int(n)

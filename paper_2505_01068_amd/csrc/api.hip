@@ -79,6 +79,9 @@ static int validate_shape(const im_shape_t* s) {
   if (s->dtype != IM_DTYPE_F32 && s->dtype != IM_DTYPE_BF16)
     return fail(IM_ERR_INVALID, "dtype must be IM_DTYPE_F32 or IM_DTYPE_BF16 (got %d)", s->dtype);
   if ((long)s->batch * T * s->d_model > (1l << 40)) return fail(IM_ERR_INVALID, "problem too large");
+  if (s->cu_rows && (s->total_rows < 1 || s->total_rows > (long)s->batch * T))
+    return fail(IM_ERR_INVALID, "packed rows: total_rows must be in 1..batch * T_m = %ld (got %ld)", (long)s->batch * T,
+                (long)s->total_rows);
   return IM_OK;
 }
 
@@ -137,6 +140,8 @@ void build_geo(const im_shape_t* s, int q_tile, int k_tile, Geo* g) {
   order(g->k_live, k_tile, g->k_order, g->k_tile_prefix, &g->k_nord);
   g->scale = s->scale;
   g->scale_log2e = s->scale * 1.44269504088896340736f;
+  g->cu = s->cu_rows;
+  g->R = shape_rows(s);
 }
 
 static inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
@@ -154,12 +159,12 @@ static SavedLayout saved_layout(const im_shape_t* s) {
   const size_t es = s->dtype == IM_DTYPE_BF16 ? 2 : 4;
   long T = 0;
   for (int i = 0; i < s->n_seg; ++i) T += s->seg_len[i];
-  const size_t R = (size_t)s->batch * T, d = s->d_model;
+  const size_t R = (size_t)shape_rows(s), d = s->d_model;
   SavedLayout L;
   size_t off = 0;
   L.qkv = off; off += align256(R * 3 * d * es);
   L.o = off; off += align256(R * d * es);
-  L.lse = off; off += align256((size_t)s->batch * s->n_heads * T * sizeof(float));
+  L.lse = off; off += align256((size_t)s->n_heads * R * sizeof(float));
   L.extra = off;
   if (pick_path(s) == PATH_MFMA) off += align256(mfma_saved_extra_bytes(s));
   L.total = off;
@@ -170,12 +175,12 @@ static size_t bwd_workspace_bytes(const im_shape_t* s) {
   const size_t es = s->dtype == IM_DTYPE_BF16 ? 2 : 4;
   long T = 0;
   for (int i = 0; i < s->n_seg; ++i) T += s->seg_len[i];
-  const size_t R = (size_t)s->batch * T, d = s->d_model;
+  const size_t R = (size_t)shape_rows(s), d = s->d_model;
   if (pick_path(s) == PATH_MFMA) return mfma_bwd_workspace_bytes(s);
   size_t n = 0;
   n += align256(R * d * es);                                          // dO
   n += align256(R * 3 * d * es);                                      // dQ | dK | dV
-  n += align256((size_t)s->batch * s->n_heads * T * sizeof(float));   // delta
+  n += align256((size_t)s->n_heads * R * sizeof(float));   // delta
   size_t pb = std::max(gemm_alu_partial_bytes((int)d, (int)(3 * d), (int)R, nullptr),
                        gemm_alu_partial_bytes((int)d, (int)d, (int)R, nullptr));
   if (mfma_linear_ok(s->dtype == IM_DTYPE_BF16, d, d))
@@ -200,7 +205,7 @@ static int fwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
   Geo g;
   build_geo(s, 64, 64, &g);
   const SavedLayout L = saved_layout(s);
-  const long R = (long)g.B * g.T, d = g.d;
+  const long R = g.R, d = g.d;
   char* qkv = sv + L.qkv;
   void* o = sv + L.o;
   float* lse2 = (float*)(sv + L.lse);
@@ -243,7 +248,7 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
   Geo g;
   build_geo(s, 64, 64, &g);
   const SavedLayout L = saved_layout(s);
-  const long R = (long)g.B * g.T, d = g.d;
+  const long R = g.R, d = g.d;
   const char* qkv = sv + L.qkv;
   const void* o = sv + L.o;
   const float* lse2 = (const float*)(sv + L.lse);
@@ -251,7 +256,7 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
   Bump b{ws, 0, 0};
   char* d_o = (char*)b.take(R * d * es);
   char* dqkv = (char*)b.take(R * 3 * d * es);
-  float* delta = (float*)b.take((size_t)g.B * g.H * g.T * sizeof(float));
+  float* delta = (float*)b.take((size_t)g.H * R * sizeof(float));
   int split = 1;
   size_t pbytes = std::max(gemm_alu_partial_bytes((int)d, (int)(3 * d), (int)R, &split),
                            gemm_alu_partial_bytes((int)d, (int)d, (int)R, nullptr));
@@ -418,6 +423,7 @@ int im_attention_fwd(const im_shape_t* shape, const void* x, const void* wq, con
   int rc = validate_shape(shape);
   if (rc) return rc;
   if ((rc = check_supported(shape))) return rc;
+  if (shape->cu_rows && valid_len) return fail(IM_ERR_INVALID, "packed rows carry the lengths in cu_rows: valid_len must be NULL");
   if (!x || !wq || !wk || !wv || !wo || !y) return fail(IM_ERR_INVALID, "x, wq, wk, wv, wo and y must not be NULL");
   const SavedLayout L = saved_layout(shape);
   const Path path = pick_path(shape);
@@ -441,6 +447,7 @@ int im_attention_bwd(const im_shape_t* shape, const void* x, const void* wq, con
   int rc = validate_shape(shape);
   if (rc) return rc;
   if ((rc = check_supported(shape))) return rc;
+  if (shape->cu_rows && valid_len) return fail(IM_ERR_INVALID, "packed rows carry the lengths in cu_rows: valid_len must be NULL");
   if (!x || !wq || !wk || !wv || !wo || !saved || !dy)
     return fail(IM_ERR_INVALID, "x, wq, wk, wv, wo, saved and dy must not be NULL");
   const size_t need = bwd_workspace_bytes(shape);
@@ -467,7 +474,7 @@ static size_t layer_ws(const im_shape_t* s, int32_t d_ff, size_t* attn_ws_bytes)
   const size_t es = s->dtype == IM_DTYPE_BF16 ? 2 : 4;
   long T = 0;
   for (int i = 0; i < s->n_seg; ++i) T += s->seg_len[i];
-  const size_t R = (size_t)s->batch * T, d = s->d_model;
+  const size_t R = (size_t)shape_rows(s), d = s->d_model;
   size_t aws = saved_layout(s).total;
   if (pick_path(s) == PATH_MFMA) aws += mfma_fwd_workspace_bytes(s->d_model);
   if (attn_ws_bytes) *attn_ws_bytes = aws;
@@ -488,6 +495,7 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
                    const uint8_t* key_pad, void* y, void* workspace, size_t workspace_bytes, void* hip_stream) {
   int rc = layer_check(shape, d_ff);
   if (rc) return rc;
+  if (shape->cu_rows && valid_len) return fail(IM_ERR_INVALID, "packed rows carry the lengths in cu_rows: valid_len must be NULL");
   if (!x || !ln1_g || !ln1_b || !wq || !wk || !wv || !wo || !ln2_g || !ln2_b || !w1 || !w2 || !y)
     return fail(IM_ERR_INVALID, "x, LayerNorm parameters, wq, wk, wv, wo, w1, w2 and y must not be NULL");
   if (!(ln_eps >= 0.f)) return fail(IM_ERR_INVALID, "ln_eps must be >= 0");
@@ -500,7 +508,7 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
   const size_t es = bf ? 2 : 4;
   long T = 0;
   for (int i = 0; i < shape->n_seg; ++i) T += shape->seg_len[i];
-  const long R = (long)shape->batch * T, d = shape->d_model;
+  const long R = shape_rows(shape), d = shape->d_model;
   Bump b{(char*)workspace, 0, 0};
   void* u = b.take(R * d * es);
   void* h = b.take(R * d * es);
@@ -551,7 +559,7 @@ static LayerTrain layer_train_layout(const im_shape_t* s, int32_t d_ff) {
   const size_t es = s->dtype == IM_DTYPE_BF16 ? 2 : 4;
   long T = 0;
   for (int i = 0; i < s->n_seg; ++i) T += s->seg_len[i];
-  const size_t R = (size_t)s->batch * T, d = s->d_model, f = (size_t)d_ff;
+  const size_t R = (size_t)shape_rows(s), d = s->d_model, f = (size_t)d_ff;
   size_t off = 0;
   L.att = off; off += align256(saved_layout(s).total);
   L.h = off; off += align256(R * d * es);
@@ -595,6 +603,7 @@ int gsit_layer_fwd_train(const im_shape_t* shape, int32_t d_ff, const void* x, c
                          size_t workspace_bytes, void* hip_stream) {
   int rc = layer_check(shape, d_ff);
   if (rc) return rc;
+  if (shape->cu_rows && valid_len) return fail(IM_ERR_INVALID, "packed rows carry the lengths in cu_rows: valid_len must be NULL");
   if (!x || !p || !y || !saved) return fail(IM_ERR_INVALID, "x, params, y and saved must not be NULL");
   if (!p->ln1_g || !p->ln1_b || !p->wq || !p->wk || !p->wv || !p->wo || !p->ln2_g || !p->ln2_b || !p->w1 || !p->w2)
     return fail(IM_ERR_INVALID, "LayerNorm parameters, wq, wk, wv, wo, w1 and w2 must not be NULL");
@@ -606,7 +615,7 @@ int gsit_layer_fwd_train(const im_shape_t* shape, int32_t d_ff, const void* x, c
   const int bf = shape->dtype == IM_DTYPE_BF16;
   long T = 0;
   for (int i = 0; i < shape->n_seg; ++i) T += shape->seg_len[i];
-  const long R = (long)shape->batch * T, d = shape->d_model;
+  const long R = shape_rows(shape), d = shape->d_model;
   char* sv = (char*)saved;
   char* ws = (char*)workspace;
   void* u = ws + L.u;
@@ -648,6 +657,7 @@ int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const g
                    const gsit_layer_grads_t* gr, void* workspace, size_t workspace_bytes, void* hip_stream) {
   int rc = layer_check(shape, d_ff);
   if (rc) return rc;
+  if (shape->cu_rows && valid_len) return fail(IM_ERR_INVALID, "packed rows carry the lengths in cu_rows: valid_len must be NULL");
   if (!x || !p || !saved || !dy || !dx || !gr) return fail(IM_ERR_INVALID, "x, params, saved, dy, dx and grads must not be NULL");
   if (!p->ln1_g || !p->ln1_b || !p->wq || !p->wk || !p->wv || !p->wo || !p->ln2_g || !p->ln2_b || !p->w1 || !p->w2)
     return fail(IM_ERR_INVALID, "LayerNorm parameters, wq, wk, wv, wo, w1 and w2 must not be NULL");
@@ -659,7 +669,7 @@ int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const g
   const int bf = shape->dtype == IM_DTYPE_BF16;
   long T = 0;
   for (int i = 0; i < shape->n_seg; ++i) T += shape->seg_len[i];
-  const long R = (long)shape->batch * T, d = shape->d_model;
+  const long R = shape_rows(shape), d = shape->d_model;
   const char* sv = (const char*)saved;
   char* ws = (char*)workspace;
   const void* h = sv + L.h;

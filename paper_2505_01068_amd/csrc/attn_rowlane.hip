@@ -32,9 +32,11 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_fwd_kernel(Geo g, const T* __
   const int lane = threadIdx.x, h = blockIdx.y, b = blockIdx.z;
   int qs, q0;
   decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, RL_ROWS, blockIdx.x, qs, q0);
+  const int qlen = seg_rows(g, b, qs);
+  if (q0 >= qlen) return;  // packed rows: this batch element's segment ends before the tile
   const int row = q0 + lane;
-  const bool active = row < g.seg_len[qs];
-  const long t = (long)b * g.T + g.seg_off[qs] + (active ? row : 0);
+  const bool active = row < qlen;
+  const long t = seg_row0(g, b, qs) + (active ? row : 0);
   const int dh = g.dh, hc = h * dh;
 
   float q[DH], acc[DH];
@@ -48,9 +50,9 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_fwd_kernel(Geo g, const T* __
   const unsigned live = g.q_live[qs];
   for (int j = 0; j < g.n_seg; ++j) {
     if (!((live >> j) & 1u)) continue;
-    int klen = g.seg_len[j];
+    int klen = seg_rows(g, b, j);
     if (valid_len) klen = min(klen, max(0, valid_len[b * g.n_seg + j]));
-    const long kbase = (long)b * g.T + g.seg_off[j];
+    const long kbase = seg_row0(g, b, j);
     for (int c0 = 0; c0 < klen; c0 += RL_CHUNK) {
       const int n = min(RL_CHUNK, klen - c0);
       const int n4 = (n + 3) & ~3;
@@ -64,7 +66,7 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_fwd_kernel(Geo g, const T* __
       }
       for (int c = lane; c < n4; c += RL_ROWS) {
         bool ok = c < n;
-        if (ok && key_pad) ok = key_pad[(long)b * g.T + g.seg_off[j] + c0 + c] == 0;
+        if (ok && key_pad) ok = key_pad[kbase + c0 + c] == 0;
         sBias[c] = ok ? 0.f : IM_NEG_INF;
       }
       __syncthreads();
@@ -99,7 +101,7 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_fwd_kernel(Geo g, const T* __
 #pragma unroll
     for (int e = 0; e < DH; ++e)
       if (e < dh) stf(O + t * ldo + hc + e, acc[e] * inv);
-    if (lse2) lse2[((long)b * g.H + h) * g.T + g.seg_off[qs] + row] = (l > 0.f) ? m + log2f(l) : IM_NEG_INF;
+    if (lse2) lse2[seg_stat0(g, b, h, qs) + row] = (l > 0.f) ? m + log2f(l) : IM_NEG_INF;
   }
 }
 
@@ -119,11 +121,13 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dq_kernel(Geo g, const T* __r
   const int lane = threadIdx.x, h = blockIdx.y, b = blockIdx.z;
   int qs, q0;
   decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, RL_ROWS, blockIdx.x, qs, q0);
+  const int qlen = seg_rows(g, b, qs);
+  if (q0 >= qlen) return;  // packed rows: this batch element's segment ends before the tile
   const int row = q0 + lane;
-  const bool active = row < g.seg_len[qs];
-  const long t = (long)b * g.T + g.seg_off[qs] + (active ? row : 0);
+  const bool active = row < qlen;
+  const long t = seg_row0(g, b, qs) + (active ? row : 0);
   const int dh = g.dh, hc = h * dh;
-  const long li = ((long)b * g.H + h) * g.T + g.seg_off[qs] + (active ? row : 0);
+  const long li = seg_stat0(g, b, h, qs) + (active ? row : 0);
 
   float q[DH], go[DH], acc[DH];
   float dl = 0.f;
@@ -142,9 +146,9 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dq_kernel(Geo g, const T* __r
   const unsigned live = g.q_live[qs];
   for (int j = 0; j < g.n_seg; ++j) {
     if (!((live >> j) & 1u)) continue;
-    int klen = g.seg_len[j];
+    int klen = seg_rows(g, b, j);
     if (valid_len) klen = min(klen, max(0, valid_len[b * g.n_seg + j]));
-    const long kbase = (long)b * g.T + g.seg_off[j];
+    const long kbase = seg_row0(g, b, j);
     for (int c0 = 0; c0 < klen; c0 += RL_CHUNK) {
       const int n = min(RL_CHUNK, klen - c0);
       __syncthreads();
@@ -156,7 +160,7 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dq_kernel(Geo g, const T* __r
       }
       for (int c = lane; c < n; c += RL_ROWS) {
         bool ok = true;
-        if (key_pad) ok = key_pad[(long)b * g.T + g.seg_off[j] + c0 + c] == 0;
+        if (key_pad) ok = key_pad[kbase + c0 + c] == 0;
         sBias[c] = ok ? 0.f : IM_NEG_INF;
       }
       __syncthreads();
@@ -200,11 +204,13 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dkv_kernel(Geo g, const T* __
   const int lane = threadIdx.x, h = blockIdx.y, b = blockIdx.z;
   int ks, k0;
   decode_tile(g.k_order, g.k_tile_prefix, g.k_nord, RL_ROWS, blockIdx.x, ks, k0);
+  const int klen_seg = seg_rows(g, b, ks);
+  if (k0 >= klen_seg) return;  // packed rows: this batch element's segment ends before the tile
   const int row = k0 + lane;
-  const bool in_seg = row < g.seg_len[ks];
+  const bool in_seg = row < klen_seg;
   bool valid = in_seg;
   if (valid && valid_len) valid = row < valid_len[b * g.n_seg + ks];
-  const long t = (long)b * g.T + g.seg_off[ks] + (in_seg ? row : 0);
+  const long t = seg_row0(g, b, ks) + (in_seg ? row : 0);
   if (valid && key_pad) valid = key_pad[t] == 0;
   const int dh = g.dh, hc = h * dh;
 
@@ -219,9 +225,9 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dkv_kernel(Geo g, const T* __
   const unsigned live = g.k_live[ks];
   for (int i = 0; i < g.n_seg; ++i) {
     if (!((live >> i) & 1u)) continue;
-    const int qlen = g.seg_len[i];
-    const long qbase = (long)b * g.T + g.seg_off[i];
-    const long lbase = ((long)b * g.H + h) * g.T + g.seg_off[i];
+    const int qlen = seg_rows(g, b, i);
+    const long qbase = seg_row0(g, b, i);
+    const long lbase = seg_stat0(g, b, h, i);
     for (int r0 = 0; r0 < qlen; r0 += RL_CHUNK) {
       const int n = min(RL_CHUNK, qlen - r0);
       __syncthreads();
@@ -265,16 +271,36 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dkv_kernel(Geo g, const T* __
   }
 }
 
-// Zero the gradient rows of segments that no live block reads as keys / as queries.
+// Zero columns col0 .. col0+ncols-1 of the rows of segment s (all batch elements): outputs of query
+// segments with no live key segment, gradients of segments that no live block reads.
 template <typename T>
-__global__ void zero_rows_kernel(T* p, long ld, int B, int T_m, int row0, int nrows, int d) {
-  const long n = (long)B * nrows * d;
+__global__ void zero_seg_rows_kernel(Geo g, int s, T* p, long ld, int col0, int ncols) {
+  const int nrows = g.seg_len[s];
+  const long n = (long)g.B * nrows * ncols;
   for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
-    const int e = i % d;
-    const long r = i / d;
+    const int e = i % ncols;
+    const long r = i / ncols;
     const int b = r / nrows, rr = r % nrows;
-    stf(p + ((long)b * T_m + row0 + rr) * ld + e, 0.f);
+    if (rr < seg_rows(g, b, s)) stf(p + (seg_row0(g, b, s) + rr) * ld + col0 + e, 0.f);
   }
+}
+// per-row statistic (lse) of segment s, all batch elements and heads := value
+__global__ void fill_seg_stat_kernel(Geo g, int s, float* stat, float value) {
+  const int nrows = g.seg_len[s];
+  const long n = (long)g.B * g.H * nrows;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
+    const int rr = i % nrows;
+    const long bh = i / nrows;
+    const int b = bh / g.H, h = bh % g.H;
+    if (rr < seg_rows(g, b, s)) stat[seg_stat0(g, b, h, s) + rr] = value;
+  }
+}
+void launch_zero_seg_rows(const Geo& g, int s, int bf16, void* p, long ld, int col0, int ncols, hipStream_t st) {
+  if (bf16) hipLaunchKernelGGL((zero_seg_rows_kernel<bf16_t>), dim3(64), dim3(256), 0, st, g, s, (bf16_t*)p, ld, col0, ncols);
+  else hipLaunchKernelGGL((zero_seg_rows_kernel<float>), dim3(64), dim3(256), 0, st, g, s, (float*)p, ld, col0, ncols);
+}
+void launch_fill_seg_stat(const Geo& g, int s, float* stat, float value, hipStream_t st) {
+  hipLaunchKernelGGL(fill_seg_stat_kernel, dim3(16), dim3(256), 0, st, g, s, stat, value);
 }
 
 bool rowlane_supports(int dh) { return dh >= 1 && dh <= 16; }
@@ -309,15 +335,8 @@ static void zero_dead_rows(const Geo& g, bool query_side, T* p, long ld, hipStre
   for (int s = 0; s < g.n_seg; ++s) {
     const unsigned live = query_side ? g.q_live[s] : g.k_live[s];
     if (live) continue;
-    hipLaunchKernelGGL((zero_rows_kernel<T>), dim3(64), dim3(256), 0, st, p, ld, g.B, g.T, g.seg_off[s], g.seg_len[s],
-                       g.d);
+    launch_zero_seg_rows(g, s, sizeof(T) == 2, p, ld, 0, g.d, st);
   }
-}
-
-__global__ void fill_lse_kernel(float* lse2, int BH, int T_m, int row0, int nrows) {
-  const long n = (long)BH * nrows;
-  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x)
-    lse2[(i / nrows) * T_m + row0 + (i % nrows)] = IM_NEG_INF;
 }
 
 int launch_rowlane_fwd(const Geo& g, int bf16, const void* q, const void* k, const void* v, long ld,
@@ -326,7 +345,7 @@ int launch_rowlane_fwd(const Geo& g, int bf16, const void* q, const void* k, con
   if (!rowlane_supports(g.dh)) return IM_ERR_UNSUPPORTED;
   for (int s = 0; s < g.n_seg; ++s)
     if (!g.q_live[s] && lse2)
-      hipLaunchKernelGGL(fill_lse_kernel, dim3(16), dim3(256), 0, st, lse2, g.B * g.H, g.T, g.seg_off[s], g.seg_len[s]);
+      launch_fill_seg_stat(g, s, lse2, IM_NEG_INF, st);
   if (bf16) {
     zero_dead_rows<bf16_t>(g, true, (bf16_t*)o, ldo, st);
     return fwd_dispatch<bf16_t>(g, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, ld, valid_len, key_pad,

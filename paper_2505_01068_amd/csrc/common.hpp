@@ -24,7 +24,43 @@ struct Geo {
   int q_order[IM_MAX_SEG], q_tile_prefix[IM_MAX_SEG + 1], q_nord;
   int k_order[IM_MAX_SEG], k_tile_prefix[IM_MAX_SEG + 1], k_nord;
   float scale, scale_log2e;
+  // Packed rows (im_shape_t::cu_rows): row offsets [B * n_seg + 1] on the device, and the row count.
+  // cu == nullptr: padded rows, batch element b owns rows b*T .. b*T + T - 1.
+  const int32_t* cu;
+  long R;
 };
+
+// First row, and number of rows, of segment s of batch element b in the [rows, .] tensors; first
+// element of the per-row fp32 tensors (lse, delta) of head h for that segment: [B, H, T] padded,
+// [H, R] packed.
+__device__ __forceinline__ long seg_row0(const Geo& g, int b, int s) {
+  return g.cu ? (long)g.cu[b * g.n_seg + s] : (long)b * g.T + g.seg_off[s];
+}
+__device__ __forceinline__ int seg_rows(const Geo& g, int b, int s) {
+  return g.cu ? g.cu[b * g.n_seg + s + 1] - g.cu[b * g.n_seg + s] : g.seg_len[s];
+}
+__device__ __forceinline__ long seg_stat0(const Geo& g, int b, int h, int s) {
+  return g.cu ? (long)h * g.R + g.cu[b * g.n_seg + s] : ((long)b * g.H + h) * g.T + g.seg_off[s];
+}
+// The same for callers whose b and s are wave-uniform (the matrix-core kernels): the row offsets
+// read from memory are moved to scalar registers, so pointers derived from them stay scalar.
+__device__ __forceinline__ int cu_u(const Geo& g, int i) { return __builtin_amdgcn_readfirstlane(g.cu[i]); }
+__device__ __forceinline__ long useg_row0(const Geo& g, int b, int s) {
+  return g.cu ? (long)cu_u(g, b * g.n_seg + s) : (long)b * g.T + g.seg_off[s];
+}
+__device__ __forceinline__ int useg_rows(const Geo& g, int b, int s) {
+  return g.cu ? cu_u(g, b * g.n_seg + s + 1) - cu_u(g, b * g.n_seg + s) : g.seg_len[s];
+}
+__device__ __forceinline__ long useg_stat0(const Geo& g, int b, int h, int s) {
+  return g.cu ? (long)h * g.R + cu_u(g, b * g.n_seg + s) : ((long)b * g.H + h) * g.T + g.seg_off[s];
+}
+// rows of the [rows, .] tensors of a shape (host)
+inline long shape_rows(const im_shape_t* s) {
+  if (s->cu_rows) return (long)s->total_rows;
+  long T = 0;
+  for (int i = 0; i < s->n_seg; ++i) T += s->seg_len[i];
+  return (long)s->batch * T;
+}
 
 // tile index -> (segment, first row).  Same code on host (schedule listing)
 // and device (kernels), so the listing is what the kernels execute.
@@ -98,6 +134,11 @@ size_t gemm_alu_partial_bytes(int M, int N, int K, int* split_k);
 // column sums of a [R, n] matrix (bias gradients), deterministic two-stage
 int launch_colsum(const void* a, long lda, int R, int n, int a_bf16, float* out, float* partial, hipStream_t st);
 size_t colsum_partial_bytes(int R, int n);
+
+// Zero columns col0 .. col0+ncols-1 of the rows of segment s of a [rows, ld] matrix; set a per-row
+// fp32 statistic ([B,H,T] padded / [H,R] packed) of the rows of segment s.  All batch elements.
+void launch_zero_seg_rows(const Geo& g, int s, int bf16, void* p, long ld, int col0, int ncols, hipStream_t st);
+void launch_fill_seg_stat(const Geo& g, int s, float* stat, float value, hipStream_t st);
 
 // row-per-lane attention for small head dims (plain ALU)
 int launch_rowlane_fwd(const Geo& g, int bf16, const void* q, const void* k, const void* v, long ld,

@@ -46,6 +46,7 @@ struct ModelWs {
 
 static int model_ws(const im_shape_t* s, const gsit_model_t* m, im_shape_t* intra_shape, ModelWs* w) {
   if (!s || !m) { set_error("shape and model must not be NULL"); return IM_ERR_INVALID; }
+  if (s->cu_rows) { set_error("the whole-model call needs padded rows (shape->cu_rows must be NULL)"); return IM_ERR_UNSUPPORTED; }
   if (m->n_layers_inter < 1 || m->n_layers_intra < 1 || m->n_out < 1) {
     set_error("n_layers_inter, n_layers_intra and n_out must be >= 1");
     return IM_ERR_INVALID;

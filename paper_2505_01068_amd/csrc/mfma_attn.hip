@@ -146,7 +146,8 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
   constexpr int WG_ROWS = 128 * QB;
   int qs, q0;
   decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, WG_ROWS, tile, qs, q0);
-  const int qlen = g.seg_len[qs];
+  const int qlen = useg_rows(g, b, qs);
+  if (q0 >= qlen) return;  // packed rows: this batch element's segment ends before the tile
   const int d = g.d;
   const float c = fmaxf(g.scale_log2e, 1e-30f);  // > 0 so that -inf * c stays -inf when scale == 0
 
@@ -164,7 +165,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
   for (int qb = 0; qb < QB; ++qb) {
     qrow[qb] = q0 + (wave * QB + qb) * 32 + lo;
     const int rc = min(qrow[qb], qlen - 1);
-    const bf16_t* p = QKV + ((long)b * g.T + g.seg_off[qs] + rc) * ld + cg * 64 + hi * 8;
+    const bf16_t* p = QKV + (useg_row0(g, b, qs) + rc) * ld + cg * 64 + hi * 8;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       u32x4 v = *(const u32x4*)(p + (s0 + s) * 16);
@@ -196,7 +197,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
 
   // key tiles of the live key segments; a segment contributes its first min(length, valid length) keys
   auto klen_of = [&](int j) {
-    int n = g.seg_len[j];
+    int n = useg_rows(g, b, j);
     if (valid_len) n = min(n, max(0, valid_len[b * g.n_seg + j]));
     return n;
   };
@@ -210,9 +211,9 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
   RingFeed feed = {nullptr, nullptr, 0};
   // K and V rows of segment ic.seg; rows past the valid length but inside the segment are fetched and masked
   auto seg_begin = [&]() {
-    feed.a = (const char*)(QKV + ((long)b * g.T + g.seg_off[ic.seg]) * ld + d);
+    feed.a = (const char*)(QKV + useg_row0(g, b, ic.seg) * ld + d);
     feed.b = feed.a + (size_t)d * 2;
-    feed.rows = g.seg_len[ic.seg];
+    feed.rows = useg_rows(g, b, ic.seg);
   };
   if (ic.len > 0) seg_begin();
   auto issue = [&]() {
@@ -233,7 +234,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
     const bf16_t* sV = sK + KT * SW_LD;
     cslot = (cslot + 1 == RING_NST) ? 0 : cslot + 1;
     const int k0 = cc.r0, klen = cc.len;
-    const uint8_t* kp_row = key_pad ? key_pad + (long)b * g.T + g.seg_off[cc.seg] : nullptr;
+    const uint8_t* kp_row = key_pad ? key_pad + useg_row0(g, b, cc.seg) : nullptr;
     cursor_step(cc, klen_of);
     {
       // ---- S^T = K Q^T ----
@@ -323,8 +324,8 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
     const float inv = lt > 0.f ? 1.f / lt : 0.f;
     const int row = qrow[qb];
     if (row >= qlen) continue;
-    const long t = (long)b * g.T + g.seg_off[qs] + row;
-    if (hi == 0 && lse2) lse2[((long)b * g.H + h) * g.T + g.seg_off[qs] + row] = lt > 0.f ? fmaf(m[qb], c, log2f(lt)) : __builtin_inff();
+    const long t = useg_row0(g, b, qs) + row;
+    if (hi == 0 && lse2) lse2[useg_stat0(g, b, h, qs) + row] = lt > 0.f ? fmaf(m[qb], c, log2f(lt)) : __builtin_inff();
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -358,7 +359,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
   constexpr int WG_ROWS = 128 * QB;
   int qs, q0;
   decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, WG_ROWS, tile, qs, q0);
-  const int qlen = g.seg_len[qs];
+  const int qlen = useg_rows(g, b, qs);
+  if (q0 >= qlen) return;  // packed rows: this batch element's segment ends before the tile
   const int d = g.d;
   const float c = fmaxf(g.scale_log2e, 1e-30f);  // > 0 so that -inf * c stays -inf when scale == 0
 
@@ -376,7 +378,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
   for (int qb = 0; qb < QB; ++qb) {
     qrow[qb] = q0 + (wave * QB + qb) * 32 + lo;
     const int rc = min(qrow[qb], qlen - 1);
-    const long t = (long)b * g.T + g.seg_off[qs] + rc;
+    const long t = useg_row0(g, b, qs) + rc;
     const bf16_t* p = QKV + t * ld + cg * 64 + hi * 8;
     const bf16_t* pg = dO + t * ldo + cg * 64 + hi * 8;
     const bf16_t* po = O + t * ldo + cg * 64 + hi * 8;
@@ -397,7 +399,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
     }
     acc += __shfl_xor(acc, 32, 64);
     dl[qb] = acc;
-    const long li = ((long)b * g.H + h) * g.T + g.seg_off[qs] + rc;
+    const long li = useg_stat0(g, b, h, qs) + rc;
     const float lv = lse2[li];
     ls[qb] = lv;  // +inf for a row without valid keys: every probability is exactly zero
     if (hi == 0 && qrow[qb] < qlen) delta[li] = DH == 64 ? -acc : acc;  // see the dK/dV kernel
@@ -422,7 +424,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
   }
 
   auto klen_of = [&](int j) {
-    int n = g.seg_len[j];
+    int n = useg_rows(g, b, j);
     if (valid_len) n = min(n, max(0, valid_len[b * g.n_seg + j]));
     return n;
   };
@@ -436,9 +438,9 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
   RingFeed feed = {nullptr, nullptr, 0};
   // K and V rows of segment ic.seg; rows past the valid length but inside the segment are fetched and masked
   auto seg_begin = [&]() {
-    feed.a = (const char*)(QKV + ((long)b * g.T + g.seg_off[ic.seg]) * ld + d);
+    feed.a = (const char*)(QKV + useg_row0(g, b, ic.seg) * ld + d);
     feed.b = feed.a + (size_t)d * 2;
-    feed.rows = g.seg_len[ic.seg];
+    feed.rows = useg_rows(g, b, ic.seg);
   };
   if (ic.len > 0) seg_begin();
   auto issue = [&]() {
@@ -459,7 +461,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
     const bf16_t* sV = sK + KT * SW_LD;
     cslot = (cslot + 1 == RING_NST) ? 0 : cslot + 1;
     const int k0 = cc.r0, klen = cc.len;
-    const uint8_t* kp_row = key_pad ? key_pad + (long)b * g.T + g.seg_off[cc.seg] : nullptr;
+    const uint8_t* kp_row = key_pad ? key_pad + useg_row0(g, b, cc.seg) : nullptr;
     cursor_step(cc, klen_of);
     {
       const bool need_mask = (k0 + KT > klen) || (kp_row != nullptr);
@@ -518,7 +520,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
   for (int qb = 0; qb < QB; ++qb) {
     const int row = qrow[qb];
     if (row >= qlen) continue;
-    const long t = (long)b * g.T + g.seg_off[qs] + row;
+    const long t = useg_row0(g, b, qs) + row;
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -560,7 +562,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
   constexpr int WG_ROWS = 128 * KB;
   int ks, k0;
   decode_tile(g.k_order, g.k_tile_prefix, g.k_nord, WG_ROWS, tile, ks, k0);
-  const int klen_seg = g.seg_len[ks];
+  const int klen_seg = useg_rows(g, b, ks);
+  if (k0 >= klen_seg) return;  // packed rows: this batch element's segment ends before the tile
   const int d = g.d;
   const float c = fmaxf(g.scale_log2e, 1e-30f);  // > 0 so that -inf * c stays -inf when scale == 0
 
@@ -571,7 +574,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
   const int s0 = DH == 64 ? 0 : wo >> 4, db0 = DH == 64 ? 0 : wo >> 5;
   const bool other_half = DH == 8 && hi != ((wo >> 3) & 1);  // this lane half holds another head's columns
 
-  auto qlen_of = [&](int i) { return g.seg_len[i]; };
+  auto qlen_of = [&](int i) { return useg_rows(g, b, i); };
   const RingLane rl = ring_lane(wave, lane, cg);
   const unsigned ldb = (unsigned)ld * 2u, ldob = (unsigned)ldo * 2u;  // row pitches in bytes
   TileCursor ic = {g.k_live[ks], 0, 0, 0}, cc = ic;
@@ -583,8 +586,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
   const float* feed_l = nullptr;  // lse and delta of the next tile's first row
   const float* feed_d = nullptr;
   auto seg_begin = [&]() {  // Q and dO rows, lse and delta of segment ic.seg
-    const long row0 = (long)b * g.T + g.seg_off[ic.seg];
-    const long lb = ((long)b * g.H + h) * g.T + g.seg_off[ic.seg];
+    const long row0 = useg_row0(g, b, ic.seg);
+    const long lb = useg_stat0(g, b, h, ic.seg);
     feed.a = (const char*)(QKV + row0 * ld);
     feed.b = (const char*)(dO + row0 * ldo);
     feed.rows = ic.len;
@@ -622,7 +625,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
   for (int kb = 0; kb < KB; ++kb) {
     krow[kb] = k0 + (wave * KB + kb) * 32 + lo;
     const int rc = min(krow[kb], klen_seg - 1);
-    const long t = (long)b * g.T + g.seg_off[ks] + rc;
+    const long t = useg_row0(g, b, ks) + rc;
     const bf16_t* p = QKV + t * ld + d + cg * 64 + hi * 8;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
@@ -735,7 +738,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
   for (int kb = 0; kb < KB; ++kb) {
     const int row = krow[kb];
     if (row >= klen_seg) continue;
-    const long t = (long)b * g.T + g.seg_off[ks] + row;
+    const long t = useg_row0(g, b, ks) + row;
     const float zk = kvalid[kb] ? g.scale : 0.f, zv = kvalid[kb] ? 1.f : 0.f;
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
@@ -753,22 +756,6 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
   }
 }
 
-// zero a column range of some rows of a row-major activation matrix
-__global__ void zero_rows16_kernel(bf16_t* p, long ld, int B, int T_m, int row0, int nrows, int col0, int ncols) {
-  const long n = (long)B * nrows * ncols;
-  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
-    const int e = i % ncols;
-    const long r = i / ncols;
-    const int b = r / nrows, rr = r % nrows;
-    p[((long)b * T_m + row0 + rr) * ld + col0 + e] = 0;
-  }
-}
-__global__ void fill_lse_seg_kernel(float* lse2, int BH, int T_m, int row0, int nrows) {
-  const long n = (long)BH * nrows;
-  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x)
-    lse2[(i / nrows) * T_m + row0 + (i % nrows)] = __builtin_inff();
-}
-
 // ---- host launchers ----
 constexpr int FWD_QB = 2, DQ_QB = 1, DKV_KB = 1;
 int mfma_fwd_tile_rows() { return 128 * FWD_QB; }
@@ -780,8 +767,8 @@ void launch_mfma_fwd(const Geo& g, const bf16_t* qkv, long ld, const int32_t* va
   // query segments with no live block: output 0, lse -inf
   for (int s = 0; s < g.n_seg; ++s) {
     if (g.q_live[s]) continue;
-    hipLaunchKernelGGL(zero_rows16_kernel, dim3(64), dim3(256), 0, st, o, ldo, g.B, g.T, g.seg_off[s], g.seg_len[s], 0, g.d);
-    if (lse2) hipLaunchKernelGGL(fill_lse_seg_kernel, dim3(16), dim3(256), 0, st, lse2, g.B * g.H, g.T, g.seg_off[s], g.seg_len[s]);
+    launch_zero_seg_rows(g, s, 1, o, ldo, 0, g.d, st);
+    if (lse2) launch_fill_seg_stat(g, s, lse2, __builtin_inff(), st);
   }
   const int nt = g.q_tile_prefix[g.q_nord];
   if (nt == 0) return;
@@ -797,9 +784,9 @@ void launch_mfma_bwd(const Geo& g, const bf16_t* qkv, long ld, const bf16_t* o, 
                      long ldg, hipStream_t st) {
   for (int s = 0; s < g.n_seg; ++s) {
     if (!g.q_live[s])
-      hipLaunchKernelGGL(zero_rows16_kernel, dim3(64), dim3(256), 0, st, dqkv, ldg, g.B, g.T, g.seg_off[s], g.seg_len[s], 0, g.d);
+      launch_zero_seg_rows(g, s, 1, dqkv, ldg, 0, g.d, st);
     if (!g.k_live[s])
-      hipLaunchKernelGGL(zero_rows16_kernel, dim3(64), dim3(256), 0, st, dqkv, ldg, g.B, g.T, g.seg_off[s], g.seg_len[s], g.d, 2 * g.d);
+      launch_zero_seg_rows(g, s, 1, dqkv, ldg, g.d, 2 * g.d, st);
   }
   const int nq = g.q_tile_prefix[g.q_nord], nk = g.k_tile_prefix[g.k_nord];
   if (nq == 0) return;

@@ -21,7 +21,7 @@ static Dims dims(const im_shape_t* s) {
   Dims x;
   x.B = s->batch; x.d = s->d_model; x.T = 0;
   for (int i = 0; i < s->n_seg; ++i) x.T += s->seg_len[i];
-  x.R = x.B * x.T;
+  x.R = (size_t)shape_rows(s);
   return x;
 }
 
@@ -34,7 +34,7 @@ static BwdWs bwd_ws(const im_shape_t* s) {
   BwdWs w;
   size_t off = 0;
   w.d_o = off; off += al(x.R * x.d * 2);
-  w.delta = off; off += al(x.B * s->n_heads * x.T * 4);
+  w.delta = off; off += al((size_t)s->n_heads * x.R * 4);
   w.dqkv = off; off += al(x.R * 3 * x.d * 2);
   w.split_w = mfma_gemm_split((int)x.d, (int)(3 * x.d), (int)x.R);
   w.split_o = mfma_gemm_split((int)x.d, (int)x.d, (int)x.R);

@@ -146,6 +146,51 @@ def attention_inputs(batch, seg_len, d_model, n_heads, dtype="fp32", padding="no
     return g
 
 
+# Sequence-length statistics of the CMU-MOSI training split (dataset table of App. "Datasets": maximum,
+# average length, length variance), in concatenation order (text, vision, audio).  The table lists
+# 50/375/500, 14/42/38 and 66/927/805; its order is matched to the benchmark configuration's
+# L_t/L_v/L_a = 50/500/375 through the maxima.
+MOSI_LENGTH_STATS = dict(max=(50, 500, 375), mean=(14.0, 38.0, 42.0), var=(66.0, 805.0, 927.0))
+
+
+def dataset_lengths(batch, seg_max, mean, var, seed=BASE_SEED, stream=13):
+    """Per-sample, per-modality sequence lengths int32 [batch, n_seg]: a log-normal with the given mean and
+    variance (the table gives no more than these two moments), rounded, clipped to 1..seg_max."""
+    mean = np.asarray(mean, dtype=np.float64)
+    var = np.asarray(var, dtype=np.float64)
+    s2 = np.log1p(var / (mean * mean))
+    mu = np.log(mean) - 0.5 * s2
+    z = normal(seed, stream, (batch, len(seg_max))).astype(np.float64)
+    n = np.rint(np.exp(mu[None, :] + np.sqrt(s2)[None, :] * z))
+    return np.clip(n, 1, np.asarray(seg_max)[None, :]).astype(np.int32)
+
+
+def row_offsets(lengths):
+    """Packed-row offsets int32 [batch * n_seg + 1] of per-sample segment lengths [batch, n_seg]
+    (sample-major, segments in concatenation order)."""
+    return np.concatenate([[0], np.cumsum(np.asarray(lengths, dtype=np.int64).reshape(-1))]).astype(np.int32)
+
+
+def pack_rows(a, lengths, seg_len):
+    """[batch, T_m, ...] -> [total_rows, ...]: the first lengths[b, s] rows of every segment, in row_offsets order."""
+    off = np.concatenate([[0], np.cumsum(seg_len)]).astype(int)
+    parts = [a[b, off[s]:off[s] + int(lengths[b, s])] for b in range(a.shape[0]) for s in range(len(seg_len))]
+    return np.ascontiguousarray(np.concatenate(parts, axis=0))
+
+
+def unpack_rows(p, lengths, seg_len, fill=0.0):
+    """Inverse of pack_rows; rows beyond the lengths are `fill`."""
+    lengths = np.asarray(lengths)
+    off = np.concatenate([[0], np.cumsum(seg_len)]).astype(int)
+    out = np.full((lengths.shape[0], int(off[-1])) + p.shape[1:], fill, dtype=p.dtype)
+    cu = row_offsets(lengths)
+    for b in range(lengths.shape[0]):
+        for s in range(len(seg_len)):
+            i = b * len(seg_len) + s
+            out[b, off[s]:off[s] + int(lengths[b, s])] = p[cu[i]:cu[i + 1]]
+    return out
+
+
 def layer_params(d_model, d_ff, seed, layer, dtype="bf16", bias=True):
     """Weights of one encoder layer: Xavier matrices, LN gain 1 + 0.1 N, LN bias 0.1 N."""
     d = d_model

@@ -110,3 +110,56 @@ class Problem:
                     scale = max(float(np.max(np.sum(np.abs(ref["dk"]), axis=(0, 1)))), floor)
                 errs[n] = assert_close(v, ref[n], tol, what + " " + n, scale)
         return errs
+
+
+class PackedProblem(Problem):
+    """The same problem with packed rows: sample b keeps the first lengths[b, s] rows of segment s and the
+    tensors hold no padding rows.  The oracle sees the padded problem with valid_len = lengths and dy = 0
+    beyond them, which has the same values on the kept rows and the same weight gradients."""
+
+    def __init__(self, g, live_mask, lengths):
+        from paper_2505_01068_amd import synth
+        self.g, self.lm, self.dtype = g, int(live_mask), g["dtype"]
+        self.lengths = np.asarray(lengths, dtype=np.int32)
+        x = g["x"]
+        seg = g["seg_len"]
+        cu = synth.row_offsets(self.lengths)
+        self.cu = torch.from_numpy(cu).cuda()
+        self.shape = B.make_shape(x.shape[0], seg, x.shape[2], g["n_heads"], live_mask, g["scale"], self.dtype,
+                                  cu_rows=self.cu, total_rows=int(cu[-1]))
+        self.t = {n: to_dev(g.get(n), self.dtype) for n in W_NAMES + B_NAMES}
+        self.t["x"] = to_dev(synth.pack_rows(x, self.lengths, seg), self.dtype)
+        self.t["dy"] = to_dev(synth.pack_rows(g["dy"], self.lengths, seg), self.dtype)
+        self.t["valid_len"] = None
+        self.t["key_pad"] = None
+        sb, wb = B.im_attention_sizes(self.shape)
+        self.saved = torch.empty(sb, dtype=torch.uint8, device="cuda")
+        self.ws = torch.empty(max(wb, 1), dtype=torch.uint8, device="cuda")
+
+    def check(self, backward=True, tol=None, what=""):
+        from paper_2505_01068_amd import synth
+        tol = TOL[self.dtype] if tol is None else tol
+        g, seg = self.g, self.g["seg_len"]
+        pack = lambda a: synth.pack_rows(a, self.lengths, seg)
+        y = self.fwd(save=True)
+        torch.cuda.synchronize()
+        y_ref, cache = oracle.forward(g["x"], g["wq"], g["wk"], g["wv"], g["wo"], seg, self.lm, g["n_heads"], g["scale"],
+                                      bq=g.get("bq"), bk=g.get("bk"), bv=g.get("bv"), bo=g.get("bo"),
+                                      valid_len=self.lengths, return_cache=True)
+        errs = {"y": assert_close(y, pack(y_ref), tol, what + " y")}
+        if backward:
+            grads = self.bwd()
+            torch.cuda.synchronize()
+            dy = synth.unpack_rows(pack(g["dy"]), self.lengths, seg)   # zero beyond the lengths
+            ref = oracle.backward(cache, dy)
+            ulp = 2.0 ** -8 if self.dtype == "bf16" else 2.0 ** -23
+            floor = ulp * max(float(np.max(np.abs(ref[n]))) for n in grads if grads[n] is not None)
+            for n, v in grads.items():
+                if v is None:
+                    continue
+                r = pack(ref[n]) if n == "dx" else ref[n]
+                scale = max(float(np.max(np.abs(r))), floor)
+                if n == "dbk":
+                    scale = max(float(np.max(np.sum(np.abs(ref["dk"]), axis=(0, 1)))), floor)
+                errs[n] = assert_close(v, r, tol, what + " " + n, scale)
+        return errs
