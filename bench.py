@@ -270,7 +270,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="c5", choices=["c2", "c3", "c4", "c4train", "c5", "gsit"])
+    ap.add_argument("--config", default="c5", choices=["c2", "c3", "c3p", "c3v", "c4", "c4train", "c5", "gsit"],
+                    help="c3p: the C3 shape with the dataset's sequence-length statistics, packed rows; "
+                         "c3v: the same lengths with padded rows and valid_len")
     ap.add_argument("--mask", default="ifm_forward", choices=["ifm_forward", "ifm_backward", "iem"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -295,8 +297,18 @@ def main():
     masks = {"ifm_forward": B.IM_IFM_FORWARD, "ifm_backward": B.IM_IFM_BACKWARD, "iem": B.IM_IEM}
     lm = masks[args.mask]
 
-    w = synth.workload(args.config)
-    g = synth.attention_inputs(**w)
+    lengths = None
+    if args.config in ("c3p", "c3v"):
+        # C3 shape; per-sample lengths with the mean and variance of the dataset table (App. "Datasets")
+        w = synth.workload("c3", padding="none")
+        g = synth.attention_inputs(**w)
+        st = synth.MOSI_LENGTH_STATS
+        lengths = synth.dataset_lengths(w["batch"], st["max"], st["mean"], st["var"], seed=w["seed"])
+        g["valid_len"] = lengths
+        w["padding"] = "packed rows" if args.config == "c3p" else "valid_len"
+    else:
+        w = synth.workload(args.config)
+        g = synth.attention_inputs(**w)
     dtype = g["dtype"]
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     Bsz, T, d = g["x"].shape
@@ -308,10 +320,19 @@ def main():
         t = torch.from_numpy(np.ascontiguousarray(a))
         return (t.to(tdt) if t.dtype == torch.float32 else t).cuda()
 
-    shape = B.make_shape(Bsz, g["seg_len"], d, H, lm, g["scale"], dtype)
-    x, dy = dev(g["x"]), dev(g["dy"])
+    rows = Bsz * T
+    if args.config == "c3p":
+        cu = synth.row_offsets(lengths)
+        cu_dev = torch.from_numpy(cu).cuda()
+        rows = int(cu[-1])
+        shape = B.make_shape(Bsz, g["seg_len"], d, H, lm, g["scale"], dtype, cu_rows=cu_dev, total_rows=rows)
+        x, dy = dev(synth.pack_rows(g["x"], lengths, g["seg_len"])), dev(synth.pack_rows(g["dy"], lengths, g["seg_len"]))
+        vl, kp = None, None
+    else:
+        shape = B.make_shape(Bsz, g["seg_len"], d, H, lm, g["scale"], dtype)
+        x, dy = dev(g["x"]), dev(g["dy"])
+        vl, kp = dev(g["valid_len"]), dev(g["key_pad"])
     wq, wk, wv, wo = (dev(g[n]) for n in ("wq", "wk", "wv", "wo"))
-    vl, kp = dev(g["valid_len"]), dev(g["key_pad"])
     sb, wb = B.im_attention_sizes(shape)
     saved = torch.empty(sb, dtype=torch.uint8, device="cuda")
     ws = torch.empty(wb, dtype=torch.uint8, device="cuda")
@@ -331,15 +352,20 @@ def main():
     ms_step, per_step, launches, dom = timed_run(step, args, B, torch)
 
     P = live_pairs(g["seg_len"], lm, Bsz, g["valid_len"], g["key_pad"])
+    if lengths is not None:
+        # only the rows inside the lengths are work that was asked for, as queries too
+        n = len(g["seg_len"])
+        P = int(sum(int(lengths[b, i]) * int(lengths[b, j]) for b in range(Bsz) for i in range(n) for j in range(n)
+                    if (lm >> (i * n + j)) & 1))
     core_flops = 14.0 * P * d                         # 4 P d forward + 10 P d backward (summed over heads)
-    proj_flops = 24.0 * Bsz * T * d * d               # 8 fwd + 16 bwd
+    proj_flops = 24.0 * rows * d * d                  # 8 fwd + 16 bwd, on the rows held in memory
     value = core_flops / (ms_step * 1e-3) / 1e12
 
     # ---- roofline of the dominant kernel (by accumulated event time) ----
     # algorithmic flops per launch: forward 4 P d (two products); dK/dV kernel 8 P d (S, dP, dV, dK);
     # dQ kernel 2 P d (the dQ product; its recomputed S and dP are not algorithmic work)
     alg = {"attn_fwd": 4.0 * P * d, "attn_dkv": 8.0 * P * d, "attn_dq": 2.0 * P * d,
-           "proj_fwd": 8.0 * Bsz * T * d * d, "proj_bwd": 8.0 * Bsz * T * d * d, "wgrad": 8.0 * Bsz * T * d * d}
+           "proj_fwd": 8.0 * rows * d * d, "proj_bwd": 8.0 * rows * d * d, "wgrad": 8.0 * rows * d * d}
     attn_keys = [k for k in ("attn_fwd", "attn_dq", "attn_dkv") if k in per_step]
     dom_ms = per_step[dom]
     traffic = stored_traffic(args.config, dom) if args.mask == "ifm_forward" else None   # counters were taken with the default mask
@@ -363,7 +389,7 @@ def main():
         "dtype": "bf16" if dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{args.config}: B={Bsz} L_t/L_v/L_a={'/'.join(map(str, g['seg_len']))} d={d} H={H} "
                                f"{dtype} fwd+bwd, mask={args.mask}, padding={w['padding']}",
-                   "live_pairs": P, "core_gflop_per_step": round(core_flops / 1e9, 2),
+                   "rows_in_memory": rows, "live_pairs": P, "core_gflop_per_step": round(core_flops / 1e9, 2),
                    "proj_gflop_per_step": round(proj_flops / 1e9, 2)},
         "with_projection_tflops": round((core_flops + proj_flops) / (ms_step * 1e-3) / 1e12, 3),
         "kernel_ms_per_step": {k: round(v, 4) for k, v in per_step.items()},
