@@ -75,8 +75,28 @@ __device__ __forceinline__ void store_km(const Tile128& t, bf16_t* lds, int tid)
 
 // EPI: the epilogue may apply GELU and add a residual (separate instantiation, so that the plain
 // bias epilogue of the attention projections stays a few hundred instructions long).
+// Bias of the 4 consecutive output columns n .. n+3 (n % 4 == 0) as fp32; 0 without a bias or past
+// N.  The columns lie in one of at most three blocks of width n_per (one bias vector each), so the
+// block index needs no integer division.
+__device__ __forceinline__ void bias4(const MGemm& p, int n, float (&out)[4]) {
+  out[0] = out[1] = out[2] = out[3] = 0.f;
+  if (p.n_per <= 0 || n >= p.N) return;
+  const int sel = (n >= p.n_per) + (n >= 2 * p.n_per);
+  const bf16_t* bp = sel == 0 ? p.bias[0] : sel == 1 ? p.bias[1] : p.bias[2];
+  if (!bp) return;
+  const bf16_t* q = bp + (n - sel * p.n_per);
+  if ((reinterpret_cast<uintptr_t>(bp) & 7) == 0) {
+    const u32x2 v = *(const u32x2*)q;
+    out[0] = __uint_as_float(v[0] << 16); out[1] = __uint_as_float(v[0] & 0xffff0000u);
+    out[2] = __uint_as_float(v[1] << 16); out[3] = __uint_as_float(v[1] & 0xffff0000u);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) out[j] = bf2f(q[j]);
+  }
+}
+
 template <bool AKM, bool BKM, bool EPI>
-__global__ __launch_bounds__(256) void mfma_gemm_kernel(MGemm p) {
+__global__ __launch_bounds__(256, 3) void mfma_gemm_kernel(MGemm p) {  // three workgroups per CU: at most 168 registers
   __shared__ __attribute__((aligned(16))) bf16_t sA[AKM ? GK * KM_LD : GM * LDS_LD];
   __shared__ __attribute__((aligned(16))) bf16_t sB[BKM ? GK * KM_LD : GN * LDS_LD];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
@@ -89,13 +109,21 @@ __global__ __launch_bounds__(256) void mfma_gemm_kernel(MGemm p) {
   const int per_split = (ktiles + p.split_k - 1) / p.split_k;
   const int it_begin = bz * per_split, it_end = min(ktiles, it_begin + per_split);
 
-  f32x16 acc[2][2];  // [n block][m block]: rows of the accumulator = n, cols = m
+  // [n block][m block]: rows of the accumulator = n, cols = m; registers 4i..4i+3 are columns
+  // n = 8i + 4hi + 0..3 of the block.  The accumulators start at the bias of their column (split-K launches
+  // carry no bias), so the epilogue has nothing to add.
+  f32x16 acc[2][2];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int i = 0; i < 4; ++i) {
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (!p.partial) bias4(p, n0 + wn * 64 + nb * 32 + 8 * i + 4 * hi, bv);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) acc[nb][mb][4 * i + jj] = bv[jj];
+    }
 
   const bf16_t* amat[3] = {p.A, p.A, p.A};
   const bf16_t* bmat[3] = {p.B[0], p.B[1], p.B[2]};
@@ -155,23 +183,6 @@ __global__ __launch_bounds__(256) void mfma_gemm_kernel(MGemm p) {
     }
     return;
   }
-  // The bias depends on the column only: fetch this lane's 8 x 4 values once.
-  float bv[2][4][4];
-#pragma unroll
-  for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int n = n0 + wn * 64 + nb * 32 + 8 * i + 4 * hi;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) bv[nb][i][j] = 0.f;
-      if (p.n_per > 0 && n < p.N) {
-        const int sel = n / p.n_per, nn = n - sel * p.n_per;
-        if (p.bias[sel]) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) bv[nb][i][j] = bf2f(p.bias[sel][nn + j]);
-        }
-      }
-    }
   // Direct 8-byte stores (a lane owns a row of the accumulator tile).  Staging the tile through LDS
   // for 16-byte row-contiguous stores was measured slower here: with three workgroups per CU the
   // stores of one overlap the loads of the others, and the extra barrier costs more than it saves.
@@ -187,7 +198,7 @@ __global__ __launch_bounds__(256) void mfma_gemm_kernel(MGemm p) {
         if (n >= p.N) continue;  // N is a multiple of 4 for every caller
         float v[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j] + bv[nb][i][j];
+        for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j];
         if constexpr (EPI) {
           if (p.gelu) {
 #pragma unroll
@@ -299,13 +310,20 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
     }
   };
 
-  f32x16 acc[4][4];  // [n block][m block]
+  // [n block][m block]; registers 4i..4i+3 are columns n = 8i + 4hi + 0..3 of the block.  The
+  // accumulators start at the bias of their column (split-K launches carry no bias).
+  f32x16 acc[4][4];
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+  for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
+    for (int i = 0; i < 4; ++i) {
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (!p.partial) bias4(p, n0 + wn * 128 + nb * 32 + 8 * i + 4 * hi, bv);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) acc[nb][mb][4 * i + jj] = bv[jj];
+    }
 
   // ---- LDS byte offsets of this lane's fragments inside a stage ----
   int offA[2][4], offB[2][4];   // [k-step][block]; for k-major operands the second transpose read is +4 rows
@@ -400,23 +418,8 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
   asm volatile("" ::: "memory");
   constexpr int EP_LD = 136;     // bf16 per staged row (128 + 8 pad)
   bf16_t* stg = smem + wave * (DMA_LDS_BYTES / 8);
-  // The bias depends on the column only: fetch this lane's 16 x 4 values once, not once per row block.
-  float bv[4][4][4];
-#pragma unroll
-  for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int n = n0 + wn * 128 + nb * 32 + 8 * i + 4 * hi;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) bv[nb][i][j] = 0.f;
-      if (p.n_per > 0 && n < p.N) {
-        const int sel = n / p.n_per, nn = n - sel * p.n_per;
-        if (p.bias[sel]) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) bv[nb][i][j] = bf2f(p.bias[sel][nn + j]);
-        }
-      }
-    }
+  // a tile inside the matrix stores without bounds checks
+  const bool interior = m0 + DM <= p.M && n0 + DN <= p.N;
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
 #pragma unroll
@@ -431,13 +434,13 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
           const int n = n0 + wn * 128 + nl;
           float v[4];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j] + bv[nb][i][j];
+          for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j];
           if constexpr (EPI) {
             if (p.gelu) {
 #pragma unroll
               for (int j = 0; j < 4; ++j) v[j] = gelu_exact_f(v[j]);
             }
-            if (p.res && m < p.M && n < p.N) {
+            if (p.res && (interior || (m < p.M && n < p.N))) {
               const u32x2 rv = *(const u32x2*)(p.res + (long)m * p.ldc + n);
               v[0] += __uint_as_float(rv[0] << 16); v[1] += __uint_as_float(rv[0] & 0xffff0000u);
               v[2] += __uint_as_float(rv[1] << 16); v[3] += __uint_as_float(rv[1] & 0xffff0000u);
@@ -447,13 +450,18 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
           *(u32x2*)(stg + (mq * 32 + lo) * EP_LD + nl) = pk;
         }
     }
-    // 64 rows x 16 chunks of 16 bytes; lane -> (row = q / 16, chunk = q % 16)
+    // 64 rows x 16 chunks of 16 bytes; lane -> (row = 4 t + lane / 16, chunk = lane % 16)
+    const int row0 = lane >> 4, ch = lane & 15;
+    const int mrow = m0 + wm * 128 + half * 64 + row0, n = n0 + wn * 128 + ch * 8;
+    bf16_t* cp = p.C + (long)mrow * p.ldc + n;
+    const bf16_t* sp = stg + row0 * EP_LD + ch * 8;
+    if (interior) {
 #pragma unroll
-    for (int t = 0; t < 16; ++t) {
-      const int q = t * 64 + lane, row = q >> 4, ch = q & 15;
-      const int m = m0 + wm * 128 + half * 64 + row, n = n0 + wn * 128 + ch * 8;
-      const u32x4 val = *(const u32x4*)(stg + row * EP_LD + ch * 8);
-      if (m < p.M && n < p.N) *(u32x4*)(p.C + (long)m * p.ldc + n) = val;  // N is a multiple of 8 on this path
+      for (int t = 0; t < 16; ++t) *(u32x4*)(cp + (long)(4 * t) * p.ldc) = *(const u32x4*)(sp + 4 * t * EP_LD);
+    } else {
+#pragma unroll
+      for (int t = 0; t < 16; ++t)   // N is a multiple of 8 on this path
+        if (mrow + 4 * t < p.M && n < p.N) *(u32x4*)(cp + (long)(4 * t) * p.ldc) = *(const u32x4*)(sp + 4 * t * EP_LD);
     }
   }
 }
