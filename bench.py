@@ -274,6 +274,9 @@ def main():
                     help="c3p: the C3 shape with the dataset's sequence-length statistics, packed rows; "
                          "c3v: the same lengths with padded rows and valid_len")
     ap.add_argument("--mask", default="ifm_forward", choices=["ifm_forward", "ifm_backward", "iem"])
+    ap.add_argument("--graph", action="store_true",
+                    help="attention configs: capture one forward+backward into a HIP graph and time its replays "
+                         "(the per-kernel table and the roofline still come from eager passes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one 1 GiB device copy first (reference reading for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -350,6 +353,26 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     ms_step, per_step, launches, dom = timed_run(step, args, B, torch)
+    ms_eager = None
+    if args.graph:
+        # the calls allocate nothing and record no memsets: one step is capturable as it is
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms_eager, ms_step = ms_step, (time.perf_counter() - t0) * 1e3 / args.steps
 
     P = live_pairs(g["seg_len"], lm, Bsz, g["valid_len"], g["key_pad"])
     if lengths is not None:
@@ -397,6 +420,9 @@ def main():
         "attn_core_tflops": round(core_flops / (sum(per_step[k] for k in attn_keys) * 1e-3) / 1e12, 3),
         "roofline": roof,
     }
+    if ms_eager is not None:
+        out["config"]["launch"] = "HIP graph replay"
+        out["ms_per_step_eager"] = round(ms_eager, 4)
 
     if not args.no_cpu_baseline:
         import oracle
