@@ -157,8 +157,6 @@ struct SavedLayout {
 };
 static SavedLayout saved_layout(const im_shape_t* s) {
   const size_t es = s->dtype == IM_DTYPE_BF16 ? 2 : 4;
-  long T = 0;
-  for (int i = 0; i < s->n_seg; ++i) T += s->seg_len[i];
   const size_t R = (size_t)shape_rows(s), d = s->d_model;
   SavedLayout L;
   size_t off = 0;
@@ -173,8 +171,6 @@ static SavedLayout saved_layout(const im_shape_t* s) {
 
 static size_t bwd_workspace_bytes(const im_shape_t* s) {
   const size_t es = s->dtype == IM_DTYPE_BF16 ? 2 : 4;
-  long T = 0;
-  for (int i = 0; i < s->n_seg; ++i) T += s->seg_len[i];
   const size_t R = (size_t)shape_rows(s), d = s->d_model;
   if (pick_path(s) == PATH_MFMA) return mfma_bwd_workspace_bytes(s);
   size_t n = 0;
@@ -472,8 +468,6 @@ static int layer_check(const im_shape_t* shape, int32_t d_ff) {
 
 static size_t layer_ws(const im_shape_t* s, int32_t d_ff, size_t* attn_ws_bytes) {
   const size_t es = s->dtype == IM_DTYPE_BF16 ? 2 : 4;
-  long T = 0;
-  for (int i = 0; i < s->n_seg; ++i) T += s->seg_len[i];
   const size_t R = (size_t)shape_rows(s), d = s->d_model;
   size_t aws = saved_layout(s).total;
   if (pick_path(s) == PATH_MFMA) aws += mfma_fwd_workspace_bytes(s->d_model);
@@ -506,8 +500,6 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
   hipStream_t st = as_stream(hip_stream);
   const int bf = shape->dtype == IM_DTYPE_BF16;
   const size_t es = bf ? 2 : 4;
-  long T = 0;
-  for (int i = 0; i < shape->n_seg; ++i) T += shape->seg_len[i];
   const long R = shape_rows(shape), d = shape->d_model;
   Bump b{(char*)workspace, 0, 0};
   void* u = b.take(R * d * es);
@@ -557,8 +549,6 @@ struct LayerTrain {
 static LayerTrain layer_train_layout(const im_shape_t* s, int32_t d_ff) {
   LayerTrain L;
   const size_t es = s->dtype == IM_DTYPE_BF16 ? 2 : 4;
-  long T = 0;
-  for (int i = 0; i < s->n_seg; ++i) T += s->seg_len[i];
   const size_t R = (size_t)shape_rows(s), d = s->d_model, f = (size_t)d_ff;
   size_t off = 0;
   L.att = off; off += align256(saved_layout(s).total);
@@ -613,8 +603,6 @@ int gsit_layer_fwd_train(const im_shape_t* shape, int32_t d_ff, const void* x, c
     return fail(IM_ERR_WORKSPACE, "gsit_layer_fwd_train needs %zu workspace bytes, got %zu", L.fwd_ws_total, workspace_bytes);
   hipStream_t st = as_stream(hip_stream);
   const int bf = shape->dtype == IM_DTYPE_BF16;
-  long T = 0;
-  for (int i = 0; i < shape->n_seg; ++i) T += shape->seg_len[i];
   const long R = shape_rows(shape), d = shape->d_model;
   char* sv = (char*)saved;
   char* ws = (char*)workspace;
@@ -667,8 +655,6 @@ int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const g
     return fail(IM_ERR_WORKSPACE, "gsit_layer_bwd needs %zu workspace bytes, got %zu", L.ws_total, workspace_bytes);
   hipStream_t st = as_stream(hip_stream);
   const int bf = shape->dtype == IM_DTYPE_BF16;
-  long T = 0;
-  for (int i = 0; i < shape->n_seg; ++i) T += shape->seg_len[i];
   const long R = shape_rows(shape), d = shape->d_model;
   const char* sv = (const char*)saved;
   char* ws = (char*)workspace;

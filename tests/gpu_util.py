@@ -131,7 +131,8 @@ class PackedProblem(Problem):
         self.t["x"] = to_dev(synth.pack_rows(x, self.lengths, seg), self.dtype)
         self.t["dy"] = to_dev(synth.pack_rows(g["dy"], self.lengths, seg), self.dtype)
         self.t["valid_len"] = None
-        self.t["key_pad"] = None
+        kp = g.get("key_pad")   # [B, T_m] -> [total_rows]
+        self.t["key_pad"] = None if kp is None else to_dev(synth.pack_rows(kp, self.lengths, seg), self.dtype)
         sb, wb = B.im_attention_sizes(self.shape)
         self.saved = torch.empty(sb, dtype=torch.uint8, device="cuda")
         self.ws = torch.empty(max(wb, 1), dtype=torch.uint8, device="cuda")
@@ -145,7 +146,7 @@ class PackedProblem(Problem):
         torch.cuda.synchronize()
         y_ref, cache = oracle.forward(g["x"], g["wq"], g["wk"], g["wv"], g["wo"], seg, self.lm, g["n_heads"], g["scale"],
                                       bq=g.get("bq"), bk=g.get("bk"), bv=g.get("bv"), bo=g.get("bo"),
-                                      valid_len=self.lengths, return_cache=True)
+                                      valid_len=self.lengths, key_pad=g.get("key_pad"), return_cache=True)
         errs = {"y": assert_close(y, pack(y_ref), tol, what + " y")}
         if backward:
             grads = self.bwd()

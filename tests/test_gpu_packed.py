@@ -44,6 +44,15 @@ def test_packed_bf16_matrix_cores(name):
     PackedProblem(g, oracle.NAMED_PATTERNS[name], lengths_for(3, seg, 302)).check(what=f"packed/bf16/{name}")
 
 
+@pytest.mark.parametrize("dtype,d,H", [("fp32", 40, 8), ("bf16", 128, 2), ("bf16", 64, 8)])
+def test_packed_with_key_pad(dtype, d, H):
+    # key_pad over the packed rows: 10 % of the positions are padding keys on top of the per-sample lengths
+    say(f"[case] packed + key_pad {dtype} d={d} H={H}")
+    seg = (40, 210, 150)
+    g = synth.attention_inputs(3, seg, d, H, dtype, "key_pad", seed=308, bias=True)
+    PackedProblem(g, oracle.IM_IFM_BACKWARD, lengths_for(3, seg, 308, lo_frac=0.3)).check(what=f"packed/key_pad/{dtype}")
+
+
 @pytest.mark.parametrize("dh", [8, 16])
 def test_packed_bf16_subhead(dh):
     say(f"[case] packed bf16 sub-head dh={dh}")
