@@ -3,33 +3,66 @@
 // The multimodal-sentiment shapes have head dimension 5..8: a contraction that
 // short cannot fill an MFMA tile, so the live-block products are done as FMAs
 // with one query row (forward, dQ) or one key row (dK/dV) per lane and the
-// other operand broadcast from LDS.  Each workgroup is one 64-wide wavefront
-// owning a tile of 64 rows of one modality segment; it visits only the key
-// (query) segments the Interlaced Mask leaves live for its segment (Sec. 6
-// "Decomposition"), trimmed to the valid length, and keeps one running maximum
-// and sum per row across all of them (joint row softmax, Sec. 7.1).
+// other operand broadcast from LDS.  Each workgroup owns a tile of 64 rows of
+// one modality segment (1 or 4 wavefronts, which share the rows of the other
+// operand between them); it visits only the key (query) segments the Interlaced
+// Mask leaves live for its segment (Sec. 6 "Decomposition"), trimmed to the
+// valid length, and keeps one running maximum and sum per row across all of
+// them (joint row softmax, Sec. 7.1).
 #include "common.hpp"
 
 namespace imattn {
 
 constexpr int RL_ROWS = 64;    // rows per tile == lanes
-constexpr int RL_CHUNK = 128;  // rows of the other operand staged in LDS at a time
+constexpr int RL_CHUNK = 64;    // rows of the other operand staged in LDS at a time
 // Kernels are instantiated for the exact head dimension DH (register arrays and FMA loops have DH
 // entries: at dh = 5 a padded-to-8 loop would waste 3 of every 8 FMAs); LDS rows are padded to a
 // power of two for aligned broadcast reads.
 __host__ __device__ constexpr int lds_row(int dh) { return dh <= 4 ? 4 : dh <= 8 ? 8 : 16; }
 
-template <typename T, int DH>
-__global__ __launch_bounds__(RL_ROWS) void rowlane_fwd_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K,
-                                                              const T* __restrict__ V, long ld,
-                                                              const int32_t* __restrict__ valid_len,
-                                                              const uint8_t* __restrict__ key_pad, T* __restrict__ O,
-                                                              long ldo, float* __restrict__ lse2) {
+// Splitting one tile's work over the NW waves of a workgroup.  The rows of the other operand (keys
+// for forward / dQ, queries for dK/dV) are visited in chunks of RL_CHUNK rows; the chunks of all live
+// segments form one numbered sequence, and wave w takes chunks w, w + NW, ...  Each wave stages its
+// chunk in its own LDS slice and keeps its own partial result; the partials are combined in wave
+// order at the end (fixed order: results are reproducible).  With a single wave per tile the longest
+// tile (one wave walking through every key of a long segment) set the kernel time at the small
+// multimodal shapes, where the grid is only a few waves per SIMD.
+//
+// chunk id -> (segment, first row, rows); false once id is past the last chunk
+template <class LenFn>
+__device__ __forceinline__ bool locate_chunk(unsigned live, int n_seg, int id, LenFn len_of, int& seg, int& c0, int& n) {
+  for (int j = 0; j < n_seg; ++j) {
+    if (!((live >> j) & 1u)) continue;
+    const int len = len_of(j);
+    const int nch = (len + RL_CHUNK - 1) / RL_CHUNK;
+    if (id < nch) {
+      seg = j;
+      c0 = id * RL_CHUNK;
+      n = min(RL_CHUNK, len - c0);
+      return true;
+    }
+    id -= nch;
+  }
+  return false;
+}
+template <class LenFn>
+__device__ __forceinline__ int count_chunks(unsigned live, int n_seg, LenFn len_of) {
+  int total = 0;
+  for (int j = 0; j < n_seg; ++j)
+    if ((live >> j) & 1u) total += (len_of(j) + RL_CHUNK - 1) / RL_CHUNK;
+  return total;
+}
+
+template <typename T, int DH, int NW>
+__global__ __launch_bounds__(NW * RL_ROWS) void rowlane_fwd_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K,
+                                                                   const T* __restrict__ V, long ld,
+                                                                   const int32_t* __restrict__ valid_len,
+                                                                   const uint8_t* __restrict__ key_pad, T* __restrict__ O,
+                                                                   long ldo, float* __restrict__ lse2) {
   constexpr int LP = lds_row(DH);
-  __shared__ float sK[RL_CHUNK][LP];
-  __shared__ float sV[RL_CHUNK][LP];
-  __shared__ float sBias[RL_CHUNK];
-  const int lane = threadIdx.x, h = blockIdx.y, b = blockIdx.z;
+  __shared__ float sKV[NW][2][RL_CHUNK][LP];  // per wave: K rows, V rows of its chunk
+  __shared__ float sBias[NW][RL_CHUNK];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = blockIdx.y, b = blockIdx.z;
   int qs, q0;
   decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, RL_ROWS, blockIdx.x, qs, q0);
   const int qlen = seg_rows(g, b, qs);
@@ -48,52 +81,81 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_fwd_kernel(Geo g, const T* __
   float m = IM_NEG_INF, l = 0.f;
 
   const unsigned live = g.q_live[qs];
-  for (int j = 0; j < g.n_seg; ++j) {
-    if (!((live >> j) & 1u)) continue;
+  auto klen_of = [&](int j) {
     int klen = seg_rows(g, b, j);
     if (valid_len) klen = min(klen, max(0, valid_len[b * g.n_seg + j]));
-    const long kbase = seg_row0(g, b, j);
-    for (int c0 = 0; c0 < klen; c0 += RL_CHUNK) {
-      const int n = min(RL_CHUNK, klen - c0);
-      const int n4 = (n + 3) & ~3;
-      __syncthreads();
+    return klen;
+  };
+  const int rounds = (count_chunks(live, g.n_seg, klen_of) + NW - 1) / NW;
+  for (int r = 0; r < rounds; ++r) {
+    int j = 0, c0 = 0, n = 0;
+    const bool has = locate_chunk(live, g.n_seg, r * NW + wave, klen_of, j, c0, n);
+    const int n4 = (n + 3) & ~3;
+    __syncthreads();
+    if (has) {
+      const long kbase = seg_row0(g, b, j);
       for (int i = lane; i < n4 * LP; i += RL_ROWS) {
         const int c = i / LP, e = i % LP;
         const bool ok = (c < n) && (e < dh);
         const long a = (kbase + c0 + c) * ld + hc + e;
-        sK[c][e] = ok ? ldf(K + a) : 0.f;
-        sV[c][e] = ok ? ldf(V + a) : 0.f;
+        sKV[wave][0][c][e] = ok ? ldf(K + a) : 0.f;
+        sKV[wave][1][c][e] = ok ? ldf(V + a) : 0.f;
       }
       for (int c = lane; c < n4; c += RL_ROWS) {
         bool ok = c < n;
         if (ok && key_pad) ok = key_pad[kbase + c0 + c] == 0;
-        sBias[c] = ok ? 0.f : IM_NEG_INF;
+        sBias[wave][c] = ok ? 0.f : IM_NEG_INF;
       }
-      __syncthreads();
-      for (int c = 0; c < n4; c += 4) {
-        float s[4];
+    }
+    __syncthreads();
+    if (!has) continue;
+    for (int c = 0; c < n4; c += 4) {
+      float s[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          float a = sBias[c + u];
+      for (int u = 0; u < 4; ++u) {
+        float a = sBias[wave][c + u];
 #pragma unroll
-          for (int e = 0; e < DH; ++e) a = fmaf(q[e], sK[c + u][e], a);
-          s[u] = a;
-        }
-        const float mn = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), m);
-        const float ms = (mn == IM_NEG_INF) ? 0.f : mn;
-        const float alpha = __builtin_amdgcn_exp2f(m - ms);
-        l *= alpha;
-#pragma unroll
-        for (int e = 0; e < DH; ++e) acc[e] *= alpha;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const float p = __builtin_amdgcn_exp2f(s[u] - ms);
-          l += p;
-#pragma unroll
-          for (int e = 0; e < DH; ++e) acc[e] = fmaf(p, sV[c + u][e], acc[e]);
-        }
-        m = mn;
+        for (int e = 0; e < DH; ++e) a = fmaf(q[e], sKV[wave][0][c + u][e], a);
+        s[u] = a;
       }
+      const float mn = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), m);
+      const float ms = (mn == IM_NEG_INF) ? 0.f : mn;
+      const float alpha = __builtin_amdgcn_exp2f(m - ms);
+      l *= alpha;
+#pragma unroll
+      for (int e = 0; e < DH; ++e) acc[e] *= alpha;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float p = __builtin_amdgcn_exp2f(s[u] - ms);
+        l += p;
+#pragma unroll
+        for (int e = 0; e < DH; ++e) acc[e] = fmaf(p, sKV[wave][1][c + u][e], acc[e]);
+      }
+      m = mn;
+    }
+  }
+  if (NW > 1) {
+    // combine the waves' (max, sum, accumulator) triples; wave w's LDS slice holds its partial
+    constexpr int PS = DH + 2;
+    static_assert(RL_ROWS * PS <= 2 * RL_CHUNK * LP, "partial results must fit in a wave's LDS slice");
+    __syncthreads();
+    float* part = &sKV[wave][0][0][0] + lane * PS;
+    part[0] = m;
+    part[1] = l;
+#pragma unroll
+    for (int e = 0; e < DH; ++e) part[2 + e] = acc[e];
+    __syncthreads();
+    if (wave != 0) return;
+    for (int w = 1; w < NW; ++w) {
+      const float* o = &sKV[w][0][0][0] + lane * PS;
+      const float m2 = o[0];
+      const float mn = fmaxf(m, m2);
+      const float ms = (mn == IM_NEG_INF) ? 0.f : mn;
+      const float a1 = __builtin_amdgcn_exp2f(m - ms), a2 = __builtin_amdgcn_exp2f(m2 - ms);
+      l = l * a1 + o[1] * a2;
+#pragma unroll
+      for (int e = 0; e < DH; ++e) acc[e] = acc[e] * a1 + o[2 + e] * a2;
+      m = mn;
     }
   }
   if (active) {
@@ -106,19 +168,18 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_fwd_kernel(Geo g, const T* __
 }
 
 // dQ (and delta = rowsum(dO * O)) : one query row per lane, keys broadcast from LDS.
-template <typename T, int DH>
-__global__ __launch_bounds__(RL_ROWS) void rowlane_dq_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K,
-                                                             const T* __restrict__ V, long ld, const T* __restrict__ O,
-                                                             const T* __restrict__ dO, long ldo,
-                                                             const float* __restrict__ lse2,
-                                                             const int32_t* __restrict__ valid_len,
-                                                             const uint8_t* __restrict__ key_pad,
-                                                             float* __restrict__ delta, T* __restrict__ dQ, long ldg) {
+template <typename T, int DH, int NW>
+__global__ __launch_bounds__(NW * RL_ROWS) void rowlane_dq_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K,
+                                                                  const T* __restrict__ V, long ld, const T* __restrict__ O,
+                                                                  const T* __restrict__ dO, long ldo,
+                                                                  const float* __restrict__ lse2,
+                                                                  const int32_t* __restrict__ valid_len,
+                                                                  const uint8_t* __restrict__ key_pad,
+                                                                  float* __restrict__ delta, T* __restrict__ dQ, long ldg) {
   constexpr int LP = lds_row(DH);
-  __shared__ float sK[RL_CHUNK][LP];
-  __shared__ float sV[RL_CHUNK][LP];
-  __shared__ float sBias[RL_CHUNK];
-  const int lane = threadIdx.x, h = blockIdx.y, b = blockIdx.z;
+  __shared__ float sKV[NW][2][RL_CHUNK][LP];  // per wave: K rows, V rows of its chunk
+  __shared__ float sBias[NW][RL_CHUNK];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = blockIdx.y, b = blockIdx.z;
   int qs, q0;
   decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, RL_ROWS, blockIdx.x, qs, q0);
   const int qlen = seg_rows(g, b, qs);
@@ -141,41 +202,61 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dq_kernel(Geo g, const T* __r
   }
   float ls = lse2[li];
   if (ls == IM_NEG_INF) ls = __builtin_inff();  // row with no live valid key: every p becomes 0
-  if (active) delta[li] = dl;
+  if (active && wave == 0) delta[li] = dl;
 
   const unsigned live = g.q_live[qs];
-  for (int j = 0; j < g.n_seg; ++j) {
-    if (!((live >> j) & 1u)) continue;
+  auto klen_of = [&](int j) {
     int klen = seg_rows(g, b, j);
     if (valid_len) klen = min(klen, max(0, valid_len[b * g.n_seg + j]));
-    const long kbase = seg_row0(g, b, j);
-    for (int c0 = 0; c0 < klen; c0 += RL_CHUNK) {
-      const int n = min(RL_CHUNK, klen - c0);
-      __syncthreads();
+    return klen;
+  };
+  const int rounds = (count_chunks(live, g.n_seg, klen_of) + NW - 1) / NW;
+  for (int r = 0; r < rounds; ++r) {
+    int j = 0, c0 = 0, n = 0;
+    const bool has = locate_chunk(live, g.n_seg, r * NW + wave, klen_of, j, c0, n);
+    __syncthreads();
+    if (has) {
+      const long kbase = seg_row0(g, b, j);
       for (int i = lane; i < n * LP; i += RL_ROWS) {
         const int c = i / LP, e = i % LP;
         const long a = (kbase + c0 + c) * ld + hc + e;
-        sK[c][e] = (e < dh) ? ldf(K + a) : 0.f;
-        sV[c][e] = (e < dh) ? ldf(V + a) : 0.f;
+        sKV[wave][0][c][e] = (e < dh) ? ldf(K + a) : 0.f;
+        sKV[wave][1][c][e] = (e < dh) ? ldf(V + a) : 0.f;
       }
       for (int c = lane; c < n; c += RL_ROWS) {
         bool ok = true;
         if (key_pad) ok = key_pad[kbase + c0 + c] == 0;
-        sBias[c] = ok ? 0.f : IM_NEG_INF;
+        sBias[wave][c] = ok ? 0.f : IM_NEG_INF;
       }
-      __syncthreads();
-      for (int c = 0; c < n; ++c) {
-        float s = sBias[c], dp = 0.f;
+    }
+    __syncthreads();
+    if (!has) continue;
+    for (int c = 0; c < n; ++c) {
+      float s = sBias[wave][c], dp = 0.f;
 #pragma unroll
-        for (int e = 0; e < DH; ++e) {
-          s = fmaf(q[e], sK[c][e], s);
-          dp = fmaf(go[e], sV[c][e], dp);
-        }
-        const float p = __builtin_amdgcn_exp2f(s - ls);
-        const float ds = p * (dp - dl);
-#pragma unroll
-        for (int e = 0; e < DH; ++e) acc[e] = fmaf(ds, sK[c][e], acc[e]);
+      for (int e = 0; e < DH; ++e) {
+        s = fmaf(q[e], sKV[wave][0][c][e], s);
+        dp = fmaf(go[e], sKV[wave][1][c][e], dp);
       }
+      const float p = __builtin_amdgcn_exp2f(s - ls);
+      const float ds = p * (dp - dl);
+#pragma unroll
+      for (int e = 0; e < DH; ++e) acc[e] = fmaf(ds, sKV[wave][0][c][e], acc[e]);
+    }
+  }
+  if (NW > 1) {
+    // sum the waves' partial dQ rows in wave order
+    static_assert(RL_ROWS * DH <= 2 * RL_CHUNK * LP, "partial results must fit in a wave's LDS slice");
+    __syncthreads();
+    float* part = &sKV[wave][0][0][0] + lane * DH;
+#pragma unroll
+    for (int e = 0; e < DH; ++e) part[e] = acc[e];
+    __syncthreads();
+    if (wave != 0) return;
+    for (int w = 1; w < NW; ++w) {
+      const float* o = &sKV[w][0][0][0] + lane * DH;
+#pragma unroll
+      for (int e = 0; e < DH; ++e) acc[e] += o[e];
     }
   }
   if (active) {
@@ -187,21 +268,20 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dq_kernel(Geo g, const T* __r
 
 // dK, dV : one key row per lane, query rows (Q, dO, lse, delta) broadcast from LDS.
 // Each key segment has a single producer workgroup per tile, so no atomics.
-template <typename T, int DH>
-__global__ __launch_bounds__(RL_ROWS) void rowlane_dkv_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K,
-                                                              const T* __restrict__ V, long ld,
-                                                              const T* __restrict__ dO, long ldo,
-                                                              const float* __restrict__ lse2,
-                                                              const float* __restrict__ delta,
-                                                              const int32_t* __restrict__ valid_len,
-                                                              const uint8_t* __restrict__ key_pad, T* __restrict__ dK,
-                                                              T* __restrict__ dV, long ldg) {
+template <typename T, int DH, int NW>
+__global__ __launch_bounds__(NW * RL_ROWS) void rowlane_dkv_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K,
+                                                                   const T* __restrict__ V, long ld,
+                                                                   const T* __restrict__ dO, long ldo,
+                                                                   const float* __restrict__ lse2,
+                                                                   const float* __restrict__ delta,
+                                                                   const int32_t* __restrict__ valid_len,
+                                                                   const uint8_t* __restrict__ key_pad, T* __restrict__ dK,
+                                                                   T* __restrict__ dV, long ldg) {
   constexpr int LP = lds_row(DH);
-  __shared__ float sQ[RL_CHUNK][LP];
-  __shared__ float sG[RL_CHUNK][LP];
-  __shared__ float sL[RL_CHUNK];
-  __shared__ float sD[RL_CHUNK];
-  const int lane = threadIdx.x, h = blockIdx.y, b = blockIdx.z;
+  __shared__ float sQG[NW][2][RL_CHUNK][LP];  // per wave: Q rows, dO rows of its chunk
+  __shared__ float sL[NW][RL_CHUNK];
+  __shared__ float sD[NW][RL_CHUNK];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = blockIdx.y, b = blockIdx.z;
   int ks, k0;
   decode_tile(g.k_order, g.k_tile_prefix, g.k_nord, RL_ROWS, blockIdx.x, ks, k0);
   const int klen_seg = seg_rows(g, b, ks);
@@ -223,40 +303,57 @@ __global__ __launch_bounds__(RL_ROWS) void rowlane_dkv_kernel(Geo g, const T* __
     av[e] = 0.f;
   }
   const unsigned live = g.k_live[ks];
-  for (int i = 0; i < g.n_seg; ++i) {
-    if (!((live >> i) & 1u)) continue;
-    const int qlen = seg_rows(g, b, i);
-    const long qbase = seg_row0(g, b, i);
-    const long lbase = seg_stat0(g, b, h, i);
-    for (int r0 = 0; r0 < qlen; r0 += RL_CHUNK) {
-      const int n = min(RL_CHUNK, qlen - r0);
-      __syncthreads();
+  auto qlen_of = [&](int i) { return seg_rows(g, b, i); };
+  const int rounds = (count_chunks(live, g.n_seg, qlen_of) + NW - 1) / NW;
+  for (int rd = 0; rd < rounds; ++rd) {
+    int i = 0, r0 = 0, n = 0;
+    const bool has = locate_chunk(live, g.n_seg, rd * NW + wave, qlen_of, i, r0, n);
+    __syncthreads();
+    if (has) {
+      const long qbase = seg_row0(g, b, i);
+      const long lbase = seg_stat0(g, b, h, i);
       for (int x = lane; x < n * LP; x += RL_ROWS) {
         const int r = x / LP, e = x % LP;
-        sQ[r][e] = (e < dh) ? ldf(Q + (qbase + r0 + r) * ld + hc + e) * g.scale_log2e : 0.f;
-        sG[r][e] = (e < dh) ? ldf(dO + (qbase + r0 + r) * ldo + hc + e) : 0.f;
+        sQG[wave][0][r][e] = (e < dh) ? ldf(Q + (qbase + r0 + r) * ld + hc + e) * g.scale_log2e : 0.f;
+        sQG[wave][1][r][e] = (e < dh) ? ldf(dO + (qbase + r0 + r) * ldo + hc + e) : 0.f;
       }
       for (int r = lane; r < n; r += RL_ROWS) {
         const float ls = lse2[lbase + r0 + r];
-        sL[r] = (ls == IM_NEG_INF) ? __builtin_inff() : ls;
-        sD[r] = delta[lbase + r0 + r];
+        sL[wave][r] = (ls == IM_NEG_INF) ? __builtin_inff() : ls;
+        sD[wave][r] = delta[lbase + r0 + r];
       }
-      __syncthreads();
-      for (int r = 0; r < n; ++r) {
-        float s = 0.f, dp = 0.f;
+    }
+    __syncthreads();
+    if (!has) continue;
+    for (int r = 0; r < n; ++r) {
+      float s = 0.f, dp = 0.f;
 #pragma unroll
-        for (int e = 0; e < DH; ++e) {
-          s = fmaf(sQ[r][e], k[e], s);
-          dp = fmaf(sG[r][e], v[e], dp);
-        }
-        const float p = __builtin_amdgcn_exp2f(s - sL[r]);
-        const float ds = p * (dp - sD[r]);
-#pragma unroll
-        for (int e = 0; e < DH; ++e) {
-          av[e] = fmaf(p, sG[r][e], av[e]);
-          ak[e] = fmaf(ds, sQ[r][e], ak[e]);
-        }
+      for (int e = 0; e < DH; ++e) {
+        s = fmaf(sQG[wave][0][r][e], k[e], s);
+        dp = fmaf(sQG[wave][1][r][e], v[e], dp);
       }
+      const float p = __builtin_amdgcn_exp2f(s - sL[wave][r]);
+      const float ds = p * (dp - sD[wave][r]);
+#pragma unroll
+      for (int e = 0; e < DH; ++e) {
+        av[e] = fmaf(p, sQG[wave][1][r][e], av[e]);
+        ak[e] = fmaf(ds, sQG[wave][0][r][e], ak[e]);
+      }
+    }
+  }
+  if (NW > 1) {
+    // sum the waves' partial dK / dV rows in wave order
+    static_assert(RL_ROWS * 2 * DH <= 2 * RL_CHUNK * LP, "partial results must fit in a wave's LDS slice");
+    __syncthreads();
+    float* part = &sQG[wave][0][0][0] + lane * 2 * DH;
+#pragma unroll
+    for (int e = 0; e < DH; ++e) { part[e] = ak[e]; part[DH + e] = av[e]; }
+    __syncthreads();
+    if (wave != 0) return;
+    for (int w = 1; w < NW; ++w) {
+      const float* o = &sQG[w][0][0][0] + lane * 2 * DH;
+#pragma unroll
+      for (int e = 0; e < DH; ++e) { ak[e] += o[e]; av[e] += o[DH + e]; }
     }
   }
   if (in_seg) {
@@ -316,13 +413,34 @@ bool rowlane_supports(int dh) { return dh >= 1 && dh <= 16; }
     else LAUNCH(16);            \
   } while (0)
 
+// Waves per tile: 4 when some tile has more than one chunk of the other operand to walk through
+// (by the maximum segment lengths), else 1.
+constexpr int RL_SPLIT = 4;
+static int max_chunks(const Geo& g, bool query_side) {
+  int best = 0;
+  for (int i = 0; i < g.n_seg; ++i) {
+    const unsigned live = query_side ? g.q_live[i] : g.k_live[i];
+    int n = 0;
+    for (int j = 0; j < g.n_seg; ++j)
+      if ((live >> j) & 1u) n += (g.seg_len[j] + RL_CHUNK - 1) / RL_CHUNK;
+    best = n > best ? n : best;
+  }
+  return best;
+}
+
 template <typename T>
 static int fwd_dispatch(const Geo& g, const T* q, const T* k, const T* v, long ld, const int32_t* vl, const uint8_t* kp,
                         T* o, long ldo, float* lse2, hipStream_t st) {
   const int ntiles = g.q_tile_prefix[g.q_nord];
   if (ntiles == 0) return IM_OK;
-  dim3 grid(ntiles, g.H, g.B), block(RL_ROWS);
-#define RL_FWD(DHV) hipLaunchKernelGGL((rowlane_fwd_kernel<T, DHV>), grid, block, 0, st, g, q, k, v, ld, vl, kp, o, ldo, lse2)
+  dim3 grid(ntiles, g.H, g.B);
+  const bool split = max_chunks(g, true) > 1;
+#define RL_FWD(DHV)                                                                                                        \
+  do {                                                                                                                     \
+    if (split) hipLaunchKernelGGL((rowlane_fwd_kernel<T, DHV, RL_SPLIT>), grid, dim3(RL_SPLIT * RL_ROWS), 0, st, g, q, k, v, \
+                                  ld, vl, kp, o, ldo, lse2);                                                               \
+    else hipLaunchKernelGGL((rowlane_fwd_kernel<T, DHV, 1>), grid, dim3(RL_ROWS), 0, st, g, q, k, v, ld, vl, kp, o, ldo, lse2); \
+  } while (0)
   RL_DISPATCH(g.dh, RL_FWD);
 #undef RL_FWD
   return IM_OK;
@@ -365,9 +483,21 @@ static int bwd_dispatch(const Geo& g, const T* q, const T* k, const T* v, long l
   zero_dead_rows<T>(g, false, dv, ldg, st);
   const int nq = g.q_tile_prefix[g.q_nord], nk = g.k_tile_prefix[g.k_nord];
   if (nq == 0) return IM_OK;
-  dim3 block(RL_ROWS);
-#define RL_DQ(DHV) hipLaunchKernelGGL((rowlane_dq_kernel<T, DHV>), dim3(nq, g.H, g.B), block, 0, st, g, q, k, v, ld, o, d_o, ldo, lse2, vl, kp, delta, dq, ldg)
-#define RL_DKV(DHV) hipLaunchKernelGGL((rowlane_dkv_kernel<T, DHV>), dim3(nk, g.H, g.B), block, 0, st, g, q, k, v, ld, d_o, ldo, lse2, delta, vl, kp, dk, dv, ldg)
+  const bool split_q = max_chunks(g, true) > 1, split_k = max_chunks(g, false) > 1;
+#define RL_DQ(DHV)                                                                                                         \
+  do {                                                                                                                     \
+    if (split_q) hipLaunchKernelGGL((rowlane_dq_kernel<T, DHV, RL_SPLIT>), dim3(nq, g.H, g.B), dim3(RL_SPLIT * RL_ROWS), 0, st, \
+                                    g, q, k, v, ld, o, d_o, ldo, lse2, vl, kp, delta, dq, ldg);                             \
+    else hipLaunchKernelGGL((rowlane_dq_kernel<T, DHV, 1>), dim3(nq, g.H, g.B), dim3(RL_ROWS), 0, st, g, q, k, v, ld, o, d_o, \
+                            ldo, lse2, vl, kp, delta, dq, ldg);                                                            \
+  } while (0)
+#define RL_DKV(DHV)                                                                                                        \
+  do {                                                                                                                     \
+    if (split_k) hipLaunchKernelGGL((rowlane_dkv_kernel<T, DHV, RL_SPLIT>), dim3(nk, g.H, g.B), dim3(RL_SPLIT * RL_ROWS), 0,  \
+                                    st, g, q, k, v, ld, d_o, ldo, lse2, delta, vl, kp, dk, dv, ldg);                        \
+    else hipLaunchKernelGGL((rowlane_dkv_kernel<T, DHV, 1>), dim3(nk, g.H, g.B), dim3(RL_ROWS), 0, st, g, q, k, v, ld, d_o,  \
+                            ldo, lse2, delta, vl, kp, dk, dv, ldg);                                                        \
+  } while (0)
   { ProfScope ps(PF_ATTN_DQ, st); RL_DISPATCH(g.dh, RL_DQ); }
   { ProfScope ps(PF_ATTN_DKV, st); RL_DISPATCH(g.dh, RL_DKV); }
 #undef RL_DQ
