@@ -183,7 +183,7 @@ static size_t bwd_workspace_bytes(const im_shape_t* s) {
     pb = std::max(pb, std::max(mfma_wgrad_partial_bytes((int)d, (int)(3 * d), (int)R), mfma_wgrad_partial_bytes((int)d, (int)d, (int)R)));
   if (wgrad_small_ok((int)d, (int)(3 * d), (int)d)) pb = std::max(pb, wgrad_small_partial_bytes((int)d, (int)(3 * d), (int)R));
   n += align256(pb);
-  n += align256(colsum_partial_bytes((int)R, (int)d));
+  n += align256(3 * colsum_partial_bytes((int)R, (int)d));            // dbq, dbk, dbv in one launch
   n += align256(3 * d * d * sizeof(float));                           // sinks for unwanted weight gradients
   return n;
 }
@@ -263,7 +263,7 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
   const bool ws_small = !mm && wgrad_small_ok((int)d, (int)(3 * d), (int)d);
   if (ws_small) pbytes = std::max(pbytes, wgrad_small_partial_bytes((int)d, (int)(3 * d), (int)R));
   float* partial = (float*)b.take(pbytes);
-  float* cpart = (float*)b.take(colsum_partial_bytes((int)R, (int)d));
+  float* cpart = (float*)b.take(3 * colsum_partial_bytes((int)R, (int)d));
   float* sink = (float*)b.take(3 * d * d * sizeof(float));
 
   GemmDesc p;
@@ -318,12 +318,13 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
     ProfScope ps(PF_WGRAD, st);
     if ((rc = launch_gemm_alu(p, bf, bf, 0, st))) return rc;
   }
-  void* dbs[3] = {dbq, dbk, dbv};
-  for (int i = 0; i < 3; ++i)
-    if (dbs[i]) {
-      ProfScope ps(PF_WGRAD, st);
-      if ((rc = launch_colsum(dqkv + i * d * es, 3 * d, (int)R, (int)d, bf, (float*)dbs[i], cpart, st))) return rc;
-    }
+  if (dbq || dbk || dbv) {  // column sums of the dQ | dK | dV column blocks
+    const void* src[3] = {dqkv, dqkv + d * es, dqkv + 2 * d * es};
+    const long lds3[3] = {3 * d, 3 * d, 3 * d};
+    float* dbs[3] = {(float*)dbq, (float*)dbk, (float*)dbv};
+    ProfScope ps(PF_WGRAD, st);
+    if ((rc = launch_colsum_multi(src, lds3, dbs, 3, (int)R, (int)d, bf, cpart, st))) return rc;
+  }
   // dx = dQ Wq^T + dK Wk^T + dV Wv^T
   if (dx && mm && d % 64 == 0) {  // the contraction is split over three weights: whole 64-deep k-tiles per weight
     ProfScope ps(PF_PROJ_BWD, st);
@@ -572,7 +573,7 @@ static LayerTrain layer_train_layout(const im_shape_t* s, int32_t d_ff) {
     p2 = std::max(p2, mfma_wgrad_partial_bytes(d_ff, (int)d, (int)R));
   }
   L.partial = off; off += align256(std::max(p1, p2));
-  L.cpart = off; off += align256(colsum_partial_bytes((int)R, (int)std::max(d, f)));
+  L.cpart = off; off += align256(colsum_partial_bytes((int)R, (int)std::max(2 * d, f)));   // two LayerNorm sums at once
   L.aws_bytes = bwd_workspace_bytes(s);
   L.attws = off; off += align256(L.aws_bytes);
   L.ws_total = off;
@@ -713,8 +714,12 @@ int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const g
   }
   // dh = dy + LN2 backward(dv)
   if ((rc = launch_layernorm_bwd(h, p->ln2_g, dv, dy, dh, t, (int)R, (int)d, ln_eps, bf, st))) return rc;
-  if (gr->ln2_g && (rc = launch_colsum(t, d, (int)R, (int)d, bf, (float*)gr->ln2_g, cpart, st))) return rc;
-  if (gr->ln2_b && (rc = launch_colsum(dv, d, (int)R, (int)d, bf, (float*)gr->ln2_b, cpart, st))) return rc;
+  {  // gradients of the LayerNorm gain and bias: column sums of dy * xhat and of dy
+    const void* src[2] = {t, dv};
+    const long ld2[2] = {d, d};
+    float* out2[2] = {(float*)gr->ln2_g, (float*)gr->ln2_b};
+    if ((rc = launch_colsum_multi(src, ld2, out2, 2, (int)R, (int)d, bf, cpart, st))) return rc;
+  }
   // h = x + IMAttention(u), u = LN(x; ln1): attention backward with upstream gradient dh; its dx is du (into dv)
   if ((rc = launch_layernorm(x, p->ln1_g, p->ln1_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
   const SavedLayout A = saved_layout(shape);
@@ -727,8 +732,12 @@ int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const g
   if (rc) return rc;
   // dx = dh + LN1 backward(du)
   if ((rc = launch_layernorm_bwd(x, p->ln1_g, dv, dh, dx, t, (int)R, (int)d, ln_eps, bf, st))) return rc;
-  if (gr->ln1_g && (rc = launch_colsum(t, d, (int)R, (int)d, bf, (float*)gr->ln1_g, cpart, st))) return rc;
-  if (gr->ln1_b && (rc = launch_colsum(dv, d, (int)R, (int)d, bf, (float*)gr->ln1_b, cpart, st))) return rc;
+  {
+    const void* src[2] = {t, dv};
+    const long ld2[2] = {d, d};
+    float* out2[2] = {(float*)gr->ln1_g, (float*)gr->ln1_b};
+    if ((rc = launch_colsum_multi(src, ld2, out2, 2, (int)R, (int)d, bf, cpart, st))) return rc;
+  }
   return check_hip("gsit_layer_bwd launch");
 }
 

@@ -133,7 +133,10 @@ size_t gemm_alu_partial_bytes(int M, int N, int K, int* split_k);
 
 // column sums of a [R, n] matrix (bias gradients), deterministic two-stage
 int launch_colsum(const void* a, long lda, int R, int n, int a_bf16, float* out, float* partial, hipStream_t st);
-size_t colsum_partial_bytes(int R, int n);
+size_t colsum_partial_bytes(int R, int n);   // for one matrix; launch_colsum_multi needs count times as much
+// column sums of up to 3 [R, n] matrices (same element type) in one pair of launches; out[i] == nullptr skips matrix i
+int launch_colsum_multi(const void* const* a, const long* lda, float* const* out, int count, int R, int n, int a_bf16,
+                        float* partial, hipStream_t st);
 
 // Zero columns col0 .. col0+ncols-1 of the rows of segment s of a [rows, ld] matrix; set a per-row
 // fp32 statistic ([B,H,T] padded / [H,R] packed) of the rows of segment s.  All batch elements.

@@ -344,16 +344,25 @@ int launch_wgrad_small(const void* A, long lda, const void* G, long ldg, int R, 
   return blocks;
 }
 
-// Column sums of a [R, n] matrix in two deterministic stages.  Stage 1: a block of 256 threads =
-// 4 row groups x 64 columns sums CS_ROWS rows (thread (g, c): rows r0 + g, r0 + g + 4, ..., with four
-// independent running sums so loads overlap), then the 4 groups are added in a fixed order through
-// LDS.  Stage 2 does the same over the per-block partials.
+// Column sums of up to three [R, n] matrices in two deterministic stages (one launch each for all of
+// them: blockIdx.z selects the matrix).  Stage 1: a block of 256 threads = 4 row groups x 64 columns
+// sums CS_ROWS rows (thread (g, c): rows r0 + g, r0 + g + 4, ..., with four independent running sums so
+// loads overlap), then the 4 groups are added in a fixed order through LDS.  Stage 2 does the same
+// over the per-block partials ([matrix][row block][n]).
 constexpr int CS_ROWS = 256;
+struct ColsumArgs {
+  const void* a[3];
+  long lda[3];
+  float* out[3];   // nullptr: this matrix is skipped
+};
 
 template <typename T>
-__global__ __launch_bounds__(256) void colsum_stage1(const T* __restrict__ a, long lda, int R, int n,
-                                                     float* __restrict__ partial) {
+__global__ __launch_bounds__(256) void colsum_stage1(ColsumArgs q, int R, int n, float* __restrict__ partial) {
   __shared__ float red[4][64];
+  const int z = blockIdx.z;
+  if (!q.out[z]) return;
+  const T* __restrict__ a = (const T*)q.a[z];
+  const long lda = q.lda[z];
   const int tx = threadIdx.x & 63, g = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + tx;
   const int r0 = blockIdx.y * CS_ROWS, r1 = min(R, r0 + CS_ROWS);
@@ -370,29 +379,45 @@ __global__ __launch_bounds__(256) void colsum_stage1(const T* __restrict__ a, lo
   }
   red[g][tx] = (s0 + s1) + (s2 + s3);
   __syncthreads();
-  if (g == 0 && c < n) partial[(long)blockIdx.y * n + c] = (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]);
+  if (g == 0 && c < n)
+    partial[((long)z * gridDim.y + blockIdx.y) * n + c] = (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]);
 }
-__global__ __launch_bounds__(256) void colsum_stage2(const float* __restrict__ partial, int nblk, int n,
-                                                     float* __restrict__ out) {
+__global__ __launch_bounds__(256) void colsum_stage2(const float* __restrict__ partial, int nblk, int n, ColsumArgs q) {
   __shared__ float red[4][64];
+  const int z = blockIdx.z;
+  if (!q.out[z]) return;
   const int tx = threadIdx.x & 63, g = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + tx;
   float s = 0.f;
   if (c < n)
-    for (int b = g; b < nblk; b += 4) s += partial[(long)b * n + c];
+    for (int b = g; b < nblk; b += 4) s += partial[((long)z * nblk + b) * n + c];
   red[g][tx] = s;
   __syncthreads();
-  if (g == 0 && c < n) out[c] = (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]);
+  if (g == 0 && c < n) q.out[z][c] = (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]);
 }
+// bytes of `partial` for ONE matrix; launch_colsum_multi needs count times as much
 size_t colsum_partial_bytes(int R, int n) { return (size_t)((R + CS_ROWS - 1) / CS_ROWS) * n * sizeof(float); }
 
-int launch_colsum(const void* a, long lda, int R, int n, int a_bf16, float* out, float* partial, hipStream_t st) {
+int launch_colsum_multi(const void* const* a, const long* lda, float* const* out, int count, int R, int n, int a_bf16,
+                        float* partial, hipStream_t st) {
+  ColsumArgs q;
+  bool any = false;
+  for (int i = 0; i < 3; ++i) {
+    q.a[i] = i < count ? a[i] : nullptr;
+    q.lda[i] = i < count ? lda[i] : 0;
+    q.out[i] = i < count ? out[i] : nullptr;
+    any = any || q.out[i];
+  }
+  if (!any) return IM_OK;
   const int nblk = (R + CS_ROWS - 1) / CS_ROWS;
-  dim3 grid((n + 63) / 64, nblk), block(256);
-  if (a_bf16) hipLaunchKernelGGL((colsum_stage1<bf16_t>), grid, block, 0, st, (const bf16_t*)a, lda, R, n, partial);
-  else hipLaunchKernelGGL((colsum_stage1<float>), grid, block, 0, st, (const float*)a, lda, R, n, partial);
-  hipLaunchKernelGGL(colsum_stage2, dim3((n + 63) / 64), dim3(256), 0, st, partial, nblk, n, out);
+  dim3 grid((n + 63) / 64, nblk, count), block(256);
+  if (a_bf16) hipLaunchKernelGGL((colsum_stage1<bf16_t>), grid, block, 0, st, q, R, n, partial);
+  else hipLaunchKernelGGL((colsum_stage1<float>), grid, block, 0, st, q, R, n, partial);
+  hipLaunchKernelGGL(colsum_stage2, dim3((n + 63) / 64, 1, count), dim3(256), 0, st, partial, nblk, n, q);
   return IM_OK;
+}
+int launch_colsum(const void* a, long lda, int R, int n, int a_bf16, float* out, float* partial, hipStream_t st) {
+  return launch_colsum_multi(&a, &lda, &out, 1, R, n, a_bf16, partial, st);
 }
 
 // ---- LayerNorm over the feature axis: one wavefront per row, two-pass (mean, then variance) in fp32 ----

@@ -40,7 +40,7 @@ static BwdWs bwd_ws(const im_shape_t* s) {
   w.split_o = mfma_gemm_split((int)x.d, (int)x.d, (int)x.R);
   w.partial = off;
   off += al(std::max((size_t)w.split_w * x.d * 3 * x.d, (size_t)w.split_o * x.d * x.d) * 4);
-  w.cpart = off; off += al(colsum_partial_bytes((int)x.R, (int)x.d));
+  w.cpart = off; off += al(3 * colsum_partial_bytes((int)x.R, (int)x.d));   // dbq, dbk, dbv in one launch
   w.total = off;
   return w;
 }
@@ -193,9 +193,13 @@ int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const
     launch_mfma_gemm(p, st);
     launch_splitk_reduce(partial, w.split_w, d, 3 * d, (float*)dwq, (float*)dwk, (float*)dwv, d, st);
   }
-  void* dbs[3] = {dbq, dbk, dbv};
-  for (int i = 0; i < 3; ++i)
-    if (dbs[i]) { ProfScope ps(PF_WGRAD, st); launch_colsum(dqkv + (size_t)i * d, 3 * d, R, d, 1, (float*)dbs[i], cpart, st); }
+  if (dbq || dbk || dbv) {  // column sums of the dQ | dK | dV column blocks
+    const void* src[3] = {dqkv, dqkv + d, dqkv + 2 * (size_t)d};
+    const long lds3[3] = {3 * (long)d, 3 * (long)d, 3 * (long)d};
+    float* dbs[3] = {(float*)dbq, (float*)dbk, (float*)dbv};
+    ProfScope ps(PF_WGRAD, st);
+    launch_colsum_multi(src, lds3, dbs, 3, R, d, 1, cpart, st);
+  }
 
   if (dx) {
     // dx = dQ Wq^T + dK Wk^T + dV Wv^T : K = 3d split over the three weights, each m-major as stored
