@@ -487,6 +487,39 @@ __global__ void mfma_splitk_reduce_kernel(const float* partial, int split_k, int
   }
 }
 
+// The same for small outputs: with few output quads the kernel above is a handful of workgroups whose
+// threads each walk through split_k dependent-latency loads.  Here a block is 16 quads x 16 lanes over
+// z: lane zl sums z = zl, zl + 16, ... in ascending order, then the 16 lane sums are added in a fixed
+// order through LDS (deterministic; the grouping differs from the kernel above, which is why a shape
+// always takes the same one of the two).
+__global__ __launch_bounds__(256) void mfma_splitk_reduce_par_kernel(const float* partial, int split_k, int M, int N,
+                                                                     float* o0, float* o1, float* o2, int n_per) {
+  __shared__ float4 red[16][16];
+  const long n_out = (long)M * N;
+  const int ql = threadIdx.x & 15, zl = threadIdx.x >> 4;
+  const long i = ((long)blockIdx.x * 16 + ql) * 4;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i < n_out)
+    for (int z = zl; z < split_k; z += 16) {
+      const float4 v = *(const float4*)(partial + z * n_out + i);
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+  red[zl][ql] = s;
+  __syncthreads();
+  if (zl != 0 || i >= n_out) return;
+  for (int k = 1; k < 16; ++k) {
+    const float4 v = red[k][ql];
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  const int m = i / N, n = i % N;
+  if (n_per > 0) {
+    float* o = (n / n_per == 0) ? o0 : (n / n_per == 1) ? o1 : o2;
+    if (o) *(float4*)(o + (long)m * n_per + n % n_per) = s;
+  } else {
+    *(float4*)(o0 + i) = s;
+  }
+}
+
 // Which kernel (measured on MI355X, C5 shapes):
 //  - weight gradients (both operands k-major, long contraction over token rows): the asynchronous
 //    256 x 256 kernel is 1.5x faster than the 128 x 128 kernel;
@@ -550,8 +583,12 @@ void launch_mfma_gemm(const MGemm& p, hipStream_t st) {
 void launch_splitk_reduce(const float* partial, int split_k, int M, int N, float* o0, float* o1, float* o2, int n_per,
                           hipStream_t st) {
   const long quads = ((long)M * N + 3) / 4;
-  hipLaunchKernelGGL(mfma_splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, partial, split_k,
-                     M, N, o0, o1, o2, n_per);
+  if (quads <= 65536 && split_k >= 8)   // small output, long reduction: parallel over z as well
+    hipLaunchKernelGGL(mfma_splitk_reduce_par_kernel, dim3((unsigned)((quads + 15) / 16)), dim3(256), 0, st, partial,
+                       split_k, M, N, o0, o1, o2, n_per);
+  else
+    hipLaunchKernelGGL(mfma_splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, partial, split_k,
+                       M, N, o0, o1, o2, n_per);
 }
 
 }  // namespace imattn
