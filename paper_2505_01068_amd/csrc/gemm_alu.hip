@@ -347,8 +347,8 @@ int launch_wgrad_small(const void* A, long lda, const void* G, long ldg, int R, 
 // Column sums of up to three [R, n] matrices in two deterministic stages (one launch each for all of
 // them: blockIdx.z selects the matrix).  Stage 1: a block of 256 threads = 4 row groups x 64 columns
 // sums CS_ROWS rows (thread (g, c): rows r0 + g, r0 + g + 4, ..., with four independent running sums so
-// loads overlap), then the 4 groups are added in a fixed order through LDS.  Stage 2 does the same
-// over the per-block partials ([matrix][row block][n]).
+// loads overlap), then the 4 groups are added in a fixed order through LDS.  Stage 2 adds the
+// per-block partials ([matrix][row block][n]) the same way with 16 groups x 16 columns.
 constexpr int CS_ROWS = 256;
 struct ColsumArgs {
   const void* a[3];
@@ -383,17 +383,21 @@ __global__ __launch_bounds__(256) void colsum_stage1(ColsumArgs q, int R, int n,
     partial[((long)z * gridDim.y + blockIdx.y) * n + c] = (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]);
 }
 __global__ __launch_bounds__(256) void colsum_stage2(const float* __restrict__ partial, int nblk, int n, ColsumArgs q) {
-  __shared__ float red[4][64];
+  // 16 groups x 16 columns: group g adds row blocks g, g + 16, ... in ascending order, then the 16 group sums are
+  // added in a fixed order (a block of 4 groups x 64 columns left one workgroup walking through all the partials)
+  __shared__ float red[16][16];
   const int z = blockIdx.z;
   if (!q.out[z]) return;
-  const int tx = threadIdx.x & 63, g = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + tx;
+  const int tx = threadIdx.x & 15, g = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + tx;
   float s = 0.f;
   if (c < n)
-    for (int b = g; b < nblk; b += 4) s += partial[((long)z * nblk + b) * n + c];
+    for (int b = g; b < nblk; b += 16) s += partial[((long)z * nblk + b) * n + c];
   red[g][tx] = s;
   __syncthreads();
-  if (g == 0 && c < n) q.out[z][c] = (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]);
+  if (g != 0 || c >= n) return;
+  for (int k = 1; k < 16; ++k) s += red[k][tx];
+  q.out[z][c] = s;
 }
 // bytes of `partial` for ONE matrix; launch_colsum_multi needs count times as much
 size_t colsum_partial_bytes(int R, int n) { return (size_t)((R + CS_ROWS - 1) / CS_ROWS) * n * sizeof(float); }
@@ -413,7 +417,7 @@ int launch_colsum_multi(const void* const* a, const long* lda, float* const* out
   dim3 grid((n + 63) / 64, nblk, count), block(256);
   if (a_bf16) hipLaunchKernelGGL((colsum_stage1<bf16_t>), grid, block, 0, st, q, R, n, partial);
   else hipLaunchKernelGGL((colsum_stage1<float>), grid, block, 0, st, q, R, n, partial);
-  hipLaunchKernelGGL(colsum_stage2, dim3((n + 63) / 64, 1, count), dim3(256), 0, st, partial, nblk, n, q);
+  hipLaunchKernelGGL(colsum_stage2, dim3((n + 15) / 16, 1, count), dim3(256), 0, st, partial, nblk, n, q);
   return IM_OK;
 }
 int launch_colsum(const void* a, long lda, int R, int n, int a_bf16, float* out, float* partial, hipStream_t st) {
