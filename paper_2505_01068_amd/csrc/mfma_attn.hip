@@ -757,8 +757,11 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
 }
 
 // ---- host launchers ----
-constexpr int FWD_QB = 2, DQ_QB = 1, DKV_KB = 1;
-int mfma_fwd_tile_rows() { return 128 * FWD_QB; }
+// Query blocks per wave in the forward: 1 at head dim 64 (about 130 registers, three workgroups per CU: measured
+// 6 % faster than 2 blocks per wave at two workgroups per CU), 2 in sub-head mode (half the K/V tile traffic per
+// score; measured 2 % faster there).
+constexpr int FWD_QB = 1, FWD_QB_SUB = 2, DQ_QB = 1, DKV_KB = 1;
+int mfma_fwd_tile_rows(int dh) { return 128 * (dh == 64 ? FWD_QB : FWD_QB_SUB); }
 int mfma_dq_tile_rows() { return 128 * DQ_QB; }
 int mfma_dkv_tile_rows() { return 128 * DKV_KB; }
 
@@ -775,8 +778,8 @@ void launch_mfma_fwd(const Geo& g, const bf16_t* qkv, long ld, const int32_t* va
   ProfScope ps(PF_ATTN_FWD, st);
   const dim3 grid(nt, g.H, g.B);
   if (g.dh == 64) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB, 64>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
-  else if (g.dh == 16) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB, 16>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
-  else hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB, 8>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  else if (g.dh == 16) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 16>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  else hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 8>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
 }
 
 void launch_mfma_bwd(const Geo& g, const bf16_t* qkv, long ld, const bf16_t* o, const bf16_t* d_o, long ldo,

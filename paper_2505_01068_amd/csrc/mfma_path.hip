@@ -98,7 +98,7 @@ int mfma_attention_fwd(const im_shape_t* s, const void* x, const void* wq, const
                        const int32_t* valid_len, const uint8_t* key_pad, void* y, const void* res, char* sv,
                        size_t off_qkv, size_t off_o, size_t off_lse, size_t, char*, hipStream_t st) {
   Geo g;
-  build_geo(s, mfma_fwd_tile_rows(), mfma_dkv_tile_rows(), &g);
+  build_geo(s, mfma_fwd_tile_rows(s->d_model / s->n_heads), mfma_dkv_tile_rows(), &g);
   const Dims dm = dims(s);
   const int d = (int)dm.d;
   bf16_t* qkv = (bf16_t*)(sv + off_qkv);
