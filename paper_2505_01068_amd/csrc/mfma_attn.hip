@@ -547,7 +547,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
 __device__ const float k_pos_inf = __builtin_inff();
 
 template <int KB, int DH>
-__global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
+__global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void mfma_dkv_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
                                                        const bf16_t* __restrict__ dO, long ldo,
                                                        const float* __restrict__ lse2, const float* __restrict__ delta,
                                                        const int32_t* __restrict__ valid_len,
@@ -680,19 +680,20 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
     cursor_step(cc, qlen_of);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-      // per-register lse / delta of the query rows this lane half holds
-      float L[16], D[16];
-#pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        const float4 l0 = *(const float4*)&sL[qb * 32 + half * 16 + hi * 8], l1 = *(const float4*)&sL[qb * 32 + half * 16 + hi * 8 + 4];
-        const float4 d0 = *(const float4*)&sD[qb * 32 + half * 16 + hi * 8], d1 = *(const float4*)&sD[qb * 32 + half * 16 + hi * 8 + 4];
-        L[half * 8 + 0] = l0.x; L[half * 8 + 1] = l0.y; L[half * 8 + 2] = l0.z; L[half * 8 + 3] = l0.w;
-        L[half * 8 + 4] = l1.x; L[half * 8 + 5] = l1.y; L[half * 8 + 6] = l1.z; L[half * 8 + 7] = l1.w;
-        D[half * 8 + 0] = d0.x; D[half * 8 + 1] = d0.y; D[half * 8 + 2] = d0.z; D[half * 8 + 3] = d0.w;
-        D[half * 8 + 4] = d1.x; D[half * 8 + 5] = d1.y; D[half * 8 + 6] = d1.z; D[half * 8 + 7] = d1.w;
-      }
+      // lse / delta of the query rows of the block: register r of an accumulator holds row
+      // (r / 8) * 16 + hi * 8 + r % 8.  delta goes straight into the dP accumulator (head dim 64: the buffer
+      // holds -delta), lse is fetched four rows at a time where it is used.
+      auto rows4 = [&](const float* base, int r4) {   // values of registers 4 r4 .. 4 r4 + 3
+        return *(const float4*)&base[qb * 32 + (r4 >> 1) * 16 + hi * 8 + (r4 & 1) * 4];
+      };
       bf16x8 pb[KB][2], dsb[KB][2];
       f32x16 sacc[KB], pacc[KB];
+      float D[16];
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const float4 d4 = rows4(sD, r4);
+        D[4 * r4] = d4.x; D[4 * r4 + 1] = d4.y; D[4 * r4 + 2] = d4.z; D[4 * r4 + 3] = d4.w;
+      }
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -711,9 +712,15 @@ __global__ __launch_bounds__(256, 2) void mfma_dkv_kernel(Geo g, const bf16_t* _
       for (int kb = 0; kb < KB; ++kb) {
         float p[16], ds[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          p[r] = fast_exp2(fmaf(sacc[kb][r], c, -L[r]));
-          ds[r] = DH == 64 ? p[r] * pacc[kb][r] : p[r] * (pacc[kb][r] - D[r]);
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const float4 l4 = rows4(sL, r4);
+          const float L[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int r = 4 * r4 + u;
+            p[r] = fast_exp2(fmaf(sacc[kb][r], c, -L[u]));
+            ds[r] = DH == 64 ? p[r] * pacc[kb][r] : p[r] * (pacc[kb][r] - D[r]);
+          }
         }
         pb[kb][0] = pack8(p); pb[kb][1] = pack8(p + 8);
         dsb[kb][0] = pack8(ds); dsb[kb][1] = pack8(ds + 8);
