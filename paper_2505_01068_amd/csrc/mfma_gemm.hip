@@ -221,10 +221,14 @@ __global__ __launch_bounds__(256, 3) void mfma_gemm_kernel(MGemm p) {  // three 
 //
 // The 128 x 128 kernel above is bound by bytes in flight, not by the matrix cores: one
 // register-staged k-tile per workgroup covers well under the L2/HBM round trip.  Here the
-// tile is 256 x 256 (4 waves, each 128 x 128 = 4 x 4 MFMA blocks, 256 accumulator registers), a
-// quarter of the operand traffic per flop, and operands go straight from global memory into a
-// ring of four 32-deep LDS stages with global_load_lds_dwordx4 (no staging registers), three
-// stages in flight while one is multiplied, one barrier per stage.
+// tile is 256 x 256, a quarter of the operand traffic per flop, and operands go straight from
+// global memory into a ring of four 32-deep LDS stages with global_load_lds_dwordx4 (no staging
+// registers), three stages in flight while one is multiplied, one barrier per stage.
+// 8 waves, each 128 x 64 = 4 x 2 MFMA blocks (128 accumulator registers, two waves per SIMD).  The
+// first version had 4 waves of 128 x 128 (256 accumulator registers, ONE wave per SIMD): a wave alone
+// on a SIMD issues vector instructions at half rate and nothing overlaps its LDS waits, its prologue
+// or its epilogue -- with 8 waves the QKV + output projections take 0.129 instead of 0.157 ms and the
+// weight gradients 0.122 instead of 0.129 ms, although every MFMA now needs 1.5x the LDS fragment reads.
 //
 // A direct load writes lane i's 16 bytes at (wave-uniform LDS base) + 16 i, so rows cannot be
 // padded; bank conflicts are avoided by XOR-swizzling the 16-byte chunk index instead:
@@ -239,12 +243,17 @@ constexpr int DMA_LDS_BYTES = DSTAGES * DMA_STAGE_BYTES;      // 128 KB
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef const __attribute__((address_space(1))) void* glb_void_ptr;
 
-template <bool AKM, bool BKM, bool EPI>
-__global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
+// NWV waves per workgroup: 8 (each wave 128 x 64, two waves per SIMD) or 4 (each wave 128 x 128, one wave per SIMD).
+template <bool AKM, bool BKM, bool EPI, int NWV>
+__global__ __launch_bounds__(NWV * 64) void mfma_gemm_dma_kernel(MGemm p) {
   extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
+  constexpr int NWN = NWV / 2;          // wave grid: 2 (rows) x NWN (columns)
+  constexpr int WCOLS = DN / NWN;       // columns of a wave's sub-tile: 128 or 64
+  constexpr int NBN = WCOLS / 32;       // 32-column blocks per wave: 4 or 2
+  constexpr int CH = 1024 / (NWV * 64); // 16-byte chunks per thread, operand and stage: 4 or 2
   const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / NWN, wn = wave % NWN;
   int bx, by, bz;
   xcd_block_index(bx, by, bz);
   const int m0 = by * DM, n0 = bx * DN;
@@ -254,14 +263,14 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
   const int it_begin = bz * per_split, it_end = min(ktiles, it_begin + per_split);
   const int n_it = max(0, it_end - it_begin);
 
-  // ---- per-thread source pointers of the 4 + 4 chunks it fetches per stage (advanced by DK per stage) ----
-  const bf16_t* ga[4];
-  const bf16_t* gb[4];   // k-major B: source pointer; m-major B: only the offset inside one matrix is used
-  long gboff[4];
+  // ---- per-thread source pointers of the CH + CH chunks it fetches per stage (advanced by DK per stage) ----
+  const bf16_t* ga[CH];
+  const bf16_t* gb[CH];   // k-major B: source pointer; m-major B: only the offset inside one matrix is used
+  long gboff[CH];
   long a_step, b_step;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int slot = (wave * 4 + j) * 64 + lane;  // chunk slot inside the 1024-chunk tile
+  for (int j = 0; j < CH; ++j) {
+    const int slot = (wave * CH + j) * 64 + lane;  // chunk slot inside the 1024-chunk tile
     if (AKM) {
       const int k = slot >> 5, pos = slot & 31, c = pos ^ ((k & 3) << 2);
       const int col = min(m0 + c * 8, p.M - 8);
@@ -290,12 +299,12 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
   auto issue = [&](int it_rel) {  // fetch stage it_rel (relative to it_begin) into ring slot it_rel % DSTAGES
     char* base = (char*)smem + (it_rel % DSTAGES) * DMA_STAGE_BYTES;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < CH; ++j) {
       const bf16_t* src = ga[j] + (long)it_rel * a_step;
-      dma16(src, base + (wave * 4 + j) * 1024);
+      dma16(src, base + (wave * CH + j) * 1024);
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < CH; ++j) {
       const bf16_t* src;
       if (BKM) {
         src = gb[j] + (long)it_rel * b_step;
@@ -306,19 +315,19 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
         if (p.b_kper > 0) { mat = p.B[k0 / p.b_kper]; kk = k0 % p.b_kper; }
         src = mat + gboff[j] + kk;
       }
-      dma16(src, base + DM * DK * 2 + (wave * 4 + j) * 1024);
+      dma16(src, base + DM * DK * 2 + (wave * CH + j) * 1024);
     }
   };
 
   // [n block][m block]; registers 4i..4i+3 are columns n = 8i + 4hi + 0..3 of the block.  The
   // accumulators start at the bias of their column (split-K launches carry no bias).
-  f32x16 acc[4][4];
+  f32x16 acc[NBN][4];
 #pragma unroll
-  for (int nb = 0; nb < 4; ++nb)
+  for (int nb = 0; nb < NBN; ++nb)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       float bv[4] = {0.f, 0.f, 0.f, 0.f};
-      if (!p.partial) bias4(p, n0 + wn * 128 + nb * 32 + 8 * i + 4 * hi, bv);
+      if (!p.partial) bias4(p, n0 + wn * WCOLS + nb * 32 + 8 * i + 4 * hi, bv);
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
@@ -326,8 +335,8 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
     }
 
   // ---- LDS byte offsets of this lane's fragments inside a stage ----
-  int offA[2][4], offB[2][4];   // [k-step][block]; for k-major operands the second transpose read is +4 rows
-  int offA2[2][4], offB2[2][4];
+  int offA[2][4], offB[2][NBN];   // [k-step][block]; for k-major operands the second transpose read is +4 rows
+  int offA2[2][4], offB2[2][NBN];
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -342,15 +351,17 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
         offA[ks][x] = (row * 4 + (kc ^ ((row >> 2) & 3))) * 16;
         offA2[ks][x] = 0;
       }
-      if (BKM) {
-        const int j = lane & 15, gq = lane >> 4;
-        const int kr = ks * 16 + 8 * (gq >> 1) + (j >> 2), col = wn * 128 + x * 32 + 16 * (gq & 1) + 4 * (j & 3);
-        offB[ks][x] = DM * DK * 2 + (kr * 32 + ((col >> 3) ^ ((kr & 3) << 2))) * 16 + (col & 7) * 2;
-        offB2[ks][x] = DM * DK * 2 + ((kr + 4) * 32 + ((col >> 3) ^ (((kr + 4) & 3) << 2))) * 16 + (col & 7) * 2;
-      } else {
-        const int row = wn * 128 + x * 32 + lo, kc = ks * 2 + hi;
-        offB[ks][x] = DM * DK * 2 + (row * 4 + (kc ^ ((row >> 2) & 3))) * 16;
-        offB2[ks][x] = 0;
+      if (x < NBN) {
+        if (BKM) {
+          const int j = lane & 15, gq = lane >> 4;
+          const int kr = ks * 16 + 8 * (gq >> 1) + (j >> 2), col = wn * WCOLS + x * 32 + 16 * (gq & 1) + 4 * (j & 3);
+          offB[ks][x] = DM * DK * 2 + (kr * 32 + ((col >> 3) ^ ((kr & 3) << 2))) * 16 + (col & 7) * 2;
+          offB2[ks][x] = DM * DK * 2 + ((kr + 4) * 32 + ((col >> 3) ^ (((kr + 4) & 3) << 2))) * 16 + (col & 7) * 2;
+        } else {
+          const int row = wn * WCOLS + x * 32 + lo, kc = ks * 2 + hi;
+          offB[ks][x] = DM * DK * 2 + (row * 4 + (kc ^ ((row >> 2) & 3))) * 16;
+          offB2[ks][x] = 0;
+        }
       }
     }
   auto frag = [&](const char* st, int o1, int o2, bool km) -> bf16x8 {
@@ -369,24 +380,29 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
   for (int it = 0; it < n_it; ++it) {
     // this lane's loads of stage `it` have landed when at most the loads of the later stages remain
     const int later = min(DSTAGES - 2, n_it - 1 - it);
-    // (8 loads per thread and stage).  A bare s_barrier is used: __syncthreads() would also drain vmcnt.
-    if (later >= 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    else if (later == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // (2 CH loads per thread and stage).  A bare s_barrier is used: __syncthreads() would also drain vmcnt.
+    if (NWV == 4) {
+      if (later >= 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+      else if (later == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
+      if (later >= 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      else if (later == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     if (it + DSTAGES - 1 < n_it) issue(it + DSTAGES - 1);
     const char* st = (const char*)smem + (it % DSTAGES) * DMA_STAGE_BYTES;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      bf16x8 fa[4], fb[4];
+      bf16x8 fa[4], fb[NBN];
 #pragma unroll
-      for (int x = 0; x < 4; ++x) {
-        fa[x] = frag(st, offA[ks][x], offA2[ks][x], AKM);
-        fb[x] = frag(st, offB[ks][x], offB2[ks][x], BKM);
-      }
+      for (int x = 0; x < 4; ++x) fa[x] = frag(st, offA[ks][x], offA2[ks][x], AKM);
 #pragma unroll
-      for (int nb = 0; nb < 4; ++nb)
+      for (int x = 0; x < NBN; ++x) fb[x] = frag(st, offB[ks][x], offB2[ks][x], BKM);
+#pragma unroll
+      for (int nb = 0; nb < NBN; ++nb)
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) acc[nb][mb] = mfma32(fb[nb], fa[mb], acc[nb][mb]);
     }
@@ -399,10 +415,10 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
       const int m = m0 + wm * 128 + mb * 32 + lo;
       if (m >= p.M) continue;
 #pragma unroll
-      for (int nb = 0; nb < 4; ++nb)
+      for (int nb = 0; nb < NBN; ++nb)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const int n = n0 + wn * 128 + nb * 32 + 8 * i + 4 * hi;
+          const int n = n0 + wn * WCOLS + nb * 32 + 8 * i + 4 * hi;
           if (n >= p.N) continue;
           *(float4*)(p.partial + ((long)bz * p.M + m) * p.N + n) =
               make_float4(acc[nb][mb][4 * i], acc[nb][mb][4 * i + 1], acc[nb][mb][4 * i + 2], acc[nb][mb][4 * i + 3]);
@@ -411,13 +427,14 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
     return;
   }
   // bf16 output: a lane owns a ROW of the accumulator tile (8 bytes per register quad), which would
-  // make every store touch 64 different cache lines.  The wave's 128 x 128 tile therefore goes through
-  // its own quarter of the (now idle) stage ring, 64 rows at a time, and leaves as 16-byte stores in
-  // which 16 consecutive lanes cover one 256-byte row segment.
+  // make every store touch 64 different cache lines.  The wave's 128 x WCOLS tile therefore goes through
+  // its own share of the (now idle) stage ring, 64 rows at a time, and leaves as 16-byte stores in
+  // which WCOLS / 8 consecutive lanes cover one row segment of 2 WCOLS bytes.
   __builtin_amdgcn_s_barrier();  // every wave has finished reading the last stage
   asm volatile("" ::: "memory");
-  constexpr int EP_LD = 136;     // bf16 per staged row (128 + 8 pad)
-  bf16_t* stg = smem + wave * (DMA_LDS_BYTES / 8);
+  constexpr int EP_LD = WCOLS + 8;   // bf16 per staged row
+  static_assert(64 * EP_LD * 2 <= DMA_LDS_BYTES / NWV, "a wave's staging area must fit in its share of the ring");
+  bf16_t* stg = smem + wave * (DMA_LDS_BYTES / 2 / NWV);
   // a tile inside the matrix stores without bounds checks
   const bool interior = m0 + DM <= p.M && n0 + DN <= p.N;
 #pragma unroll
@@ -427,11 +444,11 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
       const int mb = half * 2 + mq;
       const int m = m0 + wm * 128 + mb * 32 + lo;
 #pragma unroll
-      for (int nb = 0; nb < 4; ++nb)
+      for (int nb = 0; nb < NBN; ++nb)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int nl = nb * 32 + 8 * i + 4 * hi;
-          const int n = n0 + wn * 128 + nl;
+          const int n = n0 + wn * WCOLS + nl;
           float v[4];
 #pragma unroll
           for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j];
@@ -450,18 +467,20 @@ __global__ __launch_bounds__(256) void mfma_gemm_dma_kernel(MGemm p) {
           *(u32x2*)(stg + (mq * 32 + lo) * EP_LD + nl) = pk;
         }
     }
-    // 64 rows x 16 chunks of 16 bytes; lane -> (row = 4 t + lane / 16, chunk = lane % 16)
-    const int row0 = lane >> 4, ch = lane & 15;
-    const int mrow = m0 + wm * 128 + half * 64 + row0, n = n0 + wn * 128 + ch * 8;
+    // 64 rows x CPR chunks of 16 bytes; lane -> (row = RPP t + lane / CPR, chunk = lane % CPR)
+    constexpr int CPR = WCOLS / 8, RPP = 64 / CPR, NT = 64 / RPP;
+    const int row0 = lane / CPR, ch = lane % CPR;
+    const int mrow = m0 + wm * 128 + half * 64 + row0, n = n0 + wn * WCOLS + ch * 8;
     bf16_t* cp = p.C + (long)mrow * p.ldc + n;
     const bf16_t* sp = stg + row0 * EP_LD + ch * 8;
     if (interior) {
 #pragma unroll
-      for (int t = 0; t < 16; ++t) *(u32x4*)(cp + (long)(4 * t) * p.ldc) = *(const u32x4*)(sp + 4 * t * EP_LD);
+      for (int t = 0; t < NT; ++t) *(u32x4*)(cp + (long)(RPP * t) * p.ldc) = *(const u32x4*)(sp + RPP * t * EP_LD);
     } else {
 #pragma unroll
-      for (int t = 0; t < 16; ++t)   // N is a multiple of 8 on this path
-        if (mrow + 4 * t < p.M && n < p.N) *(u32x4*)(cp + (long)(4 * t) * p.ldc) = *(const u32x4*)(sp + 4 * t * EP_LD);
+      for (int t = 0; t < NT; ++t)   // N is a multiple of 8 on this path
+        if (mrow + RPP * t < p.M && n < p.N)
+          *(u32x4*)(cp + (long)(RPP * t) * p.ldc) = *(const u32x4*)(sp + RPP * t * EP_LD);
     }
   }
 }
@@ -525,7 +544,8 @@ __global__ __launch_bounds__(256) void mfma_splitk_reduce_par_kernel(const float
 //    256 x 256 kernel is 1.5x faster than the 128 x 128 kernel;
 //  - projections with row-major activations and k-major weights (QKV, output projection; K = d):
 //    the 256 x 256 kernel needs half the L1 traffic per flop and wins by 1.2-1.35x;
-//  - both operands row-major (dO, dx): the 128 x 128 kernel with three workgroups per CU wins.
+//  - both operands row-major (dO, dx): the 128 x 128 kernel with three workgroups per CU wins (also against
+//    the large-tile kernel with 8 waves: 0.122 vs 0.142 ms for the two GEMMs).
 static bool use_dma(int M, int N, int K, bool akm = true, bool bkm = true) {
   if (!(bkm && M >= DM && N >= DN && K % DK == 0 && M % 8 == 0 && N % 8 == 0)) return false;
   return akm ? K >= 64 * DK : K >= 8 * DK;
@@ -549,16 +569,17 @@ int mfma_gemm_split(int M, int N, int K) {
   return s < 1 ? 1 : s;
 }
 
+constexpr int DMA_WAVES = 8;   // waves per workgroup of the large-tile kernel
 template <bool AKM, bool BKM, bool EPI>
 static void launch_dma(const MGemm& p, hipStream_t st) {
   static bool configured = false;  // raise the dynamic-LDS limit once per instantiation (128 KB > the 64 KB default)
   if (!configured) {
-    (void)hipFuncSetAttribute((const void*)mfma_gemm_dma_kernel<AKM, BKM, EPI>,
+    (void)hipFuncSetAttribute((const void*)mfma_gemm_dma_kernel<AKM, BKM, EPI, DMA_WAVES>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, DMA_LDS_BYTES);
     configured = true;
   }
   dim3 grid((p.N + DN - 1) / DN, (p.M + DM - 1) / DM, p.split_k);
-  hipLaunchKernelGGL((mfma_gemm_dma_kernel<AKM, BKM, EPI>), grid, dim3(256), DMA_LDS_BYTES, st, p);
+  hipLaunchKernelGGL((mfma_gemm_dma_kernel<AKM, BKM, EPI, DMA_WAVES>), grid, dim3(DMA_WAVES * 64), DMA_LDS_BYTES, st, p);
 }
 template <bool AKM, bool BKM>
 static void launch_layout(const MGemm& p, bool dma, hipStream_t st) {
