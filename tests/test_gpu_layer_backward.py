@@ -104,3 +104,14 @@ def test_layer_backward_bitwise_reproducible():
     assert torch.equal(a[2], b[2])
     for n in a[3]:
         assert torch.equal(a[3][n], b[3][n]), n
+
+
+def test_layer_backward_bf16_wide_model_large_tile_epilogues():
+    # d = 256, d_ff = 512: the projections and both MLP GEMMs run on the 256 x 256 large-tile kernel, including its
+    # GELU and residual epilogues; 1136 rows = 4 row tiles + a ragged one
+    say("[case] layer fwd+bwd bf16 d=256 (large-tile GEMM with GELU / residual epilogues)")
+    d, H, d_ff, seg = 256, 4, 512, (72, 296, 200)
+    g = synth.attention_inputs(2, seg, d, H, "bf16", "valid_len", seed=506)
+    p = synth.layer_params(d, d_ff, 506, 0, dtype="bf16")
+    errs = check(g, p, oracle.IM_IFM_FORWARD, "bf16", d_ff, "layer-bwd/bf16/d256")
+    say("    " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
