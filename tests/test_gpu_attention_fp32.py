@@ -135,3 +135,27 @@ def test_pattern_variants_fwd_bwd(name):
     say(f"[case] pattern variant {name} fwd+bwd")
     g = synth.attention_inputs(2, (50, 200, 150), 40, 8, "fp32", "valid_len", seed=20250511, bias=True)
     Problem(g, oracle.NAMED_PATTERNS[name]).check(what=f"variant/{name}")
+
+
+@pytest.mark.parametrize("dtype,d,H", [("fp32", 40, 8), ("bf16", 128, 2)])
+def test_optional_gradient_outputs(dtype, d, H):
+    # every gradient output may be NULL; the ones that are asked for do not depend on which others are
+    say(f"[case] optional gradient outputs {dtype}")
+    from paper_2505_01068_amd import binding as B
+    g = synth.attention_inputs(2, (33, 140, 97), d, H, dtype, "valid_len", seed=77, bias=True)
+    p = Problem(g, oracle.IM_IFM_FORWARD)
+    p.fwd()
+    full = p.bwd()
+    t = p.t
+    f32 = dict(dtype=torch.float32, device="cuda")
+    dx = torch.empty_like(t["x"])
+    dwq, dwo = torch.empty(d, d, **f32), torch.empty(d, d, **f32)
+    dbq, dbv = torch.empty(d, **f32), torch.empty(d, **f32)
+    B.im_attention_bwd(p.shape, t["x"], t["wq"], t["wk"], t["wv"], t["wo"], p.saved, t["dy"], dx, dwq, None, None, dwo,
+                       dbq, None, dbv, None, t["valid_len"], t["key_pad"], workspace=p.ws)
+    torch.cuda.synchronize()
+    for name, v in (("dx", dx), ("dwq", dwq), ("dwo", dwo), ("dbq", dbq), ("dbv", dbv)):
+        assert torch.equal(v, full[name]), name
+    B.im_attention_bwd(p.shape, t["x"], t["wq"], t["wk"], t["wv"], t["wo"], p.saved, t["dy"], None, None, None, None, None,
+                       None, None, None, None, t["valid_len"], t["key_pad"], workspace=p.ws)   # nothing asked for
+    torch.cuda.synchronize()
