@@ -62,9 +62,10 @@ __global__ __launch_bounds__(NW * RL_ROWS) void rowlane_fwd_kernel(Geo g, const 
   constexpr int LP = lds_row(DH);
   __shared__ float sKV[NW][2][RL_CHUNK][LP];  // per wave: K rows, V rows of its chunk
   __shared__ float sBias[NW][RL_CHUNK];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = blockIdx.y, b = blockIdx.z;
-  int qs, q0;
-  decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, RL_ROWS, blockIdx.x, qs, q0);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int tile, h, b, qs, q0;
+  segment_major_index(g.q_tile_prefix, g.q_nord, g.cu != nullptr, tile, h, b);
+  decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, RL_ROWS, tile, qs, q0);
   const int qlen = seg_rows(g, b, qs);
   if (q0 >= qlen) return;  // packed rows: this batch element's segment ends before the tile
   const int row = q0 + lane;
@@ -179,9 +180,10 @@ __global__ __launch_bounds__(NW * RL_ROWS) void rowlane_dq_kernel(Geo g, const T
   constexpr int LP = lds_row(DH);
   __shared__ float sKV[NW][2][RL_CHUNK][LP];  // per wave: K rows, V rows of its chunk
   __shared__ float sBias[NW][RL_CHUNK];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = blockIdx.y, b = blockIdx.z;
-  int qs, q0;
-  decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, RL_ROWS, blockIdx.x, qs, q0);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int tile, h, b, qs, q0;
+  segment_major_index(g.q_tile_prefix, g.q_nord, g.cu != nullptr, tile, h, b);
+  decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, RL_ROWS, tile, qs, q0);
   const int qlen = seg_rows(g, b, qs);
   if (q0 >= qlen) return;  // packed rows: this batch element's segment ends before the tile
   const int row = q0 + lane;
@@ -281,9 +283,10 @@ __global__ __launch_bounds__(NW * RL_ROWS) void rowlane_dkv_kernel(Geo g, const 
   __shared__ float sQG[NW][2][RL_CHUNK][LP];  // per wave: Q rows, dO rows of its chunk
   __shared__ float sL[NW][RL_CHUNK];
   __shared__ float sD[NW][RL_CHUNK];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = blockIdx.y, b = blockIdx.z;
-  int ks, k0;
-  decode_tile(g.k_order, g.k_tile_prefix, g.k_nord, RL_ROWS, blockIdx.x, ks, k0);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int tile, h, b, ks, k0;
+  segment_major_index(g.k_tile_prefix, g.k_nord, g.cu != nullptr, tile, h, b);
+  decode_tile(g.k_order, g.k_tile_prefix, g.k_nord, RL_ROWS, tile, ks, k0);
   const int klen_seg = seg_rows(g, b, ks);
   if (k0 >= klen_seg) return;  // packed rows: this batch element's segment ends before the tile
   const int row = k0 + lane;

@@ -102,6 +102,44 @@ __device__ __forceinline__ void xcd_block_index(int& bx, int& by, int& bz) {
   by = (logical / gx) % gy;
   bz = logical / (gx * gy);
 }
+// q = n / d and r = n % d of workgroup indices.  Below 2^22 the quotient comes from a float
+// reciprocal (off by at most one, corrected), a quarter of the instructions of the exact 32-bit
+// division; workgroups that find nothing to do (packed rows) spend most of their time here.
+__device__ __forceinline__ void udivmod(unsigned n, unsigned d, unsigned& q, unsigned& r) {
+  if (n < (1u << 22)) {
+    q = (unsigned)((float)n * __builtin_amdgcn_rcpf((float)d));
+    r = n - q * d;
+    if ((int)r < 0) { --q; r += d; }
+    else if (r >= d) { ++q; r -= d; }
+  } else {
+    q = n / d;
+    r = n % d;
+  }
+}
+
+// Workgroup -> (tile, head, batch element) for a grid (tiles, heads, batch), segment-major: all
+// workgroups of the first segment of the tile order (the one with the most work per tile) come
+// first, for every (batch element, head) pair, then those of the next segment.  The workgroups
+// that run longest start first and the short ones fill the tail of the launch.  Inside a segment
+// the order is pair, then tile (the tiles of one pair read the same keys and start together) --
+// except with packed rows (tile_first), where the grid covers the longest sample and the later
+// tiles of most pairs find no rows: there tile, then pair, so the tiles that have work are not
+// queued behind the empty ones.
+__device__ __forceinline__ void segment_major_index(const int* prefix, int nord, bool tile_first, int& tile, int& h,
+                                                    int& b) {
+  const unsigned gx = gridDim.x, gy = gridDim.y, npair = gy * gridDim.z;
+  const unsigned lin = blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z);
+  int k = 0;
+  while (k + 1 < nord && lin >= npair * (unsigned)prefix[k + 1]) ++k;
+  const unsigned nt = (unsigned)(prefix[k + 1] - prefix[k]), j = lin - npair * (unsigned)prefix[k];
+  unsigned pair, t, hh, bb;
+  if (tile_first) udivmod(j, npair, t, pair);
+  else udivmod(j, nt, pair, t);
+  udivmod(pair, gy, bb, hh);
+  tile = prefix[k] + (int)t;
+  h = (int)hh;
+  b = (int)bb;
+}
 #endif
 
 // ---- launchers implemented in the .hip files (all enqueue on `st`, none syncs) ----

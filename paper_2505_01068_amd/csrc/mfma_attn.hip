@@ -25,6 +25,33 @@ namespace imattn {
 
 constexpr int KT = 64;  // keys (or query rows) per staged tile
 
+// Workgroup -> (tile, head, batch element).  As with xcd_block_index every XCD owns a contiguous
+// range of (batch element, head) pairs, but inside that range the workgroups are ordered by segment
+// first (the tile order lists the segments by decreasing work per tile), then pair, then tile.  A
+// workgroup of a long live range runs several times longer than one of a short range; started pair
+// by pair, the long workgroups of the last pairs begin late and the XCD drains with most of its CUs
+// idle.  Started first, they leave the short ones to fill the tail.  The plain order is kept when
+// the pairs do not divide evenly over the 8 XCDs.
+__device__ __forceinline__ void xcd_tile_index(const int* prefix, int nord, bool tile_first, int& tile, int& h, int& b) {
+  const unsigned gx = gridDim.x, gy = gridDim.y, npair = gy * gridDim.z;
+  if (npair & 7u) {
+    xcd_block_index(tile, h, b);
+    return;
+  }
+  const unsigned lin = blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z);
+  const unsigned xcd = lin & 7u, idx = lin >> 3, per = npair >> 3;  // pairs per XCD
+  int k = 0;
+  while (k + 1 < nord && idx >= per * (unsigned)prefix[k + 1]) ++k;
+  const unsigned nt = (unsigned)(prefix[k + 1] - prefix[k]), j = idx - per * (unsigned)prefix[k];
+  unsigned pl, t, hh, bb;
+  if (tile_first) udivmod(j, per, t, pl);  // packed rows: see segment_major_index
+  else udivmod(j, nt, pl, t);
+  udivmod(xcd * per + pl, gy, bb, hh);
+  tile = prefix[k] + (int)t;
+  h = (int)hh;
+  b = (int)bb;
+}
+
 // key-validity bit mask of one 64-key tile (bit k <=> key k0+k is a valid key)
 __device__ __forceinline__ unsigned long long tile_key_mask(const uint8_t* key_pad_row, int k0, int klen, int lane) {
   const int k = k0 + lane;
@@ -142,7 +169,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
   const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: branches on it are wave-uniform
   int tile, h, b;
-  xcd_block_index(tile, h, b);
+  xcd_tile_index(g.q_tile_prefix, g.q_nord, g.cu != nullptr, tile, h, b);
   constexpr int WG_ROWS = 128 * QB;
   int qs, q0;
   decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, WG_ROWS, tile, qs, q0);
@@ -355,7 +382,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
   const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: branches on it are wave-uniform
   int tile, h, b;
-  xcd_block_index(tile, h, b);
+  xcd_tile_index(g.q_tile_prefix, g.q_nord, g.cu != nullptr, tile, h, b);
   constexpr int WG_ROWS = 128 * QB;
   int qs, q0;
   decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, WG_ROWS, tile, qs, q0);
@@ -558,7 +585,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void mfma_dkv_kernel(Geo g, 
   const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: branches on it are wave-uniform
   int tile, h, b;
-  xcd_block_index(tile, h, b);
+  xcd_tile_index(g.k_tile_prefix, g.k_nord, g.cu != nullptr, tile, h, b);
   constexpr int WG_ROWS = 128 * KB;
   int ks, k0;
   decode_tile(g.k_order, g.k_tile_prefix, g.k_nord, WG_ROWS, tile, ks, k0);
