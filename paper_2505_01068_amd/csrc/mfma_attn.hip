@@ -15,6 +15,12 @@
 // read it with the gfx950 LDS transpose read (ds_read_b64_tr_b16), so no
 // transposed copy of any tensor exists in HBM.
 //
+// Conventions between the kernels: the Q rows arrive multiplied by scale * log2(e) (the QKV projection's
+// epilogue does it before its one rounding to bf16), so Q K^T is the score in the exponent domain of
+// exp2 and no kernel multiplies scores; the per-row statistic saved by the forward is the NEGATED
+// log2-sum-exp (-inf for a row without any valid key), which the backward kernels add to the score --
+// the dK/dV kernel by starting its score accumulator from it.
+//
 // Only live (query segment, key segment) blocks of the Interlaced Mask are
 // visited (Sec. 6 "Decomposition"); a row with several live segments carries
 // one running max / sum across all of them (Sec. 7.1).
@@ -176,7 +182,6 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
   const int qlen = useg_rows(g, b, qs);
   if (q0 >= qlen) return;  // packed rows: this batch element's segment ends before the tile
   const int d = g.d;
-  const float c = fmaxf(g.scale_log2e, 1e-30f);  // > 0 so that -inf * c stays -inf when scale == 0
 
   constexpr int NS = DH == 64 ? 4 : 1;    // k-steps of S^T
   constexpr int NDB = DH == 64 ? 2 : 1;   // 32-row blocks of O^T
@@ -214,7 +219,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
   }
 
   const int prow = perm32(lo);
-  const float tau = c > 0.f ? 8.f / c : __builtin_inff();
+  constexpr float tau = 8.f;  // scores are exponents of 2 (Q carries scale * log2(e))
   // The compiler does not see the asynchronous copies in its vmcnt bookkeeping: consuming the Q
   // registers here makes it wait for their (ordinary) loads now, not inside the ring loop.
 #pragma unroll
@@ -309,7 +314,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
         const bool upd = mx > m[qb] + tau;
         if (__any(upd)) {
           const float mn = upd ? mx : m[qb];
-          const float alpha = (m[qb] == IM_NEG_INF) ? 0.f : fast_exp2((m[qb] - mn) * c);
+          const float alpha = (m[qb] == IM_NEG_INF) ? 0.f : fast_exp2(m[qb] - mn);
           l[qb] *= alpha;
 #pragma unroll
           for (int db = 0; db < NDB; ++db)
@@ -317,14 +322,14 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
             for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
           m[qb] = mn;
         }
-        const float msc = (m[qb] == IM_NEG_INF) ? 0.f : m[qb] * c;
+        const float msc = (m[qb] == IM_NEG_INF) ? 0.f : m[qb];
         float rs = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
           float p[16];
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            p[r] = fast_exp2(fmaf(sacc[kb][qb][r], c, -msc));
+            p[r] = fast_exp2(sacc[kb][qb][r] - msc);
             rs += p[r];
           }
           pb[kb][qb][0] = pack8(p);
@@ -352,7 +357,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
     const int row = qrow[qb];
     if (row >= qlen) continue;
     const long t = useg_row0(g, b, qs) + row;
-    if (hi == 0 && lse2) lse2[useg_stat0(g, b, h, qs) + row] = lt > 0.f ? fmaf(m[qb], c, log2f(lt)) : __builtin_inff();
+    if (hi == 0 && lse2) lse2[useg_stat0(g, b, h, qs) + row] = lt > 0.f ? -(m[qb] + log2f(lt)) : IM_NEG_INF;  // negated
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -389,7 +394,6 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
   const int qlen = useg_rows(g, b, qs);
   if (q0 >= qlen) return;  // packed rows: this batch element's segment ends before the tile
   const int d = g.d;
-  const float c = fmaxf(g.scale_log2e, 1e-30f);  // > 0 so that -inf * c stays -inf when scale == 0
 
   // sub-head mode (DH = 8 / 16) as in the forward: one k-step for S^T and dP^T, one 32-row block of dQ^T
   constexpr int NS = DH == 64 ? 4 : 1;
@@ -428,7 +432,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
     dl[qb] = acc;
     const long li = useg_stat0(g, b, h, qs) + rc;
     const float lv = lse2[li];
-    ls[qb] = lv;  // +inf for a row without valid keys: every probability is exactly zero
+    ls[qb] = lv;  // negated log2-sum-exp; -inf for a row without valid keys: every probability is exactly zero
     if (hi == 0 && qrow[qb] < qlen) delta[li] = DH == 64 ? -acc : acc;  // see the dK/dV kernel
   }
 
@@ -524,7 +528,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
           float ds[16];
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const float p = fast_exp2(fmaf(sacc[qb][r], c, -ls[qb]));
+            const float p = fast_exp2(sacc[qb][r] + ls[qb]);
             ds[r] = p * (pacc[qb][r] - dl[qb]);
           }
           dsb[kb][qb][0] = pack8(ds);
@@ -571,7 +575,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
 // Ring stage = Q tile, dO tile (see RING_STAGE) plus the 64 lse and 64 delta values of the rows.
 // At head dim 64 the delta buffer holds -delta (the dQ kernel writes it so): the dP accumulator
 // starts from it, so the MFMA chain ends as dP - delta and no separate subtraction is needed.
-__device__ const float k_pos_inf = __builtin_inff();
+__device__ const float k_neg_inf = -__builtin_inff();
 
 template <int KB, int DH>
 __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void mfma_dkv_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
@@ -592,7 +596,6 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void mfma_dkv_kernel(Geo g, 
   const int klen_seg = useg_rows(g, b, ks);
   if (k0 >= klen_seg) return;  // packed rows: this batch element's segment ends before the tile
   const int d = g.d;
-  const float c = fmaxf(g.scale_log2e, 1e-30f);  // > 0 so that -inf * c stays -inf when scale == 0
 
   // sub-head mode (DH = 8 / 16): one k-step for S and dP, one 32-row block of dV^T and dK^T
   constexpr int NS = DH == 64 ? 4 : 1;
@@ -623,14 +626,14 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void mfma_dkv_kernel(Geo g, 
   };
   if (ic.len > 0) seg_begin();
   auto issue = [&]() {
-    // lse (wave 0) and delta (wave 1), one float per lane.  Rows past the segment read +inf as
-    // lse, so their probabilities are exactly zero.
+    // negated lse (wave 0) and delta (wave 1), one float per lane.  Rows past the segment read -inf
+    // as negated lse, so their probabilities are exactly zero.
     if (wave < 2) {
       float* dst = sLD + islot * 2 * KT + wave * KT;
       if (feed.rows >= KT) {
         dma4_off(wave == 0 ? feed_l : feed_d, (unsigned)lane * 4u, dst);
       } else {
-        const float* src = (wave == 0) ? (lane < feed.rows ? feed_l + lane : &k_pos_inf) : feed_d + min(lane, feed.rows - 1);
+        const float* src = (wave == 0) ? (lane < feed.rows ? feed_l + lane : &k_neg_inf) : feed_d + min(lane, feed.rows - 1);
         dma4(src, dst);
       }
     }
@@ -707,24 +710,29 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void mfma_dkv_kernel(Geo g, 
     cursor_step(cc, qlen_of);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-      // lse / delta of the query rows of the block: register r of an accumulator holds row
-      // (r / 8) * 16 + hi * 8 + r % 8.  delta goes straight into the dP accumulator (head dim 64: the buffer
-      // holds -delta), lse is fetched four rows at a time where it is used.
+      // negated lse / delta of the query rows of the block: register r of an accumulator holds row
+      // (r / 8) * 16 + hi * 8 + r % 8.  At head dim 64 both go straight into the accumulators (the delta buffer
+      // holds -delta): the MFMA chains then end as S - lse and dP - delta, and neither needs a vector
+      // instruction per element.  In sub-head mode they are fetched four rows at a time where they are used.
       auto rows4 = [&](const float* base, int r4) {   // values of registers 4 r4 .. 4 r4 + 3
         return *(const float4*)&base[qb * 32 + (r4 >> 1) * 16 + hi * 8 + (r4 & 1) * 4];
       };
       bf16x8 pb[KB][2], dsb[KB][2];
       f32x16 sacc[KB], pacc[KB];
-      float D[16];
+      float D[16], NL[16];
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         const float4 d4 = rows4(sD, r4);
         D[4 * r4] = d4.x; D[4 * r4 + 1] = d4.y; D[4 * r4 + 2] = d4.z; D[4 * r4 + 3] = d4.w;
+        if (DH == 64) {
+          const float4 l4 = rows4(sL, r4);
+          NL[4 * r4] = l4.x; NL[4 * r4 + 1] = l4.y; NL[4 * r4 + 2] = l4.z; NL[4 * r4 + 3] = l4.w;
+        }
       }
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { sacc[kb][r] = 0.f; pacc[kb][r] = DH == 64 ? D[r] : 0.f; }
+        for (int r = 0; r < 16; ++r) { sacc[kb][r] = DH == 64 ? NL[r] : 0.f; pacc[kb][r] = DH == 64 ? D[r] : 0.f; }
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
         const bf16x8 aq = lds_frag_sw(sQ, qb * 32, prow, 2 * (s0 + s) + hi);
@@ -740,12 +748,15 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void mfma_dkv_kernel(Geo g, 
         float p[16], ds[16];
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
-          const float4 l4 = rows4(sL, r4);
-          const float L[4] = {l4.x, l4.y, l4.z, l4.w};
+          float L[4] = {0.f, 0.f, 0.f, 0.f};
+          if (DH != 64) {
+            const float4 l4 = rows4(sL, r4);
+            L[0] = l4.x; L[1] = l4.y; L[2] = l4.z; L[3] = l4.w;
+          }
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
             const int r = 4 * r4 + u;
-            p[r] = fast_exp2(fmaf(sacc[kb][r], c, -L[u]));
+            p[r] = DH == 64 ? fast_exp2(sacc[kb][r]) : fast_exp2(sacc[kb][r] + L[u]);
             ds[r] = DH == 64 ? p[r] * pacc[kb][r] : p[r] * (pacc[kb][r] - D[r]);
           }
         }
@@ -773,7 +784,8 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void mfma_dkv_kernel(Geo g, 
     const int row = krow[kb];
     if (row >= klen_seg) continue;
     const long t = useg_row0(g, b, ks) + row;
-    const float zk = kvalid[kb] ? g.scale : 0.f, zv = kvalid[kb] ? 1.f : 0.f;
+    // dK = scale dS^T Q, and the staged Q rows are scale log2(e) Q: the accumulator needs a factor ln 2
+    const float zk = kvalid[kb] ? 0.69314718055994530942f : 0.f, zv = kvalid[kb] ? 1.f : 0.f;
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -805,7 +817,7 @@ void launch_mfma_fwd(const Geo& g, const bf16_t* qkv, long ld, const int32_t* va
   for (int s = 0; s < g.n_seg; ++s) {
     if (g.q_live[s]) continue;
     launch_zero_seg_rows(g, s, 1, o, ldo, 0, g.d, st);
-    if (lse2) launch_fill_seg_stat(g, s, lse2, __builtin_inff(), st);
+    if (lse2) launch_fill_seg_stat(g, s, lse2, -__builtin_inff(), st);
   }
   const int nt = g.q_tile_prefix[g.q_nord];
   if (nt == 0) return;

@@ -197,8 +197,9 @@ __global__ __launch_bounds__(256, 3) void mfma_gemm_kernel(MGemm p) {  // three 
         const int n = n0 + wn * 64 + nb * 32 + 8 * i + 4 * hi;
         if (n >= p.N) continue;  // N is a multiple of 4 for every caller
         float v[4];
+        const float cs = (p.scale0_on && n < p.n_per) ? p.scale0 : 1.f;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j];
+        for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j] * cs;
         if constexpr (EPI) {
           if (p.gelu) {
 #pragma unroll
@@ -450,8 +451,9 @@ __global__ __launch_bounds__(NWV * 64) void mfma_gemm_dma_kernel(MGemm p) {
           const int nl = nb * 32 + 8 * i + 4 * hi;
           const int n = n0 + wn * WCOLS + nl;
           float v[4];
+          const float cs = (p.scale0_on && n < p.n_per) ? p.scale0 : 1.f;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j];
+          for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j] * cs;
           if constexpr (EPI) {
             if (p.gelu) {
 #pragma unroll

@@ -115,6 +115,9 @@ int mfma_attention_fwd(const im_shape_t* s, const void* x, const void* wq, const
     p.b_kmajor = 1; p.b_nper = d;
     p.M = (int)dm.R; p.N = 3 * d; p.K = d;
     p.bias[0] = (const bf16_t*)bq; p.bias[1] = (const bf16_t*)bk; p.bias[2] = (const bf16_t*)bv; p.n_per = d;
+    // Q is stored as scale * log2(e) * (x Wq + bq), rounded once: the attention kernels then get their
+    // scores in the exponent domain of exp2 straight from the matrix cores (App. B's score scaling included)
+    p.scale0_on = 1; p.scale0 = g.scale_log2e;
     p.C = qkv; p.ldc = 3 * d;
     launch_mfma_gemm(p, st);
   }

@@ -14,6 +14,7 @@ struct MGemm {
   int M, N, K;
   int split_k; float* partial;           // partial != NULL: write fp32 partial[z][M][N] instead of the epilogue
   const bf16_t* bias[3]; int n_per;      // bias[n / n_per][n % n_per] (n_per = N for a single bias), or all NULL
+  int scale0_on; float scale0;           // scale0_on: columns n < n_per leave as scale0 * (A B + bias)
   int gelu;
   const bf16_t* res;                     // residual rows, same ld as C
   bf16_t* C; long ldc;                   // row-major output
