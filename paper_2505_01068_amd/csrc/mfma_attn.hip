@@ -19,7 +19,9 @@
 // epilogue does it before its one rounding to bf16), so Q K^T is the score in the exponent domain of
 // exp2 and no kernel multiplies scores; the per-row statistic saved by the forward is the NEGATED
 // log2-sum-exp (-inf for a row without any valid key), which the backward kernels add to the score --
-// the dK/dV kernel by starting its score accumulator from it.
+// every kernel by starting its score accumulator from it (the forward from its running reference),
+// as the dP accumulators start from -delta: the MFMA chains end as S - lse and dP - delta and the
+// softmax needs no add per element (dK/dV in sub-head mode still adds them per element).
 //
 // Only live (query segment, key segment) blocks of the Interlaced Mask are
 // visited (Sec. 6 "Decomposition"); a row with several live segments carries
@@ -206,12 +208,14 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
     }
   }
 
-  f32x16 oacc[NDB][QB];
+  f32x16 oacc[NDB][QB], nm[QB];
   float m[QB], l[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     m[qb] = IM_NEG_INF;
     l[qb] = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) nm[qb][r] = 0.f;
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -270,18 +274,16 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
     cursor_step(cc, klen_of);
     {
       // ---- S^T = K Q^T ----
+      // The accumulator chain starts from -m (nm: the running reference of the lane's query row in all 16
+      // registers), so the scores leave the matrix cores already relative to it.
       f32x16 sacc[2][QB];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) sacc[kb][qb][r] = 0.f;
-#pragma unroll
         for (int s = 0; s < NS; ++s) {
           const bf16x8 a = lds_frag_sw(sK, kb * 32, prow, 2 * (s0 + s) + hi);
 #pragma unroll
-          for (int qb = 0; qb < QB; ++qb) sacc[kb][qb] = mfma32(a, qreg[qb][s], sacc[kb][qb]);
+          for (int qb = 0; qb < QB; ++qb) sacc[kb][qb] = mfma32(a, qreg[qb][s], s == 0 ? nm[qb] : sacc[kb][qb]);
         }
       }
       // ---- mask the tail / padded keys (wave-uniform branch) ----
@@ -307,29 +309,37 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
           for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][qb][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // tile maximum relative to m (the raw maximum while m = -inf)
         // Lazy rescale: the running reference m only moves when the tile maximum exceeds it by more
         // than 2^8 in the exponent domain, so probabilities stay <= 256 (exact in bf16's range) and
-        // the accumulator rescale below is skipped for almost every tile after the first.
-        const bool upd = mx > m[qb] + tau;
+        // this branch -- accumulator rescale, shifting the tile's scores to the new reference and
+        // rebuilding nm -- is skipped for almost every tile after the first.
+        const bool first = m[qb] == IM_NEG_INF;
+        const bool upd = first ? mx > IM_NEG_INF : mx > tau;
         if (__any(upd)) {
-          const float mn = upd ? mx : m[qb];
-          const float alpha = (m[qb] == IM_NEG_INF) ? 0.f : fast_exp2(m[qb] - mn);
+          const float shift = upd ? mx : 0.f;
+          const float alpha = first ? 0.f : fast_exp2(-shift);
           l[qb] *= alpha;
 #pragma unroll
           for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
-          m[qb] = mn;
+          if (upd) m[qb] = first ? mx : m[qb] + mx;
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[kb][qb][r] -= shift;
+          const float nmv = (m[qb] == IM_NEG_INF) ? 0.f : -m[qb];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) nm[qb][r] = nmv;
         }
-        const float msc = (m[qb] == IM_NEG_INF) ? 0.f : m[qb];
         float rs = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
           float p[16];
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            p[r] = fast_exp2(sacc[kb][qb][r] - msc);
+            p[r] = fast_exp2(sacc[kb][qb][r]);
             rs += p[r];
           }
           pb[kb][qb][0] = pack8(p);
@@ -375,6 +385,9 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
 
 // ------------------------------------------------------------------------------------------
 // dQ (and delta = rowsum(dO * O)).  Same ownership as the forward: lane <-> query row.
+// The two constant accumulator seeds (negated lse, -delta: 32 registers) put the kernel at 194 registers
+// and two workgroups per CU; with them the softmax is exp2, one multiply and the bf16 pack per score, and
+// that was measured faster than three workgroups per CU with two more vector instructions per score.
 template <int QB, int DH>
 __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
                                                       const bf16_t* __restrict__ O,
@@ -436,13 +449,16 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
     if (hi == 0 && qrow[qb] < qlen) delta[li] = DH == 64 ? -acc : acc;  // see the dK/dV kernel
   }
 
-  f32x16 dqacc[NDB][QB];
+  f32x16 dqacc[NDB][QB], nlb[QB], ndb[QB];
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
+  for (int qb = 0; qb < QB; ++qb) {
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
       for (int r = 0; r < 16; ++r) dqacc[db][qb][r] = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { nlb[qb][r] = ls[qb]; ndb[qb][r] = -dl[qb]; }
+  }
 
   const int prow = perm32(lo);
   // The compiler does not see the asynchronous copies in its vmcnt bookkeeping: consuming the
@@ -501,19 +517,17 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
       bf16x8 dsb[2][QB][2];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
+        // The chains start from the row's negated lse resp. -delta (nlb, ndb: the lane's value in all 16
+        // registers), so they end as S^T - lse and dP^T - delta.
         f32x16 sacc[QB], pacc[QB];
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) { sacc[qb][r] = 0.f; pacc[qb][r] = 0.f; }
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
           const bf16x8 ak = lds_frag_sw(sK, kb * 32, prow, 2 * (s0 + s) + hi);
           const bf16x8 av = lds_frag_sw(sV, kb * 32, prow, 2 * (s0 + s) + hi);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) {
-            sacc[qb] = mfma32(ak, qreg[qb][s], sacc[qb]);   // S^T  = K Q^T
-            pacc[qb] = mfma32(av, greg[qb][s], pacc[qb]);   // dP^T = V dO^T
+            sacc[qb] = mfma32(ak, qreg[qb][s], s == 0 ? nlb[qb] : sacc[qb]);   // S^T  = K Q^T
+            pacc[qb] = mfma32(av, greg[qb][s], s == 0 ? ndb[qb] : pacc[qb]);   // dP^T = V dO^T
           }
         }
         if (need_mask) {  // wave-uniform: tail tile or key_pad present
@@ -528,8 +542,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
           float ds[16];
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const float p = fast_exp2(sacc[qb][r] + ls[qb]);
-            ds[r] = p * (pacc[qb][r] - dl[qb]);
+            const float p = fast_exp2(sacc[qb][r]);
+            ds[r] = p * pacc[qb][r];
           }
           dsb[kb][qb][0] = pack8(ds);
           dsb[kb][qb][1] = pack8(ds + 8);
