@@ -446,6 +446,54 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const T* __restrict__ x,
   for (int e = lane; e < d; e += 64) stf(y + r * d + e, (ldf(xr + e) - mu) * rstd * ldf(gamma + e) + ldf(beta + e));
 }
 
+// bf16 rows of d = 8 LPR elements (LPR a power of two <= 32): LPR lanes share a row, each holds 8
+// consecutive elements (one 16-byte load), and a wave normalises 64 / LPR rows at once.  At d = 64 that is
+// 8 rows per wave and full-width loads and stores instead of one row and 2 bytes per lane.
+template <int LPR>
+__global__ __launch_bounds__(256) void layernorm_rows_kernel(const bf16_t* __restrict__ x,
+                                                             const bf16_t* __restrict__ gamma,
+                                                             const bf16_t* __restrict__ beta,
+                                                             bf16_t* __restrict__ y, int R, float eps) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  constexpr int RPW = 64 / LPR, d = 8 * LPR;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const long r = ((long)blockIdx.x * 4 + wave) * RPW + lane / LPR;
+  const int c = (lane % LPR) * 8;
+  const bool live = r < R;
+  float v[8], gm[8], bt[8];
+  {
+    u32x4 raw = {0u, 0u, 0u, 0u};
+    if (live) raw = *(const u32x4*)(x + r * d + c);
+    const u32x4 gr = *(const u32x4*)(gamma + c), br = *(const u32x4*)(beta + c);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      v[2 * j] = __uint_as_float(raw[j] << 16); v[2 * j + 1] = __uint_as_float(raw[j] & 0xffff0000u);
+      gm[2 * j] = __uint_as_float(gr[j] << 16); gm[2 * j + 1] = __uint_as_float(gr[j] & 0xffff0000u);
+      bt[2 * j] = __uint_as_float(br[j] << 16); bt[2 * j + 1] = __uint_as_float(br[j] & 0xffff0000u);
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) s += v[j];
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+  const float mu = s * (1.f / d);
+  float q = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { const float t = v[j] - mu; q = fmaf(t, t, q); }
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+  const float rstd = rsqrtf(q * (1.f / d) + eps);
+  if (!live) return;
+  u32x4 out;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float a = (v[2 * j] - mu) * rstd * gm[2 * j] + bt[2 * j], b = (v[2 * j + 1] - mu) * rstd * gm[2 * j + 1] + bt[2 * j + 1];
+    out[j] = (unsigned)f2bf(a) | ((unsigned)f2bf(b) << 16);
+  }
+  *(u32x4*)(y + r * d + c) = out;
+}
+
 // ---- pieces of the encoder-layer backward ----
 __device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.f + erff(z * 0.70710678118654752440f)); }
 // d/dz [z Phi(z)] = Phi(z) + z phi(z)
@@ -528,6 +576,16 @@ int launch_layernorm_bwd(const void* x, const void* gamma, const void* dy, const
 int launch_layernorm(const void* x, const void* gamma, const void* beta, void* y, int R, int d, float eps, int bf16,
                      hipStream_t st) {
   dim3 grid((R + 3) / 4), block(256);
+  const bool aligned = (((uintptr_t)x | (uintptr_t)y | (uintptr_t)gamma | (uintptr_t)beta) & 15) == 0;
+  if (bf16 && aligned && (d == 64 || d == 128 || d == 256)) {
+    const int lpr = d / 8, rows_per_block = 4 * (64 / lpr);
+    const dim3 g2((R + rows_per_block - 1) / rows_per_block);
+#define LN_ROWS(L) hipLaunchKernelGGL((layernorm_rows_kernel<L>), g2, block, 0, st, (const bf16_t*)x, (const bf16_t*)gamma, \
+                                      (const bf16_t*)beta, (bf16_t*)y, R, eps)
+    if (lpr == 8) LN_ROWS(8); else if (lpr == 16) LN_ROWS(16); else LN_ROWS(32);
+#undef LN_ROWS
+    return IM_OK;
+  }
   if (bf16)
     hipLaunchKernelGGL((layernorm_kernel<bf16_t>), grid, block, 0, st, (const bf16_t*)x, (const bf16_t*)gamma,
                        (const bf16_t*)beta, (bf16_t*)y, R, d, eps);
