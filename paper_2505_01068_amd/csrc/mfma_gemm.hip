@@ -25,15 +25,18 @@ constexpr int KM_LD = 160;  // row stride (bf16) of a k-major LDS tile: 128 + 32
 
 __device__ __forceinline__ float gelu_exact_f(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752440f)); }
 
-struct Tile128 {
-  u32x4 v[4];
+template <int U>
+struct TileRegs {
+  u32x4 v[U];
 };
+typedef TileRegs<4> Tile128;
 
-// m-major operand: tile rows r0..r0+127 (clamped to rmax), K columns c0..c0+63 (zero beyond cmax)
-__device__ __forceinline__ void load_mm(Tile128& t, const bf16_t* base, long ld, int r0, int rmax, int c0, int cmax,
+// m-major operand: tile rows r0..r0+32U-1 (clamped to rmax), K columns c0..c0+63 (zero beyond cmax)
+template <int U>
+__device__ __forceinline__ void load_mm(TileRegs<U>& t, const bf16_t* base, long ld, int r0, int rmax, int c0, int cmax,
                                         int tid) {
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
+  for (int u = 0; u < U; ++u) {
     const int r = (tid >> 3) + u * 32, c = c0 + (tid & 7) * 8;
     const int rr = min(r0 + r, rmax);
     u32x4 v = {0u, 0u, 0u, 0u};
@@ -41,9 +44,10 @@ __device__ __forceinline__ void load_mm(Tile128& t, const bf16_t* base, long ld,
     t.v[u] = v;
   }
 }
-__device__ __forceinline__ void store_mm(const Tile128& t, bf16_t* lds, int tid) {
+template <int U>
+__device__ __forceinline__ void store_mm(const TileRegs<U>& t, bf16_t* lds, int tid) {
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
+  for (int u = 0; u < U; ++u) {
     const int r = (tid >> 3) + u * 32, c = (tid & 7) * 8;
     *(u32x4*)(lds + r * LDS_LD + c) = t.v[u];
   }
@@ -95,15 +99,20 @@ __device__ __forceinline__ void bias4(const MGemm& p, int n, float (&out)[4]) {
   }
 }
 
-template <bool AKM, bool BKM, bool EPI>
+// TM = rows of the tile: 128, or 64 (m-major A only; each wave then owns 32 x 64) for shapes whose 128-row
+// tiles would not fill the chip -- with under one workgroup per CU nothing overlaps the chain load ->
+// LDS -> MFMA -> store of a workgroup, and twice as many half-size workgroups finish sooner.
+template <bool AKM, bool BKM, bool EPI, int TM = GM>
 __global__ __launch_bounds__(256, 3) void mfma_gemm_kernel(MGemm p) {  // three workgroups per CU: at most 168 registers
-  __shared__ __attribute__((aligned(16))) bf16_t sA[AKM ? GK * KM_LD : GM * LDS_LD];
+  static_assert(TM == GM || (TM == 64 && !AKM), "the 64-row tile exists for m-major A only");
+  constexpr int MB = TM / 64;  // 32-row blocks per wave
+  __shared__ __attribute__((aligned(16))) bf16_t sA[AKM ? GK * KM_LD : TM * LDS_LD];
   __shared__ __attribute__((aligned(16))) bf16_t sB[BKM ? GK * KM_LD : GN * LDS_LD];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int wm = wave >> 1, wn = wave & 1;
   int bx, by, bz;
   xcd_block_index(bx, by, bz);
-  const int m0 = by * GM, n0 = bx * GN;
+  const int m0 = by * TM, n0 = bx * GN;
 
   const int ktiles = (p.K + GK - 1) / GK;
   const int per_split = (ktiles + p.split_k - 1) / p.split_k;
@@ -112,7 +121,7 @@ __global__ __launch_bounds__(256, 3) void mfma_gemm_kernel(MGemm p) {  // three 
   // [n block][m block]: rows of the accumulator = n, cols = m; registers 4i..4i+3 are columns
   // n = 8i + 4hi + 0..3 of the block.  The accumulators start at the bias of their column (split-K launches
   // carry no bias), so the epilogue has nothing to add.
-  f32x16 acc[2][2];
+  f32x16 acc[2][MB];
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
@@ -120,17 +129,18 @@ __global__ __launch_bounds__(256, 3) void mfma_gemm_kernel(MGemm p) {  // three 
       float bv[4] = {0.f, 0.f, 0.f, 0.f};
       if (!p.partial) bias4(p, n0 + wn * 64 + nb * 32 + 8 * i + 4 * hi, bv);
 #pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
+      for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) acc[nb][mb][4 * i + jj] = bv[jj];
     }
 
   const bf16_t* amat[3] = {p.A, p.A, p.A};
   const bf16_t* bmat[3] = {p.B[0], p.B[1], p.B[2]};
-  Tile128 ta, tb;
+  TileRegs<TM / 32> ta;
+  Tile128 tb;
   auto prefetch = [&](int it) {
     const int k0 = it * GK;
-    if (AKM) load_km(ta, amat, 0, p.lda, k0, p.K, m0, p.M, tid);
+    if constexpr (AKM) load_km(ta, amat, 0, p.lda, k0, p.K, m0, p.M, tid);
     else load_mm(ta, p.A, p.lda, m0, p.M - 1, k0, p.K, tid);
     if (BKM) {
       load_km(tb, bmat, p.b_nper, p.ldb, k0, p.K, n0, p.N, tid);
@@ -144,32 +154,33 @@ __global__ __launch_bounds__(256, 3) void mfma_gemm_kernel(MGemm p) {  // three 
   if (it_begin < it_end) prefetch(it_begin);
   for (int it = it_begin; it < it_end; ++it) {
     __syncthreads();
-    if (AKM) store_km(ta, sA, tid); else store_mm(ta, sA, tid);
+    if constexpr (AKM) store_km(ta, sA, tid); else store_mm(ta, sA, tid);
     if (BKM) store_km(tb, sB, tid); else store_mm(tb, sB, tid);
     __syncthreads();
     if (it + 1 < it_end) prefetch(it + 1);
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      bf16x8 fa[2], fb[2];
+      bf16x8 fa[MB], fb[2];
 #pragma unroll
-      for (int x = 0; x < 2; ++x) {
-        fa[x] = AKM ? lds_frag_tr(sA, KM_LD, s * 16, wm * 64 + x * 32, lane)
-                    : lds_frag(sA, wm * 64 + x * 32 + lo, s * 16 + hi * 8);
+      for (int x = 0; x < MB; ++x)
+        fa[x] = AKM ? lds_frag_tr(sA, KM_LD, s * 16, wm * 32 * MB + x * 32, lane)
+                    : lds_frag(sA, wm * 32 * MB + x * 32 + lo, s * 16 + hi * 8);
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
         fb[x] = BKM ? lds_frag_tr(sB, KM_LD, s * 16, wn * 64 + x * 32, lane)
                     : lds_frag(sB, wn * 64 + x * 32 + lo, s * 16 + hi * 8);
-      }
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) acc[nb][mb] = mfma32(fb[nb], fa[mb], acc[nb][mb]);
+        for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = mfma32(fb[nb], fa[mb], acc[nb][mb]);
     }
   }
 
   // ---- epilogue: lane owns row m; registers 4i..4i+3 are columns n = 8i + 4hi + 0..3 of the block ----
   if (p.partial) {  // split-K: fp32 partial sums, 16 bytes per lane
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-      const int m = m0 + wm * 64 + mb * 32 + lo;
+    for (int mb = 0; mb < MB; ++mb) {
+      const int m = m0 + wm * 32 * MB + mb * 32 + lo;
       if (m >= p.M) continue;
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb)
@@ -187,8 +198,8 @@ __global__ __launch_bounds__(256, 3) void mfma_gemm_kernel(MGemm p) {  // three 
   // for 16-byte row-contiguous stores was measured slower here: with three workgroups per CU the
   // stores of one overlap the loads of the others, and the extra barrier costs more than it saves.
 #pragma unroll
-  for (int mb = 0; mb < 2; ++mb) {
-    const int m = m0 + wm * 64 + mb * 32 + lo;
+  for (int mb = 0; mb < MB; ++mb) {
+    const int m = m0 + wm * 32 * MB + mb * 32 + lo;
     if (m >= p.M) continue;
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
@@ -590,6 +601,15 @@ static void launch_layout(const MGemm& p, bool dma, hipStream_t st) {
     if (epi) launch_dma<AKM, BKM, true>(p, st);
     else launch_dma<AKM, BKM, false>(p, st);
     return;
+  }
+  const long tiles = (long)((p.N + GN - 1) / GN) * ((p.M + GM - 1) / GM);
+  if constexpr (!AKM) {
+    if (p.split_k == 1 && !p.partial && tiles < 512 && p.M > 64) {  // under two workgroups per CU: 64-row tiles
+      dim3 grid((p.N + GN - 1) / GN, (p.M + 63) / 64, 1);
+      if (epi) hipLaunchKernelGGL((mfma_gemm_kernel<AKM, BKM, true, 64>), grid, dim3(256), 0, st, p);
+      else hipLaunchKernelGGL((mfma_gemm_kernel<AKM, BKM, false, 64>), grid, dim3(256), 0, st, p);
+      return;
+    }
   }
   dim3 grid((p.N + GN - 1) / GN, (p.M + GM - 1) / GM, p.split_k);
   if (epi) hipLaunchKernelGGL((mfma_gemm_kernel<AKM, BKM, true>), grid, dim3(256), 0, st, p);
