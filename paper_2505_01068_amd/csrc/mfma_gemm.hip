@@ -23,7 +23,21 @@ namespace imattn {
 constexpr int GM = 128, GN = 128, GK = 64;
 constexpr int KM_LD = 160;  // row stride (bf16) of a k-major LDS tile: 128 + 32 pad -> conflict-free transpose reads
 
-__device__ __forceinline__ float gelu_exact_f(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752440f)); }
+// GELU(x) = x Phi(x) with the error function from Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7, three
+// orders below the bf16 rounding of the result): one reciprocal, one exp2 and six multiply-adds instead of
+// the library erff's several dozen instructions -- the epilogue of the first MLP GEMM evaluates it for
+// every output element.
+__device__ __forceinline__ float gelu_erf_f(float x) {
+  const float u = fabsf(x) * 0.70710678118654752440f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, u, 1.f));
+  float pl = fmaf(1.061405429f, t, -1.453152027f);
+  pl = fmaf(pl, t, 1.421413741f);
+  pl = fmaf(pl, t, -0.284496736f);
+  pl = fmaf(pl, t, 0.254829592f);
+  const float e = pl * t * __builtin_amdgcn_exp2f(-1.44269504088896340736f * u * u);  // 1 - erf(u), u >= 0
+  const float phi = x >= 0.f ? 1.f - 0.5f * e : 0.5f * e;                              // Phi(x)
+  return x * phi;
+}
 
 template <int U>
 struct TileRegs {
@@ -100,8 +114,8 @@ __device__ __forceinline__ void bias4(const MGemm& p, int n, float (&out)[4]) {
 }
 
 // TM = rows of the tile: 128, or 64 (m-major A only; each wave then owns 32 x 64) for shapes whose 128-row
-// tiles would not fill the chip -- with under one workgroup per CU nothing overlaps the chain load ->
-// LDS -> MFMA -> store of a workgroup, and twice as many half-size workgroups finish sooner.
+// tiles would not fill the chip -- with about one workgroup per CU nothing overlaps the chain load ->
+// LDS -> MFMA -> epilogue loads -> store of a workgroup, and twice as many half-size workgroups finish sooner.
 template <bool AKM, bool BKM, bool EPI, int TM = GM>
 __global__ __launch_bounds__(256, 3) void mfma_gemm_kernel(MGemm p) {  // three workgroups per CU: at most 168 registers
   static_assert(TM == GM || (TM == 64 && !AKM), "the 64-row tile exists for m-major A only");
@@ -214,7 +228,7 @@ __global__ __launch_bounds__(256, 3) void mfma_gemm_kernel(MGemm p) {  // three 
         if constexpr (EPI) {
           if (p.gelu) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = gelu_exact_f(v[j]);
+            for (int j = 0; j < 4; ++j) v[j] = gelu_erf_f(v[j]);
           }
           if (p.res) {
             const u32x2 rv = *(const u32x2*)(p.res + (long)m * p.ldc + n);
@@ -468,7 +482,7 @@ __global__ __launch_bounds__(NWV * 64) void mfma_gemm_dma_kernel(MGemm p) {
           if constexpr (EPI) {
             if (p.gelu) {
 #pragma unroll
-              for (int j = 0; j < 4; ++j) v[j] = gelu_exact_f(v[j]);
+              for (int j = 0; j < 4; ++j) v[j] = gelu_erf_f(v[j]);
             }
             if (p.res && (interior || (m < p.M && n < p.N))) {
               const u32x2 rv = *(const u32x2*)(p.res + (long)m * p.ldc + n);
@@ -604,7 +618,9 @@ static void launch_layout(const MGemm& p, bool dma, hipStream_t st) {
   }
   const long tiles = (long)((p.N + GN - 1) / GN) * ((p.M + GM - 1) / GM);
   if constexpr (!AKM) {
-    if (p.split_k == 1 && !p.partial && tiles < 512 && p.M > 64) {  // under two workgroups per CU: 64-row tiles
+    // under one workgroup per CU, or under two with an epilogue that loads a residual / evaluates GELU
+    // (measured at M = 29 600: plain N = 192 11.8 -> 13.4 us, N = 64 + residual 14.6 -> 12.6, N = 256 + GELU 17.7 -> 15.8)
+    if (p.split_k == 1 && !p.partial && p.M > 64 && (tiles < 256 || (epi && tiles < 512))) {
       dim3 grid((p.N + GN - 1) / GN, (p.M + 63) / 64, 1);
       if (epi) hipLaunchKernelGGL((mfma_gemm_kernel<AKM, BKM, true, 64>), grid, dim3(256), 0, st, p);
       else hipLaunchKernelGGL((mfma_gemm_kernel<AKM, BKM, false, 64>), grid, dim3(256), 0, st, p);
