@@ -592,7 +592,7 @@ int mfma_gemm_split(int M, int N, int K) {
   if (tiles >= 256 || ktiles < 16) return 1;
   int s = (int)((512 + tiles - 1) / tiles);
   if (s > ktiles / 4) s = ktiles / 4;
-  if (s > 64) s = 64;  // beyond this the fixed-order reduction of the partials costs more than the GEMM gains
+  if (s > 192) s = 192;  // beyond this the fixed-order reduction of the partials costs more than the GEMM gains
   return s < 1 ? 1 : s;
 }
 
