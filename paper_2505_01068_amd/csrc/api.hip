@@ -508,20 +508,29 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
   void* z = b.take(R * (size_t)d_ff * es);
   char* aw = (char*)b.take(aws);
 
-  if ((rc = launch_layernorm(x, ln1_g, ln1_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
+  // At d = 64 a GEMM tile row is the whole feature row: both LayerNorms then run inside the GEMM that consumes
+  // them (the QKV projection, the first MLP GEMM) and u is never written.
+  const bool mfma = pick_path(shape) == PATH_MFMA;
+  auto al16 = [](const void* a, const void* b2) { return (((uintptr_t)a | (uintptr_t)b2) & 15) == 0; };
+  const bool ln1_fused = mfma && mfma_gemm_fuses_ln(bf, d, 3 * d) && al16(ln1_g, ln1_b);
+  const bool mlp_mfma = mfma_linear_ok(bf, d, d_ff) && mfma_linear_ok(bf, d_ff, d);
+  const bool ln2_fused = mlp_mfma && mfma_gemm_fuses_ln(bf, d, d_ff) && al16(ln2_g, ln2_b);
+  if (!ln1_fused && (rc = launch_layernorm(x, ln1_g, ln1_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
   // h = x + IMAttention(u)
   const SavedLayout L = saved_layout(shape);
-  if (pick_path(shape) == PATH_MFMA)
-    rc = mfma_attention_fwd(shape, u, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, h, x, aw, L.qkv, L.o, L.lse,
-                            L.extra, aw + L.total, st);
+  if (mfma)
+    rc = mfma_attention_fwd(shape, ln1_fused ? x : u, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, h, x, aw, L.qkv,
+                            L.o, L.lse, L.extra, aw + L.total, st,
+                            ln1_fused ? LnArgs{ln1_g, ln1_b, ln_eps} : LnArgs{nullptr, nullptr, 0.f});
   else
     rc = fwd_rowlane(shape, u, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, h, x, aw, st);
   if (rc) return rc;
-  if ((rc = launch_layernorm(h, ln2_g, ln2_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
+  if (!ln2_fused && (rc = launch_layernorm(h, ln2_g, ln2_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
   // z = GELU(u W1 + b1);  y = h + z W2 + b2
-  if (mfma_linear_ok(bf, d, d_ff) && mfma_linear_ok(bf, d_ff, d)) {
+  if (mlp_mfma) {
     ProfScope ps(PF_MISC, st);
-    mfma_linear(u, d, w1, nullptr, nullptr, d_ff, d_ff, b1, nullptr, nullptr, 1, nullptr, z, d_ff, (int)R, d_ff, (int)d, st);
+    mfma_linear(ln2_fused ? h : u, d, w1, nullptr, nullptr, d_ff, d_ff, b1, nullptr, nullptr, 1, nullptr, z, d_ff, (int)R,
+                d_ff, (int)d, st, ln2_fused ? LnArgs{ln2_g, ln2_b, ln_eps} : LnArgs{nullptr, nullptr, 0.f});
     mfma_linear(z, d_ff, w2, nullptr, nullptr, d, (int)d, b2, nullptr, nullptr, 0, h, y, d, (int)R, (int)d, d_ff, st);
     return check_hip("gsit_layer_fwd launch");
   }

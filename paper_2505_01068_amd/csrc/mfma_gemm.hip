@@ -91,6 +91,39 @@ __device__ __forceinline__ void store_km(const Tile128& t, bf16_t* lds, int tid)
   }
 }
 
+// LayerNorm of the staged rows of a row-major A tile whose 64 columns are the whole feature row
+// (K == 64): the 8 lanes that hold a row (8 elements each) share its mean and variance through three
+// shuffles; two-pass in fp32 and rounded to bf16 exactly as the stand-alone kernel does.
+template <int U>
+__device__ __forceinline__ void ln_tile_rows(TileRegs<U>& t, const bf16_t* gamma, const bf16_t* beta, float eps, int tid) {
+  const int c = (tid & 7) * 8;
+  const u32x4 gr = *(const u32x4*)(gamma + c), br = *(const u32x4*)(beta + c);
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { v[2 * j] = __uint_as_float(t.v[u][j] << 16); v[2 * j + 1] = __uint_as_float(t.v[u][j] & 0xffff0000u); }
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s += v[j];
+#pragma unroll
+    for (int o = 4; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    const float mu = s * (1.f / 64.f);
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { const float w = v[j] - mu; q = fmaf(w, w, q); }
+#pragma unroll
+    for (int o = 4; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+    const float rstd = rsqrtf(q * (1.f / 64.f) + eps);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float a = (v[2 * j] - mu) * rstd * __uint_as_float(gr[j] << 16) + __uint_as_float(br[j] << 16);
+      const float b = (v[2 * j + 1] - mu) * rstd * __uint_as_float(gr[j] & 0xffff0000u) + __uint_as_float(br[j] & 0xffff0000u);
+      t.v[u][j] = pack_bf16(a, b);
+    }
+  }
+}
+
 // EPI: the epilogue may apply GELU and add a residual (separate instantiation, so that the plain
 // bias epilogue of the attention projections stays a few hundred instructions long).
 // Bias of the 4 consecutive output columns n .. n+3 (n % 4 == 0) as fp32; 0 without a bias or past
@@ -155,7 +188,10 @@ __global__ __launch_bounds__(256, 3) void mfma_gemm_kernel(MGemm p) {  // three 
   auto prefetch = [&](int it) {
     const int k0 = it * GK;
     if constexpr (AKM) load_km(ta, amat, 0, p.lda, k0, p.K, m0, p.M, tid);
-    else load_mm(ta, p.A, p.lda, m0, p.M - 1, k0, p.K, tid);
+    else {
+      load_mm(ta, p.A, p.lda, m0, p.M - 1, k0, p.K, tid);
+      if (p.ln_g) ln_tile_rows(ta, p.ln_g, p.ln_b, p.ln_eps, tid);  // K == 64: this is the only k-tile
+    }
     if (BKM) {
       load_km(tb, bmat, p.b_nper, p.ldb, k0, p.K, n0, p.N, tid);
     } else {
@@ -633,7 +669,7 @@ static void launch_layout(const MGemm& p, bool dma, hipStream_t st) {
 }
 
 void launch_mfma_gemm(const MGemm& p, hipStream_t st) {
-  const bool dma = use_dma(p.M, p.N, p.K, p.a_kmajor, p.b_kmajor) && (p.b_kper == 0 || p.b_kper % DK == 0);
+  const bool dma = use_dma(p.M, p.N, p.K, p.a_kmajor, p.b_kmajor) && (p.b_kper == 0 || p.b_kper % DK == 0) && !p.ln_g;
   if (p.a_kmajor && p.b_kmajor) launch_layout<true, true>(p, dma, st);
   else if (p.b_kmajor) launch_layout<false, true>(p, dma, st);
   else if (p.a_kmajor) launch_layout<true, false>(p, dma, st);

@@ -53,9 +53,10 @@ static void init_gemm(MGemm* p) {
 
 void mfma_linear(const void* A, long lda, const void* w0, const void* w1, const void* w2, long ldb, int n_per,
                  const void* b0, const void* b1, const void* b2, int gelu, const void* res, void* C, long ldc, int M,
-                 int N, int K, hipStream_t st) {
+                 int N, int K, hipStream_t st, LnArgs ln) {
   MGemm p;
   init_gemm(&p);
+  p.ln_g = (const bf16_t*)ln.g; p.ln_b = (const bf16_t*)ln.b; p.ln_eps = ln.eps;
   p.A = (const bf16_t*)A; p.lda = lda;
   p.B[0] = (const bf16_t*)w0; p.B[1] = (const bf16_t*)w1; p.B[2] = (const bf16_t*)w2; p.ldb = ldb;
   p.b_kmajor = 1; p.b_nper = (w1 || w2) ? n_per : 0;
@@ -96,7 +97,7 @@ void mfma_wgrad(const void* A, long lda, const void* G, long ldg, float* o0, flo
 int mfma_attention_fwd(const im_shape_t* s, const void* x, const void* wq, const void* wk, const void* wv,
                        const void* wo, const void* bq, const void* bk, const void* bv, const void* bo,
                        const int32_t* valid_len, const uint8_t* key_pad, void* y, const void* res, char* sv,
-                       size_t off_qkv, size_t off_o, size_t off_lse, size_t, char*, hipStream_t st) {
+                       size_t off_qkv, size_t off_o, size_t off_lse, size_t, char*, hipStream_t st, LnArgs ln) {
   Geo g;
   build_geo(s, mfma_fwd_tile_rows(s->d_model / s->n_heads), mfma_dkv_tile_rows(), &g);
   const Dims dm = dims(s);
@@ -118,6 +119,7 @@ int mfma_attention_fwd(const im_shape_t* s, const void* x, const void* wq, const
     // Q is stored as scale * log2(e) * (x Wq + bq), rounded once: the attention kernels then get their
     // scores in the exponent domain of exp2 straight from the matrix cores (App. B's score scaling included)
     p.scale0_on = 1; p.scale0 = g.scale_log2e;
+    p.ln_g = (const bf16_t*)ln.g; p.ln_b = (const bf16_t*)ln.b; p.ln_eps = ln.eps;
     p.C = qkv; p.ldc = 3 * d;
     launch_mfma_gemm(p, st);
   }

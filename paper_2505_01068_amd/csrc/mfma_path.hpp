@@ -15,11 +15,17 @@ struct MGemm {
   int split_k; float* partial;           // partial != NULL: write fp32 partial[z][M][N] instead of the epilogue
   const bf16_t* bias[3]; int n_per;      // bias[n / n_per][n % n_per] (n_per = N for a single bias), or all NULL
   int scale0_on; float scale0;           // scale0_on: columns n < n_per leave as scale0 * (A B + bias)
+  const bf16_t* ln_g; const bf16_t* ln_b; float ln_eps;  // ln_g != NULL: the rows of A are LayerNorm-ed as they are
+                                                         // staged (row-major A, K == 64 only: mfma_gemm_fuses_ln)
   int gelu;
   const bf16_t* res;                     // residual rows, same ld as C
   bf16_t* C; long ldc;                   // row-major output
 };
 void launch_mfma_gemm(const MGemm& p, hipStream_t st);
+// LayerNorm over the K axis of a row-major A can run inside the GEMM when a tile row is the whole feature row
+inline bool mfma_gemm_fuses_ln(int is_bf16, long K, long N) { return is_bf16 && K == 64 && N % 8 == 0 && N >= 8; }
+// LayerNorm parameters for the rows of the left operand (all NULL / 0: none)
+struct LnArgs { const void* g; const void* b; float eps; };
 // bf16 linear layer C[M,N] = A[M,K] W + bias (+ GELU) (+ residual) with weights stored [K][N] (k-major),
 // optionally three weight / bias blocks of n_per columns each.  Usable when K % 8 == 0 and N % 8 == 0.
 inline bool mfma_linear_ok(int is_bf16, long K, long N) { return is_bf16 && K % 8 == 0 && N % 8 == 0 && K >= 8 && N >= 8; }
@@ -35,7 +41,7 @@ void mfma_wgrad(const void* A, long lda, const void* G, long ldg, float* o0, flo
                 int N, int R, float* partial, hipStream_t st);
 void mfma_linear(const void* A, long lda, const void* w0, const void* w1, const void* w2, long ldb, int n_per,
                  const void* b0, const void* b1, const void* b2, int gelu, const void* res, void* C, long ldc, int M,
-                 int N, int K, hipStream_t st);
+                 int N, int K, hipStream_t st, LnArgs ln = {nullptr, nullptr, 0.f});
 int mfma_gemm_split(int M, int N, int K);
 void launch_splitk_reduce(const float* partial, int split_k, int M, int N, float* o0, float* o1, float* o2, int n_per,
                           hipStream_t st);
@@ -61,7 +67,8 @@ size_t mfma_bwd_workspace_bytes(const im_shape_t* s);
 int mfma_attention_fwd(const im_shape_t* s, const void* x, const void* wq, const void* wk, const void* wv,
                        const void* wo, const void* bq, const void* bk, const void* bv, const void* bo,
                        const int32_t* valid_len, const uint8_t* key_pad, void* y, const void* res, char* sv,
-                       size_t off_qkv, size_t off_o, size_t off_lse, size_t off_extra, char* ws, hipStream_t st);
+                       size_t off_qkv, size_t off_o, size_t off_lse, size_t off_extra, char* ws, hipStream_t st,
+                       LnArgs ln = {nullptr, nullptr, 0.f});   // ln: LayerNorm x inside the QKV projection
 int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const void* wk, const void* wv,
                        const void* wo, const int32_t* valid_len, const uint8_t* key_pad, const char* sv,
                        size_t off_qkv, size_t off_o, size_t off_lse, size_t off_extra, const void* dy, void* dx,
