@@ -525,6 +525,11 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
   else
     rc = fwd_rowlane(shape, u, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, h, x, aw, st);
   if (rc) return rc;
+  if (mlp64_ok(bf, d, d_ff, h, ln2_g, ln2_b, w1, w2, y)) {   // the whole MLP sub-block in one kernel
+    ProfScope ps(PF_MISC, st);
+    launch_mlp64(h, ln2_g, ln2_b, ln_eps, w1, b1, w2, b2, y, (int)R, d_ff, st);
+    return check_hip("gsit_layer_fwd launch");
+  }
   if (!ln2_fused && (rc = launch_layernorm(h, ln2_g, ln2_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
   // z = GELU(u W1 + b1);  y = h + z W2 + b2
   if (mlp_mfma) {

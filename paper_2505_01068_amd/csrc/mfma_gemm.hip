@@ -548,6 +548,88 @@ __global__ __launch_bounds__(NWV * 64) void mfma_gemm_dma_kernel(MGemm p) {
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Whole MLP sub-block of an encoder layer at model width 64 in one kernel:
+//   y = h + GELU(LN(h) W1 + b1) W2 + b2        (h [R, 64], W1 [64, d_ff], W2 [d_ff, 64], d_ff % 64 == 0)
+// A workgroup owns 64 rows.  The hidden layer is walked in chunks of 64 columns: the chunk
+// z_j = GELU(LN(h) W1[:, j] + b1[j]) (64 x 64) goes to LDS as bf16 and is at once multiplied into the
+// 64 x 64 output accumulator with W2[j, :], so the [R, d_ff] activation never exists in memory and the
+// three launches LayerNorm, first GEMM, second GEMM become one.  Four waves in a 2 x 2 grid, each 32 x 32
+// of both products; the same transposed-product tiles as mfma_gemm_kernel (lane owns an output row).
+struct Mlp64Args {
+  const bf16_t* h; const bf16_t* ln_g; const bf16_t* ln_b; float ln_eps;
+  const bf16_t* w1; const bf16_t* b1; const bf16_t* w2; const bf16_t* b2;
+  bf16_t* y; int R, d_ff;
+};
+__global__ __launch_bounds__(256) void mlp64_kernel(Mlp64Args p) {
+  __shared__ __attribute__((aligned(16))) bf16_t sA[64 * LDS_LD], sW1[64 * LDS_LD], sW2[64 * LDS_LD], sZ[64 * LDS_LD];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = blockIdx.x * 64;
+  TileRegs<2> ta, t1, t2;
+  load_mm(ta, p.h, 64, m0, p.R - 1, 0, 64, tid);
+  ln_tile_rows(ta, p.ln_g, p.ln_b, p.ln_eps, tid);
+  store_mm(ta, sA, tid);
+  const int nchunk = p.d_ff / 64;
+  auto fetch = [&](int j) {   // W1[:, 64 j .. 64 j + 63] (rows = k) and W2[64 j .. 64 j + 63, :] (rows = k)
+    load_mm(t1, p.w1 + j * 64, p.d_ff, 0, 63, 0, 64, tid);
+    load_mm(t2, p.w2 + (long)j * 64 * 64, 64, 0, 63, 0, 64, tid);
+  };
+  fetch(0);
+  // output accumulator: rows wm*32 + lo, registers 4i..4i+3 = columns wn*32 + 8i + 4hi + 0..3; starts at b2
+  f32x16 acc2;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc2[4 * i + j] = p.b2 ? bf2f(p.b2[wn * 32 + 8 * i + 4 * hi + j]) : 0.f;
+  for (int c = 0; c < nchunk; ++c) {
+    __syncthreads();  // the previous chunk's W1, W2 and z tiles have been read (first pass: sA is complete)
+    store_mm(t1, sW1, tid);
+    store_mm(t2, sW2, tid);
+    __syncthreads();
+    if (c + 1 < nchunk) fetch(c + 1);
+    f32x16 acc1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc1[4 * i + j] = p.b1 ? bf2f(p.b1[c * 64 + wn * 32 + 8 * i + 4 * hi + j]) : 0.f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      acc1 = mfma32(lds_frag_tr(sW1, LDS_LD, s * 16, wn * 32, lane), lds_frag(sA, wm * 32 + lo, s * 16 + hi * 8), acc1);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const u32x2 pk = {pack_bf16(gelu_erf_f(acc1[4 * i]), gelu_erf_f(acc1[4 * i + 1])),
+                        pack_bf16(gelu_erf_f(acc1[4 * i + 2]), gelu_erf_f(acc1[4 * i + 3]))};
+      *(u32x2*)(sZ + (wm * 32 + lo) * LDS_LD + wn * 32 + 8 * i + 4 * hi) = pk;
+    }
+    __syncthreads();  // z chunk complete
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      acc2 = mfma32(lds_frag_tr(sW2, LDS_LD, s * 16, wn * 32, lane), lds_frag(sZ, wm * 32 + lo, s * 16 + hi * 8), acc2);
+  }
+  const int m = m0 + wm * 32 + lo;
+  if (m >= p.R) return;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int n = wn * 32 + 8 * i + 4 * hi;
+    const u32x2 rv = *(const u32x2*)(p.h + (long)m * 64 + n);   // residual: the rows before the LayerNorm
+    const u32x2 pk = {pack_bf16(acc2[4 * i] + __uint_as_float(rv[0] << 16), acc2[4 * i + 1] + __uint_as_float(rv[0] & 0xffff0000u)),
+                      pack_bf16(acc2[4 * i + 2] + __uint_as_float(rv[1] << 16), acc2[4 * i + 3] + __uint_as_float(rv[1] & 0xffff0000u))};
+    *(u32x2*)(p.y + (long)m * 64 + n) = pk;
+  }
+}
+bool mlp64_ok(int is_bf16, long d, long d_ff, const void* h, const void* ln_g, const void* ln_b, const void* w1,
+              const void* w2, const void* y) {
+  const uintptr_t a = (uintptr_t)h | (uintptr_t)ln_g | (uintptr_t)ln_b | (uintptr_t)w1 | (uintptr_t)w2 | (uintptr_t)y;
+  return is_bf16 && d == 64 && d_ff >= 64 && d_ff % 64 == 0 && (a & 15) == 0;
+}
+void launch_mlp64(const void* h, const void* ln_g, const void* ln_b, float ln_eps, const void* w1, const void* b1,
+                  const void* w2, const void* b2, void* y, int R, int d_ff, hipStream_t st) {
+  Mlp64Args p = {(const bf16_t*)h, (const bf16_t*)ln_g, (const bf16_t*)ln_b, ln_eps, (const bf16_t*)w1, (const bf16_t*)b1,
+                 (const bf16_t*)w2, (const bf16_t*)b2, (bf16_t*)y, R, d_ff};
+  hipLaunchKernelGGL(mlp64_kernel, dim3((R + 63) / 64), dim3(256), 0, st, p);
+}
+
 // partial[z][M][N] -> out (fp32), z summed in fixed order; output column blocks may go to 3 matrices.
 // One thread per 4 consecutive outputs (N and n_per are multiples of 4).
 __global__ void mfma_splitk_reduce_kernel(const float* partial, int split_k, int M, int N, float* o0, float* o1,
