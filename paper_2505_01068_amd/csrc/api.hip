@@ -518,13 +518,21 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
   if (!ln1_fused && (rc = launch_layernorm(x, ln1_g, ln1_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
   // h = x + IMAttention(u)
   const SavedLayout L = saved_layout(shape);
+  // At d = 64 on the matrix-core path the rest of the layer after the attention kernel -- output projection,
+  // residual, LayerNorm, MLP, residual -- is row-local and runs as ONE kernel on the attention's O rows.
+  const bool tail_fused = mfma && mlp64_ok(bf, d, d_ff, x, ln2_g, ln2_b, w1, w2, y) && (((uintptr_t)wo | (uintptr_t)aw) & 15) == 0;
   if (mfma)
-    rc = mfma_attention_fwd(shape, ln1_fused ? x : u, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, h, x, aw, L.qkv,
-                            L.o, L.lse, L.extra, aw + L.total, st,
+    rc = mfma_attention_fwd(shape, ln1_fused ? x : u, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad,
+                            tail_fused ? nullptr : h, x, aw, L.qkv, L.o, L.lse, L.extra, aw + L.total, st,
                             ln1_fused ? LnArgs{ln1_g, ln1_b, ln_eps} : LnArgs{nullptr, nullptr, 0.f});
   else
     rc = fwd_rowlane(shape, u, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, h, x, aw, st);
   if (rc) return rc;
+  if (tail_fused) {
+    ProfScope ps(PF_MISC, st);
+    launch_mlp64(x, ln2_g, ln2_b, ln_eps, w1, b1, w2, b2, y, (int)R, d_ff, st, aw + L.o, wo, bo);
+    return check_hip("gsit_layer_fwd launch");
+  }
   if (mlp64_ok(bf, d, d_ff, h, ln2_g, ln2_b, w1, w2, y)) {   // the whole MLP sub-block in one kernel
     ProfScope ps(PF_MISC, st);
     launch_mlp64(h, ln2_g, ln2_b, ln_eps, w1, b1, w2, b2, y, (int)R, d_ff, st);

@@ -551,6 +551,8 @@ __global__ __launch_bounds__(NWV * 64) void mfma_gemm_dma_kernel(MGemm p) {
 // ------------------------------------------------------------------------------------------
 // Whole MLP sub-block of an encoder layer at model width 64 in one kernel:
 //   y = h + GELU(LN(h) W1 + b1) W2 + b2        (h [R, 64], W1 [64, d_ff], W2 [d_ff, 64], d_ff % 64 == 0)
+// and, with PROJ, also the attention's output projection and residual in front of it:
+//   h = x + O Wo + bo                          (O, x [R, 64]; h is rounded to bf16 and kept in LDS only)
 // A workgroup owns 64 rows.  The hidden layer is walked in chunks of 64 columns: the chunk
 // z_j = GELU(LN(h) W1[:, j] + b1[j]) (64 x 64) goes to LDS as bf16 and is at once multiplied into the
 // 64 x 64 output accumulator with W2[j, :], so the [R, d_ff] activation never exists in memory and the
@@ -560,14 +562,46 @@ struct Mlp64Args {
   const bf16_t* h; const bf16_t* ln_g; const bf16_t* ln_b; float ln_eps;
   const bf16_t* w1; const bf16_t* b1; const bf16_t* w2; const bf16_t* b2;
   bf16_t* y; int R, d_ff;
+  const bf16_t* o; const bf16_t* wo; const bf16_t* bo;   // PROJ: h above is x, the residual of the projection
 };
+template <bool PROJ>
 __global__ __launch_bounds__(256) void mlp64_kernel(Mlp64Args p) {
   __shared__ __attribute__((aligned(16))) bf16_t sA[64 * LDS_LD], sW1[64 * LDS_LD], sW2[64 * LDS_LD], sZ[64 * LDS_LD];
+  __shared__ __attribute__((aligned(16))) bf16_t sH[PROJ ? 64 * LDS_LD : 8];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int wm = wave >> 1, wn = wave & 1;
   const int m0 = blockIdx.x * 64;
   TileRegs<2> ta, t1, t2;
-  load_mm(ta, p.h, 64, m0, p.R - 1, 0, 64, tid);
+  if constexpr (PROJ) {
+    // h = x + O Wo + bo for the 64 rows, through the same tiles: O -> sA, Wo -> sW1, h (bf16) -> sH
+    load_mm(ta, p.o, 64, m0, p.R - 1, 0, 64, tid);
+    load_mm(t1, p.wo, 64, 0, 63, 0, 64, tid);
+    store_mm(ta, sA, tid);
+    store_mm(t1, sW1, tid);
+    __syncthreads();
+    f32x16 acc;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[4 * i + j] = p.bo ? bf2f(p.bo[wn * 32 + 8 * i + 4 * hi + j]) : 0.f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      acc = mfma32(lds_frag_tr(sW1, LDS_LD, s * 16, wn * 32, lane), lds_frag(sA, wm * 32 + lo, s * 16 + hi * 8), acc);
+    const int mr = min(m0 + wm * 32 + lo, p.R - 1);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int n = wn * 32 + 8 * i + 4 * hi;
+      const u32x2 rv = *(const u32x2*)(p.h + (long)mr * 64 + n);
+      const u32x2 pk = {pack_bf16(acc[4 * i] + __uint_as_float(rv[0] << 16), acc[4 * i + 1] + __uint_as_float(rv[0] & 0xffff0000u)),
+                        pack_bf16(acc[4 * i + 2] + __uint_as_float(rv[1] << 16), acc[4 * i + 3] + __uint_as_float(rv[1] & 0xffff0000u))};
+      *(u32x2*)(sH + (wm * 32 + lo) * LDS_LD + n) = pk;
+    }
+    __syncthreads();  // sH complete; every wave is done with sA and sW1
+#pragma unroll
+    for (int u = 0; u < 2; ++u) ta.v[u] = *(const u32x4*)(sH + ((tid >> 3) + u * 32) * LDS_LD + (tid & 7) * 8);
+  } else {
+    load_mm(ta, p.h, 64, m0, p.R - 1, 0, 64, tid);
+  }
   ln_tile_rows(ta, p.ln_g, p.ln_b, p.ln_eps, tid);
   store_mm(ta, sA, tid);
   const int nchunk = p.d_ff / 64;
@@ -612,7 +646,8 @@ __global__ __launch_bounds__(256) void mlp64_kernel(Mlp64Args p) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int n = wn * 32 + 8 * i + 4 * hi;
-    const u32x2 rv = *(const u32x2*)(p.h + (long)m * 64 + n);   // residual: the rows before the LayerNorm
+    // residual: the rows before the LayerNorm
+    const u32x2 rv = PROJ ? *(const u32x2*)(sH + (wm * 32 + lo) * LDS_LD + n) : *(const u32x2*)(p.h + (long)m * 64 + n);
     const u32x2 pk = {pack_bf16(acc2[4 * i] + __uint_as_float(rv[0] << 16), acc2[4 * i + 1] + __uint_as_float(rv[0] & 0xffff0000u)),
                       pack_bf16(acc2[4 * i + 2] + __uint_as_float(rv[1] << 16), acc2[4 * i + 3] + __uint_as_float(rv[1] & 0xffff0000u))};
     *(u32x2*)(p.y + (long)m * 64 + n) = pk;
@@ -624,10 +659,13 @@ bool mlp64_ok(int is_bf16, long d, long d_ff, const void* h, const void* ln_g, c
   return is_bf16 && d == 64 && d_ff >= 64 && d_ff % 64 == 0 && (a & 15) == 0;
 }
 void launch_mlp64(const void* h, const void* ln_g, const void* ln_b, float ln_eps, const void* w1, const void* b1,
-                  const void* w2, const void* b2, void* y, int R, int d_ff, hipStream_t st) {
+                  const void* w2, const void* b2, void* y, int R, int d_ff, hipStream_t st, const void* o,
+                  const void* wo, const void* bo) {
   Mlp64Args p = {(const bf16_t*)h, (const bf16_t*)ln_g, (const bf16_t*)ln_b, ln_eps, (const bf16_t*)w1, (const bf16_t*)b1,
-                 (const bf16_t*)w2, (const bf16_t*)b2, (bf16_t*)y, R, d_ff};
-  hipLaunchKernelGGL(mlp64_kernel, dim3((R + 63) / 64), dim3(256), 0, st, p);
+                 (const bf16_t*)w2, (const bf16_t*)b2, (bf16_t*)y, R, d_ff, (const bf16_t*)o, (const bf16_t*)wo,
+                 (const bf16_t*)bo};
+  if (o) hipLaunchKernelGGL(mlp64_kernel<true>, dim3((R + 63) / 64), dim3(256), 0, st, p);
+  else hipLaunchKernelGGL(mlp64_kernel<false>, dim3((R + 63) / 64), dim3(256), 0, st, p);
 }
 
 // partial[z][M][N] -> out (fp32), z summed in fixed order; output column blocks may go to 3 matrices.

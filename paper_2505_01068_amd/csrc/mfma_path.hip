@@ -126,7 +126,7 @@ int mfma_attention_fwd(const im_shape_t* s, const void* x, const void* wq, const
 
   launch_mfma_fwd(g, qkv, 3 * d, valid_len, key_pad, o, d, lse2, st);
 
-  {
+  if (y) {   // y == NULL: the caller applies the output projection itself (to O at sv + off_o)
     ProfScope ps(PF_PROJ_FWD, st);
     init_gemm(&p);
     p.A = o; p.lda = d;
