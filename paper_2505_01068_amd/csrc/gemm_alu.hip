@@ -509,13 +509,70 @@ __global__ void gelu_bwd_kernel(const T* __restrict__ z, T* __restrict__ g, long
   for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x)
     stf(g + i, ldf(g + i) * gelu_grad_f(ldf(z + i)));
 }
+// bf16, 8 elements (16 bytes) per thread and step
+__device__ __forceinline__ void unpack8(const uint4& r, float (&v)[8]) {
+  const unsigned w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) { v[2 * j] = __uint_as_float(w[j] << 16); v[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u); }
+}
+__device__ __forceinline__ uint4 pack8_rne(const float (&v)[8]) {
+  unsigned w[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) w[j] = (unsigned)f2bf(v[2 * j]) | ((unsigned)f2bf(v[2 * j + 1]) << 16);
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+// Phi(x), the standard normal CDF, with erf from Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7, far below the
+// bf16 rounding of the results): a reciprocal, an exp2 and six multiply-adds instead of the library erff.
+__device__ __forceinline__ float phi_as_f(float x) {
+  const float u = fabsf(x) * 0.70710678118654752440f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, u, 1.f));
+  float pl = fmaf(1.061405429f, t, -1.453152027f);
+  pl = fmaf(pl, t, 1.421413741f);
+  pl = fmaf(pl, t, -0.284496736f);
+  pl = fmaf(pl, t, 0.254829592f);
+  const float e = pl * t * __builtin_amdgcn_exp2f(-1.44269504088896340736f * u * u);  // 1 - erf(u)
+  return x >= 0.f ? 1.f - 0.5f * e : 0.5f * e;
+}
+__global__ void gelu_fwd8_kernel(const bf16_t* __restrict__ z, bf16_t* __restrict__ a, long n8) {
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n8; i += (long)gridDim.x * blockDim.x) {
+    float v[8];
+    unpack8(*(const uint4*)(z + 8 * i), v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] *= phi_as_f(v[j]);
+    *(uint4*)(a + 8 * i) = pack8_rne(v);
+  }
+}
+__global__ void gelu_bwd8_kernel(const bf16_t* __restrict__ z, bf16_t* __restrict__ g, long n8) {
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n8; i += (long)gridDim.x * blockDim.x) {
+    float v[8], w[8];
+    unpack8(*(const uint4*)(z + 8 * i), v);
+    unpack8(*(const uint4*)(g + 8 * i), w);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)   // d/dz [z Phi(z)] = Phi(z) + z phi(z)
+      w[j] *= phi_as_f(v[j]) + v[j] * __expf(-0.5f * v[j] * v[j]) * 0.39894228040143267794f;
+    *(uint4*)(g + 8 * i) = pack8_rne(w);
+  }
+}
+static bool vec8_ok(const void* a, const void* b, long n) { return n % 8 == 0 && (((uintptr_t)a | (uintptr_t)b) & 15) == 0; }
 int launch_gelu_fwd(const void* z, void* a, long n, int bf16, hipStream_t st) {
+  if (bf16 && vec8_ok(z, a, n)) {
+    const long n8 = n / 8;
+    const int blocks8 = (int)((n8 + 255) / 256 < 8192 ? (n8 + 255) / 256 : 8192);
+    hipLaunchKernelGGL(gelu_fwd8_kernel, dim3(blocks8), dim3(256), 0, st, (const bf16_t*)z, (bf16_t*)a, n8);
+    return IM_OK;
+  }
   const int blocks = (int)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
   if (bf16) hipLaunchKernelGGL((gelu_fwd_kernel<bf16_t>), dim3(blocks), dim3(256), 0, st, (const bf16_t*)z, (bf16_t*)a, n);
   else hipLaunchKernelGGL((gelu_fwd_kernel<float>), dim3(blocks), dim3(256), 0, st, (const float*)z, (float*)a, n);
   return IM_OK;
 }
 int launch_gelu_bwd(const void* z, void* g, long n, int bf16, hipStream_t st) {
+  if (bf16 && vec8_ok(z, g, n)) {
+    const long n8 = n / 8;
+    const int blocks8 = (int)((n8 + 255) / 256 < 8192 ? (n8 + 255) / 256 : 8192);
+    hipLaunchKernelGGL(gelu_bwd8_kernel, dim3(blocks8), dim3(256), 0, st, (const bf16_t*)z, (bf16_t*)g, n8);
+    return IM_OK;
+  }
   const int blocks = (int)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
   if (bf16) hipLaunchKernelGGL((gelu_bwd_kernel<bf16_t>), dim3(blocks), dim3(256), 0, st, (const bf16_t*)z, (bf16_t*)g, n);
   else hipLaunchKernelGGL((gelu_bwd_kernel<float>), dim3(blocks), dim3(256), 0, st, (const float*)z, (float*)g, n);
@@ -561,9 +618,69 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const T* __restrict_
     stf(t + r * d + e, g * xh);
   }
 }
+// The same for bf16 rows of d = 8 LPR elements, LPR lanes per row and 64 / LPR rows per wave (see layernorm_rows_kernel).
+template <int LPR>
+__global__ __launch_bounds__(256) void layernorm_bwd_rows_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
+                                                                 const bf16_t* __restrict__ dy, const bf16_t* __restrict__ res,
+                                                                 bf16_t* __restrict__ dx, bf16_t* __restrict__ t, int R,
+                                                                 float eps) {
+  constexpr int RPW = 64 / LPR, d = 8 * LPR;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const long r = ((long)blockIdx.x * 4 + wave) * RPW + lane / LPR;
+  const int c = (lane % LPR) * 8;
+  const bool live = r < R;
+  const long at = (live ? r : 0) * d + c;
+  float xv[8], gv[8], gm[8], rs[8];
+  unpack8(*(const uint4*)(x + at), xv);
+  unpack8(*(const uint4*)(dy + at), gv);
+  unpack8(*(const uint4*)(gamma + c), gm);
+  if (res) unpack8(*(const uint4*)(res + at), rs);
+  auto rowsum = [&](float v) {
+#pragma unroll
+    for (int o = LPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+  };
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) s += xv[j];
+  const float mu = rowsum(s) * (1.f / d);
+  float q = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { const float w = xv[j] - mu; q = fmaf(w, w, q); }
+  const float rstd = rsqrtf(rowsum(q) * (1.f / d) + eps);
+  float m1 = 0.f, m2 = 0.f, xh[8], a[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    a[j] = gm[j] * gv[j];
+    xh[j] = (xv[j] - mu) * rstd;
+    m1 += a[j];
+    m2 = fmaf(a[j], xh[j], m2);
+  }
+  m1 = rowsum(m1) * (1.f / d);
+  m2 = rowsum(m2) * (1.f / d);
+  if (!live) return;
+  float o1[8], o2[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    o1[j] = rstd * (a[j] - m1 - xh[j] * m2) + (res ? rs[j] : 0.f);
+    o2[j] = gv[j] * xh[j];
+  }
+  *(uint4*)(dx + at) = pack8_rne(o1);
+  *(uint4*)(t + at) = pack8_rne(o2);
+}
 int launch_layernorm_bwd(const void* x, const void* gamma, const void* dy, const void* res, void* dx, void* t, int R,
                          int d, float eps, int bf16, hipStream_t st) {
   dim3 grid((R + 3) / 4), block(256);
+  const uintptr_t al = (uintptr_t)x | (uintptr_t)gamma | (uintptr_t)dy | (uintptr_t)res | (uintptr_t)dx | (uintptr_t)t;
+  if (bf16 && (al & 15) == 0 && (d == 64 || d == 128 || d == 256)) {
+    const int lpr = d / 8, rows_per_block = 4 * (64 / lpr);
+    const dim3 g2((R + rows_per_block - 1) / rows_per_block);
+#define LNB_ROWS(L) hipLaunchKernelGGL((layernorm_bwd_rows_kernel<L>), g2, block, 0, st, (const bf16_t*)x, (const bf16_t*)gamma, \
+                                       (const bf16_t*)dy, (const bf16_t*)res, (bf16_t*)dx, (bf16_t*)t, R, eps)
+    if (lpr == 8) LNB_ROWS(8); else if (lpr == 16) LNB_ROWS(16); else LNB_ROWS(32);
+#undef LNB_ROWS
+    return IM_OK;
+  }
   if (bf16)
     hipLaunchKernelGGL((layernorm_bwd_kernel<bf16_t>), grid, block, 0, st, (const bf16_t*)x, (const bf16_t*)gamma,
                        (const bf16_t*)dy, (const bf16_t*)res, (bf16_t*)dx, (bf16_t*)t, R, d, eps);
