@@ -595,7 +595,7 @@ static LayerTrain layer_train_layout(const im_shape_t* s, int32_t d_ff) {
     p2 = std::max(p2, mfma_wgrad_partial_bytes(d_ff, (int)d, (int)R));
   }
   L.partial = off; off += align256(std::max(p1, p2));
-  L.cpart = off; off += align256(colsum_partial_bytes((int)R, (int)std::max(2 * d, f)));   // two LayerNorm sums at once
+  L.cpart = off; off += align256(colsum_partial_bytes((int)R, (int)std::max(3 * d, f)));   // db2 and two LayerNorm sums at once
   L.aws_bytes = bwd_workspace_bytes(s);
   L.attws = off; off += align256(L.aws_bytes);
   L.ws_total = off;
@@ -704,7 +704,7 @@ int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const g
     g.C[0] = gr->w2; g.ldc = d; g.M = d_ff; g.N = (int)d; g.K = (int)R; g.split_k = L.split_w2; g.partial = partial;
     if ((rc = launch_gemm_alu(g, bf, bf, 0, st))) return rc;
   }
-  if (gr->b2 && (rc = launch_colsum(dy, d, (int)R, (int)d, bf, (float*)gr->b2, cpart, st))) return rc;
+  // (db2 = column sums of dy: taken further down, together with the second LayerNorm's parameter gradients)
   // dz = (dy W2^T) * GELU'(z)
   if (mm) {
     mfma_dgrad(dy, d, p->w2, nullptr, nullptr, d, 0, dz, d_ff, (int)R, d_ff, (int)d, st);
@@ -736,11 +736,11 @@ int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const g
   }
   // dh = dy + LN2 backward(dv)
   if ((rc = launch_layernorm_bwd(h, p->ln2_g, dv, dy, dh, t, (int)R, (int)d, ln_eps, bf, st))) return rc;
-  {  // gradients of the LayerNorm gain and bias: column sums of dy * xhat and of dy
-    const void* src[2] = {t, dv};
-    const long ld2[2] = {d, d};
-    float* out2[2] = {(float*)gr->ln2_g, (float*)gr->ln2_b};
-    if ((rc = launch_colsum_multi(src, ld2, out2, 2, (int)R, (int)d, bf, cpart, st))) return rc;
+  {  // gradients of the LayerNorm gain and bias: column sums of dy * xhat and of dy; and db2 = column sums of dy
+    const void* src[3] = {t, dv, dy};
+    const long ld3[3] = {d, d, d};
+    float* out3[3] = {(float*)gr->ln2_g, (float*)gr->ln2_b, (float*)gr->b2};
+    if ((rc = launch_colsum_multi(src, ld3, out3, 3, (int)R, (int)d, bf, cpart, st))) return rc;
   }
   // h = x + IMAttention(u), u = LN(x; ln1): attention backward with upstream gradient dh; its dx is du (into dv)
   if ((rc = launch_layernorm(x, p->ln1_g, p->ln1_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;

@@ -171,7 +171,7 @@ size_t gemm_alu_partial_bytes(int M, int N, int K, int* split_k);
 
 // column sums of a [R, n] matrix (bias gradients), deterministic two-stage
 int launch_colsum(const void* a, long lda, int R, int n, int a_bf16, float* out, float* partial, hipStream_t st);
-size_t colsum_partial_bytes(int R, int n);   // for one matrix; launch_colsum_multi needs count times as much
+size_t colsum_partial_bytes(int R, int n);   // for one matrix; launch_colsum_multi (count <= 4) needs count times as much
 // column sums of up to 3 [R, n] matrices (same element type) in one pair of launches; out[i] == nullptr skips matrix i
 int launch_colsum_multi(const void* const* a, const long* lda, float* const* out, int count, int R, int n, int a_bf16,
                         float* partial, hipStream_t st);

@@ -351,9 +351,9 @@ int launch_wgrad_small(const void* A, long lda, const void* G, long ldg, int R, 
 // per-block partials ([matrix][row block][n]) the same way with 16 groups x 16 columns.
 constexpr int CS_ROWS = 256;
 struct ColsumArgs {
-  const void* a[3];
-  long lda[3];
-  float* out[3];   // nullptr: this matrix is skipped
+  const void* a[4];
+  long lda[4];
+  float* out[4];   // nullptr: this matrix is skipped
 };
 
 template <typename T>
@@ -406,7 +406,7 @@ int launch_colsum_multi(const void* const* a, const long* lda, float* const* out
                         float* partial, hipStream_t st) {
   ColsumArgs q;
   bool any = false;
-  for (int i = 0; i < 3; ++i) {
+  for (int i = 0; i < 4; ++i) {   // count <= 4
     q.a[i] = i < count ? a[i] : nullptr;
     q.lda[i] = i < count ? lda[i] : 0;
     q.out[i] = i < count ? out[i] : nullptr;

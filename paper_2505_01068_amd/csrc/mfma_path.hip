@@ -40,7 +40,7 @@ static BwdWs bwd_ws(const im_shape_t* s) {
   w.split_o = mfma_gemm_split((int)x.d, (int)x.d, (int)x.R);
   w.partial = off;
   off += al(std::max((size_t)w.split_w * x.d * 3 * x.d, (size_t)w.split_o * x.d * x.d) * 4);
-  w.cpart = off; off += al(3 * colsum_partial_bytes((int)x.R, (int)x.d));   // dbq, dbk, dbv in one launch
+  w.cpart = off; off += al(4 * colsum_partial_bytes((int)x.R, (int)x.d));   // dbo, dbq, dbk, dbv in one launch
   w.total = off;
   return w;
 }
@@ -183,7 +183,6 @@ int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const
     launch_mfma_gemm(p, st);
     launch_splitk_reduce(partial, w.split_o, d, d, (float*)dwo, nullptr, nullptr, 0, st);
   }
-  if (dbo) { ProfScope ps(PF_WGRAD, st); launch_colsum(dy, d, R, d, 1, (float*)dbo, cpart, st); }
 
   launch_mfma_bwd(g, qkv, 3 * d, o, d_o, d, lse2, valid_len, key_pad, delta, dqkv, 3 * d, st);
 
@@ -198,12 +197,12 @@ int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const
     launch_mfma_gemm(p, st);
     launch_splitk_reduce(partial, w.split_w, d, 3 * d, (float*)dwq, (float*)dwk, (float*)dwv, d, st);
   }
-  if (dbq || dbk || dbv) {  // column sums of the dQ | dK | dV column blocks
-    const void* src[3] = {dqkv, dqkv + d, dqkv + 2 * (size_t)d};
-    const long lds3[3] = {3 * (long)d, 3 * (long)d, 3 * (long)d};
-    float* dbs[3] = {(float*)dbq, (float*)dbk, (float*)dbv};
+  if (dbo || dbq || dbk || dbv) {  // column sums of dy and of the dQ | dK | dV column blocks, one pair of launches
+    const void* src[4] = {dy, dqkv, dqkv + d, dqkv + 2 * (size_t)d};
+    const long lds4[4] = {(long)d, 3 * (long)d, 3 * (long)d, 3 * (long)d};
+    float* dbs[4] = {(float*)dbo, (float*)dbq, (float*)dbk, (float*)dbv};
     ProfScope ps(PF_WGRAD, st);
-    launch_colsum_multi(src, lds3, dbs, 3, R, d, 1, cpart, st);
+    launch_colsum_multi(src, lds4, dbs, 4, R, d, 1, cpart, st);
   }
 
   if (dx) {
