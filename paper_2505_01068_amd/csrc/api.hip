@@ -183,7 +183,7 @@ static size_t bwd_workspace_bytes(const im_shape_t* s) {
     pb = std::max(pb, std::max(mfma_wgrad_partial_bytes((int)d, (int)(3 * d), (int)R), mfma_wgrad_partial_bytes((int)d, (int)d, (int)R)));
   if (wgrad_small_ok((int)d, (int)(3 * d), (int)d)) pb = std::max(pb, wgrad_small_partial_bytes((int)d, (int)(3 * d), (int)R));
   n += align256(pb);
-  n += align256(3 * colsum_partial_bytes((int)R, (int)d));            // dbq, dbk, dbv in one launch
+  n += align256(4 * colsum_partial_bytes((int)R, (int)d));            // dbo, dbq, dbk, dbv in one launch
   n += align256(3 * d * d * sizeof(float));                           // sinks for unwanted weight gradients
   return n;
 }
@@ -263,7 +263,7 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
   const bool ws_small = !mm && wgrad_small_ok((int)d, (int)(3 * d), (int)d);
   if (ws_small) pbytes = std::max(pbytes, wgrad_small_partial_bytes((int)d, (int)(3 * d), (int)R));
   float* partial = (float*)b.take(pbytes);
-  float* cpart = (float*)b.take(3 * colsum_partial_bytes((int)R, (int)d));
+  float* cpart = (float*)b.take(4 * colsum_partial_bytes((int)R, (int)d));
   float* sink = (float*)b.take(3 * d * d * sizeof(float));
 
   GemmDesc p;
@@ -294,8 +294,6 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
     ProfScope ps(PF_WGRAD, st);
     if ((rc = launch_gemm_alu(p, bf, bf, 0, st))) return rc;
   }
-  if (dbo) { ProfScope ps(PF_WGRAD, st); if ((rc = launch_colsum(dy, d, (int)R, (int)d, bf, (float*)dbo, cpart, st))) return rc; }
-
   rc = launch_rowlane_bwd(g, bf, qkv, qkv + d * es, qkv + 2 * d * es, 3 * d, o, d_o, d, lse2, valid_len, key_pad,
                           delta, dqkv, dqkv + d * es, dqkv + 2 * d * es, 3 * d, st);
   if (rc) return rc;
@@ -318,12 +316,12 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
     ProfScope ps(PF_WGRAD, st);
     if ((rc = launch_gemm_alu(p, bf, bf, 0, st))) return rc;
   }
-  if (dbq || dbk || dbv) {  // column sums of the dQ | dK | dV column blocks
-    const void* src[3] = {dqkv, dqkv + d * es, dqkv + 2 * d * es};
-    const long lds3[3] = {3 * d, 3 * d, 3 * d};
-    float* dbs[3] = {(float*)dbq, (float*)dbk, (float*)dbv};
+  if (dbo || dbq || dbk || dbv) {  // column sums of dy and of the dQ | dK | dV column blocks, one pair of launches
+    const void* src[4] = {dy, dqkv, dqkv + d * es, dqkv + 2 * d * es};
+    const long lds4[4] = {d, 3 * d, 3 * d, 3 * d};
+    float* dbs[4] = {(float*)dbo, (float*)dbq, (float*)dbk, (float*)dbv};
     ProfScope ps(PF_WGRAD, st);
-    if ((rc = launch_colsum_multi(src, lds3, dbs, 3, (int)R, (int)d, bf, cpart, st))) return rc;
+    if ((rc = launch_colsum_multi(src, lds4, dbs, 4, (int)R, (int)d, bf, cpart, st))) return rc;
   }
   // dx = dQ Wq^T + dK Wk^T + dV Wv^T
   if (dx && mm && d % 64 == 0) {  // the contraction is split over three weights: whole 64-deep k-tiles per weight
