@@ -344,7 +344,7 @@ int launch_wgrad_small(const void* A, long lda, const void* G, long ldg, int R, 
   return blocks;
 }
 
-// Column sums of up to three [R, n] matrices in two deterministic stages (one launch each for all of
+// Column sums of up to four [R, n] matrices in two deterministic stages (one launch each for all of
 // them: blockIdx.z selects the matrix).  Stage 1: a block of 256 threads = 4 row groups x 64 columns
 // sums CS_ROWS rows (thread (g, c): rows r0 + g, r0 + g + 4, ..., with four independent running sums so
 // loads overlap), then the 4 groups are added in a fixed order through LDS.  Stage 2 adds the
