@@ -51,6 +51,30 @@ def test_layer_odd_widths_fp32():
     assert_close(y, ref, TOL["fp32"], "layer odd widths")
 
 
+@pytest.mark.parametrize("d_ff", [200, 64, 320])
+def test_layer_bf16_width_64_hidden_widths(d_ff):
+    # d = 64: the LayerNorms run inside the GEMMs; a hidden width that is a multiple of 64 takes the fused
+    # layer tail (one chunk, five chunks), any other the separate MLP GEMMs with the fused LayerNorm
+    say(f"[case] layer bf16 d=64 d_ff={d_ff}")
+    d, H, seg = 64, 8, (33, 140, 97)
+    g = synth.attention_inputs(2, seg, d, H, "bf16", "key_pad", seed=306, with_dy=False)
+    p = synth.layer_params(d, d_ff, 306, 0, dtype="bf16")
+    y = run_layers(g, [p], oracle.IM_IEM, "bf16", d_ff)
+    ref = oracle.gsit_layer_forward(g["x"], p, seg, oracle.IM_IEM, H, g["scale"], key_pad=g["key_pad"])
+    assert_close(y, ref, TOL["bf16"], f"layer d=64 d_ff={d_ff}")
+
+
+def test_layer_bf16_width_64_in_place_and_ragged_rows():
+    # 2 * 93 = 186 rows: the last 64-row tile of the fused tail holds 58 rows; y written over x
+    say("[case] layer bf16 d=64 in place, ragged last tile")
+    d, H, d_ff, seg = 64, 8, 128, (20, 40, 33)
+    g = synth.attention_inputs(2, seg, d, H, "bf16", "valid_len", seed=307, with_dy=False)
+    p = synth.layer_params(d, d_ff, 307, 0, dtype="bf16", bias=False)
+    y = run_layers(g, [p], oracle.IM_IFM_BACKWARD, "bf16", d_ff, in_place=True)
+    ref = oracle.gsit_layer_forward(g["x"], p, seg, oracle.IM_IFM_BACKWARD, H, g["scale"], valid_len=g["valid_len"])
+    assert_close(y, ref, TOL["bf16"], "layer d=64 in place")
+
+
 def test_layer_identity_when_output_weights_vanish():
     say("[case] layer identity")
     d, H, d_ff, seg = 64, 8, 256, (20, 70, 33)
