@@ -632,18 +632,27 @@ int gsit_layer_fwd_train(const im_shape_t* shape, int32_t d_ff, const void* x, c
   void* zpre = sv + L.zpre;
   void* a = sv + L.a;
 
-  if ((rc = launch_layernorm(x, p->ln1_g, p->ln1_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
+  // at d = 64 both LayerNorms run inside the GEMMs that consume them (see gsit_layer_fwd)
+  auto al16 = [](const void* a0, const void* a1) { return (((uintptr_t)a0 | (uintptr_t)a1) & 15) == 0; };
+  const bool mfma = pick_path(shape) == PATH_MFMA;
+  const bool ln1_fused = mfma && mfma_gemm_fuses_ln(bf, d, 3 * d) && al16(p->ln1_g, p->ln1_b);
+  const bool mlp_mfma = mfma_linear_ok(bf, d, d_ff) && mfma_linear_ok(bf, d_ff, d);
+  const bool ln2_fused = mlp_mfma && mfma_gemm_fuses_ln(bf, d, d_ff) && al16(p->ln2_g, p->ln2_b);
+  if (!ln1_fused && (rc = launch_layernorm(x, p->ln1_g, p->ln1_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
   const SavedLayout A = saved_layout(shape);
-  if (pick_path(shape) == PATH_MFMA)
-    rc = mfma_attention_fwd(shape, u, p->wq, p->wk, p->wv, p->wo, p->bq, p->bk, p->bv, p->bo, valid_len, key_pad, h, x,
-                            sv + L.att, A.qkv, A.o, A.lse, A.extra, ws + L.u + align256((size_t)R * d * (bf ? 2 : 4)), st);
+  if (mfma)
+    rc = mfma_attention_fwd(shape, ln1_fused ? x : u, p->wq, p->wk, p->wv, p->wo, p->bq, p->bk, p->bv, p->bo, valid_len,
+                            key_pad, h, x, sv + L.att, A.qkv, A.o, A.lse, A.extra,
+                            ws + L.u + align256((size_t)R * d * (bf ? 2 : 4)), st,
+                            ln1_fused ? LnArgs{p->ln1_g, p->ln1_b, ln_eps} : LnArgs{nullptr, nullptr, 0.f});
   else
     rc = fwd_rowlane(shape, u, p->wq, p->wk, p->wv, p->wo, p->bq, p->bk, p->bv, p->bo, valid_len, key_pad, h, x,
                      sv + L.att, st);
   if (rc) return rc;
-  if ((rc = launch_layernorm(h, p->ln2_g, p->ln2_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
-  if (mfma_linear_ok(bf, d, d_ff) && mfma_linear_ok(bf, d_ff, d)) {
-    mfma_linear(u, d, p->w1, nullptr, nullptr, d_ff, d_ff, p->b1, nullptr, nullptr, 0, nullptr, zpre, d_ff, (int)R, d_ff, (int)d, st);
+  if (!ln2_fused && (rc = launch_layernorm(h, p->ln2_g, p->ln2_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
+  if (mlp_mfma) {
+    mfma_linear(ln2_fused ? h : u, d, p->w1, nullptr, nullptr, d_ff, d_ff, p->b1, nullptr, nullptr, 0, nullptr, zpre, d_ff,
+                (int)R, d_ff, (int)d, st, ln2_fused ? LnArgs{p->ln2_g, p->ln2_b, ln_eps} : LnArgs{nullptr, nullptr, 0.f});
     if ((rc = launch_gelu_fwd(zpre, a, R * (long)d_ff, bf, st))) return rc;
     mfma_linear(a, d_ff, p->w2, nullptr, nullptr, d, (int)d, p->b2, nullptr, nullptr, 0, h, y, d, (int)R, (int)d, d_ff, st);
     return check_hip("gsit_layer_fwd_train launch");
