@@ -516,9 +516,9 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
   if (!ln1_fused && (rc = launch_layernorm(x, ln1_g, ln1_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
   // h = x + IMAttention(u)
   const SavedLayout L = saved_layout(shape);
-  // At d = 64 on the matrix-core path the rest of the layer after the attention kernel -- output projection,
+  // At d = 64 / 128 on the matrix-core path the rest of the layer after the attention kernel -- output projection,
   // residual, LayerNorm, MLP, residual -- is row-local and runs as ONE kernel on the attention's O rows.
-  const bool tail_fused = mfma && mlp64_ok(bf, d, d_ff, x, ln2_g, ln2_b, w1, w2, y) && (((uintptr_t)wo | (uintptr_t)aw) & 15) == 0;
+  const bool tail_fused = mfma && mlp_tail_ok(bf, d, d_ff, x, ln2_g, ln2_b, w1, w2, y) && (((uintptr_t)wo | (uintptr_t)aw) & 15) == 0;
   if (mfma)
     rc = mfma_attention_fwd(shape, ln1_fused ? x : u, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad,
                             tail_fused ? nullptr : h, x, aw, L.qkv, L.o, L.lse, L.extra, aw + L.total, st,
@@ -528,12 +528,12 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
   if (rc) return rc;
   if (tail_fused) {
     ProfScope ps(PF_MISC, st);
-    launch_mlp64(x, ln2_g, ln2_b, ln_eps, w1, b1, w2, b2, y, (int)R, d_ff, st, aw + L.o, wo, bo);
+    launch_mlp_tail(x, ln2_g, ln2_b, ln_eps, w1, b1, w2, b2, y, (int)R, (int)d, d_ff, st, aw + L.o, wo, bo);
     return check_hip("gsit_layer_fwd launch");
   }
-  if (mlp64_ok(bf, d, d_ff, h, ln2_g, ln2_b, w1, w2, y)) {   // the whole MLP sub-block in one kernel
+  if (mlp_tail_ok(bf, d, d_ff, h, ln2_g, ln2_b, w1, w2, y)) {   // the whole MLP sub-block in one kernel
     ProfScope ps(PF_MISC, st);
-    launch_mlp64(h, ln2_g, ln2_b, ln_eps, w1, b1, w2, b2, y, (int)R, d_ff, st);
+    launch_mlp_tail(h, ln2_g, ln2_b, ln_eps, w1, b1, w2, b2, y, (int)R, (int)d, d_ff, st);
     return check_hip("gsit_layer_fwd launch");
   }
   if (!ln2_fused && (rc = launch_layernorm(h, ln2_g, ln2_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;

@@ -549,77 +549,158 @@ __global__ __launch_bounds__(NWV * 64) void mfma_gemm_dma_kernel(MGemm p) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Whole MLP sub-block of an encoder layer at model width 64 in one kernel:
-//   y = h + GELU(LN(h) W1 + b1) W2 + b2        (h [R, 64], W1 [64, d_ff], W2 [d_ff, 64], d_ff % 64 == 0)
+// Whole MLP sub-block of an encoder layer at model width D = 64 or 128 in one kernel:
+//   y = h + GELU(LN(h) W1 + b1) W2 + b2        (h [R, D], W1 [D, d_ff], W2 [d_ff, D], d_ff % 64 == 0)
 // and, with PROJ, also the attention's output projection and residual in front of it:
-//   h = x + O Wo + bo                          (O, x [R, 64]; h is rounded to bf16 and kept in LDS only)
+//   h = x + O Wo + bo                          (O, x [R, D]; h is rounded to bf16 and kept in LDS only)
 // A workgroup owns 64 rows.  The hidden layer is walked in chunks of 64 columns: the chunk
 // z_j = GELU(LN(h) W1[:, j] + b1[j]) (64 x 64) goes to LDS as bf16 and is at once multiplied into the
-// 64 x 64 output accumulator with W2[j, :], so the [R, d_ff] activation never exists in memory and the
-// three launches LayerNorm, first GEMM, second GEMM become one.  Four waves in a 2 x 2 grid, each 32 x 32
-// of both products; the same transposed-product tiles as mfma_gemm_kernel (lane owns an output row).
-struct Mlp64Args {
+// 64 x D output accumulator with W2[j, :], so the [R, d_ff] activation never exists in memory and the
+// launches output projection, LayerNorm, first GEMM, second GEMM become one.  Four waves in a 2 x 2 grid: each
+// owns 32 x 32 of a z chunk and 32 x D/2 of the output; the same transposed-product tiles as
+// mfma_gemm_kernel (a lane owns an output row; registers 4i..4i+3 are columns 8i + 4hi + 0..3 of a 32-column block).
+struct MlpTailArgs {
   const bf16_t* h; const bf16_t* ln_g; const bf16_t* ln_b; float ln_eps;
   const bf16_t* w1; const bf16_t* b1; const bf16_t* w2; const bf16_t* b2;
   bf16_t* y; int R, d_ff;
   const bf16_t* o; const bf16_t* wo; const bf16_t* bo;   // PROJ: h above is x, the residual of the projection
 };
-template <bool PROJ>
-__global__ __launch_bounds__(256) void mlp64_kernel(Mlp64Args p) {
-  __shared__ __attribute__((aligned(16))) bf16_t sA[64 * LDS_LD], sW1[64 * LDS_LD], sW2[64 * LDS_LD], sZ[64 * LDS_LD];
-  __shared__ __attribute__((aligned(16))) bf16_t sH[PROJ ? 64 * LDS_LD : 8];
+// ROWS x COLS bf16 tile as 16-byte chunks, chunk (tid + 256 u): row = chunk / (COLS / 8), so the COLS / 8 lanes that
+// hold a row are consecutive.  Rows are clamped to rmax.
+template <int ROWS, int COLS>
+struct ChunkTile {
+  static constexpr int CPR = COLS / 8, N = ROWS * CPR / 256;
+  u32x4 v[N];
+  __device__ __forceinline__ void load(const bf16_t* base, long ld, int r0, int rmax, int tid) {
+#pragma unroll
+    for (int u = 0; u < N; ++u) {
+      const int idx = tid + u * 256, r = idx / CPR, c = (idx % CPR) * 8;
+      v[u] = *(const u32x4*)(base + (long)min(r0 + r, rmax) * ld + c);
+    }
+  }
+  __device__ __forceinline__ void store(bf16_t* lds, int ld, int tid) const {
+#pragma unroll
+    for (int u = 0; u < N; ++u) {
+      const int idx = tid + u * 256, r = idx / CPR, c = (idx % CPR) * 8;
+      *(u32x4*)(lds + r * ld + c) = v[u];
+    }
+  }
+  __device__ __forceinline__ void load_lds(const bf16_t* lds, int ld, int tid) {
+#pragma unroll
+    for (int u = 0; u < N; ++u) {
+      const int idx = tid + u * 256, r = idx / CPR, c = (idx % CPR) * 8;
+      v[u] = *(const u32x4*)(lds + r * ld + c);
+    }
+  }
+  // LayerNorm of every row (COLS = the whole feature row): two-pass in fp32, as the stand-alone kernel
+  __device__ __forceinline__ void layernorm(const bf16_t* gamma, const bf16_t* beta, float eps, int tid) {
+    const int c = (tid % CPR) * 8;
+    const u32x4 gr = *(const u32x4*)(gamma + c), br = *(const u32x4*)(beta + c);
+#pragma unroll
+    for (int u = 0; u < N; ++u) {
+      float x[8];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { x[2 * j] = __uint_as_float(v[u][j] << 16); x[2 * j + 1] = __uint_as_float(v[u][j] & 0xffff0000u); }
+      float s = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) s += x[j];
+#pragma unroll
+      for (int o = CPR / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+      const float mu = s * (1.f / COLS);
+      float q = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { const float w = x[j] - mu; q = fmaf(w, w, q); }
+#pragma unroll
+      for (int o = CPR / 2; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+      const float rstd = rsqrtf(q * (1.f / COLS) + eps);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float a = (x[2 * j] - mu) * rstd * __uint_as_float(gr[j] << 16) + __uint_as_float(br[j] << 16);
+        const float b = (x[2 * j + 1] - mu) * rstd * __uint_as_float(gr[j] & 0xffff0000u) + __uint_as_float(br[j] & 0xffff0000u);
+        v[u][j] = pack_bf16(a, b);
+      }
+    }
+  }
+};
+__device__ __forceinline__ bf16x8 frag_rows(const bf16_t* lds, int ld, int row, int col) {  // m-major operand fragment
+  return as_bf16x8(*(const u32x4*)(lds + row * ld + col));
+}
+template <int D, bool PROJ>
+__global__ __launch_bounds__(256) void mlp_tail_kernel(MlpTailArgs p) {
+  constexpr int LDD = D + 8, LDC = 64 + 8;   // row strides (bf16) of tiles with D resp. 64 columns
+  constexpr int NB = D / 64;                 // 32-column output blocks per wave
+  __shared__ __attribute__((aligned(16))) bf16_t sA[64 * LDD];    // LN(h) rows
+  __shared__ __attribute__((aligned(16))) bf16_t sW1[D * LDC];    // W1 chunk: rows k < D, 64 hidden columns
+  __shared__ __attribute__((aligned(16))) bf16_t sW2[64 * LDD];   // W2 chunk: rows k < 64, D columns (PROJ: a Wo chunk)
+  __shared__ __attribute__((aligned(16))) bf16_t sZ[64 * LDC];    // z chunk rows (PROJ: a 64-column chunk of O)
+  __shared__ __attribute__((aligned(16))) bf16_t sH[PROJ ? 64 * LDD : 8];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int wm = wave >> 1, wn = wave & 1;
   const int m0 = blockIdx.x * 64;
-  TileRegs<2> ta, t1, t2;
+  const int row = wm * 32 + lo;              // the output row of this lane inside the tile
+  ChunkTile<64, D> ta;
+  ChunkTile<D, 64> t1;
+  ChunkTile<64, D> t2;
   if constexpr (PROJ) {
-    // h = x + O Wo + bo for the 64 rows, through the same tiles: O -> sA, Wo -> sW1, h (bf16) -> sH
-    load_mm(ta, p.o, 64, m0, p.R - 1, 0, 64, tid);
-    load_mm(t1, p.wo, 64, 0, 63, 0, 64, tid);
-    store_mm(ta, sA, tid);
-    store_mm(t1, sW1, tid);
-    __syncthreads();
-    f32x16 acc;
+    // h = x + O Wo + bo, the contraction in chunks of 64: O chunk -> sZ, Wo chunk -> sW2, h (bf16) -> sH
+    f32x16 acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[nb][4 * i + j] = p.bo ? bf2f(p.bo[wn * (D / 2) + nb * 32 + 8 * i + 4 * hi + j]) : 0.f;
+    for (int kc = 0; kc < D / 64; ++kc) {
+      ChunkTile<64, 64> to;
+      to.load(p.o + kc * 64, D, m0, p.R - 1, tid);
+      t2.load(p.wo + (long)kc * 64 * D, D, 0, 63, tid);
+      if (kc) __syncthreads();
+      to.store(sZ, LDC, tid);
+      t2.store(sW2, LDD, tid);
+      __syncthreads();
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const bf16x8 fa = frag_rows(sZ, LDC, row, s * 16 + hi * 8);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[nb] = mfma32(lds_frag_tr(sW2, LDD, s * 16, wn * (D / 2) + nb * 32, lane), fa, acc[nb]);
+      }
+    }
+    const int mr = min(m0 + row, p.R - 1);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int n = wn * (D / 2) + nb * 32 + 8 * i + 4 * hi;
+        const u32x2 rv = *(const u32x2*)(p.h + (long)mr * D + n);
+        const u32x2 pk = {pack_bf16(acc[nb][4 * i] + __uint_as_float(rv[0] << 16), acc[nb][4 * i + 1] + __uint_as_float(rv[0] & 0xffff0000u)),
+                          pack_bf16(acc[nb][4 * i + 2] + __uint_as_float(rv[1] << 16), acc[nb][4 * i + 3] + __uint_as_float(rv[1] & 0xffff0000u))};
+        *(u32x2*)(sH + row * LDD + n) = pk;
+      }
+    __syncthreads();  // sH complete; every wave is done with sZ and sW2
+    ta.load_lds(sH, LDD, tid);
+  } else {
+    ta.load(p.h, D, m0, p.R - 1, tid);
+  }
+  ta.layernorm(p.ln_g, p.ln_b, p.ln_eps, tid);
+  ta.store(sA, LDD, tid);
+  const int nchunk = p.d_ff / 64;
+  auto fetch = [&](int j) {   // W1[:, 64 j .. 64 j + 63] (rows = k < D) and W2[64 j .. 64 j + 63, :] (rows = k < 64)
+    t1.load(p.w1 + j * 64, p.d_ff, 0, D - 1, tid);
+    t2.load(p.w2 + (long)j * 64 * D, D, 0, 63, tid);
+  };
+  fetch(0);
+  // output accumulators: row `row`, block nb = columns wn * D/2 + 32 nb + ...; they start at b2
+  f32x16 acc2[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[4 * i + j] = p.bo ? bf2f(p.bo[wn * 32 + 8 * i + 4 * hi + j]) : 0.f;
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-      acc = mfma32(lds_frag_tr(sW1, LDS_LD, s * 16, wn * 32, lane), lds_frag(sA, wm * 32 + lo, s * 16 + hi * 8), acc);
-    const int mr = min(m0 + wm * 32 + lo, p.R - 1);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int n = wn * 32 + 8 * i + 4 * hi;
-      const u32x2 rv = *(const u32x2*)(p.h + (long)mr * 64 + n);
-      const u32x2 pk = {pack_bf16(acc[4 * i] + __uint_as_float(rv[0] << 16), acc[4 * i + 1] + __uint_as_float(rv[0] & 0xffff0000u)),
-                        pack_bf16(acc[4 * i + 2] + __uint_as_float(rv[1] << 16), acc[4 * i + 3] + __uint_as_float(rv[1] & 0xffff0000u))};
-      *(u32x2*)(sH + (wm * 32 + lo) * LDS_LD + n) = pk;
-    }
-    __syncthreads();  // sH complete; every wave is done with sA and sW1
-#pragma unroll
-    for (int u = 0; u < 2; ++u) ta.v[u] = *(const u32x4*)(sH + ((tid >> 3) + u * 32) * LDS_LD + (tid & 7) * 8);
-  } else {
-    load_mm(ta, p.h, 64, m0, p.R - 1, 0, 64, tid);
-  }
-  ln_tile_rows(ta, p.ln_g, p.ln_b, p.ln_eps, tid);
-  store_mm(ta, sA, tid);
-  const int nchunk = p.d_ff / 64;
-  auto fetch = [&](int j) {   // W1[:, 64 j .. 64 j + 63] (rows = k) and W2[64 j .. 64 j + 63, :] (rows = k)
-    load_mm(t1, p.w1 + j * 64, p.d_ff, 0, 63, 0, 64, tid);
-    load_mm(t2, p.w2 + (long)j * 64 * 64, 64, 0, 63, 0, 64, tid);
-  };
-  fetch(0);
-  // output accumulator: rows wm*32 + lo, registers 4i..4i+3 = columns wn*32 + 8i + 4hi + 0..3; starts at b2
-  f32x16 acc2;
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc2[4 * i + j] = p.b2 ? bf2f(p.b2[wn * 32 + 8 * i + 4 * hi + j]) : 0.f;
+      for (int j = 0; j < 4; ++j) acc2[nb][4 * i + j] = p.b2 ? bf2f(p.b2[wn * (D / 2) + nb * 32 + 8 * i + 4 * hi + j]) : 0.f;
   for (int c = 0; c < nchunk; ++c) {
     __syncthreads();  // the previous chunk's W1, W2 and z tiles have been read (first pass: sA is complete)
-    store_mm(t1, sW1, tid);
-    store_mm(t2, sW2, tid);
+    t1.store(sW1, LDC, tid);
+    t2.store(sW2, LDD, tid);
     __syncthreads();
     if (c + 1 < nchunk) fetch(c + 1);
     f32x16 acc1;
@@ -628,44 +709,55 @@ __global__ __launch_bounds__(256) void mlp64_kernel(Mlp64Args p) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc1[4 * i + j] = p.b1 ? bf2f(p.b1[c * 64 + wn * 32 + 8 * i + 4 * hi + j]) : 0.f;
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
-      acc1 = mfma32(lds_frag_tr(sW1, LDS_LD, s * 16, wn * 32, lane), lds_frag(sA, wm * 32 + lo, s * 16 + hi * 8), acc1);
+    for (int s = 0; s < D / 16; ++s)
+      acc1 = mfma32(lds_frag_tr(sW1, LDC, s * 16, wn * 32, lane), frag_rows(sA, LDD, row, s * 16 + hi * 8), acc1);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const u32x2 pk = {pack_bf16(gelu_erf_f(acc1[4 * i]), gelu_erf_f(acc1[4 * i + 1])),
                         pack_bf16(gelu_erf_f(acc1[4 * i + 2]), gelu_erf_f(acc1[4 * i + 3]))};
-      *(u32x2*)(sZ + (wm * 32 + lo) * LDS_LD + wn * 32 + 8 * i + 4 * hi) = pk;
+      *(u32x2*)(sZ + row * LDC + wn * 32 + 8 * i + 4 * hi) = pk;
     }
     __syncthreads();  // z chunk complete
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
-      acc2 = mfma32(lds_frag_tr(sW2, LDS_LD, s * 16, wn * 32, lane), lds_frag(sZ, wm * 32 + lo, s * 16 + hi * 8), acc2);
+    for (int s = 0; s < 4; ++s) {
+      const bf16x8 fa = frag_rows(sZ, LDC, row, s * 16 + hi * 8);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) acc2[nb] = mfma32(lds_frag_tr(sW2, LDD, s * 16, wn * (D / 2) + nb * 32, lane), fa, acc2[nb]);
+    }
   }
-  const int m = m0 + wm * 32 + lo;
+  const int m = m0 + row;
   if (m >= p.R) return;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int n = wn * 32 + 8 * i + 4 * hi;
-    // residual: the rows before the LayerNorm
-    const u32x2 rv = PROJ ? *(const u32x2*)(sH + (wm * 32 + lo) * LDS_LD + n) : *(const u32x2*)(p.h + (long)m * 64 + n);
-    const u32x2 pk = {pack_bf16(acc2[4 * i] + __uint_as_float(rv[0] << 16), acc2[4 * i + 1] + __uint_as_float(rv[0] & 0xffff0000u)),
-                      pack_bf16(acc2[4 * i + 2] + __uint_as_float(rv[1] << 16), acc2[4 * i + 3] + __uint_as_float(rv[1] & 0xffff0000u))};
-    *(u32x2*)(p.y + (long)m * 64 + n) = pk;
-  }
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int n = wn * (D / 2) + nb * 32 + 8 * i + 4 * hi;
+      // residual: the rows before the LayerNorm
+      const u32x2 rv = PROJ ? *(const u32x2*)(sH + row * LDD + n) : *(const u32x2*)(p.h + (long)m * D + n);
+      const u32x2 pk = {pack_bf16(acc2[nb][4 * i] + __uint_as_float(rv[0] << 16), acc2[nb][4 * i + 1] + __uint_as_float(rv[0] & 0xffff0000u)),
+                        pack_bf16(acc2[nb][4 * i + 2] + __uint_as_float(rv[1] << 16), acc2[nb][4 * i + 3] + __uint_as_float(rv[1] & 0xffff0000u))};
+      *(u32x2*)(p.y + (long)m * D + n) = pk;
+    }
 }
-bool mlp64_ok(int is_bf16, long d, long d_ff, const void* h, const void* ln_g, const void* ln_b, const void* w1,
-              const void* w2, const void* y) {
+bool mlp_tail_ok(int is_bf16, long d, long d_ff, const void* h, const void* ln_g, const void* ln_b, const void* w1,
+                 const void* w2, const void* y) {
   const uintptr_t a = (uintptr_t)h | (uintptr_t)ln_g | (uintptr_t)ln_b | (uintptr_t)w1 | (uintptr_t)w2 | (uintptr_t)y;
-  return is_bf16 && d == 64 && d_ff >= 64 && d_ff % 64 == 0 && (a & 15) == 0;
+  return is_bf16 && (d == 64 || d == 128) && d_ff >= 64 && d_ff % 64 == 0 && (a & 15) == 0;
 }
-void launch_mlp64(const void* h, const void* ln_g, const void* ln_b, float ln_eps, const void* w1, const void* b1,
-                  const void* w2, const void* b2, void* y, int R, int d_ff, hipStream_t st, const void* o,
-                  const void* wo, const void* bo) {
-  Mlp64Args p = {(const bf16_t*)h, (const bf16_t*)ln_g, (const bf16_t*)ln_b, ln_eps, (const bf16_t*)w1, (const bf16_t*)b1,
-                 (const bf16_t*)w2, (const bf16_t*)b2, (bf16_t*)y, R, d_ff, (const bf16_t*)o, (const bf16_t*)wo,
-                 (const bf16_t*)bo};
-  if (o) hipLaunchKernelGGL(mlp64_kernel<true>, dim3((R + 63) / 64), dim3(256), 0, st, p);
-  else hipLaunchKernelGGL(mlp64_kernel<false>, dim3((R + 63) / 64), dim3(256), 0, st, p);
+void launch_mlp_tail(const void* h, const void* ln_g, const void* ln_b, float ln_eps, const void* w1, const void* b1,
+                     const void* w2, const void* b2, void* y, int R, int d, int d_ff, hipStream_t st, const void* o,
+                     const void* wo, const void* bo) {
+  MlpTailArgs p = {(const bf16_t*)h, (const bf16_t*)ln_g, (const bf16_t*)ln_b, ln_eps, (const bf16_t*)w1, (const bf16_t*)b1,
+                   (const bf16_t*)w2, (const bf16_t*)b2, (bf16_t*)y, R, d_ff, (const bf16_t*)o, (const bf16_t*)wo,
+                   (const bf16_t*)bo};
+  const dim3 grid((R + 63) / 64), block(256);
+  if (d == 64) {
+    if (o) hipLaunchKernelGGL((mlp_tail_kernel<64, true>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((mlp_tail_kernel<64, false>), grid, block, 0, st, p);
+  } else {
+    if (o) hipLaunchKernelGGL((mlp_tail_kernel<128, true>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((mlp_tail_kernel<128, false>), grid, block, 0, st, p);
+  }
 }
 
 // partial[z][M][N] -> out (fp32), z summed in fixed order; output column blocks may go to 3 matrices.

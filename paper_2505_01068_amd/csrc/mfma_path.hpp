@@ -42,14 +42,14 @@ void mfma_wgrad(const void* A, long lda, const void* G, long ldg, float* o0, flo
 void mfma_linear(const void* A, long lda, const void* w0, const void* w1, const void* w2, long ldb, int n_per,
                  const void* b0, const void* b1, const void* b2, int gelu, const void* res, void* C, long ldc, int M,
                  int N, int K, hipStream_t st, LnArgs ln = {nullptr, nullptr, 0.f});
-// y = h + GELU(LayerNorm(h) W1 + b1) W2 + b2 in one kernel at model width 64 (bf16, d_ff % 64 == 0,
+// y = h + GELU(LayerNorm(h) W1 + b1) W2 + b2 in one kernel at model width 64 or 128 (bf16, d_ff % 64 == 0,
 // 16-byte aligned pointers; b1 / b2 may be NULL)
-bool mlp64_ok(int is_bf16, long d, long d_ff, const void* h, const void* ln_g, const void* ln_b, const void* w1,
-              const void* w2, const void* y);
+bool mlp_tail_ok(int is_bf16, long d, long d_ff, const void* h, const void* ln_g, const void* ln_b, const void* w1,
+                 const void* w2, const void* y);
 // o != NULL: h is computed in the kernel as x + o Wo + bo, with x passed as `h` (o, Wo 16-byte aligned; bo may be NULL)
-void launch_mlp64(const void* h, const void* ln_g, const void* ln_b, float ln_eps, const void* w1, const void* b1,
-                  const void* w2, const void* b2, void* y, int R, int d_ff, hipStream_t st, const void* o = nullptr,
-                  const void* wo = nullptr, const void* bo = nullptr);
+void launch_mlp_tail(const void* h, const void* ln_g, const void* ln_b, float ln_eps, const void* w1, const void* b1,
+                     const void* w2, const void* b2, void* y, int R, int d, int d_ff, hipStream_t st,
+                     const void* o = nullptr, const void* wo = nullptr, const void* bo = nullptr);
 int mfma_gemm_split(int M, int N, int K);
 void launch_splitk_reduce(const float* partial, int split_k, int M, int N, float* o0, float* o1, float* o2, int n_per,
                           hipStream_t st);

@@ -64,6 +64,19 @@ def test_layer_bf16_width_64_hidden_widths(d_ff):
     assert_close(y, ref, TOL["bf16"], f"layer d=64 d_ff={d_ff}")
 
 
+@pytest.mark.parametrize("d_ff", [512, 192, 200])
+def test_layer_bf16_width_128(d_ff):
+    # d = 128 (head dim 16): hidden widths that are multiples of 64 take the fused layer tail (two 64-deep
+    # chunks of the output projection, 8 resp. 3 hidden chunks), 200 the separate kernels
+    say(f"[case] layer bf16 d=128 d_ff={d_ff}")
+    d, H, seg = 128, 8, (33, 140, 97)
+    g = synth.attention_inputs(2, seg, d, H, "bf16", "valid_len", seed=308, with_dy=False)
+    p = synth.layer_params(d, d_ff, 308, 0, dtype="bf16")
+    y = run_layers(g, [p], oracle.IM_IFM_FORWARD, "bf16", d_ff)
+    ref = oracle.gsit_layer_forward(g["x"], p, seg, oracle.IM_IFM_FORWARD, H, g["scale"], valid_len=g["valid_len"])
+    assert_close(y, ref, TOL["bf16"], f"layer d=128 d_ff={d_ff}")
+
+
 def test_layer_bf16_width_64_in_place_and_ragged_rows():
     # 2 * 93 = 186 rows: the last 64-row tile of the fused tail holds 58 rows; y written over x
     say("[case] layer bf16 d=64 in place, ragged last tile")
