@@ -137,6 +137,26 @@ int im_attention_bwd(const im_shape_t* shape, const void* x, const void* wq, con
                      const void* dy, void* dx, void* dwq, void* dwk, void* dwv, void* dwo, void* dbq, void* dbk,
                      void* dbv, void* dbo, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* im_attention_fwd (inference: nothing saved) for callers that cannot allocate or pass device scratch
+ * memory -- code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * projected Q, K, V, the attention output before W_o and the row statistics live in a buffer that is
+ * part of the library image: IM_NOALLOC_MAX_BYTES per GPU, held from library load until the process
+ * ends.  The call allocates nothing (no hipMalloc / hipFree, no allocating library routine) and
+ * returns IM_ERR_WORKSPACE -- before anything is enqueued -- for a shape whose
+ * im_attention_sizes workspace exceeds IM_NOALLOC_MAX_BYTES.  Arguments, results and errors are
+ * otherwise those of im_attention_fwd with saved = NULL; the output is bitwise the same.
+ * All calls on one GPU share that GPU's buffer: calls that may overlap in time on one GPU (different
+ * streams or host threads) race and must be serialised by the caller.  Nothing in the buffer needs
+ * to start at zero (every part is written before it is read), so the previous call's contents are
+ * harmless.  im_noalloc_init looks up the buffer's address on the CURRENT device (hipGetSymbolAddress,
+ * once per device); it is optional -- the first call on a device does the same -- but a caller that
+ * captures a graph should make it before the capture begins.  Host-side state is mutex-protected. */
+#define IM_NOALLOC_MAX_BYTES (64u << 20)
+int im_noalloc_init(void);
+int im_attention_fwd_noalloc(const im_shape_t* shape, const void* x, const void* wq, const void* wk, const void* wv,
+                             const void* wo, const void* bq, const void* bk, const void* bv, const void* bo,
+                             const int32_t* valid_len, const uint8_t* key_pad, void* y, void* hip_stream);
+
 /* One GsiT encoder layer, a = MLP o MHSA_2 (Sec. 5 Eq. "allmodalinone fusion";
  * MLP weights W_1 [d, d_ff], W_2 [d_ff, d] as in App. B), in the pre-LayerNorm
  * residual form:  h = x + IMAttention(LN(x; ln1)),  y = h + GELU(LN(h; ln2) W_1 + b_1) W_2 + b_2

@@ -57,6 +57,8 @@ def lib():
         L.im_attention_sizes.argtypes = [shp, C.POINTER(sz), C.POINTER(sz)]
         L.im_attention_fwd.argtypes = [shp] + [vp] * 14 + [sz, vp]
         L.im_attention_bwd.argtypes = [shp] + [vp] * 19 + [sz, vp]
+        L.im_attention_fwd_noalloc.argtypes = [shp] + [vp] * 13
+        L.im_noalloc_init.argtypes = []
         L.gsit_layer_sizes.argtypes = [shp, C.c_int32, C.POINTER(sz)]
         L.gsit_layer_fwd.argtypes = [shp, C.c_int32] + [vp] * 17 + [C.c_float] + [vp] * 4 + [sz, vp]
         L.im_profile_enable.argtypes = [C.c_int]
@@ -72,6 +74,7 @@ def lib():
         L.gsit_model_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_size_t, C.c_void_p]
         for f in (L.im_schedule_build, L.im_attention_sizes, L.im_attention_fwd, L.im_attention_bwd,
+                  L.im_attention_fwd_noalloc, L.im_noalloc_init,
                   L.gsit_layer_sizes, L.gsit_layer_fwd, L.gsit_model_sizes, L.gsit_model_fwd,
                   L.gsit_layer_train_sizes, L.gsit_layer_fwd_train, L.gsit_layer_bwd):
             f.restype = C.c_int
@@ -138,6 +141,21 @@ def im_attention_fwd(shape, x, wq, wk, wv, wo, bq=None, bk=None, bv=None, bo=Non
     _check(lib().im_attention_fwd(C.byref(shape), _p(x), _p(wq), _p(wk), _p(wv), _p(wo), _p(bq), _p(bk), _p(bv),
                                   _p(bo), _p(valid_len), _p(key_pad), _p(y), _p(saved), _p(workspace), wbytes,
                                   _stream()))
+    return y
+
+
+IM_NOALLOC_MAX_BYTES = 64 << 20
+
+
+def im_noalloc_init():
+    _check(lib().im_noalloc_init())
+
+
+def im_attention_fwd_noalloc(shape, x, wq, wk, wv, wo, bq=None, bk=None, bv=None, bo=None, valid_len=None,
+                             key_pad=None, y=None):
+    """Inference forward on the library's built-in scratch buffer; `y` must be given (nothing is allocated)."""
+    _check(lib().im_attention_fwd_noalloc(C.byref(shape), _p(x), _p(wq), _p(wk), _p(wv), _p(wo), _p(bq), _p(bk),
+                                          _p(bv), _p(bo), _p(valid_len), _p(key_pad), _p(y), _stream()))
     return y
 
 

@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 
 #include "common.hpp"
 #include "mfma_path.hpp"
@@ -189,6 +190,31 @@ static size_t bwd_workspace_bytes(const im_shape_t* s) {
 }
 
 static hipStream_t as_stream(void* p) { return (hipStream_t)p; }
+
+// ---- scratch memory of the allocation-free entry point ----
+// One file-scope device array per GPU the library is loaded on (held until the process ends).  In host
+// code the array's NAME is only a stand-in for the symbol: the device address is looked up once per
+// device with hipGetSymbolAddress and that pointer is what kernels and copies receive.
+static __device__ __align__(256) unsigned char scratch[IM_NOALLOC_MAX_BYTES];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mu;
+
+static int scratch_of_current_device(char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(IM_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(IM_ERR_UNSUPPORTED, "device index %d outside 0..%d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail(IM_ERR_HIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = (char*)g_scratch_ptr[dev];
+  return IM_OK;
+}
 
 // ---------------------------------------------------------------------------------------------
 // forward on the ALU path; `res` (same layout as y) is added to y when not NULL.
@@ -455,6 +481,39 @@ int im_attention_bwd(const im_shape_t* shape, const void* x, const void* wq, con
                               as_stream(hip_stream));
   return bwd_rowlane(shape, x, wq, wk, wv, wo, valid_len, key_pad, (const char*)saved, dy, dx, dwq, dwk, dwv, dwo, dbq,
                      dbk, dbv, dbo, (char*)workspace, as_stream(hip_stream));
+}
+
+int im_noalloc_init(void) {
+  char* p = nullptr;
+  return scratch_of_current_device(&p);
+}
+
+int im_attention_fwd_noalloc(const im_shape_t* shape, const void* x, const void* wq, const void* wk, const void* wv,
+                             const void* wo, const void* bq, const void* bk, const void* bv, const void* bo,
+                             const int32_t* valid_len, const uint8_t* key_pad, void* y, void* hip_stream) {
+  int rc = validate_shape(shape);
+  if (rc) return rc;
+  if ((rc = check_supported(shape))) return rc;
+  if (shape->cu_rows && valid_len) return fail(IM_ERR_INVALID, "packed rows carry the lengths in cu_rows: valid_len must be NULL");
+  if (!x || !wq || !wk || !wv || !wo || !y) return fail(IM_ERR_INVALID, "x, wq, wk, wv, wo and y must not be NULL");
+  const SavedLayout L = saved_layout(shape);
+  const Path path = pick_path(shape);
+  size_t need = L.total;
+  if (path == PATH_MFMA) need += mfma_fwd_workspace_bytes(shape->d_model);
+  if (need > (size_t)IM_NOALLOC_MAX_BYTES)
+    return fail(IM_ERR_WORKSPACE,
+                "im_attention_fwd_noalloc: this shape needs %zu bytes of scratch, the built-in buffer holds %zu "
+                "(IM_NOALLOC_MAX_BYTES); use im_attention_fwd with a caller workspace",
+                need, (size_t)IM_NOALLOC_MAX_BYTES);
+  char* sv = nullptr;
+  if ((rc = scratch_of_current_device(&sv))) return rc;
+  // Q|K|V, O and the row statistics are all written before they are read (query segments without a live
+  // block are zero-filled by a kernel), so nothing left in the buffer by an earlier call matters.
+  if (path == PATH_MFMA)
+    return mfma_attention_fwd(shape, x, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, y, nullptr, sv, L.qkv,
+                              L.o, L.lse, L.extra, sv + L.total, as_stream(hip_stream));
+  return fwd_rowlane(shape, x, wq, wk, wv, wo, bq, bk, bv, bo, valid_len, key_pad, y, nullptr, sv,
+                     as_stream(hip_stream));
 }
 
 static int layer_check(const im_shape_t* shape, int32_t d_ff) {

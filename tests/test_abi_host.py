@@ -19,7 +19,7 @@ def test_every_declared_symbol_is_exported():
     names = re.findall(r"^\s*(?:const\s+char\s*\*|int)\s+(\w+)\s*\(", hdr, flags=re.M)
     assert set(names) >= {"im_attention_fwd", "im_attention_bwd", "gsit_layer_fwd", "im_attention_sizes",
                           "gsit_layer_sizes", "gsit_model_sizes", "gsit_model_fwd", "im_schedule_build", "im_last_error",
-                          "im_version"}
+                          "im_version", "im_attention_fwd_noalloc", "im_noalloc_init"}
     L = B.lib()
     for n in names:
         assert hasattr(L, n), n
