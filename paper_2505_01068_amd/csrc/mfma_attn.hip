@@ -106,10 +106,13 @@ struct RingLane {
   int trow0, trow1;
   unsigned col0, col1;
 };
+// NW = waves per workgroup: with 4 waves a lane fills chunk positions in two tile rows (trow0, trow0 + 32) of
+// each streamed matrix, with 8 waves in one row (trow1 / col1 unused).
+template <int NW = 4>
 __device__ __forceinline__ RingLane ring_lane(int wave, int lane, int h) {
   RingLane r;
   r.trow0 = wave * 8 + (lane >> 3);
-  r.trow1 = r.trow0 + 32;
+  r.trow1 = NW == 4 ? r.trow0 + 32 : r.trow0;
   r.col0 = (unsigned)(h * 64 + (((lane & 7) ^ sw_f(r.trow0)) << 3)) * 2u;
   r.col1 = (unsigned)(h * 64 + (((lane & 7) ^ sw_f(r.trow1)) << 3)) * 2u;
   return r;
@@ -128,33 +131,43 @@ __device__ __forceinline__ RingLaneOff ring_lane_off(const RingLane& rl, unsigne
   return {__umul24((unsigned)rl.trow0, pitch_a) + rl.col0, __umul24((unsigned)rl.trow0, pitch_b) + rl.col0,
           __umul24((unsigned)rl.trow1, pitch_a) + rl.col1, __umul24((unsigned)rl.trow1, pitch_b) + rl.col1};
 }
-// Request the next 64-row tile pair of the segment into LDS stage `stage` (4 copies per wave; row
-// pitches in bytes) and advance the feed.  Only the last tile of a segment can be ragged; its
+// Request the next 64-row tile pair of the segment into LDS stage `stage` (4 copies per wave with 4 waves, 2
+// with 8; row pitches in bytes) and advance the feed.  Only the last tile of a segment can be ragged; its
 // missing rows repeat the segment's last row.
+template <int NW = 4>
 __device__ __forceinline__ void ring_feed_issue(const RingLane& rl, const RingLaneOff& lo, RingFeed& f, unsigned pitch_a,
                                                 unsigned pitch_b, int wave, bf16_t* stage) {
   if (f.rows >= KT) {
     dma16_off(f.a, lo.a0, stage + wave * 512);
     dma16_off(f.b, lo.b0, stage + KT * SW_LD + wave * 512);
-    dma16_off(f.a, lo.a1, stage + (4 + wave) * 512);
-    dma16_off(f.b, lo.b1, stage + KT * SW_LD + (4 + wave) * 512);
+    if (NW == 4) {
+      dma16_off(f.a, lo.a1, stage + (4 + wave) * 512);
+      dma16_off(f.b, lo.b1, stage + KT * SW_LD + (4 + wave) * 512);
+    }
   } else {
     const unsigned r0c = (unsigned)min(rl.trow0, f.rows - 1), r1c = (unsigned)min(rl.trow1, f.rows - 1);
     dma16_off(f.a, __umul24(r0c, pitch_a) + rl.col0, stage + wave * 512);
     dma16_off(f.b, __umul24(r0c, pitch_b) + rl.col0, stage + KT * SW_LD + wave * 512);
-    dma16_off(f.a, __umul24(r1c, pitch_a) + rl.col1, stage + (4 + wave) * 512);
-    dma16_off(f.b, __umul24(r1c, pitch_b) + rl.col1, stage + KT * SW_LD + (4 + wave) * 512);
+    if (NW == 4) {
+      dma16_off(f.a, __umul24(r1c, pitch_a) + rl.col1, stage + (4 + wave) * 512);
+      dma16_off(f.b, __umul24(r1c, pitch_b) + rl.col1, stage + KT * SW_LD + (4 + wave) * 512);
+    }
   }
   f.a += (size_t)KT * pitch_a;
   f.b += (size_t)KT * pitch_b;
   f.rows -= KT;
 }
-// wait until at most `later` (0 or 1) stages of 4 copies requested after the wanted one are
-// outstanding, then meet the other waves: the wanted stage is visible to all, and every wave has
-// finished reading the stage consumed before it.
+// wait until at most `later` (0 or 1) stages of copies (4 per wave with 4 waves, 2 with 8) requested after the
+// wanted one are outstanding, then meet the other waves: the wanted stage is visible to all, and every wave
+// has finished reading the stage consumed before it.
+template <int NW = 4>
 __device__ __forceinline__ void ring_wait(int later) {
-  if (later > 0) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if (later > 0) {
+    if (NW == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+  } else {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
   __builtin_amdgcn_s_barrier();
 }
 
@@ -168,17 +181,17 @@ __device__ __forceinline__ void ring_wait(int later) {
 // O^T only the one 32-row block of V^T that holds them.  Per 64-key tile that is 2 + 4 MFMAs per
 // query block instead of 8 + 8, and the softmax stays on 32 x 32 accumulator tiles -- about a
 // quarter of the VALU instructions of the row-per-lane kernel at these head sizes.
-template <int QB, int DH>
-__global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
+template <int QB, int DH, int NST, int WGS, int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(WGS * NW / 4, WGS * NW / 4))) void mfma_fwd_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
                                                        const int32_t* __restrict__ valid_len,
                                                        const uint8_t* __restrict__ key_pad, bf16_t* __restrict__ O,
                                                        long ldo, float* __restrict__ lse2) {
-  __shared__ __attribute__((aligned(1024))) bf16_t sT[RING_NST * RING_STAGE];  // per stage: K tile, V tile
+  __shared__ __attribute__((aligned(1024))) bf16_t sT[NST * RING_STAGE];  // per stage: K tile, V tile
   const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: branches on it are wave-uniform
   int tile, h, b;
   xcd_tile_index(g.q_tile_prefix, g.q_nord, g.cu != nullptr, tile, h, b);
-  constexpr int WG_ROWS = 128 * QB;
+  constexpr int WG_ROWS = 32 * NW * QB;
   int qs, q0;
   decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, WG_ROWS, tile, qs, q0);
   const int qlen = useg_rows(g, b, qs);
@@ -237,7 +250,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
     if (valid_len) n = min(n, max(0, valid_len[b * g.n_seg + j]));
     return n;
   };
-  const RingLane rl = ring_lane(wave, lane, cg);
+  const RingLane rl = ring_lane<NW>(wave, lane, cg);
   const unsigned ldb = (unsigned)ld * 2u;
   TileCursor ic = {g.q_live[qs], 0, 0, 0}, cc = ic;
   cursor_next_seg(ic, klen_of);
@@ -253,70 +266,82 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
   };
   if (ic.len > 0) seg_begin();
   auto issue = [&]() {
-    ring_feed_issue(rl, rlo, feed, ldb, ldb, wave, sT + islot * RING_STAGE);
-    islot = (islot + 1 == RING_NST) ? 0 : islot + 1;
+    ring_feed_issue<NW>(rl, rlo, feed, ldb, ldb, wave, sT + islot * RING_STAGE);
+    islot = (islot + 1 == NST) ? 0 : islot + 1;
     ic.r0 += KT;
     if (ic.r0 >= ic.len) {
       cursor_next_seg(ic, klen_of);
       if (ic.len > 0) seg_begin();
     }
   };
+  // NST - 1 stages are requested ahead: the slot refilled in an iteration is the one consumed in the one before
   if (ic.len > 0) { issue(); ++inflight; }
-  if (ic.len > 0) { issue(); ++inflight; }
+  if (NST > 2 && ic.len > 0) { issue(); ++inflight; }
   while (cc.len > 0) {
-    ring_wait(inflight - 1);
+    ring_wait<NW>(inflight - 1);
     if (ic.len > 0) issue(); else --inflight;
     const bf16_t* sK = sT + cslot * RING_STAGE;
     const bf16_t* sV = sK + KT * SW_LD;
-    cslot = (cslot + 1 == RING_NST) ? 0 : cslot + 1;
+    cslot = (cslot + 1 == NST) ? 0 : cslot + 1;
     const int k0 = cc.r0, klen = cc.len;
     const uint8_t* kp_row = key_pad ? key_pad + useg_row0(g, b, cc.seg) : nullptr;
     cursor_step(cc, klen_of);
-    {
+    const bool need_mask = (k0 + KT > klen) || (kp_row != nullptr);  // tail tile or key_pad present (wave-uniform)
+    unsigned long long km = ~0ull;
+    if (need_mask) km = tile_key_mask(kp_row, k0, klen, lane) >> (8 * hi);
+    // The tile is processed as two blocks of 32 keys, each S^T -> softmax -> O^T, so that only one block of
+    // scores and of probabilities is live at a time.
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
       // ---- S^T = K Q^T ----
       // The accumulator chain starts from -m (nm: the running reference of the lane's query row in all 16
       // registers), so the scores leave the matrix cores already relative to it.
-      f32x16 sacc[2][QB];
+      f32x16 sacc[QB];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
+      for (int s = 0; s < NS; ++s) {
+        const bf16x8 a = lds_frag_sw(sK, kb * 32, prow, 2 * (s0 + s) + hi);
 #pragma unroll
-        for (int s = 0; s < NS; ++s) {
-          const bf16x8 a = lds_frag_sw(sK, kb * 32, prow, 2 * (s0 + s) + hi);
+        for (int qb = 0; qb < QB; ++qb) sacc[qb] = mfma32(a, qreg[qb][s], s == 0 ? nm[qb] : sacc[qb]);
+      }
+      if (need_mask) {
 #pragma unroll
-          for (int qb = 0; qb < QB; ++qb) sacc[kb][qb] = mfma32(a, qreg[qb][s], s == 0 ? nm[qb] : sacc[kb][qb]);
+        for (int r = 0; r < 16; ++r) {
+          // register r of block kb on this lane half is key kb*32 + 16*(r/8) + 8*hi + r%8
+          const bool ok = (km >> (kb * 32 + 16 * (r >> 3) + (r & 7))) & 1ull;
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb) sacc[qb][r] = ok ? sacc[qb][r] : IM_NEG_INF;
         }
       }
-      // ---- mask the tail / padded keys (wave-uniform branch) ----
-      const bool need_mask = (k0 + KT > klen) || (kp_row != nullptr);
-      if (need_mask) {
-        const unsigned long long km = tile_key_mask(kp_row, k0, klen, lane) >> (8 * hi);
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            // register r of block kb on this lane half is key kb*32 + 16*(r/8) + 8*hi + r%8
-            const bool ok = (km >> (kb * 32 + 16 * (r >> 3) + (r & 7))) & 1ull;
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) sacc[kb][qb][r] = ok ? sacc[kb][qb][r] : IM_NEG_INF;
-          }
-      }
-      // ---- online softmax, one running (max, sum) per query row ----
-      bf16x8 pb[2][QB][2];
+      // ---- online softmax, one running (reference, sum) per query row ----
+      bf16x8 pb[QB][2];
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
-        float mx = sacc[0][qb][0];
+        // P^T operands of the block from its scores; returns the lane's part of the row sum, taken over the
+        // bf16-rounded probabilities (the values that multiply V) with two-element dot products against (1, 1)
+        auto exponentiate = [&]() {
+          float p[16];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+          for (int r = 0; r < 16; ++r) p[r] = fast_exp2(sacc[qb][r]);
+          pb[qb][0] = pack8(p);
+          pb[qb][1] = pack8(p + 8);
+          return sum_bf16x8(pb[qb][1], sum_bf16x8(pb[qb][0], 0.f));
+        };
+        // Almost every block: every row of the wave has a reference already and the scores are exponentiated
+        // as they left the matrix cores -- no maximum is taken at all.  fp32 and bf16 share their exponent
+        // range, so probabilities far above 1 lose nothing; only a row without a reference yet, or a row sum
+        // beyond 2^24 (or inf / NaN), sends the block through the rescaling branch, which recomputes it.
+        float rs = exponentiate();
+        if (__builtin_expect(__any(m[qb] == IM_NEG_INF || !(rs <= 16777216.f)), 0)) {
+          asm volatile("" ::: "memory");  // a real branch: nothing of it is to be executed speculatively
+          float mx = sacc[qb][0];
 #pragma unroll
-          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][qb][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // tile maximum relative to m (the raw maximum while m = -inf)
-        // Lazy rescale: the running reference m only moves when the tile maximum exceeds it by more
-        // than 2^8 in the exponent domain, so probabilities stay <= 256 (exact in bf16's range) and
-        // this branch -- accumulator rescale, shifting the tile's scores to the new reference and
-        // rebuilding nm -- is skipped for almost every tile after the first.
-        const bool first = m[qb] == IM_NEG_INF;
-        const bool upd = first ? mx > IM_NEG_INF : mx > tau;
-        if (__any(upd)) {
+          for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[qb][r]);
+          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // block maximum relative to m (the raw maximum while m = -inf)
+          // The reference moves when a row has none yet, or when the block maximum exceeds it by more than
+          // 2^8 in the exponent domain: accumulator rescale, shifting the block's scores to the new reference
+          // and rebuilding nm.
+          const bool first = m[qb] == IM_NEG_INF;
+          const bool upd = first ? mx > IM_NEG_INF : mx > tau;
           const float shift = upd ? mx : 0.f;
           const float alpha = first ? 0.f : fast_exp2(-shift);
           l[qb] *= alpha;
@@ -326,35 +351,22 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
             for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
           if (upd) m[qb] = first ? mx : m[qb] + mx;
 #pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[kb][qb][r] -= shift;
+          for (int r = 0; r < 16; ++r) sacc[qb][r] -= shift;
           const float nmv = (m[qb] == IM_NEG_INF) ? 0.f : -m[qb];
 #pragma unroll
           for (int r = 0; r < 16; ++r) nm[qb][r] = nmv;
-        }
-        float rs = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          float p[16];
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            p[r] = fast_exp2(sacc[kb][qb][r]);
-            rs += p[r];
-          }
-          pb[kb][qb][0] = pack8(p);
-          pb[kb][qb][1] = pack8(p + 8);
+          rs = exponentiate();
         }
         l[qb] += rs;
       }
-      // ---- O^T += V^T P^T ----
+      // ---- O^T += V^T P^T over the 32 keys of the block ----
 #pragma unroll
       for (int db = 0; db < NDB; ++db)
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const bf16x8 a = lds_frag_tr_sw(sV, s * 16, (db0 + db) * 32, lane);
+        for (int half = 0; half < 2; ++half) {
+          const bf16x8 a = lds_frag_tr_sw(sV, kb * 32 + half * 16, (db0 + db) * 32, lane);
 #pragma unroll
-          for (int qb = 0; qb < QB; ++qb) oacc[db][qb] = mfma32(a, pb[s >> 1][qb][s & 1], oacc[db][qb]);
+          for (int qb = 0; qb < QB; ++qb) oacc[db][qb] = mfma32(a, pb[qb][half], oacc[db][qb]);
         }
     }
   }
@@ -388,8 +400,11 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(Geo g, const bf16_t* _
 // The two constant accumulator seeds (negated lse, -delta: 32 registers) put the kernel at 194 registers
 // and two workgroups per CU; with them the softmax is exp2, one multiply and the bf16 pack per score, and
 // that was measured faster than three workgroups per CU with two more vector instructions per score.
+#ifndef IM_DQ_WGS
+#define IM_DQ_WGS 2
+#endif
 template <int QB, int DH>
-__global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
+__global__ __launch_bounds__(256, DH == 64 ? IM_DQ_WGS : 2) void mfma_dq_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
                                                       const bf16_t* __restrict__ O,
                                                       const bf16_t* __restrict__ dO, long ldo,
                                                       const float* __restrict__ lse2,
@@ -514,9 +529,10 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
       const bool need_mask = (k0 + KT > klen) || (kp_row != nullptr);
       unsigned long long km = ~0ull;
       if (need_mask) km = tile_key_mask(kp_row, k0, klen, lane) >> (8 * hi);
-      bf16x8 dsb[2][QB][2];
+      // two blocks of 32 keys, each S^T, dP^T -> dS^T -> dQ^T, so that one block of dS^T is live at a time
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
+        bf16x8 dsb[QB][2];
         // The chains start from the row's negated lse resp. -delta (nlb, ndb: the lane's value in all 16
         // registers), so they end as S^T - lse and dP^T - delta.
         f32x16 sacc[QB], pacc[QB];
@@ -545,19 +561,19 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(Geo g, const bf16_t* __
             const float p = fast_exp2(sacc[qb][r]);
             ds[r] = p * pacc[qb][r];
           }
-          dsb[kb][qb][0] = pack8(ds);
-          dsb[kb][qb][1] = pack8(ds + 8);
+          dsb[qb][0] = pack8(ds);
+          dsb[qb][1] = pack8(ds + 8);
         }
+        // dQ^T += K^T dS^T over the 32 keys of the block
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            const bf16x8 a = lds_frag_tr_sw(sK, kb * 32 + half * 16, (db0 + db) * 32, lane);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) dqacc[db][qb] = mfma32(a, dsb[qb][half], dqacc[db][qb]);
+          }
       }
-      // dQ^T += K^T dS^T
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const bf16x8 a = lds_frag_tr_sw(sK, s * 16, (db0 + db) * 32, lane);
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb) dqacc[db][qb] = mfma32(a, dsb[s >> 1][qb][s & 1], dqacc[db][qb]);
-        }
     }
   }
 
@@ -821,7 +837,20 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void mfma_dkv_kernel(Geo g, 
 // 6 % faster than 2 blocks per wave at two workgroups per CU), 2 in sub-head mode (half the K/V tile traffic per
 // score; measured 2 % faster there).
 constexpr int FWD_QB = 1, FWD_QB_SUB = 2, DQ_QB = 1, DKV_KB = 1;
-int mfma_fwd_tile_rows(int dh) { return 128 * (dh == 64 ? FWD_QB : FWD_QB_SUB); }
+#ifndef IM_FWD_NST
+#define IM_FWD_NST 2
+#endif
+#ifndef IM_FWD_WGS
+#define IM_FWD_WGS 4
+#endif
+#ifndef IM_FWD_SUB_WGS
+#define IM_FWD_SUB_WGS 3
+#endif
+#ifndef IM_FWD_NW
+#define IM_FWD_NW 4
+#endif
+constexpr int FWD_NST = IM_FWD_NST, FWD_WGS = IM_FWD_WGS, FWD_NW = IM_FWD_NW;  // ring stages, workgroups per CU and waves per workgroup of the forward at head dim 64
+int mfma_fwd_tile_rows(int dh) { return dh == 64 ? 32 * FWD_NW * FWD_QB : 128 * FWD_QB_SUB; }
 int mfma_dq_tile_rows() { return 128 * DQ_QB; }
 int mfma_dkv_tile_rows() { return 128 * DKV_KB; }
 
@@ -837,9 +866,9 @@ void launch_mfma_fwd(const Geo& g, const bf16_t* qkv, long ld, const int32_t* va
   if (nt == 0) return;
   ProfScope ps(PF_ATTN_FWD, st);
   const dim3 grid(nt, g.H, g.B);
-  if (g.dh == 64) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB, 64>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
-  else if (g.dh == 16) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 16>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
-  else hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 8>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  if (g.dh == 64) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB, 64, FWD_NST, FWD_WGS, FWD_NW>), grid, dim3(64 * FWD_NW), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  else if (g.dh == 16) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 16, 3, IM_FWD_SUB_WGS, 4>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  else hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 8, 3, IM_FWD_SUB_WGS, 4>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
 }
 
 void launch_mfma_bwd(const Geo& g, const bf16_t* qkv, long ld, const bf16_t* o, const bf16_t* d_o, long ldo,
