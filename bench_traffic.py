@@ -1,7 +1,7 @@
 """Turn two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE) of `bench.py --calibrate-copy`
 into the HBM-traffic figure that bench.py reports for the dominant attention kernel.
 
-    python -m paper_2505_01068_amd.traffic <fetch_dir> <write_dir> <out.md> [kernel-substring]
+    python bench_traffic.py <fetch_dir> <write_dir> <out.md> [kernel-substring]
 
 Each directory holds rocprofv3's *_counter_collection.csv.  The counters (KiB per dispatch) are
 scaled by what the same counter reads for the plain copy kernel of known size that bench.py runs
@@ -21,7 +21,7 @@ import json
 import os
 import sys
 
-HERE = os.path.dirname(os.path.abspath(__file__))
+HERE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2505_01068_amd")
 COPY_BYTES = 1 << 30
 KERNEL_SOURCES = {"mfma_": ["csrc/mfma_attn.hip", "csrc/mfma_common.hpp", "csrc/common.hpp"],
                   "rowlane_": ["csrc/attn_rowlane.hip", "csrc/common.hpp"]}
@@ -91,7 +91,7 @@ def main(argv):
         "",
         "    rocprofv3 --pmc FETCH_SIZE --output-format csv -d <fetch_dir> -o p -- python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --calibrate-copy",
         "    rocprofv3 --pmc WRITE_SIZE --output-format csv -d <write_dir> -o p -- python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --calibrate-copy",
-        "    python -m paper_2505_01068_amd.traffic <fetch_dir> <write_dir> profiles/c5_attn_dkv_traffic.md mfma_dkv_kernel",
+        "    python bench_traffic.py <fetch_dir> <write_dir> profiles/c5_attn_dkv_traffic.md mfma_dkv_kernel",
         "",
         "TRAFFIC_JSON " + json.dumps(rec),
         "",

@@ -26,16 +26,21 @@
  *   - dtype IM_DTYPE_F32: every float array is fp32.
  *     dtype IM_DTYPE_BF16: activations, weights and biases are bfloat16; all
  *     accumulation is fp32; weight/bias GRADIENTS are written in fp32.
- *   - Return value: IM_OK, or a negative error code.  Arguments are validated
- *     before anything is enqueued, so a failing call has no side effects.
+ *   - Return value: IM_OK, or a negative error code.  Shape, pointer, alignment
+ *     and workspace-size validation precedes any launch (a call rejected with
+ *     IM_ERR_INVALID / UNSUPPORTED / WORKSPACE has enqueued nothing); IM_ERR_HIP
+ *     reports a launch error collected after the call's kernels were enqueued.
  *     im_last_error() returns a thread-local description of the last failure.
+ *   - Limits: batch <= 65535.  With dtype IM_DTYPE_BF16 and a head dimension of
+ *     8, 16 or 64 (d_model a multiple of 64: the matrix-core kernels) x, the
+ *     weights, dy, y, dx, saved and workspace must be 16-byte aligned.
  *   - Numerical conventions: a key is padding if key_pad[b, c] != 0 or if its
  *     position inside its segment is >= valid_len[b, segment]; padded keys get
  *     weight exactly 0.  Padded QUERY rows are computed like any other row.  A
  *     query row with no live, valid key has attention output 0 (y = b_o) and
  *     contributes 0 to every gradient.  A row with several live blocks is
  *     normalised by ONE softmax over all its live keys (the additive -inf
- *     definition; Sec. 7.1 "Information Disorder").
+ *     definition; Sec. "Information Disorder" under "Further Analysis").
  */
 #ifndef IMATTN_H
 #define IMATTN_H
@@ -65,6 +70,16 @@ extern "C" {
 #define IM_IFM_BACKWARD 0x08Cull /* live (t,a), (v,t), (a,v) */
 #define IM_IEM 0x111ull          /* live (t,t), (v,v), (a,a) */
 #define IM_DENSE3 0x1FFull       /* ordinary self-attention over V_m */
+/* The other structures of the ablation (Sec. "Ablation Study"; App. "Graph Structures"), each a pair of
+ * masks, and Self-Only, whose rows have two live blocks each and share one softmax across them
+ * (Sec. "Information Disorder").  Structure-1's first set follows the text's edge list. */
+#define IM_STRUCTURE1_A 0x0A4ull /* live (t,a), (v,a), (a,v) */
+#define IM_STRUCTURE1_B 0x04Aull /* live (t,v), (v,t), (a,t) */
+#define IM_STRUCTURE2_A 0x08Aull /* live (t,v), (v,t), (a,v) */
+#define IM_STRUCTURE2_B 0x064ull /* live (t,a), (v,a), (a,t) */
+#define IM_STRUCTURE3_A 0x0A2ull /* live (t,v), (v,a), (a,v) */
+#define IM_STRUCTURE3_B 0x04Cull /* live (t,a), (v,t), (a,t) */
+#define IM_SELF_ONLY 0x0EEull    /* every block but the diagonal */
 
 /* The problem statement: per-modality lengths, model width, heads, block pattern. */
 typedef struct im_shape {
@@ -100,7 +115,9 @@ typedef struct im_work_item {
 
 /* Sec. 6 "Decomposition": enumerate, for ONE (batch element, head), the query
  * tiles and the live key segments each must visit; nothing is emitted for a
- * masked block.  Items are ordered by decreasing `pairs` (heaviest first).  Pure
+ * masked block.  Items are ordered by query segment, the segments by decreasing
+ * number of live keys per query row (heaviest rows first; inside a segment by
+ * row, so a ragged last tile has fewer pairs than its predecessors).  Pure
  * host function, no GPU needed.  items may be NULL to only count.  *n_pairs
  * receives sum(pairs) = sum over live (i,j) of T_i T_j (App. B, attention cost
  * "w/ Decomposition").  Returns IM_ERR_INVALID if max_items is too small. */
@@ -246,6 +263,14 @@ int gsit_model_fwd(const im_shape_t* shape, const gsit_model_t* model, const voi
  * launches are recorded between resets (later ones are not timed).  Host memory only. */
 int im_profile_enable(int on);
 int im_profile_get(int idx, const char** name, double* total_ms, int64_t* launches);
+
+/* Benchmark aids: what this GPU sustains, to set measured rates against.  im_calibrate_mfma enqueues a
+ * register-resident loop of `iters` x 16 v_mfma_f32_32x32x16_bf16 per wave on every SIMD (no memory
+ * traffic; `sink` is a device pointer to >= 4 bytes that is practically never written) and returns
+ * the flops it launched in *flops; im_calibrate_copy enqueues a streaming device copy of `bytes`
+ * (16-byte aligned, a multiple of 16).  The caller times them with events on hip_stream. */
+int im_calibrate_mfma(int32_t iters, void* sink, double* flops, void* hip_stream);
+int im_calibrate_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
 /* Description of the last error on the calling thread ("" if none).  Static storage. */
 const char* im_last_error(void);

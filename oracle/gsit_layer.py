@@ -126,6 +126,7 @@ def gsit_layer_backward(x, p, dy, seg_len, live_mask, n_heads, scale, eps=1e-5, 
             g["d" + n] = ga["d" + n]
     dx_ln, g["dln1_g"], g["dln1_b"] = layer_norm_backward(x, p["ln1_g"], eps, ga["dx"])
     g["dx"] = dh + dx_ln
+    g["attn_dk"] = ga["dk"]   # intermediate of the attention backward (what dbk sums), for error scales in tests
     return g
 
 

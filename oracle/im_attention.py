@@ -17,7 +17,7 @@ whose softmax weight is exp(-inf) = 0), so the oracle is the dense definition.
 
 Parity pins (tests/test_oracle_*.py): scalar-loop brute force on tiny inputs,
 the equivalence with separately computed cross-modal / self attention of the
-paper (Sec. 4 and Lemma 1), the joint-softmax behaviour of Sec. 7.1
+paper (Sec. 4 and Lemma 1), the joint-softmax behaviour of Sec. "Information Disorder"
 ("Information Disorder"), row-stochastic and zero-block invariants, the
 special cases that reduce to textbook multi-head attention, the 3x3 patterns
 printed in the paper (tests/golden/im_patterns.txt), the live-pair count of the
@@ -36,7 +36,7 @@ Conventions (each is a reading of a point the paper leaves open):
   * a row whose every key is masked has attention output 0 (so y = b_o) and
     contributes nothing to any gradient;
   * rows with several live blocks share ONE softmax over all their live keys
-    (the additive -inf definition; Sec. 7.1).
+    (the additive -inf definition; Sec. "Information Disorder").
 """
 from __future__ import annotations
 
@@ -65,8 +65,8 @@ def live_mask_from_edges(edges, n_seg=3, names="tva"):
 
 
 # Patterns used in the paper.  The ablation structures follow the edge sets in
-# the text of Sec. 6.3 / App. D (for Structure-1 the text, not the garbled
-# matrix, see the design notes); Self-Only follows the printed matrix of App. D:
+# the text of Sec. "Ablation Study" / App. "Graph Structures" (for Structure-1 the text, not the garbled
+# matrix, see the design notes); Self-Only follows the printed matrix of App. "Graph Structures":
 # J on the diagonal and O elsewhere (two live blocks per row, which is what
 # makes it the information-disorder case).
 NAMED_PATTERNS = {

@@ -15,6 +15,12 @@ IM_MAX_SEG = 8
 IM_DTYPE_F32, IM_DTYPE_BF16 = 0, 1
 IM_OK, IM_ERR_INVALID, IM_ERR_UNSUPPORTED, IM_ERR_WORKSPACE, IM_ERR_HIP = 0, -1, -2, -3, -4
 IM_IFM_FORWARD, IM_IFM_BACKWARD, IM_IEM, IM_DENSE = 0x062, 0x08C, 0x111, 0x1FF
+# the named 3 x 3 patterns of include/imattn.h (segment order t, v, a; bit i*3 + j <=> block (query i, key j) live)
+NAMED_MASKS = {
+    "ifm_forward": IM_IFM_FORWARD, "ifm_backward": IM_IFM_BACKWARD, "iem": IM_IEM, "dense": IM_DENSE,
+    "structure1_a": 0x0A4, "structure1_b": 0x04A, "structure2_a": 0x08A, "structure2_b": 0x064,
+    "structure3_a": 0x0A2, "structure3_b": 0x04C, "self_only": 0x0EE,
+}
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libimattn.so")
 
@@ -59,6 +65,8 @@ def lib():
         L.im_attention_bwd.argtypes = [shp] + [vp] * 19 + [sz, vp]
         L.im_attention_fwd_noalloc.argtypes = [shp] + [vp] * 13
         L.im_noalloc_init.argtypes = []
+        L.im_calibrate_mfma.argtypes = [C.c_int32, vp, C.POINTER(C.c_double), vp]
+        L.im_calibrate_copy.argtypes = [vp, vp, sz, vp]
         L.gsit_layer_sizes.argtypes = [shp, C.c_int32, C.POINTER(sz)]
         L.gsit_layer_fwd.argtypes = [shp, C.c_int32] + [vp] * 17 + [C.c_float] + [vp] * 4 + [sz, vp]
         L.im_profile_enable.argtypes = [C.c_int]
@@ -74,7 +82,7 @@ def lib():
         L.gsit_model_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_size_t, C.c_void_p]
         for f in (L.im_schedule_build, L.im_attention_sizes, L.im_attention_fwd, L.im_attention_bwd,
-                  L.im_attention_fwd_noalloc, L.im_noalloc_init,
+                  L.im_attention_fwd_noalloc, L.im_noalloc_init, L.im_calibrate_mfma, L.im_calibrate_copy,
                   L.gsit_layer_sizes, L.gsit_layer_fwd, L.gsit_model_sizes, L.gsit_model_fwd,
                   L.gsit_layer_train_sizes, L.gsit_layer_fwd_train, L.gsit_layer_bwd):
             f.restype = C.c_int
@@ -275,6 +283,18 @@ def gsit_model_fwd(shape, model, x, valid_len=None, key_pad=None, out=None, work
     _check(lib().gsit_model_fwd(C.byref(shape), C.byref(model), _p(x), _p(valid_len), _p(key_pad), _p(out),
                                 _p(workspace), wbytes, _stream()))
     return out
+
+
+def im_calibrate_mfma(iters, sink):
+    """Enqueue the register-resident MFMA loop; returns the flops it launched."""
+    f = C.c_double(0)
+    _check(lib().im_calibrate_mfma(int(iters), _p(sink), C.byref(f), _stream()))
+    return f.value
+
+
+def im_calibrate_copy(dst, src):
+    """Enqueue a streaming device copy of src (uint8 tensor) into dst."""
+    _check(lib().im_calibrate_copy(_p(dst), _p(src), src.numel() * src.element_size(), _stream()))
 
 
 def im_profile_enable(on, only=None):

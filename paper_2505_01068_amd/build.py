@@ -12,7 +12,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SOURCES = ["api.hip", "attn_rowlane.hip", "gemm_alu.hip", "mfma_path.hip", "mfma_gemm.hip", "mfma_attn.hip",
-           "gsit_model.hip"]
+           "gsit_model.hip", "calibrate.hip"]
 LIB = os.path.join(HERE, "libimattn.so")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"),

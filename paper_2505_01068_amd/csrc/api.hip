@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <initializer_list>
 #include <mutex>
 
 #include "common.hpp"
@@ -62,7 +63,7 @@ static int check_hip(const char* what) {
 
 static int validate_shape(const im_shape_t* s) {
   if (!s) return fail(IM_ERR_INVALID, "shape is NULL");
-  if (s->batch < 1) return fail(IM_ERR_INVALID, "batch must be >= 1 (got %d)", s->batch);
+  if (s->batch < 1 || s->batch > 65535) return fail(IM_ERR_INVALID, "batch must be in 1..65535 (got %d)", s->batch);
   if (s->n_seg < 1 || s->n_seg > IM_MAX_SEG)
     return fail(IM_ERR_INVALID, "n_seg must be in 1..%d (got %d)", IM_MAX_SEG, s->n_seg);
   long T = 0;
@@ -106,6 +107,16 @@ static int check_supported(const im_shape_t* s) {
                 "no kernel for dtype %d with head dimension %d (supported: head dim <= 16 for fp32/bf16; bf16 with "
                 "head dim 8, 16 or 64, d_model %% 64 == 0 and segment length * d_model < 2^28)",
                 s->dtype, s->d_model / s->n_heads);
+  return IM_OK;
+}
+
+// The matrix-core kernels read and write activations, weights and their scratch tensors in 16-byte
+// units (vector loads, global->LDS copies): every such pointer must be 16-byte aligned.
+static int check_align16(const im_shape_t* s, const char* what, std::initializer_list<const void*> ptrs) {
+  if (pick_path(s) != PATH_MFMA) return IM_OK;
+  for (const void* p : ptrs)
+    if (((uintptr_t)p & 15) != 0)
+      return fail(IM_ERR_INVALID, "%s: with bf16 and head dimension 8 / 16 / 64 every tensor pointer must be 16-byte aligned", what);
   return IM_OK;
 }
 
@@ -446,6 +457,7 @@ int im_attention_fwd(const im_shape_t* shape, const void* x, const void* wq, con
   if ((rc = check_supported(shape))) return rc;
   if (shape->cu_rows && valid_len) return fail(IM_ERR_INVALID, "packed rows carry the lengths in cu_rows: valid_len must be NULL");
   if (!x || !wq || !wk || !wv || !wo || !y) return fail(IM_ERR_INVALID, "x, wq, wk, wv, wo and y must not be NULL");
+  if ((rc = check_align16(shape, "im_attention_fwd", {x, wq, wk, wv, wo, y, saved, workspace}))) return rc;
   const SavedLayout L = saved_layout(shape);
   const Path path = pick_path(shape);
   size_t need = saved ? 0 : L.total;
@@ -471,6 +483,7 @@ int im_attention_bwd(const im_shape_t* shape, const void* x, const void* wq, con
   if (shape->cu_rows && valid_len) return fail(IM_ERR_INVALID, "packed rows carry the lengths in cu_rows: valid_len must be NULL");
   if (!x || !wq || !wk || !wv || !wo || !saved || !dy)
     return fail(IM_ERR_INVALID, "x, wq, wk, wv, wo, saved and dy must not be NULL");
+  if ((rc = check_align16(shape, "im_attention_bwd", {x, wq, wk, wv, wo, saved, dy, dx, workspace}))) return rc;
   const size_t need = bwd_workspace_bytes(shape);
   if (!workspace || workspace_bytes < need)
     return fail(IM_ERR_WORKSPACE, "im_attention_bwd needs %zu workspace bytes, got %zu", need, workspace_bytes);
@@ -496,6 +509,7 @@ int im_attention_fwd_noalloc(const im_shape_t* shape, const void* x, const void*
   if ((rc = check_supported(shape))) return rc;
   if (shape->cu_rows && valid_len) return fail(IM_ERR_INVALID, "packed rows carry the lengths in cu_rows: valid_len must be NULL");
   if (!x || !wq || !wk || !wv || !wo || !y) return fail(IM_ERR_INVALID, "x, wq, wk, wv, wo and y must not be NULL");
+  if ((rc = check_align16(shape, "im_attention_fwd_noalloc", {x, wq, wk, wv, wo, y}))) return rc;
   const SavedLayout L = saved_layout(shape);
   const Path path = pick_path(shape);
   size_t need = L.total;
@@ -551,6 +565,7 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
   if (!x || !ln1_g || !ln1_b || !wq || !wk || !wv || !wo || !ln2_g || !ln2_b || !w1 || !w2 || !y)
     return fail(IM_ERR_INVALID, "x, LayerNorm parameters, wq, wk, wv, wo, w1, w2 and y must not be NULL");
   if (!(ln_eps >= 0.f)) return fail(IM_ERR_INVALID, "ln_eps must be >= 0");
+  if ((rc = check_align16(shape, "gsit_layer_fwd", {x, wq, wk, wv, wo, w1, w2, y, workspace}))) return rc;
   size_t aws = 0;
   const size_t need = layer_ws(shape, d_ff, &aws);
   if (!workspace || workspace_bytes < need)
@@ -678,6 +693,7 @@ int gsit_layer_fwd_train(const im_shape_t* shape, int32_t d_ff, const void* x, c
   if (!p->ln1_g || !p->ln1_b || !p->wq || !p->wk || !p->wv || !p->wo || !p->ln2_g || !p->ln2_b || !p->w1 || !p->w2)
     return fail(IM_ERR_INVALID, "LayerNorm parameters, wq, wk, wv, wo, w1 and w2 must not be NULL");
   if (!(ln_eps >= 0.f)) return fail(IM_ERR_INVALID, "ln_eps must be >= 0");
+  if ((rc = check_align16(shape, "gsit_layer_fwd_train", {x, p->wq, p->wk, p->wv, p->wo, p->w1, p->w2, y, saved, workspace}))) return rc;
   const LayerTrain L = layer_train_layout(shape, d_ff);
   if (!workspace || workspace_bytes < L.fwd_ws_total)
     return fail(IM_ERR_WORKSPACE, "gsit_layer_fwd_train needs %zu workspace bytes, got %zu", L.fwd_ws_total, workspace_bytes);
@@ -739,6 +755,7 @@ int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const g
   if (!p->ln1_g || !p->ln1_b || !p->wq || !p->wk || !p->wv || !p->wo || !p->ln2_g || !p->ln2_b || !p->w1 || !p->w2)
     return fail(IM_ERR_INVALID, "LayerNorm parameters, wq, wk, wv, wo, w1 and w2 must not be NULL");
   if (!(ln_eps >= 0.f)) return fail(IM_ERR_INVALID, "ln_eps must be >= 0");
+  if ((rc = check_align16(shape, "gsit_layer_bwd", {x, p->wq, p->wk, p->wv, p->wo, p->w1, p->w2, saved, dy, dx, workspace}))) return rc;
   const LayerTrain L = layer_train_layout(shape, d_ff);
   if (!workspace || workspace_bytes < L.ws_total)
     return fail(IM_ERR_WORKSPACE, "gsit_layer_bwd needs %zu workspace bytes, got %zu", L.ws_total, workspace_bytes);

@@ -8,7 +8,7 @@
 // operand between them); it visits only the key (query) segments the Interlaced
 // Mask leaves live for its segment (Sec. 6 "Decomposition"), trimmed to the
 // valid length, and keeps one running maximum and sum per row across all of
-// them (joint row softmax, Sec. 7.1).
+// them (joint row softmax, Sec. "Information Disorder").
 #include "common.hpp"
 
 namespace imattn {

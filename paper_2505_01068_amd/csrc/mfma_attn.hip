@@ -25,7 +25,7 @@
 //
 // Only live (query segment, key segment) blocks of the Interlaced Mask are
 // visited (Sec. 6 "Decomposition"); a row with several live segments carries
-// one running max / sum across all of them (Sec. 7.1).
+// one running max / sum across all of them (Sec. "Information Disorder").
 #include "mfma_common.hpp"
 #include "mfma_path.hpp"
 
@@ -400,18 +400,15 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(WGS * N
 // The two constant accumulator seeds (negated lse, -delta: 32 registers) put the kernel at 194 registers
 // and two workgroups per CU; with them the softmax is exp2, one multiply and the bf16 pack per score, and
 // that was measured faster than three workgroups per CU with two more vector instructions per score.
-#ifndef IM_DQ_WGS
-#define IM_DQ_WGS 2
-#endif
-template <int QB, int DH>
-__global__ __launch_bounds__(256, DH == 64 ? IM_DQ_WGS : 2) void mfma_dq_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
+template <int QB, int DH, int NST, int WGS, bool SEED>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGS, WGS))) void mfma_dq_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
                                                       const bf16_t* __restrict__ O,
                                                       const bf16_t* __restrict__ dO, long ldo,
                                                       const float* __restrict__ lse2,
                                                       const int32_t* __restrict__ valid_len,
                                                       const uint8_t* __restrict__ key_pad, float* __restrict__ delta,
                                                       bf16_t* __restrict__ dQKV, long ldg) {
-  __shared__ __attribute__((aligned(1024))) bf16_t sT[RING_NST * RING_STAGE];  // per stage: K tile, V tile
+  __shared__ __attribute__((aligned(1024))) bf16_t sT[NST * RING_STAGE];  // per stage: K tile, V tile
   const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: branches on it are wave-uniform
   int tile, h, b;
@@ -472,7 +469,7 @@ __global__ __launch_bounds__(256, DH == 64 ? IM_DQ_WGS : 2) void mfma_dq_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) dqacc[db][qb][r] = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { nlb[qb][r] = ls[qb]; ndb[qb][r] = -dl[qb]; }
+    for (int r = 0; r < 16; ++r) { nlb[qb][r] = SEED ? ls[qb] : 0.f; ndb[qb][r] = SEED ? -dl[qb] : 0.f; }
   }
 
   const int prow = perm32(lo);
@@ -507,7 +504,7 @@ __global__ __launch_bounds__(256, DH == 64 ? IM_DQ_WGS : 2) void mfma_dq_kernel(
   if (ic.len > 0) seg_begin();
   auto issue = [&]() {
     ring_feed_issue(rl, rlo, feed, ldb, ldb, wave, sT + islot * RING_STAGE);
-    islot = (islot + 1 == RING_NST) ? 0 : islot + 1;
+    islot = (islot + 1 == NST) ? 0 : islot + 1;
     ic.r0 += KT;
     if (ic.r0 >= ic.len) {
       cursor_next_seg(ic, klen_of);
@@ -515,13 +512,13 @@ __global__ __launch_bounds__(256, DH == 64 ? IM_DQ_WGS : 2) void mfma_dq_kernel(
     }
   };
   if (ic.len > 0) { issue(); ++inflight; }
-  if (ic.len > 0) { issue(); ++inflight; }
+  if (NST > 2 && ic.len > 0) { issue(); ++inflight; }
   while (cc.len > 0) {
     ring_wait(inflight - 1);
     if (ic.len > 0) issue(); else --inflight;
     const bf16_t* sK = sT + cslot * RING_STAGE;
     const bf16_t* sV = sK + KT * SW_LD;
-    cslot = (cslot + 1 == RING_NST) ? 0 : cslot + 1;
+    cslot = (cslot + 1 == NST) ? 0 : cslot + 1;
     const int k0 = cc.r0, klen = cc.len;
     const uint8_t* kp_row = key_pad ? key_pad + useg_row0(g, b, cc.seg) : nullptr;
     cursor_step(cc, klen_of);
@@ -558,8 +555,8 @@ __global__ __launch_bounds__(256, DH == 64 ? IM_DQ_WGS : 2) void mfma_dq_kernel(
           float ds[16];
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const float p = fast_exp2(sacc[qb][r]);
-            ds[r] = p * pacc[qb][r];
+            const float p = fast_exp2(SEED ? sacc[qb][r] : sacc[qb][r] + ls[qb]);
+            ds[r] = p * (SEED ? pacc[qb][r] : pacc[qb][r] - dl[qb]);
           }
           dsb[qb][0] = pack8(ds);
           dsb[qb][1] = pack8(ds + 8);
@@ -849,6 +846,15 @@ constexpr int FWD_QB = 1, FWD_QB_SUB = 2, DQ_QB = 1, DKV_KB = 1;
 #ifndef IM_FWD_NW
 #define IM_FWD_NW 4
 #endif
+#ifndef IM_DQ_NST
+#define IM_DQ_NST 3
+#endif
+#ifndef IM_DQ_WGS
+#define IM_DQ_WGS 3
+#endif
+#ifndef IM_DQ_SEED
+#define IM_DQ_SEED true
+#endif
 constexpr int FWD_NST = IM_FWD_NST, FWD_WGS = IM_FWD_WGS, FWD_NW = IM_FWD_NW;  // ring stages, workgroups per CU and waves per workgroup of the forward at head dim 64
 int mfma_fwd_tile_rows(int dh) { return dh == 64 ? 32 * FWD_NW * FWD_QB : 128 * FWD_QB_SUB; }
 int mfma_dq_tile_rows() { return 128 * DQ_QB; }
@@ -884,9 +890,9 @@ void launch_mfma_bwd(const Geo& g, const bf16_t* qkv, long ld, const bf16_t* o, 
   if (nq == 0) return;
   { ProfScope ps(PF_ATTN_DQ, st);
     const dim3 grid(nq, g.H, g.B);
-    if (g.dh == 64) hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 64>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg);
-    else if (g.dh == 16) hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 16>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg);
-    else hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 8>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg); }
+    if (g.dh == 64) hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 64, IM_DQ_NST, IM_DQ_WGS, IM_DQ_SEED>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg);
+    else if (g.dh == 16) hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 16, 3, 2, true>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg);
+    else hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 8, 3, 2, true>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg); }
   { ProfScope ps(PF_ATTN_DKV, st);
     const dim3 grid(nk, g.H, g.B);
     if (g.dh == 64) hipLaunchKernelGGL((mfma_dkv_kernel<DKV_KB, 64>), grid, dim3(256), 0, st, g, qkv, ld, d_o, ldo, lse2, delta, valid_len, key_pad, dqkv, ldg);

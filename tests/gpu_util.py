@@ -40,6 +40,18 @@ def assert_close(gpu, ref, tol, what="", scale=None):
     return e
 
 
+def grad_scale(name, ref, floor, dk_sum_abs=None):
+    """Scale an error of gradient `name` is measured against: max|oracle|, but never below `floor` (one rounding
+    unit of the largest gradient of the call: a gradient that is identically zero in exact arithmetic has no
+    scale of its own).  The key bias gradient (dbk / dbk of a layer) is identically 0 -- every row of dS sums
+    to 0 -- so its max|oracle| is rounding noise; its error is measured against the magnitude of what is summed,
+    max over columns of sum |dK| (`dk_sum_abs`)."""
+    scale = max(float(np.max(np.abs(ref))), floor)
+    if name in ("dbk", "bk") and dk_sum_abs is not None:
+        scale = max(float(dk_sum_abs), floor)
+    return scale
+
+
 class Problem:
     """One IM-attention problem resident on the GPU."""
 
@@ -102,12 +114,7 @@ class Problem:
             for n, v in grads.items():
                 if v is None:
                     continue
-                scale = max(float(np.max(np.abs(ref[n]))), floor)
-                if n == "dbk":
-                    # dbk = sum over keys of dK is identically 0 (every row of dS sums to 0), so
-                    # max|oracle| is rounding noise; the error of the sum is measured against the
-                    # magnitude of what is summed instead.
-                    scale = max(float(np.max(np.sum(np.abs(ref["dk"]), axis=(0, 1)))), floor)
+                scale = grad_scale(n, ref[n], floor, np.max(np.sum(np.abs(ref["dk"]), axis=(0, 1))))
                 errs[n] = assert_close(v, ref[n], tol, what + " " + n, scale)
         return errs
 
@@ -159,8 +166,6 @@ class PackedProblem(Problem):
                 if v is None:
                     continue
                 r = pack(ref[n]) if n == "dx" else ref[n]
-                scale = max(float(np.max(np.abs(r))), floor)
-                if n == "dbk":
-                    scale = max(float(np.max(np.sum(np.abs(ref["dk"]), axis=(0, 1)))), floor)
+                scale = grad_scale(n, r, floor, np.max(np.sum(np.abs(ref["dk"]), axis=(0, 1))))
                 errs[n] = assert_close(v, r, tol, what + " " + n, scale)
         return errs

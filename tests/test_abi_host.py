@@ -33,6 +33,26 @@ def test_named_constants_agree_with_header_and_oracle():
     assert vals["IM_IFM_BACKWARD"] == oracle.IM_IFM_BACKWARD == B.IM_IFM_BACKWARD
     assert vals["IM_IEM"] == oracle.IM_IEM == B.IM_IEM
     assert vals["IM_DENSE3"] == oracle.IM_DENSE == B.IM_DENSE
+    # every named pattern of the ablation: header constant == binding table == the oracle's (which the golden
+    # file pins to the printed matrices and edge lists)
+    assert set(B.NAMED_MASKS) == set(oracle.NAMED_PATTERNS)
+    for name, bits in oracle.NAMED_PATTERNS.items():
+        assert B.NAMED_MASKS[name] == bits, name
+        assert vals["IM_DENSE3" if name == "dense" else "IM_" + name.upper()] == bits, name
+
+
+def test_batch_limit_and_alignment_are_checked_on_the_host():
+    L = B.lib()
+    with pytest.raises(B.ImAttnError) as e:
+        B.im_attention_sizes(shape(batch=65536))
+    assert e.value.code == -1
+    s = shape(seg_len=(64, 64, 64), d_model=128, n_heads=2, dtype="bf16")   # matrix-core path
+    sb, wb = B.im_attention_sizes(s)
+    ok, odd = C.c_void_p(256), C.c_void_p(264)   # never dereferenced: validation fails first
+    rc = L.im_attention_fwd(C.byref(s), odd, ok, ok, ok, ok, None, None, None, None, None, None, ok, ok, ok, wb, None)
+    assert rc == -1 and b"16-byte aligned" in L.im_last_error()
+    rc = L.im_attention_bwd(C.byref(s), ok, ok, ok, ok, ok, None, None, ok, ok, odd, ok, ok, ok, ok, None, None, None, None, ok, wb, None)
+    assert rc == -1 and b"16-byte aligned" in L.im_last_error()
 
 
 def shape(**kw):

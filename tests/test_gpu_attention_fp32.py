@@ -130,8 +130,8 @@ def test_other_dataset_shapes(ds, name):
 
 @pytest.mark.parametrize("name", [n for n in sorted(oracle.NAMED_PATTERNS) if n.startswith(("structure", "self_only"))])
 def test_pattern_variants_fwd_bwd(name):
-    # Structures 1-3 and Self-Only (Sec. 5.3, Appendix D; Self-Only is also the multi-live-block case of the information-disorder discussion): rows
-    # with several live blocks share ONE softmax across segments (Sec. 7.1)
+    # Structures 1-3 and Self-Only (Sec. "Ablation Study", App. "Graph Structures"; Self-Only is also the multi-live-block case of the information-disorder discussion): rows
+    # with several live blocks share ONE softmax across segments (Sec. "Information Disorder")
     say(f"[case] pattern variant {name} fwd+bwd")
     g = synth.attention_inputs(2, (50, 200, 150), 40, 8, "fp32", "valid_len", seed=20250511, bias=True)
     Problem(g, oracle.NAMED_PATTERNS[name]).check(what=f"variant/{name}")

@@ -99,16 +99,18 @@ def test_layer_identity_when_output_weights_vanish():
     assert torch.equal(y.float().cpu(), torch.from_numpy(g["x"]))
 
 
-@pytest.mark.parametrize("name", ["ifm_forward", "iem"])
-def test_c4_four_layer_encoder_full_size(name):
-    say(f"[case] c4 full size 4 layers pattern={name}")
-    w = synth.workload("c4")
+@pytest.mark.parametrize("name,padding", [("ifm_forward", "none"), ("iem", "none"), ("ifm_forward", "valid_len"),
+                                          ("ifm_backward", "valid_len")])
+def test_c4_four_layer_encoder_full_size(name, padding):
+    # padding = "valid_len": the variant `bench.py --config c4v` times (per-sample valid lengths as in C3)
+    say(f"[case] c4 full size 4 layers pattern={name} padding={padding}")
+    w = synth.workload("c4", padding=padding)
     g = synth.attention_inputs(**{**w, "with_dy": False})
     layers = [synth.layer_params(w["d_model"], w["d_ff"], w["seed"], l, dtype="bf16") for l in range(w["n_layers"])]
     lm = oracle.NAMED_PATTERNS[name]
     y = run_layers(g, layers, lm, "bf16", w["d_ff"], in_place=False)
-    ref = oracle.gsit_encoder_forward(g["x"], layers, g["seg_len"], lm, g["n_heads"], g["scale"])
-    e = assert_close(y, ref, TOL["bf16"], f"c4/{name}")
+    ref = oracle.gsit_encoder_forward(g["x"], layers, g["seg_len"], lm, g["n_heads"], g["scale"], valid_len=g.get("valid_len"))
+    e = assert_close(y, ref, TOL["bf16"], f"c4/{name}/{padding}")
     say(f"    y={e:.1e}")
     y2 = run_layers(g, layers, lm, "bf16", w["d_ff"], in_place=True)     # y aliasing x
     assert torch.equal(y, y2)

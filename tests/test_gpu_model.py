@@ -86,3 +86,27 @@ def test_model_other_masks_two_segments():
     masks = (0b0110, 0b1001, 0b1111)
     out, ref = run_model(g, m, "fp32", d_ff, 2 * d_ff, H, masks)
     assert_close(out, ref, TOL["fp32"], "model/2seg")
+
+
+@pytest.mark.parametrize("padding", ["none", "valid_len"])
+def test_model_at_the_benchmark_shape_and_depth(padding):
+    """The configuration `bench.py --config gsit` times: B = 32, 50/500/375, d = 64, 8 heads, 4 + 4 IFM layers and
+    4 IEM layers at width 128, bf16 -- twelve layers of bf16 rounding against the 2e-2 bar.  The whole batch runs
+    on the GPU in one call; batch elements are independent, so the dense oracle evaluates a slice of four (the
+    first two and the last two) and those outputs are compared."""
+    say(f"[case] model bf16 at the gsit benchmark shape, 4+4+4 layers, padding={padding}")
+    w = synth.workload("c4", padding=padding)
+    g = synth.attention_inputs(**{**w, "with_dy": False})
+    d, H, d_ff, L, seg = w["d_model"], w["n_heads"], w["d_ff"], w["n_layers"], g["seg_len"]
+    m = synth.model_params(d, d_ff, 2 * d_ff, L, L, len(seg), 1, w["seed"], dtype="bf16")
+    shape = B.make_shape(g["x"].shape[0], seg, d, H, 0, g["scale"], "bf16")
+    scale_intra = 1.0 / np.sqrt(2 * d / H)
+    model = B.make_model(dev_model(m, "bf16"), d_ff, 2 * d_ff, H, scale_intra)
+    ws = torch.empty(B.gsit_model_sizes(shape, model), dtype=torch.uint8, device="cuda")
+    out = B.gsit_model_fwd(shape, model, to_dev(g["x"], "bf16"), valid_len=to_dev(g.get("valid_len"), "bf16"), workspace=ws)
+    torch.cuda.synchronize()
+    pick = [0, 1, g["x"].shape[0] - 2, g["x"].shape[0] - 1]
+    vl = None if g.get("valid_len") is None else g["valid_len"][pick]
+    ref = oracle.gsit_model_forward(g["x"][pick], m, seg, H, g["scale"], H, scale_intra, valid_len=vl)
+    e = assert_close(out[pick], ref, TOL["bf16"], f"model at benchmark shape/{padding}")
+    say(f"    error {e:.2e} on batch elements {pick}")

@@ -6,7 +6,7 @@ mathematics, never against the oracle itself:
   * the 3x3 patterns the paper prints (tests/golden/im_patterns.txt);
   * the paper's equivalence claim (Sec. 4: the masked shared-weight pass equals
     the separately computed cross-modal / self attentions; Lemma 1);
-  * Sec. 7.1 "Information Disorder": several live blocks in a row are
+  * Sec. "Information Disorder" under "Further Analysis": several live blocks in a row are
     normalised jointly;
   * row-stochastic / zero-block invariants (App. A softmax equation);
   * special cases that are textbook multi-head attention (library routine);
@@ -196,7 +196,7 @@ def test_iem_is_three_independent_mhas_and_ifm_is_three_cross_attentions():
 
 
 def test_information_disorder_joint_softmax():
-    """Sec. 7.1: with (t,v) and (t,a) both live, the t rows are one softmax over [V_v; V_a]
+    """Sec. "Information Disorder": with (t,v) and (t,a) both live, the t rows are one softmax over [V_v; V_a]
     and differ from the single-block result; v and a rows are unchanged."""
     g = tiny(seed=13, B=1, seg=(4, 6, 5), d=16, H=2, bias=False)
     off = [0, 4, 10, 15]
@@ -232,7 +232,7 @@ def test_rows_are_stochastic_on_live_keys_and_zero_elsewhere(name):
 
 
 def test_dead_segment_contents_do_not_matter():
-    """Worked block product of Sec. 7.1: rows of modality i depend only on V_j of the live j."""
+    """Worked block product of Sec. "Information Disorder": rows of modality i depend only on V_j of the live j."""
     g = tiny(seed=17, B=1, seg=(4, 6, 5), d=8, H=2, bias=True)
     y0 = run(g, oracle.IM_IFM_FORWARD)
     g2 = dict(g)
