@@ -632,6 +632,65 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
 }
 
 
+}  // extern "C"
+
+namespace imattn {
+
+// Workspace of gsit_layer_fwd_pair; 0 when the shape is not one the paired kernels serve.
+size_t gsit_layer_pair_ws(const im_shape_t* s) {
+  if (s->cu_rows || 2L * s->batch > 65535 || pick_path(s) != PATH_MFMA || s->d_model / s->n_heads == 64) return 0;
+  im_shape_t s2 = *s;
+  s2.batch = 2 * s->batch;
+  return align256(saved_layout(&s2).total);
+}
+
+// One layer of each of two encoders that run side by side on inputs of the same shape (the forward- and the
+// backward-IFM encoder over the same V_m, Sec. 5 Eq. "allmodalinone fusion"): y0 = layer(x0; p0, mask of s0),
+// y1 = layer(x1; p1, mask1), in three launches (both QKV projections with their LayerNorms, both attention
+// kernels, both fused tails) instead of six, so that each launch fills the chip.  *done = false with nothing
+// enqueued when the shape or the parameters are not served (the caller then runs the layers one by one).
+int gsit_layer_fwd_pair(const im_shape_t* s0, uint64_t mask1, int32_t d_ff, const void* x0, const void* x1,
+                        const gsit_layer_params_t& p0, const gsit_layer_params_t& p1, float ln_eps,
+                        const int32_t* valid_len, const uint8_t* key_pad, void* y0, void* y1, void* workspace,
+                        size_t workspace_bytes, hipStream_t st, bool* done) {
+  *done = false;
+  const size_t need = gsit_layer_pair_ws(s0);
+  if (!need || !workspace || workspace_bytes < need) return IM_OK;
+  const int bf = s0->dtype == IM_DTYPE_BF16;
+  const long R = shape_rows(s0), d = s0->d_model;
+  auto al16 = [](std::initializer_list<const void*> ps) {
+    uintptr_t a = 0;
+    for (const void* q : ps) a |= (uintptr_t)q;
+    return (a & 15) == 0;
+  };
+  auto side_ok = [&](const gsit_layer_params_t& p, const void* x, const void* y) {
+    return p.ln1_g && p.ln1_b && p.wq && p.wk && p.wv && p.wo && p.ln2_g && p.ln2_b && p.w1 && p.w2 &&
+           mfma_gemm_fuses_ln(bf, d, 3 * d) && mlp_tail_ok(bf, d, d_ff, x, p.ln2_g, p.ln2_b, p.w1, p.w2, y) &&
+           al16({p.ln1_g, p.ln1_b, p.wq, p.wk, p.wv, p.wo, x, y, workspace});
+  };
+  if (!side_ok(p0, x0, y0) || !side_ok(p1, x1, y1)) return IM_OK;
+  im_shape_t s2 = *s0;
+  s2.batch = 2 * s0->batch;
+  const SavedLayout L = saved_layout(&s2);
+  char* sv = (char*)workspace;
+  if (!mfma_attention_fwd_pair(s0, mask1, x0, x1, p0, p1, LnArgs{p0.ln1_g, p0.ln1_b, ln_eps}, LnArgs{p1.ln1_g, p1.ln1_b, ln_eps},
+                               valid_len, key_pad, sv, L.qkv, L.o, L.lse, st))
+    return IM_OK;
+  {
+    ProfScope ps(PF_MISC, st);
+    const size_t es = 2;
+    const MlpTailPairSide a = {x0, p0.ln2_g, p0.ln2_b, p0.w1, p0.b1, p0.w2, p0.b2, sv + L.o, p0.wo, p0.bo, y0};
+    const MlpTailPairSide b = {x1, p1.ln2_g, p1.ln2_b, p1.w1, p1.b1, p1.w2, p1.b2, sv + L.o + (size_t)R * d * es, p1.wo, p1.bo, y1};
+    launch_mlp_tail_pair(a, b, ln_eps, (int)R, (int)d, d_ff, st);
+  }
+  *done = true;
+  return check_hip("gsit_layer_fwd_pair launch");
+}
+
+}  // namespace imattn
+
+extern "C" {
+
 // ---- encoder layer, training: forward that saves what the backward needs, and the backward ----
 
 struct LayerTrain {

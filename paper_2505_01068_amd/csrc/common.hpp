@@ -28,6 +28,13 @@ struct Geo {
   // cu == nullptr: padded rows, batch element b owns rows b*T .. b*T + T - 1.
   const int32_t* cu;
   long R;
+  // Two problems of the same shape in one launch (pair_B > 0; forward only, padded rows): batch elements
+  // b >= pair_B belong to the second problem, whose rows follow the first one's in every tensor and whose
+  // mask gives the query segments the live sets / tile order below; valid_len and key_pad are shared
+  // (indexed by b - pair_B).
+  int pair_B;
+  unsigned q_live2[IM_MAX_SEG];
+  int q_order2[IM_MAX_SEG], q_tile_prefix2[IM_MAX_SEG + 1], q_nord2;
 };
 
 // First row, and number of rows, of segment s of batch element b in the [rows, .] tensors; first
@@ -211,6 +218,13 @@ int launch_layernorm_bwd(const void* x, const void* gamma, const void* dy, const
                          int d, float eps, int bf16, hipStream_t st);
 
 void set_error(const char* fmt, ...);
+
+// One layer of each of two encoders side by side (see api.hip); workspace bytes (0: shape not served)
+size_t gsit_layer_pair_ws(const im_shape_t* s);
+int gsit_layer_fwd_pair(const im_shape_t* s0, uint64_t mask1, int32_t d_ff, const void* x0, const void* x1,
+                        const gsit_layer_params_t& p0, const gsit_layer_params_t& p1, float ln_eps,
+                        const int32_t* valid_len, const uint8_t* key_pad, void* y0, void* y1, void* workspace,
+                        size_t workspace_bytes, hipStream_t st, bool* done);
 
 // Optional per-kernel-family timing (see im_profile_enable): records an event pair
 // around the launches issued while the scope is alive.

@@ -77,7 +77,11 @@ static int model_ws(const im_shape_t* s, const gsit_model_t* m, im_shape_t* intr
   w->b = off; off += al256(R * d * es);
   w->cat = off; off += al256(R * 2 * d * es);
   w->z = off; off += al256((size_t)s->batch * s->n_seg * 2 * d * es);
-  w->layer = off; off += al256(w->layer_inter > w->layer_intra ? w->layer_inter : w->layer_intra);
+  size_t lw = w->layer_inter > w->layer_intra ? w->layer_inter : w->layer_intra;
+  inter.live_mask = m->mask_fwd;
+  const size_t pw = gsit_layer_pair_ws(&inter);   // the two inter-modal encoders layer by layer in shared launches
+  if (pw > lw) lw = pw;
+  w->layer = off; off += al256(lw);
   w->total = off;
   return IM_OK;
 }
@@ -157,13 +161,26 @@ int gsit_model_fwd(const im_shape_t* shape, const gsit_model_t* model, const voi
   void* lws = ws + w.layer;
   const size_t lws_bytes = w.total - w.layer;
 
+  // The two inter-modal encoders read the same V_m and are independent of each other: layer l of both runs in
+  // shared launches when the shape allows (one read of x for the first layer's projections, twice the
+  // workgroups per launch); otherwise, and from the first layer that is not served on, one encoder after the other.
   im_shape_t inter = *shape;
   inter.live_mask = model->mask_fwd;
-  if ((rc = run_encoder(&inter, model->d_ff_inter, model->fwd_layers, model->n_layers_inter, model->ln_eps, x, F, valid_len,
-                        key_pad, lws, lws_bytes, hip_stream))) return rc;
-  inter.live_mask = model->mask_bwd;
-  if ((rc = run_encoder(&inter, model->d_ff_inter, model->bwd_layers, model->n_layers_inter, model->ln_eps, x, Bk, valid_len,
-                        key_pad, lws, lws_bytes, hip_stream))) return rc;
+  int l0 = 0;
+  for (; l0 < model->n_layers_inter; ++l0) {
+    bool done = false;
+    if ((rc = gsit_layer_fwd_pair(&inter, model->mask_bwd, model->d_ff_inter, l0 ? F : x, l0 ? Bk : x, model->fwd_layers[l0],
+                                  model->bwd_layers[l0], model->ln_eps, valid_len, key_pad, F, Bk, lws, lws_bytes, st, &done)))
+      return rc;
+    if (!done) break;
+  }
+  if (l0 < model->n_layers_inter) {
+    if ((rc = run_encoder(&inter, model->d_ff_inter, model->fwd_layers + l0, model->n_layers_inter - l0, model->ln_eps,
+                          l0 ? F : x, F, valid_len, key_pad, lws, lws_bytes, hip_stream))) return rc;
+    inter.live_mask = model->mask_bwd;
+    if ((rc = run_encoder(&inter, model->d_ff_inter, model->bwd_layers + l0, model->n_layers_inter - l0, model->ln_eps,
+                          l0 ? Bk : x, Bk, valid_len, key_pad, lws, lws_bytes, hip_stream))) return rc;
+  }
   const int blocks = (int)((R * 2 * d + 255) / 256 < 4096 ? (R * 2 * d + 255) / 256 : 4096);
   if (bf) hipLaunchKernelGGL(concat_features_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, (const uint16_t*)F, (const uint16_t*)Bk, (uint16_t*)cat, R, d);
   else hipLaunchKernelGGL(concat_features_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)F, (const float*)Bk, (float*)cat, R, d);

@@ -181,7 +181,8 @@ __device__ __forceinline__ void ring_wait(int later) {
 // O^T only the one 32-row block of V^T that holds them.  Per 64-key tile that is 2 + 4 MFMAs per
 // query block instead of 8 + 8, and the softmax stays on 32 x 32 accumulator tiles -- about a
 // quarter of the VALU instructions of the row-per-lane kernel at these head sizes.
-template <int QB, int DH, int NST, int WGS, int NW>
+// PAIR: two problems of the same shape in one launch (two encoders side by side; see Geo::pair_B): grid z = 2 B.
+template <int QB, int DH, int NST, int WGS, int NW, bool PAIR>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(WGS * NW / 4, WGS * NW / 4))) void mfma_fwd_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
                                                        const int32_t* __restrict__ valid_len,
                                                        const uint8_t* __restrict__ key_pad, bf16_t* __restrict__ O,
@@ -191,9 +192,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(WGS * N
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: branches on it are wave-uniform
   int tile, h, b;
   xcd_tile_index(g.q_tile_prefix, g.q_nord, g.cu != nullptr, tile, h, b);
+  const bool second = PAIR && b >= g.pair_B;
+  const int bm = second ? b - g.pair_B : b;   // batch element of the masks (valid_len, key_pad)
   constexpr int WG_ROWS = 32 * NW * QB;
   int qs, q0;
-  decode_tile(g.q_order, g.q_tile_prefix, g.q_nord, WG_ROWS, tile, qs, q0);
+  decode_tile(second ? g.q_order2 : g.q_order, second ? g.q_tile_prefix2 : g.q_tile_prefix, second ? g.q_nord2 : g.q_nord,
+              WG_ROWS, tile, qs, q0);
+  const unsigned live = second ? g.q_live2[qs] : g.q_live[qs];   // live key segments of the tile's query segment
   const int qlen = useg_rows(g, b, qs);
   if (q0 >= qlen) return;  // packed rows: this batch element's segment ends before the tile
   const int d = g.d;
@@ -247,12 +252,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(WGS * N
   // key tiles of the live key segments; a segment contributes its first min(length, valid length) keys
   auto klen_of = [&](int j) {
     int n = useg_rows(g, b, j);
-    if (valid_len) n = min(n, max(0, valid_len[b * g.n_seg + j]));
+    if (valid_len) n = min(n, max(0, valid_len[bm * g.n_seg + j]));
     return n;
   };
   const RingLane rl = ring_lane<NW>(wave, lane, cg);
   const unsigned ldb = (unsigned)ld * 2u;
-  TileCursor ic = {g.q_live[qs], 0, 0, 0}, cc = ic;
+  TileCursor ic = {live, 0, 0, 0}, cc = ic;
   cursor_next_seg(ic, klen_of);
   cursor_next_seg(cc, klen_of);
   int islot = 0, cslot = 0, inflight = 0;
@@ -284,7 +289,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(WGS * N
     const bf16_t* sV = sK + KT * SW_LD;
     cslot = (cslot + 1 == NST) ? 0 : cslot + 1;
     const int k0 = cc.r0, klen = cc.len;
-    const uint8_t* kp_row = key_pad ? key_pad + useg_row0(g, b, cc.seg) : nullptr;
+    const uint8_t* kp_row = key_pad ? key_pad + useg_row0(g, bm, cc.seg) : nullptr;
     cursor_step(cc, klen_of);
     const bool need_mask = (k0 + KT > klen) || (kp_row != nullptr);  // tail tile or key_pad present (wave-uniform)
     unsigned long long km = ~0ull;
@@ -872,9 +877,31 @@ void launch_mfma_fwd(const Geo& g, const bf16_t* qkv, long ld, const int32_t* va
   if (nt == 0) return;
   ProfScope ps(PF_ATTN_FWD, st);
   const dim3 grid(nt, g.H, g.B);
-  if (g.dh == 64) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB, 64, FWD_NST, FWD_WGS, FWD_NW>), grid, dim3(64 * FWD_NW), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
-  else if (g.dh == 16) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 16, 3, IM_FWD_SUB_WGS, 4>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
-  else hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 8, 3, IM_FWD_SUB_WGS, 4>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  if (g.dh == 64) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB, 64, FWD_NST, FWD_WGS, FWD_NW, false>), grid, dim3(64 * FWD_NW), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  else if (g.dh == 16) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 16, 3, IM_FWD_SUB_WGS, 4, false>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  else hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 8, 3, IM_FWD_SUB_WGS, 4, false>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+}
+
+// Forward of two problems of the same shape (masks g0 / g1) in one launch; their rows follow each other in
+// qkv, o and lse2 (2 B batch elements).  Sub-head mode and padded rows only; both masks must give every query
+// segment a live block (same tile count), which the caller checks with mfma_fwd_pair_ok.
+bool mfma_fwd_pair_ok(const Geo& g0, const Geo& g1) {
+  if (g0.dh == 64 || g0.cu || g1.cu || g0.q_tile_prefix[g0.q_nord] != g1.q_tile_prefix[g1.q_nord]) return false;
+  for (int s = 0; s < g0.n_seg; ++s)
+    if (!g0.q_live[s] || !g1.q_live[s]) return false;
+  return 2L * g0.B <= 65535;
+}
+void launch_mfma_fwd_pair(const Geo& g0, const Geo& g1, const bf16_t* qkv, long ld, const int32_t* valid_len,
+                          const uint8_t* key_pad, bf16_t* o, long ldo, float* lse2, hipStream_t st) {
+  Geo g = g0;
+  g.pair_B = g0.B;
+  g.q_nord2 = g1.q_nord;
+  for (int i = 0; i < IM_MAX_SEG; ++i) { g.q_live2[i] = g1.q_live[i]; g.q_order2[i] = g1.q_order[i]; }
+  for (int i = 0; i <= IM_MAX_SEG; ++i) g.q_tile_prefix2[i] = g1.q_tile_prefix[i];
+  ProfScope ps(PF_ATTN_FWD, st);
+  const dim3 grid(g.q_tile_prefix[g.q_nord], g.H, 2 * g.B);
+  if (g.dh == 16) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 16, 3, IM_FWD_SUB_WGS, 4, true>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  else hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 8, 3, IM_FWD_SUB_WGS, 4, true>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
 }
 
 void launch_mfma_bwd(const Geo& g, const bf16_t* qkv, long ld, const bf16_t* o, const bf16_t* d_o, long ldo,

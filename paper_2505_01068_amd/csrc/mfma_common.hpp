@@ -103,26 +103,28 @@ __device__ __forceinline__ bf16x8 lds_frag_tr(const bf16_t* lds, int ld, int k_b
 // which serialises a prefetch ring.  The kernels order the copies against their LDS reads
 // themselves (s_waitcnt vmcnt(n) + workgroup barrier).  The compiler's own vmcnt bookkeeping for
 // ordinary loads stays safe: the counter counts these copies too and returns are in order, so its
-// waits can only be longer than it thinks, never shorter.  M0 is written here and listed as clobbered.
+// waits can only be longer than it thinks, never shorter.  M0 is a reserved register: the compiler
+// never keeps a value live in it across statements (it writes it immediately before each of its own
+// uses) and warns that a clobber entry for a reserved register has no defined meaning, so none is listed.
 __device__ __forceinline__ unsigned lds_offset(const void* lds_ptr) {  // wave-uniform by contract -> SGPR
   return (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(uintptr_t)lds_ptr);
 }
 __device__ __forceinline__ void dma16(const void* gptr, const void* lds_wave_base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-               :: "s"(lds_offset(lds_wave_base)), "v"(gptr) : "memory", "m0");
+               :: "s"(lds_offset(lds_wave_base)), "v"(gptr) : "memory");
 }
 // same, global address = wave-uniform base + per-lane unsigned 32-bit byte offset
 __device__ __forceinline__ void dma16_off(const void* gbase, unsigned byte_off, const void* lds_wave_base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_offset(lds_wave_base)), "v"(byte_off), "s"(gbase) : "memory", "m0");
+               :: "s"(lds_offset(lds_wave_base)), "v"(byte_off), "s"(gbase) : "memory");
 }
 __device__ __forceinline__ void dma4_off(const void* gbase, unsigned byte_off, const void* lds_wave_base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
-               :: "s"(lds_offset(lds_wave_base)), "v"(byte_off), "s"(gbase) : "memory", "m0");
+               :: "s"(lds_offset(lds_wave_base)), "v"(byte_off), "s"(gbase) : "memory");
 }
 __device__ __forceinline__ void dma4(const void* gptr, const void* lds_wave_base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
-               :: "s"(lds_offset(lds_wave_base)), "v"(gptr) : "memory", "m0");
+               :: "s"(lds_offset(lds_wave_base)), "v"(gptr) : "memory");
 }
 
 // ---- swizzled, unpadded 64-column tiles (attention kernels) ----

@@ -77,7 +77,11 @@ __device__ __forceinline__ void load_km(Tile128& t, const bf16_t* const* mats, i
     if (k0 + r < kmax && c < cmax) {
       const bf16_t* m = mats[0];
       int cc = c;
-      if (n_per > 0) { m = mats[c / n_per]; cc = c % n_per; }
+      if (n_per > 0) {   // select chain, not a dynamic index: the three pointers stay in scalar registers
+        const int bi = c / n_per;
+        m = bi == 0 ? mats[0] : bi == 1 ? mats[1] : mats[2];
+        cc = c - bi * n_per;
+      }
       v = *(const u32x4*)(m + (long)(k0 + r) * ld + cc);
     }
     t.v[u] = v;
@@ -129,11 +133,11 @@ __device__ __forceinline__ void ln_tile_rows(TileRegs<U>& t, const bf16_t* gamma
 // Bias of the 4 consecutive output columns n .. n+3 (n % 4 == 0) as fp32; 0 without a bias or past
 // N.  The columns lie in one of at most three blocks of width n_per (one bias vector each), so the
 // block index needs no integer division.
-__device__ __forceinline__ void bias4(const MGemm& p, int n, float (&out)[4]) {
+__device__ __forceinline__ void bias4(const MGemm& p, const bf16_t* const (&bias)[3], int n, float (&out)[4]) {
   out[0] = out[1] = out[2] = out[3] = 0.f;
   if (p.n_per <= 0 || n >= p.N) return;
   const int sel = (n >= p.n_per) + (n >= 2 * p.n_per);
-  const bf16_t* bp = sel == 0 ? p.bias[0] : sel == 1 ? p.bias[1] : p.bias[2];
+  const bf16_t* bp = sel == 0 ? bias[0] : sel == 1 ? bias[1] : bias[2];
   if (!bp) return;
   const bf16_t* q = bp + (n - sel * p.n_per);
   if ((reinterpret_cast<uintptr_t>(bp) & 7) == 0) {
@@ -149,17 +153,23 @@ __device__ __forceinline__ void bias4(const MGemm& p, int n, float (&out)[4]) {
 // TM = rows of the tile: 128, or 64 (m-major A only; each wave then owns 32 x 64) for shapes whose 128-row
 // tiles would not fill the chip -- with about one workgroup per CU nothing overlaps the chain load ->
 // LDS -> MFMA -> epilogue loads -> store of a workgroup, and twice as many half-size workgroups finish sooner.
-template <bool AKM, bool BKM, bool EPI, int TM = GM>
-__global__ __launch_bounds__(256, 3) void mfma_gemm_kernel(MGemm p) {  // three workgroups per CU: at most 168 registers
+template <bool AKM, bool BKM, bool EPI, int TM>
+__device__ __forceinline__ void mfma_gemm_tile(const MGemm& p, int bx, int by, int bz, int pz) {
   static_assert(TM == GM || (TM == 64 && !AKM), "the 64-row tile exists for m-major A only");
   constexpr int MB = TM / 64;  // 32-row blocks per wave
   __shared__ __attribute__((aligned(16))) bf16_t sA[AKM ? GK * KM_LD : TM * LDS_LD];
   __shared__ __attribute__((aligned(16))) bf16_t sB[BKM ? GK * KM_LD : GN * LDS_LD];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int wm = wave >> 1, wn = wave & 1;
-  int bx, by, bz;
-  xcd_block_index(bx, by, bz);
   const int m0 = by * TM, n0 = bx * GN;
+  // pz = 1: the second problem of a paired launch, whose tensors lie at the byte offsets p.z_* from the first one's
+  auto zoff = [&](const bf16_t* q, long off) { return q && pz ? (const bf16_t*)((const char*)q + off) : q; };
+  const bf16_t* const pA = zoff(p.A, p.z_a);
+  const bf16_t* const pln_g = zoff(p.ln_g, p.z_ln_g);
+  const bf16_t* const pln_b = zoff(p.ln_b, p.z_ln_b);
+  const bf16_t* const pres = zoff(p.res, p.z_res);
+  bf16_t* const pC = (bf16_t*)zoff(p.C, p.z_c);
+  const bf16_t* pbias[3] = {zoff(p.bias[0], p.z_bias[0]), zoff(p.bias[1], p.z_bias[1]), zoff(p.bias[2], p.z_bias[2])};
 
   const int ktiles = (p.K + GK - 1) / GK;
   const int per_split = (ktiles + p.split_k - 1) / p.split_k;
@@ -174,30 +184,34 @@ __global__ __launch_bounds__(256, 3) void mfma_gemm_kernel(MGemm p) {  // three 
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       float bv[4] = {0.f, 0.f, 0.f, 0.f};
-      if (!p.partial) bias4(p, n0 + wn * 64 + nb * 32 + 8 * i + 4 * hi, bv);
+      if (!p.partial) bias4(p, pbias, n0 + wn * 64 + nb * 32 + 8 * i + 4 * hi, bv);
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) acc[nb][mb][4 * i + jj] = bv[jj];
     }
 
-  const bf16_t* amat[3] = {p.A, p.A, p.A};
-  const bf16_t* bmat[3] = {p.B[0], p.B[1], p.B[2]};
+  const bf16_t* amat[3] = {pA, pA, pA};
+  const bf16_t* bmat[3] = {zoff(p.B[0], p.z_b[0]), zoff(p.B[1], p.z_b[1]), zoff(p.B[2], p.z_b[2])};
   TileRegs<TM / 32> ta;
   Tile128 tb;
   auto prefetch = [&](int it) {
     const int k0 = it * GK;
     if constexpr (AKM) load_km(ta, amat, 0, p.lda, k0, p.K, m0, p.M, tid);
     else {
-      load_mm(ta, p.A, p.lda, m0, p.M - 1, k0, p.K, tid);
-      if (p.ln_g) ln_tile_rows(ta, p.ln_g, p.ln_b, p.ln_eps, tid);  // K == 64: this is the only k-tile
+      load_mm(ta, pA, p.lda, m0, p.M - 1, k0, p.K, tid);
+      if (pln_g) ln_tile_rows(ta, pln_g, pln_b, p.ln_eps, tid);  // K == 64: this is the only k-tile
     }
     if (BKM) {
       load_km(tb, bmat, p.b_nper, p.ldb, k0, p.K, n0, p.N, tid);
     } else {
-      const bf16_t* Bp = p.B[0];
+      const bf16_t* Bp = bmat[0];
       int kk = k0, kmax = p.K;
-      if (p.b_kper > 0) { Bp = p.B[k0 / p.b_kper]; kk = k0 % p.b_kper; kmax = p.b_kper; }
+      if (p.b_kper > 0) {
+        const int bi = k0 / p.b_kper;
+        Bp = bi == 0 ? bmat[0] : bi == 1 ? bmat[1] : bmat[2];
+        kk = k0 - bi * p.b_kper; kmax = p.b_kper;
+      }
       load_mm(tb, Bp, p.ldb, n0, p.N - 1, kk, kmax, tid);
     }
   };
@@ -266,16 +280,31 @@ __global__ __launch_bounds__(256, 3) void mfma_gemm_kernel(MGemm p) {  // three 
 #pragma unroll
             for (int j = 0; j < 4; ++j) v[j] = gelu_erf_f(v[j]);
           }
-          if (p.res) {
-            const u32x2 rv = *(const u32x2*)(p.res + (long)m * p.ldc + n);
+          if (pres) {
+            const u32x2 rv = *(const u32x2*)(pres + (long)m * p.ldc + n);
             v[0] += __uint_as_float(rv[0] << 16); v[1] += __uint_as_float(rv[0] & 0xffff0000u);
             v[2] += __uint_as_float(rv[1] << 16); v[3] += __uint_as_float(rv[1] & 0xffff0000u);
           }
         }
         const u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-        *(u32x2*)(p.C + (long)m * p.ldc + n) = pk;
+        *(u32x2*)(pC + (long)m * p.ldc + n) = pk;
       }
   }
+}
+
+template <bool AKM, bool BKM, bool EPI, int TM = GM>
+__global__ __launch_bounds__(256, 3) void mfma_gemm_kernel(MGemm p) {  // three workgroups per CU: at most 168 registers
+  int bx, by, bz;
+  xcd_block_index(bx, by, bz);
+  mfma_gemm_tile<AKM, BKM, EPI, TM>(p, bx, by, bz, 0);
+}
+// Two independent GEMMs of the same shape in one launch (grid z = 2, no split-K): the layers of two encoders
+// that run side by side.  Each fills about half a launch on its own; together the tail of one is filled by the other.
+template <bool AKM, bool BKM, bool EPI, int TM = GM>
+__global__ __launch_bounds__(256, 3) void mfma_gemm_pair_kernel(MGemm p) {
+  int bx, by, bz;
+  xcd_block_index(bx, by, bz);
+  mfma_gemm_tile<AKM, BKM, EPI, TM>(p, bx, by, 0, bz);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -389,7 +418,7 @@ __global__ __launch_bounds__(NWV * 64) void mfma_gemm_dma_kernel(MGemm p) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       float bv[4] = {0.f, 0.f, 0.f, 0.f};
-      if (!p.partial) bias4(p, n0 + wn * WCOLS + nb * 32 + 8 * i + 4 * hi, bv);
+      if (!p.partial) bias4(p, p.bias, n0 + wn * WCOLS + nb * 32 + 8 * i + 4 * hi, bv);
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
@@ -626,7 +655,7 @@ __device__ __forceinline__ bf16x8 frag_rows(const bf16_t* lds, int ld, int row, 
   return as_bf16x8(*(const u32x4*)(lds + row * ld + col));
 }
 template <int D, bool PROJ>
-__global__ __launch_bounds__(256) void mlp_tail_kernel(MlpTailArgs p) {
+__device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
   constexpr int LDD = D + 8, LDC = 64 + 8;   // row strides (bf16) of tiles with D resp. 64 columns
   constexpr int NB = D / 64;                 // 32-column output blocks per wave
   __shared__ __attribute__((aligned(16))) bf16_t sA[64 * LDD];    // LN(h) rows
@@ -739,6 +768,15 @@ __global__ __launch_bounds__(256) void mlp_tail_kernel(MlpTailArgs p) {
       *(u32x2*)(p.y + (long)m * D + n) = pk;
     }
 }
+template <int D, bool PROJ>
+__global__ __launch_bounds__(256) void mlp_tail_kernel(MlpTailArgs p) {
+  mlp_tail_tile<D, PROJ>(p);
+}
+// the tails of two layers of the same shape (two encoders side by side) in one launch: grid y = 2
+template <int D, bool PROJ>
+__global__ __launch_bounds__(256) void mlp_tail_pair_kernel(MlpTailArgs p0, MlpTailArgs p1) {
+  mlp_tail_tile<D, PROJ>(blockIdx.y == 0 ? p0 : p1);
+}
 bool mlp_tail_ok(int is_bf16, long d, long d_ff, const void* h, const void* ln_g, const void* ln_b, const void* w1,
                  const void* w2, const void* y) {
   const uintptr_t a = (uintptr_t)h | (uintptr_t)ln_g | (uintptr_t)ln_b | (uintptr_t)w1 | (uintptr_t)w2 | (uintptr_t)y;
@@ -758,6 +796,18 @@ void launch_mlp_tail(const void* h, const void* ln_g, const void* ln_b, float ln
     if (o) hipLaunchKernelGGL((mlp_tail_kernel<128, true>), grid, block, 0, st, p);
     else hipLaunchKernelGGL((mlp_tail_kernel<128, false>), grid, block, 0, st, p);
   }
+}
+
+void launch_mlp_tail_pair(const MlpTailPairSide& a, const MlpTailPairSide& b, float ln_eps, int R, int d, int d_ff,
+                          hipStream_t st) {
+  auto mk = [&](const MlpTailPairSide& s) {
+    return MlpTailArgs{(const bf16_t*)s.x, (const bf16_t*)s.ln_g, (const bf16_t*)s.ln_b, ln_eps, (const bf16_t*)s.w1,
+                       (const bf16_t*)s.b1, (const bf16_t*)s.w2, (const bf16_t*)s.b2, (bf16_t*)s.y, R, d_ff,
+                       (const bf16_t*)s.o, (const bf16_t*)s.wo, (const bf16_t*)s.bo};
+  };
+  const dim3 grid((R + 63) / 64, 2), block(256);
+  if (d == 64) hipLaunchKernelGGL((mlp_tail_pair_kernel<64, true>), grid, block, 0, st, mk(a), mk(b));
+  else hipLaunchKernelGGL((mlp_tail_pair_kernel<128, true>), grid, block, 0, st, mk(a), mk(b));
 }
 
 // partial[z][M][N] -> out (fp32), z summed in fixed order; output column blocks may go to 3 matrices.
@@ -878,6 +928,37 @@ static void launch_layout(const MGemm& p, bool dma, hipStream_t st) {
   dim3 grid((p.N + GN - 1) / GN, (p.M + GM - 1) / GM, p.split_k);
   if (epi) hipLaunchKernelGGL((mfma_gemm_kernel<AKM, BKM, true>), grid, dim3(256), 0, st, p);
   else hipLaunchKernelGGL((mfma_gemm_kernel<AKM, BKM, false>), grid, dim3(256), 0, st, p);
+}
+
+// Two GEMMs of identical shape and layout (row-major A, k-major B, 64-row tiles, no split-K) in one launch.
+bool mfma_gemm_pair_ok(const MGemm& a, const MGemm& b) {
+  return !a.a_kmajor && a.b_kmajor && !b.a_kmajor && b.b_kmajor && a.M == b.M && a.N == b.N && a.K == b.K &&
+         a.lda == b.lda && a.ldb == b.ldb && a.ldc == b.ldc && a.b_nper == b.b_nper && a.b_kper == b.b_kper &&
+         a.n_per == b.n_per && a.scale0_on == b.scale0_on && a.scale0 == b.scale0 && a.ln_eps == b.ln_eps &&
+         a.gelu == b.gelu && (a.ln_g != nullptr) == (b.ln_g != nullptr) && (a.res != nullptr) == (b.res != nullptr) &&
+         (a.B[1] != nullptr) == (b.B[1] != nullptr) && (a.B[2] != nullptr) == (b.B[2] != nullptr) &&
+         (a.bias[0] != nullptr) == (b.bias[0] != nullptr) && (a.bias[1] != nullptr) == (b.bias[1] != nullptr) &&
+         (a.bias[2] != nullptr) == (b.bias[2] != nullptr) &&
+         a.split_k == 1 && b.split_k == 1 && !a.partial && !b.partial && a.M > 64;
+}
+void launch_mfma_gemm_pair(const MGemm& a, const MGemm& b, hipStream_t st) {
+  MGemm p = a;
+  auto off = [](const void* x, const void* y) { return (long)((const char*)y - (const char*)x); };
+  p.z_a = off(a.A, b.A); p.z_c = off(a.C, b.C); p.z_res = off(a.res, b.res);
+  p.z_ln_g = off(a.ln_g, b.ln_g); p.z_ln_b = off(a.ln_b, b.ln_b);
+  for (int i = 0; i < 3; ++i) { p.z_b[i] = off(a.B[i], b.B[i]); p.z_bias[i] = off(a.bias[i], b.bias[i]); }
+  const bool epi = a.gelu || a.res != nullptr;
+  // 64-row tiles when 128-row tiles would leave the chip under-filled (the rule of launch_layout, on both problems)
+  const long tiles = 2L * ((a.N + GN - 1) / GN) * ((a.M + GM - 1) / GM);
+  if (tiles < 256 || (epi && tiles < 512)) {
+    dim3 grid((a.N + GN - 1) / GN, (a.M + 63) / 64, 2);
+    if (epi) hipLaunchKernelGGL((mfma_gemm_pair_kernel<false, true, true, 64>), grid, dim3(256), 0, st, p);
+    else hipLaunchKernelGGL((mfma_gemm_pair_kernel<false, true, false, 64>), grid, dim3(256), 0, st, p);
+  } else {
+    dim3 grid((a.N + GN - 1) / GN, (a.M + GM - 1) / GM, 2);
+    if (epi) hipLaunchKernelGGL((mfma_gemm_pair_kernel<false, true, true, GM>), grid, dim3(256), 0, st, p);
+    else hipLaunchKernelGGL((mfma_gemm_pair_kernel<false, true, false, GM>), grid, dim3(256), 0, st, p);
+  }
 }
 
 void launch_mfma_gemm(const MGemm& p, hipStream_t st) {

@@ -94,6 +94,53 @@ void mfma_wgrad(const void* A, long lda, const void* G, long ldg, float* o0, flo
   launch_splitk_reduce(partial, p.split_k, M, N, o0, o1, o2, n_per, st);
 }
 
+// Q|K|V = x [Wq|Wk|Wv] + [bq|bk|bv]: the weights are [d_in][d_out] = k-major B operands.
+// Q is stored as scale * log2(e) * (x Wq + bq), rounded once: the attention kernels then get their
+// scores in the exponent domain of exp2 straight from the matrix cores (App. B's score scaling included)
+static void qkv_gemm(MGemm* p, const void* x, const void* wq, const void* wk, const void* wv, const void* bq,
+                     const void* bk, const void* bv, LnArgs ln, float scale_log2e, bf16_t* qkv, int R, int d) {
+  init_gemm(p);
+  p->A = (const bf16_t*)x; p->lda = d;
+  p->B[0] = (const bf16_t*)wq; p->B[1] = (const bf16_t*)wk; p->B[2] = (const bf16_t*)wv; p->ldb = d;
+  p->b_kmajor = 1; p->b_nper = d;
+  p->M = R; p->N = 3 * d; p->K = d;
+  p->bias[0] = (const bf16_t*)bq; p->bias[1] = (const bf16_t*)bk; p->bias[2] = (const bf16_t*)bv; p->n_per = d;
+  p->scale0_on = 1; p->scale0 = scale_log2e;
+  p->ln_g = (const bf16_t*)ln.g; p->ln_b = (const bf16_t*)ln.b; p->ln_eps = ln.eps;
+  p->C = qkv; p->ldc = 3 * d;
+}
+
+// The attention of two layers of the same shape (masks s0->live_mask and mask1, own weights, inputs x0 / x1) up
+// to the attention output O, in two launches instead of four: one launch holds both QKV projections (the
+// LayerNorm inside, model width 64), one both attention kernels.  sv: the forward's tensors for 2 B batch
+// elements (rows of the second problem after the first one's).  Returns false, with nothing enqueued, when the
+// shape is not one the paired kernels serve.
+bool mfma_attention_fwd_pair(const im_shape_t* s0, uint64_t mask1, const void* x0, const void* x1,
+                             const gsit_layer_params_t& p0, const gsit_layer_params_t& p1, LnArgs ln0, LnArgs ln1,
+                             const int32_t* valid_len, const uint8_t* key_pad, char* sv, size_t off_qkv, size_t off_o,
+                             size_t off_lse, hipStream_t st) {
+  const int dh = s0->d_model / s0->n_heads;
+  im_shape_t s1 = *s0;
+  s1.live_mask = mask1;
+  Geo g0, g1;
+  build_geo(s0, mfma_fwd_tile_rows(dh), mfma_dkv_tile_rows(), &g0);
+  build_geo(&s1, mfma_fwd_tile_rows(dh), mfma_dkv_tile_rows(), &g1);
+  if (!mfma_fwd_pair_ok(g0, g1) || !ln0.g || !ln1.g) return false;
+  const Dims dm = dims(s0);
+  const int d = (int)dm.d, R = (int)dm.R;
+  bf16_t* qkv = (bf16_t*)(sv + off_qkv);
+  bf16_t* o = (bf16_t*)(sv + off_o);
+  float* lse2 = (float*)(sv + off_lse);
+  MGemm a, b;
+  qkv_gemm(&a, x0, p0.wq, p0.wk, p0.wv, p0.bq, p0.bk, p0.bv, ln0, g0.scale_log2e, qkv, R, d);
+  qkv_gemm(&b, x1, p1.wq, p1.wk, p1.wv, p1.bq, p1.bk, p1.bv, ln1, g1.scale_log2e, qkv + (size_t)R * 3 * d, R, d);
+  if (!mfma_gemm_pair_ok(a, b)) return false;
+  { ProfScope ps(PF_PROJ_FWD, st);
+    launch_mfma_gemm_pair(a, b, st); }
+  launch_mfma_fwd_pair(g0, g1, qkv, 3 * d, valid_len, key_pad, o, d, lse2, st);
+  return true;
+}
+
 int mfma_attention_fwd(const im_shape_t* s, const void* x, const void* wq, const void* wk, const void* wv,
                        const void* wo, const void* bq, const void* bk, const void* bv, const void* bo,
                        const int32_t* valid_len, const uint8_t* key_pad, void* y, const void* res, char* sv,
@@ -108,19 +155,8 @@ int mfma_attention_fwd(const im_shape_t* s, const void* x, const void* wq, const
 
   MGemm p;
   {
-    // Q|K|V = x [Wq|Wk|Wv] + [bq|bk|bv]: the weights are [d_in][d_out] = k-major B operands
     ProfScope ps(PF_PROJ_FWD, st);
-    init_gemm(&p);
-    p.A = (const bf16_t*)x; p.lda = d;
-    p.B[0] = (const bf16_t*)wq; p.B[1] = (const bf16_t*)wk; p.B[2] = (const bf16_t*)wv; p.ldb = d;
-    p.b_kmajor = 1; p.b_nper = d;
-    p.M = (int)dm.R; p.N = 3 * d; p.K = d;
-    p.bias[0] = (const bf16_t*)bq; p.bias[1] = (const bf16_t*)bk; p.bias[2] = (const bf16_t*)bv; p.n_per = d;
-    // Q is stored as scale * log2(e) * (x Wq + bq), rounded once: the attention kernels then get their
-    // scores in the exponent domain of exp2 straight from the matrix cores (App. B's score scaling included)
-    p.scale0_on = 1; p.scale0 = g.scale_log2e;
-    p.ln_g = (const bf16_t*)ln.g; p.ln_b = (const bf16_t*)ln.b; p.ln_eps = ln.eps;
-    p.C = qkv; p.ldc = 3 * d;
+    qkv_gemm(&p, x, wq, wk, wv, bq, bk, bv, ln, g.scale_log2e, qkv, (int)dm.R, d);
     launch_mfma_gemm(p, st);
   }
 

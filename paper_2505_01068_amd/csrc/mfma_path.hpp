@@ -20,8 +20,13 @@ struct MGemm {
   int gelu;
   const bf16_t* res;                     // residual rows, same ld as C
   bf16_t* C; long ldc;                   // row-major output
+  // paired launch (launch_mfma_gemm_pair): byte offsets from this problem's tensors to the second problem's
+  long z_a, z_b[3], z_bias[3], z_ln_g, z_ln_b, z_res, z_c;
 };
 void launch_mfma_gemm(const MGemm& p, hipStream_t st);
+// two GEMMs of identical shape (row-major A, k-major B, no split-K) in one launch, when mfma_gemm_pair_ok
+bool mfma_gemm_pair_ok(const MGemm& a, const MGemm& b);
+void launch_mfma_gemm_pair(const MGemm& a, const MGemm& b, hipStream_t st);
 // LayerNorm over the K axis of a row-major A can run inside the GEMM when a tile row is the whole feature row
 inline bool mfma_gemm_fuses_ln(int is_bf16, long K, long N) { return is_bf16 && K == 64 && N % 8 == 0 && N >= 8; }
 // LayerNorm parameters for the rows of the left operand (all NULL / 0: none)
@@ -50,6 +55,13 @@ bool mlp_tail_ok(int is_bf16, long d, long d_ff, const void* h, const void* ln_g
 void launch_mlp_tail(const void* h, const void* ln_g, const void* ln_b, float ln_eps, const void* w1, const void* b1,
                      const void* w2, const void* b2, void* y, int R, int d, int d_ff, hipStream_t st,
                      const void* o = nullptr, const void* wo = nullptr, const void* bo = nullptr);
+// the same for two layers of identical shape in one launch (output projection included: o, wo, bo as above)
+struct MlpTailPairSide {
+  const void *x, *ln_g, *ln_b, *w1, *b1, *w2, *b2, *o, *wo, *bo;
+  void* y;
+};
+void launch_mlp_tail_pair(const MlpTailPairSide& a, const MlpTailPairSide& b, float ln_eps, int R, int d, int d_ff,
+                          hipStream_t st);
 int mfma_gemm_split(int M, int N, int K);
 void launch_splitk_reduce(const float* partial, int split_k, int M, int N, float* o0, float* o1, float* o2, int n_per,
                           hipStream_t st);
@@ -59,6 +71,9 @@ int mfma_dq_tile_rows();
 int mfma_dkv_tile_rows();
 void launch_mfma_fwd(const Geo& g, const bf16_t* qkv, long ld, const int32_t* valid_len, const uint8_t* key_pad,
                      bf16_t* o, long ldo, float* lse2, hipStream_t st);
+bool mfma_fwd_pair_ok(const Geo& g0, const Geo& g1);
+void launch_mfma_fwd_pair(const Geo& g0, const Geo& g1, const bf16_t* qkv, long ld, const int32_t* valid_len,
+                          const uint8_t* key_pad, bf16_t* o, long ldo, float* lse2, hipStream_t st);
 void launch_mfma_bwd(const Geo& g, const bf16_t* qkv, long ld, const bf16_t* o, const bf16_t* d_o, long ldo,
                      const float* lse2, const int32_t* valid_len, const uint8_t* key_pad, float* delta, bf16_t* dqkv,
                      long ldg, hipStream_t st);
@@ -77,6 +92,10 @@ int mfma_attention_fwd(const im_shape_t* s, const void* x, const void* wq, const
                        const int32_t* valid_len, const uint8_t* key_pad, void* y, const void* res, char* sv,
                        size_t off_qkv, size_t off_o, size_t off_lse, size_t off_extra, char* ws, hipStream_t st,
                        LnArgs ln = {nullptr, nullptr, 0.f});   // ln: LayerNorm x inside the QKV projection
+bool mfma_attention_fwd_pair(const im_shape_t* s0, uint64_t mask1, const void* x0, const void* x1,
+                             const gsit_layer_params_t& p0, const gsit_layer_params_t& p1, LnArgs ln0, LnArgs ln1,
+                             const int32_t* valid_len, const uint8_t* key_pad, char* sv, size_t off_qkv, size_t off_o,
+                             size_t off_lse, hipStream_t st);
 int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const void* wk, const void* wv,
                        const void* wo, const int32_t* valid_len, const uint8_t* key_pad, const char* sv,
                        size_t off_qkv, size_t off_o, size_t off_lse, size_t off_extra, const void* dy, void* dx,
