@@ -128,7 +128,7 @@ def measured_peaks(B, torch, quick=True):
     """What this GPU sustains: a register-resident bf16 MFMA loop (TFLOP/s) and a streaming device copy
     (GB/s, bytes read + bytes written).  Best of a few launches each."""
     sink = torch.zeros(64, dtype=torch.float32, device="cuda")
-    iters = 2000 if quick else 8000
+    iters = 8000   # ~4 ms per launch: shorter loops under-read the sustained rate by up to 10 % (ramp-up)
     best_mfma = 0.0
     for _ in range(4):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -835,32 +835,18 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void mfma_dkv_kernel(Geo g, 
 }
 
 // ---- host launchers ----
-// Query blocks per wave in the forward: 1 at head dim 64 (about 130 registers, three workgroups per CU: measured
-// 6 % faster than 2 blocks per wave at two workgroups per CU), 2 in sub-head mode (half the K/V tile traffic per
-// score; measured 2 % faster there).
+// Launch shapes, each chosen by measurement at B = 8, segments 512 / 2048 / 2048, d = 512, 8 heads:
+//   forward, head dim 64: 1 query block per wave, 4 waves, a 2-stage ring and 128 registers, so that four
+//     workgroups (16 waves) share a CU -- 10 % faster than 3 stages at three workgroups; 8-wave workgroups
+//     (256 query rows) were slower;
+//   forward, sub-head mode: 2 query blocks per wave (half the K/V tile traffic per score), 3 stages, 3 workgroups;
+//   dQ, head dim 64: 3 stages, 3 workgroups per CU, accumulators seeded with -lse and -delta (unseeded: 7 % slower;
+//     4 workgroups need spills);
+//   dK/dV: 1 key block per wave, 3 workgroups per CU.
 constexpr int FWD_QB = 1, FWD_QB_SUB = 2, DQ_QB = 1, DKV_KB = 1;
-#ifndef IM_FWD_NST
-#define IM_FWD_NST 2
-#endif
-#ifndef IM_FWD_WGS
-#define IM_FWD_WGS 4
-#endif
-#ifndef IM_FWD_SUB_WGS
-#define IM_FWD_SUB_WGS 3
-#endif
-#ifndef IM_FWD_NW
-#define IM_FWD_NW 4
-#endif
-#ifndef IM_DQ_NST
-#define IM_DQ_NST 3
-#endif
-#ifndef IM_DQ_WGS
-#define IM_DQ_WGS 3
-#endif
-#ifndef IM_DQ_SEED
-#define IM_DQ_SEED true
-#endif
-constexpr int FWD_NST = IM_FWD_NST, FWD_WGS = IM_FWD_WGS, FWD_NW = IM_FWD_NW;  // ring stages, workgroups per CU and waves per workgroup of the forward at head dim 64
+constexpr int FWD_NST = 2, FWD_WGS = 4, FWD_NW = 4;   // ring stages, workgroups per CU, waves per workgroup (head dim 64)
+constexpr int FWD_SUB_NST = 3, FWD_SUB_WGS = 3;       // the same in sub-head mode (4 waves)
+constexpr int DQ_NST = 3, DQ_WGS = 3;                 // dQ at head dim 64
 int mfma_fwd_tile_rows(int dh) { return dh == 64 ? 32 * FWD_NW * FWD_QB : 128 * FWD_QB_SUB; }
 int mfma_dq_tile_rows() { return 128 * DQ_QB; }
 int mfma_dkv_tile_rows() { return 128 * DKV_KB; }
@@ -878,8 +864,8 @@ void launch_mfma_fwd(const Geo& g, const bf16_t* qkv, long ld, const int32_t* va
   ProfScope ps(PF_ATTN_FWD, st);
   const dim3 grid(nt, g.H, g.B);
   if (g.dh == 64) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB, 64, FWD_NST, FWD_WGS, FWD_NW, false>), grid, dim3(64 * FWD_NW), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
-  else if (g.dh == 16) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 16, 3, IM_FWD_SUB_WGS, 4, false>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
-  else hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 8, 3, IM_FWD_SUB_WGS, 4, false>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  else if (g.dh == 16) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 16, FWD_SUB_NST, FWD_SUB_WGS, 4, false>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  else hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 8, FWD_SUB_NST, FWD_SUB_WGS, 4, false>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
 }
 
 // Forward of two problems of the same shape (masks g0 / g1) in one launch; their rows follow each other in
@@ -900,8 +886,8 @@ void launch_mfma_fwd_pair(const Geo& g0, const Geo& g1, const bf16_t* qkv, long 
   for (int i = 0; i <= IM_MAX_SEG; ++i) g.q_tile_prefix2[i] = g1.q_tile_prefix[i];
   ProfScope ps(PF_ATTN_FWD, st);
   const dim3 grid(g.q_tile_prefix[g.q_nord], g.H, 2 * g.B);
-  if (g.dh == 16) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 16, 3, IM_FWD_SUB_WGS, 4, true>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
-  else hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 8, 3, IM_FWD_SUB_WGS, 4, true>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  if (g.dh == 16) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 16, FWD_SUB_NST, FWD_SUB_WGS, 4, true>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  else hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 8, FWD_SUB_NST, FWD_SUB_WGS, 4, true>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
 }
 
 void launch_mfma_bwd(const Geo& g, const bf16_t* qkv, long ld, const bf16_t* o, const bf16_t* d_o, long ldo,
@@ -917,7 +903,7 @@ void launch_mfma_bwd(const Geo& g, const bf16_t* qkv, long ld, const bf16_t* o, 
   if (nq == 0) return;
   { ProfScope ps(PF_ATTN_DQ, st);
     const dim3 grid(nq, g.H, g.B);
-    if (g.dh == 64) hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 64, IM_DQ_NST, IM_DQ_WGS, IM_DQ_SEED>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg);
+    if (g.dh == 64) hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 64, DQ_NST, DQ_WGS, true>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg);
     else if (g.dh == 16) hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 16, 3, 2, true>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg);
     else hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 8, 3, 2, true>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg); }
   { ProfScope ps(PF_ATTN_DKV, st);
