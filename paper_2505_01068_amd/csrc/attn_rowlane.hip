@@ -296,6 +296,18 @@ __global__ __launch_bounds__(NW * RL_ROWS) void rowlane_dkv_kernel(Geo g, const 
   const long t = seg_row0(g, b, ks) + (in_seg ? row : 0);
   if (valid && key_pad) valid = key_pad[t] == 0;
   const int dh = g.dh, hc = h * dh;
+  // A tile that lies entirely behind the segment's valid length has no key that any query attends: zeros.
+  if (valid_len && k0 >= valid_len[b * g.n_seg + ks]) {
+    if (in_seg && wave == 0) {
+#pragma unroll
+      for (int e = 0; e < DH; ++e)
+        if (e < dh) {
+          stf(dK + t * ldg + hc + e, 0.f);
+          stf(dV + t * ldg + hc + e, 0.f);
+        }
+    }
+    return;
+  }
 
   float k[DH], v[DH], ak[DH], av[DH];
 #pragma unroll
@@ -416,9 +428,13 @@ bool rowlane_supports(int dh) { return dh >= 1 && dh <= 16; }
     else LAUNCH(16);            \
   } while (0)
 
-// Waves per tile: 4 when some tile has more than one chunk of the other operand to walk through
-// (by the maximum segment lengths), else 1.
-constexpr int RL_SPLIT = 4;
+// Waves per tile when some tile has more than one chunk of the other operand to walk through (by the maximum
+// segment lengths), else 1.  Measured at B = 32, 50/500/375 rows, 8 heads of 5 (forward / dQ / dK/dV in us):
+// 1 wave 63 / 74 / -, 2 waves 43 / 60 / 70, 3 waves 46 / 65 / 63, 4 waves 48 / 71 / 64.  A wave lives for three
+// dependent memory round trips (indices and lengths, its rows, its chunk) around about 45 keys of arithmetic, so
+// the kernels are bound by latency and by the instructions around the loop, and fewer, longer waves win until the
+// longest tile (one wave walking through 500 keys) sets the time.
+constexpr int RL_SPLIT = 2, RL_SPLIT_KV = 4;
 static int max_chunks(const Geo& g, bool query_side) {
   int best = 0;
   for (int i = 0; i < g.n_seg; ++i) {
@@ -496,7 +512,7 @@ static int bwd_dispatch(const Geo& g, const T* q, const T* k, const T* v, long l
   } while (0)
 #define RL_DKV(DHV)                                                                                                        \
   do {                                                                                                                     \
-    if (split_k) hipLaunchKernelGGL((rowlane_dkv_kernel<T, DHV, RL_SPLIT>), dim3(nk, g.H, g.B), dim3(RL_SPLIT * RL_ROWS), 0,  \
+    if (split_k) hipLaunchKernelGGL((rowlane_dkv_kernel<T, DHV, RL_SPLIT_KV>), dim3(nk, g.H, g.B), dim3(RL_SPLIT_KV * RL_ROWS), 0,  \
                                     st, g, q, k, v, ld, d_o, ldo, lse2, delta, vl, kp, dk, dv, ldg);                        \
     else hipLaunchKernelGGL((rowlane_dkv_kernel<T, DHV, 1>), dim3(nk, g.H, g.B), dim3(RL_ROWS), 0, st, g, q, k, v, ld, d_o,  \
                             ldo, lse2, delta, vl, kp, dk, dv, ldg);                                                        \

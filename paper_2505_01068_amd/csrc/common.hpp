@@ -209,6 +209,12 @@ void launch_wgrad_small_reduce(const float* partial, int nz, int M, int N, float
                                hipStream_t st);
 int launch_wgrad_small(const void* A, long lda, const void* G, long ldg, int R, int M, int N, int in_bf16, float* partial,
                        hipStream_t st);
+// the same for fp32 operands of a tall matrix (R >= 1024, M <= 64, N <= 128) on the fp32 matrix instruction; sums the
+// partial results itself: C into o0 (n_per == 0) or column blocks of n_per columns into o0 | o1 | o2 (NULL = dropped)
+bool wgrad_mfma_ok(int M, int N, int R, int in_bf16);
+size_t wgrad_mfma_partial_bytes(int M, int N, int R);
+void launch_wgrad_mfma_f32(const float* A, long lda, const float* G, long ldg, int R, int M, int N, float* partial,
+                           float* o0, float* o1, float* o2, int n_per, hipStream_t st);
 
 // encoder-layer backward pieces: a = GELU(z); g <- g * GELU'(z) in place; LayerNorm backward of rows
 // (dx = input gradient + res (res may be NULL), t = dy * xhat for the gamma gradient)

@@ -162,6 +162,244 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmDev g) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// fp32 GEMM of a tall matrix with a small weight on the fp32 matrix instruction
+// (v_mfma_f32_32x32x2_f32: products and sums in fp32, twice the vector FMA rate): the projections of the
+// narrow models (d = 32..64: [rows, d] x [d, 3d], [rows, 3d] x [3d, d], ...).  One pass over A, no tiles of A
+// in LDS: the product is computed transposed, C^T = B^T A^T, so that a lane owns one output row --
+//   matrix-instruction "A" operand = the weight: lane (n = lane % 32, h = lane / 32) holds B(k = h Kh + j, n)
+//     for step j; the whole weight sits in LDS in exactly that order (Kh x NB x 64 floats, one conflict-free
+//     4-byte read per instruction), filled once per workgroup with 16-byte loads;
+//   "B" operand = a 32-row block of A: lane (m, h) holds A(m, h Kh + j), i.e. the lane reads Kh CONSECUTIVE
+//     elements of its row (16-byte loads, all requested at once) -- the contraction index is simply visited in
+//     the order (0, Kh), (1, Kh + 1), ..., which both operands agree on;
+//   accumulator register r of block nb = column nb 32 + 8 (r / 4) + 4 h + r % 4 of row m: four consecutive
+//     columns per register quad; the accumulators start at the bias and are stored with 16-byte stores.
+// A wave owns a 32-row block and at most two 32-column blocks (wider outputs are shared by two waves that read
+// the same rows): at these sizes the kernel is not bound by the matrix pipe but by the instructions around it,
+// executed by waves that have a SIMD to themselves, so the work per wave is kept short and the index arithmetic
+// out of the loops.  K is padded to a multiple of 8 with zeros (LDS is cleared first; A elements past K are not
+// loaded).
+typedef float f32x16s __attribute__((ext_vector_type(16)));
+constexpr int SK_MAX_LDS_FLOATS = 12288;   // 48 KB: Kh * NB * 64 floats
+constexpr int SK_MAX_CH = 16;              // 4-element chunks of a lane's half row held in registers: K <= 128
+constexpr int SK_NBW = 2;                  // 32-column blocks per wave (the kernel is written for 2)
+
+// fill: 0 = element by element (any strides), 1 = B(k, n .. n+3) contiguous, 2 = B(k .. k+3, n) contiguous
+template <bool AVEC, int NCH>   // NCH = Kh / 4: 4-element chunks of a lane's half row (straight-line code per size)
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmDev g, int NB, int nparts, int fill) {
+  constexpr int Kh = 4 * NCH;
+  extern __shared__ __attribute__((aligned(16))) float wl[];   // [Kh][NB][64]
+  const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, ml = lane & 31;
+  const float* A = (const float*)g.A;
+  const int nblk = (g.M + 31) >> 5;
+  const int units = nblk * nparts, stride = gridDim.x * 4;   // stride is a multiple of nparts (1 or 2)
+  const int k0 = h * Kh;
+  float x[NCH][4];
+  auto load_rows = [&](int rb) {
+    const int m = rb * 32 + ml;
+    const int mr = m < g.M ? m : g.M - 1;   // rows past the end read the last row; they are not stored
+    const float* arow = A + (long)mr * g.sam;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      if (AVEC) {
+        const float4 v = *(const float4*)(arow + k0 + 4 * c);
+        x[c][0] = v.x; x[c][1] = v.y; x[c][2] = v.z; x[c][3] = v.w;
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int k = k0 + 4 * c + u;
+          x[c][u] = k < g.K ? arow[(long)k * g.sak] : 0.f;
+        }
+      }
+    }
+  };
+  int unit = blockIdx.x * 4 + (tid >> 6);
+  const int nb0 = (unit % nparts) * SK_NBW;   // the same for every unit of this wave
+  if (unit < units) load_rows(unit / nparts);
+
+  // accumulators start at the bias
+  f32x16s binit[SK_NBW];
+#pragma unroll
+  for (int nb = 0; nb < SK_NBW; ++nb)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int n0 = (nb0 + nb) * 32 + 8 * q + 4 * h;
+      float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (n0 < g.N) {
+        int sel = 0, nn = n0;
+        if (g.bias_split) { sel = (n0 >= g.n_per) + (n0 >= 2 * g.n_per); nn = n0 - sel * g.n_per; }
+        const float* bp = sel == 0 ? (const float*)g.bias[0] : sel == 1 ? (const float*)g.bias[1] : (const float*)g.bias[2];
+        if (bp) bv = *(const float4*)(bp + nn);
+      }
+      binit[nb][4 * q] = bv.x; binit[nb][4 * q + 1] = bv.y; binit[nb][4 * q + 2] = bv.z; binit[nb][4 * q + 3] = bv.w;
+    }
+
+  // the weight into LDS
+  const int nw = Kh * NB * 64;
+  for (int i = tid * 4; i < nw; i += 1024) *(float4*)(wl + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+  __syncthreads();
+  if (fill == 1) {
+    const int Q = g.N >> 2, G = g.K * Q;
+    for (int base = tid; base < G; base += 4 * 256) {
+      float4 wv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int gi = base + u * 256;
+        wv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (gi < G) {
+          const int k = gi / Q, n0 = (gi - k * Q) * 4;
+          int sel = 0, kk = k, nn = n0;
+          if (g.b_split == 1) { sel = (n0 >= g.n_per) + (n0 >= 2 * g.n_per); nn = n0 - sel * g.n_per; }
+          else if (g.b_split == 2) { sel = (k >= g.k_per) + (k >= 2 * g.k_per); kk = k - sel * g.k_per; }
+          const float* bp = sel == 0 ? (const float*)g.B[0] : sel == 1 ? (const float*)g.B[1] : (const float*)g.B[2];
+          wv[u] = *(const float4*)(bp + (long)kk * g.sbk + nn);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int gi = base + u * 256;
+        if (gi < G) {
+          const int k = gi / Q, n0 = (gi - k * Q) * 4;
+          const int hh = k >= Kh, j = k - hh * Kh;
+          *(float4*)(wl + (j * NB + (n0 >> 5)) * 64 + hh * 32 + (n0 & 31)) = wv[u];
+        }
+      }
+    }
+  } else if (fill == 2) {
+    const int Q = g.K >> 2, G = g.N * Q;
+    for (int base = tid; base < G; base += 4 * 256) {
+      float4 wv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int gi = base + u * 256;
+        wv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (gi < G) {
+          const int n = gi / Q, kb = (gi - n * Q) * 4;
+          int sel = 0, kk = kb, nn = n;
+          if (g.b_split == 1) { sel = (n >= g.n_per) + (n >= 2 * g.n_per); nn = n - sel * g.n_per; }
+          else if (g.b_split == 2) { sel = (kb >= g.k_per) + (kb >= 2 * g.k_per); kk = kb - sel * g.k_per; }
+          const float* bp = sel == 0 ? (const float*)g.B[0] : sel == 1 ? (const float*)g.B[1] : (const float*)g.B[2];
+          wv[u] = *(const float4*)(bp + (long)nn * g.sbn + kk);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int gi = base + u * 256;
+        if (gi < G) {
+          const int n = gi / Q, kb = (gi - n * Q) * 4;
+          const int hh = kb >= Kh, j = kb - hh * Kh;   // Kh and kb are multiples of 4: the four k share a half
+          float* dst = wl + (j * NB + (n >> 5)) * 64 + hh * 32 + (n & 31);
+          dst[0] = wv[u].x; dst[NB * 64] = wv[u].y; dst[2 * NB * 64] = wv[u].z; dst[3 * NB * 64] = wv[u].w;
+        }
+      }
+    }
+  } else {
+    for (int idx = tid; idx < nw; idx += 256) {
+      const int l = idx & 63, nb = (idx >> 6) % NB, j = idx / (64 * NB);
+      const int n = nb * 32 + (l & 31), k = (l >> 5) * Kh + j;
+      if (n < g.N && k < g.K) {
+        int sel = 0, kk = k, nn = n;
+        if (g.b_split == 1) { sel = (n >= g.n_per) + (n >= 2 * g.n_per); nn = n - sel * g.n_per; }
+        else if (g.b_split == 2) { sel = (k >= g.k_per) + (k >= 2 * g.k_per); kk = k - sel * g.k_per; }
+        const float* bp = sel == 0 ? (const float*)g.B[0] : sel == 1 ? (const float*)g.B[1] : (const float*)g.B[2];
+        wl[idx] = bp[(long)kk * g.sbk + (long)nn * g.sbn];
+      }
+    }
+  }
+  __syncthreads();
+
+  for (; unit < units; unit += stride) {
+    const int rb = unit / nparts;
+    const int m = rb * 32 + ml;
+    f32x16s acc[SK_NBW];
+#pragma unroll
+    for (int nb = 0; nb < SK_NBW; ++nb) acc[nb] = binit[nb];
+    // a wave whose second column block does not exist (odd NB) multiplies its first block twice; nothing of the
+    // copy is stored.  No branch around a matrix instruction: the accumulators stay where they are.
+    const float* wbase = wl + nb0 * 64 + lane;
+    const int second = nb0 + 1 < NB ? 64 : 0;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float* wrow = wbase + (c * 4 + u) * NB * 64;
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(wrow[0], x[c][u], acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(wrow[second], x[c][u], acc[1], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);   // one chunk's weight reads at a time (hoisted together they take 2 * Kh registers)
+    }
+    if (unit + stride < units) load_rows((unit + stride) / nparts);
+    if (m >= g.M) continue;
+#pragma unroll
+    for (int nb = 0; nb < SK_NBW; ++nb)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n0 = (nb0 + nb) * 32 + 8 * q + 4 * h;
+        if (n0 >= g.N) continue;
+        float4 v = make_float4(acc[nb][4 * q], acc[nb][4 * q + 1], acc[nb][4 * q + 2], acc[nb][4 * q + 3]);
+        float* dst;
+        if (g.c_split) {
+          const int sel = (n0 >= g.n_per) + (n0 >= 2 * g.n_per);
+          float* cp = sel == 0 ? (float*)g.C[0] : sel == 1 ? (float*)g.C[1] : (float*)g.C[2];
+          dst = cp + (long)m * g.ldc + (n0 - sel * g.n_per);
+        } else {
+          dst = (float*)g.C[0] + (long)m * g.ldc + n0;
+          if (g.res) {
+            const float4 r = *(const float4*)((const float*)g.res + (long)m * g.ldc + n0);
+            v.x += r.x; v.y += r.y; v.z += r.z; v.w += r.w;
+          }
+        }
+        *(float4*)dst = v;
+      }
+  }
+}
+
+static bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
+
+// true if the launch was done by the matrix-instruction kernel above
+static bool launch_gemm_skinny(const GemmDev& g, hipStream_t st) {
+  // (a GELU epilogue stays with the ALU kernel: erf inlined once per accumulator register is too much code)
+  if (g.gelu || g.split_k > 1 || g.kb > 1 || g.M < 1024 || g.N > 128 || g.K > 8 * SK_MAX_CH) return false;
+  const int NB = (g.N + 31) / 32;
+  const int Kh = ((g.K + 7) / 8) * 4;
+  if ((long)Kh * NB * 64 > SK_MAX_LDS_FLOATS) return false;
+  if ((g.b_split == 1 || g.c_split || g.bias_split) && g.n_per <= 0) return false;
+  if (g.b_split == 2 && (g.k_per <= 0 || g.K > 3 * g.k_per)) return false;
+  if (g.n_per > 0 && g.N > 3 * g.n_per) return false;
+  const bool avec = g.sak == 1 && g.K % 8 == 0 && g.sam % 4 == 0 && aligned16(g.A);
+  // outputs, residual and biases are accessed four columns at a time
+  const bool split_n = g.c_split || g.bias_split;
+  bool cvec = g.N % 4 == 0 && g.ldc % 4 == 0 && (!split_n || g.n_per % 4 == 0) && (!g.res || aligned16(g.res));
+  const int nbuf = split_n ? (g.N + g.n_per - 1) / g.n_per : 1;
+  for (int i = 0; i < (g.c_split ? nbuf : 1); ++i) cvec = cvec && g.C[i] && aligned16(g.C[i]);
+  for (int i = 0; i < (g.bias_split ? nbuf : 1); ++i) cvec = cvec && (!g.bias[i] || aligned16(g.bias[i]));
+  if (!cvec) return false;   // the ALU kernel takes those
+  // how the weight can be read
+  const int nB = g.b_split ? (g.b_split == 1 ? (g.N + g.n_per - 1) / g.n_per : (g.K + g.k_per - 1) / g.k_per) : 1;
+  bool b_al = true;
+  for (int i = 0; i < nB; ++i) b_al = b_al && aligned16(g.B[i]);
+  int fill = 0;
+  if (b_al && g.sbn == 1 && g.sbk % 4 == 0 && g.N % 4 == 0 && (g.b_split != 1 || g.n_per % 4 == 0)) fill = 1;
+  else if (b_al && g.sbk == 1 && g.sbn % 4 == 0 && g.K % 4 == 0 && (g.b_split != 2 || g.k_per % 4 == 0)) fill = 2;
+  const int nblk = (g.M + 31) / 32;
+  const int nparts = (NB + SK_NBW - 1) / SK_NBW;   // 1 or 2
+  const dim3 grid(std::min((nblk * nparts + 3) / 4, 2048)), block(256);
+  const size_t lds = (size_t)Kh * NB * 64 * sizeof(float);
+#define SK_CASE(N_)                                                                                               \
+  case N_:                                                                                                        \
+    if (avec) hipLaunchKernelGGL((gemm_skinny_kernel<true, N_>), grid, block, lds, st, g, NB, nparts, fill);       \
+    else hipLaunchKernelGGL((gemm_skinny_kernel<false, N_>), grid, block, lds, st, g, NB, nparts, fill);           \
+    break
+  switch (Kh / 4) {
+    SK_CASE(1); SK_CASE(2); SK_CASE(3); SK_CASE(4); SK_CASE(5); SK_CASE(6); SK_CASE(7); SK_CASE(8);
+    SK_CASE(9); SK_CASE(10); SK_CASE(11); SK_CASE(12); SK_CASE(13); SK_CASE(14); SK_CASE(15); SK_CASE(16);
+    default: return false;
+  }
+#undef SK_CASE
+  return true;
+}
+
 size_t gemm_alu_partial_bytes(int M, int N, int K, int* split_k) {
   // Split only reductions that are much longer than the output is wide (weight gradients).
   int s = 1;
@@ -187,6 +425,7 @@ int launch_gemm_alu(const GemmDesc& d, int a_bf16, int b_bf16, int c_bf16, hipSt
   g.split_k = d.split_k > 1 ? d.split_k : 1; g.partial = d.partial;
   g.kb = d.kb > 1 ? d.kb : 1; g.kt = d.kb > 1 ? d.kt : d.K; g.sab = d.sab; g.sbb = d.sbb;
   if (g.M <= 0 || g.N <= 0) return IM_OK;
+  if (!a_bf16 && !b_bf16 && !c_bf16 && launch_gemm_skinny(g, st)) return IM_OK;
   dim3 grid((g.N + GA_BN - 1) / GA_BN, (g.M + GA_BM - 1) / GA_BM, g.split_k), block(GA_THREADS);
   const int key = (a_bf16 ? 4 : 0) | (b_bf16 ? 2 : 0) | (c_bf16 ? 1 : 0);
   switch (key) {
@@ -306,6 +545,182 @@ void launch_wgrad_small_reduce(const float* partial, int nz, int M, int N, float
   const long n_out = (long)M * N;
   hipLaunchKernelGGL(wgrad_small_reduce_kernel, dim3((unsigned)((n_out + 15) / 16)), dim3(256), 0, st, partial, nz, M, N, o0,
                      o1, o2, n_per);
+}
+
+// The same weight gradient on the fp32 matrix instruction: C = A^T G is a product whose contraction runs over the
+// rows, and both operands are read exactly as they lie in memory -- lane (c = lane % 32, h = lane / 32) takes
+// column c of row r + h, a coalesced 128-byte piece per half wave; no LDS in the loop.  A workgroup of 4 waves owns
+// `rows_per_wg` consecutive rows, a quarter each; the four accumulator sets are added through LDS as
+// (w0 + w2) + (w1 + w3), a fixed order, and the workgroup writes one partial result IN ACCUMULATOR ORDER
+// ([block][register quad][lane][4]: 16-byte stores, no index arithmetic); wgrad_mfma_reduce_kernel adds the
+// partials in a fixed order and undoes the layout.  Columns past M resp. N read the last valid column: they only
+// reach accumulator rows / columns that nobody reads.
+template <int MB, int NB>
+__global__ __launch_bounds__(256) void wgrad_mfma_f32_kernel(const float* __restrict__ A, long lda,
+                                                              const float* __restrict__ G, long ldg, int R, int M, int N,
+                                                              int rows_per_wg, float* __restrict__ partial) {
+  constexpr int NBLK = MB * NB;
+  __shared__ __attribute__((aligned(16))) float red[2][NBLK * 16 * 64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, c = lane & 31, h = lane >> 5;
+  const int rpw = rows_per_wg >> 2;   // a multiple of 16
+  const long row0 = (long)blockIdx.x * rows_per_wg + (long)w * rpw;
+  f32x16s acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  int ca[MB], cg[NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i) ca[i] = min(i * 32 + c, M - 1);
+#pragma unroll
+  for (int j = 0; j < NB; ++j) cg[j] = min(j * 32 + c, N - 1);
+  const bool full = row0 + rpw <= R;   // wave-uniform: only the last rows of the matrix need the row test
+  // Eight rows (four contraction steps) per group; the next group's 4 (MB + NB) loads are in flight while the
+  // current group is multiplied.  rpw is a multiple of 16: two groups per trip, in two fixed register sets.
+  float a0[4][MB], g0[4][NB], a1[4][MB], g1[4][NB];
+  auto load = [&](int r, float (&a)[4][MB], float (&g)[4][NB]) {
+    const float* pa = A + (row0 + r + h) * lda;
+    const float* pg = G + (row0 + r + h) * ldg;
+    if (full) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i) a[u][i] = pa[2 * u * lda + ca[i]];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) g[u][j] = pg[2 * u * ldg + cg[j]];
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const bool ok = row0 + r + 2 * u + h < R;
+#pragma unroll
+        for (int i = 0; i < MB; ++i) a[u][i] = ok ? pa[2 * u * lda + ca[i]] : 0.f;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) g[u][j] = ok ? pg[2 * u * ldg + cg[j]] : 0.f;
+      }
+    }
+  };
+  auto multiply = [&](const float (&a)[4][MB], const float (&g)[4][NB]) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][i], g[u][j], acc[i][j], 0, 0, 0);
+  };
+  load(0, a0, g0);
+  for (int r = 0; r < rpw; r += 16) {
+    load(r + 8, a1, g1);
+    multiply(a0, g0);
+    if (r + 16 < rpw) load(r + 16, a0, g0);
+    multiply(a1, g1);
+  }
+  // (w0 + w2) + (w1 + w3) through LDS, 16 bytes per lane and access
+  auto put = [&](float* dst) {
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          *(float4*)(dst + (((i * NB + j) * 4 + q) * 64 + lane) * 4) =
+              make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+  };
+  auto add = [&](const float* src) {
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float4 v = *(const float4*)(src + (((i * NB + j) * 4 + q) * 64 + lane) * 4);
+          acc[i][j][4 * q] += v.x; acc[i][j][4 * q + 1] += v.y; acc[i][j][4 * q + 2] += v.z; acc[i][j][4 * q + 3] += v.w;
+        }
+  };
+  if (w >= 2) put(red[w - 2]);
+  __syncthreads();
+  if (w < 2) add(red[w]);
+  __syncthreads();
+  if (w == 1) put(red[0]);
+  __syncthreads();
+  if (w != 0) return;
+  add(red[0]);
+  put(partial + (long)blockIdx.x * (NBLK * 16 * 64));
+}
+
+// out[m, n] = sum_z partial[z] (accumulator order, see above), z ascending in 16 interleaved groups that are then
+// added in a fixed order; column block s of n_per columns goes to o<s> (NULL = dropped) when n_per > 0.
+__global__ __launch_bounds__(256) void wgrad_mfma_reduce_kernel(const float* __restrict__ partial, int nz, int M, int N,
+                                                                int NB, int nblk, float* o0, float* o1, float* o2,
+                                                                int n_per) {
+  __shared__ float red[16][16];
+  const int o = threadIdx.x & 15, g = threadIdx.x >> 4;
+  const long n_out = (long)M * N;
+  const long i = (long)blockIdx.x * 16 + o;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int m = 0, n = 0;
+  if (i < n_out) {
+    m = (int)(i / N); n = (int)(i - (long)m * N);
+    // accumulator register r of lane (c, h) in block (m / 32, n / 32): row 8 (r / 4) + 4 h + r % 4, column c
+    const int mi = m & 31, r = 4 * (mi >> 3) + (mi & 3), hh = (mi >> 2) & 1;
+    const long off = ((((long)(m >> 5) * NB + (n >> 5)) * 4 + (r >> 2)) * 64 + hh * 32 + (n & 31)) * 4 + (r & 3);
+    const long pz = (long)nblk * 16 * 64;
+    int z = g;
+    for (; z + 48 < nz; z += 64) {
+      s0 += partial[(long)z * pz + off];
+      s1 += partial[(long)(z + 16) * pz + off];
+      s2 += partial[(long)(z + 32) * pz + off];
+      s3 += partial[(long)(z + 48) * pz + off];
+    }
+    for (; z < nz; z += 16) s0 += partial[(long)z * pz + off];
+  }
+  red[g][o] = (s0 + s1) + (s2 + s3);
+  __syncthreads();
+  if (g == 0 && i < n_out) {
+    float v = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v += red[k][o];
+    if (n_per > 0) {
+      float* dst = (n / n_per == 0) ? o0 : (n / n_per == 1) ? o1 : o2;
+      if (dst) dst[(long)m * n_per + n % n_per] = v;
+    } else {
+      o0[i] = v;
+    }
+  }
+}
+
+static int wgrad_mfma_rows_per_wg(int R) {
+  // at most 1024 workgroups = partial results, and at least 128 rows each (measured at 29 600 rows, 40 x 120:
+  // 64 rows 22 us, 128 rows 17 us, 256 rows 25 us including the reduction); a multiple of 64: every wave then has
+  // a multiple of 16 rows = two groups of four steps per trip
+  const int rows = std::max((R + 1023) / 1024, 128);
+  return ((rows + 63) / 64) * 64;
+}
+bool wgrad_mfma_ok(int M, int N, int R, int in_bf16) { return !in_bf16 && M <= 64 && N <= 128 && R >= 1024; }
+size_t wgrad_mfma_partial_bytes(int M, int N, int R) {
+  const int rows = wgrad_mfma_rows_per_wg(R);
+  return (size_t)((R + rows - 1) / rows) * ((M + 31) / 32) * ((N + 31) / 32) * 16 * 64 * sizeof(float);
+}
+// C[M, N] = A[R, M]^T G[R, N] into o0 (n_per == 0) or column blocks of n_per columns into o0 | o1 | o2
+void launch_wgrad_mfma_f32(const float* A, long lda, const float* G, long ldg, int R, int M, int N, float* partial,
+                           float* o0, float* o1, float* o2, int n_per, hipStream_t st) {
+  const int rows = wgrad_mfma_rows_per_wg(R);
+  const int blocks = (R + rows - 1) / rows;
+  const int MB = (M + 31) / 32, NB = (N + 31) / 32;
+#define WM_LAUNCH(MBV, NBV) \
+  hipLaunchKernelGGL((wgrad_mfma_f32_kernel<MBV, NBV>), dim3(blocks), dim3(256), 0, st, A, lda, G, ldg, R, M, N, rows, partial)
+  if (MB == 1) {
+    if (NB == 1) WM_LAUNCH(1, 1); else if (NB == 2) WM_LAUNCH(1, 2); else if (NB == 3) WM_LAUNCH(1, 3); else WM_LAUNCH(1, 4);
+  } else {
+    if (NB == 1) WM_LAUNCH(2, 1); else if (NB == 2) WM_LAUNCH(2, 2); else if (NB == 3) WM_LAUNCH(2, 3); else WM_LAUNCH(2, 4);
+  }
+#undef WM_LAUNCH
+  const long n_out = (long)M * N;
+  hipLaunchKernelGGL(wgrad_mfma_reduce_kernel, dim3((unsigned)((n_out + 15) / 16)), dim3(256), 0, st, partial, blocks, M, N,
+                     NB, MB * NB, o0, o1, o2, n_per);
 }
 
 bool wgrad_small_ok(int M, int N, int n_per) {

@@ -39,6 +39,16 @@ def test_full_size_configs(cfg, name):
     say(f"    errors: " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
 
 
+@pytest.mark.parametrize("d,H", [(40, 8), (36, 6), (48, 4), (20, 4), (64, 8), (42, 7)])
+def test_tall_projections_ragged_rows(d, H):
+    """More than 1024 rows, not a multiple of 32: the fp32 projections of a tall input run on the matrix-instruction
+    GEMM (32-row blocks, widths padded to 32 columns, K padded to 8; d = 42 cannot store four columns at a time and
+    stays on the ALU GEMM)."""
+    say(f"[case] tall fp32 projections d={d} H={H}")
+    g = synth.attention_inputs(3, (37, 201, 150), d, H, "fp32", "valid_len", seed=311, bias=True)
+    Problem(g, oracle.IM_IFM_FORWARD).check(what=f"tall/d={d}")
+
+
 def test_c2_trailing_padding_through_valid_len():
     say("[case] c2 trailing-5 valid_len variant")
     w = synth.workload("c2", padding="none")
