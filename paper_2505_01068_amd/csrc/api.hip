@@ -194,7 +194,8 @@ static size_t bwd_workspace_bytes(const im_shape_t* s) {
   if (mfma_linear_ok(s->dtype == IM_DTYPE_BF16, d, d))
     pb = std::max(pb, std::max(mfma_wgrad_partial_bytes((int)d, (int)(3 * d), (int)R), mfma_wgrad_partial_bytes((int)d, (int)d, (int)R)));
   if (wgrad_small_ok((int)d, (int)(3 * d), (int)d)) pb = std::max(pb, wgrad_small_partial_bytes((int)d, (int)(3 * d), (int)R));
-  if (wgrad_mfma_ok((int)d, (int)(3 * d), (int)R, 0)) pb = std::max(pb, wgrad_mfma_partial_bytes((int)d, (int)(3 * d), (int)R));
+  if (wgrad_mfma_ok((int)d, (int)(3 * d), (int)R, 0))
+    pb = std::max(pb, wgrad_mfma_partial_bytes((int)d, (int)(3 * d), (int)R) + wgrad_mfma_partial_bytes((int)d, (int)d, (int)R));
   n += align256(pb);
   n += align256(4 * colsum_partial_bytes((int)R, (int)d));            // dbo, dbq, dbk, dbv in one launch
   n += align256(3 * d * d * sizeof(float));                           // sinks for unwanted weight gradients
@@ -302,7 +303,7 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
   if (ws_small) pbytes = std::max(pbytes, wgrad_small_partial_bytes((int)d, (int)(3 * d), (int)R));
   // ... and tall fp32 inputs on the fp32 matrix instruction
   const bool ws_mfma = !mm && wgrad_mfma_ok((int)d, (int)(3 * d), (int)R, bf);
-  if (ws_mfma) pbytes = std::max(pbytes, wgrad_mfma_partial_bytes((int)d, (int)(3 * d), (int)R));
+  if (ws_mfma) pbytes = std::max(pbytes, wgrad_mfma_partial_bytes((int)d, (int)(3 * d), (int)R) + wgrad_mfma_partial_bytes((int)d, (int)d, (int)R));
   float* partial = (float*)b.take(pbytes);
   float* cpart = (float*)b.take(4 * colsum_partial_bytes((int)R, (int)d));
   float* sink = (float*)b.take(3 * d * d * sizeof(float));
@@ -322,9 +323,12 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
     ProfScope ps(PF_WGRAD, st);
     mfma_wgrad(o, d, dy, d, (float*)dwo, nullptr, nullptr, 0, (int)d, (int)d, (int)R, partial, st);
   } else if (dwo && ws_mfma) {
-    ProfScope ps(PF_WGRAD, st);
-    launch_wgrad_mfma_f32((const float*)o, d, (const float*)dy, d, (int)R, (int)d, (int)d, partial, (float*)dwo, nullptr,
-                          nullptr, 0, st);
+    // with dWq | dWk | dWv below when those are wanted too (one pair of launches for both), else alone
+    if (!(dwq || dwk || dwv)) {
+      ProfScope ps(PF_WGRAD, st);
+      launch_wgrad_mfma_f32((const float*)o, d, (const float*)dy, d, (int)R, (int)d, (int)d, partial, (float*)dwo, nullptr,
+                            nullptr, 0, st);
+    }
   } else if (dwo && ws_small) {
     ProfScope ps(PF_WGRAD, st);
     const int nb = launch_wgrad_small(o, d, dy, d, (int)R, (int)d, (int)d, bf, partial, st);
@@ -349,8 +353,10 @@ static int bwd_rowlane(const im_shape_t* s, const void* x, const void* wq, const
     mfma_wgrad(x, d, dqkv, 3 * d, (float*)dwq, (float*)dwk, (float*)dwv, (int)d, (int)d, (int)(3 * d), (int)R, partial, st);
   } else if ((dwq || dwk || dwv) && ws_mfma) {
     ProfScope ps(PF_WGRAD, st);
-    launch_wgrad_mfma_f32((const float*)x, d, (const float*)dqkv, 3 * d, (int)R, (int)d, (int)(3 * d), partial, (float*)dwq,
-                          (float*)dwk, (float*)dwv, (int)d, st);
+    if (dwo) launch_wgrad_mfma_f32_attn((const float*)x, (const float*)dqkv, (const float*)o, (const float*)dy, (int)R, (int)d,
+                                        partial, (float*)dwq, (float*)dwk, (float*)dwv, (float*)dwo, st);
+    else launch_wgrad_mfma_f32((const float*)x, d, (const float*)dqkv, 3 * d, (int)R, (int)d, (int)(3 * d), partial,
+                               (float*)dwq, (float*)dwk, (float*)dwv, (int)d, st);
   } else if ((dwq || dwk || dwv) && ws_small) {
     ProfScope ps(PF_WGRAD, st);
     const int nb = launch_wgrad_small(x, d, dqkv, 3 * d, (int)R, (int)d, (int)(3 * d), bf, partial, st);

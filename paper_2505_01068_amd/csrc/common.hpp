@@ -215,6 +215,10 @@ bool wgrad_mfma_ok(int M, int N, int R, int in_bf16);
 size_t wgrad_mfma_partial_bytes(int M, int N, int R);
 void launch_wgrad_mfma_f32(const float* A, long lda, const float* G, long ldg, int R, int M, int N, float* partial,
                            float* o0, float* o1, float* o2, int n_per, hipStream_t st);
+// both weight gradients of an attention block (d <= 42: 3 d <= 128) in one pair of launches; NULL outputs are dropped;
+// partial: wgrad_mfma_partial_bytes(d, 3 d, R) + wgrad_mfma_partial_bytes(d, d, R) bytes
+void launch_wgrad_mfma_f32_attn(const float* X, const float* dQKV, const float* O, const float* dY, int R, int d,
+                                float* partial, float* q0, float* q1, float* q2, float* dwo, hipStream_t st);
 
 // encoder-layer backward pieces: a = GELU(z); g <- g * GELU'(z) in place; LayerNorm backward of rows
 // (dx = input gradient + res (res may be NULL), t = dy * xhat for the gamma gradient)

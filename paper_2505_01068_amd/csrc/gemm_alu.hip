@@ -555,12 +555,22 @@ void launch_wgrad_small_reduce(const float* partial, int nz, int M, int N, float
 // ([block][register quad][lane][4]: 16-byte stores, no index arithmetic); wgrad_mfma_reduce_kernel adds the
 // partials in a fixed order and undoes the layout.  Columns past M resp. N read the last valid column: they only
 // reach accumulator rows / columns that nobody reads.
+struct WgradProblem {
+  const float* A;
+  long lda;
+  const float* G;
+  long ldg;
+  int M, N;
+  float* partial;
+  float *o0, *o1, *o2;   // outputs of the reduction (see wgrad_mfma_reduce_kernel)
+  int n_per;
+};
 template <int MB, int NB>
-__global__ __launch_bounds__(256) void wgrad_mfma_f32_kernel(const float* __restrict__ A, long lda,
-                                                              const float* __restrict__ G, long ldg, int R, int M, int N,
-                                                              int rows_per_wg, float* __restrict__ partial) {
+__device__ __forceinline__ void wgrad_mfma_body(const float* __restrict__ A, long lda, const float* __restrict__ G, long ldg,
+                                                int R, int M, int N, int rows_per_wg, float* __restrict__ partial,
+                                                float* red_base) {
   constexpr int NBLK = MB * NB;
-  __shared__ __attribute__((aligned(16))) float red[2][NBLK * 16 * 64];
+  float(*red)[NBLK * 16 * 64] = (float(*)[NBLK * 16 * 64])red_base;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, c = lane & 31, h = lane >> 5;
   const int rpw = rows_per_wg >> 2;   // a multiple of 16
   const long row0 = (long)blockIdx.x * rows_per_wg + (long)w * rpw;
@@ -650,13 +660,27 @@ __global__ __launch_bounds__(256) void wgrad_mfma_f32_kernel(const float* __rest
   add(red[0]);
   put(partial + (long)blockIdx.x * (NBLK * 16 * 64));
 }
+template <int MB, int NB>
+__global__ __launch_bounds__(256) void wgrad_mfma_f32_kernel(WgradProblem p, int R, int rows_per_wg) {
+  __shared__ __attribute__((aligned(16))) float red[2 * MB * NB * 16 * 64];
+  wgrad_mfma_body<MB, NB>(p.A, p.lda, p.G, p.ldg, R, p.M, p.N, rows_per_wg, p.partial, red);
+}
+// two weight gradients over the same rows in one launch (blockIdx.y picks the problem)
+template <int MB0, int NB0, int MB1, int NB1>
+__global__ __launch_bounds__(256) void wgrad_mfma_f32_pair_kernel(WgradProblem p0, WgradProblem p1, int R, int rows_per_wg) {
+  constexpr int NBLK = MB0 * NB0 > MB1 * NB1 ? MB0 * NB0 : MB1 * NB1;
+  __shared__ __attribute__((aligned(16))) float red[2 * NBLK * 16 * 64];
+  if (blockIdx.y == 0) wgrad_mfma_body<MB0, NB0>(p0.A, p0.lda, p0.G, p0.ldg, R, p0.M, p0.N, rows_per_wg, p0.partial, red);
+  else wgrad_mfma_body<MB1, NB1>(p1.A, p1.lda, p1.G, p1.ldg, R, p1.M, p1.N, rows_per_wg, p1.partial, red);
+}
 
 // out[m, n] = sum_z partial[z] (accumulator order, see above), z ascending in 16 interleaved groups that are then
 // added in a fixed order; column block s of n_per columns goes to o<s> (NULL = dropped) when n_per > 0.
-__global__ __launch_bounds__(256) void wgrad_mfma_reduce_kernel(const float* __restrict__ partial, int nz, int M, int N,
-                                                                int NB, int nblk, float* o0, float* o1, float* o2,
-                                                                int n_per) {
+__global__ __launch_bounds__(256) void wgrad_mfma_reduce_kernel(WgradProblem p0, WgradProblem p1, int nz) {
   __shared__ float red[16][16];
+  const WgradProblem& p = blockIdx.y == 0 ? p0 : p1;
+  const float* __restrict__ partial = p.partial;
+  const int M = p.M, N = p.N, NB = (N + 31) / 32, nblk = ((M + 31) / 32) * NB, n_per = p.n_per;
   const int o = threadIdx.x & 15, g = threadIdx.x >> 4;
   const long n_out = (long)M * N;
   const long i = (long)blockIdx.x * 16 + o;
@@ -684,10 +708,10 @@ __global__ __launch_bounds__(256) void wgrad_mfma_reduce_kernel(const float* __r
 #pragma unroll
     for (int k = 0; k < 16; ++k) v += red[k][o];
     if (n_per > 0) {
-      float* dst = (n / n_per == 0) ? o0 : (n / n_per == 1) ? o1 : o2;
+      float* dst = (n / n_per == 0) ? p.o0 : (n / n_per == 1) ? p.o1 : p.o2;
       if (dst) dst[(long)m * n_per + n % n_per] = v;
     } else {
-      o0[i] = v;
+      p.o0[i] = v;
     }
   }
 }
@@ -710,8 +734,8 @@ void launch_wgrad_mfma_f32(const float* A, long lda, const float* G, long ldg, i
   const int rows = wgrad_mfma_rows_per_wg(R);
   const int blocks = (R + rows - 1) / rows;
   const int MB = (M + 31) / 32, NB = (N + 31) / 32;
-#define WM_LAUNCH(MBV, NBV) \
-  hipLaunchKernelGGL((wgrad_mfma_f32_kernel<MBV, NBV>), dim3(blocks), dim3(256), 0, st, A, lda, G, ldg, R, M, N, rows, partial)
+  const WgradProblem p{A, lda, G, ldg, M, N, partial, o0, o1, o2, n_per};
+#define WM_LAUNCH(MBV, NBV) hipLaunchKernelGGL((wgrad_mfma_f32_kernel<MBV, NBV>), dim3(blocks), dim3(256), 0, st, p, R, rows)
   if (MB == 1) {
     if (NB == 1) WM_LAUNCH(1, 1); else if (NB == 2) WM_LAUNCH(1, 2); else if (NB == 3) WM_LAUNCH(1, 3); else WM_LAUNCH(1, 4);
   } else {
@@ -719,8 +743,27 @@ void launch_wgrad_mfma_f32(const float* A, long lda, const float* G, long ldg, i
   }
 #undef WM_LAUNCH
   const long n_out = (long)M * N;
-  hipLaunchKernelGGL(wgrad_mfma_reduce_kernel, dim3((unsigned)((n_out + 15) / 16)), dim3(256), 0, st, partial, blocks, M, N,
-                     NB, MB * NB, o0, o1, o2, n_per);
+  hipLaunchKernelGGL(wgrad_mfma_reduce_kernel, dim3((unsigned)((n_out + 15) / 16), 1), dim3(256), 0, st, p, p, blocks);
+}
+// The two weight gradients of an attention block in one pair of launches:
+//   [dWq | dWk | dWv] = X^T [dQ | dK | dV]  (d x 3d, column blocks of d columns into q0 | q1 | q2, NULL = dropped)
+//   dWo               = O^T dY              (d x d)
+// partial: wgrad_mfma_partial_bytes(d, 3 d, R) + wgrad_mfma_partial_bytes(d, d, R) bytes.
+void launch_wgrad_mfma_f32_attn(const float* X, const float* dQKV, const float* O, const float* dY, int R, int d,
+                                float* partial, float* q0, float* q1, float* q2, float* dwo, hipStream_t st) {
+  const int rows = wgrad_mfma_rows_per_wg(R);
+  const int blocks = (R + rows - 1) / rows;
+  float* partial1 = partial + wgrad_mfma_partial_bytes(d, 3 * d, R) / sizeof(float);
+  const WgradProblem p0{X, d, dQKV, 3L * d, d, 3 * d, partial, q0, q1, q2, d};
+  const WgradProblem p1{O, d, dY, d, d, d, partial1, dwo, nullptr, nullptr, 0};
+  const int MB = (d + 31) / 32, NB0 = (3 * d + 31) / 32;
+  const dim3 grid(blocks, 2), block(256);
+  if (MB == 2) hipLaunchKernelGGL((wgrad_mfma_f32_pair_kernel<2, 4, 2, 2>), grid, block, 0, st, p0, p1, R, rows);
+  else if (NB0 == 3) hipLaunchKernelGGL((wgrad_mfma_f32_pair_kernel<1, 3, 1, 1>), grid, block, 0, st, p0, p1, R, rows);
+  else if (NB0 == 2) hipLaunchKernelGGL((wgrad_mfma_f32_pair_kernel<1, 2, 1, 1>), grid, block, 0, st, p0, p1, R, rows);
+  else hipLaunchKernelGGL((wgrad_mfma_f32_pair_kernel<1, 1, 1, 1>), grid, block, 0, st, p0, p1, R, rows);
+  const long n_out = (long)d * 3 * d;
+  hipLaunchKernelGGL(wgrad_mfma_reduce_kernel, dim3((unsigned)((n_out + 15) / 16), 2), dim3(256), 0, st, p0, p1, blocks);
 }
 
 bool wgrad_small_ok(int M, int N, int n_per) {
