@@ -182,7 +182,7 @@ __device__ __forceinline__ void ring_wait(int later) {
 // query block instead of 8 + 8, and the softmax stays on 32 x 32 accumulator tiles -- about a
 // quarter of the VALU instructions of the row-per-lane kernel at these head sizes.
 // PAIR: two problems of the same shape in one launch (two encoders side by side; see Geo::pair_B): grid z = 2 B.
-template <int QB, int DH, int NST, int WGS, int NW, bool PAIR>
+template <int QB, int DH, int NST, int WGS, int NW, bool PAIR, bool HEADW = false>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(WGS * NW / 4, WGS * NW / 4))) void mfma_fwd_kernel(Geo g, const bf16_t* __restrict__ QKV, long ld,
                                                        const int32_t* __restrict__ valid_len,
                                                        const uint8_t* __restrict__ key_pad, bf16_t* __restrict__ O,
@@ -192,9 +192,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(WGS * N
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: branches on it are wave-uniform
   int tile, h, b;
   xcd_tile_index(g.q_tile_prefix, g.q_nord, g.cu != nullptr, tile, h, b);
+  // HEADW (sub-head mode): the NW waves of a workgroup are NW heads of one 64-column group over the SAME 32 QB query
+  // rows (grid.y counts groups of NW heads) -- the K/V stream is shared as before, but a tile is 64 rows instead of
+  // 256, which at segment lengths like 50 / 500 / 375 leaves 4 % of the rows of the tiles empty instead of 28 %.
+  if (HEADW) h = h * NW + wave;
   const bool second = PAIR && b >= g.pair_B;
   const int bm = second ? b - g.pair_B : b;   // batch element of the masks (valid_len, key_pad)
-  constexpr int WG_ROWS = 32 * NW * QB;
+  constexpr int WG_ROWS = HEADW ? 32 * QB : 32 * NW * QB;
   int qs, q0;
   decode_tile(second ? g.q_order2 : g.q_order, second ? g.q_tile_prefix2 : g.q_tile_prefix, second ? g.q_nord2 : g.q_nord,
               WG_ROWS, tile, qs, q0);
@@ -215,7 +219,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(WGS * N
   int qrow[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
-    qrow[qb] = q0 + (wave * QB + qb) * 32 + lo;
+    qrow[qb] = q0 + ((HEADW ? 0 : wave * QB) + qb) * 32 + lo;
     const int rc = min(qrow[qb], qlen - 1);
     const bf16_t* p = QKV + (useg_row0(g, b, qs) + rc) * ld + cg * 64 + hi * 8;
 #pragma unroll
@@ -847,7 +851,9 @@ constexpr int FWD_QB = 1, FWD_QB_SUB = 2, DQ_QB = 1, DKV_KB = 1;
 constexpr int FWD_NST = 2, FWD_WGS = 4, FWD_NW = 4;   // ring stages, workgroups per CU, waves per workgroup (head dim 64)
 constexpr int FWD_SUB_NST = 3, FWD_SUB_WGS = 3;       // the same in sub-head mode (4 waves)
 constexpr int DQ_NST = 3, DQ_WGS = 3;                 // dQ at head dim 64
-int mfma_fwd_tile_rows(int dh) { return dh == 64 ? 32 * FWD_NW * FWD_QB : 128 * FWD_QB_SUB; }
+// sub-head mode with a multiple of 4 heads: four heads of a 64-column group per workgroup, 64-row tiles
+static bool fwd_headw(int dh, int H) { return dh != 64 && H % 4 == 0; }
+int mfma_fwd_tile_rows(int dh, int H) { return dh == 64 ? 32 * FWD_NW * FWD_QB : fwd_headw(dh, H) ? 32 * FWD_QB_SUB : 128 * FWD_QB_SUB; }
 int mfma_dq_tile_rows() { return 128 * DQ_QB; }
 int mfma_dkv_tile_rows() { return 128 * DKV_KB; }
 
@@ -862,8 +868,11 @@ void launch_mfma_fwd(const Geo& g, const bf16_t* qkv, long ld, const int32_t* va
   const int nt = g.q_tile_prefix[g.q_nord];
   if (nt == 0) return;
   ProfScope ps(PF_ATTN_FWD, st);
-  const dim3 grid(nt, g.H, g.B);
+  const dim3 grid(nt, g.H, g.B), gridw(nt, g.H / 4, g.B);
+  const bool hw = fwd_headw(g.dh, g.H);
   if (g.dh == 64) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB, 64, FWD_NST, FWD_WGS, FWD_NW, false>), grid, dim3(64 * FWD_NW), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  else if (g.dh == 16 && hw) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 16, FWD_SUB_NST, FWD_SUB_WGS, 4, false, true>), gridw, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  else if (hw) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 8, FWD_SUB_NST, FWD_SUB_WGS, 4, false, true>), gridw, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
   else if (g.dh == 16) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 16, FWD_SUB_NST, FWD_SUB_WGS, 4, false>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
   else hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 8, FWD_SUB_NST, FWD_SUB_WGS, 4, false>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
 }
@@ -885,8 +894,11 @@ void launch_mfma_fwd_pair(const Geo& g0, const Geo& g1, const bf16_t* qkv, long 
   for (int i = 0; i < IM_MAX_SEG; ++i) { g.q_live2[i] = g1.q_live[i]; g.q_order2[i] = g1.q_order[i]; }
   for (int i = 0; i <= IM_MAX_SEG; ++i) g.q_tile_prefix2[i] = g1.q_tile_prefix[i];
   ProfScope ps(PF_ATTN_FWD, st);
-  const dim3 grid(g.q_tile_prefix[g.q_nord], g.H, 2 * g.B);
-  if (g.dh == 16) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 16, FWD_SUB_NST, FWD_SUB_WGS, 4, true>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  const dim3 grid(g.q_tile_prefix[g.q_nord], g.H, 2 * g.B), gridw(g.q_tile_prefix[g.q_nord], g.H / 4, 2 * g.B);
+  const bool hw = fwd_headw(g.dh, g.H);
+  if (g.dh == 16 && hw) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 16, FWD_SUB_NST, FWD_SUB_WGS, 4, true, true>), gridw, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  else if (hw) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 8, FWD_SUB_NST, FWD_SUB_WGS, 4, true, true>), gridw, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
+  else if (g.dh == 16) hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 16, FWD_SUB_NST, FWD_SUB_WGS, 4, true>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
   else hipLaunchKernelGGL((mfma_fwd_kernel<FWD_QB_SUB, 8, FWD_SUB_NST, FWD_SUB_WGS, 4, true>), grid, dim3(256), 0, st, g, qkv, ld, valid_len, key_pad, o, ldo, lse2);
 }
 

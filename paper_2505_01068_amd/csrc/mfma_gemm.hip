@@ -713,11 +713,17 @@ __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
   ta.layernorm(p.ln_g, p.ln_b, p.ln_eps, tid);
   ta.store(sA, LDD, tid);
   const int nchunk = p.d_ff / 64;
-  auto fetch = [&](int j) {   // W1[:, 64 j .. 64 j + 63] (rows = k < D) and W2[64 j .. 64 j + 63, :] (rows = k < 64)
-    t1.load(p.w1 + j * 64, p.d_ff, 0, D - 1, tid);
-    t2.load(p.w2 + (long)j * 64 * D, D, 0, 63, tid);
+  // W1[:, 64 j .. 64 j + 63] (rows = k < D) and W2[64 j .. 64 j + 63, :] (rows = k < 64), requested TWO chunks ahead
+  // into two alternating register sets: with one chunk of arithmetic (16 matrix instructions per wave) between
+  // request and use, the trip to L2 was exposed in every chunk
+  ChunkTile<D, 64> t1b;
+  ChunkTile<64, D> t2b;
+  auto fetch = [&](int j, ChunkTile<D, 64>& a, ChunkTile<64, D>& b) {
+    a.load(p.w1 + j * 64, p.d_ff, 0, D - 1, tid);
+    b.load(p.w2 + (long)j * 64 * D, D, 0, 63, tid);
   };
-  fetch(0);
+  fetch(0, t1, t2);
+  if (nchunk > 1) fetch(1, t1b, t2b);
   // output accumulators: row `row`, block nb = columns wn * D/2 + 32 nb + ...; they start at b2
   f32x16 acc2[NB];
 #pragma unroll
@@ -726,12 +732,12 @@ __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc2[nb][4 * i + j] = p.b2 ? bf2f(p.b2[wn * (D / 2) + nb * 32 + 8 * i + 4 * hi + j]) : 0.f;
-  for (int c = 0; c < nchunk; ++c) {
+  auto chunk = [&](int c, ChunkTile<D, 64>& ra, ChunkTile<64, D>& rb) {
     __syncthreads();  // the previous chunk's W1, W2 and z tiles have been read (first pass: sA is complete)
-    t1.store(sW1, LDC, tid);
-    t2.store(sW2, LDD, tid);
+    ra.store(sW1, LDC, tid);
+    rb.store(sW2, LDD, tid);
     __syncthreads();
-    if (c + 1 < nchunk) fetch(c + 1);
+    if (c + 2 < nchunk) fetch(c + 2, ra, rb);
     f32x16 acc1;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -753,6 +759,10 @@ __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) acc2[nb] = mfma32(lds_frag_tr(sW2, LDD, s * 16, wn * (D / 2) + nb * 32, lane), fa, acc2[nb]);
     }
+  };
+  for (int c = 0; c < nchunk; c += 2) {
+    chunk(c, t1, t2);
+    if (c + 1 < nchunk) chunk(c + 1, t1b, t2b);
   }
   const int m = m0 + row;
   if (m >= p.R) return;

@@ -123,8 +123,8 @@ bool mfma_attention_fwd_pair(const im_shape_t* s0, uint64_t mask1, const void* x
   im_shape_t s1 = *s0;
   s1.live_mask = mask1;
   Geo g0, g1;
-  build_geo(s0, mfma_fwd_tile_rows(dh), mfma_dkv_tile_rows(), &g0);
-  build_geo(&s1, mfma_fwd_tile_rows(dh), mfma_dkv_tile_rows(), &g1);
+  build_geo(s0, mfma_fwd_tile_rows(dh, s0->n_heads), mfma_dkv_tile_rows(), &g0);
+  build_geo(&s1, mfma_fwd_tile_rows(dh, s1.n_heads), mfma_dkv_tile_rows(), &g1);
   if (!mfma_fwd_pair_ok(g0, g1) || !ln0.g || !ln1.g) return false;
   const Dims dm = dims(s0);
   const int d = (int)dm.d, R = (int)dm.R;
@@ -146,7 +146,7 @@ int mfma_attention_fwd(const im_shape_t* s, const void* x, const void* wq, const
                        const int32_t* valid_len, const uint8_t* key_pad, void* y, const void* res, char* sv,
                        size_t off_qkv, size_t off_o, size_t off_lse, size_t, char*, hipStream_t st, LnArgs ln) {
   Geo g;
-  build_geo(s, mfma_fwd_tile_rows(s->d_model / s->n_heads), mfma_dkv_tile_rows(), &g);
+  build_geo(s, mfma_fwd_tile_rows(s->d_model / s->n_heads, s->n_heads), mfma_dkv_tile_rows(), &g);
   const Dims dm = dims(s);
   const int d = (int)dm.d;
   bf16_t* qkv = (bf16_t*)(sv + off_qkv);

@@ -66,7 +66,7 @@ int mfma_gemm_split(int M, int N, int K);
 void launch_splitk_reduce(const float* partial, int split_k, int M, int N, float* o0, float* o1, float* o2, int n_per,
                           hipStream_t st);
 
-int mfma_fwd_tile_rows(int dh);
+int mfma_fwd_tile_rows(int dh, int n_heads);
 int mfma_dq_tile_rows();
 int mfma_dkv_tile_rows();
 void launch_mfma_fwd(const Geo& g, const bf16_t* qkv, long ld, const int32_t* valid_len, const uint8_t* key_pad,
