@@ -62,6 +62,19 @@ def test_layer_backward_fp32(name, padding):
     say("    " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
 
 
+@pytest.mark.parametrize("d,H,d_ff", [(40, 8, 100), (64, 8, 128)])
+def test_layer_tall_fp32(d, H, d_ff):
+    """More than 1024 rows in fp32: the layer's narrow GEMMs (output projection and second MLP layer with their
+    residuals, the input-gradient products with transposed weights; K = 100 is not a multiple of 8) run on the
+    fp32 matrix-instruction kernel."""
+    say(f"[case] layer fwd+bwd fp32, tall input, d={d} d_ff={d_ff}")
+    seg = (37, 201, 150)
+    g = synth.attention_inputs(3, seg, d, H, "fp32", "valid_len", seed=507)
+    p = synth.layer_params(d, d_ff, 507, 0, dtype="fp32")
+    errs = check(g, p, oracle.IM_IFM_FORWARD, "fp32", d_ff, f"layer-bwd/fp32/tall/d={d}")
+    say("    " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
+
+
 @pytest.mark.parametrize("bias", [True, False])
 def test_layer_backward_bf16_small_heads(bias):
     say(f"[case] layer bwd bf16 d=64 (sub-head matrix-core attention) bias={bias}")
