@@ -578,6 +578,190 @@ __global__ __launch_bounds__(NWV * 64) void mfma_gemm_dma_kernel(MGemm p) {
 }
 
 // ------------------------------------------------------------------------------------------
+// The same kernel for row-major A and k-major B with a 288 x 256 tile and twelve waves (3 x 4, each 96 x 64:
+// three waves per SIMD).  The tile height is chosen for the launch, not for the CU: 36 864 rows are 128 tiles of
+// 288, so N = 1536 gives 768 workgroups = exactly three rounds of the 256 CUs (256-row tiles: 864 = three rounds
+// and a fourth with 96), and N = 512 gives 256 = one round (256-row tiles: 288 = one round and a second with 32).
+// Per stage 288 x 4 + 32 x 32 = 2176 16-byte chunks for 768 threads: thread t copies A chunks t and t + 768 (< 1152)
+// and B chunks t and t + 768 (< 1024), i.e. waves 0-3 issue 4 copies per stage, waves 4-5 three, waves 6-11 two --
+// each wave waits for its own count.
+constexpr int TM = 288, TWAVES = 12;
+constexpr int T_A_BYTES = TM * DK * 2;                         // 18 KB
+constexpr int T_STAGE_BYTES = T_A_BYTES + DN * DK * 2;         // 34 KB
+constexpr int T_LDS_BYTES = DSTAGES * T_STAGE_BYTES;           // 136 KB
+constexpr int T_STG_BYTES = 10240;                             // epilogue staging per wave: 64 rows x 72 bf16 (9216) rounded up
+
+template <bool EPI>
+__global__ __launch_bounds__(TWAVES * 64) void mfma_gemm_dma12_kernel(MGemm p) {
+  extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
+  constexpr int NBN = 2, MBW = 3, WCOLS = 64, NT_THREADS = TWAVES * 64;
+  const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 2, wn = wave & 3;
+  int bx, by, bz;
+  xcd_block_index(bx, by, bz);
+  const int m0 = by * TM, n0 = bx * DN;
+  const int n_it = p.K / DK;   // K % 32 == 0 is required by the launcher; no split-K on this path
+
+  // ---- source pointers of this thread's chunks (advanced by DK per stage) ----
+  const bool a2 = tid + NT_THREADS < TM * 4, b2 = tid + NT_THREADS < DN * 4;   // wave-uniform
+  const bf16_t* ga[2];
+  const bf16_t* gb[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int slot = j * NT_THREADS + tid;
+    {
+      const int sa = min(slot, TM * 4 - 1);
+      const int r = sa >> 2, pos = sa & 3, kc = pos ^ ((r >> 2) & 3);
+      ga[j] = p.A + (long)min(m0 + r, p.M - 1) * p.lda + kc * 8;
+    }
+    {
+      const int sb = min(slot, DN * 4 - 1);
+      const int k = sb >> 5, pos = sb & 31, c = pos ^ ((k & 3) << 2);
+      const int col = min(n0 + c * 8, p.N - 8);
+      const bf16_t* mat = p.B[0];
+      int cc = col;
+      if (p.b_nper > 0) {
+        const int sel = col / p.b_nper;
+        mat = sel == 0 ? p.B[0] : sel == 1 ? p.B[1] : p.B[2];
+        cc = col - sel * p.b_nper;
+      }
+      gb[j] = mat + (long)k * p.ldb + cc;
+    }
+  }
+  const long b_step = (long)DK * p.ldb;
+  auto issue = [&](int it) {   // stage `it` into ring slot it % DSTAGES
+    char* base = (char*)smem + (it % DSTAGES) * T_STAGE_BYTES;
+    dma16(ga[0] + (long)it * DK, base + wave * 1024);
+    if (a2) dma16(ga[1] + (long)it * DK, base + (TWAVES + wave) * 1024);
+    dma16(gb[0] + (long)it * b_step, base + T_A_BYTES + wave * 1024);
+    if (b2) dma16(gb[1] + (long)it * b_step, base + T_A_BYTES + (TWAVES + wave) * 1024);
+  };
+
+  // [n block][m block]; registers 4i..4i+3 are columns n = 8i + 4hi + 0..3 of the block; they start at the bias
+  f32x16 acc[NBN][MBW];
+#pragma unroll
+  for (int nb = 0; nb < NBN; ++nb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      bias4(p, p.bias, n0 + wn * WCOLS + nb * 32 + 8 * i + 4 * hi, bv);
+#pragma unroll
+      for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) acc[nb][mb][4 * i + jj] = bv[jj];
+    }
+
+  // ---- LDS byte offsets of this lane's fragments inside a stage ----
+  int offA[2][MBW], offB[2][NBN], offB2[2][NBN];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+    for (int x = 0; x < MBW; ++x) {
+      const int row = wm * 96 + x * 32 + lo, kc = ks * 2 + hi;
+      offA[ks][x] = (row * 4 + (kc ^ ((row >> 2) & 3))) * 16;
+    }
+#pragma unroll
+    for (int x = 0; x < NBN; ++x) {
+      const int j = lane & 15, gq = lane >> 4;
+      const int kr = ks * 16 + 8 * (gq >> 1) + (j >> 2), col = wn * WCOLS + x * 32 + 16 * (gq & 1) + 4 * (j & 3);
+      offB[ks][x] = T_A_BYTES + (kr * 32 + ((col >> 3) ^ ((kr & 3) << 2))) * 16 + (col & 7) * 2;
+      offB2[ks][x] = T_A_BYTES + ((kr + 4) * 32 + ((col >> 3) ^ (((kr + 4) & 3) << 2))) * 16 + (col & 7) * 2;
+    }
+  }
+  auto frag_t = [&](const char* st, int o1, int o2) -> bf16x8 {
+    typedef v4i16 __attribute__((address_space(3))) * lds_v4_ptr;
+    union { v4i16 h[2]; bf16x8 v; } x;
+    x.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_ptr)(st + o1));
+    x.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_ptr)(st + o2));
+    return x.v;
+  };
+
+  // ---- pipeline: stages it+1 .. it+3 in flight while stage it is multiplied ----
+  const int ncopy = 2 + (a2 ? 1 : 0) + (b2 ? 1 : 0);   // this wave's copies per stage: 4, 3 or 2
+#pragma unroll
+  for (int s = 0; s < DSTAGES - 1; ++s)
+    if (s < n_it) issue(s);
+  for (int it = 0; it < n_it; ++it) {
+    // this wave's copies of stage `it` have landed when at most the copies of the later stages remain
+    const int later = min(DSTAGES - 2, n_it - 1 - it);
+    if (later == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if (ncopy == 4) { if (later >= 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); }
+    else if (ncopy == 3) { if (later >= 2) asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(3)" ::: "memory"); }
+    else { if (later >= 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); }
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (it + DSTAGES - 1 < n_it) issue(it + DSTAGES - 1);
+    const char* st = (const char*)smem + (it % DSTAGES) * T_STAGE_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      bf16x8 fa[MBW], fb[NBN];
+#pragma unroll
+      for (int x = 0; x < MBW; ++x) fa[x] = as_bf16x8(*(const u32x4*)(st + offA[ks][x]));
+#pragma unroll
+      for (int x = 0; x < NBN; ++x) fb[x] = frag_t(st, offB[ks][x], offB2[ks][x]);
+#pragma unroll
+      for (int nb = 0; nb < NBN; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < MBW; ++mb) acc[nb][mb] = mfma32(fb[nb], fa[mb], acc[nb][mb]);
+    }
+  }
+
+  // ---- epilogue: the wave's 96 x 64 tile through its own staging area, 32 rows at a time, 16-byte stores ----
+  __builtin_amdgcn_s_barrier();  // every wave has finished reading the last stage
+  asm volatile("" ::: "memory");
+  constexpr int EP_LD = WCOLS + 8;   // bf16 per staged row
+  static_assert(32 * EP_LD * 2 <= T_STG_BYTES && TWAVES * T_STG_BYTES <= T_LDS_BYTES, "staging areas must fit in the ring");
+  bf16_t* stg = smem + wave * (T_STG_BYTES / 2);
+  const bool interior = m0 + TM <= p.M && n0 + DN <= p.N;
+#pragma unroll
+  for (int mb = 0; mb < MBW; ++mb) {
+    const int m = m0 + wm * 96 + mb * 32 + lo;
+#pragma unroll
+    for (int nb = 0; nb < NBN; ++nb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int nl = nb * 32 + 8 * i + 4 * hi;
+        const int n = n0 + wn * WCOLS + nl;
+        float v[4];
+        const float cs = (p.scale0_on && n < p.n_per) ? p.scale0 : 1.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j] * cs;
+        if constexpr (EPI) {
+          if (p.gelu) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = gelu_erf_f(v[j]);
+          }
+          if (p.res && (interior || (m < p.M && n < p.N))) {
+            const u32x2 rv = *(const u32x2*)(p.res + (long)m * p.ldc + n);
+            v[0] += __uint_as_float(rv[0] << 16); v[1] += __uint_as_float(rv[0] & 0xffff0000u);
+            v[2] += __uint_as_float(rv[1] << 16); v[3] += __uint_as_float(rv[1] & 0xffff0000u);
+          }
+        }
+        const u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+        *(u32x2*)(stg + lo * EP_LD + nl) = pk;
+      }
+    // 32 rows x 8 chunks of 16 bytes; lane -> (row = 8 t + lane / 8, chunk = lane % 8).  The staging area is
+    // private to the wave and its LDS instructions complete in order: no barrier between the passes.
+    const int row0 = lane >> 3, ch = lane & 7;
+    const int mrow = m0 + wm * 96 + mb * 32 + row0, n = n0 + wn * WCOLS + ch * 8;
+    bf16_t* cp = p.C + (long)mrow * p.ldc + n;
+    const bf16_t* sp = stg + row0 * EP_LD + ch * 8;
+    u32x4 out[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) out[t] = *(const u32x4*)(sp + 8 * t * EP_LD);
+    if (interior) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) *(u32x4*)(cp + (long)(8 * t) * p.ldc) = out[t];
+    } else {
+#pragma unroll
+      for (int t = 0; t < 4; ++t)   // N is a multiple of 8 on this path
+        if (mrow + 8 * t < p.M && n < p.N) *(u32x4*)(cp + (long)(8 * t) * p.ldc) = out[t];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // Whole MLP sub-block of an encoder layer at model width D = 64 or 128 in one kernel:
 //   y = h + GELU(LN(h) W1 + b1) W2 + b2        (h [R, D], W1 [D, d_ff], W2 [d_ff, D], d_ff % 64 == 0)
 // and, with PROJ, also the attention's output projection and residual in front of it:
@@ -916,9 +1100,36 @@ static void launch_dma(const MGemm& p, hipStream_t st) {
   dim3 grid((p.N + DN - 1) / DN, (p.M + DM - 1) / DM, p.split_k);
   hipLaunchKernelGGL((mfma_gemm_dma_kernel<AKM, BKM, EPI, DMA_WAVES>), grid, dim3(DMA_WAVES * 64), DMA_LDS_BYTES, st, p);
 }
+// the 288-row variant when its workgroups need fewer (weighted) rounds of the CUs than the 256-row tiles
+static bool use_dma12(const MGemm& p) {
+  if (p.split_k > 1 || p.partial || p.M < TM || p.b_kper > 0) return false;
+  int dev = 0, cus = 256;
+  if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  const long nt = (p.N + DN - 1) / DN;
+  const long t256 = (long)((p.M + DM - 1) / DM) * nt, t288 = (long)((p.M + TM - 1) / TM) * nt;
+  const double r256 = (double)((t256 + cus - 1) / cus), r288 = (double)((t288 + cus - 1) / cus) * (double)TM / DM;
+  return r288 < r256;
+}
+template <bool EPI>
+static void launch_dma12(const MGemm& p, hipStream_t st) {
+  static bool configured = false;
+  if (!configured) {
+    (void)hipFuncSetAttribute((const void*)mfma_gemm_dma12_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, T_LDS_BYTES);
+    configured = true;
+  }
+  dim3 grid((p.N + DN - 1) / DN, (p.M + TM - 1) / TM, 1);
+  hipLaunchKernelGGL((mfma_gemm_dma12_kernel<EPI>), grid, dim3(TWAVES * 64), T_LDS_BYTES, st, p);
+}
 template <bool AKM, bool BKM>
 static void launch_layout(const MGemm& p, bool dma, hipStream_t st) {
   const bool epi = p.gelu || p.res != nullptr;
+  if constexpr (!AKM && BKM) {
+    if (dma && use_dma12(p)) {
+      if (epi) launch_dma12<true>(p, st);
+      else launch_dma12<false>(p, st);
+      return;
+    }
+  }
   if (dma) {
     if (epi) launch_dma<AKM, BKM, true>(p, st);
     else launch_dma<AKM, BKM, false>(p, st);
@@ -938,6 +1149,31 @@ static void launch_layout(const MGemm& p, bool dma, hipStream_t st) {
   dim3 grid((p.N + GN - 1) / GN, (p.M + GM - 1) / GM, p.split_k);
   if (epi) hipLaunchKernelGGL((mfma_gemm_kernel<AKM, BKM, true>), grid, dim3(256), 0, st, p);
   else hipLaunchKernelGGL((mfma_gemm_kernel<AKM, BKM, false>), grid, dim3(256), 0, st, p);
+}
+
+// Data gradients C = G W^T multiply by a weight stored [n][k] (an m-major B operand).  The large-tile kernels want
+// k-major B, and a weight is tiny beside the activations: when they apply, the caller transposes the weights once
+// per call (2 MB at d = 512) and the data gradients run on the same kernel as the forward projections.
+bool mfma_dgrad_wants_transposed_weights(int M, int N, int K) { return use_dma(M, N, K, false, true) && M >= TM; }
+// out[s][c][r] = w[s][r][c] for up to four square d x d matrices (d % 32 == 0); grid (d / 32, d / 32, count)
+__global__ __launch_bounds__(256) void transpose_square_kernel(const bf16_t* w0, const bf16_t* w1, const bf16_t* w2,
+                                                               const bf16_t* w3, int d, bf16_t* out) {
+  __shared__ bf16_t t[32][33];
+  const int z = blockIdx.z;
+  const bf16_t* w = z == 0 ? w0 : z == 1 ? w1 : z == 2 ? w2 : w3;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+  const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) t[ty + 8 * i][tx] = w[(long)(r0 + ty + 8 * i) * d + c0 + tx];
+  __syncthreads();
+  bf16_t* o = out + (long)z * d * d;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) o[(long)(c0 + ty + 8 * i) * d + r0 + tx] = t[tx][ty + 8 * i];
+}
+void launch_transpose_weights(const void* w0, const void* w1, const void* w2, const void* w3, int count, int d, void* out,
+                              hipStream_t st) {
+  hipLaunchKernelGGL(transpose_square_kernel, dim3(d / 32, d / 32, count), dim3(256), 0, st, (const bf16_t*)w0,
+                     (const bf16_t*)w1, (const bf16_t*)w2, (const bf16_t*)w3, d, (bf16_t*)out);
 }
 
 // Two GEMMs of identical shape and layout (row-major A, k-major B, 64-row tiles, no split-K) in one launch.

@@ -28,7 +28,7 @@ static Dims dims(const im_shape_t* s) {
 size_t mfma_saved_extra_bytes(const im_shape_t*) { return 0; }
 size_t mfma_fwd_workspace_bytes(int) { return 0; }
 
-struct BwdWs { size_t d_o, delta, dqkv, partial, cpart, total; int split_w, split_o; };
+struct BwdWs { size_t d_o, delta, dqkv, partial, cpart, wt, total; int split_w, split_o; bool tw; };
 static BwdWs bwd_ws(const im_shape_t* s) {
   const Dims x = dims(s);
   BwdWs w;
@@ -41,6 +41,9 @@ static BwdWs bwd_ws(const im_shape_t* s) {
   w.partial = off;
   off += al(std::max((size_t)w.split_w * x.d * 3 * x.d, (size_t)w.split_o * x.d * x.d) * 4);
   w.cpart = off; off += al(4 * colsum_partial_bytes((int)x.R, (int)x.d));   // dbo, dbq, dbk, dbv in one launch
+  // Wo^T and [Wq^T; Wk^T; Wv^T] for the data gradients, where the large-tile GEMM serves them
+  w.tw = x.d % 32 == 0 && mfma_dgrad_wants_transposed_weights((int)x.R, (int)x.d, (int)x.d);
+  w.wt = off; off += w.tw ? al(4 * x.d * x.d * 2) : 0;
   w.total = off;
   return w;
 }
@@ -198,12 +201,15 @@ int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const
   float* cpart = (float*)(ws + w.cpart);
 
   MGemm p;
+  bf16_t* wt = (bf16_t*)(ws + w.wt);   // [Wo^T; Wq^T; Wk^T; Wv^T], each d x d
   {
-    // dO = dy Wo^T : B(n = i, k = o) = Wo[i][o], an m-major operand as stored
+    // dO = dy Wo^T : B(n = i, k = o) = Wo[i][o], an m-major operand as stored (or k-major after the transpose)
     ProfScope ps(PF_PROJ_BWD, st);
+    if (w.tw) launch_transpose_weights(wo, wq, wk, wv, 4, d, wt, st);
     init_gemm(&p);
     p.A = (const bf16_t*)dy; p.lda = d;
     p.B[0] = (const bf16_t*)wo; p.ldb = d;
+    if (w.tw) { p.B[0] = wt; p.b_kmajor = 1; }
     p.M = R; p.N = d; p.K = d;
     p.C = d_o; p.ldc = d;
     launch_mfma_gemm(p, st);
@@ -247,6 +253,7 @@ int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const
     init_gemm(&p);
     p.A = dqkv; p.lda = 3 * d;
     p.B[0] = (const bf16_t*)wq; p.B[1] = (const bf16_t*)wk; p.B[2] = (const bf16_t*)wv; p.ldb = d; p.b_kper = d;
+    if (w.tw) { p.B[0] = wt + (size_t)d * d; p.B[1] = p.B[2] = nullptr; p.b_kper = 0; p.b_kmajor = 1; }   // [3d][d], k-major
     p.M = R; p.N = d; p.K = 3 * d;
     p.C = (bf16_t*)dx; p.ldc = d;
     launch_mfma_gemm(p, st);

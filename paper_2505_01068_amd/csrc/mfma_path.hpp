@@ -24,6 +24,10 @@ struct MGemm {
   long z_a, z_b[3], z_bias[3], z_ln_g, z_ln_b, z_res, z_c;
 };
 void launch_mfma_gemm(const MGemm& p, hipStream_t st);
+// data gradients with weights transposed once per call: see mfma_gemm.hip
+bool mfma_dgrad_wants_transposed_weights(int M, int N, int K);
+void launch_transpose_weights(const void* w0, const void* w1, const void* w2, const void* w3, int count, int d, void* out,
+                              hipStream_t st);
 // two GEMMs of identical shape (row-major A, k-major B, no split-K) in one launch, when mfma_gemm_pair_ok
 bool mfma_gemm_pair_ok(const MGemm& a, const MGemm& b);
 void launch_mfma_gemm_pair(const MGemm& a, const MGemm& b, hipStream_t st);
