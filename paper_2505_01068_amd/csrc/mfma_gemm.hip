@@ -1103,8 +1103,12 @@ static void launch_dma(const MGemm& p, hipStream_t st) {
 // the 288-row variant when its workgroups need fewer (weighted) rounds of the CUs than the 256-row tiles
 static bool use_dma12(const MGemm& p) {
   if (p.split_k > 1 || p.partial || p.M < TM || p.b_kper > 0) return false;
-  int dev = 0, cus = 256;
-  if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  static int cus = 0;   // compute units of the device (the first device that launches; one GPU per process)
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
+    else cus = 256;
+  }
   const long nt = (p.N + DN - 1) / DN;
   const long t256 = (long)((p.M + DM - 1) / DM) * nt, t288 = (long)((p.M + TM - 1) / TM) * nt;
   const double r256 = (double)((t256 + cus - 1) / cus), r288 = (double)((t288 + cus - 1) / cus) * (double)TM / DM;
