@@ -38,7 +38,7 @@ PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_BF16_TFLOPS = 2500.0
 PEAK_FP32_VALU_TFLOPS = 157.3        # published fp32 vector rate: counts packed (two-wide) fp32 instructions
 PEAK_FP32_VALU_UNPACKED_TFLOPS = 78.6  # 256 CU x 64 lanes x 2 flop x 2.4 GHz: the rate of code without packed fp32,
-                                       # which is what this build emits (packed fp32 selection is switched off)
+                                       # which is what the library is compiled to (packed fp32 selection is switched off)
 
 # Maximum sequence lengths of the datasets (App. "Datasets"), reordered to text / vision / audio the way the
 # benchmark configuration's 50 / 500 / 375 reads the first row.
@@ -226,7 +226,7 @@ def roofline_of(dom, fr, bf16_mfma, peaks, traffic, traffic_src, dom_launches, s
                 "avg_launch_ms": round(e["ms"] / max(dom_launches, 1.0), 4),
                 "note": "row-per-lane fp32 kernels: fused multiply-adds of the products counted, exp and softmax bookkeeping "
                         "not; peak = fp32 vector rate without packed instructions (256 CU x 64 lanes x 2 flop x 2.4 GHz), "
-                        "the published 157.3 TFLOP/s assumes packed fp32, which this build does not emit"}
+                        "the published 157.3 TFLOP/s assumes packed fp32, which the library is compiled without"}
     return roof
 
 
@@ -456,7 +456,7 @@ def main():
                     help="run one 1 GiB device copy first (reference reading for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        print("bench.py: the library runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

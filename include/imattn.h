@@ -59,7 +59,7 @@ extern "C" {
 
 #define IM_OK 0
 #define IM_ERR_INVALID (-1)     /* null required pointer, bad shape, live_mask bits out of range */
-#define IM_ERR_UNSUPPORTED (-2) /* dtype / head dimension / model dimension this build has no kernel for */
+#define IM_ERR_UNSUPPORTED (-2) /* dtype / head dimension / model dimension the library has no kernel for */
 #define IM_ERR_WORKSPACE (-3)   /* workspace_bytes smaller than im_attention_sizes / gsit_layer_sizes reports */
 #define IM_ERR_HIP (-4)         /* a HIP runtime call failed; text in im_last_error() */
 
