@@ -56,6 +56,17 @@ def test_mfma_projection_large_tile_ragged_rows():
     say("    " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
 
 
+def test_mfma_projection_288_row_tiles_ragged():
+    """409 samples x (24 + 32 + 32) rows = 35 992 token rows, d = 320 (5 heads): 256-row tiles would need three rounds
+    of the 256 CUs for the QKV projection (141 x 4 tiles), 288-row tiles two (125 x 4) -- the launcher takes the
+    twelve-wave 288 x 256 kernel, here with a ragged last row tile (35 992 = 124 x 288 + 280), ragged column tiles
+    (960 = 3 x 256 + 192, 320 = 256 + 64), biases, and, in the backward, the data gradients on transposed weights."""
+    say("[case] mfma d=320 R=35992 (288-row projection tiles, ragged rows and columns)")
+    g = synth.attention_inputs(409, (24, 32, 32), 320, 5, "bf16", "valid_len", seed=47, bias=True)
+    errs = Problem(g, oracle.IM_IFM_FORWARD).check(what="mfma d=320 R=35992")
+    say("    " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
+
+
 def test_mfma_dead_segments_and_fully_masked_rows():
     say("[case] mfma dead segments / fully masked rows")
     g = synth.attention_inputs(2, (9, 70, 33), 64, 1, "bf16", "none", seed=9, bias=True)
