@@ -902,12 +902,17 @@ __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
   // request and use, the trip to L2 was exposed in every chunk
   ChunkTile<D, 64> t1b;
   ChunkTile<64, D> t2b;
-  auto fetch = [&](int j, ChunkTile<D, 64>& a, ChunkTile<64, D>& b) {
+  // ... and with them the 16 bias values b1[64 j + 32 wn + 8 i + 4 hi + 0..3] the lane's z accumulator starts from
+  u32x2 bia[4], bib[4];
+  auto fetch = [&](int j, ChunkTile<D, 64>& a, ChunkTile<64, D>& b, u32x2 (&bi)[4]) {
     a.load(p.w1 + j * 64, p.d_ff, 0, D - 1, tid);
     b.load(p.w2 + (long)j * 64 * D, D, 0, 63, tid);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      bi[i] = p.b1 ? *(const u32x2*)(p.b1 + j * 64 + wn * 32 + 8 * i + 4 * hi) : u32x2{0u, 0u};
   };
-  fetch(0, t1, t2);
-  if (nchunk > 1) fetch(1, t1b, t2b);
+  fetch(0, t1, t2, bia);
+  if (nchunk > 1) fetch(1, t1b, t2b, bib);
   // output accumulators: row `row`, block nb = columns wn * D/2 + 32 nb + ...; they start at b2
   f32x16 acc2[NB];
 #pragma unroll
@@ -916,17 +921,18 @@ __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc2[nb][4 * i + j] = p.b2 ? bf2f(p.b2[wn * (D / 2) + nb * 32 + 8 * i + 4 * hi + j]) : 0.f;
-  auto chunk = [&](int c, ChunkTile<D, 64>& ra, ChunkTile<64, D>& rb) {
+  auto chunk = [&](int c, ChunkTile<D, 64>& ra, ChunkTile<64, D>& rb, u32x2 (&bi)[4]) {
     __syncthreads();  // the previous chunk's W1, W2 and z tiles have been read (first pass: sA is complete)
     ra.store(sW1, LDC, tid);
     rb.store(sW2, LDD, tid);
-    __syncthreads();
-    if (c + 2 < nchunk) fetch(c + 2, ra, rb);
     f32x16 acc1;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) acc1[4 * i + j] = p.b1 ? bf2f(p.b1[c * 64 + wn * 32 + 8 * i + 4 * hi + j]) : 0.f;
+    for (int i = 0; i < 4; ++i) {
+      acc1[4 * i] = __uint_as_float(bi[i][0] << 16); acc1[4 * i + 1] = __uint_as_float(bi[i][0] & 0xffff0000u);
+      acc1[4 * i + 2] = __uint_as_float(bi[i][1] << 16); acc1[4 * i + 3] = __uint_as_float(bi[i][1] & 0xffff0000u);
+    }
+    __syncthreads();
+    if (c + 2 < nchunk) fetch(c + 2, ra, rb, bi);
 #pragma unroll
     for (int s = 0; s < D / 16; ++s)
       acc1 = mfma32(lds_frag_tr(sW1, LDC, s * 16, wn * 32, lane), frag_rows(sA, LDD, row, s * 16 + hi * 8), acc1);
@@ -945,8 +951,8 @@ __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
     }
   };
   for (int c = 0; c < nchunk; c += 2) {
-    chunk(c, t1, t2);
-    if (c + 1 < nchunk) chunk(c + 1, t1b, t2b);
+    chunk(c, t1, t2, bia);
+    if (c + 1 < nchunk) chunk(c + 1, t1b, t2b, bib);
   }
   const int m = m0 + row;
   if (m >= p.R) return;
