@@ -863,13 +863,26 @@ __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[nb][4 * i + j] = p.bo ? bf2f(p.bo[wn * (D / 2) + nb * 32 + 8 * i + 4 * hi + j]) : 0.f;
-    for (int kc = 0; kc < D / 64; ++kc) {
-      ChunkTile<64, 64> to;
-      to.load(p.o + kc * 64, D, m0, p.R - 1, tid);
-      t2.load(p.wo + (long)kc * 64 * D, D, 0, 63, tid);
+    // every chunk of O and Wo (one or two) and the residual rows are requested at once, before the first is used
+    constexpr int NKC = D / 64;
+    ChunkTile<64, 64> to[NKC];
+    ChunkTile<64, D> tw[NKC];
+#pragma unroll
+    for (int kc = 0; kc < NKC; ++kc) {
+      to[kc].load(p.o + kc * 64, D, m0, p.R - 1, tid);
+      tw[kc].load(p.wo + (long)kc * 64 * D, D, 0, 63, tid);
+    }
+    const int mr = min(m0 + row, p.R - 1);
+    u32x2 resv[NB][4];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) resv[nb][i] = *(const u32x2*)(p.h + (long)mr * D + wn * (D / 2) + nb * 32 + 8 * i + 4 * hi);
+#pragma unroll
+    for (int kc = 0; kc < NKC; ++kc) {
       if (kc) __syncthreads();
-      to.store(sZ, LDC, tid);
-      t2.store(sW2, LDD, tid);
+      to[kc].store(sZ, LDC, tid);
+      tw[kc].store(sW2, LDD, tid);
       __syncthreads();
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
@@ -878,13 +891,12 @@ __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
         for (int nb = 0; nb < NB; ++nb) acc[nb] = mfma32(lds_frag_tr(sW2, LDD, s * 16, wn * (D / 2) + nb * 32, lane), fa, acc[nb]);
       }
     }
-    const int mr = min(m0 + row, p.R - 1);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int n = wn * (D / 2) + nb * 32 + 8 * i + 4 * hi;
-        const u32x2 rv = *(const u32x2*)(p.h + (long)mr * D + n);
+        const u32x2 rv = resv[nb][i];
         const u32x2 pk = {pack_bf16(acc[nb][4 * i] + __uint_as_float(rv[0] << 16), acc[nb][4 * i + 1] + __uint_as_float(rv[0] & 0xffff0000u)),
                           pack_bf16(acc[nb][4 * i + 2] + __uint_as_float(rv[1] << 16), acc[nb][4 * i + 3] + __uint_as_float(rv[1] & 0xffff0000u))};
         *(u32x2*)(sH + row * LDD + n) = pk;
@@ -968,13 +980,15 @@ __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
       *(u32x2*)(p.y + (long)m * D + n) = pk;
     }
 }
+// Registers: 168 at D = 64 (three workgroups per CU, as the LDS allows), 256 at D = 128 (two; left to itself the
+// compiler took 260 and halved the resident workgroups).
 template <int D, bool PROJ>
-__global__ __launch_bounds__(256) void mlp_tail_kernel(MlpTailArgs p) {
+__global__ __launch_bounds__(256, D == 64 ? 3 : 2) void mlp_tail_kernel(MlpTailArgs p) {
   mlp_tail_tile<D, PROJ>(p);
 }
 // the tails of two layers of the same shape (two encoders side by side) in one launch: grid y = 2
 template <int D, bool PROJ>
-__global__ __launch_bounds__(256) void mlp_tail_pair_kernel(MlpTailArgs p0, MlpTailArgs p1) {
+__global__ __launch_bounds__(256, D == 64 ? 3 : 2) void mlp_tail_pair_kernel(MlpTailArgs p0, MlpTailArgs p1) {
   mlp_tail_tile<D, PROJ>(blockIdx.y == 0 ? p0 : p1);
 }
 bool mlp_tail_ok(int is_bf16, long d, long d_ff, const void* h, const void* ln_g, const void* ln_b, const void* w1,
