@@ -599,10 +599,11 @@ int gsit_layer_fwd(const im_shape_t* shape, int32_t d_ff, const void* x, const v
   char* aw = (char*)b.take(aws);
 
   // At d = 64 a GEMM tile row is the whole feature row: both LayerNorms then run inside the GEMM that consumes
-  // them (the QKV projection, the first MLP GEMM) and u is never written.
+  // them (the QKV projection, the first MLP GEMM) and u is never written.  The QKV projection of a width-128
+  // model normalises its rows too.
   const bool mfma = pick_path(shape) == PATH_MFMA;
   auto al16 = [](const void* a, const void* b2) { return (((uintptr_t)a | (uintptr_t)b2) & 15) == 0; };
-  const bool ln1_fused = mfma && mfma_gemm_fuses_ln(bf, d, 3 * d) && al16(ln1_g, ln1_b);
+  const bool ln1_fused = mfma && mfma_qkv_fuses_ln(bf, d) && al16(ln1_g, ln1_b);
   const bool mlp_mfma = mfma_linear_ok(bf, d, d_ff) && mfma_linear_ok(bf, d_ff, d);
   const bool ln2_fused = mlp_mfma && mfma_gemm_fuses_ln(bf, d, d_ff) && al16(ln2_g, ln2_b);
   if (!ln1_fused && (rc = launch_layernorm(x, ln1_g, ln1_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
@@ -784,10 +785,10 @@ int gsit_layer_fwd_train(const im_shape_t* shape, int32_t d_ff, const void* x, c
   void* zpre = sv + L.zpre;
   void* a = sv + L.a;
 
-  // at d = 64 both LayerNorms run inside the GEMMs that consume them (see gsit_layer_fwd)
+  // the LayerNorms run inside the GEMMs that consume them where those can (see gsit_layer_fwd)
   auto al16 = [](const void* a0, const void* a1) { return (((uintptr_t)a0 | (uintptr_t)a1) & 15) == 0; };
   const bool mfma = pick_path(shape) == PATH_MFMA;
-  const bool ln1_fused = mfma && mfma_gemm_fuses_ln(bf, d, 3 * d) && al16(p->ln1_g, p->ln1_b);
+  const bool ln1_fused = mfma && mfma_qkv_fuses_ln(bf, d) && al16(p->ln1_g, p->ln1_b);
   const bool mlp_mfma = mfma_linear_ok(bf, d, d_ff) && mfma_linear_ok(bf, d_ff, d);
   const bool ln2_fused = mlp_mfma && mfma_gemm_fuses_ln(bf, d, d_ff) && al16(p->ln2_g, p->ln2_b);
   if (!ln1_fused && (rc = launch_layernorm(x, p->ln1_g, p->ln1_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;

@@ -308,6 +308,148 @@ __global__ __launch_bounds__(256, 3) void mfma_gemm_pair_kernel(MGemm p) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Q|K|V projection of narrow models (d = 64 or 128), optionally with the LayerNorm of the input rows inside.
+//
+// At these widths the whole problem is a few hundred rows per CU and the 128 x 128 tile kernel spends its time
+// in one load -> LDS -> multiply -> store chain per workgroup.  Here a WAVE owns 32 rows and one of Q, K, V:
+// it loads its rows straight into the operand layout of the matrix instruction (lane = row, 8 consecutive
+// features per 16-byte load), normalises them in registers (a row lies in two lanes: one exchange per
+// statistic), multiplies by the d x d weight the workgroup holds in LDS (k-major as stored, read with the
+// transpose read) and stores 16 bytes per lane.  The three workgroups that share 128 rows are neighbours in
+// launch order on one XCD, so the rows come from HBM once.  Up to two problems (two encoders) per launch.
+struct QkvRows {
+  const bf16_t* x[2]; const bf16_t* w[2][3]; const bf16_t* bias[2][3];
+  const bf16_t* ln_g[2]; const bf16_t* ln_b[2];
+  bf16_t* qkv[2];
+  int R, groups; float ln_eps, qscale;   // groups = ceil(R / 128)
+};
+template <int D>
+__global__ __launch_bounds__(256, 3) void qkv_rows_kernel(QkvRows p) {
+  constexpr int KS = D / 16, NBK = D / 32, LD = D + 32;   // row stride = 64 bytes mod 256: conflict-free transpose reads
+  __shared__ __attribute__((aligned(16))) bf16_t sW[D * LD];
+  __shared__ __attribute__((aligned(16))) float sG[D], sBt[D];
+  int part, rg, z;
+  {   // 1-D grid: (part, row group, problem), part fastest
+    int lin, u0, u1;
+    xcd_block_index(lin, u0, u1);
+    part = lin % 3;
+    const int t = lin / 3;
+    rg = t % p.groups; z = t / p.groups;
+  }
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
+  const bf16_t* const x = z ? p.x[1] : p.x[0];
+  const bf16_t* const w = z ? (part == 0 ? p.w[1][0] : part == 1 ? p.w[1][1] : p.w[1][2])
+                            : (part == 0 ? p.w[0][0] : part == 1 ? p.w[0][1] : p.w[0][2]);
+  const bf16_t* const bias = z ? (part == 0 ? p.bias[1][0] : part == 1 ? p.bias[1][1] : p.bias[1][2])
+                               : (part == 0 ? p.bias[0][0] : part == 1 ? p.bias[0][1] : p.bias[0][2]);
+  const bf16_t* const ln_g = z ? p.ln_g[1] : p.ln_g[0];
+  const bf16_t* const ln_b = z ? p.ln_b[1] : p.ln_b[0];
+  bf16_t* const out = z ? p.qkv[1] : p.qkv[0];
+
+  const int m = (rg * 4 + wave) * 32 + lo;
+  const long mc = min(m, p.R - 1);
+  u32x4 xr[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) xr[s] = *(const u32x4*)(x + mc * D + s * 16 + hi * 8);
+  // the weight as stored, 16 bytes per thread and request
+#pragma unroll
+  for (int i = 0; i < D * D / 8 / 256; ++i) {
+    const int idx = tid + i * 256, k = idx / (D / 8), c = (idx % (D / 8)) * 8;
+    *(u32x4*)(sW + k * LD + c) = *(const u32x4*)(w + (long)k * D + c);
+  }
+  if (ln_g && tid < D) {
+    sG[tid] = __uint_as_float((unsigned)ln_g[tid] << 16);
+    sBt[tid] = __uint_as_float((unsigned)ln_b[tid] << 16);
+  }
+  // accumulators start at the bias of their column: register 4i + j of block nb is column 32 nb + 8i + 4hi + j
+  f32x16 acc[NBK];
+#pragma unroll
+  for (int nb = 0; nb < NBK; ++nb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (bias) {
+        const bf16_t* q = bias + nb * 32 + 8 * i + 4 * hi;
+        if ((reinterpret_cast<uintptr_t>(bias) & 7) == 0) {
+          const u32x2 v = *(const u32x2*)q;
+          bv[0] = __uint_as_float(v[0] << 16); bv[1] = __uint_as_float(v[0] & 0xffff0000u);
+          bv[2] = __uint_as_float(v[1] << 16); bv[3] = __uint_as_float(v[1] & 0xffff0000u);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) bv[j] = __uint_as_float((unsigned)q[j] << 16);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[nb][4 * i + j] = bv[j];
+    }
+  __syncthreads();
+
+  bf16x8 xa[KS];
+  if (ln_g) {   // two-pass in fp32, rounded to bf16 as the stand-alone LayerNorm kernel does
+    float v[KS][8];
+    float sum = 0.f;
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        v[s][2 * j] = __uint_as_float(xr[s][j] << 16); v[s][2 * j + 1] = __uint_as_float(xr[s][j] & 0xffff0000u);
+        sum += v[s][2 * j] + v[s][2 * j + 1];
+      }
+    sum += __shfl_xor(sum, 32, 64);
+    const float mu = sum * (1.f / D);
+    float q = 0.f;
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { const float t = v[s][j] - mu; q = fmaf(t, t, q); }
+    q += __shfl_xor(q, 32, 64);
+    const float rstd = rsqrtf(q * (1.f / D) + p.ln_eps);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const float4 g0 = *(const float4*)(sG + s * 16 + hi * 8), g1 = *(const float4*)(sG + s * 16 + hi * 8 + 4);
+      const float4 b0 = *(const float4*)(sBt + s * 16 + hi * 8), b1 = *(const float4*)(sBt + s * 16 + hi * 8 + 4);
+      const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+      const float bb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+      float y[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) y[j] = (v[s][j] - mu) * rstd * gg[j] + bb[j];
+      xa[s] = pack8(y);
+    }
+  } else {
+#pragma unroll
+    for (int s = 0; s < KS; ++s) xa[s] = as_bf16x8(xr[s]);
+  }
+
+#pragma unroll
+  for (int s = 0; s < KS; ++s)
+#pragma unroll
+    for (int nb = 0; nb < NBK; ++nb) acc[nb] = mfma32(lds_frag_tr(sW, LD, s * 16, nb * 32, lane), xa[s], acc[nb]);
+
+  // Two neighbouring register quads hold columns 8i + 4hi + 0..3 and 8(i+1) + 4hi + 0..3; swapping the upper
+  // half-wave of the first with the lower half-wave of the second leaves every lane 8 consecutive columns.
+  const float cs = part == 0 ? p.qscale : 1.f;
+  bf16_t* const orow = out + (long)m * (3 * D) + part * D + 8 * hi;
+#pragma unroll
+  for (int nb = 0; nb < NBK; ++nb)
+#pragma unroll
+    for (int ip = 0; ip < 2; ++ip) {
+      unsigned a[2], b[2];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        a[h] = pack_bf16(acc[nb][8 * ip + 2 * h] * cs, acc[nb][8 * ip + 2 * h + 1] * cs);
+        b[h] = pack_bf16(acc[nb][8 * ip + 4 + 2 * h] * cs, acc[nb][8 * ip + 4 + 2 * h + 1] * cs);
+      }
+      u32x4 o;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const u32x2 sw = __builtin_amdgcn_permlane32_swap(a[h], b[h], false, false);
+        o[h] = sw[0]; o[2 + h] = sw[1];
+      }
+      if (m < p.R) *(u32x4*)(orow + nb * 32 + 16 * ip) = o;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Large-tile kernel with asynchronous global->LDS staging.
 //
 // The 128 x 128 kernel above is bound by bytes in flight, not by the matrix cores: one
@@ -1200,6 +1342,28 @@ void launch_transpose_weights(const void* w0, const void* w1, const void* w2, co
                      (const bf16_t*)w1, (const bf16_t*)w2, (const bf16_t*)w3, d, (bf16_t*)out);
 }
 
+// The Q|K|V projection shape qkv_rows_kernel serves: x [R][d] rows, three [d][d] weights, output rows [R][3d].
+static bool qkv_rows_shape(const MGemm& p) {
+  auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
+  return (p.K == 64 || p.K == 128) && p.N == 3 * p.K && !p.a_kmajor && p.b_kmajor && p.b_nper == p.K && p.b_kper == 0 &&
+         p.lda == p.K && p.ldb == p.K && p.ldc == p.N && p.n_per == p.K && p.split_k == 1 && !p.partial && !p.gelu &&
+         !p.res && p.M >= 1 && p.B[0] && p.B[1] && p.B[2] && al16(p.A) && al16(p.B[0]) && al16(p.B[1]) && al16(p.B[2]) &&
+         al16(p.C) && (!p.ln_g || (p.ln_b && al16(p.ln_g) && al16(p.ln_b)));
+}
+static void launch_qkv_rows(const MGemm& a, const MGemm* b, hipStream_t st) {
+  QkvRows q = {};
+  const MGemm* pr[2] = {&a, b};
+  for (int z = 0; z < (b ? 2 : 1); ++z) {
+    q.x[z] = pr[z]->A; q.qkv[z] = pr[z]->C; q.ln_g[z] = pr[z]->ln_g; q.ln_b[z] = pr[z]->ln_b;
+    for (int i = 0; i < 3; ++i) { q.w[z][i] = pr[z]->B[i]; q.bias[z][i] = pr[z]->bias[i]; }
+  }
+  q.R = a.M; q.ln_eps = a.ln_eps; q.qscale = a.scale0_on ? a.scale0 : 1.f;
+  q.groups = (a.M + 127) / 128;
+  const dim3 grid(3u * q.groups * (b ? 2 : 1));
+  if (a.K == 64) hipLaunchKernelGGL(qkv_rows_kernel<64>, grid, dim3(256), 0, st, q);
+  else hipLaunchKernelGGL(qkv_rows_kernel<128>, grid, dim3(256), 0, st, q);
+}
+
 // Two GEMMs of identical shape and layout (row-major A, k-major B, 64-row tiles, no split-K) in one launch.
 bool mfma_gemm_pair_ok(const MGemm& a, const MGemm& b) {
   return !a.a_kmajor && a.b_kmajor && !b.a_kmajor && b.b_kmajor && a.M == b.M && a.N == b.N && a.K == b.K &&
@@ -1212,6 +1376,7 @@ bool mfma_gemm_pair_ok(const MGemm& a, const MGemm& b) {
          a.split_k == 1 && b.split_k == 1 && !a.partial && !b.partial && a.M > 64;
 }
 void launch_mfma_gemm_pair(const MGemm& a, const MGemm& b, hipStream_t st) {
+  if (qkv_rows_shape(a) && qkv_rows_shape(b)) return launch_qkv_rows(a, &b, st);   // mfma_gemm_pair_ok: same shape, scale, eps
   MGemm p = a;
   auto off = [](const void* x, const void* y) { return (long)((const char*)y - (const char*)x); };
   p.z_a = off(a.A, b.A); p.z_c = off(a.C, b.C); p.z_res = off(a.res, b.res);
@@ -1232,6 +1397,7 @@ void launch_mfma_gemm_pair(const MGemm& a, const MGemm& b, hipStream_t st) {
 }
 
 void launch_mfma_gemm(const MGemm& p, hipStream_t st) {
+  if (qkv_rows_shape(p)) return launch_qkv_rows(p, nullptr, st);
   const bool dma = use_dma(p.M, p.N, p.K, p.a_kmajor, p.b_kmajor) && (p.b_kper == 0 || p.b_kper % DK == 0) && !p.ln_g;
   if (p.a_kmajor && p.b_kmajor) launch_layout<true, true>(p, dma, st);
   else if (p.b_kmajor) launch_layout<false, true>(p, dma, st);

@@ -16,7 +16,7 @@ struct MGemm {
   const bf16_t* bias[3]; int n_per;      // bias[n / n_per][n % n_per] (n_per = N for a single bias), or all NULL
   int scale0_on; float scale0;           // scale0_on: columns n < n_per leave as scale0 * (A B + bias)
   const bf16_t* ln_g; const bf16_t* ln_b; float ln_eps;  // ln_g != NULL: the rows of A are LayerNorm-ed as they are
-                                                         // staged (row-major A, K == 64 only: mfma_gemm_fuses_ln)
+                                                         // staged (row-major A; K == 64: mfma_gemm_fuses_ln, or the Q|K|V shape: mfma_qkv_fuses_ln)
   int gelu;
   const bf16_t* res;                     // residual rows, same ld as C
   bf16_t* C; long ldc;                   // row-major output
@@ -33,6 +33,9 @@ bool mfma_gemm_pair_ok(const MGemm& a, const MGemm& b);
 void launch_mfma_gemm_pair(const MGemm& a, const MGemm& b, hipStream_t st);
 // LayerNorm over the K axis of a row-major A can run inside the GEMM when a tile row is the whole feature row
 inline bool mfma_gemm_fuses_ln(int is_bf16, long K, long N) { return is_bf16 && K == 64 && N % 8 == 0 && N >= 8; }
+// ... and inside the Q|K|V projection of a width-64 or width-128 model (x, the three weights, the output and
+// the LayerNorm vectors 16-byte aligned)
+inline bool mfma_qkv_fuses_ln(int is_bf16, long d) { return is_bf16 && (d == 64 || d == 128); }
 // LayerNorm parameters for the rows of the left operand (all NULL / 0: none)
 struct LnArgs { const void* g; const void* b; float eps; };
 // bf16 linear layer C[M,N] = A[M,K] W + bias (+ GELU) (+ residual) with weights stored [K][N] (k-major),
