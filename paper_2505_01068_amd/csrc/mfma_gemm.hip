@@ -23,20 +23,19 @@ namespace imattn {
 constexpr int GM = 128, GN = 128, GK = 64;
 constexpr int KM_LD = 160;  // row stride (bf16) of a k-major LDS tile: 128 + 32 pad -> conflict-free transpose reads
 
-// GELU(x) = x Phi(x) with the error function from Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7, three
-// orders below the bf16 rounding of the result): one reciprocal, one exp2 and six multiply-adds instead of
-// the library erff's several dozen instructions -- the epilogue of the first MLP GEMM evaluates it for
-// every output element.
+// GELU(x) = x Phi(x) = max(x, 0) - |x| erfc(|x| / sqrt 2) / 2, with erfc(u) = 2^(-u p(u)) for a quartic p fitted on
+// [0, 6.5] (|error| of erfc <= 6e-7, of GELU <= 1.2e-6 in fp32 -- three orders below the bf16 rounding of the
+// result; the coefficients below are those of p with the 1 / sqrt 2 folded in).  Four multiply-adds for p, one
+// for the exponent, one exp2, a multiply, a maximum and a subtraction: the epilogue of the first MLP GEMM
+// evaluates this for every hidden element, and the library erff takes several dozen instructions.
 __device__ __forceinline__ float gelu_erf_f(float x) {
-  const float u = fabsf(x) * 0.70710678118654752440f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, u, 1.f));
-  float pl = fmaf(1.061405429f, t, -1.453152027f);
-  pl = fmaf(pl, t, 1.421413741f);
-  pl = fmaf(pl, t, -0.284496736f);
-  pl = fmaf(pl, t, 0.254829592f);
-  const float e = pl * t * __builtin_amdgcn_exp2f(-1.44269504088896340736f * u * u);  // 1 - erf(u), u >= 0
-  const float phi = x >= 0.f ? 1.f - 0.5f * e : 0.5f * e;                              // Phi(x)
-  return x * phi;
+  const float a = fabsf(x);
+  float p = fmaf(0.0005204590852372348f, a, -0.007397513370960951f);
+  p = fmaf(p, a, 0.05256124213337898f);
+  p = fmaf(p, a, 0.4592546820640564f);
+  p = fmaf(p, a, 1.1510913372039795f);
+  const float e = __builtin_amdgcn_exp2f(fmaf(-p, a, -1.f));   // erfc(|x| / sqrt 2) / 2
+  return fmaxf(x, 0.f) - e * a;
 }
 
 template <int U>
@@ -311,37 +310,38 @@ __global__ __launch_bounds__(256, 3) void mfma_gemm_pair_kernel(MGemm p) {
 // Q|K|V projection of narrow models (d = 64 or 128), optionally with the LayerNorm of the input rows inside.
 //
 // At these widths the whole problem is a few hundred rows per CU and the 128 x 128 tile kernel spends its time
-// in one load -> LDS -> multiply -> store chain per workgroup.  Here a WAVE owns 32 rows and one of Q, K, V:
-// it loads its rows straight into the operand layout of the matrix instruction (lane = row, 8 consecutive
-// features per 16-byte load), normalises them in registers (a row lies in two lanes: one exchange per
-// statistic), multiplies by the d x d weight the workgroup holds in LDS (k-major as stored, read with the
-// transpose read) and stores 16 bytes per lane.  The three workgroups that share 128 rows are neighbours in
-// launch order on one XCD, so the rows come from HBM once.  Up to two problems (two encoders) per launch.
+// in one load -> LDS -> multiply -> store chain per workgroup.  Here a WAVE owns 32 rows: it loads them straight
+// into the operand layout of the matrix instruction (lane = row, 8 consecutive features per 16-byte load),
+// normalises them in registers once (a row lies in two lanes: one exchange per statistic) and multiplies them by
+// Wq, Wk and Wv in turn.  The workgroup holds all three d x d weights in LDS, k-major as stored, read with the
+// transpose read; biases, pre-multiplied by the score scale for Q, sit there as fp32 and enter in the one
+// multiply-add per element of the epilogue.  Vector instructions per row are what bounds this kernel (the first
+// version gave every projection its own wave and normalised every row three times: 14 instead of 9 us per launch).
+// Up to two problems (two encoders) per launch.
 struct QkvRows {
   const bf16_t* x[2]; const bf16_t* w[2][3]; const bf16_t* bias[2][3];
   const bf16_t* ln_g[2]; const bf16_t* ln_b[2];
   bf16_t* qkv[2];
   int R, groups; float ln_eps, qscale;   // groups = ceil(R / 128)
 };
+template <int D> constexpr int qkv_rows_lds_bytes() { return 3 * D * (D + 32) * 2 + 5 * D * 4; }
 template <int D>
-__global__ __launch_bounds__(256, 3) void qkv_rows_kernel(QkvRows p) {
+__global__ __launch_bounds__(256) void qkv_rows_kernel(QkvRows p) {
   constexpr int KS = D / 16, NBK = D / 32, LD = D + 32;   // row stride = 64 bytes mod 256: conflict-free transpose reads
-  __shared__ __attribute__((aligned(16))) bf16_t sW[D * LD];
-  __shared__ __attribute__((aligned(16))) float sG[D], sBt[D];
-  int part, rg, z;
-  {   // 1-D grid: (part, row group, problem), part fastest
+  constexpr int WCH = D * D / 8 / 256;                    // 16-byte requests per thread and weight
+  extern __shared__ __attribute__((aligned(16))) unsigned char qkv_smem[];
+  bf16_t* const sW = (bf16_t*)qkv_smem;                   // [3][D][LD]
+  float* const sG = (float*)(qkv_smem + 3 * D * LD * 2);  // gamma, beta, then the three biases
+  float* const sBt = sG + D;
+  float* const sBias = sG + 2 * D;
+  int rg, z;
+  {
     int lin, u0, u1;
     xcd_block_index(lin, u0, u1);
-    part = lin % 3;
-    const int t = lin / 3;
-    rg = t % p.groups; z = t / p.groups;
+    rg = lin % p.groups; z = lin / p.groups;
   }
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const bf16_t* const x = z ? p.x[1] : p.x[0];
-  const bf16_t* const w = z ? (part == 0 ? p.w[1][0] : part == 1 ? p.w[1][1] : p.w[1][2])
-                            : (part == 0 ? p.w[0][0] : part == 1 ? p.w[0][1] : p.w[0][2]);
-  const bf16_t* const bias = z ? (part == 0 ? p.bias[1][0] : part == 1 ? p.bias[1][1] : p.bias[1][2])
-                               : (part == 0 ? p.bias[0][0] : part == 1 ? p.bias[0][1] : p.bias[0][2]);
   const bf16_t* const ln_g = z ? p.ln_g[1] : p.ln_g[0];
   const bf16_t* const ln_b = z ? p.ln_b[1] : p.ln_b[0];
   bf16_t* const out = z ? p.qkv[1] : p.qkv[0];
@@ -351,57 +351,57 @@ __global__ __launch_bounds__(256, 3) void qkv_rows_kernel(QkvRows p) {
   u32x4 xr[KS];
 #pragma unroll
   for (int s = 0; s < KS; ++s) xr[s] = *(const u32x4*)(x + mc * D + s * 16 + hi * 8);
-  // the weight as stored, 16 bytes per thread and request
+  {   // the weights as stored: every request of the three is in flight before the first is written to LDS
+    u32x4 wr[3][WCH];
 #pragma unroll
-  for (int i = 0; i < D * D / 8 / 256; ++i) {
-    const int idx = tid + i * 256, k = idx / (D / 8), c = (idx % (D / 8)) * 8;
-    *(u32x4*)(sW + k * LD + c) = *(const u32x4*)(w + (long)k * D + c);
-  }
-  if (ln_g && tid < D) {
-    sG[tid] = __uint_as_float((unsigned)ln_g[tid] << 16);
-    sBt[tid] = __uint_as_float((unsigned)ln_b[tid] << 16);
-  }
-  // accumulators start at the bias of their column: register 4i + j of block nb is column 32 nb + 8i + 4hi + j
-  f32x16 acc[NBK];
+    for (int part = 0; part < 3; ++part) {
+      const bf16_t* const w = z ? p.w[1][part] : p.w[0][part];
 #pragma unroll
-  for (int nb = 0; nb < NBK; ++nb)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float bv[4] = {0.f, 0.f, 0.f, 0.f};
-      if (bias) {
-        const bf16_t* q = bias + nb * 32 + 8 * i + 4 * hi;
-        if ((reinterpret_cast<uintptr_t>(bias) & 7) == 0) {
-          const u32x2 v = *(const u32x2*)q;
-          bv[0] = __uint_as_float(v[0] << 16); bv[1] = __uint_as_float(v[0] & 0xffff0000u);
-          bv[2] = __uint_as_float(v[1] << 16); bv[3] = __uint_as_float(v[1] & 0xffff0000u);
-        } else {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) bv[j] = __uint_as_float((unsigned)q[j] << 16);
-        }
+      for (int i = 0; i < WCH; ++i) {
+        const int idx = tid + i * 256, k = idx / (D / 8), c = (idx % (D / 8)) * 8;
+        wr[part][i] = *(const u32x4*)(w + (long)k * D + c);
       }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) acc[nb][4 * i + j] = bv[j];
     }
+#pragma unroll
+    for (int part = 0; part < 3; ++part)
+#pragma unroll
+      for (int i = 0; i < WCH; ++i) {
+        const int idx = tid + i * 256, k = idx / (D / 8), c = (idx % (D / 8)) * 8;
+        *(u32x4*)(sW + (part * D + k) * LD + c) = wr[part][i];
+      }
+  }
+  if (tid < D) {
+    if (ln_g) {
+      sG[tid] = __uint_as_float((unsigned)ln_g[tid] << 16);
+      sBt[tid] = __uint_as_float((unsigned)ln_b[tid] << 16);
+    }
+#pragma unroll
+    for (int part = 0; part < 3; ++part) {
+      const bf16_t* const bias = z ? p.bias[1][part] : p.bias[0][part];
+      const float bv = bias ? __uint_as_float((unsigned)bias[tid] << 16) : 0.f;
+      sBias[part * D + tid] = part == 0 ? bv * p.qscale : bv;
+    }
+  }
   __syncthreads();
 
   bf16x8 xa[KS];
   if (ln_g) {   // two-pass in fp32, rounded to bf16 as the stand-alone LayerNorm kernel does
-    float v[KS][8];
     float sum = 0.f;
 #pragma unroll
-    for (int s = 0; s < KS; ++s)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        v[s][2 * j] = __uint_as_float(xr[s][j] << 16); v[s][2 * j + 1] = __uint_as_float(xr[s][j] & 0xffff0000u);
-        sum += v[s][2 * j] + v[s][2 * j + 1];
-      }
+    for (int s = 0; s < KS; ++s) sum = sum_bf16x8(as_bf16x8(xr[s]), sum);
     sum += __shfl_xor(sum, 32, 64);
     const float mu = sum * (1.f / D);
+    float t[KS][8];
     float q = 0.f;
 #pragma unroll
     for (int s = 0; s < KS; ++s)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) { const float t = v[s][j] - mu; q = fmaf(t, t, q); }
+      for (int j = 0; j < 4; ++j) {
+        t[s][2 * j] = __uint_as_float(xr[s][j] << 16) - mu;
+        t[s][2 * j + 1] = __uint_as_float(xr[s][j] & 0xffff0000u) - mu;
+        q = fmaf(t[s][2 * j], t[s][2 * j], q);
+        q = fmaf(t[s][2 * j + 1], t[s][2 * j + 1], q);
+      }
     q += __shfl_xor(q, 32, 64);
     const float rstd = rsqrtf(q * (1.f / D) + p.ln_eps);
 #pragma unroll
@@ -412,7 +412,7 @@ __global__ __launch_bounds__(256, 3) void qkv_rows_kernel(QkvRows p) {
       const float bb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
       float y[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) y[j] = (v[s][j] - mu) * rstd * gg[j] + bb[j];
+      for (int j = 0; j < 8; ++j) y[j] = fmaf(t[s][j], rstd * gg[j], bb[j]);
       xa[s] = pack8(y);
     }
   } else {
@@ -420,33 +420,46 @@ __global__ __launch_bounds__(256, 3) void qkv_rows_kernel(QkvRows p) {
     for (int s = 0; s < KS; ++s) xa[s] = as_bf16x8(xr[s]);
   }
 
+  bf16_t* const orow = out + (long)m * (3 * D) + 8 * hi;
 #pragma unroll
-  for (int s = 0; s < KS; ++s)
+  for (int part = 0; part < 3; ++part) {
+    // register 4i + j of block nb is column 32 nb + 8i + 4hi + j
+    f32x16 acc[NBK];
 #pragma unroll
-    for (int nb = 0; nb < NBK; ++nb) acc[nb] = mfma32(lds_frag_tr(sW, LD, s * 16, nb * 32, lane), xa[s], acc[nb]);
+    for (int nb = 0; nb < NBK; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+#pragma unroll
+      for (int nb = 0; nb < NBK; ++nb)
+        acc[nb] = mfma32(lds_frag_tr(sW + part * D * LD, LD, s * 16, nb * 32, lane), xa[s], acc[nb]);
 
-  // Two neighbouring register quads hold columns 8i + 4hi + 0..3 and 8(i+1) + 4hi + 0..3; swapping the upper
-  // half-wave of the first with the lower half-wave of the second leaves every lane 8 consecutive columns.
-  const float cs = part == 0 ? p.qscale : 1.f;
-  bf16_t* const orow = out + (long)m * (3 * D) + part * D + 8 * hi;
+    // Two neighbouring register quads hold columns 8i + 4hi + 0..3 and 8(i+1) + 4hi + 0..3; swapping the upper
+    // half-wave of the first with the lower half-wave of the second leaves every lane 8 consecutive columns.
+    const float cs = part == 0 ? p.qscale : 1.f;
+    u32x4 o[NBK][2];
 #pragma unroll
-  for (int nb = 0; nb < NBK; ++nb)
+    for (int nb = 0; nb < NBK; ++nb)
 #pragma unroll
-    for (int ip = 0; ip < 2; ++ip) {
-      unsigned a[2], b[2];
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        a[h] = pack_bf16(acc[nb][8 * ip + 2 * h] * cs, acc[nb][8 * ip + 2 * h + 1] * cs);
-        b[h] = pack_bf16(acc[nb][8 * ip + 4 + 2 * h] * cs, acc[nb][8 * ip + 4 + 2 * h + 1] * cs);
+      for (int ip = 0; ip < 2; ++ip) {
+        const float4 ba = *(const float4*)(sBias + part * D + nb * 32 + 16 * ip + 4 * hi);
+        const float4 bb = *(const float4*)(sBias + part * D + nb * 32 + 16 * ip + 8 + 4 * hi);
+        const unsigned a0 = pack_bf16(fmaf(acc[nb][8 * ip], cs, ba.x), fmaf(acc[nb][8 * ip + 1], cs, ba.y));
+        const unsigned a1 = pack_bf16(fmaf(acc[nb][8 * ip + 2], cs, ba.z), fmaf(acc[nb][8 * ip + 3], cs, ba.w));
+        const unsigned b0 = pack_bf16(fmaf(acc[nb][8 * ip + 4], cs, bb.x), fmaf(acc[nb][8 * ip + 5], cs, bb.y));
+        const unsigned b1 = pack_bf16(fmaf(acc[nb][8 * ip + 6], cs, bb.z), fmaf(acc[nb][8 * ip + 7], cs, bb.w));
+        const u32x2 s0 = __builtin_amdgcn_permlane32_swap(a0, b0, false, false);
+        const u32x2 s1 = __builtin_amdgcn_permlane32_swap(a1, b1, false, false);
+        o[nb][ip][0] = s0[0]; o[nb][ip][1] = s1[0]; o[nb][ip][2] = s0[1]; o[nb][ip][3] = s1[1];
       }
-      u32x4 o;
+    if (m < p.R) {
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const u32x2 sw = __builtin_amdgcn_permlane32_swap(a[h], b[h], false, false);
-        o[h] = sw[0]; o[2 + h] = sw[1];
-      }
-      if (m < p.R) *(u32x4*)(orow + nb * 32 + 16 * ip) = o;
+      for (int nb = 0; nb < NBK; ++nb)
+#pragma unroll
+        for (int ip = 0; ip < 2; ++ip) *(u32x4*)(orow + part * D + nb * 32 + 16 * ip) = o[nb][ip];
     }
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1359,9 +1372,15 @@ static void launch_qkv_rows(const MGemm& a, const MGemm* b, hipStream_t st) {
   }
   q.R = a.M; q.ln_eps = a.ln_eps; q.qscale = a.scale0_on ? a.scale0 : 1.f;
   q.groups = (a.M + 127) / 128;
-  const dim3 grid(3u * q.groups * (b ? 2 : 1));
-  if (a.K == 64) hipLaunchKernelGGL(qkv_rows_kernel<64>, grid, dim3(256), 0, st, q);
-  else hipLaunchKernelGGL(qkv_rows_kernel<128>, grid, dim3(256), 0, st, q);
+  const dim3 grid((unsigned)q.groups * (b ? 2 : 1));
+  static bool configured = false;
+  if (!configured) {
+    (void)hipFuncSetAttribute((const void*)qkv_rows_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, qkv_rows_lds_bytes<64>());
+    (void)hipFuncSetAttribute((const void*)qkv_rows_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, qkv_rows_lds_bytes<128>());
+    configured = true;
+  }
+  if (a.K == 64) hipLaunchKernelGGL(qkv_rows_kernel<64>, grid, dim3(256), qkv_rows_lds_bytes<64>(), st, q);
+  else hipLaunchKernelGGL(qkv_rows_kernel<128>, grid, dim3(256), qkv_rows_lds_bytes<128>(), st, q);
 }
 
 // Two GEMMs of identical shape and layout (row-major A, k-major B, 64-row tiles, no split-K) in one launch.
