@@ -94,6 +94,21 @@ __device__ __forceinline__ bf16x8 lds_frag_tr(const bf16_t* lds, int ld, int k_b
   return x.v;
 }
 
+// The same fragment with the 32 columns in the order perm32 (lane lo receives column m_base + perm32(lo)): the
+// columns of each group of 16 lanes are exchanged in blocks of four, which the transpose read does when the
+// lanes' addresses point at the exchanged blocks.
+__device__ __forceinline__ bf16x8 lds_frag_tr_perm(const bf16_t* lds, int ld, int k_base, int m_base, int lane) {
+  const int j = lane & 15, g = lane >> 4, q = j & 3;
+  const bf16_t* p = lds + (k_base + 8 * (g >> 1) + (j >> 2)) * ld + m_base + 16 * (g & 1) + 4 * (((q & 1) << 1) | (q >> 1));
+  typedef v4i16 __attribute__((address_space(3))) * lds_v4_ptr;
+  const v4i16 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_ptr)(p));
+  const v4i16 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_ptr)(p + 4 * ld));
+  union { v4i16 h[2]; bf16x8 v; } x;
+  x.h[0] = a;
+  x.h[1] = b;
+  return x.v;
+}
+
 // ---- asynchronous global -> LDS copy ----
 // One instruction moves 16 (or 4) bytes per lane from the lane's global address to LDS address
 // (wave-uniform base) + 16 (or 4) * lane, with no staging register.  It counts in vmcnt like any

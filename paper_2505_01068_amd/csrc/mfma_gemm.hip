@@ -997,11 +997,17 @@ template <int D, bool PROJ>
 __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
   constexpr int LDD = D + 8, LDC = 64 + 8;   // row strides (bf16) of tiles with D resp. 64 columns
   constexpr int NB = D / 64;                 // 32-column output blocks per wave
-  __shared__ __attribute__((aligned(16))) bf16_t sA[64 * LDD];    // LN(h) rows
-  __shared__ __attribute__((aligned(16))) bf16_t sW1[D * LDC];    // W1 chunk: rows k < D, 64 hidden columns
-  __shared__ __attribute__((aligned(16))) bf16_t sW2[64 * LDD];   // W2 chunk: rows k < 64, D columns (PROJ: a Wo chunk)
-  __shared__ __attribute__((aligned(16))) bf16_t sZ[64 * LDC];    // z chunk rows (PROJ: a 64-column chunk of O)
-  __shared__ __attribute__((aligned(16))) bf16_t sH[PROJ ? 64 * LDD : 8];
+  // LDS: LN(h) rows | W1 chunk (rows k < D, 64 hidden columns) | W2 chunk (rows k < 64, D columns; PROJ: a Wo
+  // chunk) | PROJ only: a 64-column chunk of O, then the h rows.  The two weight tiles are also the buffer
+  // through which the waves exchange their partial outputs at the end.
+  constexpr int N_A = 64 * LDD, N_W1 = D * LDC, N_W2 = 64 * LDD, N_Z = PROJ ? 64 * LDC : 0, N_H = PROJ ? 64 * LDD : 0;
+  __shared__ __attribute__((aligned(16))) bf16_t smem[N_A + N_W1 + N_W2 + N_Z + N_H];
+  bf16_t* const sA = smem;
+  bf16_t* const sW1 = sA + N_A;
+  bf16_t* const sW2 = sW1 + N_W1;
+  bf16_t* const sZ = sW2 + N_W2;
+  bf16_t* const sH = sZ + N_Z;
+  static_assert((N_W1 + N_W2) * 2 >= 4 * NB * 16 * 64 * 4, "the exchange buffer must fit in the weight tiles");
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int wm = wave >> 1, wn = wave & 1;
   const int m0 = blockIdx.x * 64;
@@ -1069,57 +1075,106 @@ __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
   // request and use, the trip to L2 was exposed in every chunk
   ChunkTile<D, 64> t1b;
   ChunkTile<64, D> t2b;
-  // ... and with them the 16 bias values b1[64 j + 32 wn + 8 i + 4 hi + 0..3] the lane's z accumulator starts from
-  u32x2 bia[4], bib[4];
-  auto fetch = [&](int j, ChunkTile<D, 64>& a, ChunkTile<64, D>& b, u32x2 (&bi)[4]) {
+  // ... and with them the 16 bias values the lane's z accumulator starts from.  The z block of a wave is 32 rows x
+  // 32 hidden columns wn * 32 ..; W1's columns are fed in the order perm32, so register 8 u + e of the block
+  // is hidden column 16 u + 8 hi + e: two runs of 8 consecutive columns, the k-slots of the lane in the second product.
+  u32x4 bia[2], bib[2];
+  const bool b1_vec = (reinterpret_cast<uintptr_t>(p.b1) & 15) == 0;
+  auto fetch = [&](int j, ChunkTile<D, 64>& a, ChunkTile<64, D>& b, u32x4 (&bi)[2]) {
     a.load(p.w1 + j * 64, p.d_ff, 0, D - 1, tid);
     b.load(p.w2 + (long)j * 64 * D, D, 0, 63, tid);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      bi[i] = p.b1 ? *(const u32x2*)(p.b1 + j * 64 + wn * 32 + 8 * i + 4 * hi) : u32x2{0u, 0u};
+    for (int u = 0; u < 2; ++u) {
+      const bf16_t* q = p.b1 + j * 64 + wn * 32 + 16 * u + 8 * hi;
+      if (!p.b1) bi[u] = u32x4{0u, 0u, 0u, 0u};
+      else if (b1_vec) bi[u] = *(const u32x4*)q;
+      else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bi[u][e] = (unsigned)q[2 * e] | ((unsigned)q[2 * e + 1] << 16);
+      }
+    }
   };
   fetch(0, t1, t2, bia);
   if (nchunk > 1) fetch(1, t1b, t2b, bib);
-  // output accumulators: row `row`, block nb = columns wn * D/2 + 32 nb + ...; they start at b2
-  f32x16 acc2[NB];
+  // Output accumulators: row `row`, ALL D columns (block nb = columns 32 nb ..), contracted over the wave's own 32
+  // hidden columns of every chunk -- z then goes from the accumulator of the first product into the operand of
+  // the second without leaving registers, and the two waves of a row block add their halves once, at the end.
+  // The wave that writes a column block (blocks wn * NB ..) starts it at b2.
+  f32x16 acc2[2 * NB];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb)
+  for (int nb = 0; nb < 2 * NB; ++nb)
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc2[nb][4 * i + j] = p.b2 ? bf2f(p.b2[wn * (D / 2) + nb * 32 + 8 * i + 4 * hi + j]) : 0.f;
-  auto chunk = [&](int c, ChunkTile<D, 64>& ra, ChunkTile<64, D>& rb, u32x2 (&bi)[4]) {
-    __syncthreads();  // the previous chunk's W1, W2 and z tiles have been read (first pass: sA is complete)
+      for (int j = 0; j < 4; ++j)
+        acc2[nb][4 * i + j] = (p.b2 && (nb / NB) == wn) ? bf2f(p.b2[nb * 32 + 8 * i + 4 * hi + j]) : 0.f;
+  auto chunk = [&](int c, ChunkTile<D, 64>& ra, ChunkTile<64, D>& rb, u32x4 (&bi)[2]) {
+    __syncthreads();  // the previous chunk's W1 and W2 tiles have been read (first pass: sA is complete)
     ra.store(sW1, LDC, tid);
     rb.store(sW2, LDD, tid);
     f32x16 acc1;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      acc1[4 * i] = __uint_as_float(bi[i][0] << 16); acc1[4 * i + 1] = __uint_as_float(bi[i][0] & 0xffff0000u);
-      acc1[4 * i + 2] = __uint_as_float(bi[i][1] << 16); acc1[4 * i + 3] = __uint_as_float(bi[i][1] & 0xffff0000u);
-    }
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc1[8 * u + 2 * e] = __uint_as_float(bi[u][e] << 16);
+        acc1[8 * u + 2 * e + 1] = __uint_as_float(bi[u][e] & 0xffff0000u);
+      }
     __syncthreads();
     if (c + 2 < nchunk) fetch(c + 2, ra, rb, bi);
 #pragma unroll
     for (int s = 0; s < D / 16; ++s)
-      acc1 = mfma32(lds_frag_tr(sW1, LDC, s * 16, wn * 32, lane), frag_rows(sA, LDD, row, s * 16 + hi * 8), acc1);
+      acc1 = mfma32(lds_frag_tr_perm(sW1, LDC, s * 16, wn * 32, lane), frag_rows(sA, LDD, row, s * 16 + hi * 8), acc1);
+    bf16x8 zb[2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const u32x2 pk = {pack_bf16(gelu_erf_f(acc1[4 * i]), gelu_erf_f(acc1[4 * i + 1])),
-                        pack_bf16(gelu_erf_f(acc1[4 * i + 2]), gelu_erf_f(acc1[4 * i + 3]))};
-      *(u32x2*)(sZ + row * LDC + wn * 32 + 8 * i + 4 * hi) = pk;
+    for (int u = 0; u < 2; ++u) {
+      float zv[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) zv[e] = gelu_erf_f(acc1[8 * u + e]);
+      zb[u] = pack8(zv);
     }
-    __syncthreads();  // z chunk complete
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const bf16x8 fa = frag_rows(sZ, LDC, row, s * 16 + hi * 8);
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) acc2[nb] = mfma32(lds_frag_tr(sW2, LDD, s * 16, wn * (D / 2) + nb * 32, lane), fa, acc2[nb]);
-    }
+      for (int nb = 0; nb < 2 * NB; ++nb)
+        acc2[nb] = mfma32(lds_frag_tr(sW2, LDD, wn * 32 + u * 16, nb * 32, lane), zb[u], acc2[nb]);
   };
   for (int c = 0; c < nchunk; c += 2) {
     chunk(c, t1, t2, bia);
     if (c + 1 < nchunk) chunk(c + 1, t1b, t2b, bib);
+  }
+  // each wave hands the NB column blocks it does not write to its neighbour (wave ^ 1: same rows, other wn);
+  // wn is wave-uniform and every accumulator index below a compile-time constant
+  float* const xch = (float*)sW1;
+  __syncthreads();  // the last chunk's tiles have been read
+  auto put = [&](const f32x16& a, int nbi) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      *(float4*)(xch + (((wave * NB + nbi) * 4 + i) * 64 + lane) * 4) = make_float4(a[4 * i], a[4 * i + 1], a[4 * i + 2], a[4 * i + 3]);
+  };
+  auto get = [&](const f32x16& mine, int nbi) {
+    f32x16 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float4 v = *(const float4*)(xch + ((((wave ^ 1) * NB + nbi) * 4 + i) * 64 + lane) * 4);
+      r[4 * i] = mine[4 * i] + v.x; r[4 * i + 1] = mine[4 * i + 1] + v.y;
+      r[4 * i + 2] = mine[4 * i + 2] + v.z; r[4 * i + 3] = mine[4 * i + 3] + v.w;
+    }
+    return r;
+  };
+  f32x16 accf[NB];
+  if (wn == 0) {
+#pragma unroll
+    for (int nbi = 0; nbi < NB; ++nbi) put(acc2[NB + nbi], nbi);
+    __syncthreads();
+#pragma unroll
+    for (int nbi = 0; nbi < NB; ++nbi) accf[nbi] = get(acc2[nbi], nbi);
+  } else {
+#pragma unroll
+    for (int nbi = 0; nbi < NB; ++nbi) put(acc2[nbi], nbi);
+    __syncthreads();
+#pragma unroll
+    for (int nbi = 0; nbi < NB; ++nbi) accf[nbi] = get(acc2[NB + nbi], nbi);
   }
   const int m = m0 + row;
   if (m >= p.R) return;
@@ -1130,8 +1185,8 @@ __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
       const int n = wn * (D / 2) + nb * 32 + 8 * i + 4 * hi;
       // residual: the rows before the LayerNorm
       const u32x2 rv = PROJ ? *(const u32x2*)(sH + row * LDD + n) : *(const u32x2*)(p.h + (long)m * D + n);
-      const u32x2 pk = {pack_bf16(acc2[nb][4 * i] + __uint_as_float(rv[0] << 16), acc2[nb][4 * i + 1] + __uint_as_float(rv[0] & 0xffff0000u)),
-                        pack_bf16(acc2[nb][4 * i + 2] + __uint_as_float(rv[1] << 16), acc2[nb][4 * i + 3] + __uint_as_float(rv[1] & 0xffff0000u))};
+      const u32x2 pk = {pack_bf16(accf[nb][4 * i] + __uint_as_float(rv[0] << 16), accf[nb][4 * i + 1] + __uint_as_float(rv[0] & 0xffff0000u)),
+                        pack_bf16(accf[nb][4 * i + 2] + __uint_as_float(rv[1] << 16), accf[nb][4 * i + 3] + __uint_as_float(rv[1] & 0xffff0000u))};
       *(u32x2*)(p.y + (long)m * D + n) = pk;
     }
 }
