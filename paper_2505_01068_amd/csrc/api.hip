@@ -804,9 +804,12 @@ int gsit_layer_fwd_train(const im_shape_t* shape, int32_t d_ff, const void* x, c
   if (rc) return rc;
   if (!ln2_fused && (rc = launch_layernorm(h, p->ln2_g, p->ln2_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
   if (mlp_mfma) {
-    mfma_linear(ln2_fused ? h : u, d, p->w1, nullptr, nullptr, d_ff, d_ff, p->b1, nullptr, nullptr, 0, nullptr, zpre, d_ff,
-                (int)R, d_ff, (int)d, st, ln2_fused ? LnArgs{p->ln2_g, p->ln2_b, ln_eps} : LnArgs{nullptr, nullptr, 0.f});
-    if ((rc = launch_gelu_fwd(zpre, a, R * (long)d_ff, bf, st))) return rc;
+    // at the small shapes the first GEMM writes the pre-activation and its GELU in one epilogue
+    const bool both = mfma_gemm_small_tile((int)R, d_ff, (int)d, true);
+    mfma_linear(ln2_fused ? h : u, d, p->w1, nullptr, nullptr, d_ff, d_ff, p->b1, nullptr, nullptr, both ? MGEMM_GELU_BOTH : 0,
+                nullptr, zpre, d_ff, (int)R, d_ff, (int)d, st,
+                ln2_fused ? LnArgs{p->ln2_g, p->ln2_b, ln_eps} : LnArgs{nullptr, nullptr, 0.f}, both ? a : nullptr);
+    if (!both && (rc = launch_gelu_fwd(zpre, a, R * (long)d_ff, bf, st))) return rc;
     mfma_linear(a, d_ff, p->w2, nullptr, nullptr, d, (int)d, p->b2, nullptr, nullptr, 0, h, y, d, (int)R, (int)d, d_ff, st);
     return check_hip("gsit_layer_fwd_train launch");
   }
@@ -867,15 +870,16 @@ int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const g
   }
   // (db2 = column sums of dy: taken further down, together with the second LayerNorm's parameter gradients)
   // dz = (dy W2^T) * GELU'(z)
+  const bool dz_fused = mm && mfma_gemm_small_tile((int)R, d_ff, (int)d, false);   // GELU' in the GEMM's epilogue
   if (mm) {
-    mfma_dgrad(dy, d, p->w2, nullptr, nullptr, d, 0, dz, d_ff, (int)R, d_ff, (int)d, st);
+    mfma_dgrad(dy, d, p->w2, nullptr, nullptr, d, 0, dz, d_ff, (int)R, d_ff, (int)d, st, dz_fused ? zpre : nullptr);
   } else {
     memset(&g, 0, sizeof(g));
     g.A = dy; g.sam = d; g.sak = 1; g.B[0] = p->w2; g.sbk = 1; g.sbn = d;
     g.C[0] = dz; g.ldc = d_ff; g.M = (int)R; g.N = d_ff; g.K = (int)d;
     if ((rc = launch_gemm_alu(g, bf, bf, bf, st))) return rc;
   }
-  if ((rc = launch_gelu_bwd(zpre, dz, R * (long)d_ff, bf, st))) return rc;
+  if (!dz_fused && (rc = launch_gelu_bwd(zpre, dz, R * (long)d_ff, bf, st))) return rc;
   // z = v W1 + b1 with v = LN(h; ln2)
   if ((rc = launch_layernorm(h, p->ln2_g, p->ln2_b, v, (int)R, (int)d, ln_eps, bf, st))) return rc;
   if (gr->w1 && mm) {

@@ -38,6 +38,19 @@ __device__ __forceinline__ float gelu_erf_f(float x) {
   return fmaxf(x, 0.f) - e * a;
 }
 
+// d/dx [x Phi(x)] = Phi(x) + x phi(x), Phi from the same erfc form, phi(x) = exp(-x^2 / 2) / sqrt(2 pi)
+__device__ __forceinline__ float gelu_grad_f(float x) {
+  const float a = fabsf(x);
+  float p = fmaf(0.0005204590852372348f, a, -0.007397513370960951f);
+  p = fmaf(p, a, 0.05256124213337898f);
+  p = fmaf(p, a, 0.4592546820640564f);
+  p = fmaf(p, a, 1.1510913372039795f);
+  const float e = __builtin_amdgcn_exp2f(fmaf(-p, a, -1.f));   // erfc(|x| / sqrt 2) / 2
+  const float Phi = x >= 0.f ? 1.f - e : e;
+  const float pdf = 0.39894228040143267794f * __builtin_amdgcn_exp2f(-0.72134752044448170368f * x * x);
+  return fmaf(x, pdf, Phi);
+}
+
 template <int U>
 struct TileRegs {
   u32x4 v[U];
@@ -275,14 +288,30 @@ __device__ __forceinline__ void mfma_gemm_tile(const MGemm& p, int bx, int by, i
 #pragma unroll
         for (int j = 0; j < 4; ++j) v[j] = acc[nb][mb][4 * i + j] * cs;
         if constexpr (EPI) {
-          if (p.gelu) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = gelu_erf_f(v[j]);
+          if (p.gelu == MGEMM_GELU_BOTH) {
+            // the pre-activation goes to C as it is; C2 gets GELU of the ROUNDED pre-activation, the value a
+            // backward pass will read back
+            const u32x2 pre = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+            *(u32x2*)(pC + (long)m * p.ldc + n) = pre;
+            const u32x2 act = {pack_bf16(gelu_erf_f(__uint_as_float(pre[0] << 16)), gelu_erf_f(__uint_as_float(pre[0] & 0xffff0000u))),
+                               pack_bf16(gelu_erf_f(__uint_as_float(pre[1] << 16)), gelu_erf_f(__uint_as_float(pre[1] & 0xffff0000u)))};
+            *(u32x2*)(p.C2 + (long)m * p.ldc + n) = act;
+            continue;
           }
-          if (pres) {
+          if (p.gelu == MGEMM_GELU_GRAD) {   // C = (A B) * GELU'(res)
             const u32x2 rv = *(const u32x2*)(pres + (long)m * p.ldc + n);
-            v[0] += __uint_as_float(rv[0] << 16); v[1] += __uint_as_float(rv[0] & 0xffff0000u);
-            v[2] += __uint_as_float(rv[1] << 16); v[3] += __uint_as_float(rv[1] & 0xffff0000u);
+            v[0] *= gelu_grad_f(__uint_as_float(rv[0] << 16)); v[1] *= gelu_grad_f(__uint_as_float(rv[0] & 0xffff0000u));
+            v[2] *= gelu_grad_f(__uint_as_float(rv[1] << 16)); v[3] *= gelu_grad_f(__uint_as_float(rv[1] & 0xffff0000u));
+          } else {
+            if (p.gelu) {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) v[j] = gelu_erf_f(v[j]);
+            }
+            if (pres) {
+              const u32x2 rv = *(const u32x2*)(pres + (long)m * p.ldc + n);
+              v[0] += __uint_as_float(rv[0] << 16); v[1] += __uint_as_float(rv[0] & 0xffff0000u);
+              v[2] += __uint_as_float(rv[1] << 16); v[3] += __uint_as_float(rv[1] & 0xffff0000u);
+            }
           }
         }
         const u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
@@ -1300,6 +1329,10 @@ static bool use_dma(int M, int N, int K, bool akm = true, bool bkm = true) {
   return akm ? K >= 64 * DK : K >= 8 * DK;
 }
 
+// true if a row-major-A, k-major-B (forward linear) or all-row-major (data gradient) GEMM of this shape runs on the
+// 128 x 128 kernel, whose epilogue knows MGEMM_GELU_BOTH and MGEMM_GELU_GRAD
+bool mfma_gemm_small_tile(int M, int N, int K, bool b_kmajor) { return !use_dma(M, N, K, false, b_kmajor); }
+
 int mfma_gemm_split(int M, int N, int K) {
   if (use_dma(M, N, K)) {
     const long tiles = (long)((M + DM - 1) / DM) * ((N + DN - 1) / DN);
@@ -1447,7 +1480,7 @@ bool mfma_gemm_pair_ok(const MGemm& a, const MGemm& b) {
          (a.B[1] != nullptr) == (b.B[1] != nullptr) && (a.B[2] != nullptr) == (b.B[2] != nullptr) &&
          (a.bias[0] != nullptr) == (b.bias[0] != nullptr) && (a.bias[1] != nullptr) == (b.bias[1] != nullptr) &&
          (a.bias[2] != nullptr) == (b.bias[2] != nullptr) &&
-         a.split_k == 1 && b.split_k == 1 && !a.partial && !b.partial && a.M > 64;
+         a.split_k == 1 && b.split_k == 1 && !a.partial && !b.partial && a.M > 64 && a.gelu <= 1;
 }
 void launch_mfma_gemm_pair(const MGemm& a, const MGemm& b, hipStream_t st) {
   if (qkv_rows_shape(a) && qkv_rows_shape(b)) return launch_qkv_rows(a, &b, st);   // mfma_gemm_pair_ok: same shape, scale, eps
@@ -1472,7 +1505,8 @@ void launch_mfma_gemm_pair(const MGemm& a, const MGemm& b, hipStream_t st) {
 
 void launch_mfma_gemm(const MGemm& p, hipStream_t st) {
   if (qkv_rows_shape(p)) return launch_qkv_rows(p, nullptr, st);
-  const bool dma = use_dma(p.M, p.N, p.K, p.a_kmajor, p.b_kmajor) && (p.b_kper == 0 || p.b_kper % DK == 0) && !p.ln_g;
+  const bool dma = use_dma(p.M, p.N, p.K, p.a_kmajor, p.b_kmajor) && (p.b_kper == 0 || p.b_kper % DK == 0) && !p.ln_g &&
+                   p.gelu <= 1;   // MGEMM_GELU_BOTH / _GRAD exist in the 128 x 128 kernel only
   if (p.a_kmajor && p.b_kmajor) launch_layout<true, true>(p, dma, st);
   else if (p.b_kmajor) launch_layout<false, true>(p, dma, st);
   else if (p.a_kmajor) launch_layout<true, false>(p, dma, st);

@@ -56,9 +56,10 @@ static void init_gemm(MGemm* p) {
 
 void mfma_linear(const void* A, long lda, const void* w0, const void* w1, const void* w2, long ldb, int n_per,
                  const void* b0, const void* b1, const void* b2, int gelu, const void* res, void* C, long ldc, int M,
-                 int N, int K, hipStream_t st, LnArgs ln) {
+                 int N, int K, hipStream_t st, LnArgs ln, void* C2) {
   MGemm p;
   init_gemm(&p);
+  p.C2 = (bf16_t*)C2;
   p.ln_g = (const bf16_t*)ln.g; p.ln_b = (const bf16_t*)ln.b; p.ln_eps = ln.eps;
   p.A = (const bf16_t*)A; p.lda = lda;
   p.B[0] = (const bf16_t*)w0; p.B[1] = (const bf16_t*)w1; p.B[2] = (const bf16_t*)w2; p.ldb = ldb;
@@ -72,9 +73,10 @@ void mfma_linear(const void* A, long lda, const void* w0, const void* w1, const 
 }
 
 void mfma_dgrad(const void* G, long ldg, const void* w0, const void* w1, const void* w2, long ldw, int k_per, void* C,
-                long ldc, int M, int N, int K, hipStream_t st) {
+                long ldc, int M, int N, int K, hipStream_t st, const void* gelu_grad_of) {
   MGemm p;
   init_gemm(&p);
+  if (gelu_grad_of) { p.res = (const bf16_t*)gelu_grad_of; p.gelu = MGEMM_GELU_GRAD; }
   p.A = (const bf16_t*)G; p.lda = ldg;
   p.B[0] = (const bf16_t*)w0; p.B[1] = (const bf16_t*)w1; p.B[2] = (const bf16_t*)w2; p.ldb = ldw;
   p.b_kper = (w1 || w2) ? k_per : 0;

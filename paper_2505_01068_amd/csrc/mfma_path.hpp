@@ -6,6 +6,10 @@
 namespace imattn {
 
 // Descriptor of one bf16 MFMA GEMM  C[M,N] = sum_k A(m,k) B(n,k)  (see mfma_gemm.hip).
+// Epilogue modes of the 128 x 128 kernel beyond the plain GELU (gelu = 1), for a layer's training passes:
+//   BOTH: C = A B + bias (the pre-activation), C2 = GELU(C as rounded to bf16);
+//   GRAD: C = (A B) * GELU'(res), res = the saved pre-activation (not added).
+constexpr int MGEMM_GELU_BOTH = 2, MGEMM_GELU_GRAD = 3;
 struct MGemm {
   const bf16_t* A; long lda; int a_kmajor;  // a_kmajor = 0: A is [M][K] rows; 1: A is [K][M] rows
   const bf16_t* B[3]; long ldb; int b_kmajor;  // b_kmajor = 0: B is [N][K] rows; 1: B is [K][N] rows
@@ -17,7 +21,8 @@ struct MGemm {
   int scale0_on; float scale0;           // scale0_on: columns n < n_per leave as scale0 * (A B + bias)
   const bf16_t* ln_g; const bf16_t* ln_b; float ln_eps;  // ln_g != NULL: the rows of A are LayerNorm-ed as they are
                                                          // staged (row-major A; K == 64: mfma_gemm_fuses_ln, or the Q|K|V shape: mfma_qkv_fuses_ln)
-  int gelu;
+  int gelu;                              // 0, 1 = GELU epilogue, or one of the two modes below (EPI kernels)
+  bf16_t* C2;                            // MGEMM_GELU_BOTH: the activation output, same ld as C
   const bf16_t* res;                     // residual rows, same ld as C
   bf16_t* C; long ldc;                   // row-major output
   // paired launch (launch_mfma_gemm_pair): byte offsets from this problem's tensors to the second problem's
@@ -44,7 +49,8 @@ inline bool mfma_linear_ok(int is_bf16, long K, long N) { return is_bf16 && K % 
 // data gradient  C[M,N] = G[M,K] W^T  with W stored [N][K'] row-major; the contraction may run over up to three
 // weights of k_per columns each (K = 3 k_per, k_per % 64 == 0), as in dx = dQ Wq^T + dK Wk^T + dV Wv^T
 void mfma_dgrad(const void* G, long ldg, const void* w0, const void* w1, const void* w2, long ldw, int k_per, void* C,
-                long ldc, int M, int N, int K, hipStream_t st);
+                long ldc, int M, int N, int K, hipStream_t st, const void* gelu_grad_of = nullptr);
+// (gelu_grad_of != NULL, shapes with mfma_gemm_small_tile only: C = (G W^T) * GELU'(gelu_grad_of), same ld as C)
 // weight gradient  C[M,N] (fp32) = A[R,M]^T G[R,N]  (contraction over rows), split-K with a fixed-order
 // reduction; n_per > 0: column block s of n_per columns goes to the [M, n_per] output o<s> (NULL = dropped);
 // n_per = 0: one [M, N] output o0.  `partial`: mfma_wgrad_partial_bytes.  M % 8 == 0 and N % 8 == 0.
@@ -53,7 +59,8 @@ void mfma_wgrad(const void* A, long lda, const void* G, long ldg, float* o0, flo
                 int N, int R, float* partial, hipStream_t st);
 void mfma_linear(const void* A, long lda, const void* w0, const void* w1, const void* w2, long ldb, int n_per,
                  const void* b0, const void* b1, const void* b2, int gelu, const void* res, void* C, long ldc, int M,
-                 int N, int K, hipStream_t st, LnArgs ln = {nullptr, nullptr, 0.f});
+                 int N, int K, hipStream_t st, LnArgs ln = {nullptr, nullptr, 0.f}, void* C2 = nullptr);
+// (gelu = MGEMM_GELU_BOTH, shapes with mfma_gemm_small_tile only: C = the pre-activation, C2 = GELU of it)
 // y = h + GELU(LayerNorm(h) W1 + b1) W2 + b2 in one kernel at model width 64 or 128 (bf16, d_ff % 64 == 0,
 // 16-byte aligned pointers; b1 / b2 may be NULL)
 bool mlp_tail_ok(int is_bf16, long d, long d_ff, const void* h, const void* ln_g, const void* ln_b, const void* w1,
@@ -69,6 +76,7 @@ struct MlpTailPairSide {
 };
 void launch_mlp_tail_pair(const MlpTailPairSide& a, const MlpTailPairSide& b, float ln_eps, int R, int d, int d_ff,
                           hipStream_t st);
+bool mfma_gemm_small_tile(int M, int N, int K, bool b_kmajor);
 int mfma_gemm_split(int M, int N, int K);
 void launch_splitk_reduce(const float* partial, int split_k, int M, int N, float* o0, float* o1, float* o2, int n_per,
                           hipStream_t st);
