@@ -714,7 +714,7 @@ extern "C" {
 
 struct LayerTrain {
   size_t att, h, zpre, a, saved_total;                                   // saved
-  size_t u, v, dz, dv, dh, t, partial, cpart, attws, ws_total;           // backward workspace
+  size_t u, v, dz, dv, dh, t, partial, partial1, cpart, cpart2, cpart3, attws, ws_total;   // backward workspace
   size_t fwd_ws_total;                                                   // forward workspace: u
   int split_w1, split_w2;
   size_t aws_bytes;
@@ -744,8 +744,13 @@ static LayerTrain layer_train_layout(const im_shape_t* s, int32_t d_ff) {
     p1 = std::max(p1, mfma_wgrad_partial_bytes((int)d, d_ff, (int)R));
     p2 = std::max(p2, mfma_wgrad_partial_bytes(d_ff, (int)d, (int)R));
   }
-  L.partial = off; off += align256(std::max(p1, p2));
-  L.cpart = off; off += align256(colsum_partial_bytes((int)R, (int)std::max(3 * d, f)));   // db2 and two LayerNorm sums at once
+  // every second-stage sum of the backward may be postponed to one launch at its end (ReduceList): each set of
+  // partials keeps a region of its own
+  L.partial = off; off += align256(p2);     // dW2
+  L.partial1 = off; off += align256(p1);    // dW1
+  L.cpart = off; off += align256(colsum_partial_bytes((int)R, (int)f));         // db1
+  L.cpart2 = off; off += align256(colsum_partial_bytes((int)R, (int)(3 * d)));  // second LayerNorm's two sums and db2
+  L.cpart3 = off; off += align256(colsum_partial_bytes((int)R, (int)(2 * d)));  // first LayerNorm's two sums
   L.aws_bytes = bwd_workspace_bytes(s);
   L.attws = off; off += align256(L.aws_bytes);
   L.ws_total = off;
@@ -855,13 +860,18 @@ int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const g
   void* dh = ws + L.dh;
   void* t = ws + L.t;
   float* partial = (float*)(ws + L.partial);
+  float* partial1 = (float*)(ws + L.partial1);
   float* cpart = (float*)(ws + L.cpart);
+  float* cpart2 = (float*)(ws + L.cpart2);
+  float* cpart3 = (float*)(ws + L.cpart3);
+  ReduceList later;   // second-stage sums postponed to one launch at the end (matrix-core path, small outputs)
+  later.n = 0;
   GemmDesc g;
   const bool mm = mfma_linear_ok(bf, d, d_ff) && mfma_linear_ok(bf, d_ff, d);  // bf16 GEMMs on the matrix cores
 
   // y = h + a W2 + b2
   if (gr->w2 && mm) {
-    mfma_wgrad(a, d_ff, dy, d, (float*)gr->w2, nullptr, nullptr, 0, d_ff, (int)d, (int)R, partial, st);
+    mfma_wgrad(a, d_ff, dy, d, (float*)gr->w2, nullptr, nullptr, 0, d_ff, (int)d, (int)R, partial, st, &later);
   } else if (gr->w2) {  // dW2 = a^T dy
     memset(&g, 0, sizeof(g));
     g.A = a; g.sam = 1; g.sak = d_ff; g.B[0] = dy; g.sbk = d; g.sbn = 1;
@@ -883,14 +893,19 @@ int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const g
   // z = v W1 + b1 with v = LN(h; ln2)
   if ((rc = launch_layernorm(h, p->ln2_g, p->ln2_b, v, (int)R, (int)d, ln_eps, bf, st))) return rc;
   if (gr->w1 && mm) {
-    mfma_wgrad(v, d, dz, d_ff, (float*)gr->w1, nullptr, nullptr, 0, (int)d, d_ff, (int)R, partial, st);
+    mfma_wgrad(v, d, dz, d_ff, (float*)gr->w1, nullptr, nullptr, 0, (int)d, d_ff, (int)R, partial1, st, &later);
   } else if (gr->w1) {  // dW1 = v^T dz
     memset(&g, 0, sizeof(g));
     g.A = v; g.sam = 1; g.sak = d; g.B[0] = dz; g.sbk = d_ff; g.sbn = 1;
-    g.C[0] = gr->w1; g.ldc = d_ff; g.M = (int)d; g.N = d_ff; g.K = (int)R; g.split_k = L.split_w1; g.partial = partial;
+    g.C[0] = gr->w1; g.ldc = d_ff; g.M = (int)d; g.N = d_ff; g.K = (int)R; g.split_k = L.split_w1; g.partial = partial1;
     if ((rc = launch_gemm_alu(g, bf, bf, 0, st))) return rc;
   }
-  if (gr->b1 && (rc = launch_colsum(dz, d_ff, (int)R, d_ff, bf, (float*)gr->b1, cpart, st))) return rc;
+  if (gr->b1) {
+    const void* src1[1] = {dz};
+    const long ld1[1] = {d_ff};
+    float* out1[1] = {(float*)gr->b1};
+    if ((rc = launch_colsum_multi(src1, ld1, out1, 1, (int)R, d_ff, bf, cpart, st, mm ? &later : nullptr))) return rc;
+  }
   if (mm) {  // dv = dz W1^T
     mfma_dgrad(dz, d_ff, p->w1, nullptr, nullptr, d_ff, 0, dv, d, (int)R, (int)d, d_ff, st);
   } else {
@@ -905,14 +920,15 @@ int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const g
     const void* src[3] = {t, dv, dy};
     const long ld3[3] = {d, d, d};
     float* out3[3] = {(float*)gr->ln2_g, (float*)gr->ln2_b, (float*)gr->b2};
-    if ((rc = launch_colsum_multi(src, ld3, out3, 3, (int)R, (int)d, bf, cpart, st))) return rc;
+    if ((rc = launch_colsum_multi(src, ld3, out3, 3, (int)R, (int)d, bf, cpart2, st, mm ? &later : nullptr))) return rc;
   }
   // h = x + IMAttention(u), u = LN(x; ln1): attention backward with upstream gradient dh; its dx is du (into dv)
   if ((rc = launch_layernorm(x, p->ln1_g, p->ln1_b, u, (int)R, (int)d, ln_eps, bf, st))) return rc;
   const SavedLayout A = saved_layout(shape);
   if (pick_path(shape) == PATH_MFMA)
     rc = mfma_attention_bwd(shape, u, p->wq, p->wk, p->wv, p->wo, valid_len, key_pad, sv + L.att, A.qkv, A.o, A.lse, A.extra,
-                            dh, dv, gr->wq, gr->wk, gr->wv, gr->wo, gr->bq, gr->bk, gr->bv, gr->bo, ws + L.attws, st);
+                            dh, dv, gr->wq, gr->wk, gr->wv, gr->wo, gr->bq, gr->bk, gr->bv, gr->bo, ws + L.attws, st,
+                            mm ? &later : nullptr);
   else
     rc = bwd_rowlane(shape, u, p->wq, p->wk, p->wv, p->wo, valid_len, key_pad, sv + L.att, dh, dv, gr->wq, gr->wk, gr->wv,
                      gr->wo, gr->bq, gr->bk, gr->bv, gr->bo, ws + L.attws, st);
@@ -923,8 +939,9 @@ int gsit_layer_bwd(const im_shape_t* shape, int32_t d_ff, const void* x, const g
     const void* src[2] = {t, dv};
     const long ld2[2] = {d, d};
     float* out2[2] = {(float*)gr->ln1_g, (float*)gr->ln1_b};
-    if ((rc = launch_colsum_multi(src, ld2, out2, 2, (int)R, (int)d, bf, cpart, st))) return rc;
+    if ((rc = launch_colsum_multi(src, ld2, out2, 2, (int)R, (int)d, bf, cpart3, st, mm ? &later : nullptr))) return rc;
   }
+  launch_reduce_list(later, st);
   return check_hip("gsit_layer_bwd launch");
 }
 

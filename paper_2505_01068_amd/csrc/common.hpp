@@ -176,12 +176,22 @@ struct GemmDesc {
 int launch_gemm_alu(const GemmDesc& g, int a_bf16, int b_bf16, int c_bf16, hipStream_t st);
 size_t gemm_alu_partial_bytes(int M, int N, int K, int* split_k);
 
+// Second stages that a caller may postpone to ONE launch at the end of a backward pass: the fixed-order sums over
+// split-K partials [nparts][M][N] (outputs as mfma_wgrad's) and over the row-block partials of column sums (M = 1).
+// Each is a few microseconds of launch latency on its own.  A postponed job's partial buffer must stay untouched
+// until launch_reduce_list.
+struct ReduceJob { const float* partial; int nparts, M, N, n_per; float* o[3]; };
+struct ReduceList { ReduceJob job[16]; int n; };
+// N % 4 == 0 and at most 65536 output quads: the job can go on a list
+bool reduce_deferrable(int M, int N);
+void reduce_push(ReduceList* l, const float* partial, int nparts, int M, int N, float* o0, float* o1, float* o2, int n_per);
+void launch_reduce_list(const ReduceList& l, hipStream_t st);
 // column sums of a [R, n] matrix (bias gradients), deterministic two-stage
 int launch_colsum(const void* a, long lda, int R, int n, int a_bf16, float* out, float* partial, hipStream_t st);
 size_t colsum_partial_bytes(int R, int n);   // for one matrix; launch_colsum_multi (count <= 4) needs count times as much
 // column sums of up to 3 [R, n] matrices (same element type) in one pair of launches; out[i] == nullptr skips matrix i
 int launch_colsum_multi(const void* const* a, const long* lda, float* const* out, int count, int R, int n, int a_bf16,
-                        float* partial, hipStream_t st);
+                        float* partial, hipStream_t st, ReduceList* defer = nullptr);   // defer: second stage onto the list
 
 // Zero columns col0 .. col0+ncols-1 of the rows of segment s of a [rows, ld] matrix; set a per-row
 // fp32 statistic ([B,H,T] padded / [H,R] packed) of the rows of segment s.  All batch elements.

@@ -906,8 +906,55 @@ __global__ __launch_bounds__(256) void colsum_stage2(const float* __restrict__ p
 // bytes of `partial` for ONE matrix; launch_colsum_multi needs count times as much
 size_t colsum_partial_bytes(int R, int n) { return (size_t)((R + CS_ROWS - 1) / CS_ROWS) * n * sizeof(float); }
 
+// One launch for a list of second-stage sums (blockIdx.y = job).  A block is 16 output quads x 16 lanes over the
+// partials: lane zl adds partials zl, zl + 16, ... in ascending order, then the 16 lane sums are added in a fixed
+// order through LDS -- the same order as colsum_stage2 and the parallel split-K reduction use on their own.
+__global__ __launch_bounds__(256) void reduce_list_kernel(ReduceList l) {
+  __shared__ float4 red[16][16];
+  const ReduceJob& j = l.job[blockIdx.y];
+  const long n_out = (long)j.M * j.N;
+  const int ql = threadIdx.x & 15, zl = threadIdx.x >> 4;
+  if ((long)blockIdx.x * 64 >= n_out) return;   // block-uniform
+  const long i = ((long)blockIdx.x * 16 + ql) * 4;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i < n_out)
+    for (int z = zl; z < j.nparts; z += 16) {
+      const float4 v = *(const float4*)(j.partial + z * n_out + i);
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+  red[zl][ql] = s;
+  __syncthreads();
+  if (zl != 0 || i >= n_out) return;
+  for (int k = 1; k < 16; ++k) {
+    const float4 v = red[k][ql];
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  const int m = (int)(i / j.N), n = (int)(i % j.N);
+  float* o = j.o[0];
+  long at = i;
+  if (j.n_per > 0) {
+    const int sel = n / j.n_per;
+    o = sel == 0 ? j.o[0] : sel == 1 ? j.o[1] : j.o[2];
+    at = (long)m * j.n_per + n % j.n_per;
+  }
+  if (!o) return;
+  o[at] = s.x; o[at + 1] = s.y; o[at + 2] = s.z; o[at + 3] = s.w;   // caller pointers: no alignment assumed
+}
+bool reduce_deferrable(int M, int N) { return N % 4 == 0 && (long)M * N <= 4L * 65536; }
+void reduce_push(ReduceList* l, const float* partial, int nparts, int M, int N, float* o0, float* o1, float* o2, int n_per) {
+  ReduceJob& j = l->job[l->n++];
+  j.partial = partial; j.nparts = nparts; j.M = M; j.N = N; j.n_per = n_per;
+  j.o[0] = o0; j.o[1] = o1; j.o[2] = o2;
+}
+void launch_reduce_list(const ReduceList& l, hipStream_t st) {
+  if (l.n == 0) return;
+  long mx = 0;
+  for (int i = 0; i < l.n; ++i) mx = std::max(mx, (long)l.job[i].M * l.job[i].N);
+  hipLaunchKernelGGL(reduce_list_kernel, dim3((unsigned)((mx + 63) / 64), l.n), dim3(256), 0, st, l);
+}
+
 int launch_colsum_multi(const void* const* a, const long* lda, float* const* out, int count, int R, int n, int a_bf16,
-                        float* partial, hipStream_t st) {
+                        float* partial, hipStream_t st, ReduceList* defer) {
   ColsumArgs q;
   bool any = false;
   for (int i = 0; i < 4; ++i) {   // count <= 4
@@ -927,6 +974,11 @@ int launch_colsum_multi(const void* const* a, const long* lda, float* const* out
   else if (vec) hipLaunchKernelGGL((colsum_stage1_vec<float>), dim3(1, nblk, count), block, 0, st, q, R, n, partial);
   else if (a_bf16) hipLaunchKernelGGL((colsum_stage1<bf16_t>), grid, block, 0, st, q, R, n, partial);
   else hipLaunchKernelGGL((colsum_stage1<float>), grid, block, 0, st, q, R, n, partial);
+  if (defer && reduce_deferrable(1, n) && defer->n + count <= 16) {
+    for (int i = 0; i < count; ++i)
+      if (q.out[i]) reduce_push(defer, partial + (long)i * nblk * n, nblk, 1, n, q.out[i], nullptr, nullptr, 0);
+    return IM_OK;
+  }
   hipLaunchKernelGGL(colsum_stage2, dim3((n + 15) / 16, 1, count), dim3(256), 0, st, partial, nblk, n, q);
   return IM_OK;
 }

@@ -28,7 +28,7 @@ static Dims dims(const im_shape_t* s) {
 size_t mfma_saved_extra_bytes(const im_shape_t*) { return 0; }
 size_t mfma_fwd_workspace_bytes(int) { return 0; }
 
-struct BwdWs { size_t d_o, delta, dqkv, partial, cpart, wt, total; int split_w, split_o; bool tw; };
+struct BwdWs { size_t d_o, delta, dqkv, partial, partial_o, cpart, wt, total; int split_w, split_o; bool tw; };
 static BwdWs bwd_ws(const im_shape_t* s) {
   const Dims x = dims(s);
   BwdWs w;
@@ -38,8 +38,9 @@ static BwdWs bwd_ws(const im_shape_t* s) {
   w.dqkv = off; off += al(x.R * 3 * x.d * 2);
   w.split_w = mfma_gemm_split((int)x.d, (int)(3 * x.d), (int)x.R);
   w.split_o = mfma_gemm_split((int)x.d, (int)x.d, (int)x.R);
-  w.partial = off;
-  off += al(std::max((size_t)w.split_w * x.d * 3 * x.d, (size_t)w.split_o * x.d * x.d) * 4);
+  // one region per weight gradient: a postponed reduction (ReduceList) reads its partials at the end of the pass
+  w.partial = off; off += al((size_t)w.split_w * x.d * 3 * x.d * 4);
+  w.partial_o = off; off += al((size_t)w.split_o * x.d * x.d * 4);
   w.cpart = off; off += al(4 * colsum_partial_bytes((int)x.R, (int)x.d));   // dbo, dbq, dbk, dbv in one launch
   // Wo^T and [Wq^T; Wk^T; Wv^T] for the data gradients, where the large-tile GEMM serves them
   w.tw = x.d % 32 == 0 && mfma_dgrad_wants_transposed_weights((int)x.R, (int)x.d, (int)x.d);
@@ -88,7 +89,7 @@ void mfma_dgrad(const void* G, long ldg, const void* w0, const void* w1, const v
 size_t mfma_wgrad_partial_bytes(int M, int N, int R) { return (size_t)mfma_gemm_split(M, N, R) * M * N * sizeof(float); }
 
 void mfma_wgrad(const void* A, long lda, const void* G, long ldg, float* o0, float* o1, float* o2, int n_per, int M,
-                int N, int R, float* partial, hipStream_t st) {
+                int N, int R, float* partial, hipStream_t st, ReduceList* defer) {
   MGemm p;
   init_gemm(&p);
   p.A = (const bf16_t*)A; p.lda = lda; p.a_kmajor = 1;
@@ -96,7 +97,8 @@ void mfma_wgrad(const void* A, long lda, const void* G, long ldg, float* o0, flo
   p.M = M; p.N = N; p.K = R;
   p.split_k = mfma_gemm_split(M, N, R); p.partial = partial;
   launch_mfma_gemm(p, st);
-  launch_splitk_reduce(partial, p.split_k, M, N, o0, o1, o2, n_per, st);
+  if (defer && reduce_deferrable(M, N) && defer->n < 16) reduce_push(defer, partial, p.split_k, M, N, o0, o1, o2, n_per);
+  else launch_splitk_reduce(partial, p.split_k, M, N, o0, o1, o2, n_per, st);
 }
 
 // Q|K|V = x [Wq|Wk|Wv] + [bq|bk|bv]: the weights are [d_in][d_out] = k-major B operands.
@@ -187,7 +189,7 @@ int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const
                        const void* wo, const int32_t* valid_len, const uint8_t* key_pad, const char* sv,
                        size_t off_qkv, size_t off_o, size_t off_lse, size_t, const void* dy, void* dx, void* dwq,
                        void* dwk, void* dwv, void* dwo, void* dbq, void* dbk, void* dbv, void* dbo, char* ws,
-                       hipStream_t st) {
+                       hipStream_t st, ReduceList* defer) {
   Geo g;
   build_geo(s, mfma_dq_tile_rows(), mfma_dkv_tile_rows(), &g);
   const Dims dm = dims(s);
@@ -200,6 +202,7 @@ int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const
   float* delta = (float*)(ws + w.delta);
   bf16_t* dqkv = (bf16_t*)(ws + w.dqkv);
   float* partial = (float*)(ws + w.partial);
+  float* partial_o = (float*)(ws + w.partial_o);
   float* cpart = (float*)(ws + w.cpart);
 
   MGemm p;
@@ -223,9 +226,10 @@ int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const
     p.A = o; p.lda = d; p.a_kmajor = 1;
     p.B[0] = (const bf16_t*)dy; p.ldb = d; p.b_kmajor = 1;
     p.M = d; p.N = d; p.K = R;
-    p.split_k = w.split_o; p.partial = partial;
+    p.split_k = w.split_o; p.partial = partial_o;
     launch_mfma_gemm(p, st);
-    launch_splitk_reduce(partial, w.split_o, d, d, (float*)dwo, nullptr, nullptr, 0, st);
+    if (defer && reduce_deferrable(d, d) && defer->n < 16) reduce_push(defer, partial_o, w.split_o, d, d, (float*)dwo, nullptr, nullptr, 0);
+    else launch_splitk_reduce(partial_o, w.split_o, d, d, (float*)dwo, nullptr, nullptr, 0, st);
   }
 
   launch_mfma_bwd(g, qkv, 3 * d, o, d_o, d, lse2, valid_len, key_pad, delta, dqkv, 3 * d, st);
@@ -239,14 +243,16 @@ int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const
     p.M = d; p.N = 3 * d; p.K = R;
     p.split_k = w.split_w; p.partial = partial;
     launch_mfma_gemm(p, st);
-    launch_splitk_reduce(partial, w.split_w, d, 3 * d, (float*)dwq, (float*)dwk, (float*)dwv, d, st);
+    if (defer && reduce_deferrable(d, 3 * d) && defer->n < 16)
+      reduce_push(defer, partial, w.split_w, d, 3 * d, (float*)dwq, (float*)dwk, (float*)dwv, d);
+    else launch_splitk_reduce(partial, w.split_w, d, 3 * d, (float*)dwq, (float*)dwk, (float*)dwv, d, st);
   }
   if (dbo || dbq || dbk || dbv) {  // column sums of dy and of the dQ | dK | dV column blocks, one pair of launches
     const void* src[4] = {dy, dqkv, dqkv + d, dqkv + 2 * (size_t)d};
     const long lds4[4] = {(long)d, 3 * (long)d, 3 * (long)d, 3 * (long)d};
     float* dbs[4] = {(float*)dbo, (float*)dbq, (float*)dbk, (float*)dbv};
     ProfScope ps(PF_WGRAD, st);
-    launch_colsum_multi(src, lds4, dbs, 4, R, d, 1, cpart, st);
+    launch_colsum_multi(src, lds4, dbs, 4, R, d, 1, cpart, st, defer);
   }
 
   if (dx) {

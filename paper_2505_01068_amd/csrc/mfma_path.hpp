@@ -56,7 +56,7 @@ void mfma_dgrad(const void* G, long ldg, const void* w0, const void* w1, const v
 // n_per = 0: one [M, N] output o0.  `partial`: mfma_wgrad_partial_bytes.  M % 8 == 0 and N % 8 == 0.
 size_t mfma_wgrad_partial_bytes(int M, int N, int R);
 void mfma_wgrad(const void* A, long lda, const void* G, long ldg, float* o0, float* o1, float* o2, int n_per, int M,
-                int N, int R, float* partial, hipStream_t st);
+                int N, int R, float* partial, hipStream_t st, ReduceList* defer = nullptr);
 void mfma_linear(const void* A, long lda, const void* w0, const void* w1, const void* w2, long ldb, int n_per,
                  const void* b0, const void* b1, const void* b2, int gelu, const void* res, void* C, long ldc, int M,
                  int N, int K, hipStream_t st, LnArgs ln = {nullptr, nullptr, 0.f}, void* C2 = nullptr);
@@ -115,6 +115,6 @@ int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const
                        const void* wo, const int32_t* valid_len, const uint8_t* key_pad, const char* sv,
                        size_t off_qkv, size_t off_o, size_t off_lse, size_t off_extra, const void* dy, void* dx,
                        void* dwq, void* dwk, void* dwv, void* dwo, void* dbq, void* dbk, void* dbv, void* dbo, char* ws,
-                       hipStream_t st);
+                       hipStream_t st, ReduceList* defer = nullptr);   // defer: see ReduceList (small outputs only)
 
 }  // namespace imattn
