@@ -506,10 +506,16 @@ int im_attention_bwd(const im_shape_t* shape, const void* x, const void* wq, con
   if (!workspace || workspace_bytes < need)
     return fail(IM_ERR_WORKSPACE, "im_attention_bwd needs %zu workspace bytes, got %zu", need, workspace_bytes);
   const SavedLayout L = saved_layout(shape);
-  if (pick_path(shape) == PATH_MFMA)
-    return mfma_attention_bwd(shape, x, wq, wk, wv, wo, valid_len, key_pad, (const char*)saved, L.qkv, L.o, L.lse,
-                              L.extra, dy, dx, dwq, dwk, dwv, dwo, dbq, dbk, dbv, dbo, (char*)workspace,
-                              as_stream(hip_stream));
+  if (pick_path(shape) == PATH_MFMA) {
+    ReduceList later;   // at small widths the second-stage sums of the gradients run as one launch at the end
+    later.n = 0;
+    if ((rc = mfma_attention_bwd(shape, x, wq, wk, wv, wo, valid_len, key_pad, (const char*)saved, L.qkv, L.o, L.lse,
+                                 L.extra, dy, dx, dwq, dwk, dwv, dwo, dbq, dbk, dbv, dbo, (char*)workspace,
+                                 as_stream(hip_stream), &later)))
+      return rc;
+    launch_reduce_list(later, as_stream(hip_stream));
+    return check_hip("im_attention_bwd launch");
+  }
   return bwd_rowlane(shape, x, wq, wk, wv, wo, valid_len, key_pad, (const char*)saved, dy, dx, dwq, dwk, dwv, dwo, dbq,
                      dbk, dbv, dbo, (char*)workspace, as_stream(hip_stream));
 }
