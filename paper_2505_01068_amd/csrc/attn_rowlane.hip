@@ -53,6 +53,43 @@ __device__ __forceinline__ int count_chunks(unsigned live, int n_seg, LenFn len_
   return total;
 }
 
+// The head's dh values of one row (base = the row's first column of the head), zero beyond dh.  Every load is
+// issued, none sits behind a branch on dh: a conditional load per element is a round trip per element.
+template <typename T, int DH>
+__device__ __forceinline__ void load_head_row(const T* base, int dh, float (&out)[DH]) {
+  float v[DH];
+#pragma unroll
+  for (int e = 0; e < DH; ++e) v[e] = ldf(base + (e < dh ? e : 0));
+#pragma unroll
+  for (int e = 0; e < DH; ++e) out[e] = e < dh ? v[e] : 0.f;
+}
+// Rows row0 .. row0 + n - 1 (n <= RL_CHUNK) of the head's columns of two matrices into two [RL_CHUNK][LP] LDS
+// tiles of one wave, zero beyond n and beyond dh; the first matrix is multiplied by scale_a.  All 2 LP loads of
+// a lane are in flight before the first LDS store: written as a loop over the chunk with a store after every
+// load, staging was one memory round trip per 64 elements, eight per chunk, and these kernels are latency-bound.
+template <typename T, int LP>
+__device__ __forceinline__ void stage_chunk(const T* A, long lda, const T* B, long ldb, long row0, int n, int hc, int dh,
+                                            float scale_a, float (*sa)[LP], float (*sb)[LP], int lane) {
+  constexpr int PER = RL_CHUNK * LP / RL_ROWS;
+  float va[PER], vb[PER];
+#pragma unroll
+  for (int u = 0; u < PER; ++u) {
+    const int i = lane + u * RL_ROWS, c = i / LP, e = i % LP;
+    const bool ok = c < n && e < dh;
+    const long r = row0 + (ok ? c : 0);
+    const int col = hc + (ok ? e : 0);
+    va[u] = ldf(A + r * lda + col);
+    vb[u] = ldf(B + r * ldb + col);
+  }
+#pragma unroll
+  for (int u = 0; u < PER; ++u) {
+    const int i = lane + u * RL_ROWS, c = i / LP, e = i % LP;
+    const bool ok = c < n && e < dh;
+    sa[c][e] = ok ? va[u] * scale_a : 0.f;
+    sb[c][e] = ok ? vb[u] : 0.f;
+  }
+}
+
 template <typename T, int DH, int NW>
 __global__ __launch_bounds__(NW * RL_ROWS) void rowlane_fwd_kernel(Geo g, const T* __restrict__ Q, const T* __restrict__ K,
                                                                    const T* __restrict__ V, long ld,
@@ -74,9 +111,10 @@ __global__ __launch_bounds__(NW * RL_ROWS) void rowlane_fwd_kernel(Geo g, const 
   const int dh = g.dh, hc = h * dh;
 
   float q[DH], acc[DH];
+  load_head_row<T, DH>(Q + t * ld + hc, dh, q);
 #pragma unroll
   for (int e = 0; e < DH; ++e) {
-    q[e] = (e < dh) ? ldf(Q + t * ld + hc + e) * g.scale_log2e : 0.f;
+    q[e] *= g.scale_log2e;
     acc[e] = 0.f;
   }
   float m = IM_NEG_INF, l = 0.f;
@@ -95,13 +133,7 @@ __global__ __launch_bounds__(NW * RL_ROWS) void rowlane_fwd_kernel(Geo g, const 
     __syncthreads();
     if (has) {
       const long kbase = seg_row0(g, b, j);
-      for (int i = lane; i < n4 * LP; i += RL_ROWS) {
-        const int c = i / LP, e = i % LP;
-        const bool ok = (c < n) && (e < dh);
-        const long a = (kbase + c0 + c) * ld + hc + e;
-        sKV[wave][0][c][e] = ok ? ldf(K + a) : 0.f;
-        sKV[wave][1][c][e] = ok ? ldf(V + a) : 0.f;
-      }
+      stage_chunk<T, LP>(K, ld, V, ld, kbase + c0, n, hc, dh, 1.f, sKV[wave][0], sKV[wave][1], lane);
       for (int c = lane; c < n4; c += RL_ROWS) {
         bool ok = c < n;
         if (ok && key_pad) ok = key_pad[kbase + c0 + c] == 0;
@@ -194,12 +226,14 @@ __global__ __launch_bounds__(NW * RL_ROWS) void rowlane_dq_kernel(Geo g, const T
 
   float q[DH], go[DH], acc[DH];
   float dl = 0.f;
+  float oo[DH];
+  load_head_row<T, DH>(Q + t * ld + hc, dh, q);
+  load_head_row<T, DH>(dO + t * ldo + hc, dh, go);
+  load_head_row<T, DH>(O + t * ldo + hc, dh, oo);
 #pragma unroll
   for (int e = 0; e < DH; ++e) {
-    q[e] = (e < dh) ? ldf(Q + t * ld + hc + e) * g.scale_log2e : 0.f;
-    go[e] = (e < dh) ? ldf(dO + t * ldo + hc + e) : 0.f;
-    const float oo = (e < dh) ? ldf(O + t * ldo + hc + e) : 0.f;
-    dl = fmaf(go[e], oo, dl);
+    q[e] *= g.scale_log2e;
+    dl = fmaf(go[e], oo[e], dl);
     acc[e] = 0.f;
   }
   float ls = lse2[li];
@@ -219,12 +253,7 @@ __global__ __launch_bounds__(NW * RL_ROWS) void rowlane_dq_kernel(Geo g, const T
     __syncthreads();
     if (has) {
       const long kbase = seg_row0(g, b, j);
-      for (int i = lane; i < n * LP; i += RL_ROWS) {
-        const int c = i / LP, e = i % LP;
-        const long a = (kbase + c0 + c) * ld + hc + e;
-        sKV[wave][0][c][e] = (e < dh) ? ldf(K + a) : 0.f;
-        sKV[wave][1][c][e] = (e < dh) ? ldf(V + a) : 0.f;
-      }
+      stage_chunk<T, LP>(K, ld, V, ld, kbase + c0, n, hc, dh, 1.f, sKV[wave][0], sKV[wave][1], lane);
       for (int c = lane; c < n; c += RL_ROWS) {
         bool ok = true;
         if (key_pad) ok = key_pad[kbase + c0 + c] == 0;
@@ -310,10 +339,10 @@ __global__ __launch_bounds__(NW * RL_ROWS) void rowlane_dkv_kernel(Geo g, const 
   }
 
   float k[DH], v[DH], ak[DH], av[DH];
+  load_head_row<T, DH>(K + t * ld + hc, dh, k);
+  load_head_row<T, DH>(V + t * ld + hc, dh, v);
 #pragma unroll
   for (int e = 0; e < DH; ++e) {
-    k[e] = (e < dh) ? ldf(K + t * ld + hc + e) : 0.f;
-    v[e] = (e < dh) ? ldf(V + t * ld + hc + e) : 0.f;
     ak[e] = 0.f;
     av[e] = 0.f;
   }
@@ -327,11 +356,7 @@ __global__ __launch_bounds__(NW * RL_ROWS) void rowlane_dkv_kernel(Geo g, const 
     if (has) {
       const long qbase = seg_row0(g, b, i);
       const long lbase = seg_stat0(g, b, h, i);
-      for (int x = lane; x < n * LP; x += RL_ROWS) {
-        const int r = x / LP, e = x % LP;
-        sQG[wave][0][r][e] = (e < dh) ? ldf(Q + (qbase + r0 + r) * ld + hc + e) * g.scale_log2e : 0.f;
-        sQG[wave][1][r][e] = (e < dh) ? ldf(dO + (qbase + r0 + r) * ldo + hc + e) : 0.f;
-      }
+      stage_chunk<T, LP>(Q, ld, dO, ldo, qbase + r0, n, hc, dh, g.scale_log2e, sQG[wave][0], sQG[wave][1], lane);
       for (int r = lane; r < n; r += RL_ROWS) {
         const float ls = lse2[lbase + r0 + r];
         sL[wave][r] = (ls == IM_NEG_INF) ? __builtin_inff() : ls;
