@@ -182,8 +182,9 @@ size_t gemm_alu_partial_bytes(int M, int N, int K, int* split_k);
 // until launch_reduce_list.
 struct ReduceJob { const float* partial; int nparts, M, N, n_per; float* o[3]; };
 struct ReduceList { ReduceJob job[16]; int n; };
-// N % 4 == 0 and at most 65536 output quads: the job can go on a list
-bool reduce_deferrable(int M, int N);
+// N % 4 == 0, at most 65536 output quads and at most 8 MB of partials (a larger set is read back faster right after
+// it was written, while it is still in the last-level cache): the job can go on a list
+bool reduce_deferrable(int M, int N, int nparts);
 void reduce_push(ReduceList* l, const float* partial, int nparts, int M, int N, float* o0, float* o1, float* o2, int n_per);
 void launch_reduce_list(const ReduceList& l, hipStream_t st);
 // column sums of a [R, n] matrix (bias gradients), deterministic two-stage

@@ -917,11 +917,20 @@ __global__ __launch_bounds__(256) void reduce_list_kernel(ReduceList l) {
   if ((long)blockIdx.x * 64 >= n_out) return;   // block-uniform
   const long i = ((long)blockIdx.x * 16 + ql) * 4;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (i < n_out)
-    for (int z = zl; z < j.nparts; z += 16) {
+  if (i < n_out) {
+    int z = zl;
+    for (; z + 48 < j.nparts; z += 64) {   // four requests in flight; added in the same ascending order
+      float4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = *(const float4*)(j.partial + (z + 16 * u) * n_out + i);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+    }
+    for (; z < j.nparts; z += 16) {
       const float4 v = *(const float4*)(j.partial + z * n_out + i);
       s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
+  }
   red[zl][ql] = s;
   __syncthreads();
   if (zl != 0 || i >= n_out) return;
@@ -940,7 +949,9 @@ __global__ __launch_bounds__(256) void reduce_list_kernel(ReduceList l) {
   if (!o) return;
   o[at] = s.x; o[at + 1] = s.y; o[at + 2] = s.z; o[at + 3] = s.w;   // caller pointers: no alignment assumed
 }
-bool reduce_deferrable(int M, int N) { return N % 4 == 0 && (long)M * N <= 4L * 65536; }
+bool reduce_deferrable(int M, int N, int nparts) {
+  return N % 4 == 0 && (long)M * N <= 4L * 65536 && (long)M * N * nparts * 4 <= (8L << 20);
+}
 void reduce_push(ReduceList* l, const float* partial, int nparts, int M, int N, float* o0, float* o1, float* o2, int n_per) {
   ReduceJob& j = l->job[l->n++];
   j.partial = partial; j.nparts = nparts; j.M = M; j.N = N; j.n_per = n_per;
@@ -974,7 +985,7 @@ int launch_colsum_multi(const void* const* a, const long* lda, float* const* out
   else if (vec) hipLaunchKernelGGL((colsum_stage1_vec<float>), dim3(1, nblk, count), block, 0, st, q, R, n, partial);
   else if (a_bf16) hipLaunchKernelGGL((colsum_stage1<bf16_t>), grid, block, 0, st, q, R, n, partial);
   else hipLaunchKernelGGL((colsum_stage1<float>), grid, block, 0, st, q, R, n, partial);
-  if (defer && reduce_deferrable(1, n) && defer->n + count <= 16) {
+  if (defer && reduce_deferrable(1, n, nblk) && defer->n + count <= 16) {
     for (int i = 0; i < count; ++i)
       if (q.out[i]) reduce_push(defer, partial + (long)i * nblk * n, nblk, 1, n, q.out[i], nullptr, nullptr, 0);
     return IM_OK;

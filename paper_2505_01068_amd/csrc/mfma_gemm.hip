@@ -1271,7 +1271,15 @@ __global__ void mfma_splitk_reduce_kernel(const float* partial, int split_k, int
   const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (i >= n_out) return;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int z = 0; z < split_k; ++z) {
+  int z = 0;
+  for (; z + 3 < split_k; z += 4) {   // four requests in flight; added in the same ascending order
+    float4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = *(const float4*)(partial + (z + u) * n_out + i);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+  }
+  for (; z < split_k; ++z) {
     const float4 v = *(const float4*)(partial + z * n_out + i);
     s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
   }
@@ -1296,11 +1304,20 @@ __global__ __launch_bounds__(256) void mfma_splitk_reduce_par_kernel(const float
   const int ql = threadIdx.x & 15, zl = threadIdx.x >> 4;
   const long i = ((long)blockIdx.x * 16 + ql) * 4;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (i < n_out)
-    for (int z = zl; z < split_k; z += 16) {
+  if (i < n_out) {
+    int z = zl;
+    for (; z + 48 < split_k; z += 64) {   // four requests in flight; added in the same ascending order
+      float4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = *(const float4*)(partial + (z + 16 * u) * n_out + i);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+    }
+    for (; z < split_k; z += 16) {
       const float4 v = *(const float4*)(partial + z * n_out + i);
       s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
+  }
   red[zl][ql] = s;
   __syncthreads();
   if (zl != 0 || i >= n_out) return;

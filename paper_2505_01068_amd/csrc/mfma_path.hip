@@ -97,7 +97,7 @@ void mfma_wgrad(const void* A, long lda, const void* G, long ldg, float* o0, flo
   p.M = M; p.N = N; p.K = R;
   p.split_k = mfma_gemm_split(M, N, R); p.partial = partial;
   launch_mfma_gemm(p, st);
-  if (defer && reduce_deferrable(M, N) && defer->n < 16) reduce_push(defer, partial, p.split_k, M, N, o0, o1, o2, n_per);
+  if (defer && reduce_deferrable(M, N, p.split_k) && defer->n < 16) reduce_push(defer, partial, p.split_k, M, N, o0, o1, o2, n_per);
   else launch_splitk_reduce(partial, p.split_k, M, N, o0, o1, o2, n_per, st);
 }
 
@@ -228,7 +228,7 @@ int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const
     p.M = d; p.N = d; p.K = R;
     p.split_k = w.split_o; p.partial = partial_o;
     launch_mfma_gemm(p, st);
-    if (defer && reduce_deferrable(d, d) && defer->n < 16) reduce_push(defer, partial_o, w.split_o, d, d, (float*)dwo, nullptr, nullptr, 0);
+    if (defer && reduce_deferrable(d, d, w.split_o) && defer->n < 16) reduce_push(defer, partial_o, w.split_o, d, d, (float*)dwo, nullptr, nullptr, 0);
     else launch_splitk_reduce(partial_o, w.split_o, d, d, (float*)dwo, nullptr, nullptr, 0, st);
   }
 
@@ -243,7 +243,7 @@ int mfma_attention_bwd(const im_shape_t* s, const void* x, const void* wq, const
     p.M = d; p.N = 3 * d; p.K = R;
     p.split_k = w.split_w; p.partial = partial;
     launch_mfma_gemm(p, st);
-    if (defer && reduce_deferrable(d, 3 * d) && defer->n < 16)
+    if (defer && reduce_deferrable(d, 3 * d, w.split_w) && defer->n < 16)
       reduce_push(defer, partial, w.split_w, d, 3 * d, (float*)dwq, (float*)dwk, (float*)dwv, d);
     else launch_splitk_reduce(partial, w.split_w, d, 3 * d, (float*)dwq, (float*)dwk, (float*)dwv, d, st);
   }
