@@ -674,10 +674,11 @@ size_t gsit_layer_pair_ws(const im_shape_t* s) {
 // y1 = layer(x1; p1, mask1), in three launches (both QKV projections with their LayerNorms, both attention
 // kernels, both fused tails) instead of six, so that each launch fills the chip.  *done = false with nothing
 // enqueued when the shape or the parameters are not served (the caller then runs the layers one by one).
+// ldy: row stride of y0 and y1 in elements (0 = d_model; wider: the outputs are column blocks of one matrix).
 int gsit_layer_fwd_pair(const im_shape_t* s0, uint64_t mask1, int32_t d_ff, const void* x0, const void* x1,
                         const gsit_layer_params_t& p0, const gsit_layer_params_t& p1, float ln_eps,
                         const int32_t* valid_len, const uint8_t* key_pad, void* y0, void* y1, void* workspace,
-                        size_t workspace_bytes, hipStream_t st, bool* done) {
+                        size_t workspace_bytes, hipStream_t st, bool* done, long ldy) {
   *done = false;
   const size_t need = gsit_layer_pair_ws(s0);
   if (!need || !workspace || workspace_bytes < need) return IM_OK;
@@ -704,8 +705,8 @@ int gsit_layer_fwd_pair(const im_shape_t* s0, uint64_t mask1, int32_t d_ff, cons
   {
     ProfScope ps(PF_MISC, st);
     const size_t es = 2;
-    const MlpTailPairSide a = {x0, p0.ln2_g, p0.ln2_b, p0.w1, p0.b1, p0.w2, p0.b2, sv + L.o, p0.wo, p0.bo, y0};
-    const MlpTailPairSide b = {x1, p1.ln2_g, p1.ln2_b, p1.w1, p1.b1, p1.w2, p1.b2, sv + L.o + (size_t)R * d * es, p1.wo, p1.bo, y1};
+    const MlpTailPairSide a = {x0, p0.ln2_g, p0.ln2_b, p0.w1, p0.b1, p0.w2, p0.b2, sv + L.o, p0.wo, p0.bo, y0, ldy};
+    const MlpTailPairSide b = {x1, p1.ln2_g, p1.ln2_b, p1.w1, p1.b1, p1.w2, p1.b2, sv + L.o + (size_t)R * d * es, p1.wo, p1.bo, y1, ldy};
     launch_mlp_tail_pair(a, b, ln_eps, (int)R, (int)d, d_ff, st);
   }
   *done = true;

@@ -245,7 +245,7 @@ size_t gsit_layer_pair_ws(const im_shape_t* s);
 int gsit_layer_fwd_pair(const im_shape_t* s0, uint64_t mask1, int32_t d_ff, const void* x0, const void* x1,
                         const gsit_layer_params_t& p0, const gsit_layer_params_t& p1, float ln_eps,
                         const int32_t* valid_len, const uint8_t* key_pad, void* y0, void* y1, void* workspace,
-                        size_t workspace_bytes, hipStream_t st, bool* done);
+                        size_t workspace_bytes, hipStream_t st, bool* done, long ldy = 0);
 
 // Optional per-kernel-family timing (see im_profile_enable): records an event pair
 // around the launches issued while the scope is alive.

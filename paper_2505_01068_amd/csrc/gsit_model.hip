@@ -167,12 +167,21 @@ int gsit_model_fwd(const im_shape_t* shape, const gsit_model_t* model, const voi
   im_shape_t inter = *shape;
   inter.live_mask = model->mask_fwd;
   int l0 = 0;
+  // The last pair of layers writes its two outputs as the column blocks of the concatenated matrix (row stride 2d):
+  // no separate concatenation pass.
+  bool concatenated = false;
+  const size_t es = bf ? 2 : 4;
   for (; l0 < model->n_layers_inter; ++l0) {
     bool done = false;
+    const bool last = l0 + 1 == model->n_layers_inter;
+    void* y0 = last ? cat : F;
+    void* y1 = last ? (void*)((char*)cat + (size_t)d * es) : Bk;
     if ((rc = gsit_layer_fwd_pair(&inter, model->mask_bwd, model->d_ff_inter, l0 ? F : x, l0 ? Bk : x, model->fwd_layers[l0],
-                                  model->bwd_layers[l0], model->ln_eps, valid_len, key_pad, F, Bk, lws, lws_bytes, st, &done)))
+                                  model->bwd_layers[l0], model->ln_eps, valid_len, key_pad, y0, y1, lws, lws_bytes, st, &done,
+                                  last ? 2L * d : 0L)))
       return rc;
     if (!done) break;
+    concatenated = last;
   }
   if (l0 < model->n_layers_inter) {
     if ((rc = run_encoder(&inter, model->d_ff_inter, model->fwd_layers + l0, model->n_layers_inter - l0, model->ln_eps,
@@ -182,7 +191,8 @@ int gsit_model_fwd(const im_shape_t* shape, const gsit_model_t* model, const voi
                           l0 ? Bk : x, Bk, valid_len, key_pad, lws, lws_bytes, hip_stream))) return rc;
   }
   const int blocks = (int)((R * 2 * d + 255) / 256 < 4096 ? (R * 2 * d + 255) / 256 : 4096);
-  if (bf) hipLaunchKernelGGL(concat_features_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, (const uint16_t*)F, (const uint16_t*)Bk, (uint16_t*)cat, R, d);
+  if (concatenated) {}
+  else if (bf) hipLaunchKernelGGL(concat_features_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, (const uint16_t*)F, (const uint16_t*)Bk, (uint16_t*)cat, R, d);
   else hipLaunchKernelGGL(concat_features_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)F, (const float*)Bk, (float*)cat, R, d);
   if ((rc = run_encoder(&intra, model->d_ff_intra, model->intra_layers, model->n_layers_intra, model->ln_eps, cat, cat,
                         valid_len, key_pad, lws, lws_bytes, hip_stream))) return rc;

@@ -961,6 +961,7 @@ struct MlpTailArgs {
   const bf16_t* w1; const bf16_t* b1; const bf16_t* w2; const bf16_t* b2;
   bf16_t* y; int R, d_ff;
   const bf16_t* o; const bf16_t* wo; const bf16_t* bo;   // PROJ: h above is x, the residual of the projection
+  long ldy;                                              // row stride of y (d, or wider: y is a column block)
 };
 // ROWS x COLS bf16 tile as 16-byte chunks, chunk (tid + 256 u): row = chunk / (COLS / 8), so the COLS / 8 lanes that
 // hold a row are consecutive.  Rows are clamped to rmax.
@@ -1216,7 +1217,7 @@ __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
       const u32x2 rv = PROJ ? *(const u32x2*)(sH + row * LDD + n) : *(const u32x2*)(p.h + (long)m * D + n);
       const u32x2 pk = {pack_bf16(accf[nb][4 * i] + __uint_as_float(rv[0] << 16), accf[nb][4 * i + 1] + __uint_as_float(rv[0] & 0xffff0000u)),
                         pack_bf16(accf[nb][4 * i + 2] + __uint_as_float(rv[1] << 16), accf[nb][4 * i + 3] + __uint_as_float(rv[1] & 0xffff0000u))};
-      *(u32x2*)(p.y + (long)m * D + n) = pk;
+      *(u32x2*)(p.y + (long)m * p.ldy + n) = pk;
     }
 }
 // Registers: 168 at D = 64 (three workgroups per CU, as the LDS allows), 256 at D = 128 (two; left to itself the
@@ -1240,7 +1241,7 @@ void launch_mlp_tail(const void* h, const void* ln_g, const void* ln_b, float ln
                      const void* wo, const void* bo) {
   MlpTailArgs p = {(const bf16_t*)h, (const bf16_t*)ln_g, (const bf16_t*)ln_b, ln_eps, (const bf16_t*)w1, (const bf16_t*)b1,
                    (const bf16_t*)w2, (const bf16_t*)b2, (bf16_t*)y, R, d_ff, (const bf16_t*)o, (const bf16_t*)wo,
-                   (const bf16_t*)bo};
+                   (const bf16_t*)bo, (long)d};
   const dim3 grid((R + 63) / 64), block(256);
   if (d == 64) {
     if (o) hipLaunchKernelGGL((mlp_tail_kernel<64, true>), grid, block, 0, st, p);
@@ -1256,7 +1257,7 @@ void launch_mlp_tail_pair(const MlpTailPairSide& a, const MlpTailPairSide& b, fl
   auto mk = [&](const MlpTailPairSide& s) {
     return MlpTailArgs{(const bf16_t*)s.x, (const bf16_t*)s.ln_g, (const bf16_t*)s.ln_b, ln_eps, (const bf16_t*)s.w1,
                        (const bf16_t*)s.b1, (const bf16_t*)s.w2, (const bf16_t*)s.b2, (bf16_t*)s.y, R, d_ff,
-                       (const bf16_t*)s.o, (const bf16_t*)s.wo, (const bf16_t*)s.bo};
+                       (const bf16_t*)s.o, (const bf16_t*)s.wo, (const bf16_t*)s.bo, s.ldy ? s.ldy : (long)d};
   };
   const dim3 grid((R + 63) / 64, 2), block(256);
   if (d == 64) hipLaunchKernelGGL((mlp_tail_pair_kernel<64, true>), grid, block, 0, st, mk(a), mk(b));

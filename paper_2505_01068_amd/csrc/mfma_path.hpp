@@ -73,6 +73,7 @@ void launch_mlp_tail(const void* h, const void* ln_g, const void* ln_b, float ln
 struct MlpTailPairSide {
   const void *x, *ln_g, *ln_b, *w1, *b1, *w2, *b2, *o, *wo, *bo;
   void* y;
+  long ldy;   // row stride of y in elements; 0 = d
 };
 void launch_mlp_tail_pair(const MlpTailPairSide& a, const MlpTailPairSide& b, float ln_eps, int R, int d, int d_ff,
                           hipStream_t st);
