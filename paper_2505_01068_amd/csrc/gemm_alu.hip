@@ -863,11 +863,12 @@ __global__ __launch_bounds__(256) void colsum_stage1_vec(ColsumArgs q, int R, in
       uint4 v[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        const int rr = r + u * RG;
-        v[u] = rr < r1 ? *(const uint4*)(a + (long)rr * lda + cg * VW) : make_uint4(0u, 0u, 0u, 0u);
+        const int rr = min(r + u * RG, r1 - 1);   // every load is issued (no branch, no wait per row); rows past the
+        v[u] = *(const uint4*)(a + (long)rr * lda + cg * VW);   // block are read again and dropped below
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
+        if (r + u * RG >= r1) v[u] = make_uint4(0u, 0u, 0u, 0u);
         const unsigned w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
