@@ -15,6 +15,7 @@ namespace imattn {
 
 constexpr int RL_ROWS = 64;    // rows per tile == lanes
 constexpr int RL_CHUNK = 64;    // rows of the other operand staged in LDS at a time
+static_assert(RL_CHUNK == RL_ROWS, "a lane stages exactly one per-row value (key validity, row statistics) of a chunk");
 // Kernels are instantiated for the exact head dimension DH (register arrays and FMA loops have DH
 // entries: at dh = 5 a padded-to-8 loop would waste 3 of every 8 FMAs); LDS rows are padded to a
 // power of two for aligned broadcast reads.
@@ -133,12 +134,11 @@ __global__ __launch_bounds__(NW * RL_ROWS) void rowlane_fwd_kernel(Geo g, const 
     __syncthreads();
     if (has) {
       const long kbase = seg_row0(g, b, j);
+      // the lane's key-validity byte is requested before the chunk (RL_CHUNK == RL_ROWS: one key per lane): asked for
+      // after the chunk's LDS stores it was a round trip of its own
+      const unsigned char pad = key_pad ? key_pad[kbase + c0 + min(lane, n - 1)] : (unsigned char)0;
       stage_chunk<T, LP>(K, ld, V, ld, kbase + c0, n, hc, dh, 1.f, sKV[wave][0], sKV[wave][1], lane);
-      for (int c = lane; c < n4; c += RL_ROWS) {
-        bool ok = c < n;
-        if (ok && key_pad) ok = key_pad[kbase + c0 + c] == 0;
-        sBias[wave][c] = ok ? 0.f : IM_NEG_INF;
-      }
+      sBias[wave][lane] = (lane < n && pad == 0) ? 0.f : IM_NEG_INF;
     }
     __syncthreads();
     if (!has) continue;
@@ -253,12 +253,9 @@ __global__ __launch_bounds__(NW * RL_ROWS) void rowlane_dq_kernel(Geo g, const T
     __syncthreads();
     if (has) {
       const long kbase = seg_row0(g, b, j);
+      const unsigned char pad = key_pad ? key_pad[kbase + c0 + min(lane, n - 1)] : (unsigned char)0;   // before the chunk
       stage_chunk<T, LP>(K, ld, V, ld, kbase + c0, n, hc, dh, 1.f, sKV[wave][0], sKV[wave][1], lane);
-      for (int c = lane; c < n; c += RL_ROWS) {
-        bool ok = true;
-        if (key_pad) ok = key_pad[kbase + c0 + c] == 0;
-        sBias[wave][c] = ok ? 0.f : IM_NEG_INF;
-      }
+      sBias[wave][lane] = pad == 0 ? 0.f : IM_NEG_INF;
     }
     __syncthreads();
     if (!has) continue;
@@ -356,12 +353,12 @@ __global__ __launch_bounds__(NW * RL_ROWS) void rowlane_dkv_kernel(Geo g, const 
     if (has) {
       const long qbase = seg_row0(g, b, i);
       const long lbase = seg_stat0(g, b, h, i);
+      // the lane's row statistics are requested before the chunk (one row per lane), not after its LDS stores
+      const long at = lbase + r0 + min(lane, n - 1);
+      const float ls = lse2[at], dl = delta[at];
       stage_chunk<T, LP>(Q, ld, dO, ldo, qbase + r0, n, hc, dh, g.scale_log2e, sQG[wave][0], sQG[wave][1], lane);
-      for (int r = lane; r < n; r += RL_ROWS) {
-        const float ls = lse2[lbase + r0 + r];
-        sL[wave][r] = (ls == IM_NEG_INF) ? __builtin_inff() : ls;
-        sD[wave][r] = delta[lbase + r0 + r];
-      }
+      sL[wave][lane] = (ls == IM_NEG_INF) ? __builtin_inff() : ls;
+      sD[wave][lane] = dl;
     }
     __syncthreads();
     if (!has) continue;
