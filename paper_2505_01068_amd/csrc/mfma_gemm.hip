@@ -1138,8 +1138,13 @@ __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         acc2[nb][4 * i + j] = (p.b2 && (nb / NB) == wn) ? bf2f(p.b2[nb * 32 + 8 * i + 4 * hi + j]) : 0.f;
+  // the lane's LN(h) operand fragments (its row, all of D) stay in registers for every chunk
+  bf16x8 fa[D / 16];
+  __syncthreads();  // sA is complete
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s) fa[s] = frag_rows(sA, LDD, row, s * 16 + hi * 8);
   auto chunk = [&](int c, ChunkTile<D, 64>& ra, ChunkTile<64, D>& rb, u32x4 (&bi)[2]) {
-    __syncthreads();  // the previous chunk's W1 and W2 tiles have been read (first pass: sA is complete)
+    __syncthreads();  // the previous chunk's W1 and W2 tiles have been read
     ra.store(sW1, LDC, tid);
     rb.store(sW2, LDD, tid);
     f32x16 acc1;
@@ -1154,7 +1159,7 @@ __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
     if (c + 2 < nchunk) fetch(c + 2, ra, rb, bi);
 #pragma unroll
     for (int s = 0; s < D / 16; ++s)
-      acc1 = mfma32(lds_frag_tr_perm(sW1, LDC, s * 16, wn * 32, lane), frag_rows(sA, LDD, row, s * 16 + hi * 8), acc1);
+      acc1 = mfma32(lds_frag_tr_perm(sW1, LDC, s * 16, wn * 32, lane), fa[s], acc1);
     bf16x8 zb[2];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
