@@ -846,7 +846,9 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void mfma_dkv_kernel(Geo g, 
 //   forward, sub-head mode: 2 query blocks per wave (half the K/V tile traffic per score), 3 stages, 3 workgroups;
 //   dQ, head dim 64: 3 stages, 3 workgroups per CU, accumulators seeded with -lse and -delta (unseeded: 7 % slower;
 //     4 workgroups need spills);
-//   dK/dV: 1 key block per wave, 3 workgroups per CU.
+//   dQ, sub-head mode: 3 workgroups per CU as well (114 registers; 27 against 33 us with two at B = 32, 50 / 500 / 375
+//     rows, 8 heads of 8);
+//   dK/dV: 1 key block per wave, 3 workgroups per CU at head dim 64, 2 in sub-head mode (3 measured the same).
 constexpr int FWD_QB = 1, FWD_QB_SUB = 2, DQ_QB = 1, DKV_KB = 1;
 constexpr int FWD_NST = 2, FWD_WGS = 4, FWD_NW = 4;   // ring stages, workgroups per CU, waves per workgroup (head dim 64)
 constexpr int FWD_SUB_NST = 3, FWD_SUB_WGS = 3;       // the same in sub-head mode (4 waves)
@@ -916,8 +918,8 @@ void launch_mfma_bwd(const Geo& g, const bf16_t* qkv, long ld, const bf16_t* o, 
   { ProfScope ps(PF_ATTN_DQ, st);
     const dim3 grid(nq, g.H, g.B);
     if (g.dh == 64) hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 64, DQ_NST, DQ_WGS, true>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg);
-    else if (g.dh == 16) hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 16, 3, 2, true>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg);
-    else hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 8, 3, 2, true>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg); }
+    else if (g.dh == 16) hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 16, 3, 3, true>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg);
+    else hipLaunchKernelGGL((mfma_dq_kernel<DQ_QB, 8, 3, 3, true>), grid, dim3(256), 0, st, g, qkv, ld, o, d_o, ldo, lse2, valid_len, key_pad, delta, dqkv, ldg); }
   { ProfScope ps(PF_ATTN_DKV, st);
     const dim3 grid(nk, g.H, g.B);
     if (g.dh == 64) hipLaunchKernelGGL((mfma_dkv_kernel<DKV_KB, 64>), grid, dim3(256), 0, st, g, qkv, ld, d_o, ldo, lse2, delta, valid_len, key_pad, dqkv, ldg);
