@@ -277,6 +277,20 @@ __device__ __forceinline__ void mfma_gemm_tile(const MGemm& p, int bx, int by, i
   for (int mb = 0; mb < MB; ++mb) {
     const int m = m0 + wm * 32 * MB + mb * 32 + lo;
     if (m >= p.M) continue;
+    // the residual (or saved pre-activation) values of the lane's row: all eight requests before the first use --
+    // loaded where they are added, each was a memory round trip of its own
+    u32x2 rvs[2][4];
+    if constexpr (EPI) {
+      if (pres) {
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int n = n0 + wn * 64 + nb * 32 + 8 * i + 4 * hi;
+            rvs[nb][i] = *(const u32x2*)(pres + (long)m * p.ldc + (n < p.N ? n : 0));
+          }
+      }
+    }
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
@@ -299,7 +313,7 @@ __device__ __forceinline__ void mfma_gemm_tile(const MGemm& p, int bx, int by, i
             continue;
           }
           if (p.gelu == MGEMM_GELU_GRAD) {   // C = (A B) * GELU'(res)
-            const u32x2 rv = *(const u32x2*)(pres + (long)m * p.ldc + n);
+            const u32x2 rv = rvs[nb][i];
             v[0] *= gelu_grad_f(__uint_as_float(rv[0] << 16)); v[1] *= gelu_grad_f(__uint_as_float(rv[0] & 0xffff0000u));
             v[2] *= gelu_grad_f(__uint_as_float(rv[1] << 16)); v[3] *= gelu_grad_f(__uint_as_float(rv[1] & 0xffff0000u));
           } else {
@@ -308,7 +322,7 @@ __device__ __forceinline__ void mfma_gemm_tile(const MGemm& p, int bx, int by, i
               for (int j = 0; j < 4; ++j) v[j] = gelu_erf_f(v[j]);
             }
             if (pres) {
-              const u32x2 rv = *(const u32x2*)(pres + (long)m * p.ldc + n);
+              const u32x2 rv = rvs[nb][i];
               v[0] += __uint_as_float(rv[0] << 16); v[1] += __uint_as_float(rv[0] & 0xffff0000u);
               v[2] += __uint_as_float(rv[1] << 16); v[3] += __uint_as_float(rv[1] & 0xffff0000u);
             }
@@ -718,6 +732,18 @@ __global__ __launch_bounds__(NWV * 64) void mfma_gemm_dma_kernel(MGemm p) {
     for (int mq = 0; mq < 2; ++mq) {
       const int mb = half * 2 + mq;
       const int m = m0 + wm * 128 + mb * 32 + lo;
+      u32x2 rvs[NBN][4];   // the row's residual values, all requested before the first is added
+      if constexpr (EPI) {
+        if (p.res) {
+#pragma unroll
+          for (int nb = 0; nb < NBN; ++nb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const int n = n0 + wn * WCOLS + nb * 32 + 8 * i + 4 * hi;
+              rvs[nb][i] = *(const u32x2*)(p.res + (long)min(m, p.M - 1) * p.ldc + (n < p.N ? n : 0));
+            }
+        }
+      }
 #pragma unroll
       for (int nb = 0; nb < NBN; ++nb)
 #pragma unroll
@@ -734,7 +760,7 @@ __global__ __launch_bounds__(NWV * 64) void mfma_gemm_dma_kernel(MGemm p) {
               for (int j = 0; j < 4; ++j) v[j] = gelu_erf_f(v[j]);
             }
             if (p.res && (interior || (m < p.M && n < p.N))) {
-              const u32x2 rv = *(const u32x2*)(p.res + (long)m * p.ldc + n);
+              const u32x2 rv = rvs[nb][i];
               v[0] += __uint_as_float(rv[0] << 16); v[1] += __uint_as_float(rv[0] & 0xffff0000u);
               v[2] += __uint_as_float(rv[1] << 16); v[3] += __uint_as_float(rv[1] & 0xffff0000u);
             }
@@ -901,6 +927,18 @@ __global__ __launch_bounds__(TWAVES * 64) void mfma_gemm_dma12_kernel(MGemm p) {
 #pragma unroll
   for (int mb = 0; mb < MBW; ++mb) {
     const int m = m0 + wm * 96 + mb * 32 + lo;
+    u32x2 rvs[NBN][4];   // the row's residual values, all requested before the first is added
+    if constexpr (EPI) {
+      if (p.res) {
+#pragma unroll
+        for (int nb = 0; nb < NBN; ++nb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int n = n0 + wn * WCOLS + nb * 32 + 8 * i + 4 * hi;
+            rvs[nb][i] = *(const u32x2*)(p.res + (long)min(m, p.M - 1) * p.ldc + (n < p.N ? n : 0));
+          }
+      }
+    }
 #pragma unroll
     for (int nb = 0; nb < NBN; ++nb)
 #pragma unroll
@@ -917,7 +955,7 @@ __global__ __launch_bounds__(TWAVES * 64) void mfma_gemm_dma12_kernel(MGemm p) {
             for (int j = 0; j < 4; ++j) v[j] = gelu_erf_f(v[j]);
           }
           if (p.res && (interior || (m < p.M && n < p.N))) {
-            const u32x2 rv = *(const u32x2*)(p.res + (long)m * p.ldc + n);
+            const u32x2 rv = rvs[nb][i];
             v[0] += __uint_as_float(rv[0] << 16); v[1] += __uint_as_float(rv[0] & 0xffff0000u);
             v[2] += __uint_as_float(rv[1] << 16); v[3] += __uint_as_float(rv[1] & 0xffff0000u);
           }
@@ -956,6 +994,35 @@ __global__ __launch_bounds__(TWAVES * 64) void mfma_gemm_dma12_kernel(MGemm p) {
 // launches output projection, LayerNorm, first GEMM, second GEMM become one.  Four waves in a 2 x 2 grid: each
 // owns 32 x 32 of a z chunk and 32 x D/2 of the output; the same transposed-product tiles as
 // mfma_gemm_kernel (a lane owns an output row; registers 4i..4i+3 are columns 8i + 4hi + 0..3 of a 32-column block).
+// NQ groups of four consecutive bf16 of a bias vector (element offsets off[q], multiples of 4) as fp32; zeros
+// for a NULL vector.  All loads are issued together: written as `b ? bf2f(b[k]) : 0.f` per element, every element
+// became a conditional 2-byte load with a wait of its own (96 of them in front of the layer tail at width 128).
+template <int NQ>
+__device__ __forceinline__ void bias_quads(const bf16_t* b, const int (&off)[NQ], float (&out)[NQ][4]) {
+  if (!b) {
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) out[q][0] = out[q][1] = out[q][2] = out[q][3] = 0.f;
+    return;
+  }
+  u32x2 raw[NQ];
+  if ((reinterpret_cast<uintptr_t>(b) & 7) == 0) {
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) raw[q] = *(const u32x2*)(b + off[q]);
+  } else {
+    unsigned short h[NQ][4];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) h[q][j] = b[off[q] + j];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) raw[q] = u32x2{(unsigned)h[q][0] | ((unsigned)h[q][1] << 16), (unsigned)h[q][2] | ((unsigned)h[q][3] << 16)};
+  }
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) {
+    out[q][0] = __uint_as_float(raw[q][0] << 16); out[q][1] = __uint_as_float(raw[q][0] & 0xffff0000u);
+    out[q][2] = __uint_as_float(raw[q][1] << 16); out[q][3] = __uint_as_float(raw[q][1] & 0xffff0000u);
+  }
+}
 struct MlpTailArgs {
   const bf16_t* h; const bf16_t* ln_g; const bf16_t* ln_b; float ln_eps;
   const bf16_t* w1; const bf16_t* b1; const bf16_t* w2; const bf16_t* b2;
@@ -1048,12 +1115,21 @@ __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
   if constexpr (PROJ) {
     // h = x + O Wo + bo, the contraction in chunks of 64: O chunk -> sZ, Wo chunk -> sW2, h (bf16) -> sH
     f32x16 acc[NB];
+    {
+      int off[NB * 4];
+      float bq[NB * 4][4];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+      for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i) off[nb * 4 + i] = wn * (D / 2) + nb * 32 + 8 * i + 4 * hi;
+      bias_quads<NB * 4>(p.bo, off, bq);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[nb][4 * i + j] = p.bo ? bf2f(p.bo[wn * (D / 2) + nb * 32 + 8 * i + 4 * hi + j]) : 0.f;
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[nb][4 * i + j] = bq[nb * 4 + i][j];
+    }
     // every chunk of O and Wo (one or two) and the residual rows are requested at once, before the first is used
     constexpr int NKC = D / 64;
     ChunkTile<64, 64> to[NKC];
@@ -1131,13 +1207,21 @@ __device__ __forceinline__ void mlp_tail_tile(const MlpTailArgs& p) {
   // the second without leaving registers, and the two waves of a row block add their halves once, at the end.
   // The wave that writes a column block (blocks wn * NB ..) starts it at b2.
   f32x16 acc2[2 * NB];
+  {
+    int off[NB * 4];
+    float bq[NB * 4][4];
 #pragma unroll
-  for (int nb = 0; nb < 2 * NB; ++nb)
+    for (int nbi = 0; nbi < NB; ++nbi)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < 4; ++i) off[nbi * 4 + i] = (wn * NB + nbi) * 32 + 8 * i + 4 * hi;
+    bias_quads<NB * 4>(p.b2, off, bq);
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc2[nb][4 * i + j] = (p.b2 && (nb / NB) == wn) ? bf2f(p.b2[nb * 32 + 8 * i + 4 * hi + j]) : 0.f;
+    for (int nb = 0; nb < 2 * NB; ++nb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc2[nb][4 * i + j] = (nb / NB) == wn ? bq[(nb % NB) * 4 + i][j] : 0.f;
+  }
   // the lane's LN(h) operand fragments (its row, all of D) stay in registers for every chunk
   bf16x8 fa[D / 16];
   __syncthreads();  // sA is complete
