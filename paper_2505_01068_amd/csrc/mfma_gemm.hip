@@ -162,6 +162,49 @@ __device__ __forceinline__ void bias4(const MGemm& p, const bf16_t* const (&bias
   }
 }
 
+// The same for NQ column groups at once: every load is issued before the first value is used (one call of bias4
+// per group is a conditional load and a wait per group, eight memory round trips in front of a tile's main loop).
+template <int NQ>
+__device__ __forceinline__ void bias4_many(const MGemm& p, const bf16_t* const (&bias)[3], const int (&n)[NQ],
+                                           float (&out)[NQ][4]) {
+  const bf16_t* any = bias[0] ? bias[0] : bias[1] ? bias[1] : bias[2];
+  if (p.n_per <= 0 || !any) {
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) out[q][0] = out[q][1] = out[q][2] = out[q][3] = 0.f;
+    return;
+  }
+  const bool al = ((reinterpret_cast<uintptr_t>(bias[0]) | reinterpret_cast<uintptr_t>(bias[1]) |
+                    reinterpret_cast<uintptr_t>(bias[2])) & 7) == 0;
+  const bf16_t* src[NQ];
+  bool have[NQ];
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) {
+    const int nn = n[q] < p.N ? n[q] : 0;
+    const int sel = (nn >= p.n_per) + (nn >= 2 * p.n_per);
+    const bf16_t* bp = sel == 0 ? bias[0] : sel == 1 ? bias[1] : bias[2];
+    have[q] = bp != nullptr && n[q] < p.N;
+    src[q] = (bp ? bp : any) + (nn - sel * p.n_per);   // every bias vector has n_per elements: a valid address either way
+  }
+  u32x2 raw[NQ];
+  if (al) {
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) raw[q] = *(const u32x2*)src[q];
+  } else {
+    unsigned short h[NQ][4];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) h[q][j] = src[q][j];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) raw[q] = u32x2{(unsigned)h[q][0] | ((unsigned)h[q][1] << 16), (unsigned)h[q][2] | ((unsigned)h[q][3] << 16)};
+  }
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) {
+    out[q][0] = have[q] ? __uint_as_float(raw[q][0] << 16) : 0.f; out[q][1] = have[q] ? __uint_as_float(raw[q][0] & 0xffff0000u) : 0.f;
+    out[q][2] = have[q] ? __uint_as_float(raw[q][1] << 16) : 0.f; out[q][3] = have[q] ? __uint_as_float(raw[q][1] & 0xffff0000u) : 0.f;
+  }
+}
+
 // TM = rows of the tile: 128, or 64 (m-major A only; each wave then owns 32 x 64) for shapes whose 128-row
 // tiles would not fill the chip -- with about one workgroup per CU nothing overlaps the chain load ->
 // LDS -> MFMA -> epilogue loads -> store of a workgroup, and twice as many half-size workgroups finish sooner.
@@ -191,17 +234,6 @@ __device__ __forceinline__ void mfma_gemm_tile(const MGemm& p, int bx, int by, i
   // n = 8i + 4hi + 0..3 of the block.  The accumulators start at the bias of their column (split-K launches
   // carry no bias), so the epilogue has nothing to add.
   f32x16 acc[2][MB];
-#pragma unroll
-  for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float bv[4] = {0.f, 0.f, 0.f, 0.f};
-      if (!p.partial) bias4(p, pbias, n0 + wn * 64 + nb * 32 + 8 * i + 4 * hi, bv);
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) acc[nb][mb][4 * i + jj] = bv[jj];
-    }
 
   const bf16_t* amat[3] = {pA, pA, pA};
   const bf16_t* bmat[3] = {zoff(p.B[0], p.z_b[0]), zoff(p.B[1], p.z_b[1]), zoff(p.B[2], p.z_b[2])};
@@ -228,6 +260,23 @@ __device__ __forceinline__ void mfma_gemm_tile(const MGemm& p, int bx, int by, i
     }
   };
   if (it_begin < it_end) prefetch(it_begin);
+  {   // the bias values are requested behind the first tile, all eight groups at once
+    int nq[8];
+    float bq[8][4];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) nq[nb * 4 + i] = p.partial ? p.N : n0 + wn * 64 + nb * 32 + 8 * i + 4 * hi;
+    bias4_many<8>(p, pbias, nq, bq);
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) acc[nb][mb][4 * i + jj] = bq[nb * 4 + i][jj];
+  }
   for (int it = it_begin; it < it_end; ++it) {
     __syncthreads();
     if constexpr (AKM) store_km(ta, sA, tid); else store_mm(ta, sA, tid);
@@ -851,16 +900,19 @@ __global__ __launch_bounds__(TWAVES * 64) void mfma_gemm_dma12_kernel(MGemm p) {
   // [n block][m block]; registers 4i..4i+3 are columns n = 8i + 4hi + 0..3 of the block; they start at the bias
   f32x16 acc[NBN][MBW];
 #pragma unroll
-  for (int nb = 0; nb < NBN; ++nb)
+  for (int nb = 0; nb < NBN; ++nb) {   // one column block at a time (register budget of three waves per SIMD)
+    int nq[4];
+    float bq[4][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float bv[4] = {0.f, 0.f, 0.f, 0.f};
-      bias4(p, p.bias, n0 + wn * WCOLS + nb * 32 + 8 * i + 4 * hi, bv);
+    for (int i = 0; i < 4; ++i) nq[i] = n0 + wn * WCOLS + nb * 32 + 8 * i + 4 * hi;
+    bias4_many<4>(p, p.bias, nq, bq);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int mb = 0; mb < MBW; ++mb)
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) acc[nb][mb][4 * i + jj] = bv[jj];
-    }
+        for (int jj = 0; jj < 4; ++jj) acc[nb][mb][4 * i + jj] = bq[i][jj];
+  }
 
   // ---- LDS byte offsets of this lane's fragments inside a stage ----
   int offA[2][MBW], offB[2][NBN], offB2[2][NBN];
@@ -927,20 +979,18 @@ __global__ __launch_bounds__(TWAVES * 64) void mfma_gemm_dma12_kernel(MGemm p) {
 #pragma unroll
   for (int mb = 0; mb < MBW; ++mb) {
     const int m = m0 + wm * 96 + mb * 32 + lo;
-    u32x2 rvs[NBN][4];   // the row's residual values, all requested before the first is added
-    if constexpr (EPI) {
-      if (p.res) {
 #pragma unroll
-        for (int nb = 0; nb < NBN; ++nb)
+    for (int nb = 0; nb < NBN; ++nb) {
+      u32x2 rvs[4];   // the row's residual values of this column block, requested together (168 registers: not all eight)
+      if constexpr (EPI) {
+        if (p.res) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const int n = n0 + wn * WCOLS + nb * 32 + 8 * i + 4 * hi;
-            rvs[nb][i] = *(const u32x2*)(p.res + (long)min(m, p.M - 1) * p.ldc + (n < p.N ? n : 0));
+            rvs[i] = *(const u32x2*)(p.res + (long)min(m, p.M - 1) * p.ldc + (n < p.N ? n : 0));
           }
+        }
       }
-    }
-#pragma unroll
-    for (int nb = 0; nb < NBN; ++nb)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int nl = nb * 32 + 8 * i + 4 * hi;
@@ -955,7 +1005,7 @@ __global__ __launch_bounds__(TWAVES * 64) void mfma_gemm_dma12_kernel(MGemm p) {
             for (int j = 0; j < 4; ++j) v[j] = gelu_erf_f(v[j]);
           }
           if (p.res && (interior || (m < p.M && n < p.N))) {
-            const u32x2 rv = rvs[nb][i];
+            const u32x2 rv = rvs[i];
             v[0] += __uint_as_float(rv[0] << 16); v[1] += __uint_as_float(rv[0] & 0xffff0000u);
             v[2] += __uint_as_float(rv[1] << 16); v[3] += __uint_as_float(rv[1] & 0xffff0000u);
           }
@@ -963,6 +1013,7 @@ __global__ __launch_bounds__(TWAVES * 64) void mfma_gemm_dma12_kernel(MGemm p) {
         const u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
         *(u32x2*)(stg + lo * EP_LD + nl) = pk;
       }
+    }
     // 32 rows x 8 chunks of 16 bytes; lane -> (row = 8 t + lane / 8, chunk = lane % 8).  The staging area is
     // private to the wave and its LDS instructions complete in order: no barrier between the passes.
     const int row0 = lane >> 3, ch = lane & 7;
