@@ -463,16 +463,23 @@ __global__ __launch_bounds__(256) void qkv_rows_kernel(QkvRows p) {
       }
   }
   if (tid < D) {
-    if (ln_g) {
-      sG[tid] = __uint_as_float((unsigned)ln_g[tid] << 16);
-      sBt[tid] = __uint_as_float((unsigned)ln_b[tid] << 16);
-    }
+    // the five per-column vectors: every load issued (a NULL vector reads the first weight instead, which has more
+    // than D elements, and counts as zero) before the first value goes to LDS
+    const bf16_t* const safe = z ? p.w[1][0] : p.w[0][0];
+    const bf16_t* src[5];
+    src[0] = ln_g; src[1] = ln_b;
 #pragma unroll
-    for (int part = 0; part < 3; ++part) {
-      const bf16_t* const bias = z ? p.bias[1][part] : p.bias[0][part];
-      const float bv = bias ? __uint_as_float((unsigned)bias[tid] << 16) : 0.f;
-      sBias[part * D + tid] = part == 0 ? bv * p.qscale : bv;
-    }
+    for (int part = 0; part < 3; ++part) src[2 + part] = z ? p.bias[1][part] : p.bias[0][part];
+    float v[5];
+#pragma unroll
+    for (int u = 0; u < 5; ++u) v[u] = __uint_as_float((unsigned)(src[u] ? src[u] : safe)[tid] << 16);
+#pragma unroll
+    for (int u = 0; u < 5; ++u) v[u] = src[u] ? v[u] : 0.f;
+    sG[tid] = v[0];
+    sBt[tid] = v[1];
+    sBias[tid] = v[2] * p.qscale;
+    sBias[D + tid] = v[3];
+    sBias[2 * D + tid] = v[4];
   }
   __syncthreads();
 
