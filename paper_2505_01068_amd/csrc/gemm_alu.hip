@@ -2,6 +2,7 @@
 // multimodal-sentiment shapes (d = 32..64: the whole weight fits in a few LDS
 // tiles and the work is bandwidth / launch bound, not MFMA bound) and as the
 // fp32 path of the library.  Also: deterministic column sums and LayerNorm.
+#include <type_traits>
 #include "common.hpp"
 
 namespace imattn {
@@ -564,6 +565,7 @@ struct WgradProblem {
   float* partial;
   float *o0, *o1, *o2;   // outputs of the reduction (see wgrad_mfma_reduce_kernel)
   int n_per;
+  int n_off;             // column of the whole gradient that column 0 of this problem is (a gradient split by columns)
 };
 template <int MB, int NB>
 __device__ __forceinline__ void wgrad_mfma_body(const float* __restrict__ A, long lda, const float* __restrict__ G, long ldg,
@@ -571,7 +573,8 @@ __device__ __forceinline__ void wgrad_mfma_body(const float* __restrict__ A, lon
                                                 float* red_base) {
   constexpr int NBLK = MB * NB;
   float(*red)[NBLK * 16 * 64] = (float(*)[NBLK * 16 * 64])red_base;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, c = lane & 31, h = lane >> 5;
+  const int lane = threadIdx.x & 63, c = lane & 31, h = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: the row range of the wave is wave-uniform
   const int rpw = rows_per_wg >> 2;   // a multiple of 16
   const long row0 = (long)blockIdx.x * rows_per_wg + (long)w * rpw;
   f32x16s acc[MB][NB];
@@ -590,25 +593,45 @@ __device__ __forceinline__ void wgrad_mfma_body(const float* __restrict__ A, lon
   // Eight rows (four contraction steps) per group; the next group's 4 (MB + NB) loads are in flight while the
   // current group is multiplied.  rpw is a multiple of 16: two groups per trip, in two fixed register sets.
   float a0[4][MB], g0[4][NB], a1[4][MB], g1[4][NB];
+  // A pair of rows per contraction step: the pair's address is wave-uniform (scalar registers), the lane adds its
+  // row of the pair and its column as one 32-bit offset that never changes.
+  int la[MB], lg[NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i) la[i] = h * (int)lda + ca[i];
+#pragma unroll
+  for (int j = 0; j < NB; ++j) lg[j] = h * (int)ldg + cg[j];
   auto load = [&](int r, float (&a)[4][MB], float (&g)[4][NB]) {
-    const float* pa = A + (row0 + r + h) * lda;
-    const float* pg = G + (row0 + r + h) * ldg;
     if (full) {
+      const float* pa = A + (row0 + r) * lda;
+      const float* pg = G + (row0 + r) * ldg;
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
 #pragma unroll
-        for (int i = 0; i < MB; ++i) a[u][i] = pa[2 * u * lda + ca[i]];
+        for (int i = 0; i < MB; ++i) a[u][i] = pa[2 * u * lda + la[i]];
 #pragma unroll
-        for (int j = 0; j < NB; ++j) g[u][j] = pg[2 * u * ldg + cg[j]];
+        for (int j = 0; j < NB; ++j) g[u][j] = pg[2 * u * ldg + lg[j]];
       }
     } else {
+      // the last rows of the matrix: every load is issued, at an address inside the matrix, and rows past the end
+      // are replaced by zeros afterwards
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const bool ok = row0 + r + 2 * u + h < R;
+        const long row = row0 + r + 2 * u;
+        const long rc = row < R ? row : (long)R - 1;
+        const bool pair = row + 1 < R;   // wave-uniform: the second row of the pair exists
+        const bool ok = row + h < R;
+        const float* pa = A + rc * lda;
+        const float* pg = G + rc * ldg;
 #pragma unroll
-        for (int i = 0; i < MB; ++i) a[u][i] = ok ? pa[2 * u * lda + ca[i]] : 0.f;
+        for (int i = 0; i < MB; ++i) {
+          const float v = pa[pair ? la[i] : ca[i]];
+          a[u][i] = ok ? v : 0.f;
+        }
 #pragma unroll
-        for (int j = 0; j < NB; ++j) g[u][j] = ok ? pg[2 * u * ldg + cg[j]] : 0.f;
+        for (int j = 0; j < NB; ++j) {
+          const float v = pg[pair ? lg[j] : cg[j]];
+          g[u][j] = ok ? v : 0.f;
+        }
       }
     }
   };
@@ -674,11 +697,92 @@ __global__ __launch_bounds__(256) void wgrad_mfma_f32_pair_kernel(WgradProblem p
   else wgrad_mfma_body<MB1, NB1>(p1.A, p1.lda, p1.G, p1.ldg, R, p1.M, p1.N, rows_per_wg, p1.partial, red);
 }
 
+// Three problems of 2 x 2 blocks over the same rows (blockIdx.y picks the problem).  For 32 < d <= 42 the wide
+// gradient [dWq | dWk | dWv] is split at column 64 into two such problems beside dWo.  Here a wave owns one BLOCK
+// and all rows of the workgroup instead of all blocks and a quarter of the rows: 16 accumulator registers, no sum
+// across the waves at the end, and room for the loads of three groups of eight rows in flight behind the group being
+// multiplied at several workgroups per CU.  The partial result has the layout of wgrad_mfma_body.
+__global__ __launch_bounds__(256) void wgrad_mfma_f32_tri_kernel(WgradProblem p0, WgradProblem p1, WgradProblem p2, int R,
+                                                                 int rows_per_wg) {
+  const WgradProblem& p = blockIdx.y == 0 ? p0 : blockIdx.y == 1 ? p1 : p2;
+  const float* __restrict__ A = p.A;
+  const float* __restrict__ G = p.G;
+  const long lda = p.lda, ldg = p.ldg;
+  const int lane = threadIdx.x & 63, c = lane & 31, h = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int bi = w >> 1, bj = w & 1;
+  const long row0 = (long)blockIdx.x * rows_per_wg;   // rows_per_wg is a multiple of 32
+  const int ca = min(bi * 32 + c, p.M - 1), cg = min(bj * 32 + c, p.N - 1);
+  const int la = h * (int)lda + ca, lg = h * (int)ldg + cg;
+  const bool full = row0 + rows_per_wg <= R;   // uniform: only the last rows of the matrix need the row test
+  f32x16s acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  float a[4][4], g[4][4];   // [register set][contraction step of the group]
+  auto multiply = [&](const float (&av)[4], const float (&gv)[4]) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], gv[u], acc, 0, 0, 0);
+  };
+  // The whole loop exists twice, with and without the row test, and its last trip is peeled: no branch between a
+  // group's loads and its use, so the waits count exactly the loads requested after it.
+  auto run = [&](auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    auto load = [&](int r, float (&av)[4], float (&gv)[4]) {
+      if constexpr (FULL) {
+        const float* pa = A + (row0 + r) * lda;
+        const float* pg = G + (row0 + r) * ldg;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          av[u] = pa[2 * u * lda + la];
+          gv[u] = pg[2 * u * ldg + lg];
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {   // every load is issued, inside the matrix; rows past the end become zeros
+          const long row = row0 + r + 2 * u;
+          const long rc = row < R ? row : (long)R - 1;
+          const bool pair = row + 1 < R, ok = row + h < R;
+          const float va = A[rc * lda + (pair ? la : ca)];
+          const float vg = G[rc * ldg + (pair ? lg : cg)];
+          av[u] = ok ? va : 0.f;
+          gv[u] = ok ? vg : 0.f;
+        }
+      }
+    };
+    load(0, a[0], g[0]);
+    load(8, a[1], g[1]);
+    load(16, a[2], g[2]);
+    int r = 0;
+    for (; r + 32 < rows_per_wg; r += 32) {
+      load(r + 24, a[3], g[3]);
+      multiply(a[0], g[0]);
+      load(r + 32, a[0], g[0]);
+      multiply(a[1], g[1]);
+      load(r + 40, a[1], g[1]);
+      multiply(a[2], g[2]);
+      load(r + 48, a[2], g[2]);
+      multiply(a[3], g[3]);
+    }
+    load(r + 24, a[3], g[3]);
+    multiply(a[0], g[0]);
+    multiply(a[1], g[1]);
+    multiply(a[2], g[2]);
+    multiply(a[3], g[3]);
+  };
+  if (full) run(std::true_type{});
+  else run(std::false_type{});
+  float* dst = p.partial + (long)blockIdx.x * (4 * 16 * 64);
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    *(float4*)(dst + (((bi * 2 + bj) * 4 + q) * 64 + lane) * 4) =
+        make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+}
+
 // out[m, n] = sum_z partial[z] (accumulator order, see above), z ascending in 16 interleaved groups that are then
 // added in a fixed order; column block s of n_per columns goes to o<s> (NULL = dropped) when n_per > 0.
-__global__ __launch_bounds__(256) void wgrad_mfma_reduce_kernel(WgradProblem p0, WgradProblem p1, int nz) {
+__global__ __launch_bounds__(256) void wgrad_mfma_reduce_kernel(WgradProblem p0, WgradProblem p1, WgradProblem p2, int nz) {
   __shared__ float red[16][16];
-  const WgradProblem& p = blockIdx.y == 0 ? p0 : p1;
+  const WgradProblem& p = blockIdx.y == 0 ? p0 : blockIdx.y == 1 ? p1 : p2;
   const float* __restrict__ partial = p.partial;
   const int M = p.M, N = p.N, NB = (N + 31) / 32, nblk = ((M + 31) / 32) * NB, n_per = p.n_per;
   const int o = threadIdx.x & 15, g = threadIdx.x >> 4;
@@ -708,8 +812,9 @@ __global__ __launch_bounds__(256) void wgrad_mfma_reduce_kernel(WgradProblem p0,
 #pragma unroll
     for (int k = 0; k < 16; ++k) v += red[k][o];
     if (n_per > 0) {
-      float* dst = (n / n_per == 0) ? p.o0 : (n / n_per == 1) ? p.o1 : p.o2;
-      if (dst) dst[(long)m * n_per + n % n_per] = v;
+      const int gn = n + p.n_off;
+      float* dst = (gn / n_per == 0) ? p.o0 : (gn / n_per == 1) ? p.o1 : p.o2;
+      if (dst) dst[(long)m * n_per + gn % n_per] = v;
     } else {
       p.o0[i] = v;
     }
@@ -728,6 +833,33 @@ size_t wgrad_mfma_partial_bytes(int M, int N, int R) {
   const int rows = wgrad_mfma_rows_per_wg(R);
   return (size_t)((R + rows - 1) / rows) * ((M + 31) / 32) * ((N + 31) / 32) * 16 * 64 * sizeof(float);
 }
+// Up to two gradients with 33..64 rows through wgrad_mfma_f32_tri_kernel: `a` (at most 128 columns; more than 64
+// only with column-block outputs) becomes one or two problems of at most 64 columns, `b` (optional, at most 64
+// columns) one more.  The partial results lie one problem after the other from `partial` on.  A gradient's bits do
+// not depend on what else the launch computes.
+static void launch_wgrad_mfma_f32_tri(const WgradProblem* a, const WgradProblem* b, int R, float* partial, hipStream_t st) {
+  // rows per workgroup: a multiple of 32, those of the layout that the workspace is sized for
+  const int rows3 = (wgrad_mfma_rows_per_wg(R) + 31) / 32 * 32;
+  const int blocks3 = (R + rows3 - 1) / rows3;
+  const long pstride = (long)blocks3 * 4 * 16 * 64;
+  WgradProblem ps[3];
+  int n = 0;
+  auto push = [&](const WgradProblem& src, int col0, int ncols) {
+    ps[n] = src;
+    ps[n].G = src.G + col0;
+    ps[n].N = ncols;
+    ps[n].n_off = col0;
+    ps[n].partial = partial + n * pstride;
+    ++n;
+  };
+  if (a->N > 64) { push(*a, 0, 64); push(*a, 64, a->N - 64); }
+  else push(*a, 0, a->N);
+  if (b) push(*b, 0, b->N);
+  for (int k = n; k < 3; ++k) ps[k] = ps[0];
+  hipLaunchKernelGGL(wgrad_mfma_f32_tri_kernel, dim3(blocks3, n), dim3(256), 0, st, ps[0], ps[1], ps[2], R, rows3);
+  hipLaunchKernelGGL(wgrad_mfma_reduce_kernel, dim3((unsigned)(((long)a->M * 64 + 15) / 16), n), dim3(256), 0, st, ps[0],
+                     ps[1], ps[2], blocks3);
+}
 // C[M, N] = A[R, M]^T G[R, N] into o0 (n_per == 0) or column blocks of n_per columns into o0 | o1 | o2
 void launch_wgrad_mfma_f32(const float* A, long lda, const float* G, long ldg, int R, int M, int N, float* partial,
                            float* o0, float* o1, float* o2, int n_per, hipStream_t st) {
@@ -735,6 +867,10 @@ void launch_wgrad_mfma_f32(const float* A, long lda, const float* G, long ldg, i
   const int blocks = (R + rows - 1) / rows;
   const int MB = (M + 31) / 32, NB = (N + 31) / 32;
   const WgradProblem p{A, lda, G, ldg, M, N, partial, o0, o1, o2, n_per};
+  if (MB == 2 && (N <= 64 || n_per > 0)) {
+    launch_wgrad_mfma_f32_tri(&p, nullptr, R, partial, st);
+    return;
+  }
 #define WM_LAUNCH(MBV, NBV) hipLaunchKernelGGL((wgrad_mfma_f32_kernel<MBV, NBV>), dim3(blocks), dim3(256), 0, st, p, R, rows)
   if (MB == 1) {
     if (NB == 1) WM_LAUNCH(1, 1); else if (NB == 2) WM_LAUNCH(1, 2); else if (NB == 3) WM_LAUNCH(1, 3); else WM_LAUNCH(1, 4);
@@ -743,7 +879,7 @@ void launch_wgrad_mfma_f32(const float* A, long lda, const float* G, long ldg, i
   }
 #undef WM_LAUNCH
   const long n_out = (long)M * N;
-  hipLaunchKernelGGL(wgrad_mfma_reduce_kernel, dim3((unsigned)((n_out + 15) / 16), 1), dim3(256), 0, st, p, p, blocks);
+  hipLaunchKernelGGL(wgrad_mfma_reduce_kernel, dim3((unsigned)((n_out + 15) / 16), 1), dim3(256), 0, st, p, p, p, blocks);
 }
 // The two weight gradients of an attention block in one pair of launches:
 //   [dWq | dWk | dWv] = X^T [dQ | dK | dV]  (d x 3d, column blocks of d columns into q0 | q1 | q2, NULL = dropped)
@@ -751,19 +887,24 @@ void launch_wgrad_mfma_f32(const float* A, long lda, const float* G, long ldg, i
 // partial: wgrad_mfma_partial_bytes(d, 3 d, R) + wgrad_mfma_partial_bytes(d, d, R) bytes.
 void launch_wgrad_mfma_f32_attn(const float* X, const float* dQKV, const float* O, const float* dY, int R, int d,
                                 float* partial, float* q0, float* q1, float* q2, float* dwo, hipStream_t st) {
+  const int MB = (d + 31) / 32, NB0 = (3 * d + 31) / 32;
+  if (MB == 2) {
+    const WgradProblem wide{X, d, dQKV, 3L * d, d, 3 * d, partial, q0, q1, q2, d, 0};
+    const WgradProblem wo{O, d, dY, d, d, d, nullptr, dwo, nullptr, nullptr, 0, 0};
+    launch_wgrad_mfma_f32_tri(&wide, &wo, R, partial, st);
+    return;
+  }
   const int rows = wgrad_mfma_rows_per_wg(R);
   const int blocks = (R + rows - 1) / rows;
   float* partial1 = partial + wgrad_mfma_partial_bytes(d, 3 * d, R) / sizeof(float);
   const WgradProblem p0{X, d, dQKV, 3L * d, d, 3 * d, partial, q0, q1, q2, d};
   const WgradProblem p1{O, d, dY, d, d, d, partial1, dwo, nullptr, nullptr, 0};
-  const int MB = (d + 31) / 32, NB0 = (3 * d + 31) / 32;
   const dim3 grid(blocks, 2), block(256);
-  if (MB == 2) hipLaunchKernelGGL((wgrad_mfma_f32_pair_kernel<2, 4, 2, 2>), grid, block, 0, st, p0, p1, R, rows);
-  else if (NB0 == 3) hipLaunchKernelGGL((wgrad_mfma_f32_pair_kernel<1, 3, 1, 1>), grid, block, 0, st, p0, p1, R, rows);
+  if (NB0 == 3) hipLaunchKernelGGL((wgrad_mfma_f32_pair_kernel<1, 3, 1, 1>), grid, block, 0, st, p0, p1, R, rows);
   else if (NB0 == 2) hipLaunchKernelGGL((wgrad_mfma_f32_pair_kernel<1, 2, 1, 1>), grid, block, 0, st, p0, p1, R, rows);
   else hipLaunchKernelGGL((wgrad_mfma_f32_pair_kernel<1, 1, 1, 1>), grid, block, 0, st, p0, p1, R, rows);
   const long n_out = (long)d * 3 * d;
-  hipLaunchKernelGGL(wgrad_mfma_reduce_kernel, dim3((unsigned)((n_out + 15) / 16), 2), dim3(256), 0, st, p0, p1, blocks);
+  hipLaunchKernelGGL(wgrad_mfma_reduce_kernel, dim3((unsigned)((n_out + 15) / 16), 2), dim3(256), 0, st, p0, p1, p1, blocks);
 }
 
 bool wgrad_small_ok(int M, int N, int n_per) {
