@@ -780,43 +780,59 @@ __global__ __launch_bounds__(256) void wgrad_mfma_f32_tri_kernel(WgradProblem p0
 
 // out[m, n] = sum_z partial[z] (accumulator order, see above), z ascending in 16 interleaved groups that are then
 // added in a fixed order; column block s of n_per columns goes to o<s> (NULL = dropped) when n_per > 0.
+// A thread sums one accumulator QUAD (16 bytes: four rows of one column) of its share of the partial results, so
+// the 16 threads of a group read 256 contiguous bytes of every partial result; grid.x covers the quads of the
+// largest problem, 16 per workgroup.
 __global__ __launch_bounds__(256) void wgrad_mfma_reduce_kernel(WgradProblem p0, WgradProblem p1, WgradProblem p2, int nz) {
-  __shared__ float red[16][16];
+  __shared__ float4 red[16][16];
   const WgradProblem& p = blockIdx.y == 0 ? p0 : blockIdx.y == 1 ? p1 : p2;
-  const float* __restrict__ partial = p.partial;
+  const float4* __restrict__ partial = (const float4*)p.partial;
   const int M = p.M, N = p.N, NB = (N + 31) / 32, nblk = ((M + 31) / 32) * NB, n_per = p.n_per;
   const int o = threadIdx.x & 15, g = threadIdx.x >> 4;
-  const long n_out = (long)M * N;
-  const long i = (long)blockIdx.x * 16 + o;
-  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-  int m = 0, n = 0;
-  if (i < n_out) {
-    m = (int)(i / N); n = (int)(i - (long)m * N);
-    // accumulator register r of lane (c, h) in block (m / 32, n / 32): row 8 (r / 4) + 4 h + r % 4, column c
-    const int mi = m & 31, r = 4 * (mi >> 3) + (mi & 3), hh = (mi >> 2) & 1;
-    const long off = ((((long)(m >> 5) * NB + (n >> 5)) * 4 + (r >> 2)) * 64 + hh * 32 + (n & 31)) * 4 + (r & 3);
-    const long pz = (long)nblk * 16 * 64;
-    int z = g;
-    for (; z + 48 < nz; z += 64) {
-      s0 += partial[(long)z * pz + off];
-      s1 += partial[(long)(z + 16) * pz + off];
-      s2 += partial[(long)(z + 32) * pz + off];
-      s3 += partial[(long)(z + 48) * pz + off];
-    }
-    for (; z < nz; z += 16) s0 += partial[(long)z * pz + off];
-  }
-  red[g][o] = (s0 + s1) + (s2 + s3);
-  __syncthreads();
-  if (g == 0 && i < n_out) {
-    float v = 0.f;
+  const int nquad = nblk * 4 * 64;          // quads of one partial result: [block][register quad][lane]
+  const int i = blockIdx.x * 16 + o;
+  float4 s[4];
 #pragma unroll
-    for (int k = 0; k < 16; ++k) v += red[k][o];
-    if (n_per > 0) {
-      const int gn = n + p.n_off;
-      float* dst = (gn / n_per == 0) ? p.o0 : (gn / n_per == 1) ? p.o1 : p.o2;
-      if (dst) dst[(long)m * n_per + gn % n_per] = v;
-    } else {
-      p.o0[i] = v;
+  for (int k = 0; k < 4; ++k) s[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i < nquad) {
+    // eight partial results per trip, all requested (at an index inside the array) before the first is added
+    for (int z = g; z < nz; z += 128) {
+      float4 v[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] = partial[(long)min(z + 16 * k, nz - 1) * nquad + i];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        if (z + 16 * k < nz) {
+          float4& t = s[k & 3];
+          t.x += v[k].x; t.y += v[k].y; t.z += v[k].z; t.w += v[k].w;
+        }
+      }
+    }
+  }
+  red[g][o] = make_float4((s[0].x + s[1].x) + (s[2].x + s[3].x), (s[0].y + s[1].y) + (s[2].y + s[3].y),
+                          (s[0].z + s[1].z) + (s[2].z + s[3].z), (s[0].w + s[1].w) + (s[2].w + s[3].w));
+  __syncthreads();
+  if (g == 0 && i < nquad) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) { v.x += red[k][o].x; v.y += red[k][o].y; v.z += red[k][o].z; v.w += red[k][o].w; }
+    // quad q of lane (c, h) in block (bi, bj): rows 32 bi + 8 q + 4 h + 0..3, column 32 bj + c
+    const int lane = i & 63, q = (i >> 6) & 3, blk = i >> 8, bi = blk / NB, bj = blk - bi * NB;
+    const int n = bj * 32 + (lane & 31), m0 = bi * 32 + 8 * q + 4 * (lane >> 5);
+    if (n < N) {
+      const float vv[4] = {v.x, v.y, v.z, v.w};
+      float* dst = p.o0;
+      long ld = N, col = n;
+      if (n_per > 0) {
+        const int gn = n + p.n_off;
+        dst = (gn / n_per == 0) ? p.o0 : (gn / n_per == 1) ? p.o1 : p.o2;
+        ld = n_per; col = gn % n_per;
+      }
+      if (dst) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (m0 + j < M) dst[(long)(m0 + j) * ld + col] = vv[j];
+      }
     }
   }
 }
@@ -857,7 +873,7 @@ static void launch_wgrad_mfma_f32_tri(const WgradProblem* a, const WgradProblem*
   if (b) push(*b, 0, b->N);
   for (int k = n; k < 3; ++k) ps[k] = ps[0];
   hipLaunchKernelGGL(wgrad_mfma_f32_tri_kernel, dim3(blocks3, n), dim3(256), 0, st, ps[0], ps[1], ps[2], R, rows3);
-  hipLaunchKernelGGL(wgrad_mfma_reduce_kernel, dim3((unsigned)(((long)a->M * 64 + 15) / 16), n), dim3(256), 0, st, ps[0],
+  hipLaunchKernelGGL(wgrad_mfma_reduce_kernel, dim3(4 * 16, n), dim3(256), 0, st, ps[0],
                      ps[1], ps[2], blocks3);
 }
 // C[M, N] = A[R, M]^T G[R, N] into o0 (n_per == 0) or column blocks of n_per columns into o0 | o1 | o2
@@ -878,8 +894,7 @@ void launch_wgrad_mfma_f32(const float* A, long lda, const float* G, long ldg, i
     if (NB == 1) WM_LAUNCH(2, 1); else if (NB == 2) WM_LAUNCH(2, 2); else if (NB == 3) WM_LAUNCH(2, 3); else WM_LAUNCH(2, 4);
   }
 #undef WM_LAUNCH
-  const long n_out = (long)M * N;
-  hipLaunchKernelGGL(wgrad_mfma_reduce_kernel, dim3((unsigned)((n_out + 15) / 16), 1), dim3(256), 0, st, p, p, p, blocks);
+  hipLaunchKernelGGL(wgrad_mfma_reduce_kernel, dim3(MB * NB * 16, 1), dim3(256), 0, st, p, p, p, blocks);
 }
 // The two weight gradients of an attention block in one pair of launches:
 //   [dWq | dWk | dWv] = X^T [dQ | dK | dV]  (d x 3d, column blocks of d columns into q0 | q1 | q2, NULL = dropped)
@@ -903,8 +918,7 @@ void launch_wgrad_mfma_f32_attn(const float* X, const float* dQKV, const float* 
   if (NB0 == 3) hipLaunchKernelGGL((wgrad_mfma_f32_pair_kernel<1, 3, 1, 1>), grid, block, 0, st, p0, p1, R, rows);
   else if (NB0 == 2) hipLaunchKernelGGL((wgrad_mfma_f32_pair_kernel<1, 2, 1, 1>), grid, block, 0, st, p0, p1, R, rows);
   else hipLaunchKernelGGL((wgrad_mfma_f32_pair_kernel<1, 1, 1, 1>), grid, block, 0, st, p0, p1, R, rows);
-  const long n_out = (long)d * 3 * d;
-  hipLaunchKernelGGL(wgrad_mfma_reduce_kernel, dim3((unsigned)((n_out + 15) / 16), 2), dim3(256), 0, st, p0, p1, p1, blocks);
+  hipLaunchKernelGGL(wgrad_mfma_reduce_kernel, dim3(MB * NB0 * 16, 2), dim3(256), 0, st, p0, p1, p1, blocks);
 }
 
 bool wgrad_small_ok(int M, int N, int n_per) {
