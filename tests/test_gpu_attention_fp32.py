@@ -39,7 +39,15 @@ def test_full_size_configs(cfg, name):
     say(f"    errors: " + " ".join(f"{k}={v:.1e}" for k, v in errs.items()))
 
 
-@pytest.mark.parametrize("d,H", [(40, 8), (36, 6), (48, 4), (20, 4), (64, 8), (42, 7)])
+def test_very_tall_weight_gradients_fp32():
+    """132 000 rows at d = 40 (11 000 batch elements of 12 rows): the weight-gradient kernels take more than 128 rows
+    per workgroup (their partial results are capped at 1024 per gradient) and the last workgroup is ragged."""
+    say("[case] very tall fp32 weight gradients d=40 H=8 B=11000")
+    g = synth.attention_inputs(11000, (3, 5, 4), 40, 8, "fp32", "valid_len", seed=313, bias=True)
+    Problem(g, oracle.IM_IFM_FORWARD).check(what="very tall/d=40")
+
+
+@pytest.mark.parametrize("d,H", [(40, 8), (36, 6), (48, 4), (20, 4), (64, 8), (42, 7), (33, 3)])
 def test_tall_projections_ragged_rows(d, H):
     """More than 1024 rows, not a multiple of 32: the fp32 projections of a tall input run on the matrix-instruction
     GEMM (32-row blocks, widths padded to 32 columns, K padded to 8; d = 42 cannot store four columns at a time and
