@@ -23,6 +23,9 @@ struct Geo {
   // partner are absent.
   int q_order[IM_MAX_SEG], q_tile_prefix[IM_MAX_SEG + 1], q_nord;
   int k_order[IM_MAX_SEG], k_tile_prefix[IM_MAX_SEG + 1], k_nord;
+  // Sub-head forward only: bit k set = the query tiles of the k-th segment of q_order are half as tall
+  // (q_tile_prefix counts them so); see launch_mfma_fwd.
+  unsigned q_half;
   float scale, scale_log2e;
   // Packed rows (im_shape_t::cu_rows): row offsets [B * n_seg + 1] on the device, and the row count.
   // cu == nullptr: padded rows, batch element b owns rows b*T .. b*T + T - 1.

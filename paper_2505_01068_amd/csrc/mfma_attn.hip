@@ -26,6 +26,8 @@
 // Only live (query segment, key segment) blocks of the Interlaced Mask are
 // visited (Sec. 6 "Decomposition"); a row with several live segments carries
 // one running max / sum across all of them (Sec. "Information Disorder").
+#include <algorithm>
+#include <type_traits>
 #include "mfma_common.hpp"
 #include "mfma_path.hpp"
 
@@ -200,8 +202,20 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(WGS * N
   const int bm = second ? b - g.pair_B : b;   // batch element of the masks (valid_len, key_pad)
   constexpr int WG_ROWS = HEADW ? 32 * QB : 32 * NW * QB;
   int qs, q0;
-  decode_tile(second ? g.q_order2 : g.q_order, second ? g.q_tile_prefix2 : g.q_tile_prefix, second ? g.q_nord2 : g.q_nord,
-              WG_ROWS, tile, qs, q0);
+  // HALF: the launch may give the query segment with the longest key range tiles of half the height (one query
+  // block per wave instead of two), see launch_mfma_fwd; such a workgroup runs the loop below for one block.
+  constexpr bool HALF = HEADW && !PAIR && QB == 2;
+  bool half_tile = false;
+  if (HALF) {
+    int k = 0;
+    while (k + 1 < g.q_nord && tile >= g.q_tile_prefix[k + 1]) ++k;
+    qs = g.q_order[k];
+    half_tile = (g.q_half >> k) & 1u;
+    q0 = (tile - g.q_tile_prefix[k]) * (half_tile ? WG_ROWS / 2 : WG_ROWS);
+  } else {
+    decode_tile(second ? g.q_order2 : g.q_order, second ? g.q_tile_prefix2 : g.q_tile_prefix, second ? g.q_nord2 : g.q_nord,
+                WG_ROWS, tile, qs, q0);
+  }
   const unsigned live = second ? g.q_live2[qs] : g.q_live[qs];   // live key segments of the tile's query segment
   const int qlen = useg_rows(g, b, qs);
   if (q0 >= qlen) return;  // packed rows: this batch element's segment ends before the tile
@@ -220,6 +234,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(WGS * N
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     qrow[qb] = q0 + ((HEADW ? 0 : wave * QB) + qb) * 32 + lo;
+    if (HALF && half_tile && qb > 0) qrow[qb] = qlen;   // the next tile's rows: not computed, not stored
     const int rc = min(qrow[qb], qlen - 1);
     const bf16_t* p = QKV + (useg_row0(g, b, qs) + rc) * ld + cg * 64 + hi * 8;
 #pragma unroll
@@ -286,99 +301,105 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(WGS * N
   // NST - 1 stages are requested ahead: the slot refilled in an iteration is the one consumed in the one before
   if (ic.len > 0) { issue(); ++inflight; }
   if (NST > 2 && ic.len > 0) { issue(); ++inflight; }
-  while (cc.len > 0) {
-    ring_wait<NW>(inflight - 1);
-    if (ic.len > 0) issue(); else --inflight;
-    const bf16_t* sK = sT + cslot * RING_STAGE;
-    const bf16_t* sV = sK + KT * SW_LD;
-    cslot = (cslot + 1 == NST) ? 0 : cslot + 1;
-    const int k0 = cc.r0, klen = cc.len;
-    const uint8_t* kp_row = key_pad ? key_pad + useg_row0(g, bm, cc.seg) : nullptr;
-    cursor_step(cc, klen_of);
-    const bool need_mask = (k0 + KT > klen) || (kp_row != nullptr);  // tail tile or key_pad present (wave-uniform)
-    unsigned long long km = ~0ull;
-    if (need_mask) km = tile_key_mask(kp_row, k0, klen, lane) >> (8 * hi);
-    // The tile is processed as two blocks of 32 keys, each S^T -> softmax -> O^T, so that only one block of
-    // scores and of probabilities is live at a time.
+  // The ring loop, for NQB of the wave's QB query blocks (NQB < QB: a tile of half the height).
+  auto ring_loop = [&](auto nqb_tag) {
+    constexpr int NQB = decltype(nqb_tag)::value;
+    while (cc.len > 0) {
+      ring_wait<NW>(inflight - 1);
+      if (ic.len > 0) issue(); else --inflight;
+      const bf16_t* sK = sT + cslot * RING_STAGE;
+      const bf16_t* sV = sK + KT * SW_LD;
+      cslot = (cslot + 1 == NST) ? 0 : cslot + 1;
+      const int k0 = cc.r0, klen = cc.len;
+      const uint8_t* kp_row = key_pad ? key_pad + useg_row0(g, bm, cc.seg) : nullptr;
+      cursor_step(cc, klen_of);
+      const bool need_mask = (k0 + KT > klen) || (kp_row != nullptr);  // tail tile or key_pad present (wave-uniform)
+      unsigned long long km = ~0ull;
+      if (need_mask) km = tile_key_mask(kp_row, k0, klen, lane) >> (8 * hi);
+      // The tile is processed as two blocks of 32 keys, each S^T -> softmax -> O^T, so that only one block of
+      // scores and of probabilities is live at a time.
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      // ---- S^T = K Q^T ----
-      // The accumulator chain starts from -m (nm: the running reference of the lane's query row in all 16
-      // registers), so the scores leave the matrix cores already relative to it.
-      f32x16 sacc[QB];
+      for (int kb = 0; kb < 2; ++kb) {
+        // ---- S^T = K Q^T ----
+        // The accumulator chain starts from -m (nm: the running reference of the lane's query row in all 16
+        // registers), so the scores leave the matrix cores already relative to it.
+        f32x16 sacc[QB];
 #pragma unroll
-      for (int s = 0; s < NS; ++s) {
-        const bf16x8 a = lds_frag_sw(sK, kb * 32, prow, 2 * (s0 + s) + hi);
+        for (int s = 0; s < NS; ++s) {
+          const bf16x8 a = lds_frag_sw(sK, kb * 32, prow, 2 * (s0 + s) + hi);
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) sacc[qb] = mfma32(a, qreg[qb][s], s == 0 ? nm[qb] : sacc[qb]);
-      }
-      if (need_mask) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          // register r of block kb on this lane half is key kb*32 + 16*(r/8) + 8*hi + r%8
-          const bool ok = (km >> (kb * 32 + 16 * (r >> 3) + (r & 7))) & 1ull;
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb) sacc[qb][r] = ok ? sacc[qb][r] : IM_NEG_INF;
+          for (int qb = 0; qb < NQB; ++qb) sacc[qb] = mfma32(a, qreg[qb][s], s == 0 ? nm[qb] : sacc[qb]);
         }
-      }
-      // ---- online softmax, one running (reference, sum) per query row ----
-      bf16x8 pb[QB][2];
+        if (need_mask) {
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        // P^T operands of the block from its scores; returns the lane's part of the row sum, taken over the
-        // bf16-rounded probabilities (the values that multiply V) with two-element dot products against (1, 1)
-        auto exponentiate = [&]() {
-          float p[16];
+          for (int r = 0; r < 16; ++r) {
+            // register r of block kb on this lane half is key kb*32 + 16*(r/8) + 8*hi + r%8
+            const bool ok = (km >> (kb * 32 + 16 * (r >> 3) + (r & 7))) & 1ull;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) p[r] = fast_exp2(sacc[qb][r]);
-          pb[qb][0] = pack8(p);
-          pb[qb][1] = pack8(p + 8);
-          return sum_bf16x8(pb[qb][1], sum_bf16x8(pb[qb][0], 0.f));
-        };
-        // Almost every block: every row of the wave has a reference already and the scores are exponentiated
-        // as they left the matrix cores -- no maximum is taken at all.  fp32 and bf16 share their exponent
-        // range, so probabilities far above 1 lose nothing; only a row without a reference yet, or a row sum
-        // beyond 2^24 (or inf / NaN), sends the block through the rescaling branch, which recomputes it.
-        float rs = exponentiate();
-        if (__builtin_expect(__any(m[qb] == IM_NEG_INF || !(rs <= 16777216.f)), 0)) {
-          asm volatile("" ::: "memory");  // a real branch: nothing of it is to be executed speculatively
-          float mx = sacc[qb][0];
-#pragma unroll
-          for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[qb][r]);
-          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // block maximum relative to m (the raw maximum while m = -inf)
-          // The reference moves when a row has none yet, or when the block maximum exceeds it by more than
-          // 2^8 in the exponent domain: accumulator rescale, shifting the block's scores to the new reference
-          // and rebuilding nm.
-          const bool first = m[qb] == IM_NEG_INF;
-          const bool upd = first ? mx > IM_NEG_INF : mx > tau;
-          const float shift = upd ? mx : 0.f;
-          const float alpha = first ? 0.f : fast_exp2(-shift);
-          l[qb] *= alpha;
-#pragma unroll
-          for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
-          if (upd) m[qb] = first ? mx : m[qb] + mx;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) sacc[qb][r] -= shift;
-          const float nmv = (m[qb] == IM_NEG_INF) ? 0.f : -m[qb];
-#pragma unroll
-          for (int r = 0; r < 16; ++r) nm[qb][r] = nmv;
-          rs = exponentiate();
+            for (int qb = 0; qb < NQB; ++qb) sacc[qb][r] = ok ? sacc[qb][r] : IM_NEG_INF;
+          }
         }
-        l[qb] += rs;
-      }
-      // ---- O^T += V^T P^T over the 32 keys of the block ----
+        // ---- online softmax, one running (reference, sum) per query row ----
+        bf16x8 pb[QB][2];
 #pragma unroll
-      for (int db = 0; db < NDB; ++db)
+        for (int qb = 0; qb < NQB; ++qb) {
+          // P^T operands of the block from its scores; returns the lane's part of the row sum, taken over the
+          // bf16-rounded probabilities (the values that multiply V) with two-element dot products against (1, 1)
+          auto exponentiate = [&]() {
+            float p[16];
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          const bf16x8 a = lds_frag_tr_sw(sV, kb * 32 + half * 16, (db0 + db) * 32, lane);
+            for (int r = 0; r < 16; ++r) p[r] = fast_exp2(sacc[qb][r]);
+            pb[qb][0] = pack8(p);
+            pb[qb][1] = pack8(p + 8);
+            return sum_bf16x8(pb[qb][1], sum_bf16x8(pb[qb][0], 0.f));
+          };
+          // Almost every block: every row of the wave has a reference already and the scores are exponentiated
+          // as they left the matrix cores -- no maximum is taken at all.  fp32 and bf16 share their exponent
+          // range, so probabilities far above 1 lose nothing; only a row without a reference yet, or a row sum
+          // beyond 2^24 (or inf / NaN), sends the block through the rescaling branch, which recomputes it.
+          float rs = exponentiate();
+          if (__builtin_expect(__any(m[qb] == IM_NEG_INF || !(rs <= 16777216.f)), 0)) {
+            asm volatile("" ::: "memory");  // a real branch: nothing of it is to be executed speculatively
+            float mx = sacc[qb][0];
 #pragma unroll
-          for (int qb = 0; qb < QB; ++qb) oacc[db][qb] = mfma32(a, pb[qb][half], oacc[db][qb]);
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[qb][r]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // block maximum relative to m (the raw maximum while m = -inf)
+            // The reference moves when a row has none yet, or when the block maximum exceeds it by more than
+            // 2^8 in the exponent domain: accumulator rescale, shifting the block's scores to the new reference
+            // and rebuilding nm.
+            const bool first = m[qb] == IM_NEG_INF;
+            const bool upd = first ? mx > IM_NEG_INF : mx > tau;
+            const float shift = upd ? mx : 0.f;
+            const float alpha = first ? 0.f : fast_exp2(-shift);
+            l[qb] *= alpha;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
+            if (upd) m[qb] = first ? mx : m[qb] + mx;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[qb][r] -= shift;
+            const float nmv = (m[qb] == IM_NEG_INF) ? 0.f : -m[qb];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) nm[qb][r] = nmv;
+            rs = exponentiate();
+          }
+          l[qb] += rs;
         }
+        // ---- O^T += V^T P^T over the 32 keys of the block ----
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            const bf16x8 a = lds_frag_tr_sw(sV, kb * 32 + half * 16, (db0 + db) * 32, lane);
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb) oacc[db][qb] = mfma32(a, pb[qb][half], oacc[db][qb]);
+          }
+      }
     }
-  }
+  };
+  if (HALF && half_tile) ring_loop(std::integral_constant<int, 1>{});
+  else ring_loop(std::integral_constant<int, QB>{});
 
   // ---- epilogue: normalise, write O rows, O^T columns and the log-sum-exp ----
 #pragma unroll
@@ -859,8 +880,52 @@ int mfma_fwd_tile_rows(int dh, int H) { return dh == 64 ? 32 * FWD_NW * FWD_QB :
 int mfma_dq_tile_rows() { return 128 * DQ_QB; }
 int mfma_dkv_tile_rows() { return 128 * DKV_KB; }
 
-void launch_mfma_fwd(const Geo& g, const bf16_t* qkv, long ld, const int32_t* valid_len, const uint8_t* key_pad,
+// Sub-head forward with four heads per workgroup, padded rows.  The workgroups of the query segment with the longest
+// key range finish last; when they are few (at most a quarter of the workgroup slots -- segments 50 / 500 / 375 under
+// the forward inter-modal mask: the one tile of the 50 text rows reads 500 keys, the eight tiles of the vision rows
+// 375) and clearly the longest, their tiles become 32 rows tall: twice the workgroups, one query block per wave,
+// a shorter tail of the launch (measured: -3 % at that shape).  A half-height workgroup does more work per score (the
+// K/V fragments are read per block), so a launch whose long workgroups are many -- it is bound by the CUs'
+// instruction issue, not by its last workgroup -- keeps the full tiles (halving them there measured +3 %).
+static int device_cus() {
+  static int cus = 0;   // compute units of the device (the first device that launches; one GPU per process)
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
+    else cus = 256;
+  }
+  return cus;
+}
+static void fwd_half_tiles(Geo& g) {
+  g.q_half = 0;
+  if (g.cu || g.q_nord < 2) return;
+  const int rows = 32 * FWD_QB_SUB;
+  const long units = (long)g.B * (g.H / 4), slots = (long)FWD_SUB_WGS * device_cus();
+  long len[IM_MAX_SEG], tiles[IM_MAX_SEG];
+  int longest = 0;
+  for (int k = 0; k < g.q_nord; ++k) {
+    const int sgm = g.q_order[k];
+    len[k] = 0;
+    for (int j = 0; j < g.n_seg; ++j)
+      if ((g.q_live[sgm] >> j) & 1u) len[k] += (g.seg_len[j] + KT - 1) / KT;
+    tiles[k] = (g.seg_len[sgm] + rows - 1) / rows;
+    if (len[k] > len[longest]) longest = k;
+  }
+  long second = 0;
+  for (int k = 0; k < g.q_nord; ++k)
+    if (k != longest && len[k] > second) second = len[k];
+  if (4 * len[longest] < 5 * second || 4 * tiles[longest] * units > slots) return;
+  const long half_tiles = (g.seg_len[g.q_order[longest]] + rows / 2 - 1) / (rows / 2);
+  g.q_half = 1u << longest;
+  for (int k = 0; k < g.q_nord; ++k)
+    g.q_tile_prefix[k + 1] = g.q_tile_prefix[k] + (int)(k == longest ? half_tiles : tiles[k]);
+}
+
+void launch_mfma_fwd(const Geo& g_in, const bf16_t* qkv, long ld, const int32_t* valid_len, const uint8_t* key_pad,
                      bf16_t* o, long ldo, float* lse2, hipStream_t st) {
+  Geo g = g_in;
+  g.q_half = 0;
+  if (fwd_headw(g.dh, g.H)) fwd_half_tiles(g);
   // query segments with no live block: output 0, lse -inf
   for (int s = 0; s < g.n_seg; ++s) {
     if (g.q_live[s]) continue;
