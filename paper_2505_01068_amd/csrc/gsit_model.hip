@@ -103,16 +103,24 @@ static int run_encoder(const im_shape_t* s, int d_ff, const gsit_layer_params_t*
 // out[m, n] = sum_k z[m, k] wf[k, n] + bf[n] for the few (batch x n_out) outputs of the fusion head: one
 // wavefront per output, lanes stride over k, fixed-order shuffle reduction.  The tiled GEMM would walk
 // the 6 d-long contraction as a serial chain of 16-deep tiles in a single workgroup.
+// The gather of the last positions happens inside: z[m, s * w + c] is read from `a` where it lies
+// (gather_last_kernel's indexing), one launch instead of two.
 template <typename T>
-__global__ __launch_bounds__(256) void head_dot_kernel(const T* __restrict__ z, const T* __restrict__ wf,
-                                                       const T* __restrict__ bias, T* __restrict__ out, int M, int N,
-                                                       int K) {
+__global__ __launch_bounds__(256) void head_dot_gather_kernel(const T* __restrict__ a, const int32_t* __restrict__ valid_len,
+                                                              const T* __restrict__ wf, const T* __restrict__ bias,
+                                                              T* __restrict__ out, int M, int N, int Tm, int w, int n_seg,
+                                                              Geo g) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const long o = (long)blockIdx.x * 4 + wave;
   if (o >= (long)M * N) return;
-  const int m = (int)(o / N), n = (int)(o % N);
+  const int m = (int)(o / N), n = (int)(o % N), K = n_seg * w;
   float acc = 0.f;
-  for (int k = lane; k < K; k += 64) acc = fmaf(ldf(z + (long)m * K + k), ldf(wf + (long)k * N + n), acc);
+  for (int k = lane; k < K; k += 64) {
+    const int s = k / w, col = k - s * w;
+    int pos = g.seg_len[s] - 1;
+    if (valid_len) pos = max(min(valid_len[m * n_seg + s], g.seg_len[s]), 1) - 1;
+    acc = fmaf(ldf(a + ((long)m * Tm + g.seg_off[s] + pos) * w + col), ldf(wf + (long)k * N + n), acc);
+  }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
   if (lane == 0) stf(out + o, acc + (bias ? ldf(bias + n) : 0.f));
@@ -202,18 +210,19 @@ int gsit_model_fwd(const im_shape_t* shape, const gsit_model_t* model, const voi
   g.n_seg = shape->n_seg;
   for (int i = 0; i < shape->n_seg; ++i) { g.seg_len[i] = shape->seg_len[i]; g.seg_off[i + 1] = g.seg_off[i] + shape->seg_len[i]; }
   const int wz = 2 * d, nz = shape->n_seg * wz;
-  const int gblocks = (shape->batch * nz + 255) / 256;
-  if (bf) hipLaunchKernelGGL(gather_last_kernel<uint16_t>, dim3(gblocks), dim3(256), 0, st, (const uint16_t*)cat, (uint16_t*)z, valid_len, shape->batch, (int)T, wz, shape->n_seg, g);
-  else hipLaunchKernelGGL(gather_last_kernel<float>, dim3(gblocks), dim3(256), 0, st, (const float*)cat, (float*)z, valid_len, shape->batch, (int)T, wz, shape->n_seg, g);
-
   if ((long)shape->batch * model->n_out <= 16384) {
+    // few outputs: one launch gathers the last positions and multiplies
     const unsigned hb = (unsigned)(((long)shape->batch * model->n_out + 3) / 4);
-    if (bf) hipLaunchKernelGGL(head_dot_kernel<uint16_t>, dim3(hb), dim3(256), 0, st, (const uint16_t*)z, (const uint16_t*)model->wf, (const uint16_t*)model->bf, (uint16_t*)out, shape->batch, model->n_out, nz);
-    else hipLaunchKernelGGL(head_dot_kernel<float>, dim3(hb), dim3(256), 0, st, (const float*)z, (const float*)model->wf, (const float*)model->bf, (float*)out, shape->batch, model->n_out, nz);
+    if (bf) hipLaunchKernelGGL(head_dot_gather_kernel<uint16_t>, dim3(hb), dim3(256), 0, st, (const uint16_t*)cat, valid_len, (const uint16_t*)model->wf, (const uint16_t*)model->bf, (uint16_t*)out, shape->batch, model->n_out, (int)T, wz, shape->n_seg, g);
+    else hipLaunchKernelGGL(head_dot_gather_kernel<float>, dim3(hb), dim3(256), 0, st, (const float*)cat, valid_len, (const float*)model->wf, (const float*)model->bf, (float*)out, shape->batch, model->n_out, (int)T, wz, shape->n_seg, g);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_error("gsit_model_fwd launch: %s", hipGetErrorString(e)); return IM_ERR_HIP; }
     return IM_OK;
   }
+  const int gblocks = (shape->batch * nz + 255) / 256;
+  if (bf) hipLaunchKernelGGL(gather_last_kernel<uint16_t>, dim3(gblocks), dim3(256), 0, st, (const uint16_t*)cat, (uint16_t*)z, valid_len, shape->batch, (int)T, wz, shape->n_seg, g);
+  else hipLaunchKernelGGL(gather_last_kernel<float>, dim3(gblocks), dim3(256), 0, st, (const float*)cat, (float*)z, valid_len, shape->batch, (int)T, wz, shape->n_seg, g);
+
   GemmDesc p;
   memset(&p, 0, sizeof(p));
   p.A = z; p.sam = nz; p.sak = 1;
